@@ -1,0 +1,267 @@
+"""Oracle: slot layouts of interleaved replicated packing (TEST INFRASTRUCTURE).
+
+Everything here is about WHERE numbers sit in the S slots of a ciphertext: the activation
+layouts and the weight-diagonal plaintexts of the packed vector-matrix product (Sec. 4.1,
+App. C / Algorithm 1) and the K-cache, V-cache, query, score and mask layouts of the
+attention products (Sec. 5.1-5.3).  No cryptography.
+
+Notation (the paper's, with S for its slot count N): d = length of the shorter vector,
+t = S/d its interleave interval; alpha = aspect ratio; t' = S/(alpha d) the interval of the
+longer vector.  A slot index is written i = b*t + r (block b, residue r), and for the longer
+vector r = s*t' + r'.
+
+Readings taken where the printed algorithm and the text disagree:
+  * the preprocess rotation is 2^i (t-1) slots (the toy example of Sec. 4.1 needs a rotation
+    by t-1 = 1 to reach [a0,a1,a1,a2,...]; a rotation by d-1 does not give it);
+  * rotation amounts printed as j t' and t r_i count blocks; in slots they are j t' t and
+    r_i t' t, and r_o = d / (t' r_i), the only choice with r_i r_o t' = d;
+  * the weight plaintexts are built by pushing index labels through the same rotations
+    instead of using the printed closed forms.
+"""
+from dataclasses import dataclass
+from typing import List
+
+import numpy as np
+
+
+def _log2(x):
+    assert x > 0 and x & (x - 1) == 0, x
+    return x.bit_length() - 1
+
+
+@dataclass
+class VmmPlan:
+    S: int
+    d: int          # shorter dimension
+    alpha: int
+    mode: str       # "square" (d->d), "expand" (d -> alpha d), "contract" (alpha d -> d)
+    r_i: int
+    tau: int = 0    # residue the valid output lands on (0 unless preparing a cache append)
+
+    def __post_init__(self):
+        self.t = self.S // self.d
+        self.tp = self.S // (self.alpha * self.d)
+        assert self.t * self.d == self.S and self.tp * self.alpha * self.d == self.S
+        assert self.mode in ("square", "expand", "contract")
+        assert (self.alpha == 1) == (self.mode == "square")
+        self.t1, self.t2 = (self.tp, self.t) if self.mode == "contract" else (self.t, self.tp)
+        self.M = self.d // self.tp                      # number of diagonals
+        assert self.M >= 1 and self.M % self.r_i == 0
+        self.r_o = self.M // self.r_i
+        assert 0 <= self.tau < self.t2
+        self.d_in = self.d * (self.alpha if self.mode == "contract" else 1)
+        self.d_out = self.d * (self.alpha if self.mode == "expand" else 1)
+
+    # rotation amounts, in slots
+    @property
+    def pre_steps(self) -> List[int]:
+        return [(1 << i) * (self.t - 1) for i in range(_log2(self.t1))]
+
+    @property
+    def baby_steps(self) -> List[int]:
+        return [j * self.tp * self.t for j in range(self.r_i)]
+
+    @property
+    def giant_step(self) -> int:
+        return self.r_i * self.tp * self.t
+
+    @property
+    def reduce_steps(self) -> List[int]:
+        """2^l to the left, or to the right where bit l of tau is set: the block of t2 slots
+        then sums into residue tau instead of 0 (the 'customizable' packing of Sec. 5.1)."""
+        return [-(1 << l) if (self.tau >> l) & 1 else (1 << l) for l in range(_log2(self.t2))]
+
+    @property
+    def n_rotations(self):
+        return _log2(self.t1) + (self.r_i - 1) + (self.r_o - 1) + _log2(self.t2)
+
+    def all_steps(self):
+        s = self.pre_steps + self.baby_steps[1:] + self.reduce_steps
+        if self.r_o > 1:
+            s.append(self.giant_step)
+        return s
+
+    # layouts ---------------------------------------------------------------------------
+    def in_slot(self, a):
+        """Slot of input element a."""
+        if self.mode == "contract":
+            return (a % self.d) * self.t + (a // self.d) * self.tp
+        return a * self.t
+
+    def out_slot(self, c):
+        if self.mode == "expand":
+            return (c % self.d) * self.t + (c // self.d) * self.tp + self.tau
+        return c * self.t + self.tau
+
+    def pack_input(self, x):
+        v = np.zeros(self.S)
+        v[[self.in_slot(a) for a in range(self.d_in)]] = x
+        return v
+
+    def unpack_output(self, slots):
+        return np.asarray(slots)[[self.out_slot(c) for c in range(self.d_out)]]
+
+    def out_mask(self):
+        m = np.zeros(self.S)
+        m[[self.out_slot(c) for c in range(self.d_out)]] = 1.0
+        return m
+
+    def block_col(self):
+        """Output index owned by each block of t2 consecutive slots."""
+        B = np.arange(self.S // self.t2)
+        if self.mode == "expand":
+            return B // self.alpha + (B % self.alpha) * self.d
+        return B
+
+    def source_labels(self):
+        """Input index held by every slot after the preprocess step (labels pushed through
+        the same rotate-and-add; two labelled slots never meet)."""
+        lab = np.full(self.S, -1, dtype=np.int64)
+        for a in range(self.d_in):
+            lab[self.in_slot(a)] = a
+        for r in self.pre_steps:
+            rot = np.roll(lab, -r)
+            assert not np.any((lab >= 0) & (rot >= 0))
+            lab = np.where(rot >= 0, rot, lab)
+        assert np.all(lab >= 0)
+        return lab
+
+    def diagonals(self, W):
+        """Slot vectors p[j][k] of the weight plaintexts: slot i' of Rot(c', baby_j) holds
+        input index row; its product ends, after k giant rotations and the reduce step, in the
+        block that owns output index col."""
+        W = np.asarray(W)
+        assert W.shape == (self.d_in, self.d_out)
+        lab, col_of_block, S = self.source_labels(), self.block_col(), self.S
+        i = np.arange(S)
+        out = [[None] * self.r_o for _ in range(self.r_i)]
+        for j in range(self.r_i):
+            row = np.roll(lab, -self.baby_steps[j])
+            for k in range(self.r_o):
+                col = col_of_block[((i - k * self.giant_step) % S) // self.t2]
+                out[j][k] = W[row, col]
+        return out
+
+
+def default_r_i(M):
+    """Baby-step count: the power of two at or just above sqrt(M)."""
+    return 1 << ((_log2(M) + 1) // 2)
+
+
+def make_plan(S, d_in, d_out, r_i=None, tau=0):
+    if d_in == d_out:
+        d, alpha, mode = d_in, 1, "square"
+    elif d_out > d_in:
+        d, alpha, mode = d_in, d_out // d_in, "expand"
+    else:
+        d, alpha, mode = d_out, d_in // d_out, "contract"
+    M = d // (S // (alpha * d))
+    return VmmPlan(S, d, alpha, mode, default_r_i(M) if r_i is None else r_i, tau)
+
+
+# ---- attention layouts (Sec. 5) ------------------------------------------------------------
+@dataclass
+class KvLayout:
+    """Slot (e, h, tau) := (e*H + h)*t + tau with t = S/(H*E): head-interleaved blocks of t
+    (Sec. 5.3).  A query / key / value vector of the current token has element [h, e] at
+    (e, h, tau); K ciphertext c holds token c*t + tau at residue tau; the score ciphertext
+    holds token c*t + tau of head h at (c, h, tau), so it has room for E*t = S/H tokens;
+    V ciphertext k holds V[((e + k) mod E)*t + r, h, e] at (e, h, r), stored rotated right by
+    the giant step of its BSGS group."""
+    S: int
+    H: int
+    E: int
+    r_i: int = 0    # baby steps of the score-times-V product; 0 -> E (no giant steps)
+
+    def __post_init__(self):
+        self.t = self.S // (self.H * self.E)
+        assert self.t * self.H * self.E == self.S
+        self.r_i = self.r_i or self.E
+        assert self.E % self.r_i == 0
+        self.r_o = self.E // self.r_i
+        self.capacity = self.E * self.t
+
+    def slot(self, e, h, tau):
+        return (e * self.H + h) * self.t + tau
+
+    def pack_vec(self, v, tau=0):
+        """v[h, e] at (e, h, tau), zero elsewhere."""
+        out = np.zeros(self.S)
+        for h in range(self.H):
+            for e in range(self.E):
+                out[self.slot(e, h, tau)] = v[h, e]
+        return out
+
+    def unpack_vec(self, slots, tau=0):
+        return np.array([[slots[self.slot(e, h, tau)] for e in range(self.E)]
+                         for h in range(self.H)])
+
+    def pack_k(self, K, c):
+        """K[token, h, e] -> slots of K ciphertext c (tokens past the end are zero)."""
+        out = np.zeros(self.S)
+        for tau in range(self.t):
+            n = c * self.t + tau
+            if n < K.shape[0]:
+                out += self.pack_vec(K[n], tau)
+        return out
+
+    def pack_scores(self, s):
+        """s[h, token] -> score layout."""
+        out = np.zeros(self.S)
+        for h in range(self.H):
+            for n in range(s.shape[1]):
+                out[self.slot(n // self.t, h, n % self.t)] = s[h, n]
+        return out
+
+    def unpack_scores(self, slots, ntok):
+        return np.array([[slots[self.slot(n // self.t, h, n % self.t)] for n in range(ntok)]
+                         for h in range(self.H)])
+
+    def v_shift(self, k):
+        """Right rotation applied to stored V ciphertext k."""
+        return (k // self.r_i) * self.r_i * self.H * self.t
+
+    def pack_v(self, V, k):
+        out = np.zeros(self.S)
+        for e in range(self.E):
+            for h in range(self.H):
+                for r in range(self.t):
+                    n = ((e + k) % self.E) * self.t + r
+                    if n < V.shape[0]:
+                        out[self.slot(e, h, r)] = V[n, h, e]
+        return np.roll(out, self.v_shift(k))
+
+    def qk_mask(self, c):
+        """Keeps copy e = c of the replicated scores of K ciphertext c."""
+        m = np.zeros(self.S)
+        for h in range(self.H):
+            for tau in range(self.t):
+                m[self.slot(c % self.E, h, tau)] = 1.0
+        return m
+
+    def residue_mask(self, tau):
+        m = np.zeros(self.S)
+        m[tau::self.t] = 1.0
+        return m
+
+    def v_append_mask(self, k, n):
+        """Slots of stored V ciphertext k that token n = c*t + tau occupies:
+        e = (c - k) mod E at residue tau, moved by the stored rotation."""
+        c, tau = n // self.t, n % self.t
+        m = np.zeros(self.S)
+        for h in range(self.H):
+            m[self.slot((c - k) % self.E, h, tau)] = 1.0
+        return np.roll(m, self.v_shift(k))
+
+    def qk_steps(self):
+        return [-(1 << i) for i in range(_log2(self.t))] + \
+               [(1 << i) * self.H * self.t for i in range(_log2(self.E))]
+
+    def sv_steps(self):
+        s = [j * self.H * self.t for j in range(1, self.r_i)]
+        if self.r_o > 1:
+            s.append(self.r_i * self.H * self.t)
+        return s + [1 << l for l in range(_log2(self.t))]
+
+    def append_steps(self):
+        return [-(g * self.r_i * self.H * self.t) for g in range(1, self.r_o)]

@@ -1,0 +1,156 @@
+"""Oracle: the packed homomorphic vector-matrix products (TEST INFRASTRUCTURE).
+
+The algorithms of Sec. 4.1 / App. C (Algorithm 1: activation row times plaintext matrix) and
+Sec. 5.1-5.3 (query times K cache, scores times V cache, cache append), written once over a
+small operation set so that the same steps run on plain slot vectors (`SlotOps`, no
+cryptography) and on oracle ciphertexts (`CkksOps`).
+"""
+import numpy as np
+
+from .packing import KvLayout, VmmPlan, _log2
+
+
+class SlotOps:
+    """The CKKS operations of Sec. 2.1 on plain numpy slot vectors."""
+
+    def __init__(self):
+        self.rotations = 0
+        self.pt_mults = 0
+        self.ct_mults = 0
+
+    def add(self, a, b):
+        return a + b
+
+    def rotate(self, a, r):
+        self.rotations += 1
+        return np.roll(a, -r)          # Rot(c, r)[i] = c[i + r]
+
+    def rotate_many(self, a, steps):
+        return [self.rotate(a, r) for r in steps]
+
+    def mul_pt(self, a, slots):
+        self.pt_mults += 1
+        return a * slots
+
+    def mul_ct(self, a, b):
+        self.ct_mults += 1
+        return a * b
+
+    def relin(self, a):
+        return a
+
+    def rescale(self, a):
+        return a
+
+
+class CkksOps:
+    """The same operations on oracle ciphertexts.  `rotate_many` shares the raised digits of
+    the input among its rotations (hoisting)."""
+
+    def __init__(self, ctx, keys, pt_scale=None):
+        self.ctx, self.keys = ctx, keys
+        self.pt_scale = pt_scale
+
+    def add(self, a, b):
+        return self.ctx.ct_add(a, b)
+
+    def rotate(self, a, r):
+        return self.ctx.rotate(a, r, self.keys)
+
+    def rotate_many(self, a, steps):
+        h = self.ctx.hoist(a)
+        return [self.ctx.rotate_hoisted(a, h, r, self.keys) for r in steps]
+
+    def mul_pt(self, a, slots):
+        """`slots` is either a slot vector (encoded here at the context scale or pt_scale) or
+        an already encoded plaintext."""
+        pt = slots if hasattr(slots, "m") else self.ctx.encode(slots, a.level, self.pt_scale)
+        return self.ctx.mul_pt(a, pt)
+
+    def mul_ct(self, a, b):
+        return self.ctx.mul_ct(a, b)
+
+    def relin(self, a):
+        return self.ctx.relinearize(a, self.keys)
+
+    def rescale(self, a):
+        return self.ctx.rescale(a)
+
+
+def _sum(ops, terms):
+    acc = terms[0]
+    for x in terms[1:]:
+        acc = ops.add(acc, x)
+    return acc
+
+
+def vmm_pt(ops, plan: VmmPlan, cx, diagonals):
+    """Algorithm 1 (App. C).  cx holds x in the plan's input layout; diagonals[j][k] are the
+    weight plaintexts.  Returns y = x W in the plan's output layout (other slots hold partial
+    sums until masked, Sec. 4.2), one level lower."""
+    # 1. preprocess: interleaved replication
+    c = cx
+    for r in plan.pre_steps:
+        c = ops.add(c, ops.rotate(c, r))
+    # 2. baby steps (all rotations of the same ciphertext) and multiply-accumulate
+    babies = [c] + ops.rotate_many(c, plan.baby_steps[1:])
+    inner = [_sum(ops, [ops.mul_pt(babies[j], diagonals[j][k]) for j in range(plan.r_i)])
+             for k in range(plan.r_o)]
+    # giant steps, Horner form: one rotation amount reused r_o - 1 times
+    acc = inner[plan.r_o - 1]
+    for k in range(plan.r_o - 2, -1, -1):
+        acc = ops.add(inner[k], ops.rotate(acc, plan.giant_step))
+    # 3. reduce inside the ciphertext
+    for r in plan.reduce_steps:
+        acc = ops.add(acc, ops.rotate(acc, r))
+    return ops.rescale(acc)
+
+
+def qk_scores(ops, lay: KvLayout, cq, k_cts, masks):
+    """Sec. 5.1 with the multi-head layout of Sec. 5.3: scores of one query against the K
+    cache.  masks[c] = lay.qk_mask(c) (slot vector or encoded plaintext)."""
+    for i in range(_log2(lay.t)):                       # replicate q over the t residues
+        cq = ops.add(cq, ops.rotate(cq, -(1 << i)))
+    acc = None
+    for c, kc in enumerate(k_cts):
+        p = ops.rescale(ops.relin(ops.mul_ct(cq, kc)))
+        for i in range(_log2(lay.E)):                   # sum over the E dims of every head
+            p = ops.add(p, ops.rotate(p, (1 << i) * lay.H * lay.t))
+        p = ops.mul_pt(p, masks[c])                     # keep copy e = c
+        acc = p if acc is None else ops.add(acc, p)
+    return ops.rescale(acc)
+
+
+def score_times_v(ops, lay: KvLayout, cs, v_cts):
+    """Sec. 5.2/5.3: Att[h, e] = sum_n s[h, n] V[n, h, e]; result at (e, h, 0), the input
+    layout of the next plaintext product (other residues hold partial sums)."""
+    babies = [cs] + ops.rotate_many(cs, [j * lay.H * lay.t for j in range(1, lay.r_i)])
+    inner = []
+    for g in range(lay.r_o):
+        terms = [ops.mul_ct(babies[j], v_cts[g * lay.r_i + j]) for j in range(lay.r_i)]
+        inner.append(ops.relin(_sum(ops, terms)))
+    acc = inner[lay.r_o - 1]
+    for g in range(lay.r_o - 2, -1, -1):
+        acc = ops.add(inner[g], ops.rotate(acc, lay.r_i * lay.H * lay.t))
+    acc = ops.rescale(acc)
+    for l in range(_log2(lay.t)):
+        acc = ops.add(acc, ops.rotate(acc, 1 << l))
+    return acc
+
+
+def kv_append(ops, lay: KvLayout, k_cts, v_cts, n, ck_new, cv_new, k_mask, v_masks):
+    """Append token n = c*t + tau (Sec. 5.1 'K Cache Update', Sec. 5.2 'V Cache Update').
+    ck_new / cv_new carry the new vectors at residue tau (other slots may hold partial sums);
+    k_mask = lay.residue_mask(tau), v_masks[k] = lay.v_append_mask(k, n).  Masking costs the
+    level the paper fuses with RoPE; the cache ciphertexts live one level below the inputs."""
+    c = n // lay.t
+    knew = ops.rescale(ops.mul_pt(ck_new, k_mask))
+    if c == len(k_cts):
+        k_cts.append(knew)
+    else:
+        k_cts[c] = ops.add(k_cts[c], knew)
+    shifted = [cv_new] + [ops.rotate(cv_new, -(g * lay.r_i * lay.H * lay.t))
+                          for g in range(1, lay.r_o)]
+    for k in range(lay.E):
+        vnew = ops.rescale(ops.mul_pt(shifted[k // lay.r_i], v_masks[k]))
+        v_cts[k] = vnew if v_cts[k] is None else ops.add(v_cts[k], vnew)

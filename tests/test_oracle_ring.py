@@ -1,0 +1,227 @@
+"""Pins for the oracle's ring primitives: each is checked against Python big-int arithmetic
+or a brute-force definition, never against itself."""
+import math
+import random
+
+import numpy as np
+import pytest
+
+from oracle import ckks, params
+from oracle.native import lib, p as _p, pi as _pi
+
+Q50, Q60 = 1125899906826241, 1152921504606830593
+
+
+def test_mulmod_powmod_against_python_int():
+    rnd = random.Random(1)
+    for q in (Q50, Q60, 1099511480321, 97):
+        edge = [0, 1, 2, q - 1, q - 2, q // 2, (1 << 32) % q, ((1 << 32) - 1) % q]
+        vals = edge + [rnd.randrange(q) for _ in range(200)]
+        for a in vals:
+            for b in edge + [rnd.randrange(q)]:
+                assert lib.orc_mulmod(a, b, q) == a * b % q
+        for _ in range(20):
+            b, e = rnd.randrange(q), rnd.randrange(1 << 64)
+            assert lib.orc_powmod(b, e, q) == pow(b, e, q)
+
+
+def test_prime_chain_rule():
+    """Chain = the primes among 2^bits + 1 - k 2n, k = 1,2,.., in order, checked with an
+    independent primality test (trial by sympy) on every candidate passed over."""
+    sympy = pytest.importorskip("sympy")
+    for bits, n, cnt in ((40, 4096, 4), (50, 4096, 1), (60, 4096, 1), (50, 65536, 3), (60, 65536, 2)):
+        got = params.scan_primes(bits, n, cnt)
+        want, k = [], 1
+        while len(want) < cnt:
+            c = (1 << bits) + 1 - k * 2 * n
+            if sympy.isprime(c):
+                want.append(c)
+            k += 1
+        assert got == want
+        assert all((q - 1) % (2 * n) == 0 and q < (1 << bits) for q in got)
+
+
+def test_config_shapes():
+    c1 = params.config1()
+    assert [q.bit_length() for q in c1.q] == [50, 40, 40, 40, 40] and len(c1.p) == 1
+    assert c1.p[0].bit_length() == 60 and c1.slots == 2048 and c1.scale == 2.0 ** 40
+    c2 = params.llama_ring(24, 4, n=65536)
+    assert len(c2.q) == 24 and len(c2.p) == 4 and c2.alpha == 4 and len(c2.digits(c2.L)) == 6
+    assert c2.digits(4) == [[0, 1, 2, 3], [4]]
+    assert all(q.bit_length() == 50 for q in c2.q) and all(q.bit_length() == 60 for q in c2.p)
+
+
+def _ctx(n, **kw):
+    return ckks.Context(params.toy(n=n, **kw))
+
+
+def schoolbook_negacyclic(a, b, q):
+    n = len(a)
+    out = [0] * n
+    for i in range(n):
+        for j in range(n):
+            k, v = i + j, a[i] * b[j]
+            if k >= n:
+                out[k - n] -= v
+            else:
+                out[k] += v
+    return [x % q for x in out]
+
+
+@pytest.mark.parametrize("n", [8, 16, 64])
+def test_ntt_is_evaluation_at_odd_powers_of_psi(n):
+    ctx = _ctx(n)
+    rnd = random.Random(n)
+    idx = list(range(len(ctx.mod)))
+    a = np.array([[rnd.randrange(int(q)) for _ in range(n)] for q in ctx.mod], dtype=np.uint64)
+    A = ctx.ntt(a, idx)
+    for l, (q, psi) in enumerate(zip(ctx.mod.tolist(), ctx.psi.tolist())):
+        assert pow(psi, n, q) == q - 1
+        for k in range(n):
+            want = sum(int(a[l, i]) * pow(psi, i * (2 * k + 1), q) for i in range(n)) % q
+            assert int(A[l, k]) == want
+    assert np.array_equal(ctx.intt(A, idx), a)
+
+
+@pytest.mark.parametrize("n", [4, 32, 64])
+def test_ntt_product_is_schoolbook_negacyclic_convolution(n):
+    ctx = _ctx(n)
+    rnd = random.Random(100 + n)
+    idx = list(range(len(ctx.mod)))
+    a = np.array([[rnd.randrange(int(q)) for _ in range(n)] for q in ctx.mod], dtype=np.uint64)
+    b = np.array([[rnd.randrange(int(q)) for _ in range(n)] for q in ctx.mod], dtype=np.uint64)
+    c = ctx.intt(ctx.mul(ctx.ntt(a, idx), ctx.ntt(b, idx), idx), idx)
+    for l, q in enumerate(ctx.mod.tolist()):
+        assert c[l].tolist() == schoolbook_negacyclic(a[l].tolist(), b[l].tolist(), q)
+
+
+def test_ntt_roundtrip_and_linearity_large():
+    ctx = _ctx(4096)
+    rng = np.random.default_rng(0)
+    idx = [0, 1, 5]
+    q = ctx.mod[idx]
+    a = (rng.integers(0, 1 << 62, (3, 4096), dtype=np.uint64) % q[:, None]).astype(np.uint64)
+    b = (rng.integers(0, 1 << 62, (3, 4096), dtype=np.uint64) % q[:, None]).astype(np.uint64)
+    assert np.array_equal(ctx.intt(ctx.ntt(a, idx), idx), a)
+    assert np.array_equal(ctx.ntt(ctx.add(a, b, idx), idx),
+                          ctx.add(ctx.ntt(a, idx), ctx.ntt(b, idx), idx))
+    # X * a(X): multiplying by the monomial shifts coefficients negacyclically
+    x = np.zeros_like(a)
+    x[:, 1] = 1
+    prod = ctx.intt(ctx.mul(ctx.ntt(a, idx), ctx.ntt(x, idx), idx), idx)
+    want = np.roll(a, 1, axis=1)
+    want[:, 0] = (q - a[:, -1]) % q
+    assert np.array_equal(prod, want)
+
+
+@pytest.mark.parametrize("n,g", [(8, 3), (8, 5), (16, 31), (64, 5), (64, 25), (64, 127)])
+def test_automorphism_against_polynomial_substitution(n, g):
+    ctx = _ctx(n)
+    rnd = random.Random(g)
+    idx = [0, 1]
+    a = np.array([[rnd.randrange(int(ctx.mod[i])) for _ in range(n)] for i in idx], dtype=np.uint64)
+    got = ctx.automorphism_coeff(a, idx, g)
+    for l, i in enumerate(idx):
+        q = int(ctx.mod[i])
+        want = [0] * n
+        for k in range(n):          # a_k X^(k g), reduced with X^n = -1
+            e = k * g
+            sign = -1 if (e // n) % 2 else 1
+            want[e % n] = (want[e % n] + sign * int(a[l, k])) % q
+        assert got[l].tolist() == want
+    # evaluation-domain version permutes values: sigma(a)(psi^e) = a(psi^(e g))
+    A, B = ctx.ntt(a, idx), ctx.ntt(got, idx)
+    for k in range(n):
+        src = ((2 * k + 1) * g % (2 * n) - 1) // 2
+        assert np.array_equal(B[:, k], A[:, src])
+    assert np.array_equal(ctx.automorphism(A, idx, g), B)
+
+
+def test_base_conv_is_crt_lift_plus_small_multiple_of_basis():
+    ctx = ckks.Context(params.toy(n=64, n_qi=5, n_p=2, alpha=3))
+    rnd = random.Random(5)
+    src, dst = [0, 1, 2], [3, 4, 5, 6, 7]
+    qs = [int(ctx.mod[i]) for i in src]
+    B = math.prod(qs)
+    vals = [0, 1, B - 1, B // 2] + [rnd.randrange(B) for _ in range(60)]
+    a = np.array([[v % q for v in vals] for q in qs], dtype=np.uint64)
+    out = ctx.base_conv(a, src, dst)
+    seen_e = set()
+    for c, v in enumerate(vals):
+        # the converted residues are those of v + e*B for ONE e in [0, len(src))
+        es = [e for e in range(len(src))
+              if all(int(out[r, c]) == (v + e * B) % int(ctx.mod[i]) for r, i in enumerate(dst))]
+        assert len(es) == 1
+        seen_e.add(es[0])
+    assert seen_e - {0} and 0 in seen_e          # the overshoot really occurs, and is absent for 0
+
+
+def test_reduce_signed():
+    ctx = _ctx(8)
+    c = np.array([0, 1, -1, 2 ** 62, -(2 ** 62), 12345, -99999, 7], dtype=np.int64)
+    idx = [0, 1]
+    r = ctx.from_i64(c, idx)
+    for l, i in enumerate(idx):
+        assert r[l].tolist() == [int(v) % int(ctx.mod[i]) for v in c]
+
+
+def test_rng_definition_and_uniform_sampler():
+    M = (1 << 64) - 1
+
+    def mix(z):
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M
+        return z ^ (z >> 31)
+
+    def draw(seed, stream, ctr):
+        key = mix(mix(seed) ^ stream)
+        return mix((key + (ctr + 1) * 0x9E3779B97F4A7C15) & M)
+
+    # SplitMix64's published first output for state 0 + increment: mix(0x9E3779B97F4A7C15)
+    assert mix(0x9E3779B97F4A7C15) == 0xE220A8397B1DCDAF
+    for seed, stream, ctr in ((0, 0, 0), (1, 2, 3), (M, M, M), (42, 5 << 56 | 77, 1 << 32 | 9)):
+        assert lib.orc_rng_draw(seed, stream, ctr) == draw(seed, stream, ctr)
+    for q in (97, Q50, Q60):
+        n = 4096
+        out = np.empty(n, dtype=np.uint64)
+        lib.orc_sample_uniform(_p(out), n, q, 9, 1234)
+        bound = q * ((1 << 64) // q)
+        for i in (0, 1, 17, n - 1):
+            att = 0
+            while draw(9, 1234, att << 32 | i) >= bound:
+                att += 1
+            assert int(out[i]) == draw(9, 1234, att << 32 | i) % q
+        assert out.max() < q
+        assert abs(out.astype(np.float64).mean() / q - 0.5) < 0.03
+    # q = 97 rejects about 2^-57 of the draws; force the rejection path with a tiny modulus
+    # whose bound is far from 2^64: not possible below 2^63, so check the bound formula instead
+    assert Q60 * ((1 << 64) // Q60) <= M
+
+
+def test_gaussian_table_and_sampler():
+    cdt = ckks.gauss_cdt(3.2)
+    kmax = 19
+    assert len(cdt) == kmax
+    w = [math.exp(-k * k / (2 * 3.2 ** 2)) * (1 if k == 0 else 2) for k in range(kmax + 1)]
+    acc = 0.0
+    for k in range(kmax):
+        acc += w[k]
+        assert abs(int(cdt[k]) / 2 ** 63 - acc / sum(w)) < 1e-12
+    n = 1 << 16
+    e = np.empty(n, dtype=np.int64)
+    lib.orc_sample_gauss(_pi(e), n, _p(cdt), len(cdt), 3, 77)
+    assert abs(e.std() - 3.2) < 0.05 and abs(e.mean()) < 0.05 and np.abs(e).max() <= kmax
+    # the discrete density itself: P(X = 0) = w0 / Z
+    assert abs((e == 0).mean() - w[0] / sum(w)) < 0.01
+    assert abs((e == 3).mean() - w[3] / 2 / sum(w)) < 0.01
+
+
+def test_secret_distributions():
+    ctx = ckks.Context(params.toy(n=4096))
+    s = ctx.sample_secret(1)
+    assert set(np.unique(s)) == {-1, 0, 1}
+    assert abs((s == 0).mean() - 1 / 3) < 0.03 and abs((s == 1).mean() - 1 / 3) < 0.03
+    ctx = ckks.Context(params.toy(n=4096, hamming=192))
+    s = ctx.sample_secret(1)
+    assert (s != 0).sum() == 192 and abs(int(s.sum())) < 60
+    assert not np.array_equal(s, ctx.sample_secret(2))

@@ -1,0 +1,78 @@
+"""Oracle end to end: decrypted homomorphic products against the float64 products they stand
+for (the result has a plain definition: y = x W, m = q K^T per head, Att = s V per head)."""
+import numpy as np
+import pytest
+
+from oracle import ckks, packing, params, vmm
+from paper_2602_11470_amd import inputs
+
+TOL = 1e-4      # max-abs tolerance on decrypted results
+
+
+def test_config1_vmm_decrypts_to_x_times_W():
+    prm = params.config1()
+    ctx = ckks.Context(prm)
+    x, W = inputs.vmm_inputs(0, 64, 64, "uniform", 0.05)
+    plan = packing.make_plan(ctx.S, 64, 64)
+    sk = ctx.keygen_secret(1)
+    keys = ctx.keygen_rotations(sk, plan.all_steps(), 2)
+    assert len(keys) == 11
+    ct = ctx.encrypt(sk, ctx.encode(plan.pack_input(x), prm.L), 3)
+    diags = [[ctx.encode(v, prm.L) for v in row] for row in plan.diagonals(W)]
+    y = vmm.vmm_pt(vmm.CkksOps(ctx, keys), plan, ct, diags)
+    assert (ctx.rot_count, ctx.ptmul_count) == (11, 2)
+    assert y.level == prm.L - 1                      # depth 1
+    out = ctx.decrypt(sk, y)
+    assert np.abs(plan.unpack_output(out.real) - x @ W).max() < TOL
+    assert np.abs(out.imag).max() < TOL
+
+
+@pytest.mark.parametrize("d_in,d_out,level,tau", [(16, 16, 3, 0), (16, 64, 2, 0), (64, 16, 4, 0),
+                                                  (32, 32, 1, 3)])
+def test_small_ring_vmm_shapes_and_levels(d_in, d_out, level, tau):
+    prm = params.toy(n=512, n_qi=4, n_p=2, alpha=2, hamming=32)
+    ctx = ckks.Context(prm)
+    x, W = inputs.vmm_inputs(5, d_in, d_out, "normal", 0.1)
+    plan = packing.make_plan(ctx.S, d_in, d_out, tau=tau)
+    sk = ctx.keygen_secret(1)
+    keys = ctx.keygen_rotations(sk, plan.all_steps(), 2)
+    ct = ctx.level_drop(ctx.encrypt(sk, ctx.encode(plan.pack_input(x), prm.L), 3), level)
+    diags = [[ctx.encode(v, level) for v in row] for row in plan.diagonals(W)]
+    y = vmm.vmm_pt(vmm.CkksOps(ctx, keys), plan, ct, diags)
+    assert y.level == level - 1
+    assert np.abs(plan.unpack_output(ctx.decrypt(sk, y).real) - x @ W).max() < TOL
+
+
+@pytest.mark.parametrize("r_i", [0, 4])
+def test_small_ring_attention_and_append(r_i):
+    prm = params.toy(n=512, n_qi=4, n_p=1, alpha=1)
+    ctx = ckks.Context(prm)
+    L = prm.L
+    lay = packing.KvLayout(ctx.S, 4, 8, r_i)
+    ntok = lay.capacity - 3
+    q, K, V, s = inputs.attention_inputs(2, 4, 2, 8, ntok)
+    sk = ctx.keygen_secret(1)
+    keys = ctx.keygen_rotations(sk, lay.qk_steps() + lay.sv_steps() + lay.append_steps(), 2,
+                                with_relin=True)
+    ops = vmm.CkksOps(ctx, keys)
+    enc = lambda v, lv, seed: ctx.encrypt(sk, ctx.encode(v, lv), seed)
+    # build the cache by appending token after token (inputs one level above the cache)
+    kc, vc = [], [None] * lay.E
+    for n in range(ntok):
+        tau = n % lay.t
+        vmm.kv_append(ops, lay, kc, vc, n, enc(lay.pack_vec(K[n], tau), L, 100 + n),
+                      enc(lay.pack_vec(V[n], tau), L, 500 + n), lay.residue_mask(tau),
+                      [lay.v_append_mask(k, n) for k in range(lay.E)])
+    for c in (0, len(kc) - 1):
+        assert np.abs(ctx.decrypt(sk, kc[c]).real - lay.pack_k(K, c)).max() < TOL
+    for k in (0, lay.E - 1):
+        assert np.abs(ctx.decrypt(sk, vc[k]).real - lay.pack_v(V, k)).max() < TOL
+    cq = ctx.level_drop(enc(lay.pack_vec(q), L, 10), L - 1)
+    m = vmm.qk_scores(ops, lay, cq, kc, [lay.qk_mask(c) for c in range(len(kc))])
+    assert m.level == L - 3                            # depth 2 below the cache level
+    got = lay.unpack_scores(ctx.decrypt(sk, m).real, ntok)
+    assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
+    cs = ctx.level_drop(enc(lay.pack_scores(s), L, 50), L - 1)
+    a = vmm.score_times_v(ops, lay, cs, vc)
+    assert a.level == L - 2
+    assert np.abs(lay.unpack_vec(ctx.decrypt(sk, a).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
