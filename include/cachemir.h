@@ -1,0 +1,229 @@
+/*
+ * libcachemir -- homomorphic vector-matrix products of one LLM decode step on one MI355X.
+ *
+ * The operations are those of the Cachemir paper: RNS-CKKS ciphertext operations (Sec. 2.1),
+ * the packed activation-row x plaintext-matrix product with interleaved replicated packing
+ * (Sec. 4.1, App. C / Algorithm 1), and the products against the encrypted KV cache with its
+ * append (Sec. 5.1-5.3).  The paper treats the CKKS primitives as given; they are the
+ * textbook full-RNS scheme with hybrid key switching (digits of `alpha` primes, fast
+ * non-centred base conversion, floor division by the special modulus).
+ *
+ * Conventions
+ *  - Every function returns a cm_status (0 = CM_OK, negative = error) and never throws,
+ *    aborts or exits.  On error the outputs are untouched.
+ *  - "host" / "device" says where a pointer must live.  A cm_ct / cm_pt is a small descriptor
+ *    over CALLER-ALLOCATED device memory of cm_ct_words()/cm_pt_words() 64-bit words; the
+ *    library never frees or reallocates it.  Opaque handles own their device memory and are
+ *    released by the matching *_destroy.
+ *  - Ring degree n (the paper's N'), S = n/2 slots (the paper's N).  Ciphertext level l has
+ *    l+1 limbs.  Polynomials are stored in the evaluation (NTT) domain in an internal order;
+ *    cm_ct_export() gives the canonical interchange form: coefficient domain, residues in
+ *    [0, q_i), order [component][limb][coefficient].
+ *  - `stream` is a hipStream_t passed as void* (0 = the null stream).  Calls that take a
+ *    stream only enqueue work; the others synchronise.
+ *  - A context's scratch arena is shared by all calls on it: calls on one context must not
+ *    overlap in time.
+ */
+#ifndef CACHEMIR_H
+#define CACHEMIR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t cm_status;
+enum {
+    CM_OK = 0,
+    CM_E_INVAL = -1,   /* bad argument (null pointer, size, unsupported ring degree) */
+    CM_E_LEVEL = -2,   /* no level left, or operand levels differ */
+    CM_E_SCALE = -3,   /* operand scales differ */
+    CM_E_NOKEY = -4,   /* rotation step or relinearisation key not generated */
+    CM_E_LAYOUT = -5,  /* plan / cache / ciphertext shapes do not fit together */
+    CM_E_NOMEM = -6,   /* device or host allocation failed */
+    CM_E_HIP = -7      /* a HIP call failed; see cm_last_hip_error() */
+};
+const char *cm_strerror(cm_status s);
+int32_t cm_last_hip_error(void);
+
+/* Parameter set.  The modulus chain is derived inside the library by the rule
+ *   candidates 2^bits + 1 - k*2n (k = 1,2,..), primes kept in order:
+ * q_0 from q0_bits, q_1..q_{n_q-1} from qi_bits (one scan: if q0_bits == qi_bits the chain is
+ * the first n_q primes of that scan), special primes p_0..p_{n_p-1} from p_bits.
+ * alpha = primes per key-switch digit.  hamming = 0: i.i.d. uniform ternary secret, else the
+ * exact number of non-zero secret coefficients.  sigma must be 3.2 (error table is fixed). */
+typedef struct {
+    int32_t n;          /* ring degree: 4096 or 65536 */
+    int32_t n_q;        /* ciphertext primes (top level L = n_q - 1) */
+    int32_t n_p;        /* special primes K */
+    int32_t alpha;      /* primes per digit */
+    int32_t q0_bits, qi_bits, p_bits;
+    int32_t hamming;
+    double scale;       /* default encoding scale Delta */
+    double sigma;
+} cm_params;
+
+typedef struct cm_ctx cm_ctx;
+typedef struct cm_sk cm_sk;
+typedef struct cm_evk cm_evk;
+typedef struct cm_vmm_plan cm_vmm_plan;
+typedef struct cm_kv cm_kv;
+
+typedef struct {
+    uint64_t *dev;      /* device: ncomp * (level+1) * n words */
+    int32_t level;
+    int32_t ncomp;      /* 2, or 3 before relinearisation */
+    double scale;
+} cm_ct;
+
+typedef struct {
+    uint64_t *dev;      /* device: (level+1) * n words */
+    int32_t level;
+    int32_t mont;       /* 1: stored pre-multiplied by 2^64 mod q_i (multiplier operand form) */
+    double scale;
+} cm_pt;
+
+/* ---- context ------------------------------------------------------------------------ */
+/* Builds primes, roots, twiddle and conversion tables and uploads them; allocates the scratch
+ * arena.  Uses the current HIP device. */
+cm_status cm_ctx_create(const cm_params *p, cm_ctx **out);
+void cm_ctx_destroy(cm_ctx *ctx);
+/* host out[n_q + n_p]: q_0..q_L then p_0..p_{K-1}. */
+cm_status cm_ctx_moduli(const cm_ctx *ctx, uint64_t *out);
+size_t cm_ct_words(const cm_ctx *ctx, int32_t level, int32_t ncomp);
+size_t cm_pt_words(const cm_ctx *ctx, int32_t level);
+/* host out[19]: the cumulative table of the error sampler (for cross-checks). */
+cm_status cm_ctx_gauss_table(const cm_ctx *ctx, uint64_t *out);
+
+/* ---- keys (Sec. 2.1 rotation / ct-ct multiplication need them; client side) ---------- */
+cm_status cm_keygen_secret(cm_ctx *ctx, uint64_t seed, cm_sk **out);
+void cm_sk_destroy(cm_sk *sk);
+/* host out[n]: secret coefficients in {-1,0,1}. */
+cm_status cm_sk_coeffs(const cm_ctx *ctx, const cm_sk *sk, int8_t *out);
+/* Keys for left rotations by steps[i] slots (negative = right), and for s^2 -> s if
+ * with_relin.  Steps with equal Galois element share a key. */
+cm_status cm_keygen_rotations(cm_ctx *ctx, const cm_sk *sk, const int32_t *steps, size_t nsteps,
+                              int32_t with_relin, uint64_t seed, cm_evk **out);
+void cm_evk_destroy(cm_evk *evk);
+/* Canonical (coefficient-domain, plain residues) copy of one key polynomial to host
+ * out[(L+1+K)*n]: step = rotation step (ignored if relin != 0), comp 0 = b, 1 = a. */
+cm_status cm_evk_export(cm_ctx *ctx, const cm_evk *evk, int32_t step, int32_t relin,
+                        int32_t digit, int32_t comp, uint64_t *out);
+
+/* ---- encode / encrypt / decrypt (client side, Sec. 2.1 last paragraph) ---------------- */
+/* Integer coefficients round(scale * m_k) of the polynomial whose slot values are
+ * re[j] + i*im[j] (im may be NULL; slots past nslots are 0).  host in, host out[n]. */
+cm_status cm_encode_coeffs(const cm_ctx *ctx, const double *re, const double *im, size_t nslots,
+                           double scale, int64_t *out);
+/* Signed coefficients (host, n of them) -> plaintext in out->dev.  out->dev, out->mont must be
+ * set by the caller; level and scale are written. */
+cm_status cm_pt_from_coeffs(cm_ctx *ctx, const int64_t *coeffs, int32_t level, double scale,
+                            cm_pt *out);
+cm_status cm_encode(cm_ctx *ctx, const double *re, const double *im, size_t nslots,
+                    int32_t level, double scale, cm_pt *out);
+/* Symmetric encryption (c0, c1) = (-a s + e + m, a); pt must have mont == 0. */
+cm_status cm_encrypt(cm_ctx *ctx, const cm_sk *sk, const cm_pt *pt, uint64_t seed, cm_ct *out);
+/* c0 + c1 s (+ c2 s^2) on the lowest min(level,1)+1 limbs -> out (mont = 0). */
+cm_status cm_decrypt(cm_ctx *ctx, const cm_sk *sk, const cm_ct *ct, cm_pt *out);
+/* Slot values of a plaintext of level <= 1.  host re/im[nslots] (im may be NULL). */
+cm_status cm_decode(cm_ctx *ctx, const cm_pt *pt, double *re, double *im, size_t nslots);
+/* Canonical form to host out[ncomp*(level+1)*n]. */
+cm_status cm_ct_export(cm_ctx *ctx, const cm_ct *ct, uint64_t *out);
+cm_status cm_pt_export(cm_ctx *ctx, const cm_pt *pt, uint64_t *out);
+
+/* ---- ciphertext operations of Sec. 2.1 ------------------------------------------------ */
+cm_status cm_add(cm_ctx *ctx, const cm_ct *a, const cm_ct *b, cm_ct *out, void *stream);
+/* out = a * pt (pt->mont must be 1); scale multiplies, level unchanged (rescale separately). */
+cm_status cm_mul_pt(cm_ctx *ctx, const cm_ct *a, const cm_pt *pt, cm_ct *out, void *stream);
+/* Tensor product, three components, not relinearised. */
+cm_status cm_mul_ct(cm_ctx *ctx, const cm_ct *a, const cm_ct *b, cm_ct *out, void *stream);
+cm_status cm_relinearize(cm_ctx *ctx, const cm_evk *evk, const cm_ct *a, cm_ct *out, void *stream);
+/* Division by the last prime (floor variant): level drops by one. */
+cm_status cm_rescale(cm_ctx *ctx, const cm_ct *a, cm_ct *out, void *stream);
+cm_status cm_level_drop(cm_ctx *ctx, const cm_ct *a, int32_t level, cm_ct *out, void *stream);
+/* Rot(in, step)[i] = in[i + step]: Galois map, then key switch of the second component. */
+cm_status cm_rotate(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, int32_t step, cm_ct *out,
+                    void *stream);
+/* nsteps rotations of ONE ciphertext that share the raised digits of its second component
+ * (the map is applied after raising, so limbs differ from cm_rotate's; both are valid). */
+cm_status cm_rotate_hoisted(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, const int32_t *steps,
+                            size_t nsteps, cm_ct *outs, void *stream);
+
+/* ---- packed plaintext product (Sec. 4.1, Algorithm 1) ---------------------------------- */
+/* W: host, row-major d_in x d_out.  One of d_in == d_out, d_out = alpha*d_in, d_in =
+ * alpha*d_out (alpha a power of two); S/min(d) and S/max(d) must be integers.  r_i = baby
+ * steps (0 = default near sqrt of the diagonal count); tau = residue the outputs land on
+ * (0, or the slot residue of a token about to be appended to the cache).  The weight diagonals
+ * are encoded at `pt_scale` (0 = the context scale) for input level `level` and stay on the
+ * device.  Layouts: input element a at slot a*t (d_in <= d_out) or (a%d)*t + (a/d)*t'
+ * (d_in > d_out); output element c at slot c*t + tau, or (c%d)*t + (c/d)*t' + tau when
+ * expanding; d = min(d_in, d_out), t = S/d, t' = S/max(d_in, d_out). */
+cm_status cm_vmm_plan_create(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
+                             int32_t level, double pt_scale, const double *W, cm_vmm_plan **out);
+/* Same, from already rounded integer coefficients of the r_i*r_o diagonals:
+ * coeffs[(j*r_o + k)*n + c], host. */
+cm_status cm_vmm_plan_create_from_coeffs(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i,
+                                         int32_t tau, int32_t level, double pt_scale,
+                                         const int64_t *coeffs, cm_vmm_plan **out);
+void cm_vmm_plan_destroy(cm_vmm_plan *plan);
+/* Rotation steps the plan uses: returns their number, writes up to cap of them (host). */
+int32_t cm_vmm_plan_steps(const cm_vmm_plan *plan, int32_t *steps, int32_t cap);
+/* r_i, r_o, and the integer coefficients are not kept; the encoded diagonal (j, k) in canonical
+ * plain residues to host out[(level+1)*n]. */
+cm_status cm_vmm_plan_info(const cm_vmm_plan *plan, int32_t *r_i, int32_t *r_o, int32_t *n_rot);
+cm_status cm_vmm_plan_diag_export(cm_ctx *ctx, const cm_vmm_plan *plan, int32_t j, int32_t k,
+                                  uint64_t *out);
+/* y = x W.  x at the plan's level; y one level lower, scale x.scale*pt_scale/q_level.  Slots
+ * other than the output slots hold partial sums (masking is left to the next layer, Sec. 4.2). */
+cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *plan, const cm_ct *x,
+                    cm_ct *y, void *stream);
+
+/* ---- encrypted KV cache (Sec. 5) -------------------------------------------------------- */
+enum { CM_QK = 0, CM_SV = 1 };
+/* Cache for `heads` heads of `dim` dims (heads*dim*t = S) holding up to max_tokens tokens
+ * (<= dim*t) at ciphertext level `level` and scale `scale`.  r_i = baby steps of the
+ * score-times-V product (0 = dim, no giant steps). */
+cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level,
+                       double scale, int32_t max_tokens, cm_kv **out);
+void cm_kv_destroy(cm_kv *kv);
+int32_t cm_kv_steps(const cm_kv *kv, int32_t *steps, int32_t cap);
+int32_t cm_kv_tokens(const cm_kv *kv);
+/* Install an already packed cache ciphertext (which = CM_QK: K ciphertext idx; CM_SV: V
+ * ciphertext idx) and set the token count. */
+cm_status cm_kv_load(cm_ctx *ctx, cm_kv *kv, int32_t which, int32_t idx, const cm_ct *ct,
+                     void *stream);
+cm_status cm_kv_set_tokens(cm_kv *kv, int32_t ntok);
+cm_status cm_kv_export(cm_ctx *ctx, const cm_kv *kv, int32_t which, int32_t idx, uint64_t *out);
+/* Every mask the cache uses is a slot rotation of one of three base masks, applied as the
+ * Galois permutation of the encoded base.  This replaces a base by given integer coefficients
+ * (host, n of them; encoding scale = the prime the following rescale removes): kind 0 = slots
+ * (0, h, tau) for all h, tau, at level-1 (keeps one copy of the replicated scores, Sec. 5.1 step
+ * 3); kind 1 = slots of residue 0 at level+1 (K append); kind 2 = slots (0, h, 0) at level+1 (V
+ * append, Sec. 5.2).  For callers that need bit-identical plaintexts on two implementations. */
+cm_status cm_kv_set_mask(cm_kv *kv, int32_t kind, const int64_t *coeffs);
+/* Append the next token: k_new / v_new hold the new vectors at residue tau = ntok mod t, one
+ * level above the cache; they are masked (one plaintext product each) and added. */
+cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_new,
+                       const cm_ct *v_new, void *stream);
+/* which = CM_QK: in = query at (e, h, 0) slots, cache level; out = scores, two levels lower.
+ * which = CM_SV: in = scores; out = attention output at (e, h, 0), one level lower. */
+cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t which,
+                    const cm_ct *in, cm_ct *out, void *stream);
+
+/* ---- building blocks exposed for measurement and parity -------------------------------- */
+/* Forward / inverse negacyclic NTT of `limbs` limbs in place (device), limb i under modulus
+ * index mod_idx[i] (host array; indices into q_0..q_L,p_0..). */
+cm_status cm_ntt(cm_ctx *ctx, uint64_t *dev, const int32_t *mod_idx, int32_t limbs,
+                 int32_t inverse, void *stream);
+/* One hybrid key switch of an evaluation-domain polynomial d[level+1][n] (device) with the key
+ * of rotation `step` (or the relinearisation key): ks0, ks1 device [level+1][n]. */
+cm_status cm_keyswitch(cm_ctx *ctx, const cm_evk *evk, int32_t step, int32_t relin,
+                       const uint64_t *d, int32_t level, uint64_t *ks0, uint64_t *ks1,
+                       void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

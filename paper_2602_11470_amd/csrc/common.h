@@ -1,0 +1,145 @@
+// Internal declarations of libcachemir: modular limb arithmetic for gfx950, context tables
+// and kernel launchers.  Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <map>
+#include <vector>
+
+#include "../../include/cachemir.h"
+
+typedef uint64_t u64;
+typedef unsigned __int128 u128;
+
+// ---- 64-bit modular arithmetic -----------------------------------------------------------
+// All moduli are below 2^62.  Three multiplier forms are used:
+//   Shoup:      constant w with companion wp = floor(w 2^64 / q); result in [0, 2q) (lazy).
+//   Montgomery: one operand pre-multiplied by 2^64 mod q; products are accumulated in 128
+//               bits and reduced once (REDC), result in [0, q).
+struct ModC {
+    u64 q;
+    u64 qinv;   // q^{-1} mod 2^64
+    u64 r2;     // 2^128 mod q
+};
+
+__host__ __device__ __forceinline__ u64 mulhi64(u64 a, u64 b) {
+#ifdef __HIP_DEVICE_COMPILE__
+    return __umul64hi(a, b);
+#else
+    return (u64)(((u128)a * b) >> 64);
+#endif
+}
+
+// a*w mod q in [0, 2q) for any a < 2^64
+__device__ __forceinline__ u64 mul_shoup_lazy(u64 a, u64 w, u64 wp, u64 q) {
+    return a * w - mulhi64(a, wp) * q;
+}
+__device__ __forceinline__ u64 mul_shoup(u64 a, u64 w, u64 wp, u64 q) {
+    u64 r = mul_shoup_lazy(a, w, wp, q);
+    return r >= q ? r - q : r;
+}
+// T 2^-64 mod q in [0, q), for T with (T >> 64) < q
+__device__ __forceinline__ u64 redc(u128 T, u64 q, u64 qinv) {
+    u64 lo = (u64)T, hi = (u64)(T >> 64);
+    u64 t = mulhi64(lo * qinv, q);
+    u64 r = hi - t;
+    return hi < t ? r + q : r;
+}
+// a 2^64 mod q
+__device__ __forceinline__ u64 to_mont(u64 a, const ModC &m) { return redc((u128)a * m.r2, m.q, m.qinv); }
+__device__ __forceinline__ u64 addmod(u64 a, u64 b, u64 q) {
+    u64 s = a + b;
+    return s >= q ? s - q : s;
+}
+__device__ __forceinline__ u64 submod(u64 a, u64 b, u64 q) { return a >= b ? a - b : a + q - b; }
+
+// ---- context -----------------------------------------------------------------------------
+#define CM_MAX_LIMBS 64
+#define CM_MAX_DIGITS 16
+#define CM_GAUSS_K 19
+
+struct ConvTable {            // fast base conversion src -> dst (all indices into the modulus list)
+    int ns = 0, nt = 0;
+    u64 *d_inv_hat = nullptr;     // [ns]   (hat_m^{-1} mod q_m), plain
+    u64 *d_inv_hat_sh = nullptr;  // [ns]   Shoup companion
+    u64 *d_hat_mont = nullptr;    // [ns*nt] (hat_m mod r) 2^64 mod r
+    int *d_src = nullptr, *d_dst = nullptr;
+    std::vector<int> src, dst;
+};
+
+struct cm_ctx {
+    cm_params prm;
+    int n, logn, L, K, alpha, nmod;      // nmod = L+1+K
+    std::vector<u64> mod;                 // host copy of moduli
+    std::vector<u64> psi;
+    // device tables, indexed by modulus index
+    ModC *d_modc = nullptr;               // [nmod]
+    u64 *d_tw = nullptr, *d_twp = nullptr;      // forward twiddles psi^brev(i) and companions [nmod][n]
+    u64 *d_itw = nullptr, *d_itwp = nullptr;    // inverse
+    u64 *d_ninv = nullptr, *d_ninvp = nullptr;  // n^{-1} [nmod]
+    std::vector<ModC> modc;
+    // per-level tables (built lazily, kept): ModUp per digit, ModDown, rescale constants
+    std::map<int, std::vector<ConvTable>> modup;   // level -> digit tables
+    std::map<int, ConvTable> moddown;              // level -> P -> q_0..q_level
+    std::map<int, u64 *> pinv;                     // level -> [level+1][2]: P^{-1} mod q_i, Shoup
+    std::map<int, u64 *> qlinv;                    // level -> [level][2]: q_level^{-1} mod q_i, Shoup
+    u64 *d_cdt = nullptr;                          // Gaussian table [CM_GAUSS_K]
+    u64 cdt[CM_GAUSS_K];
+    int lazy_terms;                                // products that may be summed before one REDC
+    // scratch arena
+    u64 *arena = nullptr;
+    size_t arena_words = 0;
+    int *d_idx = nullptr;                          // small device int scratch for modulus index lists
+    // encode tables (host)
+    std::vector<int> slot_pos;
+    std::vector<double> tw_re, tw_im;              // omega^k
+};
+
+struct cm_sk {
+    std::vector<int8_t> coeffs;
+    u64 *d_ntt = nullptr;          // [nmod][n], Montgomery form, evaluation domain
+};
+
+struct EvkEntry {
+    u64 *d = nullptr;              // [digits][2][nmod][n] Montgomery form, evaluation domain
+};
+struct cm_evk {
+    int digits;
+    std::map<u64, EvkEntry> keys;  // Galois element (0 = relinearisation)
+};
+
+#define HIPCHK(x)                                  \
+    do {                                           \
+        hipError_t e_ = (x);                       \
+        if (e_ != hipSuccess) {                    \
+            cm_set_hip_error((int)e_);             \
+            return CM_E_HIP;                       \
+        }                                          \
+    } while (0)
+#define CMCHK(x)                \
+    do {                        \
+        cm_status s_ = (x);     \
+        if (s_ != CM_OK) return s_; \
+    } while (0)
+
+void cm_set_hip_error(int e);
+
+// ---- host helpers (context.hip) ------------------------------------------------------------
+u64 h_mulmod(u64 a, u64 b, u64 q);
+u64 h_powmod(u64 b, u64 e, u64 q);
+u64 h_invmod(u64 a, u64 q);
+u64 h_shoup(u64 w, u64 q);
+u64 galois_of_step(const cm_ctx *ctx, int step);
+const std::vector<ConvTable> &get_modup(cm_ctx *ctx, int level);
+const ConvTable &get_moddown(cm_ctx *ctx, int level);
+const u64 *get_pinv(cm_ctx *ctx, int level);
+const u64 *get_qlinv(cm_ctx *ctx, int level);
+std::vector<std::vector<int>> digits_at(const cm_ctx *ctx, int level);
+
+// ---- kernel launchers ----------------------------------------------------------------------
+// ntt.hip: limbs of n words each, limb i under modulus d_mod_idx[i] (device int array)
+void launch_ntt(cm_ctx *ctx, u64 *data, const int *d_mod_idx, int limbs, bool inverse, hipStream_t st);
+// convenience: limbs use consecutive modulus indices first, first+1, ...
+void launch_ntt_range(cm_ctx *ctx, u64 *data, int first_mod, int limbs, bool inverse, hipStream_t st);
+const int *iota_idx(cm_ctx *ctx);   // device array 0,1,2,...,CM_MAX_LIMBS-1

@@ -1,0 +1,54 @@
+// Launchers of the kernels in kernels.hip.  All pointers are device pointers unless named h_*.
+#pragma once
+#include "common.h"
+
+void launch_reduce_i64(cm_ctx *ctx, u64 *out, const long long *d_coeffs, const int *d_mod_idx, int limbs, hipStream_t st);
+void launch_to_mont(cm_ctx *ctx, u64 *data, const int *d_mod_idx, int limbs, hipStream_t st);
+void launch_from_mont(cm_ctx *ctx, u64 *out, const u64 *in, const int *d_mod_idx, int limbs, hipStream_t st);
+void launch_add(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int ncomp, int limbs, hipStream_t st);
+void launch_mul_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, hipStream_t st);
+void launch_mac_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, int accumulate, hipStream_t st);
+void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st);
+void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st);
+void launch_base_conv(cm_ctx *ctx, const ConvTable &t, u64 *out, const int *d_out_rows, const u64 *in,
+                      const int *d_in_rows, int batch, size_t in_stride, size_t out_stride, hipStream_t st);
+void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g, hipStream_t st);
+void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
+                           int addend_comps, int level, u64 g, hipStream_t st);
+void launch_rescale_reduce(cm_ctx *ctx, u64 *red, const u64 *last, int ncomp, int level, hipStream_t st);
+void launch_rescale_finish(cm_ctx *ctx, u64 *out, const u64 *in, const u64 *red, const u64 *d_qlinv, int ncomp, int level, hipStream_t st);
+u64 rng_key(u64 seed, u64 stream);
+u64 rng_draw(u64 key, u64 ctr);
+void launch_sample_uniform(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs, u64 seed, u64 stream_base, hipStream_t st);
+void launch_sample_gauss(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs, u64 seed, u64 stream, hipStream_t st);
+void launch_evk_assemble(cm_ctx *ctx, u64 *b_out, u64 *a_io, const u64 *e, const u64 *s_mont, const u64 *d_fac, u64 g, hipStream_t st);
+void launch_encrypt(cm_ctx *ctx, u64 *c0, const u64 *a, const u64 *e, const u64 *s_mont, const u64 *pt, int limbs, hipStream_t st);
+void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int ncomp, int ct_limbs, int limbs, hipStream_t st);
+void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, hipStream_t st);
+
+// ops.hip internals shared with vmm.hip
+struct KsLevel {            // cached per level: which rows of the digit array are converted / transformed
+    int level, ext, beta;
+    std::vector<int *> d_out_rows;    // per digit: rows (within one digit's [ext] block) the conversion writes
+    std::vector<int *> d_in_rows;     // per digit: rows of the input polynomial it reads
+    int *d_ntt_rows = nullptr;        // rows of the [beta*ext] digit array to transform
+    int *d_ntt_mods = nullptr;        // their modulus indices
+    int n_ntt = 0;
+    int *d_own_rows = nullptr;        // rows of the digit array that are copies of input limbs
+    int *d_sp_rows = nullptr;         // rows level+1.. of an ext-sized array (special limbs), for both components
+    int *d_sp_mods = nullptr;
+    int *d_q_rows = nullptr;          // 0..level
+};
+const KsLevel &ks_level(cm_ctx *ctx, int level);
+// digits[beta][ext][n] (evaluation domain) from evaluation-domain d[level+1][n]
+cm_status ks_raise(cm_ctx *ctx, const u64 *d, int level, u64 *digits, hipStream_t st);
+// (out0, out1) = ModDown(sum_j perm_g(digits_j) * evk_j) [+ perm_g(addend) on component 0]; out = [2][level+1][n]
+// addend_comps: 0 none, 1 component 0 only (rotation), 2 both (relinearisation)
+cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u64 g, const u64 *addend,
+                   int addend_comps, u64 *out, hipStream_t st);
+cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64 g, u64 *out, hipStream_t st);
+cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st);
+u64 *arena_digits(const cm_ctx *ctx);
+const u64 *find_key(const cm_evk *evk, u64 g);
+void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mods, int limbs, bool inverse, hipStream_t st);
+void decode_host(const cm_ctx *ctx, const std::vector<double> &m, double *re, double *im, size_t nslots);

@@ -1,0 +1,374 @@
+// Element-wise, base-conversion, key-switch and sampling kernels of libcachemir (gfx950).
+// Polynomials are [limbs][n] 64-bit words.  "mont" operands are pre-multiplied by 2^64 mod q.
+#include "kernels.h"
+
+#define TPB 256
+
+// position i of the evaluation order holds the value at psi^(2 brev(i) + 1); the Galois map
+// X -> X^g moves the value at exponent e*g to exponent e.
+__device__ __forceinline__ unsigned perm_src(unsigned i, unsigned g, int logn) {
+    unsigned e = 2u * (__brev(i) >> (32 - logn)) + 1u;
+    unsigned s = (e * g) & ((2u << logn) - 1u);
+    return __brev((s - 1u) >> 1) >> (32 - logn);
+}
+
+// ---- signed integers -> residues -------------------------------------------------------------
+__global__ void k_reduce_i64(u64 *out, const long long *coeffs, const int *mod_idx, const ModC *modc, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
+    const ModC m = modc[mod_idx[l]];
+    long long c = coeffs[i];
+    u64 a = c < 0 ? (u64)(-(c + 1)) + 1ULL : (u64)c;        // |c| without overflow
+    u64 r = redc((u128)to_mont(a, m), m.q, m.qinv);         // |c| mod q
+    out[(size_t)l * n + i] = (c < 0 && r) ? m.q - r : r;
+}
+void launch_reduce_i64(cm_ctx *ctx, u64 *out, const long long *d_coeffs, const int *d_mod_idx, int limbs, hipStream_t st) {
+    hipLaunchKernelGGL(k_reduce_i64, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, d_coeffs, d_mod_idx, ctx->d_modc, ctx->n);
+}
+
+__global__ void k_to_mont(u64 *data, const int *mod_idx, const ModC *modc, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
+    const ModC m = modc[mod_idx[l]];
+    size_t o = (size_t)l * n + i;
+    data[o] = to_mont(data[o], m);
+}
+void launch_to_mont(cm_ctx *ctx, u64 *data, const int *d_mod_idx, int limbs, hipStream_t st) {
+    hipLaunchKernelGGL(k_to_mont, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, data, d_mod_idx, ctx->d_modc, ctx->n);
+}
+__global__ void k_from_mont(u64 *out, const u64 *in, const int *mod_idx, const ModC *modc, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
+    const ModC m = modc[mod_idx[l]];
+    size_t o = (size_t)l * n + i;
+    out[o] = redc((u128)in[o], m.q, m.qinv);
+}
+void launch_from_mont(cm_ctx *ctx, u64 *out, const u64 *in, const int *d_mod_idx, int limbs, hipStream_t st) {
+    hipLaunchKernelGGL(k_from_mont, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, in, d_mod_idx, ctx->d_modc, ctx->n);
+}
+
+// ---- ciphertext element-wise ---------------------------------------------------------------------
+// rows = ncomp*limbs; row r has modulus index r % limbs
+__global__ void k_add(u64 *out, const u64 *a, const u64 *b, const ModC *modc, int limbs, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, r = blockIdx.y;
+    u64 q = modc[r % limbs].q;
+    size_t o = (size_t)r * n + i;
+    out[o] = addmod(a[o], b[o], q);
+}
+void launch_add(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int ncomp, int limbs, hipStream_t st) {
+    hipLaunchKernelGGL(k_add, dim3(ctx->n / TPB, ncomp * limbs), dim3(TPB), 0, st, out, a, b, ctx->d_modc, limbs, ctx->n);
+}
+
+__global__ void k_mul_pt(u64 *out, const u64 *a, const u64 *pt_mont, const ModC *modc, int limbs, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, r = blockIdx.y;
+    const ModC m = modc[r % limbs];
+    size_t o = (size_t)r * n + i;
+    out[o] = redc((u128)a[o] * pt_mont[(size_t)(r % limbs) * n + i], m.q, m.qinv);
+}
+void launch_mul_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, hipStream_t st) {
+    hipLaunchKernelGGL(k_mul_pt, dim3(ctx->n / TPB, ncomp * limbs), dim3(TPB), 0, st, out, a, pt_mont, ctx->d_modc, limbs, ctx->n);
+}
+
+// acc (+)= a * pt_mont over ncomp components; accumulate != 0 adds into out
+__global__ void k_mac_pt(u64 *out, const u64 *a, const u64 *pt_mont, const ModC *modc, int limbs, int n, int accumulate) {
+    int i = blockIdx.x * TPB + threadIdx.x, r = blockIdx.y;
+    const ModC m = modc[r % limbs];
+    size_t o = (size_t)r * n + i;
+    u64 v = redc((u128)a[o] * pt_mont[(size_t)(r % limbs) * n + i], m.q, m.qinv);
+    out[o] = accumulate ? addmod(out[o], v, m.q) : v;
+}
+void launch_mac_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, int accumulate, hipStream_t st) {
+    hipLaunchKernelGGL(k_mac_pt, dim3(ctx->n / TPB, ncomp * limbs), dim3(TPB), 0, st, out, a, pt_mont, ctx->d_modc, limbs, ctx->n, accumulate);
+}
+
+// Tensor product of two 2-component ciphertexts: (a0 b0, a0 b1 + a1 b0, a1 b1); accumulate adds.
+__global__ void k_tensor(u64 *out, const u64 *a, const u64 *b, const ModC *modc, int limbs, int n, int accumulate) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
+    const ModC m = modc[l];
+    size_t o = (size_t)l * n + i, cs = (size_t)limbs * n;
+    u64 a0 = to_mont(a[o], m), a1 = to_mont(a[o + cs], m);
+    u64 b0 = b[o], b1 = b[o + cs];
+    u64 d0 = redc((u128)a0 * b0, m.q, m.qinv);
+    u64 d1 = redc((u128)a0 * b1 + (u128)a1 * b0, m.q, m.qinv);     // two products: (T >> 64) < q holds for q < 2^63
+    u64 d2 = redc((u128)a1 * b1, m.q, m.qinv);
+    if (accumulate) {
+        d0 = addmod(d0, out[o], m.q);
+        d1 = addmod(d1, out[o + cs], m.q);
+        d2 = addmod(d2, out[o + 2 * cs], m.q);
+    }
+    out[o] = d0;
+    out[o + cs] = d1;
+    out[o + 2 * cs] = d2;
+}
+void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st) {
+    hipLaunchKernelGGL(k_tensor, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, a, b, ctx->d_modc, limbs, ctx->n, accumulate);
+}
+
+// Galois map on evaluation-domain rows (a pure permutation); rows = ncomp*limbs
+__global__ void k_automorphism(u64 *out, const u64 *in, int n, int logn, unsigned g) {
+    unsigned i = blockIdx.x * TPB + threadIdx.x;
+    size_t r = blockIdx.y;
+    out[r * n + i] = in[r * n + perm_src(i, g, logn)];
+}
+void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st) {
+    hipLaunchKernelGGL(k_automorphism, dim3(ctx->n / TPB, rows), dim3(TPB), 0, st, out, in, ctx->n, ctx->logn, (unsigned)g);
+}
+
+// ---- fast base conversion ----------------------------------------------------------------------
+// in rows in_rows[m] (coefficient domain, residues under src moduli) -> out rows out_rows[r]:
+//   y_m = a_m * inv_hat_m mod q_m;  out_r = sum_m y_m * hat_{m,r} mod q_r   (no correction term)
+#define CONV_MAX_SRC 8
+__global__ void k_base_conv(u64 *out, const int *out_rows, const u64 *in, const int *in_rows,
+                            const int *src_mod, const int *dst_mod, const u64 *inv_hat, const u64 *inv_hat_sh,
+                            const u64 *hat_mont, const ModC *modc, int ns, int nt, int n,
+                            size_t in_batch_stride, size_t out_batch_stride) {
+    int i = blockIdx.x * TPB + threadIdx.x;
+    in += blockIdx.y * in_batch_stride;
+    out += blockIdx.y * out_batch_stride;
+    u64 y[CONV_MAX_SRC];
+#pragma unroll
+    for (int m = 0; m < CONV_MAX_SRC; m++) {
+        y[m] = 0;
+        if (m < ns) {
+            u64 q = modc[src_mod[m]].q;
+            y[m] = mul_shoup(in[(size_t)in_rows[m] * n + i], inv_hat[m], inv_hat_sh[m], q);
+        }
+    }
+    for (int r = 0; r < nt; r++) {
+        const ModC md = modc[dst_mod[r]];
+        u128 acc = 0;
+#pragma unroll
+        for (int m = 0; m < CONV_MAX_SRC; m++)
+            if (m < ns) acc += (u128)y[m] * hat_mont[m * nt + r];
+        out[(size_t)out_rows[r] * n + i] = redc(acc, md.q, md.qinv);
+    }
+}
+void launch_base_conv(cm_ctx *ctx, const ConvTable &t, u64 *out, const int *d_out_rows, const u64 *in,
+                      const int *d_in_rows, int batch, size_t in_stride, size_t out_stride, hipStream_t st) {
+    hipLaunchKernelGGL(k_base_conv, dim3(ctx->n / TPB, batch), dim3(TPB), 0, st, out, d_out_rows, in, d_in_rows,
+                       t.d_src, t.d_dst, t.d_inv_hat, t.d_inv_hat_sh, t.d_hat_mont, ctx->d_modc, t.ns, t.nt,
+                       ctx->n, in_stride, out_stride);
+}
+
+// ---- evaluation-key inner product ------------------------------------------------------------------
+// u0[r] = sum_j dig[j][r] * evk[j][0][mod(r)],  u1 likewise with evk[j][1]; r over the level's
+// extended basis.  With g != 0 the digits are read through the Galois permutation (hoisted
+// rotations).  Two adjacent coefficients per lane (16-byte accesses); the permutation keeps
+// aligned pairs together (it maps i^1 to src^1).
+__global__ void k_inner_product(u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, const ModC *modc,
+                                int beta, int ext, int level, int L, int nmod, int n, int logn, unsigned g) {
+    unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
+    int r = blockIdx.y;
+    int mi = r <= level ? r : L + 1 + (r - level - 1);
+    const ModC m = modc[mi];
+    unsigned src = g ? perm_src(i2, g, logn) : i2;
+    unsigned base = src & ~1u;
+    bool swap = src & 1u;
+    u128 a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+    for (int j = 0; j < beta; j++) {
+        ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(dig + ((size_t)j * ext + r) * n + base);
+        u64 dx = swap ? d.y : d.x, dy = swap ? d.x : d.y;
+        const u64 *kb = evk + (((size_t)j * 2 + 0) * nmod + mi) * n + i2;
+        ulonglong2 eb = *reinterpret_cast<const ulonglong2 *>(kb);
+        ulonglong2 ea = *reinterpret_cast<const ulonglong2 *>(kb + (size_t)nmod * n);
+        b0 += (u128)dx * eb.x;
+        b1 += (u128)dy * eb.y;
+        a0 += (u128)dx * ea.x;
+        a1 += (u128)dy * ea.y;
+    }
+    size_t o = (size_t)r * n + i2;
+    *reinterpret_cast<ulonglong2 *>(u0 + o) = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
+    *reinterpret_cast<ulonglong2 *>(u1 + o) = make_ulonglong2(redc(a0, m.q, m.qinv), redc(a1, m.q, m.qinv));
+}
+void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g, hipStream_t st) {
+    int ext = level + 1 + ctx->K;
+    hipLaunchKernelGGL(k_inner_product, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, u0, u1, dig, evk, ctx->d_modc,
+                       beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g);
+}
+
+// ---- ModDown tail: out = (u - conv) * P^{-1} (+ addend, optionally through the Galois map) ------------
+// batch (blockIdx.z) = component; u rows [ext][n], conv rows [level+1][n], out rows [level+1][n]
+__global__ void k_moddown_finish(u64 *out, const u64 *u, const u64 *conv, const u64 *pinv, const u64 *addend,
+                                 const ModC *modc, int n, int logn, unsigned g, size_t u_stride,
+                                 size_t conv_stride, size_t out_stride, int addend_comp_only) {
+    unsigned i = blockIdx.x * TPB + threadIdx.x;
+    int l = blockIdx.y, c = blockIdx.z;
+    u64 q = modc[l].q;
+    u64 d = submod(u[c * u_stride + (size_t)l * n + i], conv[c * conv_stride + (size_t)l * n + i], q);
+    u64 v = mul_shoup(d, pinv[2 * l], pinv[2 * l + 1], q);
+    if (addend && c <= addend_comp_only) {
+        unsigned s = g ? perm_src(i, g, logn) : i;
+        v = addmod(v, addend[c * out_stride + (size_t)l * n + s], q);
+    }
+    out[c * out_stride + (size_t)l * n + i] = v;
+}
+void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
+                           int addend_comps, int level, u64 g, hipStream_t st) {
+    int ext = level + 1 + ctx->K;
+    size_t n = ctx->n;
+    hipLaunchKernelGGL(k_moddown_finish, dim3(ctx->n / TPB, level + 1, 2), dim3(TPB), 0, st, out, u, conv, d_pinv,
+                       addend, ctx->d_modc, ctx->n, ctx->logn, (unsigned)g, (size_t)ext * n, (size_t)(level + 1) * n,
+                       (size_t)(level + 1) * n, addend_comps - 1);
+}
+
+// ---- rescale ---------------------------------------------------------------------------------
+// last[comp][n]: coefficient-domain last limb in [0, q_l) -> red[comp][l][n] = last mod q_i
+__global__ void k_rescale_reduce(u64 *red, const u64 *last, const ModC *modc, int level, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y, c = blockIdx.z;
+    const ModC m = modc[l];
+    u64 v = last[(size_t)c * n + i];
+    red[((size_t)c * level + l) * n + i] = redc((u128)to_mont(v, m), m.q, m.qinv);
+}
+// out[comp][l][n] = (in[comp][l] - red[comp][l]) * q_level^{-1}; in has level+1 rows per component
+__global__ void k_rescale_finish(u64 *out, const u64 *in, const u64 *red, const u64 *qlinv, const ModC *modc, int level, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y, c = blockIdx.z;
+    u64 q = modc[l].q;
+    u64 d = submod(in[((size_t)c * (level + 1) + l) * n + i], red[((size_t)c * level + l) * n + i], q);
+    out[((size_t)c * level + l) * n + i] = mul_shoup(d, qlinv[2 * l], qlinv[2 * l + 1], q);
+}
+void launch_rescale_reduce(cm_ctx *ctx, u64 *red, const u64 *last, int ncomp, int level, hipStream_t st) {
+    hipLaunchKernelGGL(k_rescale_reduce, dim3(ctx->n / TPB, level, ncomp), dim3(TPB), 0, st, red, last, ctx->d_modc, level, ctx->n);
+}
+void launch_rescale_finish(cm_ctx *ctx, u64 *out, const u64 *in, const u64 *red, const u64 *d_qlinv, int ncomp, int level, hipStream_t st) {
+    hipLaunchKernelGGL(k_rescale_finish, dim3(ctx->n / TPB, level, ncomp), dim3(TPB), 0, st, out, in, red, d_qlinv, ctx->d_modc, level, ctx->n);
+}
+
+// ---- counter-based sampling (must reproduce the generator's published definition bit for bit) --------
+#define GOLD 0x9E3779B97F4A7C15ULL
+__host__ __device__ __forceinline__ u64 mix64(u64 z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+u64 rng_key(u64 seed, u64 stream) { return mix64(mix64(seed) ^ stream); }
+u64 rng_draw(u64 key, u64 ctr) { return mix64(key + (ctr + 1) * GOLD); }
+
+// uniform residues: row l uses stream stream_base | mod_idx[l]
+__global__ void k_sample_uniform(u64 *out, const int *mod_idx, const ModC *modc, int n, u64 mseed, u64 stream_base) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
+    int mi = mod_idx[l];
+    u64 q = modc[mi].q;
+    u64 key = mix64(mseed ^ (stream_base | (u64)mi));
+    // bound = q * floor(2^64 / q): floor(2^64/q) = floor((2^64 - 1)/q) because q is odd > 1
+    u64 bound = q * (0xFFFFFFFFFFFFFFFFULL / q);
+    u64 att = 0, v;
+    do {
+        v = mix64(key + (((att << 32) | (u64)i) + 1) * GOLD);
+        att++;
+    } while (v >= bound);
+    out[(size_t)l * n + i] = v % q;
+}
+void launch_sample_uniform(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs, u64 seed, u64 stream_base, hipStream_t st) {
+    hipLaunchKernelGGL(k_sample_uniform, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, d_mod_idx, ctx->d_modc, ctx->n,
+                       mix64(seed), stream_base);
+}
+// one Gaussian integer per coefficient, written as residues to every row
+__global__ void k_sample_gauss(u64 *out, const int *mod_idx, const ModC *modc, const u64 *cdt, int limbs, int n, u64 key) {
+    int i = blockIdx.x * TPB + threadIdx.x;
+    u64 v = mix64(key + ((u64)i + 1) * GOLD), u = v >> 1;
+    u64 mag = 0;
+    for (int k = 0; k < CM_GAUSS_K; k++) mag += (u >= cdt[k]);
+    bool neg = (v & 1) && mag;
+    for (int l = 0; l < limbs; l++) {
+        u64 q = modc[mod_idx[l]].q;
+        out[(size_t)l * n + i] = neg ? q - mag : mag;
+    }
+}
+void launch_sample_gauss(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs, u64 seed, u64 stream, hipStream_t st) {
+    hipLaunchKernelGGL(k_sample_gauss, dim3(ctx->n / TPB), dim3(TPB), 0, st, out, d_mod_idx, ctx->d_modc, ctx->d_cdt, limbs,
+                       ctx->n, rng_key(seed, stream));
+}
+
+// ---- keys and encryption ---------------------------------------------------------------------------
+// b = e - a s + fac_l * s_from, then (b, a) stored in multiplier form.  s_mont: secret, evaluation
+// domain, multiplier form, rows = all moduli.  s_from = s through the Galois map g (g != 0) or s^2.
+__global__ void k_evk_assemble(u64 *b_out, u64 *a_io, const u64 *e, const u64 *s_mont, const u64 *fac,
+                               const ModC *modc, int n, int logn, unsigned g) {
+    unsigned i = blockIdx.x * TPB + threadIdx.x;
+    int l = blockIdx.y;
+    const ModC m = modc[l];
+    size_t o = (size_t)l * n + i;
+    u64 a = a_io[o];
+    u64 b = submod(e[o], redc((u128)a * s_mont[o], m.q, m.qinv), m.q);
+    u64 f = fac[l];
+    if (f) {
+        u64 sf = g ? s_mont[(size_t)l * n + perm_src(i, g, logn)]
+                   : redc((u128)s_mont[o] * s_mont[o], m.q, m.qinv);      // s^2 in multiplier form
+        b = addmod(b, redc((u128)f * sf, m.q, m.qinv), m.q);
+    }
+    b_out[o] = to_mont(b, m);
+    a_io[o] = to_mont(a, m);
+}
+void launch_evk_assemble(cm_ctx *ctx, u64 *b_out, u64 *a_io, const u64 *e, const u64 *s_mont, const u64 *d_fac, u64 g, hipStream_t st) {
+    hipLaunchKernelGGL(k_evk_assemble, dim3(ctx->n / TPB, ctx->nmod), dim3(TPB), 0, st, b_out, a_io, e, s_mont, d_fac,
+                       ctx->d_modc, ctx->n, ctx->logn, (unsigned)g);
+}
+// c0 = e - a s + m
+__global__ void k_encrypt(u64 *c0, const u64 *a, const u64 *e, const u64 *s_mont, const u64 *pt, const ModC *modc, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
+    const ModC m = modc[l];
+    size_t o = (size_t)l * n + i;
+    u64 v = submod(e[o], redc((u128)a[o] * s_mont[o], m.q, m.qinv), m.q);
+    c0[o] = addmod(v, pt[o], m.q);
+}
+void launch_encrypt(cm_ctx *ctx, u64 *c0, const u64 *a, const u64 *e, const u64 *s_mont, const u64 *pt, int limbs, hipStream_t st) {
+    hipLaunchKernelGGL(k_encrypt, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, c0, a, e, s_mont, pt, ctx->d_modc, ctx->n);
+}
+// out = c0 + c1 s (+ c2 s^2) on the first `limbs` limbs; ct rows per component = ct_limbs
+__global__ void k_decrypt(u64 *out, const u64 *ct, const u64 *s_mont, const ModC *modc, int ncomp, int ct_limbs, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
+    const ModC m = modc[l];
+    size_t o = (size_t)l * n + i, cs = (size_t)ct_limbs * n;
+    u64 s = s_mont[o];
+    u64 acc = addmod(ct[o], redc((u128)ct[o + cs] * s, m.q, m.qinv), m.q);
+    if (ncomp == 3) {
+        u64 s2 = redc((u128)s * s, m.q, m.qinv);
+        acc = addmod(acc, redc((u128)ct[o + 2 * cs] * s2, m.q, m.qinv), m.q);
+    }
+    out[o] = acc;
+}
+void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int ncomp, int ct_limbs, int limbs, hipStream_t st) {
+    hipLaunchKernelGGL(k_decrypt, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, ct, s_mont, ctx->d_modc, ncomp, ct_limbs, ctx->n);
+}
+
+// ---- packed product: inner_k = sum_j baby_j * p_{j,k} ---------------------------------------------------
+// babies: r_i ciphertexts [2][limbs][n] at stride baby_stride; pts: plaintext (j,k) at
+// (j*r_o + k)*pt_stride, multiplier form; out: r_o ciphertexts at stride baby_stride.
+// A lane keeps its coefficient of all baby ciphertexts of a chunk in registers and streams the
+// plaintexts once; products are summed in 128 bits and reduced once per chunk.
+#define MAC_CHUNK 8
+__global__ void k_vmm_mac(u64 *out, const u64 *babies, const u64 *pts, const ModC *modc, int r_i, int r_o, int limbs,
+                          int n, size_t ct_stride, size_t pt_stride) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
+    const ModC m = modc[l];
+    size_t o = (size_t)l * n + i, cs = (size_t)limbs * n;
+    for (int j0 = 0; j0 < r_i; j0 += MAC_CHUNK) {
+        u64 c0[MAC_CHUNK], c1[MAC_CHUNK];
+#pragma unroll
+        for (int jj = 0; jj < MAC_CHUNK; jj++) {
+            bool ok = j0 + jj < r_i;
+            c0[jj] = ok ? babies[(size_t)(j0 + jj) * ct_stride + o] : 0;
+            c1[jj] = ok ? babies[(size_t)(j0 + jj) * ct_stride + cs + o] : 0;
+        }
+        for (int k = 0; k < r_o; k++) {
+            u128 s0 = 0, s1 = 0;
+#pragma unroll
+            for (int jj = 0; jj < MAC_CHUNK; jj++) {
+                if (j0 + jj < r_i) {
+                    u64 p = pts[((size_t)(j0 + jj) * r_o + k) * pt_stride + o];
+                    s0 += (u128)c0[jj] * p;
+                    s1 += (u128)c1[jj] * p;
+                }
+            }
+            u64 v0 = redc(s0, m.q, m.qinv), v1 = redc(s1, m.q, m.qinv);
+            u64 *dst = out + (size_t)k * ct_stride + o;
+            if (j0) {
+                v0 = addmod(v0, dst[0], m.q);
+                v1 = addmod(v1, dst[cs], m.q);
+            }
+            dst[0] = v0;
+            dst[cs] = v1;
+        }
+    }
+}
+void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, hipStream_t st) {
+    hipLaunchKernelGGL(k_vmm_mac, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs,
+                       ctx->n, ct_stride, pt_stride);
+}

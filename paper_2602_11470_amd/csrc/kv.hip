@@ -1,0 +1,286 @@
+// Encrypted KV cache (Sec. 5): layouts, append, query-times-K and scores-times-V.
+//
+// Slot (e, h, tau) := (e*H + h)*t + tau with t = S/(H*E): head-interleaved blocks of t slots
+// (Sec. 5.3).  The vector of the current token has element [h, e] at (e, h, tau).
+//   K ciphertext c   : token c*t + tau at residue tau                                   (Sec. 5.1)
+//   score ciphertext : token c*t + tau of head h at (c, h, tau); room for E*t = S/H tokens
+//   V ciphertext k   : V[((e + k) mod E)*t + r, h, e] at (e, h, r), stored rotated right by the
+//                      giant step of its baby-step/giant-step group                     (Sec. 5.2)
+// Every mask is a slot rotation of one of three base masks, so it is obtained from the encoded
+// base by the Galois permutation (exact on the integer coefficients).  A mask is encoded at the
+// scale of the prime the following rescale removes, so masking leaves the scale unchanged.
+#include <math.h>
+
+#include "kernels.h"
+
+struct cm_kv {
+    cm_ctx *ctx = nullptr;
+    int S, H, E, t, r_i, r_o, level, max_tokens, ntok, nk_max;
+    double scale;
+    bool scale_set = false;
+    u64 *d_k = nullptr, *d_v = nullptr;     // nk_max / E ciphertexts [2][level+1][n]
+    u64 *d_mask_qk = nullptr;               // base: slots (0, h, tau) all h, tau; level-1; multiplier form
+    u64 *d_mask_k = nullptr;                // base: slots with residue 0;         level+1
+    u64 *d_mask_v = nullptr;                // base: slots (0, h, 0) all h;        level+1
+    u64 *d_work = nullptr;
+    size_t work_words = 0;
+};
+
+static int ilog2(int x) {
+    int l = 0;
+    while ((1 << l) < x) l++;
+    return l;
+}
+static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+static cm_status encode_mask(cm_kv *kv, int kind, u64 *dst, int level, const int64_t *coeffs_or_null) {
+    cm_ctx *ctx = kv->ctx;
+    cm_pt pt;
+    pt.dev = dst, pt.mont = 1;
+    const double scale = (double)ctx->mod[level];
+    if (coeffs_or_null) return cm_pt_from_coeffs(ctx, coeffs_or_null, level, scale, &pt);
+    std::vector<double> m(kv->S, 0.0);
+    if (kind == 0)
+        for (int i = 0; i < kv->H * kv->t; i++) m[i] = 1.0;
+    else if (kind == 1)
+        for (int i = 0; i < kv->S; i += kv->t) m[i] = 1.0;
+    else
+        for (int h = 0; h < kv->H; h++) m[h * kv->t] = 1.0;
+    return cm_encode(ctx, m.data(), nullptr, m.size(), level, scale, &pt);
+}
+
+extern "C" cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level, double scale,
+                                  int32_t max_tokens, cm_kv **out) {
+    if (!ctx || !out || heads < 1 || dim < 1 || max_tokens < 1) return CM_E_INVAL;
+    if (level < 2 || level > ctx->L) return CM_E_LEVEL;
+    const int S = ctx->n / 2;
+    if (!pow2(heads) || !pow2(dim) || heads * dim > S) return CM_E_LAYOUT;
+    cm_kv *kv = new (std::nothrow) cm_kv();
+    if (!kv) return CM_E_NOMEM;
+    kv->ctx = ctx, kv->S = S, kv->H = heads, kv->E = dim, kv->t = S / (heads * dim);
+    if (r_i == 0) r_i = dim;
+    if (!pow2(r_i) || dim % r_i || max_tokens > dim * kv->t) { delete kv; return CM_E_LAYOUT; }
+    kv->r_i = r_i, kv->r_o = dim / r_i, kv->level = level, kv->max_tokens = max_tokens, kv->ntok = 0;
+    kv->scale = scale > 0 ? scale : ctx->prm.scale;
+    kv->nk_max = (max_tokens + kv->t - 1) / kv->t;
+    const size_t n = ctx->n, ctw = 2 * (size_t)(level + 1) * n;
+    // work: r_i babies + r_o inner + tensor (1.5 ct) + 5 temporaries, all sized for level+1 inputs of append
+    const size_t ctw_up = 2 * (size_t)(level + 2) * n;
+    kv->work_words = (size_t)(kv->r_i + kv->r_o + 8) * ctw_up;
+    bool ok = hipMalloc((void **)&kv->d_k, (size_t)kv->nk_max * ctw * 8) == hipSuccess &&
+              hipMalloc((void **)&kv->d_v, (size_t)kv->E * ctw * 8) == hipSuccess &&
+              hipMalloc((void **)&kv->d_mask_qk, (size_t)level * n * 8) == hipSuccess &&
+              hipMalloc((void **)&kv->d_mask_k, (size_t)(level + 2) * n * 8) == hipSuccess &&
+              hipMalloc((void **)&kv->d_mask_v, (size_t)(level + 2) * n * 8) == hipSuccess &&
+              hipMalloc((void **)&kv->d_work, kv->work_words * 8) == hipSuccess;
+    if (!ok) { cm_kv_destroy(kv); return CM_E_NOMEM; }
+    hipMemset(kv->d_k, 0, (size_t)kv->nk_max * ctw * 8);      // an all-zero ciphertext encrypts 0
+    hipMemset(kv->d_v, 0, (size_t)kv->E * ctw * 8);
+    cm_status s = encode_mask(kv, 0, kv->d_mask_qk, level - 1, nullptr);
+    if (s == CM_OK && level + 1 <= ctx->L) {
+        s = encode_mask(kv, 1, kv->d_mask_k, level + 1, nullptr);
+        if (s == CM_OK) s = encode_mask(kv, 2, kv->d_mask_v, level + 1, nullptr);
+    }
+    if (s != CM_OK) { cm_kv_destroy(kv); return s; }
+    *out = kv;
+    return CM_OK;
+}
+extern "C" void cm_kv_destroy(cm_kv *kv) {
+    if (!kv) return;
+    hipFree(kv->d_k), hipFree(kv->d_v), hipFree(kv->d_mask_qk), hipFree(kv->d_mask_k), hipFree(kv->d_mask_v);
+    hipFree(kv->d_work);
+    delete kv;
+}
+// Parity hook: replace a base mask by given integer coefficients (kind 0: query-times-K mask at
+// level-1; 1: residue mask at level+1; 2: value mask at level+1), host coeffs[n].
+extern "C" cm_status cm_kv_set_mask(cm_kv *kv, int32_t kind, const int64_t *coeffs) {
+    if (!kv || !coeffs || kind < 0 || kind > 2) return CM_E_INVAL;
+    if (kind > 0 && kv->level + 1 > kv->ctx->L) return CM_E_LEVEL;
+    u64 *dst = kind == 0 ? kv->d_mask_qk : kind == 1 ? kv->d_mask_k : kv->d_mask_v;
+    return encode_mask(kv, kind, dst, kind == 0 ? kv->level - 1 : kv->level + 1, coeffs);
+}
+
+static std::vector<int> kv_all_steps(const cm_kv *kv) {
+    std::vector<int> s;
+    for (int i = 0; i < ilog2(kv->t); i++) s.push_back(-(1 << i));                         // replicate q
+    for (int i = 0; i < ilog2(kv->E); i++) s.push_back((1 << i) * kv->H * kv->t);          // sum over dims
+    for (int j = 1; j < kv->r_i; j++) s.push_back(j * kv->H * kv->t);                      // score baby steps
+    if (kv->r_o > 1) s.push_back(kv->r_i * kv->H * kv->t);                                 // score giant step
+    for (int l = 0; l < ilog2(kv->t); l++) s.push_back(1 << l);                            // reduce residues
+    for (int g = 1; g < kv->r_o; g++) s.push_back(-(g * kv->r_i * kv->H * kv->t));         // append shifts
+    return s;
+}
+extern "C" int32_t cm_kv_steps(const cm_kv *kv, int32_t *steps, int32_t cap) {
+    if (!kv) return 0;
+    auto s = kv_all_steps(kv);
+    for (int i = 0; i < (int)s.size() && i < cap && steps; i++) steps[i] = s[i];
+    return (int32_t)s.size();
+}
+extern "C" int32_t cm_kv_tokens(const cm_kv *kv) { return kv ? kv->ntok : -1; }
+extern "C" cm_status cm_kv_set_tokens(cm_kv *kv, int32_t ntok) {
+    if (!kv || ntok < 0 || ntok > kv->max_tokens) return CM_E_INVAL;
+    kv->ntok = ntok;
+    return CM_OK;
+}
+
+static size_t kv_ctw(const cm_kv *kv) { return 2 * (size_t)(kv->level + 1) * kv->ctx->n; }
+
+extern "C" cm_status cm_kv_load(cm_ctx *ctx, cm_kv *kv, int32_t which, int32_t idx, const cm_ct *ct, void *stream) {
+    if (!ctx || !kv || kv->ctx != ctx || !ct || !ct->dev || ct->ncomp != 2) return CM_E_INVAL;
+    if (ct->level != kv->level) return CM_E_LEVEL;
+    if (kv->scale_set && fabs(ct->scale / kv->scale - 1) > 1e-9) return CM_E_SCALE;
+    if (idx < 0 || idx >= (which == CM_QK ? kv->nk_max : kv->E)) return CM_E_LAYOUT;
+    u64 *dst = (which == CM_QK ? kv->d_k : kv->d_v) + (size_t)idx * kv_ctw(kv);
+    HIPCHK(hipMemcpyAsync(dst, ct->dev, kv_ctw(kv) * 8, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    kv->scale = ct->scale, kv->scale_set = true;
+    return CM_OK;
+}
+extern "C" cm_status cm_kv_export(cm_ctx *ctx, const cm_kv *kv, int32_t which, int32_t idx, uint64_t *out) {
+    if (!ctx || !kv || !out) return CM_E_INVAL;
+    if (idx < 0 || idx >= (which == CM_QK ? kv->nk_max : kv->E)) return CM_E_LAYOUT;
+    cm_ct ct;
+    ct.dev = (which == CM_QK ? kv->d_k : kv->d_v) + (size_t)idx * kv_ctw(kv);
+    ct.level = kv->level, ct.ncomp = 2, ct.scale = kv->scale;
+    return cm_ct_export(ctx, &ct, out);
+}
+
+static u64 rot_g(const cm_kv *kv, long long step) {
+    long long S = kv->S;
+    return galois_of_step(kv->ctx, (int)(((step % S) + S) % S));
+}
+
+extern "C" cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_new, const cm_ct *v_new,
+                                  void *stream) {
+    if (!ctx || !evk || !kv || kv->ctx != ctx || !k_new || !v_new || !k_new->dev || !v_new->dev) return CM_E_INVAL;
+    if (k_new->ncomp != 2 || v_new->ncomp != 2) return CM_E_INVAL;
+    const int lv = kv->level + 1;
+    if (lv > ctx->L || k_new->level != lv || v_new->level != lv) return CM_E_LEVEL;
+    if (kv->ntok >= kv->max_tokens) return CM_E_LAYOUT;
+    if (kv->scale_set && (fabs(k_new->scale / kv->scale - 1) > 1e-9 || fabs(v_new->scale / kv->scale - 1) > 1e-9))
+        return CM_E_SCALE;
+    if (fabs(k_new->scale / v_new->scale - 1) > 1e-9) return CM_E_SCALE;
+    for (int g = 1; g < kv->r_o; g++)
+        if (!find_key(evk, rot_g(kv, -(long long)g * kv->r_i * kv->H * kv->t))) return CM_E_NOKEY;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t n = ctx->n, ctw_up = 2 * (size_t)(lv + 1) * n, ctw = kv_ctw(kv);
+    const int tok = kv->ntok, c = tok / kv->t, tau = tok % kv->t;
+    u64 *mask = kv->d_work, *prod = mask + (size_t)(lv + 1) * n, *res = prod + ctw_up, *shifted = res + ctw_up;
+    // K: K_c += rescale(k_new * mask_tau), mask_tau = residue-0 mask rotated right by tau
+    launch_automorphism(ctx, mask, kv->d_mask_k, lv + 1, rot_g(kv, -tau), st);
+    launch_mul_pt(ctx, prod, k_new->dev, mask, 2, lv + 1, st);
+    CMCHK(rescale_into(ctx, prod, 2, lv, res, st));
+    u64 *kc = kv->d_k + (size_t)c * ctw;
+    launch_add(ctx, kc, kc, res, 2, kv->level + 1, st);
+    // V: the new vector shifted right by each giant step, then one masked product per V ciphertext
+    for (int g = 1; g < kv->r_o; g++) {
+        long long step = -(long long)g * kv->r_i * kv->H * kv->t;
+        CMCHK(rotate_into(ctx, find_key(evk, rot_g(kv, step)), v_new->dev, lv, rot_g(kv, step),
+                          shifted + (size_t)(g - 1) * ctw_up, st));
+    }
+    for (int k = 0; k < kv->E; k++) {
+        int g = k / kv->r_i;
+        long long a = (long long)(((c - k) % kv->E + kv->E) % kv->E) * kv->H * kv->t + tau +
+                      (long long)g * kv->r_i * kv->H * kv->t;
+        launch_automorphism(ctx, mask, kv->d_mask_v, lv + 1, rot_g(kv, -a), st);
+        const u64 *src = g == 0 ? v_new->dev : shifted + (size_t)(g - 1) * ctw_up;
+        launch_mul_pt(ctx, prod, src, mask, 2, lv + 1, st);
+        CMCHK(rescale_into(ctx, prod, 2, lv, res, st));
+        u64 *vk = kv->d_v + (size_t)k * ctw;
+        launch_add(ctx, vk, vk, res, 2, kv->level + 1, st);
+    }
+    kv->ntok++;
+    kv->scale = k_new->scale * (double)ctx->mod[lv] / (double)ctx->mod[lv];
+    kv->scale_set = true;
+    return CM_OK;
+}
+
+static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st) {
+    const int lv = kv->level, limbs = lv + 1;
+    if (lv < 2) return CM_E_LEVEL;
+    const size_t n = ctx->n, ctw = kv_ctw(kv), ln = (size_t)limbs * n;
+    const u64 *relin = find_key(evk, 0);
+    if (!relin) return CM_E_NOKEY;
+    for (int i = 0; i < ilog2(kv->t); i++) if (!find_key(evk, rot_g(kv, -(1 << i)))) return CM_E_NOKEY;
+    for (int i = 0; i < ilog2(kv->E); i++) if (!find_key(evk, rot_g(kv, (long long)(1 << i) * kv->H * kv->t))) return CM_E_NOKEY;
+    const int nk = (kv->ntok + kv->t - 1) / kv->t;
+    if (nk < 1) return CM_E_LAYOUT;
+    u64 *cq = kv->d_work, *tmp = cq + ctw, *T = tmp + ctw, *P = T + 3 * ln, *R = P + ctw, *acc = R + ctw, *mask = acc + ctw;
+    HIPCHK(hipMemcpyAsync(cq, in->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
+    for (int i = 0; i < ilog2(kv->t); i++) {                     // replicate q over the t residues
+        u64 g = rot_g(kv, -(1 << i));
+        CMCHK(rotate_into(ctx, find_key(evk, g), cq, lv, g, tmp, st));
+        launch_add(ctx, cq, cq, tmp, 2, limbs, st);
+    }
+    u64 *digits = arena_digits(ctx);
+    for (int c = 0; c < nk; c++) {
+        launch_tensor(ctx, T, cq, kv->d_k + (size_t)c * ctw, limbs, 0, st);
+        CMCHK(ks_raise(ctx, T + 2 * ln, lv, digits, st));
+        CMCHK(ks_apply(ctx, digits, relin, lv, 0, T, 2, P, st));
+        CMCHK(rescale_into(ctx, P, 2, lv, R, st));
+        for (int i = 0; i < ilog2(kv->E); i++) {                 // sum over the E dims of every head
+            u64 g = rot_g(kv, (long long)(1 << i) * kv->H * kv->t);
+            CMCHK(rotate_into(ctx, find_key(evk, g), R, lv - 1, g, tmp, st));
+            launch_add(ctx, R, R, tmp, 2, lv, st);
+        }
+        // keep copy e = c: base mask rotated right by c*H*t
+        launch_automorphism(ctx, mask, kv->d_mask_qk, lv, rot_g(kv, -(long long)(c % kv->E) * kv->H * kv->t), st);
+        launch_mac_pt(ctx, acc, R, mask, 2, lv, c > 0, st);
+    }
+    CMCHK(rescale_into(ctx, acc, 2, lv - 1, out->dev, st));
+    out->level = lv - 2, out->ncomp = 2;
+    out->scale = in->scale * kv->scale / (double)ctx->mod[lv];      // the mask scale cancels the second rescale
+    return CM_OK;
+}
+
+static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st) {
+    const int lv = kv->level, limbs = lv + 1;
+    const size_t n = ctx->n, ctw = kv_ctw(kv), ln = (size_t)limbs * n;
+    const u64 *relin = find_key(evk, 0);
+    if (!relin) return CM_E_NOKEY;
+    const long long Ht = (long long)kv->H * kv->t;
+    for (int j = 1; j < kv->r_i; j++) if (!find_key(evk, rot_g(kv, j * Ht))) return CM_E_NOKEY;
+    if (kv->r_o > 1 && !find_key(evk, rot_g(kv, kv->r_i * Ht))) return CM_E_NOKEY;
+    for (int l = 0; l < ilog2(kv->t); l++) if (!find_key(evk, rot_g(kv, 1 << l))) return CM_E_NOKEY;
+    u64 *babies = kv->d_work, *inner = babies + (size_t)kv->r_i * ctw, *T = inner + (size_t)kv->r_o * ctw,
+        *tmp = T + 3 * ln, *R = tmp + ctw;
+    u64 *digits = arena_digits(ctx);
+    HIPCHK(hipMemcpyAsync(babies, in->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
+    if (kv->r_i > 1) {
+        CMCHK(ks_raise(ctx, babies + ln, lv, digits, st));
+        for (int j = 1; j < kv->r_i; j++)
+            CMCHK(ks_apply(ctx, digits, find_key(evk, rot_g(kv, j * Ht)), lv, rot_g(kv, j * Ht), babies, 1,
+                           babies + (size_t)j * ctw, st));
+    }
+    for (int g = 0; g < kv->r_o; g++) {
+        for (int j = 0; j < kv->r_i; j++)
+            launch_tensor(ctx, T, babies + (size_t)j * ctw, kv->d_v + (size_t)(g * kv->r_i + j) * ctw, limbs, j > 0, st);
+        CMCHK(ks_raise(ctx, T + 2 * ln, lv, digits, st));
+        CMCHK(ks_apply(ctx, digits, relin, lv, 0, T, 2, inner + (size_t)g * ctw, st));
+    }
+    u64 *acc = inner + (size_t)(kv->r_o - 1) * ctw;
+    for (int g = kv->r_o - 2; g >= 0; g--) {
+        u64 gg = rot_g(kv, kv->r_i * Ht);
+        CMCHK(rotate_into(ctx, find_key(evk, gg), acc, lv, gg, tmp, st));
+        acc = inner + (size_t)g * ctw;
+        launch_add(ctx, acc, acc, tmp, 2, limbs, st);
+    }
+    CMCHK(rescale_into(ctx, acc, 2, lv, R, st));
+    for (int l = 0; l < ilog2(kv->t); l++) {
+        u64 g = rot_g(kv, 1 << l);
+        CMCHK(rotate_into(ctx, find_key(evk, g), R, lv - 1, g, tmp, st));
+        launch_add(ctx, R, R, tmp, 2, lv, st);
+    }
+    HIPCHK(hipMemcpyAsync(out->dev, R, 2 * (size_t)lv * n * 8, hipMemcpyDeviceToDevice, st));
+    out->level = lv - 1, out->ncomp = 2;
+    out->scale = in->scale * kv->scale / (double)ctx->mod[lv];
+    return CM_OK;
+}
+
+extern "C" cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t which, const cm_ct *in,
+                               cm_ct *out, void *stream) {
+    if (!ctx || !evk || !kv || kv->ctx != ctx || !in || !in->dev || !out || !out->dev || in->ncomp != 2) return CM_E_INVAL;
+    if (in->level != kv->level) return CM_E_LEVEL;
+    if (which == CM_QK) return kv_qk(ctx, evk, kv, in, out, (hipStream_t)stream);
+    if (which == CM_SV) return kv_sv(ctx, evk, kv, in, out, (hipStream_t)stream);
+    return CM_E_INVAL;
+}

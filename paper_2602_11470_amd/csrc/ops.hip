@@ -1,0 +1,543 @@
+// C ABI: keys, encryption, the ciphertext operations of Sec. 2.1 and hybrid key switching.
+#include <math.h>
+#include <string.h>
+
+#include "kernels.h"
+
+// stream identifiers of the counter-based generator
+enum { ST_SECRET = 1, ST_EVK_A = 2, ST_EVK_E = 3, ST_ENC_A = 4, ST_ENC_E = 5 };
+static inline u64 stream_id(u64 purpose, u64 ident, u64 digit, u64 limb) {
+    return (purpose << 56) | (ident << 16) | (digit << 8) | limb;
+}
+
+// ---- arena ------------------------------------------------------------------------------------
+struct Arena {
+    u64 *ksin, *digits, *u, *conv, *tmp[3], *misc;
+};
+static Arena arena_of(const cm_ctx *ctx) {
+    const size_t n = ctx->n, q = ctx->L + 1, ext = ctx->L + 1 + ctx->K;
+    const size_t beta = (ctx->L + ctx->alpha) / ctx->alpha;
+    Arena a;
+    u64 *p = ctx->arena;
+    a.ksin = p, p += q * n;
+    a.digits = p, p += beta * ext * n;
+    a.u = p, p += 2 * ext * n;
+    a.conv = p, p += 2 * q * n;
+    for (int i = 0; i < 3; i++) a.tmp[i] = p, p += 3 * q * n;
+    a.misc = p;
+    return a;
+}
+
+template <class T>
+static T *up(const std::vector<T> &v) {
+    T *d = nullptr;
+    if (v.empty()) return nullptr;
+    if (hipMalloc((void **)&d, v.size() * sizeof(T)) != hipSuccess) return nullptr;
+    hipMemcpy(d, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
+    return d;
+}
+
+struct KsLevelFull : KsLevel {
+    int *d_q_mods3 = nullptr;   // 0..level repeated three times
+    int *d_last_mods = nullptr; // level, level, level
+    int *d_red_mods = nullptr;  // 0..level-1 repeated three times
+};
+static std::map<std::pair<cm_ctx *, int>, KsLevelFull> g_ks;
+
+static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
+    auto key = std::make_pair(ctx, level);
+    auto it = g_ks.find(key);
+    if (it != g_ks.end()) return it->second;
+    KsLevelFull k;
+    k.level = level;
+    k.ext = level + 1 + ctx->K;
+    auto digs = digits_at(ctx, level);
+    k.beta = (int)digs.size();
+    const auto &tabs = get_modup(ctx, level);
+    std::vector<int> ntt_rows, ntt_mods;
+    for (int j = 0; j < k.beta; j++) {
+        std::vector<int> out_rows;
+        for (int idx : tabs[j].dst) {
+            int row = idx <= level ? idx : level + 1 + (idx - ctx->L - 1);
+            out_rows.push_back(row);
+            ntt_rows.push_back(j * k.ext + row);
+            ntt_mods.push_back(idx);
+        }
+        k.d_out_rows.push_back(up(out_rows));
+        k.d_in_rows.push_back(up(digs[j]));
+    }
+    k.d_ntt_rows = up(ntt_rows);
+    k.d_ntt_mods = up(ntt_mods);
+    k.n_ntt = (int)ntt_rows.size();
+    std::vector<int> sp_rows, sp_mods, q_rows, q3, last(3, level), red;
+    for (int c = 0; c < 2; c++)
+        for (int s = 0; s < ctx->K; s++) {
+            sp_rows.push_back(c * k.ext + level + 1 + s);
+            sp_mods.push_back(ctx->L + 1 + s);
+        }
+    for (int i = 0; i <= level; i++) q_rows.push_back(i);
+    for (int c = 0; c < 3; c++) {
+        for (int i = 0; i <= level; i++) q3.push_back(i);
+        for (int i = 0; i < level; i++) red.push_back(i);
+    }
+    if (red.empty()) red.push_back(0);
+    k.d_sp_rows = up(sp_rows);
+    k.d_sp_mods = up(sp_mods);
+    k.d_q_rows = up(q_rows);
+    k.d_q_mods3 = up(q3);
+    k.d_last_mods = up(last);
+    k.d_red_mods = up(red);
+    get_moddown(ctx, level);
+    get_pinv(ctx, level);
+    get_qlinv(ctx, level);
+    return g_ks[key] = k;
+}
+const KsLevel &ks_level(cm_ctx *ctx, int level) { return ks_level_full(ctx, level); }
+
+static void drop_ks_levels(cm_ctx *ctx) {
+    for (auto it = g_ks.begin(); it != g_ks.end();) {
+        if (it->first.first != ctx) { ++it; continue; }
+        KsLevelFull &k = it->second;
+        for (int *p : k.d_out_rows) hipFree(p);
+        for (int *p : k.d_in_rows) hipFree(p);
+        hipFree(k.d_ntt_rows); hipFree(k.d_ntt_mods); hipFree(k.d_sp_rows); hipFree(k.d_sp_mods);
+        hipFree(k.d_q_rows); hipFree(k.d_q_mods3); hipFree(k.d_last_mods); hipFree(k.d_red_mods);
+        it = g_ks.erase(it);
+    }
+}
+// called from cm_ctx_destroy's translation unit through this hook
+void cm_ops_forget_ctx(cm_ctx *ctx) { drop_ks_levels(ctx); }
+
+static bool ct_ok(const cm_ctx *ctx, const cm_ct *c) {
+    return c && c->dev && c->level >= 0 && c->level <= ctx->L && (c->ncomp == 2 || c->ncomp == 3);
+}
+static bool same_scale(double a, double b) { return fabs(a / b - 1.0) < 1e-9; }
+
+// ---- hybrid key switching -------------------------------------------------------------------------
+cm_status ks_raise(cm_ctx *ctx, const u64 *d, int level, u64 *digits, hipStream_t st) {
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    const auto &tabs = get_modup(ctx, level);
+    Arena A = arena_of(ctx);
+    const size_t n = ctx->n;
+    HIPCHK(hipMemcpyAsync(A.ksin, d, (size_t)(level + 1) * n * 8, hipMemcpyDeviceToDevice, st));
+    launch_ntt(ctx, A.ksin, iota_idx(ctx), level + 1, true, st);
+    auto digs = digits_at(ctx, level);
+    for (int j = 0; j < k.beta; j++) {
+        u64 *dj = digits + (size_t)j * k.ext * n;
+        launch_base_conv(ctx, tabs[j], dj, k.d_out_rows[j], A.ksin, k.d_in_rows[j], 1, 0, 0, st);
+        // the digit's own limbs are the input's, already in the evaluation domain
+        HIPCHK(hipMemcpyAsync(dj + (size_t)digs[j].front() * n, d + (size_t)digs[j].front() * n,
+                              digs[j].size() * n * 8, hipMemcpyDeviceToDevice, st));
+    }
+    launch_ntt_rows(ctx, digits, k.d_ntt_rows, k.d_ntt_mods, k.n_ntt, false, st);
+    return CM_OK;
+}
+
+cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u64 g, const u64 *addend,
+                   int addend_comps, u64 *out, hipStream_t st) {
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    Arena A = arena_of(ctx);
+    const size_t n = ctx->n;
+    u64 *u0 = A.u, *u1 = A.u + (size_t)k.ext * n;
+    launch_inner_product(ctx, u0, u1, digits, evk, k.beta, level, g, st);
+    launch_ntt_rows(ctx, A.u, k.d_sp_rows, k.d_sp_mods, 2 * ctx->K, true, st);
+    const ConvTable &md = get_moddown(ctx, level);
+    launch_base_conv(ctx, md, A.conv, k.d_q_rows, A.u, k.d_sp_rows, 2, (size_t)k.ext * n, (size_t)(level + 1) * n, st);
+    launch_ntt(ctx, A.conv, k.d_q_mods3, 2 * (level + 1), false, st);
+    launch_moddown_finish(ctx, out, A.u, A.conv, get_pinv(ctx, level), addend, addend_comps, level, addend ? g : 0, st);
+    return CM_OK;
+}
+u64 *arena_digits(const cm_ctx *ctx) { return arena_of(ctx).digits; }
+
+const u64 *find_key(const cm_evk *evk, u64 g) {
+    auto it = evk->keys.find(g);
+    return it == evk->keys.end() ? nullptr : it->second.d;
+}
+
+extern "C" cm_status cm_keyswitch(cm_ctx *ctx, const cm_evk *evk, int32_t step, int32_t relin, const uint64_t *d,
+                                  int32_t level, uint64_t *ks0, uint64_t *ks1, void *stream) {
+    if (!ctx || !evk || !d || !ks0 || !ks1 || level < 0 || level > ctx->L) return CM_E_INVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const u64 *key = find_key(evk, relin ? 0 : galois_of_step(ctx, step));
+    if (!key) return CM_E_NOKEY;
+    Arena A = arena_of(ctx);
+    CMCHK(ks_raise(ctx, (const u64 *)d, level, A.digits, st));
+    CMCHK(ks_apply(ctx, A.digits, key, level, 0, nullptr, 0, A.tmp[0], st));
+    size_t bytes = (size_t)(level + 1) * ctx->n * 8;
+    HIPCHK(hipMemcpyAsync(ks0, A.tmp[0], bytes, hipMemcpyDeviceToDevice, st));
+    HIPCHK(hipMemcpyAsync(ks1, A.tmp[0] + (size_t)(level + 1) * ctx->n, bytes, hipMemcpyDeviceToDevice, st));
+    return CM_OK;
+}
+
+extern "C" cm_status cm_ntt(cm_ctx *ctx, uint64_t *dev, const int32_t *mod_idx, int32_t limbs, int32_t inverse, void *stream) {
+    if (!ctx || !dev || !mod_idx || limbs < 1 || limbs > 2 * CM_MAX_LIMBS) return CM_E_INVAL;
+    for (int i = 0; i < limbs; i++)
+        if (mod_idx[i] < 0 || mod_idx[i] >= ctx->nmod) return CM_E_INVAL;
+    // consecutive runs of modulus indices map onto the resident 0,1,2,.. table; anything else is staged
+    bool iota = true;
+    for (int i = 0; i < limbs; i++) iota &= (mod_idx[i] == mod_idx[0] + i);
+    hipStream_t st = (hipStream_t)stream;
+    if (iota) {
+        launch_ntt(ctx, (u64 *)dev, iota_idx(ctx) + mod_idx[0], limbs, inverse != 0, st);
+        return CM_OK;
+    }
+    int *d_idx = nullptr;
+    HIPCHK(hipMalloc((void **)&d_idx, limbs * sizeof(int)));
+    HIPCHK(hipMemcpy(d_idx, mod_idx, limbs * sizeof(int), hipMemcpyHostToDevice));
+    launch_ntt(ctx, (u64 *)dev, d_idx, limbs, inverse != 0, st);
+    HIPCHK(hipStreamSynchronize(st));
+    hipFree(d_idx);
+    return CM_OK;
+}
+
+// ---- keys -------------------------------------------------------------------------------------------
+extern "C" cm_status cm_keygen_secret(cm_ctx *ctx, uint64_t seed, cm_sk **out) {
+    if (!ctx || !out) return CM_E_INVAL;
+    const int n = ctx->n, h = ctx->prm.hamming;
+    cm_sk *sk = new (std::nothrow) cm_sk();
+    if (!sk) return CM_E_NOMEM;
+    sk->coeffs.assign(n, 0);
+    const u64 key = rng_key(seed, stream_id(ST_SECRET, 0, 0, 0));
+    if (h == 0) {
+        // i.i.d. uniform on {0, 1, -1}: a draw below 3*floor(2^64/3) taken mod 3
+        const u64 bound = 3 * (0xFFFFFFFFFFFFFFFFULL / 3);
+        static const int8_t val[3] = {0, 1, -1};
+        for (int i = 0; i < n; i++) {
+            u64 att = 0, v;
+            do { v = rng_draw(key, (att << 32) | (u64)i); att++; } while (v >= bound);
+            sk->coeffs[i] = val[v % 3];
+        }
+    } else {
+        // h positions by a partial Fisher-Yates shuffle, one further draw bit for each sign
+        std::vector<int> perm(n);
+        for (int i = 0; i < n; i++) perm[i] = i;
+        for (int i = 0; i < h; i++) {
+            int j = i + (int)(rng_draw(key, (u64)i) % (u64)(n - i));
+            std::swap(perm[i], perm[j]);
+            sk->coeffs[perm[i]] = (rng_draw(key, (u64)(n + i)) & 1) ? -1 : 1;
+        }
+    }
+    std::vector<u64> res((size_t)ctx->nmod * n);
+    for (int m = 0; m < ctx->nmod; m++)
+        for (int i = 0; i < n; i++) {
+            int8_t c = sk->coeffs[i];
+            res[(size_t)m * n + i] = c == 0 ? 0 : (c > 0 ? 1 : ctx->mod[m] - 1);
+        }
+    if (hipMalloc((void **)&sk->d_ntt, res.size() * 8) != hipSuccess) { delete sk; return CM_E_NOMEM; }
+    HIPCHK(hipMemcpy(sk->d_ntt, res.data(), res.size() * 8, hipMemcpyHostToDevice));
+    launch_ntt(ctx, sk->d_ntt, iota_idx(ctx), ctx->nmod, false, 0);
+    launch_to_mont(ctx, sk->d_ntt, iota_idx(ctx), ctx->nmod, 0);
+    HIPCHK(hipDeviceSynchronize());
+    *out = sk;
+    return CM_OK;
+}
+extern "C" void cm_sk_destroy(cm_sk *sk) {
+    if (!sk) return;
+    hipFree(sk->d_ntt);
+    delete sk;
+}
+extern "C" cm_status cm_sk_coeffs(const cm_ctx *ctx, const cm_sk *sk, int8_t *out) {
+    if (!ctx || !sk || !out) return CM_E_INVAL;
+    memcpy(out, sk->coeffs.data(), ctx->n);
+    return CM_OK;
+}
+
+static cm_status make_key(cm_ctx *ctx, const cm_sk *sk, u64 g, u64 seed, EvkEntry *entry, int digits) {
+    const size_t n = ctx->n, nm = ctx->nmod;
+    Arena A = arena_of(ctx);
+    HIPCHK(hipMalloc((void **)&entry->d, (size_t)digits * 2 * nm * n * 8));
+    auto digs = digits_at(ctx, ctx->L);
+    u64 *d_fac = nullptr;
+    HIPCHK(hipMalloc((void **)&d_fac, nm * 8));
+    for (int j = 0; j < digits; j++) {
+        u64 *b = entry->d + ((size_t)j * 2 + 0) * nm * n, *a = b + nm * n, *e = A.tmp[0];
+        launch_sample_uniform(ctx, a, iota_idx(ctx), (int)nm, seed, stream_id(ST_EVK_A, g, j, 0), 0);
+        launch_sample_gauss(ctx, e, iota_idx(ctx), (int)nm, seed, stream_id(ST_EVK_E, g, j, 0), 0);
+        launch_ntt(ctx, a, iota_idx(ctx), (int)nm, false, 0);
+        launch_ntt(ctx, e, iota_idx(ctx), (int)nm, false, 0);
+        // P * (Q/Q_j) * ((Q/Q_j)^{-1} mod Q_j) is P on the digit's own limbs and 0 on all others
+        std::vector<u64> fac(nm, 0);
+        for (int i : digs[j]) {
+            u64 q = ctx->mod[i], P = 1;
+            for (int k = 0; k < ctx->K; k++) P = h_mulmod(P, ctx->mod[ctx->L + 1 + k] % q, q);
+            fac[i] = P;
+        }
+        HIPCHK(hipMemcpy(d_fac, fac.data(), nm * 8, hipMemcpyHostToDevice));
+        launch_evk_assemble(ctx, b, a, e, sk->d_ntt, d_fac, g, 0);
+        HIPCHK(hipDeviceSynchronize());
+    }
+    hipFree(d_fac);
+    return CM_OK;
+}
+
+extern "C" cm_status cm_keygen_rotations(cm_ctx *ctx, const cm_sk *sk, const int32_t *steps, size_t nsteps,
+                                         int32_t with_relin, uint64_t seed, cm_evk **out) {
+    if (!ctx || !sk || !out || (nsteps && !steps)) return CM_E_INVAL;
+    if (3 * (ctx->L + 1) < ctx->nmod) return CM_E_INVAL;
+    cm_evk *evk = new (std::nothrow) cm_evk();
+    if (!evk) return CM_E_NOMEM;
+    evk->digits = (ctx->L + ctx->alpha) / ctx->alpha;
+    std::vector<u64> ids;
+    for (size_t i = 0; i < nsteps; i++) ids.push_back(galois_of_step(ctx, steps[i]));
+    if (with_relin) ids.push_back(0);
+    for (u64 g : ids) {
+        if (g == 1 || evk->keys.count(g)) continue;      // step 0 needs no key
+        EvkEntry e;
+        cm_status s = make_key(ctx, sk, g, seed, &e, evk->digits);
+        if (s != CM_OK) {
+            hipFree(e.d);
+            cm_evk_destroy(evk);
+            return s == CM_E_HIP ? CM_E_NOMEM : s;
+        }
+        evk->keys[g] = e;
+    }
+    *out = evk;
+    return CM_OK;
+}
+extern "C" void cm_evk_destroy(cm_evk *evk) {
+    if (!evk) return;
+    for (auto &kv : evk->keys) hipFree(kv.second.d);
+    delete evk;
+}
+extern "C" cm_status cm_evk_export(cm_ctx *ctx, const cm_evk *evk, int32_t step, int32_t relin, int32_t digit,
+                                   int32_t comp, uint64_t *out) {
+    if (!ctx || !evk || !out || digit < 0 || digit >= evk->digits || comp < 0 || comp > 1) return CM_E_INVAL;
+    const u64 *key = find_key(evk, relin ? 0 : galois_of_step(ctx, step));
+    if (!key) return CM_E_NOKEY;
+    const size_t n = ctx->n, nm = ctx->nmod;
+    Arena A = arena_of(ctx);
+    launch_from_mont(ctx, A.tmp[0], key + ((size_t)digit * 2 + comp) * nm * n, iota_idx(ctx), (int)nm, 0);
+    launch_ntt(ctx, A.tmp[0], iota_idx(ctx), (int)nm, true, 0);
+    HIPCHK(hipMemcpy(out, A.tmp[0], nm * n * 8, hipMemcpyDeviceToHost));
+    return CM_OK;
+}
+
+// ---- plaintexts, encryption, decryption ----------------------------------------------------------------
+extern "C" cm_status cm_pt_from_coeffs(cm_ctx *ctx, const int64_t *coeffs, int32_t level, double scale, cm_pt *out) {
+    if (!ctx || !coeffs || !out || !out->dev || level < 0 || level > ctx->L || !(scale > 0)) return CM_E_INVAL;
+    Arena A = arena_of(ctx);
+    HIPCHK(hipMemcpy(A.misc, coeffs, (size_t)ctx->n * 8, hipMemcpyHostToDevice));
+    launch_reduce_i64(ctx, out->dev, (const long long *)A.misc, iota_idx(ctx), level + 1, 0);
+    launch_ntt(ctx, out->dev, iota_idx(ctx), level + 1, false, 0);
+    if (out->mont) launch_to_mont(ctx, out->dev, iota_idx(ctx), level + 1, 0);
+    HIPCHK(hipDeviceSynchronize());
+    out->level = level;
+    out->scale = scale;
+    return CM_OK;
+}
+extern "C" cm_status cm_encode(cm_ctx *ctx, const double *re, const double *im, size_t nslots, int32_t level,
+                               double scale, cm_pt *out) {
+    if (!ctx || !out) return CM_E_INVAL;
+    if (scale == 0) scale = ctx->prm.scale;
+    std::vector<int64_t> c(ctx->n);
+    CMCHK(cm_encode_coeffs(ctx, re, im, nslots, scale, c.data()));
+    return cm_pt_from_coeffs(ctx, c.data(), level, scale, out);
+}
+
+extern "C" cm_status cm_encrypt(cm_ctx *ctx, const cm_sk *sk, const cm_pt *pt, uint64_t seed, cm_ct *out) {
+    if (!ctx || !sk || !pt || !pt->dev || !out || !out->dev || pt->mont) return CM_E_INVAL;
+    if (pt->level < 0 || pt->level > ctx->L) return CM_E_LEVEL;
+    const int limbs = pt->level + 1;
+    const size_t n = ctx->n;
+    Arena A = arena_of(ctx);
+    u64 *c0 = out->dev, *c1 = out->dev + (size_t)limbs * n, *e = A.tmp[0];
+    launch_sample_uniform(ctx, c1, iota_idx(ctx), limbs, seed, stream_id(ST_ENC_A, 0, 0, 0), 0);
+    launch_sample_gauss(ctx, e, iota_idx(ctx), limbs, seed, stream_id(ST_ENC_E, 0, 0, 0), 0);
+    launch_ntt(ctx, c1, iota_idx(ctx), limbs, false, 0);
+    launch_ntt(ctx, e, iota_idx(ctx), limbs, false, 0);
+    launch_encrypt(ctx, c0, c1, e, sk->d_ntt, pt->dev, limbs, 0);
+    HIPCHK(hipDeviceSynchronize());
+    out->level = pt->level;
+    out->ncomp = 2;
+    out->scale = pt->scale;
+    return CM_OK;
+}
+
+extern "C" cm_status cm_decrypt(cm_ctx *ctx, const cm_sk *sk, const cm_ct *ct, cm_pt *out) {
+    if (!ctx || !sk || !ct_ok(ctx, ct) || !out || !out->dev) return CM_E_INVAL;
+    const int limbs = (ct->level >= 1 ? 1 : 0) + 1;
+    launch_decrypt(ctx, out->dev, ct->dev, sk->d_ntt, ct->ncomp, ct->level + 1, limbs, 0);
+    HIPCHK(hipDeviceSynchronize());
+    out->level = limbs - 1;
+    out->scale = ct->scale;
+    out->mont = 0;
+    return CM_OK;
+}
+
+extern "C" cm_status cm_decode(cm_ctx *ctx, const cm_pt *pt, double *re, double *im, size_t nslots) {
+    if (!ctx || !pt || !pt->dev || !re || pt->mont || nslots > (size_t)ctx->n / 2) return CM_E_INVAL;
+    if (pt->level < 0 || pt->level > 1) return CM_E_LEVEL;
+    const size_t n = ctx->n;
+    const int limbs = pt->level + 1;
+    Arena A = arena_of(ctx);
+    HIPCHK(hipMemcpy(A.tmp[0], pt->dev, limbs * n * 8, hipMemcpyDeviceToDevice));
+    launch_ntt(ctx, A.tmp[0], iota_idx(ctx), limbs, true, 0);
+    std::vector<u64> h(limbs * n);
+    HIPCHK(hipMemcpy(h.data(), A.tmp[0], limbs * n * 8, hipMemcpyDeviceToHost));
+    std::vector<double> m(n);
+    const u64 q0 = ctx->mod[0];
+    if (limbs == 1) {
+        for (size_t i = 0; i < n; i++) {
+            u64 x = h[i];
+            m[i] = (x > q0 / 2 ? -(double)(q0 - x) : (double)x) / pt->scale;
+        }
+    } else {
+        const u64 q1 = ctx->mod[1], inv = h_invmod(q0 % q1, q1);
+        const u128 Q = (u128)q0 * q1;
+        for (size_t i = 0; i < n; i++) {
+            u64 x0 = h[i], x1 = h[n + i];
+            u64 diff = (x1 % q1 + q1 - x0 % q1) % q1;
+            u128 v = (u128)x0 + (u128)q0 * h_mulmod(diff, inv, q1);
+            m[i] = (v > Q / 2 ? -(double)(Q - v) : (double)v) / pt->scale;
+        }
+    }
+    decode_host(ctx, m, re, im, nslots);
+    return CM_OK;
+}
+
+static cm_status export_rows(cm_ctx *ctx, const u64 *dev, int ncomp, int level, bool mont, u64 *out) {
+    const size_t n = ctx->n, rows = (size_t)ncomp * (level + 1);
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    u64 *stage = nullptr;
+    HIPCHK(hipMalloc((void **)&stage, rows * n * 8));
+    if (mont)
+        launch_from_mont(ctx, stage, dev, k.d_q_mods3, (int)rows, 0);
+    else
+        hipMemcpyAsync(stage, dev, rows * n * 8, hipMemcpyDeviceToDevice, 0);
+    launch_ntt(ctx, stage, k.d_q_mods3, (int)rows, true, 0);
+    hipError_t e = hipMemcpy(out, stage, rows * n * 8, hipMemcpyDeviceToHost);
+    hipFree(stage);
+    HIPCHK(e);
+    return CM_OK;
+}
+extern "C" cm_status cm_ct_export(cm_ctx *ctx, const cm_ct *ct, uint64_t *out) {
+    if (!ctx || !ct_ok(ctx, ct) || !out) return CM_E_INVAL;
+    return export_rows(ctx, ct->dev, ct->ncomp, ct->level, false, (u64 *)out);
+}
+extern "C" cm_status cm_pt_export(cm_ctx *ctx, const cm_pt *pt, uint64_t *out) {
+    if (!ctx || !pt || !pt->dev || !out || pt->level < 0 || pt->level > ctx->L) return CM_E_INVAL;
+    return export_rows(ctx, pt->dev, 1, pt->level, pt->mont != 0, (u64 *)out);
+}
+
+// ---- ciphertext operations ----------------------------------------------------------------------------
+extern "C" cm_status cm_add(cm_ctx *ctx, const cm_ct *a, const cm_ct *b, cm_ct *out, void *stream) {
+    if (!ctx || !ct_ok(ctx, a) || !ct_ok(ctx, b) || !out || !out->dev) return CM_E_INVAL;
+    if (a->level != b->level || a->ncomp != b->ncomp) return CM_E_LEVEL;
+    if (!same_scale(a->scale, b->scale)) return CM_E_SCALE;
+    launch_add(ctx, out->dev, a->dev, b->dev, a->ncomp, a->level + 1, (hipStream_t)stream);
+    out->level = a->level, out->ncomp = a->ncomp, out->scale = a->scale;
+    return CM_OK;
+}
+extern "C" cm_status cm_mul_pt(cm_ctx *ctx, const cm_ct *a, const cm_pt *pt, cm_ct *out, void *stream) {
+    if (!ctx || !ct_ok(ctx, a) || !pt || !pt->dev || !pt->mont || !out || !out->dev) return CM_E_INVAL;
+    if (a->level != pt->level) return CM_E_LEVEL;
+    launch_mul_pt(ctx, out->dev, a->dev, pt->dev, a->ncomp, a->level + 1, (hipStream_t)stream);
+    out->level = a->level, out->ncomp = a->ncomp, out->scale = a->scale * pt->scale;
+    return CM_OK;
+}
+extern "C" cm_status cm_mul_ct(cm_ctx *ctx, const cm_ct *a, const cm_ct *b, cm_ct *out, void *stream) {
+    if (!ctx || !ct_ok(ctx, a) || !ct_ok(ctx, b) || !out || !out->dev || a->ncomp != 2 || b->ncomp != 2) return CM_E_INVAL;
+    if (a->level != b->level) return CM_E_LEVEL;
+    launch_tensor(ctx, out->dev, a->dev, b->dev, a->level + 1, 0, (hipStream_t)stream);
+    out->level = a->level, out->ncomp = 3, out->scale = a->scale * b->scale;
+    return CM_OK;
+}
+extern "C" cm_status cm_relinearize(cm_ctx *ctx, const cm_evk *evk, const cm_ct *a, cm_ct *out, void *stream) {
+    if (!ctx || !evk || !ct_ok(ctx, a) || a->ncomp != 3 || !out || !out->dev) return CM_E_INVAL;
+    const u64 *key = find_key(evk, 0);
+    if (!key) return CM_E_NOKEY;
+    hipStream_t st = (hipStream_t)stream;
+    Arena A = arena_of(ctx);
+    const size_t ln = (size_t)(a->level + 1) * ctx->n;
+    CMCHK(ks_raise(ctx, a->dev + 2 * ln, a->level, A.digits, st));
+    CMCHK(ks_apply(ctx, A.digits, key, a->level, 0, a->dev, 2, out->dev, st));
+    out->level = a->level, out->ncomp = 2, out->scale = a->scale;
+    return CM_OK;
+}
+
+cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st) {
+    // out[comp][level][n]; must not alias in
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    Arena A = arena_of(ctx);
+    const size_t n = ctx->n;
+    for (int c = 0; c < ncomp; c++)
+        HIPCHK(hipMemcpyAsync(A.misc + c * n, in + ((size_t)c * (level + 1) + level) * n, n * 8, hipMemcpyDeviceToDevice, st));
+    launch_ntt(ctx, A.misc, k.d_last_mods, ncomp, true, st);
+    u64 *red = A.tmp[2];
+    launch_rescale_reduce(ctx, red, A.misc, ncomp, level, st);
+    launch_ntt(ctx, red, k.d_red_mods, ncomp * level, false, st);
+    launch_rescale_finish(ctx, out, in, red, get_qlinv(ctx, level), ncomp, level, st);
+    return CM_OK;
+}
+extern "C" cm_status cm_rescale(cm_ctx *ctx, const cm_ct *a, cm_ct *out, void *stream) {
+    if (!ctx || !ct_ok(ctx, a) || !out || !out->dev) return CM_E_INVAL;
+    if (a->level < 1) return CM_E_LEVEL;
+    hipStream_t st = (hipStream_t)stream;
+    Arena A = arena_of(ctx);
+    const int level = a->level;
+    u64 *dst = out->dev == a->dev ? A.tmp[1] : out->dev;
+    CMCHK(rescale_into(ctx, a->dev, a->ncomp, level, dst, st));
+    if (dst != out->dev)
+        HIPCHK(hipMemcpyAsync(out->dev, dst, (size_t)a->ncomp * level * ctx->n * 8, hipMemcpyDeviceToDevice, st));
+    out->ncomp = a->ncomp;
+    out->scale = a->scale / (double)ctx->mod[level];
+    out->level = level - 1;
+    return CM_OK;
+}
+extern "C" cm_status cm_level_drop(cm_ctx *ctx, const cm_ct *a, int32_t level, cm_ct *out, void *stream) {
+    if (!ctx || !ct_ok(ctx, a) || !out || !out->dev) return CM_E_INVAL;
+    if (level < 0 || level > a->level) return CM_E_LEVEL;
+    if (out->dev == a->dev && level != a->level) return CM_E_INVAL;
+    const size_t n = ctx->n;
+    if (out->dev != a->dev)
+        for (int c = 0; c < a->ncomp; c++)
+            HIPCHK(hipMemcpyAsync(out->dev + (size_t)c * (level + 1) * n, a->dev + (size_t)c * (a->level + 1) * n,
+                                  (size_t)(level + 1) * n * 8, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    out->ncomp = a->ncomp, out->scale = a->scale, out->level = level;
+    return CM_OK;
+}
+
+cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64 g, u64 *out, hipStream_t st) {
+    Arena A = arena_of(ctx);
+    const int limbs = level + 1;
+    launch_automorphism(ctx, A.tmp[0], in, 2 * limbs, g, st);
+    CMCHK(ks_raise(ctx, A.tmp[0] + (size_t)limbs * ctx->n, level, A.digits, st));
+    return ks_apply(ctx, A.digits, key, level, 0, A.tmp[0], 1, out, st);
+}
+extern "C" cm_status cm_rotate(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, int32_t step, cm_ct *out, void *stream) {
+    if (!ctx || !evk || !ct_ok(ctx, in) || in->ncomp != 2 || !out || !out->dev) return CM_E_INVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const u64 g = galois_of_step(ctx, step);
+    if (g == 1) {
+        if (out->dev != in->dev)
+            HIPCHK(hipMemcpyAsync(out->dev, in->dev, cm_ct_words(ctx, in->level, 2) * 8, hipMemcpyDeviceToDevice, st));
+    } else {
+        const u64 *key = find_key(evk, g);
+        if (!key) return CM_E_NOKEY;
+        CMCHK(rotate_into(ctx, key, in->dev, in->level, g, out->dev, st));
+    }
+    out->level = in->level, out->ncomp = 2, out->scale = in->scale;
+    return CM_OK;
+}
+extern "C" cm_status cm_rotate_hoisted(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, const int32_t *steps,
+                                       size_t nsteps, cm_ct *outs, void *stream) {
+    if (!ctx || !evk || !ct_ok(ctx, in) || in->ncomp != 2 || !steps || !outs) return CM_E_INVAL;
+    hipStream_t st = (hipStream_t)stream;
+    for (size_t i = 0; i < nsteps; i++) {
+        if (!outs[i].dev || outs[i].dev == in->dev) return CM_E_INVAL;
+        u64 g = galois_of_step(ctx, steps[i]);
+        if (g != 1 && !find_key(evk, g)) return CM_E_NOKEY;
+    }
+    Arena A = arena_of(ctx);
+    const size_t ln = (size_t)(in->level + 1) * ctx->n;
+    CMCHK(ks_raise(ctx, in->dev + ln, in->level, A.digits, st));
+    for (size_t i = 0; i < nsteps; i++) {
+        u64 g = galois_of_step(ctx, steps[i]);
+        if (g == 1)
+            HIPCHK(hipMemcpyAsync(outs[i].dev, in->dev, 2 * ln * 8, hipMemcpyDeviceToDevice, st));
+        else
+            CMCHK(ks_apply(ctx, A.digits, find_key(evk, g), in->level, g, in->dev, 1, outs[i].dev, st));
+        outs[i].level = in->level, outs[i].ncomp = 2, outs[i].scale = in->scale;
+    }
+    return CM_OK;
+}

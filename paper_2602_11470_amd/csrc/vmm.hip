@@ -1,0 +1,236 @@
+// Packed homomorphic vector-matrix product (Sec. 4.1, App. C / Algorithm 1): plan building
+// (slot layout, weight diagonals, rotation amounts) and the device driver.
+//
+// Slots are written i = b*t + r (block b, residue r), t = S/d for the shorter vector length d,
+// t' = S/(alpha d) for the longer one.  Rotation amounts of the printed algorithm are read in
+// slots as: preprocess 2^i (t-1); baby step j t' t; giant step r_i t' t; reduce 2^l; and
+// r_o = d/(t' r_i), the choice for which r_i r_o t' = d.
+#include <math.h>
+
+#include <thread>
+
+#include "kernels.h"
+
+struct cm_vmm_plan {
+    cm_ctx *ctx = nullptr;
+    int S, d, alpha, t, tp, t1, t2, r_i, r_o, M, tau, d_in, d_out, level;
+    bool expand, contract;
+    double pt_scale;
+    std::vector<int> pre_steps, baby_steps, reduce_steps;
+    int giant_step;
+    u64 *d_pts = nullptr;      // [r_i*r_o][level+1][n], multiplier form
+    u64 *d_work = nullptr;     // r_i baby + r_o inner + 1 temporary ciphertexts
+};
+
+static int ilog2(int x) {
+    int l = 0;
+    while ((1 << l) < x) l++;
+    return l;
+}
+static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+static cm_status plan_shape(cm_ctx *ctx, int d_in, int d_out, int r_i, int tau, int level, double pt_scale,
+                            cm_vmm_plan *p) {
+    if (d_in < 1 || d_out < 1 || level < 1 || level > ctx->L) return level < 1 ? CM_E_LEVEL : CM_E_INVAL;
+    p->ctx = ctx;
+    p->S = ctx->n / 2;
+    p->d_in = d_in, p->d_out = d_out;
+    p->d = d_in < d_out ? d_in : d_out;
+    int big = d_in < d_out ? d_out : d_in;
+    if (!pow2(p->d) || !pow2(big) || big > p->S) return CM_E_LAYOUT;
+    p->alpha = big / p->d;
+    p->expand = d_out > d_in, p->contract = d_in > d_out;
+    p->t = p->S / p->d, p->tp = p->S / big;
+    p->t1 = p->contract ? p->tp : p->t;
+    p->t2 = p->contract ? p->t : p->tp;
+    p->M = p->d / p->tp;
+    if (p->M < 1) return CM_E_LAYOUT;
+    if (r_i == 0) r_i = 1 << ((ilog2(p->M) + 1) / 2);
+    if (!pow2(r_i) || p->M % r_i) return CM_E_LAYOUT;
+    p->r_i = r_i, p->r_o = p->M / r_i;
+    if (tau < 0 || tau >= p->t2) return CM_E_LAYOUT;
+    p->tau = tau, p->level = level;
+    p->pt_scale = pt_scale > 0 ? pt_scale : ctx->prm.scale;
+    for (int i = 0; i < ilog2(p->t1); i++) p->pre_steps.push_back((1 << i) * (p->t - 1));
+    for (int j = 0; j < r_i; j++) p->baby_steps.push_back(j * p->tp * p->t);
+    p->giant_step = r_i * p->tp * p->t;
+    // block of t2 slots sums into residue tau: rotate right where the bit of tau is set
+    for (int l = 0; l < ilog2(p->t2); l++) p->reduce_steps.push_back(((tau >> l) & 1) ? -(1 << l) : (1 << l));
+    return CM_OK;
+}
+
+static int in_slot(const cm_vmm_plan *p, int a) {
+    return p->contract ? (a % p->d) * p->t + (a / p->d) * p->tp : a * p->t;
+}
+
+// Input index present in every slot after the preprocess step, found by moving index labels
+// through the same rotate-and-add steps.
+static std::vector<int> source_labels(const cm_vmm_plan *p) {
+    const int S = p->S;
+    std::vector<int> lab(S, -1), nxt(S);
+    for (int a = 0; a < p->d_in; a++) lab[in_slot(p, a)] = a;
+    for (int r : p->pre_steps) {
+        for (int i = 0; i < S; i++) {
+            int from = lab[(i + r) % S];            // Rot(c, r)[i] = c[i + r]
+            nxt[i] = from >= 0 ? from : lab[i];
+        }
+        lab.swap(nxt);
+    }
+    return lab;
+}
+
+// Slot vector of weight plaintext (j, k): the product at slot i of baby rotation j ends, after k
+// giant rotations and the reduce step, in the block of t2 slots that owns one output index.
+static void diag_slots(const cm_vmm_plan *p, const std::vector<int> &lab, const double *W, int j, int k,
+                       std::vector<double> &out) {
+    const int S = p->S;
+    out.resize(S);
+    for (int i = 0; i < S; i++) {
+        int row = lab[(i + p->baby_steps[j]) % S];
+        int blk = (int)((((long long)i - (long long)k * p->giant_step) % S + S) % S) / p->t2;
+        int col = p->expand ? blk / p->alpha + (blk % p->alpha) * p->d : blk;
+        out[i] = W[(size_t)row * p->d_out + col];
+    }
+}
+
+static cm_status plan_alloc(cm_vmm_plan *p) {
+    const size_t n = p->ctx->n, ptw = (size_t)(p->level + 1) * n, ctw = 2 * ptw;
+    if (hipMalloc((void **)&p->d_pts, (size_t)p->M * ptw * 8) != hipSuccess) return CM_E_NOMEM;
+    if (hipMalloc((void **)&p->d_work, (size_t)(p->r_i + p->r_o + 1) * ctw * 8) != hipSuccess) return CM_E_NOMEM;
+    return CM_OK;
+}
+
+static cm_status plan_load_diag(cm_vmm_plan *p, int idx, const int64_t *coeffs) {
+    cm_pt pt;
+    pt.dev = p->d_pts + (size_t)idx * (p->level + 1) * p->ctx->n;
+    pt.mont = 1;
+    return cm_pt_from_coeffs(p->ctx, coeffs, p->level, p->pt_scale, &pt);
+}
+
+extern "C" cm_status cm_vmm_plan_create(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
+                                        int32_t level, double pt_scale, const double *W, cm_vmm_plan **out) {
+    if (!ctx || !W || !out) return CM_E_INVAL;
+    cm_vmm_plan *p = new (std::nothrow) cm_vmm_plan();
+    if (!p) return CM_E_NOMEM;
+    cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, p);
+    if (s == CM_OK) s = plan_alloc(p);
+    if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
+    const std::vector<int> lab = source_labels(p);
+    const int n = ctx->n, batch = 16;
+    std::vector<std::vector<int64_t>> coeffs(batch, std::vector<int64_t>(n));
+    std::vector<cm_status> st(batch);
+    for (int base = 0; base < p->M && s == CM_OK; base += batch) {
+        int cnt = p->M - base < batch ? p->M - base : batch;
+        std::vector<std::thread> th;
+        for (int b = 0; b < cnt; b++)
+            th.emplace_back([&, b]() {
+                int idx = base + b, j = idx / p->r_o, k = idx % p->r_o;
+                std::vector<double> slots;
+                diag_slots(p, lab, W, j, k, slots);
+                st[b] = cm_encode_coeffs(ctx, slots.data(), nullptr, slots.size(), p->pt_scale, coeffs[b].data());
+            });
+        for (auto &t : th) t.join();
+        for (int b = 0; b < cnt && s == CM_OK; b++) {
+            s = st[b];
+            if (s == CM_OK) s = plan_load_diag(p, base + b, coeffs[b].data());
+        }
+    }
+    if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
+    *out = p;
+    return CM_OK;
+}
+
+extern "C" cm_status cm_vmm_plan_create_from_coeffs(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i,
+                                                    int32_t tau, int32_t level, double pt_scale,
+                                                    const int64_t *coeffs, cm_vmm_plan **out) {
+    if (!ctx || !coeffs || !out) return CM_E_INVAL;
+    cm_vmm_plan *p = new (std::nothrow) cm_vmm_plan();
+    if (!p) return CM_E_NOMEM;
+    cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, p);
+    if (s == CM_OK) s = plan_alloc(p);
+    for (int idx = 0; idx < p->M && s == CM_OK; idx++) s = plan_load_diag(p, idx, coeffs + (size_t)idx * ctx->n);
+    if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
+    *out = p;
+    return CM_OK;
+}
+
+extern "C" void cm_vmm_plan_destroy(cm_vmm_plan *plan) {
+    if (!plan) return;
+    hipFree(plan->d_pts);
+    hipFree(plan->d_work);
+    delete plan;
+}
+
+extern "C" int32_t cm_vmm_plan_steps(const cm_vmm_plan *p, int32_t *steps, int32_t cap) {
+    if (!p) return 0;
+    std::vector<int> all(p->pre_steps);
+    for (int j = 1; j < p->r_i; j++) all.push_back(p->baby_steps[j]);
+    if (p->r_o > 1) all.push_back(p->giant_step);
+    all.insert(all.end(), p->reduce_steps.begin(), p->reduce_steps.end());
+    for (int i = 0; i < (int)all.size() && i < cap && steps; i++) steps[i] = all[i];
+    return (int32_t)all.size();
+}
+extern "C" cm_status cm_vmm_plan_info(const cm_vmm_plan *p, int32_t *r_i, int32_t *r_o, int32_t *n_rot) {
+    if (!p) return CM_E_INVAL;
+    if (r_i) *r_i = p->r_i;
+    if (r_o) *r_o = p->r_o;
+    if (n_rot) *n_rot = (int)p->pre_steps.size() + (p->r_i - 1) + (p->r_o - 1) + (int)p->reduce_steps.size();
+    return CM_OK;
+}
+extern "C" cm_status cm_vmm_plan_diag_export(cm_ctx *ctx, const cm_vmm_plan *p, int32_t j, int32_t k, uint64_t *out) {
+    if (!ctx || !p || !out || j < 0 || j >= p->r_i || k < 0 || k >= p->r_o) return CM_E_INVAL;
+    cm_pt pt;
+    pt.dev = p->d_pts + (size_t)(j * p->r_o + k) * (p->level + 1) * ctx->n;
+    pt.level = p->level, pt.mont = 1, pt.scale = p->pt_scale;
+    return cm_pt_export(ctx, &pt, out);
+}
+
+extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const cm_ct *x, cm_ct *y,
+                               void *stream) {
+    if (!ctx || !evk || !p || !x || !x->dev || !y || !y->dev || x->ncomp != 2 || p->ctx != ctx) return CM_E_INVAL;
+    if (x->level != p->level) return CM_E_LEVEL;
+    hipStream_t st = (hipStream_t)stream;
+    const int level = p->level, limbs = level + 1;
+    const size_t n = ctx->n, ctw = 2 * (size_t)limbs * n, ptw = (size_t)limbs * n;
+    // every key must be there before anything is enqueued
+    auto key_of = [&](int step) { return find_key(evk, galois_of_step(ctx, step)); };
+    for (int r : p->pre_steps) if (!key_of(r)) return CM_E_NOKEY;
+    for (int j = 1; j < p->r_i; j++) if (!key_of(p->baby_steps[j])) return CM_E_NOKEY;
+    if (p->r_o > 1 && !key_of(p->giant_step)) return CM_E_NOKEY;
+    for (int r : p->reduce_steps) if (!key_of(r)) return CM_E_NOKEY;
+
+    u64 *babies = p->d_work, *inner = babies + (size_t)p->r_i * ctw, *tmp = inner + (size_t)p->r_o * ctw;
+    // 1. preprocess: c <- c + Rot(c, 2^i (t-1))
+    u64 *c = babies;
+    HIPCHK(hipMemcpyAsync(c, x->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
+    for (int r : p->pre_steps) {
+        CMCHK(rotate_into(ctx, key_of(r), c, level, galois_of_step(ctx, r), tmp, st));
+        launch_add(ctx, c, c, tmp, 2, limbs, st);
+    }
+    // 2. baby steps: rotations of the same ciphertext share its raised digits
+    if (p->r_i > 1) {
+        u64 *digits = arena_digits(ctx);
+        CMCHK(ks_raise(ctx, c + ptw, level, digits, st));
+        for (int j = 1; j < p->r_i; j++)
+            CMCHK(ks_apply(ctx, digits, key_of(p->baby_steps[j]), level, galois_of_step(ctx, p->baby_steps[j]), c, 1,
+                           babies + (size_t)j * ctw, st));
+    }
+    //    multiply-accumulate: inner_k = sum_j baby_j * p_{j,k}
+    launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, p->r_o, limbs, ctw, ptw, st);
+    //    giant steps, Horner form
+    u64 *acc = inner + (size_t)(p->r_o - 1) * ctw;
+    for (int k = p->r_o - 2; k >= 0; k--) {
+        CMCHK(rotate_into(ctx, key_of(p->giant_step), acc, level, galois_of_step(ctx, p->giant_step), tmp, st));
+        acc = inner + (size_t)k * ctw;
+        launch_add(ctx, acc, acc, tmp, 2, limbs, st);
+    }
+    // 3. reduce inside the ciphertext
+    for (int r : p->reduce_steps) {
+        CMCHK(rotate_into(ctx, key_of(r), acc, level, galois_of_step(ctx, r), tmp, st));
+        launch_add(ctx, acc, acc, tmp, 2, limbs, st);
+    }
+    CMCHK(rescale_into(ctx, acc, 2, level, y->dev, st));
+    y->level = level - 1, y->ncomp = 2;
+    y->scale = x->scale * p->pt_scale / (double)ctx->mod[level];
+    return CM_OK;
+}

@@ -1,0 +1,188 @@
+"""GPU parity: libcachemir (through its C ABI) against the CPU oracle, element by element.
+
+Integer work (ciphertext limbs, keys, plaintext residues) must match bit for bit under the same
+seeds; decrypted results must be within 1e-4 (max-abs) of the float64 product.  Plaintext
+polynomials cross as integer coefficients (encoding is floating point, so the two encoders are
+compared separately, to within one unit per coefficient)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def both():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from oracle import ckks, params
+    from paper_2602_11470_amd import binding as B
+    prm = params.config1()
+    octx = ckks.Context(prm)
+    gctx = B.config1()
+    osk = octx.keygen_secret(7)
+    gsk = gctx.keygen_secret(7)
+    steps = [1, -1, 7, 64, 1024, 2047]
+    okeys = octx.keygen_rotations(osk, steps, 5, with_relin=True)
+    gkeys = gctx.keygen_rotations(gsk, steps, 5, with_relin=True)
+    yield dict(B=B, octx=octx, gctx=gctx, osk=osk, gsk=gsk, okeys=okeys, gkeys=gkeys, prm=prm)
+    gctx.close()
+
+
+def _pair(b, z, level, seed, scale=None):
+    """The same message encrypted on both sides from the oracle's integer coefficients."""
+    octx, gctx = b["octx"], b["gctx"]
+    scale = octx.prm.scale if scale is None else scale
+    coeffs = octx.encode_coeffs(z, scale)
+    oct_ = octx.encrypt(b["osk"], octx.pt_from_coeffs(coeffs, level, scale), seed)
+    gct = gctx.encrypt(b["gsk"], gctx.pt_from_coeffs(coeffs, level, scale), seed)
+    return oct_, gct
+
+
+def _same(b, oct_, gct):
+    assert gct.level == oct_.level and gct.ncomp == len(oct_.c)
+    assert abs(gct.scale / oct_.scale - 1) < 1e-12
+    got, want = b["gctx"].ct_export(gct), b["octx"].canonical(oct_)
+    assert got.shape == want.shape
+    assert np.array_equal(got, want)
+
+
+def test_modulus_chain_and_tables(both):
+    b = both
+    assert b["gctx"].moduli().tolist() == b["prm"].moduli
+    assert b["gctx"].gauss_table().tolist() == b["octx"].cdt.tolist()
+
+
+def test_secret_key(both):
+    assert np.array_equal(both["gsk"].coeffs().astype(np.int64), both["osk"]["coeffs"])
+
+
+def test_plaintext_residues_and_ntt_roundtrip(both):
+    b = both
+    rng = np.random.default_rng(0)
+    c = rng.integers(-2 ** 62, 2 ** 62, b["octx"].n, dtype=np.int64)
+    c[:4] = [0, -1, 2 ** 63 - 1, -2 ** 63]
+    for level in (0, 2, 4):
+        for mont in (False, True):
+            pt = b["gctx"].pt_from_coeffs(c, level, 2.0 ** 40, mont=mont)
+            want = b["octx"].from_i64(c, b["octx"].q_idx(level))
+            assert np.array_equal(b["gctx"].pt_export(pt), want)
+
+
+def test_encoder_within_one_unit_and_roundtrip(both):
+    b = both
+    rng = np.random.default_rng(1)
+    z = rng.uniform(-1, 1, b["octx"].S) + 1j * rng.uniform(-1, 1, b["octx"].S)
+    got = b["gctx"].encode_coeffs(z, 2.0 ** 40)
+    want = b["octx"].encode_coeffs(z, 2.0 ** 40)
+    assert np.abs(got - want).max() <= 1
+    ct = b["gctx"].encrypt(b["gsk"], b["gctx"].encode(z, 4), 3)
+    assert np.abs(b["gctx"].decrypt(b["gsk"], ct) - z).max() < 1e-8
+
+
+def test_encrypt(both):
+    b = both
+    z = np.random.default_rng(2).uniform(-1, 1, b["octx"].S)
+    for level in (4, 1, 0):
+        o, g = _pair(b, z, level, 11 + level)
+        _same(b, o, g)
+        assert np.abs(b["gctx"].decrypt(b["gsk"], g) - z).max() < 1e-6
+
+
+def test_evaluation_keys(both):
+    b = both
+    octx = b["octx"]
+    all_idx = list(range(len(octx.mod)))
+    from oracle import ckks as ock
+    for step, relin in ((7, False), (-1, False), (0, True)):
+        okey = b["okeys"][ock.RELIN_ID if relin else octx.galois(step)]
+        for digit in (0, 2, 4):
+            assert np.array_equal(b["gkeys"].export(step, relin, digit, 0), octx.intt(okey.b[digit], all_idx))
+            assert np.array_equal(b["gkeys"].export(step, relin, digit, 1), octx.intt(okey.a[digit], all_idx))
+
+
+@pytest.mark.parametrize("level", [4, 3, 0])
+def test_add_mul_rescale(both, level):
+    b = both
+    octx, gctx = b["octx"], b["gctx"]
+    rng = np.random.default_rng(3)
+    z1, z2 = rng.uniform(-1, 1, octx.S), rng.uniform(-1, 1, octx.S)
+    o1, g1 = _pair(b, z1, level, 21)
+    o2, g2 = _pair(b, z2, level, 22)
+    _same(b, octx.ct_add(o1, o2), gctx.add(g1, g2))
+    c = octx.encode_coeffs(z2, octx.prm.scale)
+    om = octx.mul_pt(o1, octx.pt_from_coeffs(c, level, octx.prm.scale))
+    gm = gctx.mul_pt(g1, gctx.pt_from_coeffs(c, level, octx.prm.scale, mont=True))
+    _same(b, om, gm)
+    ot, gt = octx.mul_ct(o1, o2), gctx.mul_ct(g1, g2)
+    _same(b, ot, gt)
+    orl, grl = octx.relinearize(ot, b["okeys"]), gctx.relinearize(b["gkeys"], gt)
+    _same(b, orl, grl)
+    if level >= 1:
+        _same(b, octx.rescale(om), gctx.rescale(gm))
+        _same(b, octx.rescale(ot), gctx.rescale(gt))          # three components
+        ors, grs = octx.rescale(orl), gctx.rescale(grl)
+        _same(b, ors, grs)
+        assert np.abs(gctx.decrypt(b["gsk"], grs) - z1 * z2).max() < 1e-5
+        _same(b, octx.level_drop(o1, level - 1), gctx.level_drop(g1, level - 1))
+
+
+@pytest.mark.parametrize("level", [4, 2, 0])
+@pytest.mark.parametrize("step", [1, -1, 7, 1024, 2047])
+def test_rotate(both, level, step):
+    b = both
+    z = np.random.default_rng(4).uniform(-1, 1, b["octx"].S)
+    o, g = _pair(b, z, level, 31)
+    orot, grot = b["octx"].rotate(o, step, b["okeys"]), b["gctx"].rotate(b["gkeys"], g, step)
+    _same(b, orot, grot)
+    assert np.abs(b["gctx"].decrypt(b["gsk"], grot) - np.roll(z, -step)).max() < 1e-5
+
+
+@pytest.mark.parametrize("level", [4, 1])
+def test_rotate_hoisted(both, level):
+    b = both
+    z = np.random.default_rng(5).uniform(-1, 1, b["octx"].S)
+    o, g = _pair(b, z, level, 41)
+    steps = [7, 64, -1, 2047]
+    h = b["octx"].hoist(o)
+    outs = b["gctx"].rotate_hoisted(b["gkeys"], g, steps)
+    for s, gout in zip(steps, outs):
+        _same(b, b["octx"].rotate_hoisted(o, h, s, b["okeys"]), gout)
+
+
+def test_keyswitch_alone(both):
+    import torch
+    b = both
+    octx = b["octx"]
+    rng = np.random.default_rng(6)
+    level = 3
+    idx = octx.q_idx(level)
+    d_coeff = (rng.integers(0, 2 ** 62, (level + 1, octx.n), dtype=np.uint64) % octx.mod[idx][:, None]).astype(np.uint64)
+    # bring the same polynomial to both evaluation domains from its coefficients
+    d_o = octx.ntt(d_coeff, idx)
+    dev = torch.from_numpy(d_coeff.view(np.int64)).cuda()
+    b["gctx"].ntt(dev, idx)
+    k0, k1 = b["gctx"].keyswitch(b["gkeys"], dev, level, step=64)
+    b["gctx"].ntt(k0, idx, inverse=True)
+    b["gctx"].ntt(k1, idx, inverse=True)
+    o0, o1 = octx.keyswitch(d_o, level, b["okeys"][octx.galois(64)])
+    assert np.array_equal(k0.cpu().numpy().view(np.uint64), octx.intt(o0, idx))
+    assert np.array_equal(k1.cpu().numpy().view(np.uint64), octx.intt(o1, idx))
+
+
+def test_errors(both):
+    b = both
+    B, gctx = b["B"], b["gctx"]
+    z = np.zeros(4)
+    _, g = _pair(b, z, 2, 51)
+    with pytest.raises(B.CachemirError) as e:
+        gctx.rotate(b["gkeys"], g, 3)               # no key for step 3
+    assert e.value.status == -4
+    _, g0 = _pair(b, z, 0, 52)
+    with pytest.raises(B.CachemirError) as e:
+        gctx.rescale(g0)
+    assert e.value.status == -2
+    with pytest.raises(B.CachemirError) as e:
+        gctx.add(g, g0)
+    assert e.value.status == -2

@@ -1,0 +1,204 @@
+"""GPU parity of the packed products: vmm_pt (Algorithm 1) and vmm_kv (Sec. 5) against the
+oracle, limbs bit for bit, and against the float64 products within 1e-4."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from oracle import ckks, params
+    from paper_2602_11470_amd import binding as B
+    prm = params.config1()
+    octx, gctx = ckks.Context(prm), B.config1()
+    yield dict(B=B, octx=octx, gctx=gctx, osk=octx.keygen_secret(1), gsk=gctx.keygen_secret(1), prm=prm)
+    gctx.close()
+
+
+def _enc_both(e, slots, level, seed, scale=None):
+    octx, gctx = e["octx"], e["gctx"]
+    scale = octx.prm.scale if scale is None else scale
+    coeffs = octx.encode_coeffs(slots, scale)
+    top = octx.prm.L
+    o = octx.level_drop(octx.encrypt(e["osk"], octx.pt_from_coeffs(coeffs, top, scale), seed), level)
+    g = gctx.encrypt(e["gsk"], gctx.pt_from_coeffs(coeffs, top, scale), seed)
+    if level != top:
+        g = gctx.level_drop(g, level)
+    return o, g
+
+
+def _same(e, o, g):
+    assert g.level == o.level and abs(g.scale / o.scale - 1) < 1e-12
+    assert np.array_equal(e["gctx"].ct_export(g), e["octx"].canonical(o))
+
+
+@pytest.mark.parametrize("d_in,d_out,level,r_i,tau,seed", [
+    (64, 64, 4, 0, 0, 0),          # benchmark configuration 1
+    (64, 64, 2, 1, 0, 1),          # no baby steps
+    (256, 256, 3, 0, 0, 2),        # 32 diagonals: 8 baby x 4 giant steps
+    (128, 512, 4, 0, 0, 3),        # expanding
+    (512, 128, 2, 0, 0, 4),        # contracting
+    (128, 128, 4, 0, 5, 5),        # output on residue 5 (cache append)
+])
+def test_vmm_pt_matches_oracle_and_float64(env, d_in, d_out, level, r_i, tau, seed):
+    from oracle import packing, vmm
+    from paper_2602_11470_amd import inputs
+    e = env
+    octx, gctx = e["octx"], e["gctx"]
+    x, W = inputs.vmm_inputs(seed, d_in, d_out, "uniform", 0.05)
+    plan = packing.make_plan(octx.S, d_in, d_out, r_i or None, tau)
+    scale = octx.prm.scale
+    diag_coeffs = [[octx.encode_coeffs(v, scale) for v in row] for row in plan.diagonals(W)]
+    odiags = [[octx.pt_from_coeffs(c, level, scale) for c in row] for row in diag_coeffs]
+    flat = np.stack([c for row in diag_coeffs for c in row])
+    gplan = gctx.vmm_plan(d_in, d_out, level=level, r_i=plan.r_i, tau=tau, coeffs=flat)
+    assert (gplan.r_i, gplan.r_o, gplan.n_rotations) == (plan.r_i, plan.r_o, plan.n_rotations)
+    assert sorted(set(gplan.steps())) == sorted(set(plan.all_steps()))
+    okeys = octx.keygen_rotations(e["osk"], plan.all_steps(), 2)
+    gkeys = gctx.keygen_rotations(e["gsk"], gplan.steps(), 2)
+    ox, gx = _enc_both(e, plan.pack_input(x), level, 3)
+    oy = vmm.vmm_pt(vmm.CkksOps(octx, okeys), plan, ox, odiags)
+    gy = gctx.vmm_pt(gkeys, gplan, gx)
+    _same(e, oy, gy)
+    out = gctx.decrypt(e["gsk"], gy)
+    assert np.abs(plan.unpack_output(out.real) - x @ W).max() < TOL
+
+    # the library's own diagonal extraction and encoder: within one unit of the oracle's, and
+    # the product still decrypts to x W
+    gplan2 = gctx.vmm_plan(d_in, d_out, W=W, level=level, r_i=plan.r_i, tau=tau)
+    q0 = int(octx.mod[0])
+    for j, k in {(0, 0), (plan.r_i - 1, plan.r_o - 1)}:
+        got = gplan2.diag_export(j, k)[0].astype(np.int64)
+        got = np.where(got > q0 // 2, got - q0, got)
+        assert np.abs(got - diag_coeffs[j][k]).max() <= 1
+    out2 = gctx.decrypt(e["gsk"], gctx.vmm_pt(gkeys, gplan2, gx))
+    assert np.abs(plan.unpack_output(out2.real) - x @ W).max() < TOL
+
+
+def test_vmm_pt_missing_key_and_level_errors(env):
+    e = env
+    B, gctx = e["B"], e["gctx"]
+    W = np.zeros((64, 64))
+    gplan = gctx.vmm_plan(64, 64, W=W, level=3)
+    gkeys = gctx.keygen_rotations(e["gsk"], gplan.steps()[:-1], 2)
+    _, gx = _enc_both(e, np.zeros(8), 3, 1)
+    with pytest.raises(B.CachemirError) as err:
+        gctx.vmm_pt(gkeys, gplan, gx)
+    assert err.value.status == -4
+    _, gx2 = _enc_both(e, np.zeros(8), 2, 1)
+    full = gctx.keygen_rotations(e["gsk"], gplan.steps(), 2)
+    with pytest.raises(B.CachemirError) as err:
+        gctx.vmm_pt(full, gplan, gx2)
+    assert err.value.status == -2
+    with pytest.raises(B.CachemirError) as err:
+        gctx.vmm_plan(96, 96, W=np.zeros((96, 96)), level=3)       # not a power of two
+    assert err.value.status == -5
+
+
+@pytest.mark.parametrize("r_i", [0, 4])
+def test_kv_append_scores_and_attention(env, r_i):
+    """H = 16 heads of E = 16 dims on the 2048-slot ring (t = 8): the cache is built by appends,
+    then q K^T and s V run against it."""
+    from oracle import packing, vmm
+    from paper_2602_11470_amd import inputs
+    e = env
+    B, octx, gctx = e["B"], e["octx"], e["gctx"]
+    H, E, L = 16, 16, octx.prm.L
+    lay = packing.KvLayout(octx.S, H, E, r_i)
+    ntok = 13
+    q, K, V, s = inputs.attention_inputs(7, H, 4, E, ntok)
+    lv = L - 1                                   # cache level; appended vectors arrive at L
+    kv = gctx.kv_create(H, E, lv, r_i=r_i)
+    steps = lay.qk_steps() + lay.sv_steps() + lay.append_steps()
+    assert sorted(set(kv.steps())) == sorted(set(steps))
+    okeys = octx.keygen_rotations(e["osk"], steps, 2, with_relin=True)
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2, with_relin=True)
+    ops = vmm.CkksOps(octx, okeys)
+
+    # base masks: encoded once by the oracle; both sides derive every mask from them by the
+    # exact Galois map on the integer coefficients
+    def base(kind, level):
+        m = np.zeros(octx.S)
+        if kind == 0:
+            m[:H * lay.t] = 1
+        elif kind == 1:
+            m[::lay.t] = 1
+        else:
+            m[[h * lay.t for h in range(H)]] = 1
+        return octx.encode_coeffs(m, float(octx.mod[level]))
+
+    bases = {0: base(0, lv - 1), 1: base(1, lv + 1), 2: base(2, lv + 1)}
+    for kind, c in bases.items():
+        kv.set_mask(kind, c)
+
+    def omask(kind, shift_right, level):
+        g = octx.galois(-shift_right)
+        idx = octx.q_idx(level)
+        coeff = octx.automorphism_coeff(octx.from_i64(bases[kind], idx), idx, g)
+        from oracle.ckks import Pt
+        return Pt(octx.ntt(coeff, idx), level, float(octx.mod[level]))
+
+    # the rotated base masks are the layout's masks (checked on decoded slots)
+    m = omask(2, lay.slot(3, 0, 5), lv + 1)
+    dec = octx.decode_coeffs(np.array(octx.centred_coeffs(octx.intt(m.m, octx.q_idx(lv + 1)), 1), dtype=float) / m.scale)
+    want = np.zeros(octx.S)
+    want[[lay.slot(3, h, 5) for h in range(H)]] = 1
+    assert np.abs(dec - want).max() < 1e-6
+
+    okc, ovc = [], [None] * E
+    for n in range(ntok):
+        c, tau = n // lay.t, n % lay.t
+        ok_new, gk_new = _enc_both(e, lay.pack_vec(K[n], tau), L, 100 + n)
+        ov_new, gv_new = _enc_both(e, lay.pack_vec(V[n], tau), L, 500 + n)
+        vmasks = [omask(2, lay.slot((c - k) % E, 0, tau) + lay.v_shift(k), lv + 1) for k in range(E)]
+        vmm.kv_append(ops, lay, okc, ovc, n, ok_new, ov_new, omask(1, tau, lv + 1), vmasks)
+        kv.append(gkeys, gk_new, gv_new)
+    assert kv.tokens() == ntok
+    for c in range(len(okc)):
+        assert np.array_equal(kv.export(B.CM_QK, c), octx.canonical(okc[c]))
+    for k in (0, 1, E - 1):
+        assert np.array_equal(kv.export(B.CM_SV, k), octx.canonical(ovc[k]))
+
+    oq, gq = _enc_both(e, lay.pack_vec(q), lv, 10)
+    om = vmm.qk_scores(ops, lay, oq, okc, [omask(0, (c % E) * H * lay.t, lv - 1) for c in range(len(okc))])
+    gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, gq)
+    _same(e, om, gm)
+    got = lay.unpack_scores(gctx.decrypt(e["gsk"], gm).real, ntok)
+    assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
+
+    os_, gs = _enc_both(e, lay.pack_scores(s), lv, 50)
+    oa = vmm.score_times_v(ops, lay, os_, ovc)
+    ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)
+    _same(e, oa, ga)
+    assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
+
+
+def test_kv_with_library_masks_decrypts_correctly(env):
+    """The library's own mask encoder (no coefficients handed in)."""
+    from oracle import packing
+    from paper_2602_11470_amd import inputs
+    e = env
+    B, octx, gctx = e["B"], e["octx"], e["gctx"]
+    H, E, L = 8, 32, octx.prm.L
+    lay = packing.KvLayout(octx.S, H, E, 8)
+    ntok = 11
+    q, K, V, s = inputs.attention_inputs(9, H, 2, E, ntok)
+    kv = gctx.kv_create(H, E, L - 1, r_i=8)
+    gkeys = gctx.keygen_rotations(e["gsk"], kv.steps(), 2, with_relin=True)
+    for n in range(ntok):
+        tau = n % lay.t
+        _, gk_new = _enc_both(e, lay.pack_vec(K[n], tau), L, 100 + n)
+        _, gv_new = _enc_both(e, lay.pack_vec(V[n], tau), L, 500 + n)
+        kv.append(gkeys, gk_new, gv_new)
+    _, gq = _enc_both(e, lay.pack_vec(q), L - 1, 10)
+    gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, gq)
+    got = lay.unpack_scores(gctx.decrypt(e["gsk"], gm).real, ntok)
+    assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
+    _, gs = _enc_both(e, lay.pack_scores(s), L - 1, 50)
+    ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)
+    assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
