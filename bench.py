@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the homomorphic decode-step VMM on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic input: cm_vmm_pt of an encrypted
+4096-vector (interleaved replicated packing) against a plaintext 4096x4096 matrix on the ring
+n = 2^16 with 24 ciphertext primes of 50 bits + 4 special primes of 60 bits (6 key-switch
+digits), at the top level: 52 rotations (21 full key switches + 31 hoisted), 512 plaintext
+multiply-accumulates, one rescale.  Keys, weight plaintexts and the input ciphertext are
+resident in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+
+Prints one JSON line (see the design doc for the definitions of the roofline entries).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+D = 4096
+
+
+def gpu_setup():
+    import torch
+    from paper_2602_11470_amd import binding as B, inputs
+    ctx = B.llama_ring(24, 4)
+    x, W = inputs.vmm_inputs(1, D, D)
+    plan = ctx.vmm_plan(D, D, W=W)
+    sk = ctx.keygen_secret(1)
+    keys = ctx.keygen_rotations(sk, plan.steps(), 2)
+    t = ctx.S // D
+    slots = np.zeros(ctx.S)
+    slots[::t] = x
+    ct = ctx.encrypt(sk, ctx.encode(slots, ctx.L), 3)
+    torch.cuda.synchronize()
+    return dict(torch=torch, B=B, ctx=ctx, plan=plan, sk=sk, keys=keys, ct=ct, x=x, W=W, t=t)
+
+
+def time_steps(g, steps, warmup):
+    torch, ctx = g["torch"], g["ctx"]
+    y = ctx.vmm_pt(g["keys"], g["plan"], g["ct"])
+    for _ in range(warmup):
+        ctx.vmm_pt(g["keys"], g["plan"], g["ct"], out=y)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ctx.vmm_pt(g["keys"], g["plan"], g["ct"], out=y)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    out = ctx.decrypt(g["sk"], y).real[::g["t"]]
+    err = float(np.abs(out - g["x"] @ g["W"]).max())
+    return dt / steps, err
+
+
+def kernel_profile(g, steps):
+    """The same steps again with every kernel launch bracketed by HIP events on its stream."""
+    ctx, B = g["ctx"], g["B"]
+    y = ctx.vmm_pt(g["keys"], g["plan"], g["ct"])
+    g["torch"].cuda.synchronize()
+    ctx.profile_enable(True)
+    for _ in range(steps):
+        ctx.vmm_pt(g["keys"], g["plan"], g["ct"], out=y)
+    g["torch"].cuda.synchronize()
+    names = ["ntt_fwd", "ntt_inv", "base_conv", "inner_product", "moddown_finish", "vmm_mac",
+             "elementwise", "rescale"]
+    fam = {}
+    for i, nme in enumerate(names):
+        launches, units, ms = ctx.profile_get(i)
+        fam[nme] = dict(launches=launches / steps, units=units / steps, ms=ms / steps)
+    ctx.profile_enable(False)
+    return fam
+
+
+def time_rotations(g, reps=20):
+    torch, ctx = g["torch"], g["ctx"]
+    r = ctx.rotate(g["keys"], g["ct"], 7)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        ctx.rotate(g["keys"], g["ct"], 7, out=r)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / reps
+
+
+def cpu_baseline():
+    """The oracle as it stands on the host cores, on a bounded sample of the same workload: the
+    ring of the benchmark, 3 full rotations, one hoisting + 3 hoisted rotations, 8 plaintext
+    multiply-accumulates and one rescale, each timed and scaled by the step's operation counts
+    (21 / 1 / 31 / 512 / 1)."""
+    from oracle import ckks, params
+    prm = params.config2()
+    ctx = ckks.Context(prm)
+    sk = ctx.keygen_secret(1)
+    keys = ctx.keygen_rotations(sk, [7, 64], 2)
+    rng = np.random.default_rng(0)
+    z = rng.normal(size=ctx.S)
+    ct = ctx.encrypt(sk, ctx.encode(z, prm.L), 3)
+    pt = ctx.encode(rng.normal(0, 0.02, ctx.S), prm.L)
+
+    def timed(fn, reps):
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            r = fn()
+        return (time.perf_counter() - t0) / reps, r
+
+    t_rot, _ = timed(lambda: ctx.rotate(ct, 7, keys), 3)
+    t_hoist, h = timed(lambda: ctx.hoist(ct), 1)
+    t_hrot, _ = timed(lambda: ctx.rotate_hoisted(ct, h, 64, keys), 3)
+    acc = ctx.mul_pt(ct, pt)
+    t_mac, _ = timed(lambda: ctx.mac_pt(acc, ct, pt), 8)
+    t_resc, _ = timed(lambda: ctx.rescale(acc), 1)
+    t_vmm = 21 * t_rot + t_hoist + 31 * t_hrot + 512 * t_mac + t_resc
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": 1.0 / t_vmm, "unit": "VMM/s", "cores": cores, "kind": "oracle",
+            "sample": "n=2^16, 24+4 primes: 3 rotations, 1 hoisting, 3 hoisted rotations, 8 pt-ct MACs, "
+                      "1 rescale timed; scaled by the step's counts 21/1/31/512/1 (extrapolated)",
+            "key_switch_s": t_rot, "seconds_per_vmm": t_vmm}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    g = gpu_setup()
+    sec, err = time_steps(g, a.steps, a.warmup)
+    if not err < 1e-4:
+        print(f"bench.py: decrypted result off by {err}", file=sys.stderr)
+        sys.exit(1)
+    fam = kernel_profile(g, min(a.steps, 5))
+    t_rot = time_rotations(g)
+    n, limbs, K, beta = g["ctx"].n, 24, 4, 6
+    limb_bytes = 8 * n
+    # dominant kernel family of the step by time
+    dom = max(fam, key=lambda k: fam[k]["ms"])
+    ntt = fam["ntt_fwd"]
+    ntt_per_launch_limbs = ntt["units"] / ntt["launches"]
+    ntt_launch_s = ntt["ms"] / ntt["launches"] * 1e-3
+    # forward NTT: algorithmic bytes = read + write each limb once (1 MiB per 2^16-point limb)
+    ntt_gbs = ntt_per_launch_limbs * 2 * limb_bytes / ntt_launch_s / 1e9
+    ip = fam["inner_product"]
+    ip_launch_s = ip["ms"] / ip["launches"] * 1e-3
+    ext = limbs + K
+    ip_bytes = limb_bytes * (2 * beta * ext + beta * ext + 2 * ext)      # key + raised digits + result
+    ip_gbs = ip_bytes / ip_launch_s / 1e9
+    roofs = {
+        "ntt_fwd": {"bound": "hbm", "achieved": ntt_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": ntt_gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "ntt_cols_fwd+ntt_rows256_fwd",
+                    "limbs_per_launch": ntt_per_launch_limbs, "us_per_launch": ntt_launch_s * 1e6},
+        "inner_product": {"bound": "hbm", "achieved": ip_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": ip_gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "k_inner_product",
+                          "us_per_launch": ip_launch_s * 1e6},
+    }
+    roofline = roofs.get(dom, roofs["ntt_fwd"])
+    ks_bytes = limb_bytes * (2 * beta * ext + limbs + 2 * limbs)         # key once + input + output
+    out = {
+        "metric": "homomorphic VMMs/s (d=4096 projection, n=2^16, 24x50-bit + 4x60-bit primes, top level)",
+        "value": 1.0 / sec, "unit": "VMM/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "config2: encrypted 4096-vector x plaintext 4096x4096, interleaved replicated "
+                               "packing, BSGS 32x16, 52 rotations, 512 pt-ct MACs", "ring_degree": n,
+                   "ciphertext_primes": limbs, "special_primes": K, "dnum": beta, "level": limbs - 1},
+        "max_abs_err_vs_float64": err,
+        "key_switches_per_s": 1.0 / t_rot, "key_switch_us": t_rot * 1e6,
+        "key_switch_algorithmic_gbs": ks_bytes / t_rot / 1e9,
+        "key_switch_frac_of_hbm_peak": ks_bytes / t_rot / 1e9 / HBM_PEAK_GBS,
+        "limb_ntts_per_s": ntt["units"] / (ntt["ms"] * 1e-3),
+        "kernel_ms_per_step": {k: round(v["ms"], 4) for k, v in fam.items()},
+        "roofline": roofline,
+        "roofline_inner_product": roofs["inner_product"],
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

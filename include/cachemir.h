@@ -223,6 +223,18 @@ cm_status cm_keyswitch(cm_ctx *ctx, const cm_evk *evk, int32_t step, int32_t rel
                        const uint64_t *d, int32_t level, uint64_t *ks0, uint64_t *ks1,
                        void *stream);
 
+/* Per-kernel-family timing: while enabled, every launch of the listed families is bracketed by
+ * HIP events on its own stream.  cm_profile_enable(ctx, 1) clears the records and starts,
+ * (ctx, 0) stops; cm_profile_get sums launches, work units (limbs for the NTTs, written limbs for
+ * base conversion and element-wise kernels, 1 otherwise) and milliseconds of one family. */
+enum {
+    CM_K_NTT_FWD = 0, CM_K_NTT_INV = 1, CM_K_BASE_CONV = 2, CM_K_INNER_PRODUCT = 3,
+    CM_K_MODDOWN_FINISH = 4, CM_K_VMM_MAC = 5, CM_K_ELEMENTWISE = 6, CM_K_RESCALE = 7,
+    CM_K_FAMILIES = 8
+};
+cm_status cm_profile_enable(cm_ctx *ctx, int32_t on);
+cm_status cm_profile_get(cm_ctx *ctx, int32_t family, double *launches, double *units, double *ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -84,6 +84,8 @@ _SIGS = {
     "cm_kv_set_mask": ([_vp, _i32, _vp], _i32),
     "cm_kv_append": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_vmm_kv": ([_vp, _vp, _vp, _i32, _P(cm_ct), _P(cm_ct), _vp], _i32),
+    "cm_profile_enable": ([_vp, _i32], _i32),
+    "cm_profile_get": ([_vp, _i32, _P(_f64), _P(_f64), _P(_f64)], _i32),
     "cm_ntt": ([_vp, _vp, _vp, _i32, _i32, _vp], _i32),
     "cm_keyswitch": ([_vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp], _i32),
 }
@@ -273,6 +275,15 @@ class Context:
         idx = _np(mod_idx, np.int32)
         _chk(lib.cm_ntt(self.h, data.data_ptr(), idx.ctypes.data, len(idx), int(inverse), _stream()))
 
+    def profile_enable(self, on=True):
+        _chk(lib.cm_profile_enable(self.h, int(on)))
+
+    def profile_get(self, family):
+        """(launches, units, milliseconds) of one kernel family since profile_enable(True)."""
+        a, b, c = _f64(), _f64(), _f64()
+        _chk(lib.cm_profile_get(self.h, family, C.byref(a), C.byref(b), C.byref(c)))
+        return a.value, b.value, c.value
+
     def vmm_plan(self, d_in, d_out, W=None, level=None, r_i=0, tau=0, pt_scale=0.0, coeffs=None):
         return VmmPlan(self, d_in, d_out, W, self.L if level is None else level, r_i, tau, pt_scale, coeffs)
 
@@ -301,7 +312,7 @@ class SecretKey:
         return out
 
     def __del__(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and lib is not None:
             lib.cm_sk_destroy(self.h)
             self.h = None
 
@@ -318,7 +329,7 @@ class Evk:
         return out
 
     def __del__(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and lib is not None:
             lib.cm_evk_destroy(self.h)
             self.h = None
 
@@ -351,7 +362,7 @@ class VmmPlan:
         return out
 
     def __del__(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and lib is not None:
             lib.cm_vmm_plan_destroy(self.h)
             self.h = None
 
@@ -391,7 +402,7 @@ class KvCache:
         _chk(lib.cm_kv_append(self.ctx.h, evk.h, self.h, C.byref(k_new.d), C.byref(v_new.d), _stream()))
 
     def __del__(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and lib is not None:
             lib.cm_kv_destroy(self.h)
             self.h = None
 

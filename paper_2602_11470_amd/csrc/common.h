@@ -68,8 +68,17 @@ struct ConvTable {            // fast base conversion src -> dst (all indices in
     std::vector<int> src, dst;
 };
 
+// per-kernel-family timing with HIP events on the launching stream (off unless enabled)
+struct ProfState {
+    bool on = false;
+    std::vector<hipEvent_t> pool;
+    struct Rec { int fam; double units; size_t e0; };
+    std::vector<Rec> recs;
+};
+
 struct cm_ctx {
     cm_params prm;
+    ProfState prof;
     int n, logn, L, K, alpha, nmod;      // nmod = L+1+K
     std::vector<u64> mod;                 // host copy of moduli
     std::vector<u64> psi;
@@ -124,6 +133,15 @@ struct cm_evk {
     } while (0)
 
 void cm_set_hip_error(int e);
+
+struct Prof {
+    cm_ctx *c;
+    hipStream_t st;
+    size_t e0;
+    bool live;
+    Prof(cm_ctx *ctx, int fam, double units, hipStream_t st);
+    ~Prof();
+};
 
 // ---- host helpers (context.hip) ------------------------------------------------------------
 u64 h_mulmod(u64 a, u64 b, u64 q);

@@ -25,6 +25,44 @@ extern "C" const char *cm_strerror(cm_status s) {
     return "unknown status";
 }
 
+// ---- kernel-family timing ---------------------------------------------------------------------------
+Prof::Prof(cm_ctx *ctx, int fam, double units, hipStream_t s) : c(ctx), st(s), e0(0), live(ctx->prof.on) {
+    if (!live) return;
+    ProfState &p = c->prof;
+    e0 = 2 * p.recs.size();
+    while (p.pool.size() < e0 + 2) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { live = false; return; }
+        p.pool.push_back(e);
+    }
+    p.recs.push_back({fam, units, e0});
+    hipEventRecord(p.pool[e0], st);
+}
+Prof::~Prof() {
+    if (live) hipEventRecord(c->prof.pool[e0 + 1], st);
+}
+extern "C" cm_status cm_profile_enable(cm_ctx *ctx, int32_t on) {
+    if (!ctx) return CM_E_INVAL;
+    ctx->prof.on = on != 0;
+    ctx->prof.recs.clear();
+    return CM_OK;
+}
+extern "C" cm_status cm_profile_get(cm_ctx *ctx, int32_t family, double *launches, double *units, double *ms) {
+    if (!ctx || family < 0 || family >= CM_K_FAMILIES) return CM_E_INVAL;
+    double l = 0, u = 0, t = 0;
+    for (auto &r : ctx->prof.recs) {
+        if (r.fam != family) continue;
+        float dt = 0;
+        HIPCHK(hipEventSynchronize(ctx->prof.pool[r.e0 + 1]));
+        HIPCHK(hipEventElapsedTime(&dt, ctx->prof.pool[r.e0], ctx->prof.pool[r.e0 + 1]));
+        l += 1, u += r.units, t += dt;
+    }
+    if (launches) *launches = l;
+    if (units) *units = u;
+    if (ms) *ms = t;
+    return CM_OK;
+}
+
 // ---- number theory on the host -----------------------------------------------------------------
 u64 h_mulmod(u64 a, u64 b, u64 q) { return (u64)(((u128)a * b) % q); }
 u64 h_powmod(u64 b, u64 e, u64 q) {
@@ -325,6 +363,7 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
 extern "C" void cm_ctx_destroy(cm_ctx *ctx) {
     if (!ctx) return;
     cm_ops_forget_ctx(ctx);
+    for (hipEvent_t e : ctx->prof.pool) hipEventDestroy(e);
     hipFree(ctx->d_modc);
     hipFree(ctx->d_tw);
     hipFree(ctx->d_twp);

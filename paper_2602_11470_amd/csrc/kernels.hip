@@ -53,6 +53,7 @@ __global__ void k_add(u64 *out, const u64 *a, const u64 *b, const ModC *modc, in
     out[o] = addmod(a[o], b[o], q);
 }
 void launch_add(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int ncomp, int limbs, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, ncomp * limbs, st);
     hipLaunchKernelGGL(k_add, dim3(ctx->n / TPB, ncomp * limbs), dim3(TPB), 0, st, out, a, b, ctx->d_modc, limbs, ctx->n);
 }
 
@@ -63,6 +64,7 @@ __global__ void k_mul_pt(u64 *out, const u64 *a, const u64 *pt_mont, const ModC 
     out[o] = redc((u128)a[o] * pt_mont[(size_t)(r % limbs) * n + i], m.q, m.qinv);
 }
 void launch_mul_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, ncomp * limbs, st);
     hipLaunchKernelGGL(k_mul_pt, dim3(ctx->n / TPB, ncomp * limbs), dim3(TPB), 0, st, out, a, pt_mont, ctx->d_modc, limbs, ctx->n);
 }
 
@@ -75,6 +77,7 @@ __global__ void k_mac_pt(u64 *out, const u64 *a, const u64 *pt_mont, const ModC 
     out[o] = accumulate ? addmod(out[o], v, m.q) : v;
 }
 void launch_mac_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, int accumulate, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, ncomp * limbs, st);
     hipLaunchKernelGGL(k_mac_pt, dim3(ctx->n / TPB, ncomp * limbs), dim3(TPB), 0, st, out, a, pt_mont, ctx->d_modc, limbs, ctx->n, accumulate);
 }
 
@@ -98,6 +101,7 @@ __global__ void k_tensor(u64 *out, const u64 *a, const u64 *b, const ModC *modc,
     out[o + 2 * cs] = d2;
 }
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, 3 * limbs, st);
     hipLaunchKernelGGL(k_tensor, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, a, b, ctx->d_modc, limbs, ctx->n, accumulate);
 }
 
@@ -108,6 +112,7 @@ __global__ void k_automorphism(u64 *out, const u64 *in, int n, int logn, unsigne
     out[r * n + i] = in[r * n + perm_src(i, g, logn)];
 }
 void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, rows, st);
     hipLaunchKernelGGL(k_automorphism, dim3(ctx->n / TPB, rows), dim3(TPB), 0, st, out, in, ctx->n, ctx->logn, (unsigned)g);
 }
 
@@ -142,6 +147,7 @@ __global__ void k_base_conv(u64 *out, const int *out_rows, const u64 *in, const 
 }
 void launch_base_conv(cm_ctx *ctx, const ConvTable &t, u64 *out, const int *d_out_rows, const u64 *in,
                       const int *d_in_rows, int batch, size_t in_stride, size_t out_stride, hipStream_t st) {
+    Prof prof_(ctx, CM_K_BASE_CONV, batch * t.nt, st);
     hipLaunchKernelGGL(k_base_conv, dim3(ctx->n / TPB, batch), dim3(TPB), 0, st, out, d_out_rows, in, d_in_rows,
                        t.d_src, t.d_dst, t.d_inv_hat, t.d_inv_hat_sh, t.d_hat_mont, ctx->d_modc, t.ns, t.nt,
                        ctx->n, in_stride, out_stride);
@@ -178,6 +184,7 @@ __global__ void k_inner_product(u64 *u0, u64 *u1, const u64 *dig, const u64 *evk
     *reinterpret_cast<ulonglong2 *>(u1 + o) = make_ulonglong2(redc(a0, m.q, m.qinv), redc(a1, m.q, m.qinv));
 }
 void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g, hipStream_t st) {
+    Prof prof_(ctx, CM_K_INNER_PRODUCT, 1, st);
     int ext = level + 1 + ctx->K;
     hipLaunchKernelGGL(k_inner_product, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, u0, u1, dig, evk, ctx->d_modc,
                        beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g);
@@ -201,6 +208,7 @@ __global__ void k_moddown_finish(u64 *out, const u64 *u, const u64 *conv, const 
 }
 void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
                            int addend_comps, int level, u64 g, hipStream_t st) {
+    Prof prof_(ctx, CM_K_MODDOWN_FINISH, 1, st);
     int ext = level + 1 + ctx->K;
     size_t n = ctx->n;
     hipLaunchKernelGGL(k_moddown_finish, dim3(ctx->n / TPB, level + 1, 2), dim3(TPB), 0, st, out, u, conv, d_pinv,
@@ -224,9 +232,11 @@ __global__ void k_rescale_finish(u64 *out, const u64 *in, const u64 *red, const 
     out[((size_t)c * level + l) * n + i] = mul_shoup(d, qlinv[2 * l], qlinv[2 * l + 1], q);
 }
 void launch_rescale_reduce(cm_ctx *ctx, u64 *red, const u64 *last, int ncomp, int level, hipStream_t st) {
+    Prof prof_(ctx, CM_K_RESCALE, ncomp * level, st);
     hipLaunchKernelGGL(k_rescale_reduce, dim3(ctx->n / TPB, level, ncomp), dim3(TPB), 0, st, red, last, ctx->d_modc, level, ctx->n);
 }
 void launch_rescale_finish(cm_ctx *ctx, u64 *out, const u64 *in, const u64 *red, const u64 *d_qlinv, int ncomp, int level, hipStream_t st) {
+    Prof prof_(ctx, CM_K_RESCALE, ncomp * level, st);
     hipLaunchKernelGGL(k_rescale_finish, dim3(ctx->n / TPB, level, ncomp), dim3(TPB), 0, st, out, in, red, d_qlinv, ctx->d_modc, level, ctx->n);
 }
 
@@ -369,6 +379,7 @@ __global__ void k_vmm_mac(u64 *out, const u64 *babies, const u64 *pts, const Mod
     }
 }
 void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, hipStream_t st) {
+    Prof prof_(ctx, CM_K_VMM_MAC, r_i * r_o, st);
     hipLaunchKernelGGL(k_vmm_mac, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs,
                        ctx->n, ct_stride, pt_stride);
 }

@@ -265,6 +265,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_rows16_inv(u64 *__restrict__ 
 void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mod_idx, int limbs,
                      bool inverse, hipStream_t st) {
     if (limbs <= 0) return;
+    Prof prof_(ctx, inverse ? CM_K_NTT_INV : CM_K_NTT_FWD, limbs, st);
     const int n = ctx->n, n2 = n >> 8;
     dim3 grid((unsigned)limbs * (n >> 12)), block(NTT_THREADS);
     if (!inverse) {
