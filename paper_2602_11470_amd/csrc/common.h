@@ -61,11 +61,21 @@ __device__ __forceinline__ u64 submod(u64 a, u64 b, u64 q) { return a >= b ? a -
 
 struct ConvTable {            // fast base conversion src -> dst (all indices into the modulus list)
     int ns = 0, nt = 0;
-    u64 *d_inv_hat = nullptr;     // [ns]   (hat_m^{-1} mod q_m), plain
-    u64 *d_inv_hat_sh = nullptr;  // [ns]   Shoup companion
-    u64 *d_hat_mont = nullptr;    // [ns*nt] (hat_m mod r) 2^64 mod r
-    int *d_src = nullptr, *d_dst = nullptr;
+    std::vector<u64> inv_hat;     // [ns]   (hat_m^{-1} mod q_m), plain
+    std::vector<u64> inv_hat_sh;  // [ns]   Shoup companion
+    std::vector<u64> hat_mont;    // [ns*nt] (hat_m mod r) 2^64 mod r
     std::vector<int> src, dst;
+};
+
+// The same table in the form the conversion kernel reads (one per digit / per direction).
+#define CONV_MAX_SRC 8
+#define CONV_MAX_DST 64
+struct ConvDev {
+    int ns, nt;
+    int src_mod[CONV_MAX_SRC], in_rows[CONV_MAX_SRC];
+    u64 inv_hat[CONV_MAX_SRC], inv_hat_sh[CONV_MAX_SRC];
+    int dst_mod[CONV_MAX_DST], out_rows[CONV_MAX_DST];
+    u64 hat_mont[CONV_MAX_SRC * CONV_MAX_DST];      // [m * nt + r]
 };
 
 // per-kernel-family timing with HIP events on the launching stream (off unless enabled)

@@ -168,20 +168,12 @@ static ConvTable make_conv(cm_ctx *ctx, const std::vector<int> &src, const std::
             hat_mont[(size_t)m * t.nt + r] = (u64)((((u128)hr) << 64) % qr);
         }
     }
-    t.d_inv_hat = upload(inv_hat);
-    t.d_inv_hat_sh = upload(inv_hat_sh);
-    t.d_hat_mont = upload(hat_mont);
-    t.d_src = upload(src);
-    t.d_dst = upload(dst);
+    t.inv_hat = inv_hat;
+    t.inv_hat_sh = inv_hat_sh;
+    t.hat_mont = hat_mont;
     return t;
 }
-static void free_conv(ConvTable &t) {
-    hipFree(t.d_inv_hat);
-    hipFree(t.d_inv_hat_sh);
-    hipFree(t.d_hat_mont);
-    hipFree(t.d_src);
-    hipFree(t.d_dst);
-}
+static void free_conv(ConvTable &) {}
 
 const std::vector<ConvTable> &get_modup(cm_ctx *ctx, int level) {
     auto it = ctx->modup.find(level);

@@ -10,8 +10,8 @@ void launch_mul_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int 
 void launch_mac_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, int accumulate, hipStream_t st);
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st);
 void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st);
-void launch_base_conv(cm_ctx *ctx, const ConvTable &t, u64 *out, const int *d_out_rows, const u64 *in,
-                      const int *d_in_rows, int batch, size_t in_stride, size_t out_stride, hipStream_t st);
+void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_step, int max_nt, u64 *out, const u64 *in,
+                      size_t in_stride, size_t out_stride, const u64 *own_src, hipStream_t st);
 void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g, hipStream_t st);
 void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
                            int addend_comps, int level, u64 g, hipStream_t st);
@@ -29,12 +29,9 @@ void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, in
 // ops.hip internals shared with vmm.hip
 struct KsLevel {            // cached per level: which rows of the digit array are converted / transformed
     int level, ext, beta;
-    std::vector<int *> d_out_rows;    // per digit: rows (within one digit's [ext] block) the conversion writes
-    std::vector<int *> d_in_rows;     // per digit: rows of the input polynomial it reads
     int *d_ntt_rows = nullptr;        // rows of the [beta*ext] digit array to transform
     int *d_ntt_mods = nullptr;        // their modulus indices
     int n_ntt = 0;
-    int *d_own_rows = nullptr;        // rows of the digit array that are copies of input limbs
     int *d_sp_rows = nullptr;         // rows level+1.. of an ext-sized array (special limbs), for both components
     int *d_sp_mods = nullptr;
     int *d_q_rows = nullptr;          // 0..level
@@ -51,4 +48,6 @@ cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *ou
 u64 *arena_digits(const cm_ctx *ctx);
 const u64 *find_key(const cm_evk *evk, u64 g);
 void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mods, int limbs, bool inverse, hipStream_t st);
+void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, const int *d_src_rows,
+                    const int *d_mods, int limbs, bool inverse, hipStream_t st);
 void decode_host(const cm_ctx *ctx, const std::vector<double> &m, double *re, double *im, size_t nslots);

@@ -119,38 +119,49 @@ void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, 
 // ---- fast base conversion ----------------------------------------------------------------------
 // in rows in_rows[m] (coefficient domain, residues under src moduli) -> out rows out_rows[r]:
 //   y_m = a_m * inv_hat_m mod q_m;  out_r = sum_m y_m * hat_{m,r} mod q_r   (no correction term)
-#define CONV_MAX_SRC 8
-__global__ void k_base_conv(u64 *out, const int *out_rows, const u64 *in, const int *in_rows,
-                            const int *src_mod, const int *dst_mod, const u64 *inv_hat, const u64 *inv_hat_sh,
-                            const u64 *hat_mont, const ModC *modc, int ns, int nt, int n,
-                            size_t in_batch_stride, size_t out_batch_stride) {
-    int i = blockIdx.x * TPB + threadIdx.x;
-    in += blockIdx.y * in_batch_stride;
-    out += blockIdx.y * out_batch_stride;
+// blockIdx.z = batch item: table z*tab_step, input at z*in_stride, output at z*out_stride (the
+// digits of a raise use one table each and share the input; the two components of a ModDown share
+// the table).  blockIdx.y = group of CONV_TG targets; the cheap y_m are recomputed per group so
+// that a conversion fills the machine.  If own_src is given, group 0 also copies the source rows
+// of own_src (the evaluation-domain input) to the same rows of the output.
+#define CONV_TG 4
+__global__ void k_base_conv(u64 *out, const u64 *in, const ConvDev *tabs, int tab_step, const ModC *modc, int n,
+                            size_t in_stride, size_t out_stride, const u64 *own_src) {
+    const int i = blockIdx.x * TPB + threadIdx.x;
+    const ConvDev &t = tabs[blockIdx.z * tab_step];
+    const int ns = t.ns, nt = t.nt;
+    const int r0 = blockIdx.y * CONV_TG;
+    if (r0 >= nt) return;
+    in += blockIdx.z * in_stride;
+    out += blockIdx.z * out_stride;
     u64 y[CONV_MAX_SRC];
 #pragma unroll
     for (int m = 0; m < CONV_MAX_SRC; m++) {
         y[m] = 0;
         if (m < ns) {
-            u64 q = modc[src_mod[m]].q;
-            y[m] = mul_shoup(in[(size_t)in_rows[m] * n + i], inv_hat[m], inv_hat_sh[m], q);
+            u64 q = modc[t.src_mod[m]].q;
+            y[m] = mul_shoup(in[(size_t)t.in_rows[m] * n + i], t.inv_hat[m], t.inv_hat_sh[m], q);
+            if (own_src && r0 == 0) out[(size_t)t.in_rows[m] * n + i] = own_src[(size_t)t.in_rows[m] * n + i];
         }
     }
-    for (int r = 0; r < nt; r++) {
-        const ModC md = modc[dst_mod[r]];
-        u128 acc = 0;
 #pragma unroll
-        for (int m = 0; m < CONV_MAX_SRC; m++)
-            if (m < ns) acc += (u128)y[m] * hat_mont[m * nt + r];
-        out[(size_t)out_rows[r] * n + i] = redc(acc, md.q, md.qinv);
+    for (int rr = 0; rr < CONV_TG; rr++) {
+        const int r = r0 + rr;
+        if (r < nt) {
+            const ModC md = modc[t.dst_mod[r]];
+            u128 acc = 0;
+#pragma unroll
+            for (int m = 0; m < CONV_MAX_SRC; m++)
+                if (m < ns) acc += (u128)y[m] * t.hat_mont[m * nt + r];
+            out[(size_t)t.out_rows[r] * n + i] = redc(acc, md.q, md.qinv);
+        }
     }
 }
-void launch_base_conv(cm_ctx *ctx, const ConvTable &t, u64 *out, const int *d_out_rows, const u64 *in,
-                      const int *d_in_rows, int batch, size_t in_stride, size_t out_stride, hipStream_t st) {
-    Prof prof_(ctx, CM_K_BASE_CONV, batch * t.nt, st);
-    hipLaunchKernelGGL(k_base_conv, dim3(ctx->n / TPB, batch), dim3(TPB), 0, st, out, d_out_rows, in, d_in_rows,
-                       t.d_src, t.d_dst, t.d_inv_hat, t.d_inv_hat_sh, t.d_hat_mont, ctx->d_modc, t.ns, t.nt,
-                       ctx->n, in_stride, out_stride);
+void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_step, int max_nt, u64 *out, const u64 *in,
+                      size_t in_stride, size_t out_stride, const u64 *own_src, hipStream_t st) {
+    Prof prof_(ctx, CM_K_BASE_CONV, batch * max_nt, st);
+    hipLaunchKernelGGL(k_base_conv, dim3(ctx->n / TPB, (max_nt + CONV_TG - 1) / CONV_TG, batch), dim3(TPB), 0, st, out, in,
+                       d_tabs, tab_step, ctx->d_modc, ctx->n, in_stride, out_stride, own_src);
 }
 
 // ---- evaluation-key inner product ------------------------------------------------------------------

@@ -75,6 +75,8 @@ __device__ __forceinline__ int pad(int e) { return e + (e >> 4); }
 // ---- column kernels: stages 0..7 --------------------------------------------------------------
 // grid.x = limbs * (n2/16); tile = rows 0..255 of 16 adjacent columns.
 __global__ __launch_bounds__(NTT_THREADS) void ntt_cols_fwd(u64 *__restrict__ data,
+                                                           const u64 *__restrict__ src,
+                                                           const int *__restrict__ src_rows,
                                                            const int *__restrict__ rows,
         const int *__restrict__ mod_idx,
                                                            const ModC *__restrict__ modc,
@@ -88,10 +90,11 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_cols_fwd(u64 *__restrict__ da
     const u64 q = modc[mi].q;
     const u64 *tw = tw_all + (size_t)mi * n, *twp = twp_all + (size_t)mi * n;
     u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + c0;
+    const u64 *ps = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n + c0 : p;
     const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
     u64 v[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = p[(size_t)(sub + 16 * k) * n2 + c];
+    for (int k = 0; k < 16; k++) v[k] = ps[(size_t)(sub + 16 * k) * n2 + c];
     radix16_fwd(v, tw, twp, q, 1);
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[pad((sub + 16 * k) * 16 + c)] = v[k];
@@ -180,6 +183,8 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_fwd(u64 *__restrict__
 }
 
 __global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_inv(u64 *__restrict__ data,
+                                                              const u64 *__restrict__ src,
+                                                              const int *__restrict__ src_rows,
                                                               const int *__restrict__ rows,
         const int *__restrict__ mod_idx,
                                                               const ModC *__restrict__ modc,
@@ -196,7 +201,8 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_inv(u64 *__restrict__
     const int sub = threadIdx.x & 15, blk = threadIdx.x >> 4;
     const u64 B = (u64)chunk * 16 + blk;
     u64 v[16];
-    const ulonglong2 *in = reinterpret_cast<const ulonglong2 *>(p + blk * 256 + 16 * sub);
+    const u64 *ps = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n + (size_t)chunk * 4096 : p;
+    const ulonglong2 *in = reinterpret_cast<const ulonglong2 *>(ps + blk * 256 + 16 * sub);
 #pragma unroll
     for (int k = 0; k < 8; k++) {
         ulonglong2 x = in[k];
@@ -241,6 +247,8 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_rows16_fwd(u64 *__restrict__ 
     }
 }
 __global__ __launch_bounds__(NTT_THREADS) void ntt_rows16_inv(u64 *__restrict__ data,
+                                                             const u64 *__restrict__ src,
+                                                             const int *__restrict__ src_rows,
                                                              const int *__restrict__ rows,
         const int *__restrict__ mod_idx,
                                                              const ModC *__restrict__ modc,
@@ -254,22 +262,25 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_rows16_inv(u64 *__restrict__ 
     const u64 *tw = tw_all + (size_t)mi * n, *twp = twp_all + (size_t)mi * n;
     const u64 B = (u64)chunk * 256 + threadIdx.x;
     u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + B * 16;
+    const u64 *ps = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n + B * 16 : p;
     u64 v[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = p[k];
+    for (int k = 0; k < 16; k++) v[k] = ps[k];
     radix16_inv(v, tw, twp, q, 256 + B);
 #pragma unroll
     for (int k = 0; k < 16; k++) p[k] = v[k];
 }
 
-void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mod_idx, int limbs,
-                     bool inverse, hipStream_t st) {
+// data rows d_rows[i] (or i) are transformed in place; with src != nullptr the first pass reads row
+// src_rows[i] (or i) of src instead, so the transform is out of place and src is left untouched.
+void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, const int *d_src_rows,
+                    const int *d_mod_idx, int limbs, bool inverse, hipStream_t st) {
     if (limbs <= 0) return;
     Prof prof_(ctx, inverse ? CM_K_NTT_INV : CM_K_NTT_FWD, limbs, st);
     const int n = ctx->n, n2 = n >> 8;
     dim3 grid((unsigned)limbs * (n >> 12)), block(NTT_THREADS);
     if (!inverse) {
-        hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, ctx->d_modc,
+        hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, ctx->d_modc,
                            ctx->d_tw, ctx->d_twp, n, n2);
         if (n2 == 256)
             hipLaunchKernelGGL(ntt_rows256_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, ctx->d_modc,
@@ -279,14 +290,18 @@ void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mod
                                ctx->d_tw, ctx->d_twp, n);
     } else {
         if (n2 == 256)
-            hipLaunchKernelGGL(ntt_rows256_inv, grid, block, 0, st, data, d_rows, d_mod_idx, ctx->d_modc,
-                               ctx->d_itw, ctx->d_itwp, n);
+            hipLaunchKernelGGL(ntt_rows256_inv, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx,
+                               ctx->d_modc, ctx->d_itw, ctx->d_itwp, n);
         else
-            hipLaunchKernelGGL(ntt_rows16_inv, grid, block, 0, st, data, d_rows, d_mod_idx, ctx->d_modc,
-                               ctx->d_itw, ctx->d_itwp, n);
+            hipLaunchKernelGGL(ntt_rows16_inv, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx,
+                               ctx->d_modc, ctx->d_itw, ctx->d_itwp, n);
         hipLaunchKernelGGL(ntt_cols_inv, grid, block, 0, st, data, d_rows, d_mod_idx, ctx->d_modc,
                            ctx->d_itw, ctx->d_itwp, ctx->d_ninv, ctx->d_ninvp, n, n2);
     }
+}
+void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mod_idx, int limbs,
+                     bool inverse, hipStream_t st) {
+    launch_ntt_src(ctx, data, d_rows, nullptr, nullptr, d_mod_idx, limbs, inverse, st);
 }
 
 void launch_ntt(cm_ctx *ctx, u64 *data, const int *d_mod_idx, int limbs, bool inverse,

@@ -41,7 +41,24 @@ struct KsLevelFull : KsLevel {
     int *d_q_mods3 = nullptr;   // 0..level repeated three times
     int *d_last_mods = nullptr; // level, level, level
     int *d_red_mods = nullptr;  // 0..level-1 repeated three times
+    int *d_last_rows[4] = {nullptr, nullptr, nullptr, nullptr};   // [ncomp]: rows c*(level+1)+level of a ciphertext
+    ConvDev *d_modup = nullptr; // one table per digit
+    ConvDev *d_moddown = nullptr;
+    int modup_max_nt = 0;
 };
+
+static ConvDev conv_dev(const ConvTable &t, const std::vector<int> &in_rows, const std::vector<int> &out_rows) {
+    ConvDev d;
+    memset(&d, 0, sizeof(d));
+    d.ns = t.ns, d.nt = t.nt;
+    for (int m = 0; m < t.ns; m++) {
+        d.src_mod[m] = t.src[m], d.in_rows[m] = in_rows[m];
+        d.inv_hat[m] = t.inv_hat[m], d.inv_hat_sh[m] = t.inv_hat_sh[m];
+    }
+    for (int r = 0; r < t.nt; r++) d.dst_mod[r] = t.dst[r], d.out_rows[r] = out_rows[r];
+    for (size_t i = 0; i < t.hat_mont.size(); i++) d.hat_mont[i] = t.hat_mont[i];
+    return d;
+}
 static std::map<std::pair<cm_ctx *, int>, KsLevelFull> g_ks;
 
 static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
@@ -55,6 +72,7 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
     k.beta = (int)digs.size();
     const auto &tabs = get_modup(ctx, level);
     std::vector<int> ntt_rows, ntt_mods;
+    std::vector<ConvDev> mu;
     for (int j = 0; j < k.beta; j++) {
         std::vector<int> out_rows;
         for (int idx : tabs[j].dst) {
@@ -63,9 +81,10 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
             ntt_rows.push_back(j * k.ext + row);
             ntt_mods.push_back(idx);
         }
-        k.d_out_rows.push_back(up(out_rows));
-        k.d_in_rows.push_back(up(digs[j]));
+        mu.push_back(conv_dev(tabs[j], digs[j], out_rows));
+        k.modup_max_nt = std::max(k.modup_max_nt, tabs[j].nt);
     }
+    k.d_modup = up(mu);
     k.d_ntt_rows = up(ntt_rows);
     k.d_ntt_mods = up(ntt_mods);
     k.n_ntt = (int)ntt_rows.size();
@@ -87,7 +106,17 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
     k.d_q_mods3 = up(q3);
     k.d_last_mods = up(last);
     k.d_red_mods = up(red);
-    get_moddown(ctx, level);
+    for (int nc = 1; nc <= 3; nc++) {
+        std::vector<int> lr;
+        for (int c = 0; c < nc; c++) lr.push_back(c * (level + 1) + level);
+        k.d_last_rows[nc] = up(lr);
+    }
+    {
+        std::vector<int> sp_in;
+        for (int s = 0; s < ctx->K; s++) sp_in.push_back(level + 1 + s);
+        std::vector<ConvDev> md(1, conv_dev(get_moddown(ctx, level), sp_in, q_rows));
+        k.d_moddown = up(md);
+    }
     get_pinv(ctx, level);
     get_qlinv(ctx, level);
     return g_ks[key] = k;
@@ -98,8 +127,8 @@ static void drop_ks_levels(cm_ctx *ctx) {
     for (auto it = g_ks.begin(); it != g_ks.end();) {
         if (it->first.first != ctx) { ++it; continue; }
         KsLevelFull &k = it->second;
-        for (int *p : k.d_out_rows) hipFree(p);
-        for (int *p : k.d_in_rows) hipFree(p);
+        hipFree(k.d_modup); hipFree(k.d_moddown);
+        for (int *p : k.d_last_rows) hipFree(p);
         hipFree(k.d_ntt_rows); hipFree(k.d_ntt_mods); hipFree(k.d_sp_rows); hipFree(k.d_sp_mods);
         hipFree(k.d_q_rows); hipFree(k.d_q_mods3); hipFree(k.d_last_mods); hipFree(k.d_red_mods);
         it = g_ks.erase(it);
@@ -116,19 +145,12 @@ static bool same_scale(double a, double b) { return fabs(a / b - 1.0) < 1e-9; }
 // ---- hybrid key switching -------------------------------------------------------------------------
 cm_status ks_raise(cm_ctx *ctx, const u64 *d, int level, u64 *digits, hipStream_t st) {
     const KsLevelFull &k = ks_level_full(ctx, level);
-    const auto &tabs = get_modup(ctx, level);
     Arena A = arena_of(ctx);
     const size_t n = ctx->n;
-    HIPCHK(hipMemcpyAsync(A.ksin, d, (size_t)(level + 1) * n * 8, hipMemcpyDeviceToDevice, st));
-    launch_ntt(ctx, A.ksin, iota_idx(ctx), level + 1, true, st);
-    auto digs = digits_at(ctx, level);
-    for (int j = 0; j < k.beta; j++) {
-        u64 *dj = digits + (size_t)j * k.ext * n;
-        launch_base_conv(ctx, tabs[j], dj, k.d_out_rows[j], A.ksin, k.d_in_rows[j], 1, 0, 0, st);
-        // the digit's own limbs are the input's, already in the evaluation domain
-        HIPCHK(hipMemcpyAsync(dj + (size_t)digs[j].front() * n, d + (size_t)digs[j].front() * n,
-                              digs[j].size() * n * 8, hipMemcpyDeviceToDevice, st));
-    }
+    // coefficient-domain copy of d (out of place), then all digits in one conversion launch; a
+    // digit's own limbs are copied from d itself, which is already in the evaluation domain
+    launch_ntt_src(ctx, A.ksin, nullptr, d, nullptr, iota_idx(ctx), level + 1, true, st);
+    launch_base_conv(ctx, k.d_modup, k.beta, 1, k.modup_max_nt, digits, A.ksin, 0, (size_t)k.ext * n, d, st);
     launch_ntt_rows(ctx, digits, k.d_ntt_rows, k.d_ntt_mods, k.n_ntt, false, st);
     return CM_OK;
 }
@@ -141,8 +163,7 @@ cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u6
     u64 *u0 = A.u, *u1 = A.u + (size_t)k.ext * n;
     launch_inner_product(ctx, u0, u1, digits, evk, k.beta, level, g, st);
     launch_ntt_rows(ctx, A.u, k.d_sp_rows, k.d_sp_mods, 2 * ctx->K, true, st);
-    const ConvTable &md = get_moddown(ctx, level);
-    launch_base_conv(ctx, md, A.conv, k.d_q_rows, A.u, k.d_sp_rows, 2, (size_t)k.ext * n, (size_t)(level + 1) * n, st);
+    launch_base_conv(ctx, k.d_moddown, 2, 0, level + 1, A.conv, A.u, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr, st);
     launch_ntt(ctx, A.conv, k.d_q_mods3, 2 * (level + 1), false, st);
     launch_moddown_finish(ctx, out, A.u, A.conv, get_pinv(ctx, level), addend, addend_comps, level, addend ? g : 0, st);
     return CM_OK;
@@ -460,9 +481,7 @@ cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *ou
     const KsLevelFull &k = ks_level_full(ctx, level);
     Arena A = arena_of(ctx);
     const size_t n = ctx->n;
-    for (int c = 0; c < ncomp; c++)
-        HIPCHK(hipMemcpyAsync(A.misc + c * n, in + ((size_t)c * (level + 1) + level) * n, n * 8, hipMemcpyDeviceToDevice, st));
-    launch_ntt(ctx, A.misc, k.d_last_mods, ncomp, true, st);
+    launch_ntt_src(ctx, A.misc, nullptr, in, k.d_last_rows[ncomp], k.d_last_mods, ncomp, true, st);
     u64 *red = A.tmp[2];
     launch_rescale_reduce(ctx, red, A.misc, ncomp, level, st);
     launch_ntt(ctx, red, k.d_red_mods, ncomp * level, false, st);

@@ -1,0 +1,69 @@
+"""Writes tests/golden/vmm_full_size.txt by running ONLY the oracle.
+
+Full-size parity case of the packed product: ring n = 2^16 with 24 x 50-bit + 4 x 60-bit primes
+(benchmark configuration 2), d = 4096 square plan (32 baby x 16 giant steps, 52 rotations, 512
+plaintext multiply-accumulates), top level.  Plaintexts enter as integer coefficient polynomials
+drawn from a seeded integer generator (ciphertext-level parity does not care what they encode,
+and integers cross between machines bit for bit, which encoded floats need not).
+
+The fixture stores a SHA-256 of the canonical output ciphertext and the first coefficients of
+every limb.  Run from the repository root:  python tests/golden/make_vmm_full_size_golden.py
+(about ten minutes on 8 cores, ~20 GiB of memory).
+"""
+import hashlib
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+
+from oracle import ckks, packing, params, vmm  # noqa: E402
+
+SEED_X, SEED_W, SEED_SK, SEED_EVK, SEED_ENC = 11, 12, 1, 2, 3
+D = 4096
+
+
+def integer_inputs(n, plan):
+    """x plaintext: uniform integers below 2^48 in magnitude; diagonal (j, k): below 2^44."""
+    xc = np.random.default_rng(SEED_X).integers(-2 ** 48, 2 ** 48, n, dtype=np.int64)
+    rng = np.random.default_rng(SEED_W)
+    diag = [rng.integers(-2 ** 44, 2 ** 44, n, dtype=np.int64) for _ in range(plan.r_i * plan.r_o)]
+    return xc, diag
+
+
+def main():
+    t0 = time.time()
+    prm = params.config2()
+    ctx = ckks.Context(prm)
+    plan = packing.make_plan(ctx.S, D, D)
+    xc, diag = integer_inputs(ctx.n, plan)
+    sk = ctx.keygen_secret(SEED_SK)
+    keys = ctx.keygen_rotations(sk, plan.all_steps(), SEED_EVK)
+    print("keys", len(keys), time.time() - t0, flush=True)
+    ct = ctx.encrypt(sk, ctx.pt_from_coeffs(xc, prm.L, prm.scale), SEED_ENC)
+    pts = [[ctx.pt_from_coeffs(diag[j * plan.r_o + k], prm.L, prm.scale) for k in range(plan.r_o)]
+           for j in range(plan.r_i)]
+    print("plaintexts", time.time() - t0, flush=True)
+    y = vmm.vmm_pt(vmm.CkksOps(ctx, keys), plan, ct, pts)
+    can = ctx.canonical(y)
+    print("vmm", time.time() - t0, ctx.rot_count, ctx.ptmul_count, flush=True)
+    out = os.path.join(ROOT, "tests", "golden", "vmm_full_size.txt")
+    with open(out, "w") as f:
+        f.write("# Oracle output of the full-size packed product (Algorithm 1 of App. C at the Table 2 shape\n"
+                "# (S, d) = (32768, 4096)) on integer plaintexts; written by make_vmm_full_size_golden.py.\n")
+        f.write(f"shape: {' '.join(map(str, can.shape))}\n")
+        f.write(f"level: {y.level}\n")
+        f.write(f"rotations: {ctx.rot_count}\n")
+        f.write(f"pt_mults: {ctx.ptmul_count}\n")
+        f.write(f"sha256: {hashlib.sha256(can.tobytes()).hexdigest()}\n")
+        for c in range(can.shape[0]):
+            for l in range(can.shape[1]):
+                f.write(f"head_{c}_{l}: {' '.join(str(int(v)) for v in can[c, l, :4])}\n")
+    print("wrote", out, time.time() - t0)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,136 @@
+"""GPU parity at the benchmark's full sizes (ring n = 2^16), in the launch configuration bench.py
+times: single operations element by element against the oracle, the full 4096x4096 packed
+product against a stored oracle result, and the decrypted product against float64."""
+import hashlib
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def _llama(n_q, n_p):
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from oracle import ckks, params
+    from paper_2602_11470_amd import binding as B
+    prm = params.llama_ring(n_q, n_p)
+    return B, ckks.Context(prm), B.llama_ring(n_q, n_p), prm
+
+
+@pytest.fixture(scope="module")
+def ring2():
+    B, octx, gctx, prm = _llama(24, 4)
+    yield B, octx, gctx, prm
+    gctx.close()
+
+
+def _pair(octx, gctx, osk, gsk, coeffs, level, seed):
+    scale = octx.prm.scale
+    o = octx.encrypt(osk, octx.pt_from_coeffs(coeffs, level, scale), seed)
+    g = gctx.encrypt(gsk, gctx.pt_from_coeffs(coeffs, level, scale), seed)
+    return o, g
+
+
+def test_config2_chain_keys_and_single_operations(ring2):
+    B, octx, gctx, prm = ring2
+    assert gctx.moduli().tolist() == prm.moduli
+    osk, gsk = octx.keygen_secret(1), gctx.keygen_secret(1)
+    assert np.array_equal(gsk.coeffs().astype(np.int64), osk["coeffs"])
+    assert int((osk["coeffs"] != 0).sum()) == 192
+    steps = [7, 2048]
+    okeys = octx.keygen_rotations(osk, steps, 2, with_relin=True)
+    gkeys = gctx.keygen_rotations(gsk, steps, 2, with_relin=True)
+    all_idx = list(range(len(octx.mod)))
+    g7 = octx.galois(7)
+    assert np.array_equal(gkeys.export(7, False, 5, 0), octx.intt(okeys[g7].b[5], all_idx))
+    assert np.array_equal(gkeys.export(7, False, 0, 1), octx.intt(okeys[g7].a[0], all_idx))
+    rng = np.random.default_rng(0)
+    z = rng.normal(size=octx.S)
+    coeffs = octx.encode_coeffs(z, prm.scale)
+    o, g = _pair(octx, gctx, osk, gsk, coeffs, prm.L, 3)
+    assert np.array_equal(gctx.ct_export(g), octx.canonical(o))
+    # full key switch at the top level (24 limbs, 6 digits of 4 primes, 4 special primes)
+    orot, grot = octx.rotate(o, 7, okeys), gctx.rotate(gkeys, g, 7)
+    assert np.array_equal(gctx.ct_export(grot), octx.canonical(orot))
+    assert np.abs(gctx.decrypt(gsk, grot).real - np.roll(z, -7)).max() < 1e-6
+    # hoisted rotations
+    h = octx.hoist(o)
+    for s, gout in zip(steps, gctx.rotate_hoisted(gkeys, g, steps)):
+        assert np.array_equal(gctx.ct_export(gout), octx.canonical(octx.rotate_hoisted(o, h, s, okeys)))
+    # a partial last digit (level 4: digits of 4 + 1 primes), product, relinearisation, rescale
+    o4, g4 = octx.level_drop(o, 4), gctx.level_drop(g, 4)
+    assert np.array_equal(gctx.ct_export(gctx.rotate(gkeys, g4, 2048)), octx.canonical(octx.rotate(o4, 2048, okeys)))
+    om = octx.rescale(octx.relinearize(octx.mul_ct(o4, o4), okeys))
+    gm = gctx.rescale(gctx.relinearize(gkeys, gctx.mul_ct(g4, g4)))
+    assert np.array_equal(gctx.ct_export(gm), octx.canonical(om))
+    assert np.abs(gctx.decrypt(gsk, gm).real - z * z).max() < 1e-6
+
+
+def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden):
+    """52 rotations, 512 plaintext multiply-accumulates at (S, d) = (32768, 4096); the expected
+    ciphertext was written by tests/golden/make_vmm_full_size_golden.py from the oracle."""
+    import importlib.util
+    import os
+    B, octx, gctx, prm = ring2
+    g = golden("vmm_full_size.txt")
+    spec = importlib.util.spec_from_file_location(
+        "mk", os.path.join(os.path.dirname(__file__), "golden", "make_vmm_full_size_golden.py"))
+    mk = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mk)
+    from oracle import packing
+    plan = packing.make_plan(octx.S, mk.D, mk.D)
+    xc, diag = mk.integer_inputs(octx.n, plan)
+    gplan = gctx.vmm_plan(mk.D, mk.D, level=prm.L, r_i=plan.r_i, coeffs=np.stack(diag), pt_scale=prm.scale)
+    assert gplan.n_rotations == int(g["rotations"]) == 52 and gplan.r_i * gplan.r_o == int(g["pt_mults"]) == 512
+    gsk = gctx.keygen_secret(mk.SEED_SK)
+    gkeys = gctx.keygen_rotations(gsk, gplan.steps(), mk.SEED_EVK)
+    gx = gctx.encrypt(gsk, gctx.pt_from_coeffs(xc, prm.L, prm.scale), mk.SEED_ENC)
+    gy = gctx.vmm_pt(gkeys, gplan, gx)
+    can = gctx.ct_export(gy)
+    assert list(can.shape) == [int(v) for v in g["shape"].split()] and gy.level == int(g["level"])
+    for c in range(can.shape[0]):
+        for l in range(can.shape[1]):
+            assert [int(v) for v in can[c, l, :4]] == [int(v) for v in g[f"head_{c}_{l}"].split()], (c, l)
+    assert hashlib.sha256(can.tobytes()).hexdigest() == g["sha256"]
+
+
+def test_config2_packed_product_decrypts_to_float64_product(ring2):
+    from paper_2602_11470_amd import inputs
+    B, octx, gctx, prm = ring2
+    d = 4096
+    x, W = inputs.vmm_inputs(1, d, d)
+    gplan = gctx.vmm_plan(d, d, W=W)
+    gsk = gctx.keygen_secret(1)
+    gkeys = gctx.keygen_rotations(gsk, gplan.steps(), 2)
+    t = gctx.S // d
+    slots = np.zeros(gctx.S)
+    slots[::t] = x
+    gy = gctx.vmm_pt(gkeys, gplan, gctx.encrypt(gsk, gctx.encode(slots, gctx.L), 3))
+    out = gctx.decrypt(gsk, gy)
+    assert np.abs(out.real[::t] - x @ W).max() < TOL
+    assert gy.level == gctx.L - 1
+    # the operating level of the paper's projections (level 4): two digits, the last one partial
+    gplan4 = gctx.vmm_plan(d, d, W=W, level=4)
+    gx4 = gctx.level_drop(gctx.encrypt(gsk, gctx.encode(slots, gctx.L), 3), 4)
+    out4 = gctx.decrypt(gsk, gctx.vmm_pt(gkeys, gplan4, gx4))
+    assert np.abs(out4.real[::t] - x @ W).max() < TOL
+
+
+def test_config5_ring_rotation(ring2):
+    """36 + 6 primes (6 digits of 6): one full key switch element by element."""
+    ring2[2].close()                                 # free the first context's device memory
+    B, octx, gctx, prm = _llama(36, 6)
+    try:
+        assert gctx.moduli().tolist() == prm.moduli
+        osk, gsk = octx.keygen_secret(4), gctx.keygen_secret(4)
+        okeys, gkeys = octx.keygen_rotations(osk, [256], 5), gctx.keygen_rotations(gsk, [256], 5)
+        z = np.random.default_rng(1).normal(size=octx.S)
+        o, g = _pair(octx, gctx, osk, gsk, octx.encode_coeffs(z, prm.scale), prm.L, 6)
+        orot, grot = octx.rotate(o, 256, okeys), gctx.rotate(gkeys, g, 256)
+        assert np.array_equal(gctx.ct_export(grot), octx.canonical(orot))
+        assert np.abs(gctx.decrypt(gsk, grot).real - np.roll(z, -256)).max() < 1e-6
+    finally:
+        gctx.close()
