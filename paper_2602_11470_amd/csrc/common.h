@@ -58,6 +58,7 @@ __device__ __forceinline__ u64 submod(u64 a, u64 b, u64 q) { return a >= b ? a -
 #define CM_MAX_LIMBS 64
 #define CM_MAX_DIGITS 16
 #define CM_GAUSS_K 19
+#define CM_KS_BATCH 8      // hoisted rotations whose ModDown runs as one batch
 
 struct ConvTable {            // fast base conversion src -> dst (all indices into the modulus list)
     int ns = 0, nt = 0;

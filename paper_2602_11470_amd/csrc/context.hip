@@ -326,7 +326,8 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
     const int ext = ctx->L + 1 + ctx->K;
     const int beta = (ctx->L + ctx->alpha) / ctx->alpha;
     size_t limbs = (size_t)(ctx->L + 1) + (size_t)beta * ext + 2 * (size_t)ext + 2 * (size_t)(ctx->L + 1) +
-                   9 * (size_t)(ctx->L + 1) + 4;
+                   9 * (size_t)(ctx->L + 1) + 4 +
+                   (size_t)CM_KS_BATCH * 2 * (ext + ctx->L + 1);      // batched ModDown of hoisted rotations
     ctx->arena_words = limbs * n;
     if (hipMalloc((void **)&ctx->arena, ctx->arena_words * sizeof(u64)) != hipSuccess) ctx->arena = nullptr;
     if (!ctx->d_modc || !ctx->d_tw || !ctx->d_twp || !ctx->d_itw || !ctx->d_itwp || !ctx->d_ninv ||

@@ -46,6 +46,8 @@ cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u6
 cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64 g, u64 *out, hipStream_t st);
 cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st);
 u64 *arena_digits(const cm_ctx *ctx);
+cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys, const u64 *gs,
+                        const u64 *in, u64 *const *outs, hipStream_t st);
 const u64 *find_key(const cm_evk *evk, u64 g);
 void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mods, int limbs, bool inverse, hipStream_t st);
 void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, const int *d_src_rows,

@@ -247,9 +247,15 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     HIPCHK(hipMemcpyAsync(babies, in->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
     if (kv->r_i > 1) {
         CMCHK(ks_raise(ctx, babies + ln, lv, digits, st));
-        for (int j = 1; j < kv->r_i; j++)
-            CMCHK(ks_apply(ctx, digits, find_key(evk, rot_g(kv, j * Ht)), lv, rot_g(kv, j * Ht), babies, 1,
-                           babies + (size_t)j * ctw, st));
+        std::vector<const u64 *> keys;
+        std::vector<u64> gs;
+        std::vector<u64 *> dst;
+        for (int j = 1; j < kv->r_i; j++) {
+            keys.push_back(find_key(evk, rot_g(kv, j * Ht)));
+            gs.push_back(rot_g(kv, j * Ht));
+            dst.push_back(babies + (size_t)j * ctw);
+        }
+        CMCHK(ks_apply_many(ctx, digits, lv, kv->r_i - 1, keys.data(), gs.data(), babies, dst.data(), st));
     }
     for (int g = 0; g < kv->r_o; g++) {
         for (int j = 0; j < kv->r_i; j++)

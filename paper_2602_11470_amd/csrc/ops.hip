@@ -12,7 +12,7 @@ static inline u64 stream_id(u64 purpose, u64 ident, u64 digit, u64 limb) {
 
 // ---- arena ------------------------------------------------------------------------------------
 struct Arena {
-    u64 *ksin, *digits, *u, *conv, *tmp[3], *misc;
+    u64 *ksin, *digits, *u, *conv, *tmp[3], *misc, *bu, *bconv;
 };
 static Arena arena_of(const cm_ctx *ctx) {
     const size_t n = ctx->n, q = ctx->L + 1, ext = ctx->L + 1 + ctx->K;
@@ -24,7 +24,9 @@ static Arena arena_of(const cm_ctx *ctx) {
     a.u = p, p += 2 * ext * n;
     a.conv = p, p += 2 * q * n;
     for (int i = 0; i < 3; i++) a.tmp[i] = p, p += 3 * q * n;
-    a.misc = p;
+    a.misc = p, p += 4 * n;
+    a.bu = p, p += (size_t)CM_KS_BATCH * 2 * ext * n;
+    a.bconv = p;
     return a;
 }
 
@@ -42,6 +44,8 @@ struct KsLevelFull : KsLevel {
     int *d_last_mods = nullptr; // level, level, level
     int *d_red_mods = nullptr;  // 0..level-1 repeated three times
     int *d_last_rows[4] = {nullptr, nullptr, nullptr, nullptr};   // [ncomp]: rows c*(level+1)+level of a ciphertext
+    int *d_bsp_rows = nullptr, *d_bsp_mods = nullptr;   // special rows of CM_KS_BATCH stacked [2][ext] blocks
+    int *d_bq_mods = nullptr;                           // 0..level repeated 2*CM_KS_BATCH times
     ConvDev *d_modup = nullptr; // one table per digit
     ConvDev *d_moddown = nullptr;
     int modup_max_nt = 0;
@@ -106,6 +110,18 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
     k.d_q_mods3 = up(q3);
     k.d_last_mods = up(last);
     k.d_red_mods = up(red);
+    {
+        std::vector<int> br, bm, bq;
+        for (int r = 0; r < CM_KS_BATCH; r++)
+            for (int c = 0; c < 2; c++) {
+                for (int sp = 0; sp < ctx->K; sp++) {
+                    br.push_back((r * 2 + c) * k.ext + level + 1 + sp);
+                    bm.push_back(ctx->L + 1 + sp);
+                }
+                for (int i = 0; i <= level; i++) bq.push_back(i);
+            }
+        k.d_bsp_rows = up(br), k.d_bsp_mods = up(bm), k.d_bq_mods = up(bq);
+    }
     for (int nc = 1; nc <= 3; nc++) {
         std::vector<int> lr;
         for (int c = 0; c < nc; c++) lr.push_back(c * (level + 1) + level);
@@ -127,7 +143,7 @@ static void drop_ks_levels(cm_ctx *ctx) {
     for (auto it = g_ks.begin(); it != g_ks.end();) {
         if (it->first.first != ctx) { ++it; continue; }
         KsLevelFull &k = it->second;
-        hipFree(k.d_modup); hipFree(k.d_moddown);
+        hipFree(k.d_modup); hipFree(k.d_moddown); hipFree(k.d_bsp_rows); hipFree(k.d_bsp_mods); hipFree(k.d_bq_mods);
         for (int *p : k.d_last_rows) hipFree(p);
         hipFree(k.d_ntt_rows); hipFree(k.d_ntt_mods); hipFree(k.d_sp_rows); hipFree(k.d_sp_mods);
         hipFree(k.d_q_rows); hipFree(k.d_q_mods3); hipFree(k.d_last_mods); hipFree(k.d_red_mods);
@@ -169,6 +185,30 @@ cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u6
     return CM_OK;
 }
 u64 *arena_digits(const cm_ctx *ctx) { return arena_of(ctx).digits; }
+
+// cnt hoisted rotations of one ciphertext `in` ([2][level+1][n]) whose raised digits are given:
+// outs[r] = ModDown(sum_j perm_{g_r}(digits_j) * key_r) + perm_{g_r}(in.c0).  The ModDown of up to
+// CM_KS_BATCH rotations runs as one batch so that its transforms and conversions fill the machine.
+cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys, const u64 *gs,
+                        const u64 *in, u64 *const *outs, hipStream_t st) {
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    Arena A = arena_of(ctx);
+    const size_t n = ctx->n, ublk = 2 * (size_t)k.ext * n, cblk = 2 * (size_t)(level + 1) * n;
+    for (int base = 0; base < cnt; base += CM_KS_BATCH) {
+        const int m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
+        for (int r = 0; r < m; r++)
+            launch_inner_product(ctx, A.bu + r * ublk, A.bu + r * ublk + (size_t)k.ext * n, digits, keys[base + r],
+                                 k.beta, level, gs[base + r], st);
+        launch_ntt_rows(ctx, A.bu, k.d_bsp_rows, k.d_bsp_mods, m * 2 * ctx->K, true, st);
+        launch_base_conv(ctx, k.d_moddown, 2 * m, 0, level + 1, A.bconv, A.bu, (size_t)k.ext * n,
+                         (size_t)(level + 1) * n, nullptr, st);
+        launch_ntt(ctx, A.bconv, k.d_bq_mods, m * 2 * (level + 1), false, st);
+        for (int r = 0; r < m; r++)
+            launch_moddown_finish(ctx, outs[base + r], A.bu + r * ublk, A.bconv + r * cblk, get_pinv(ctx, level), in, 1,
+                                  level, gs[base + r], st);
+    }
+    return CM_OK;
+}
 
 const u64 *find_key(const cm_evk *evk, u64 g) {
     auto it = evk->keys.find(g);
@@ -550,13 +590,18 @@ extern "C" cm_status cm_rotate_hoisted(cm_ctx *ctx, const cm_evk *evk, const cm_
     Arena A = arena_of(ctx);
     const size_t ln = (size_t)(in->level + 1) * ctx->n;
     CMCHK(ks_raise(ctx, in->dev + ln, in->level, A.digits, st));
+    std::vector<const u64 *> keys;
+    std::vector<u64> gs;
+    std::vector<u64 *> dst;
     for (size_t i = 0; i < nsteps; i++) {
         u64 g = galois_of_step(ctx, steps[i]);
-        if (g == 1)
+        if (g == 1) {
             HIPCHK(hipMemcpyAsync(outs[i].dev, in->dev, 2 * ln * 8, hipMemcpyDeviceToDevice, st));
-        else
-            CMCHK(ks_apply(ctx, A.digits, find_key(evk, g), in->level, g, in->dev, 1, outs[i].dev, st));
+        } else {
+            keys.push_back(find_key(evk, g)), gs.push_back(g), dst.push_back(outs[i].dev);
+        }
         outs[i].level = in->level, outs[i].ncomp = 2, outs[i].scale = in->scale;
     }
+    CMCHK(ks_apply_many(ctx, A.digits, in->level, (int)keys.size(), keys.data(), gs.data(), in->dev, dst.data(), st));
     return CM_OK;
 }

@@ -211,9 +211,15 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     if (p->r_i > 1) {
         u64 *digits = arena_digits(ctx);
         CMCHK(ks_raise(ctx, c + ptw, level, digits, st));
-        for (int j = 1; j < p->r_i; j++)
-            CMCHK(ks_apply(ctx, digits, key_of(p->baby_steps[j]), level, galois_of_step(ctx, p->baby_steps[j]), c, 1,
-                           babies + (size_t)j * ctw, st));
+        std::vector<const u64 *> keys;
+        std::vector<u64> gs;
+        std::vector<u64 *> dst;
+        for (int j = 1; j < p->r_i; j++) {
+            keys.push_back(key_of(p->baby_steps[j]));
+            gs.push_back(galois_of_step(ctx, p->baby_steps[j]));
+            dst.push_back(babies + (size_t)j * ctw);
+        }
+        CMCHK(ks_apply_many(ctx, digits, level, p->r_i - 1, keys.data(), gs.data(), c, dst.data(), st));
     }
     //    multiply-accumulate: inner_k = sum_j baby_j * p_{j,k}
     launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, p->r_o, limbs, ctw, ptw, st);
