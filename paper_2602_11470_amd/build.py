@@ -10,6 +10,8 @@ OUT = os.path.join(HERE, "libcachemir.so")
 BUILD = os.path.join(HERE, "_build")
 SOURCES = ["context.hip", "ntt.hip", "kernels.hip", "ops.hip", "vmm.hip", "kv.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wno-unused-result",
+         # the FP64 butterflies rely on exact products: no fused contraction the source does not spell
+         "-ffp-contract=off",
          # packed-FP32 instruction forms are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -54,6 +54,11 @@ __device__ __forceinline__ u64 addmod(u64 a, u64 b, u64 q) {
 }
 __device__ __forceinline__ u64 submod(u64 a, u64 b, u64 q) { return a >= b ? a - b : a + q - b; }
 
+// modulus as doubles for the FP64 butterflies (moduli below 2^50 only; q = 0 otherwise)
+struct FpQ {
+    double q, qinv;
+};
+
 // ---- context -----------------------------------------------------------------------------
 #define CM_MAX_LIMBS 64
 #define CM_MAX_DIGITS 16
@@ -98,6 +103,10 @@ struct cm_ctx {
     u64 *d_tw = nullptr, *d_twp = nullptr;      // forward twiddles psi^brev(i) and companions [nmod][n]
     u64 *d_itw = nullptr, *d_itwp = nullptr;    // inverse
     u64 *d_ninv = nullptr, *d_ninvp = nullptr;  // n^{-1} [nmod]
+    // the same tables as doubles (w and w/q) for the limbs whose modulus is below 2^50
+    FpQ *d_fpq = nullptr;                       // [nmod] (q, 1/q), q = 0 for larger moduli
+    double *d_twd = nullptr, *d_twqd = nullptr, *d_itwd = nullptr, *d_itwqd = nullptr;
+    double *d_ninvd = nullptr, *d_ninvqd = nullptr;
     std::vector<ModC> modc;
     // per-level tables (built lazily, kept): ModUp per digit, ModDown, rescale constants
     std::map<int, std::vector<ConvTable>> modup;   // level -> digit tables

@@ -1,6 +1,7 @@
 // Host side of the context: prime chain, roots of unity, NTT twiddle tables, base-conversion
 // tables, Montgomery constants, the canonical-embedding FFT used by encode/decode.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <complex>
@@ -315,6 +316,29 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
     ctx->d_itwp = upload(itwp);
     ctx->d_ninv = upload(ninv);
     ctx->d_ninvp = upload(ninvp);
+    {
+        // double-precision copies for the FP64 butterflies: w and the correctly rounded w/q
+        std::vector<double> twd(tw.size(), 0.0), twqd(tw.size(), 0.0), itwd(tw.size(), 0.0), itwqd(tw.size(), 0.0);
+        std::vector<double> nd(ctx->nmod, 0.0), nqd(ctx->nmod, 0.0);
+        std::vector<FpQ> fpq(ctx->nmod);
+        for (int m = 0; m < ctx->nmod; m++) {
+            const u64 q = ctx->mod[m];
+            const bool fp = q < (1ULL << 50) && !getenv("CM_NTT_INT");
+            fpq[m].q = fp ? (double)q : 0.0;
+            fpq[m].qinv = fp ? 1.0 / (double)q : 0.0;
+            if (!fp) continue;
+            for (int i = 0; i < n; i++) {
+                size_t o = (size_t)m * n + i;
+                twd[o] = (double)tw[o], twqd[o] = (double)tw[o] / (double)q;
+                itwd[o] = (double)itw[o], itwqd[o] = (double)itw[o] / (double)q;
+            }
+            nd[m] = (double)ninv[m], nqd[m] = (double)ninv[m] / (double)q;
+        }
+        ctx->d_fpq = upload(fpq);
+        ctx->d_twd = upload(twd), ctx->d_twqd = upload(twqd);
+        ctx->d_itwd = upload(itwd), ctx->d_itwqd = upload(itwqd);
+        ctx->d_ninvd = upload(nd), ctx->d_ninvqd = upload(nqd);
+    }
     std::vector<int> iota(2 * CM_MAX_LIMBS);
     for (int i = 0; i < 2 * CM_MAX_LIMBS; i++) iota[i] = i;
     ctx->d_idx = upload(iota);
@@ -364,6 +388,8 @@ extern "C" void cm_ctx_destroy(cm_ctx *ctx) {
     hipFree(ctx->d_itwp);
     hipFree(ctx->d_ninv);
     hipFree(ctx->d_ninvp);
+    hipFree(ctx->d_fpq), hipFree(ctx->d_twd), hipFree(ctx->d_twqd), hipFree(ctx->d_itwd), hipFree(ctx->d_itwqd);
+    hipFree(ctx->d_ninvd), hipFree(ctx->d_ninvqd);
     hipFree(ctx->d_idx);
     hipFree(ctx->d_cdt);
     hipFree(ctx->arena);

@@ -1,5 +1,7 @@
 // Element-wise, base-conversion, key-switch and sampling kernels of libcachemir (gfx950).
 // Polynomials are [limbs][n] 64-bit words.  "mont" operands are pre-multiplied by 2^64 mod q.
+#include <stdlib.h>
+
 #include "kernels.h"
 
 #define TPB 256
@@ -124,7 +126,7 @@ void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, 
 // the table).  blockIdx.y = group of CONV_TG targets; the cheap y_m are recomputed per group so
 // that a conversion fills the machine.  If own_src is given, group 0 also copies the source rows
 // of own_src (the evaluation-domain input) to the same rows of the output.
-#define CONV_TG 4
+template <int CONV_TG>
 __global__ void k_base_conv(u64 *out, const u64 *in, const ConvDev *tabs, int tab_step, const ModC *modc, int n,
                             size_t in_stride, size_t out_stride, const u64 *own_src) {
     const int i = blockIdx.x * TPB + threadIdx.x;
@@ -160,8 +162,15 @@ __global__ void k_base_conv(u64 *out, const u64 *in, const ConvDev *tabs, int ta
 void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_step, int max_nt, u64 *out, const u64 *in,
                       size_t in_stride, size_t out_stride, const u64 *own_src, hipStream_t st) {
     Prof prof_(ctx, CM_K_BASE_CONV, batch * max_nt, st);
-    hipLaunchKernelGGL(k_base_conv, dim3(ctx->n / TPB, (max_nt + CONV_TG - 1) / CONV_TG, batch), dim3(TPB), 0, st, out, in,
-                       d_tabs, tab_step, ctx->d_modc, ctx->n, in_stride, out_stride, own_src);
+    static int tg = getenv("CM_CONV_TG") ? atoi(getenv("CM_CONV_TG")) : 8;
+#define CONV_LAUNCH(TG)                                                                                              \
+    hipLaunchKernelGGL(k_base_conv<TG>, dim3(ctx->n / TPB, (max_nt + TG - 1) / TG, batch), dim3(TPB), 0, st, out, in, \
+                       d_tabs, tab_step, ctx->d_modc, ctx->n, in_stride, out_stride, own_src)
+    if (tg == 2) CONV_LAUNCH(2);
+    else if (tg == 8) CONV_LAUNCH(8);
+    else if (tg == 12) CONV_LAUNCH(12);
+    else if (tg == 24) CONV_LAUNCH(24);
+    else CONV_LAUNCH(4);
 }
 
 // ---- evaluation-key inner product ------------------------------------------------------------------
@@ -354,31 +363,38 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 // (j*r_o + k)*pt_stride, multiplier form; out: r_o ciphertexts at stride baby_stride.
 // A lane keeps its coefficient of all baby ciphertexts of a chunk in registers and streams the
 // plaintexts once; products are summed in 128 bits and reduced once per chunk.
-#define MAC_CHUNK 8
-__global__ void k_vmm_mac(u64 *out, const u64 *babies, const u64 *pts, const ModC *modc, int r_i, int r_o, int limbs,
-                          int n, size_t ct_stride, size_t pt_stride) {
+// RC baby ciphertexts are register-resident per pass (one pass when r_i <= RC, so every output is
+// written exactly once); products are summed 8 at a time in 128 bits before each REDC.
+template <int RC>
+__global__ __launch_bounds__(TPB) void k_vmm_mac(u64 *out, const u64 *babies, const u64 *pts, const ModC *modc, int r_i,
+                                                 int r_o, int limbs, int n, size_t ct_stride, size_t pt_stride) {
     int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
     const ModC m = modc[l];
     size_t o = (size_t)l * n + i, cs = (size_t)limbs * n;
-    for (int j0 = 0; j0 < r_i; j0 += MAC_CHUNK) {
-        u64 c0[MAC_CHUNK], c1[MAC_CHUNK];
+    for (int j0 = 0; j0 < r_i; j0 += RC) {
+        u64 c0[RC], c1[RC];
 #pragma unroll
-        for (int jj = 0; jj < MAC_CHUNK; jj++) {
+        for (int jj = 0; jj < RC; jj++) {
             bool ok = j0 + jj < r_i;
             c0[jj] = ok ? babies[(size_t)(j0 + jj) * ct_stride + o] : 0;
             c1[jj] = ok ? babies[(size_t)(j0 + jj) * ct_stride + cs + o] : 0;
         }
         for (int k = 0; k < r_o; k++) {
-            u128 s0 = 0, s1 = 0;
+            u64 v0 = 0, v1 = 0;
 #pragma unroll
-            for (int jj = 0; jj < MAC_CHUNK; jj++) {
-                if (j0 + jj < r_i) {
-                    u64 p = pts[((size_t)(j0 + jj) * r_o + k) * pt_stride + o];
-                    s0 += (u128)c0[jj] * p;
-                    s1 += (u128)c1[jj] * p;
+            for (int s8 = 0; s8 < RC; s8 += 8) {
+                u128 s0 = 0, s1 = 0;
+#pragma unroll
+                for (int jj = s8; jj < s8 + 8; jj++) {
+                    if (j0 + jj < r_i) {
+                        u64 p = pts[((size_t)(j0 + jj) * r_o + k) * pt_stride + o];
+                        s0 += (u128)c0[jj] * p;
+                        s1 += (u128)c1[jj] * p;
+                    }
                 }
+                v0 = addmod(v0, redc(s0, m.q, m.qinv), m.q);
+                v1 = addmod(v1, redc(s1, m.q, m.qinv), m.q);
             }
-            u64 v0 = redc(s0, m.q, m.qinv), v1 = redc(s1, m.q, m.qinv);
             u64 *dst = out + (size_t)k * ct_stride + o;
             if (j0) {
                 v0 = addmod(v0, dst[0], m.q);
@@ -391,6 +407,12 @@ __global__ void k_vmm_mac(u64 *out, const u64 *babies, const u64 *pts, const Mod
 }
 void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, hipStream_t st) {
     Prof prof_(ctx, CM_K_VMM_MAC, r_i * r_o, st);
-    hipLaunchKernelGGL(k_vmm_mac, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs,
-                       ctx->n, ct_stride, pt_stride);
+    dim3 grid(ctx->n / TPB, limbs), block(TPB);
+    static int rc = getenv("CM_MAC_RC") ? atoi(getenv("CM_MAC_RC")) : 8;
+    if (r_i > 16 && rc >= 32)
+        hipLaunchKernelGGL(k_vmm_mac<32>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride);
+    else if (r_i > 8 && rc >= 16)
+        hipLaunchKernelGGL(k_vmm_mac<16>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride);
+    else
+        hipLaunchKernelGGL(k_vmm_mac<8>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride);
 }

@@ -1,8 +1,7 @@
 // Batched negacyclic NTT / inverse NTT over RNS limbs for gfx950.
 //
 // Transform: a(X) in Z_q[X]/(X^n+1)  ->  values a(psi^(2 brev(i)+1)) at position i (bit-reversed
-// evaluation order), the merged-twiddle Cooley-Tukey / Gentleman-Sande pair with Harvey's lazy
-// butterflies (operands kept below 4q forward, 2q inverse; Shoup twiddles).
+// evaluation order), the merged-twiddle Cooley-Tukey / Gentleman-Sande pair.
 //
 // Decomposition for the 64-wide machine: n = 256 * n2.  A workgroup of 256 lanes owns 4096
 // words; every lane keeps 16 of them in registers and runs four butterfly stages there
@@ -10,59 +9,139 @@
 //   column kernel : stages 0..7, a tile of 256 rows x 16 adjacent columns (rows n2 apart)
 //   row kernel    : the remaining log2(n2) stages on contiguous blocks of n2 words
 // so a limb makes two round trips to HBM for n = 65536 (and for n = 4096).
+//
+// Two butterfly arithmetics, chosen per limb (uniform per workgroup):
+//   IntArith : Harvey's lazy butterflies with Shoup twiddles on u64 (any modulus below 2^62);
+//              ~32 VALU instructions per butterfly on this machine.
+//   FpArith  : for moduli below 2^50, residues held as exact integers in doubles.  FP64 FMA
+//              issues at full rate here, and a modular product is 6 instructions:
+//                  h = y*w; l = fma(y, w, -h)            (exact product h + l)
+//                  c = rint(y * (w/q)); r = fma(-c, q, h) + l
+//              exact because |h - c q| < 2^53 whenever |y| <= 2.1 q; r = y w (mod q), |r| <= 1.04 q.
+//              Values stay signed and lazy (|v| <= 1.54 q), one 3-instruction renormalisation per
+//              butterfly; ~11 instructions per butterfly.  Between the two kernels of a
+//              transform the words in memory are raw doubles; at rest they are u64 in [0, q).
+// Both give bit-identical results (all steps are exact integer arithmetic).
 #include "kernels.h"
 
 #define NTT_THREADS 256
 
-// ---- butterflies ---------------------------------------------------------------------------
-__device__ __forceinline__ void ct_bfly(u64 &X, u64 &Y, u64 w, u64 wp, u64 q, u64 q2) {
-    u64 x = X >= q2 ? X - q2 : X;
-    u64 t = mul_shoup_lazy(Y, w, wp, q);
-    X = x + t;
-    Y = x - t + q2;
-}
-__device__ __forceinline__ void gs_bfly(u64 &X, u64 &Y, u64 w, u64 wp, u64 q, u64 q2) {
-    u64 s = X + Y;
-    u64 d = X - Y + q2;
-    X = s >= q2 ? s - q2 : s;
-    Y = mul_shoup_lazy(d, w, wp, q);
-}
+struct NttTables {
+    const ModC *modc;
+    const u64 *tw, *twp;          // [nmod][n] integer twiddles and Shoup companions
+    const double *twd, *twqd;     // [nmod][n] the same twiddles as doubles, and w/q
+    const u64 *ninv, *ninvp;      // [nmod] n^{-1} (inverse only)
+    const double *ninvd, *ninvqd;
+    const FpQ *fpq;               // [nmod] q and 1/q as doubles; q = 0 where the limb must use IntArith
+};
+
+// ---- integer arithmetic --------------------------------------------------------------------------
+struct IntArith {
+    typedef u64 T;
+    u64 q, q2, ni, nip;
+    const u64 *w, *wp;
+    __device__ __forceinline__ void init(const NttTables &t, int mi, int n) {
+        q = t.modc[mi].q, q2 = 2 * q;
+        w = t.tw + (size_t)mi * n, wp = t.twp + (size_t)mi * n;
+        ni = nip = 0;
+        if (t.ninv) ni = t.ninv[mi], nip = t.ninvp[mi];
+    }
+    __device__ __forceinline__ T from_rest(u64 raw) const { return raw; }     // canonical [0, q)
+    __device__ __forceinline__ T from_mid(u64 raw) const { return raw; }
+    __device__ __forceinline__ u64 to_mid(T v) const { return v; }
+    __device__ __forceinline__ void ct(T &X, T &Y, u64 idx) const {           // in, out below 4q
+        u64 x = X >= q2 ? X - q2 : X;
+        u64 t = mul_shoup_lazy(Y, w[idx], wp[idx], q);
+        X = x + t;
+        Y = x - t + q2;
+    }
+    __device__ __forceinline__ void gs(T &X, T &Y, u64 idx) const {           // in, out below 2q
+        u64 s = X + Y, d = X - Y + q2;
+        X = s >= q2 ? s - q2 : s;
+        Y = mul_shoup_lazy(d, w[idx], wp[idx], q);
+    }
+    __device__ __forceinline__ u64 to_rest_fwd(T v) const {
+        v = v >= q2 ? v - q2 : v;
+        return v >= q ? v - q : v;
+    }
+    __device__ __forceinline__ u64 to_rest_inv(T v) const { return mul_shoup(v, ni, nip, q); }
+};
+
+// ---- FP64 arithmetic for moduli below 2^50 -----------------------------------------------------------
+#define TWO52 4503599627370496.0
+struct FpArith {
+    typedef double T;
+    double q, qinv, ni, niq;
+    const double *w, *wq;
+    __device__ __forceinline__ void init(const NttTables &t, int mi, int n) {
+        q = t.fpq[mi].q, qinv = t.fpq[mi].qinv;
+        w = t.twd + (size_t)mi * n, wq = t.twqd + (size_t)mi * n;
+        ni = niq = 0.0;
+        if (t.ninvd) ni = t.ninvd[mi], niq = t.ninvqd[mi];
+    }
+    __device__ __forceinline__ double mulmod(double y, double a, double aq) const {
+        double h = y * a;
+        double l = __builtin_fma(y, a, -h);
+        double c = __builtin_rint(y * aq);
+        return __builtin_fma(-c, q, h) + l;
+    }
+    __device__ __forceinline__ double norm(double x) const { return __builtin_fma(-__builtin_rint(x * qinv), q, x); }
+    __device__ __forceinline__ T from_rest(u64 raw) const {
+        return __longlong_as_double((long long)(raw | 0x4330000000000000ULL)) - TWO52;
+    }
+    __device__ __forceinline__ T from_mid(u64 raw) const { return __longlong_as_double((long long)raw); }
+    __device__ __forceinline__ u64 to_mid(T v) const { return (u64)__double_as_longlong(v); }
+    __device__ __forceinline__ void ct(T &X, T &Y, u64 idx) const {           // |in|, |out| <= 1.54 q
+        double x = norm(X), r = mulmod(Y, w[idx], wq[idx]);
+        X = x + r;
+        Y = x - r;
+    }
+    __device__ __forceinline__ void gs(T &X, T &Y, u64 idx) const {           // |in|, |out| <= 1.04 q
+        double s = X + Y, d = X - Y;
+        X = norm(s);
+        Y = mulmod(d, w[idx], wq[idx]);
+    }
+    __device__ __forceinline__ u64 canon(double v) const {                     // |v| < 2^52  ->  [0, q)
+        double r = __builtin_fma(-__builtin_floor(v * qinv), q, v);
+        r = r < 0.0 ? r + q : r;
+        r = r >= q ? r - q : r;
+        return (u64)__double_as_longlong(r + TWO52) & 0x000FFFFFFFFFFFFFULL;
+    }
+    __device__ __forceinline__ u64 to_rest_fwd(T v) const { return canon(v); }
+    __device__ __forceinline__ u64 to_rest_inv(T v) const { return canon(mulmod(v, ni, niq)); }
+};
 
 // Four forward stages on 16 register values whose index k is the local position inside one
 // butterfly block of the first of these stages; base0 = 2^s0 + (block index at stage s0).
-__device__ __forceinline__ void radix16_fwd(u64 (&v)[16], const u64 *__restrict__ tw,
-                                            const u64 *__restrict__ twp, u64 q, u64 base0) {
-    const u64 q2 = 2 * q;
+template <class A>
+__device__ __forceinline__ void radix16_fwd(typename A::T (&v)[16], const A &ar, u64 base0) {
 #pragma unroll
     for (int a = 0; a < 4; a++) {
         const int half = 8 >> a;
 #pragma unroll
         for (int g = 0; g < (1 << a); g++) {
             u64 idx = (base0 << a) + g;
-            u64 w = tw[idx], wp = twp[idx];
 #pragma unroll
             for (int j = 0; j < half; j++) {
                 int k = g * 2 * half + j;
-                ct_bfly(v[k], v[k + half], w, wp, q, q2);
+                ar.ct(v[k], v[k + half], idx);
             }
         }
     }
 }
-// The inverse of the above (stages in the opposite order).  Values in and out below 2q.
-__device__ __forceinline__ void radix16_inv(u64 (&v)[16], const u64 *__restrict__ tw,
-                                            const u64 *__restrict__ twp, u64 q, u64 base0) {
-    const u64 q2 = 2 * q;
+// The inverse of the above (stages in the opposite order).
+template <class A>
+__device__ __forceinline__ void radix16_inv(typename A::T (&v)[16], const A &ar, u64 base0) {
 #pragma unroll
     for (int a = 3; a >= 0; a--) {
         const int half = 8 >> a;
 #pragma unroll
         for (int g = 0; g < (1 << a); g++) {
             u64 idx = (base0 << a) + g;
-            u64 w = tw[idx], wp = twp[idx];
 #pragma unroll
             for (int j = 0; j < half; j++) {
                 int k = g * 2 * half + j;
-                gs_bfly(v[k], v[k + half], w, wp, q, q2);
+                ar.gs(v[k], v[k + half], idx);
             }
         }
     }
@@ -72,203 +151,200 @@ __device__ __forceinline__ void radix16_inv(u64 (&v)[16], const u64 *__restrict_
 __device__ __forceinline__ int pad(int e) { return e + (e >> 4); }
 #define LDS_WORDS (4096 + 256)
 
-// ---- column kernels: stages 0..7 --------------------------------------------------------------
-// grid.x = limbs * (n2/16); tile = rows 0..255 of 16 adjacent columns.
-__global__ __launch_bounds__(NTT_THREADS) void ntt_cols_fwd(u64 *__restrict__ data,
-                                                           const u64 *__restrict__ src,
+// ---- column passes: stages 0..7; tile = rows 0..255 of 16 adjacent columns ---------------------------
+template <class A>
+__device__ __forceinline__ void cols_fwd_body(u64 *lds, u64 *p, const u64 *ps, const NttTables &t, int mi, int n, int n2) {
+    A ar;
+    ar.init(t, mi, n);
+    const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
+    typename A::T v[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) v[k] = ar.from_rest(ps[(size_t)(sub + 16 * k) * n2 + c]);
+    radix16_fwd(v, ar, 1);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[pad((sub + 16 * k) * 16 + c)] = ar.to_mid(v[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad((16 * sub + k) * 16 + c)]);
+    radix16_fwd(v, ar, 16 + sub);
+#pragma unroll
+    for (int k = 0; k < 16; k++) p[(size_t)(16 * sub + k) * n2 + c] = ar.to_mid(v[k]);
+}
+template <class A>
+__device__ __forceinline__ void cols_inv_body(u64 *lds, u64 *p, const NttTables &t, int mi, int n, int n2) {
+    A ar;
+    ar.init(t, mi, n);
+    const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
+    typename A::T v[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(p[(size_t)(16 * sub + k) * n2 + c]);
+    radix16_inv(v, ar, 16 + sub);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[pad((16 * sub + k) * 16 + c)] = ar.to_mid(v[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad((sub + 16 * k) * 16 + c)]);
+    radix16_inv(v, ar, 1);
+#pragma unroll
+    for (int k = 0; k < 16; k++) p[(size_t)(sub + 16 * k) * n2 + c] = ar.to_rest_inv(v[k]);
+}
+
+// grid.x = limbs * (n2/16)
+__global__ __launch_bounds__(NTT_THREADS) void ntt_cols_fwd(u64 *__restrict__ data, const u64 *__restrict__ src,
                                                            const int *__restrict__ src_rows,
                                                            const int *__restrict__ rows,
-        const int *__restrict__ mod_idx,
-                                                           const ModC *__restrict__ modc,
-                                                           const u64 *__restrict__ tw_all,
-                                                           const u64 *__restrict__ twp_all, int n,
+                                                           const int *__restrict__ mod_idx, NttTables t, int n,
                                                            int n2) {
     __shared__ u64 lds[LDS_WORDS];
     const int tiles = n2 >> 4;
     const int limb = blockIdx.x / tiles, c0 = (blockIdx.x % tiles) << 4;
     const int mi = mod_idx[limb];
-    const u64 q = modc[mi].q;
-    const u64 *tw = tw_all + (size_t)mi * n, *twp = twp_all + (size_t)mi * n;
     u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + c0;
     const u64 *ps = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n + c0 : p;
-    const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
-    u64 v[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = ps[(size_t)(sub + 16 * k) * n2 + c];
-    radix16_fwd(v, tw, twp, q, 1);
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[pad((sub + 16 * k) * 16 + c)] = v[k];
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = lds[pad((16 * sub + k) * 16 + c)];
-    radix16_fwd(v, tw, twp, q, 16 + sub);
-#pragma unroll
-    for (int k = 0; k < 16; k++) p[(size_t)(16 * sub + k) * n2 + c] = v[k];   // below 4q
+    if (t.fpq[mi].q != 0.0)
+        cols_fwd_body<FpArith>(lds, p, ps, t, mi, n, n2);
+    else
+        cols_fwd_body<IntArith>(lds, p, ps, t, mi, n, n2);
 }
-
-__global__ __launch_bounds__(NTT_THREADS) void ntt_cols_inv(u64 *__restrict__ data,
-                                                           const int *__restrict__ rows,
-        const int *__restrict__ mod_idx,
-                                                           const ModC *__restrict__ modc,
-                                                           const u64 *__restrict__ tw_all,
-                                                           const u64 *__restrict__ twp_all,
-                                                           const u64 *__restrict__ ninv,
-                                                           const u64 *__restrict__ ninvp, int n,
+__global__ __launch_bounds__(NTT_THREADS) void ntt_cols_inv(u64 *__restrict__ data, const int *__restrict__ rows,
+                                                           const int *__restrict__ mod_idx, NttTables t, int n,
                                                            int n2) {
     __shared__ u64 lds[LDS_WORDS];
     const int tiles = n2 >> 4;
     const int limb = blockIdx.x / tiles, c0 = (blockIdx.x % tiles) << 4;
     const int mi = mod_idx[limb];
-    const u64 q = modc[mi].q;
-    const u64 *tw = tw_all + (size_t)mi * n, *twp = twp_all + (size_t)mi * n;
     u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + c0;
-    const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
-    u64 v[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = p[(size_t)(16 * sub + k) * n2 + c];   // below 2q
-    radix16_inv(v, tw, twp, q, 16 + sub);
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[pad((16 * sub + k) * 16 + c)] = v[k];
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = lds[pad((sub + 16 * k) * 16 + c)];
-    radix16_inv(v, tw, twp, q, 1);
-    const u64 ni = ninv[mi], nip = ninvp[mi];
-#pragma unroll
-    for (int k = 0; k < 16; k++) p[(size_t)(sub + 16 * k) * n2 + c] = mul_shoup(v[k], ni, nip, q);
+    if (t.fpq[mi].q != 0.0)
+        cols_inv_body<FpArith>(lds, p, t, mi, n, n2);
+    else
+        cols_inv_body<IntArith>(lds, p, t, mi, n, n2);
 }
 
-// ---- row kernels: stages 8.. on contiguous blocks of n2 words ------------------------------------
-// n2 = 256: grid.x = limbs * n/4096, a workgroup owns 16 blocks.
-__global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_fwd(u64 *__restrict__ data,
-                                                              const int *__restrict__ rows,
-        const int *__restrict__ mod_idx,
-                                                              const ModC *__restrict__ modc,
-                                                              const u64 *__restrict__ tw_all,
-                                                              const u64 *__restrict__ twp_all,
-                                                              int n) {
-    __shared__ u64 lds[LDS_WORDS];
-    const int per = n >> 12;
-    const int limb = blockIdx.x / per, chunk = blockIdx.x % per;
-    const int mi = mod_idx[limb];
-    const u64 q = modc[mi].q;
-    const u64 *tw = tw_all + (size_t)mi * n, *twp = twp_all + (size_t)mi * n;
-    u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + (size_t)chunk * 4096;
+// ---- row passes on contiguous blocks of 256 words (n = 65536): a workgroup owns 16 blocks ---------------
+template <class A>
+__device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTables &t, int mi, int n, int chunk) {
+    A ar;
+    ar.init(t, mi, n);
     const int sub = threadIdx.x & 15, blk = threadIdx.x >> 4;
     const u64 B = (u64)chunk * 16 + blk;
-    u64 v[16];
+    typename A::T v[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) {
-        u64 x = p[blk * 256 + sub + 16 * k];       // below 4q from the column kernel
-        v[k] = x;
-    }
-    radix16_fwd(v, tw, twp, q, 256 + B);
+    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(p[blk * 256 + sub + 16 * k]);
+    radix16_fwd(v, ar, 256 + B);
 #pragma unroll
-    for (int k = 0; k < 16; k++) lds[pad(blk * 256 + sub + 16 * k)] = v[k];
+    for (int k = 0; k < 16; k++) lds[pad(blk * 256 + sub + 16 * k)] = ar.to_mid(v[k]);
     __syncthreads();
 #pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = lds[pad(blk * 256 + 16 * sub + k)];
-    radix16_fwd(v, tw, twp, q, 4096 + B * 16 + sub);
-    const u64 q2 = 2 * q;
-#pragma unroll
-    for (int k = 0; k < 16; k++) {
-        u64 x = v[k];
-        x = x >= q2 ? x - q2 : x;
-        v[k] = x >= q ? x - q : x;
-    }
+    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad(blk * 256 + 16 * sub + k)]);
+    radix16_fwd(v, ar, 4096 + B * 16 + sub);
     // lane owns 16 contiguous words: store as 8 x 16 bytes
     ulonglong2 *o = reinterpret_cast<ulonglong2 *>(p + blk * 256 + 16 * sub);
 #pragma unroll
-    for (int k = 0; k < 8; k++) o[k] = make_ulonglong2(v[2 * k], v[2 * k + 1]);
+    for (int k = 0; k < 8; k++) o[k] = make_ulonglong2(ar.to_rest_fwd(v[2 * k]), ar.to_rest_fwd(v[2 * k + 1]));
 }
-
-__global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_inv(u64 *__restrict__ data,
-                                                              const u64 *__restrict__ src,
-                                                              const int *__restrict__ src_rows,
-                                                              const int *__restrict__ rows,
-        const int *__restrict__ mod_idx,
-                                                              const ModC *__restrict__ modc,
-                                                              const u64 *__restrict__ tw_all,
-                                                              const u64 *__restrict__ twp_all,
-                                                              int n) {
-    __shared__ u64 lds[LDS_WORDS];
-    const int per = n >> 12;
-    const int limb = blockIdx.x / per, chunk = blockIdx.x % per;
-    const int mi = mod_idx[limb];
-    const u64 q = modc[mi].q;
-    const u64 *tw = tw_all + (size_t)mi * n, *twp = twp_all + (size_t)mi * n;
-    u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + (size_t)chunk * 4096;
+template <class A>
+__device__ __forceinline__ void rows256_inv_body(u64 *lds, u64 *p, const u64 *ps, const NttTables &t, int mi, int n,
+                                                 int chunk) {
+    A ar;
+    ar.init(t, mi, n);
     const int sub = threadIdx.x & 15, blk = threadIdx.x >> 4;
     const u64 B = (u64)chunk * 16 + blk;
-    u64 v[16];
-    const u64 *ps = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n + (size_t)chunk * 4096 : p;
+    typename A::T v[16];
     const ulonglong2 *in = reinterpret_cast<const ulonglong2 *>(ps + blk * 256 + 16 * sub);
 #pragma unroll
     for (int k = 0; k < 8; k++) {
         ulonglong2 x = in[k];
-        v[2 * k] = x.x;
-        v[2 * k + 1] = x.y;
+        v[2 * k] = ar.from_rest(x.x);
+        v[2 * k + 1] = ar.from_rest(x.y);
     }
-    radix16_inv(v, tw, twp, q, 4096 + B * 16 + sub);
+    radix16_inv(v, ar, 4096 + B * 16 + sub);
 #pragma unroll
-    for (int k = 0; k < 16; k++) lds[pad(blk * 256 + 16 * sub + k)] = v[k];
+    for (int k = 0; k < 16; k++) lds[pad(blk * 256 + 16 * sub + k)] = ar.to_mid(v[k]);
     __syncthreads();
 #pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = lds[pad(blk * 256 + sub + 16 * k)];
-    radix16_inv(v, tw, twp, q, 256 + B);
+    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad(blk * 256 + sub + 16 * k)]);
+    radix16_inv(v, ar, 256 + B);
 #pragma unroll
-    for (int k = 0; k < 16; k++) p[blk * 256 + sub + 16 * k] = v[k];          // below 2q
+    for (int k = 0; k < 16; k++) p[blk * 256 + sub + 16 * k] = ar.to_mid(v[k]);
+}
+// grid.x = limbs * n/4096
+__global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_fwd(u64 *__restrict__ data, const int *__restrict__ rows,
+                                                              const int *__restrict__ mod_idx, NttTables t, int n) {
+    __shared__ u64 lds[LDS_WORDS];
+    const int per = n >> 12;
+    const int limb = blockIdx.x / per, chunk = blockIdx.x % per;
+    const int mi = mod_idx[limb];
+    u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + (size_t)chunk * 4096;
+    if (t.fpq[mi].q != 0.0)
+        rows256_fwd_body<FpArith>(lds, p, t, mi, n, chunk);
+    else
+        rows256_fwd_body<IntArith>(lds, p, t, mi, n, chunk);
+}
+__global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_inv(u64 *__restrict__ data, const u64 *__restrict__ src,
+                                                              const int *__restrict__ src_rows,
+                                                              const int *__restrict__ rows,
+                                                              const int *__restrict__ mod_idx, NttTables t, int n) {
+    __shared__ u64 lds[LDS_WORDS];
+    const int per = n >> 12;
+    const int limb = blockIdx.x / per, chunk = blockIdx.x % per;
+    const int mi = mod_idx[limb];
+    u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + (size_t)chunk * 4096;
+    const u64 *ps = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n + (size_t)chunk * 4096 : p;
+    if (t.fpq[mi].q != 0.0)
+        rows256_inv_body<FpArith>(lds, p, ps, t, mi, n, chunk);
+    else
+        rows256_inv_body<IntArith>(lds, p, ps, t, mi, n, chunk);
 }
 
-// n2 = 16: every lane owns one block of 16 contiguous words.  grid.x = limbs * n/4096.
-__global__ __launch_bounds__(NTT_THREADS) void ntt_rows16_fwd(u64 *__restrict__ data,
-                                                             const int *__restrict__ rows,
-        const int *__restrict__ mod_idx,
-                                                             const ModC *__restrict__ modc,
-                                                             const u64 *__restrict__ tw_all,
-                                                             const u64 *__restrict__ twp_all,
-                                                             int n) {
+// ---- row passes on blocks of 16 words (n = 4096): every lane owns one block ---------------------------------
+template <class A>
+__device__ __forceinline__ void rows16_fwd_body(u64 *p, const NttTables &t, int mi, int n, u64 B) {
+    A ar;
+    ar.init(t, mi, n);
+    typename A::T v[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(p[k]);
+    radix16_fwd(v, ar, 256 + B);
+#pragma unroll
+    for (int k = 0; k < 16; k++) p[k] = ar.to_rest_fwd(v[k]);
+}
+template <class A>
+__device__ __forceinline__ void rows16_inv_body(u64 *p, const u64 *ps, const NttTables &t, int mi, int n, u64 B) {
+    A ar;
+    ar.init(t, mi, n);
+    typename A::T v[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) v[k] = ar.from_rest(ps[k]);
+    radix16_inv(v, ar, 256 + B);
+#pragma unroll
+    for (int k = 0; k < 16; k++) p[k] = ar.to_mid(v[k]);
+}
+__global__ __launch_bounds__(NTT_THREADS) void ntt_rows16_fwd(u64 *__restrict__ data, const int *__restrict__ rows,
+                                                             const int *__restrict__ mod_idx, NttTables t, int n) {
     const int per = n >> 12;
     const int limb = blockIdx.x / per, chunk = blockIdx.x % per;
     const int mi = mod_idx[limb];
-    const u64 q = modc[mi].q, q2 = 2 * q;
-    const u64 *tw = tw_all + (size_t)mi * n, *twp = twp_all + (size_t)mi * n;
     const u64 B = (u64)chunk * 256 + threadIdx.x;
     u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + B * 16;
-    u64 v[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = p[k];
-    radix16_fwd(v, tw, twp, q, 256 + B);
-#pragma unroll
-    for (int k = 0; k < 16; k++) {
-        u64 x = v[k];
-        x = x >= q2 ? x - q2 : x;
-        p[k] = x >= q ? x - q : x;
-    }
+    if (t.fpq[mi].q != 0.0)
+        rows16_fwd_body<FpArith>(p, t, mi, n, B);
+    else
+        rows16_fwd_body<IntArith>(p, t, mi, n, B);
 }
-__global__ __launch_bounds__(NTT_THREADS) void ntt_rows16_inv(u64 *__restrict__ data,
-                                                             const u64 *__restrict__ src,
+__global__ __launch_bounds__(NTT_THREADS) void ntt_rows16_inv(u64 *__restrict__ data, const u64 *__restrict__ src,
                                                              const int *__restrict__ src_rows,
                                                              const int *__restrict__ rows,
-        const int *__restrict__ mod_idx,
-                                                             const ModC *__restrict__ modc,
-                                                             const u64 *__restrict__ tw_all,
-                                                             const u64 *__restrict__ twp_all,
-                                                             int n) {
+                                                             const int *__restrict__ mod_idx, NttTables t, int n) {
     const int per = n >> 12;
     const int limb = blockIdx.x / per, chunk = blockIdx.x % per;
     const int mi = mod_idx[limb];
-    const u64 q = modc[mi].q;
-    const u64 *tw = tw_all + (size_t)mi * n, *twp = twp_all + (size_t)mi * n;
     const u64 B = (u64)chunk * 256 + threadIdx.x;
     u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + B * 16;
     const u64 *ps = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n + B * 16 : p;
-    u64 v[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = ps[k];
-    radix16_inv(v, tw, twp, q, 256 + B);
-#pragma unroll
-    for (int k = 0; k < 16; k++) p[k] = v[k];
+    if (t.fpq[mi].q != 0.0)
+        rows16_inv_body<FpArith>(p, ps, t, mi, n, B);
+    else
+        rows16_inv_body<IntArith>(p, ps, t, mi, n, B);
 }
 
 // data rows d_rows[i] (or i) are transformed in place; with src != nullptr the first pass reads row
@@ -279,36 +355,34 @@ void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, c
     Prof prof_(ctx, inverse ? CM_K_NTT_INV : CM_K_NTT_FWD, limbs, st);
     const int n = ctx->n, n2 = n >> 8;
     dim3 grid((unsigned)limbs * (n >> 12)), block(NTT_THREADS);
+    NttTables t;
+    t.modc = ctx->d_modc, t.fpq = ctx->d_fpq;
     if (!inverse) {
-        hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, ctx->d_modc,
-                           ctx->d_tw, ctx->d_twp, n, n2);
+        t.tw = ctx->d_tw, t.twp = ctx->d_twp, t.twd = ctx->d_twd, t.twqd = ctx->d_twqd;
+        t.ninv = t.ninvp = nullptr, t.ninvd = t.ninvqd = nullptr;
+        hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, t, n, n2);
         if (n2 == 256)
-            hipLaunchKernelGGL(ntt_rows256_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, ctx->d_modc,
-                               ctx->d_tw, ctx->d_twp, n);
+            hipLaunchKernelGGL(ntt_rows256_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, t, n);
         else
-            hipLaunchKernelGGL(ntt_rows16_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, ctx->d_modc,
-                               ctx->d_tw, ctx->d_twp, n);
+            hipLaunchKernelGGL(ntt_rows16_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, t, n);
     } else {
+        t.tw = ctx->d_itw, t.twp = ctx->d_itwp, t.twd = ctx->d_itwd, t.twqd = ctx->d_itwqd;
+        t.ninv = ctx->d_ninv, t.ninvp = ctx->d_ninvp, t.ninvd = ctx->d_ninvd, t.ninvqd = ctx->d_ninvqd;
         if (n2 == 256)
-            hipLaunchKernelGGL(ntt_rows256_inv, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx,
-                               ctx->d_modc, ctx->d_itw, ctx->d_itwp, n);
+            hipLaunchKernelGGL(ntt_rows256_inv, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, t, n);
         else
-            hipLaunchKernelGGL(ntt_rows16_inv, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx,
-                               ctx->d_modc, ctx->d_itw, ctx->d_itwp, n);
-        hipLaunchKernelGGL(ntt_cols_inv, grid, block, 0, st, data, d_rows, d_mod_idx, ctx->d_modc,
-                           ctx->d_itw, ctx->d_itwp, ctx->d_ninv, ctx->d_ninvp, n, n2);
+            hipLaunchKernelGGL(ntt_rows16_inv, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, t, n);
+        hipLaunchKernelGGL(ntt_cols_inv, grid, block, 0, st, data, d_rows, d_mod_idx, t, n, n2);
     }
 }
 void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mod_idx, int limbs,
                      bool inverse, hipStream_t st) {
     launch_ntt_src(ctx, data, d_rows, nullptr, nullptr, d_mod_idx, limbs, inverse, st);
 }
-
 void launch_ntt(cm_ctx *ctx, u64 *data, const int *d_mod_idx, int limbs, bool inverse,
                 hipStream_t st) {
     launch_ntt_rows(ctx, data, nullptr, d_mod_idx, limbs, inverse, st);
 }
-
 void launch_ntt_range(cm_ctx *ctx, u64 *data, int first_mod, int limbs, bool inverse,
                       hipStream_t st) {
     launch_ntt(ctx, data, iota_idx(ctx) + first_mod, limbs, inverse, st);
