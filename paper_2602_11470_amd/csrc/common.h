@@ -54,6 +54,15 @@ __device__ __forceinline__ u64 addmod(u64 a, u64 b, u64 q) {
 }
 __device__ __forceinline__ u64 submod(u64 a, u64 b, u64 q) { return a >= b ? a - b : a + q - b; }
 
+// Position i of the evaluation order holds the value at psi^(2 brev(i) + 1); the Galois map
+// X -> X^g moves the value at exponent e*g to exponent e: out[i] = in[perm_src(i, g)].  It maps
+// aligned blocks of 2^k positions onto aligned blocks (and i^1 to src^1).
+__device__ __forceinline__ unsigned perm_src(unsigned i, unsigned g, int logn) {
+    unsigned e = 2u * (__brev(i) >> (32 - logn)) + 1u;
+    unsigned s = (e * g) & ((2u << logn) - 1u);
+    return __brev((s - 1u) >> 1) >> (32 - logn);
+}
+
 // modulus as doubles for the FP64 butterflies (moduli below 2^50 only; q = 0 otherwise)
 struct FpQ {
     double q, qinv;

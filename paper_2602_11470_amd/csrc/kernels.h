@@ -11,10 +11,10 @@ void launch_mac_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int 
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st);
 void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st);
 void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_step, int max_nt, u64 *out, const u64 *in,
-                      size_t in_stride, size_t out_stride, const u64 *own_src, hipStream_t st);
+                      size_t in_stride, size_t out_stride, const u64 *own_src, u64 own_g, hipStream_t st);
 void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g, hipStream_t st);
 void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
-                           int addend_comps, int level, u64 g, hipStream_t st);
+                           int addend_comps, int level, u64 g, const u64 *accum, hipStream_t st);
 void launch_rescale_reduce(cm_ctx *ctx, u64 *red, const u64 *last, int ncomp, int level, hipStream_t st);
 void launch_rescale_finish(cm_ctx *ctx, u64 *out, const u64 *in, const u64 *red, const u64 *d_qlinv, int ncomp, int level, hipStream_t st);
 u64 rng_key(u64 seed, u64 stream);
@@ -38,12 +38,15 @@ struct KsLevel {            // cached per level: which rows of the digit array a
 };
 const KsLevel &ks_level(cm_ctx *ctx, int level);
 // digits[beta][ext][n] (evaluation domain) from evaluation-domain d[level+1][n]
-cm_status ks_raise(cm_ctx *ctx, const u64 *d, int level, u64 *digits, hipStream_t st);
+// with g != 0: digits of the Galois-mapped polynomial (d is read through the permutation)
+cm_status ks_raise(cm_ctx *ctx, const u64 *d, int level, u64 *digits, hipStream_t st, u64 g = 0);
 // (out0, out1) = ModDown(sum_j perm_g(digits_j) * evk_j) [+ perm_g(addend) on component 0]; out = [2][level+1][n]
 // addend_comps: 0 none, 1 component 0 only (rotation), 2 both (relinearisation)
 cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u64 g, const u64 *addend,
-                   int addend_comps, u64 *out, hipStream_t st);
-cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64 g, u64 *out, hipStream_t st);
+                   int addend_comps, u64 *out, hipStream_t st, const u64 *accum = nullptr);
+// out = Rot(in) (+ accum); out may alias in or accum
+cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64 g, u64 *out, hipStream_t st,
+                      const u64 *accum = nullptr);
 cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st);
 u64 *arena_digits(const cm_ctx *ctx);
 cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys, const u64 *gs,
@@ -51,5 +54,5 @@ cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, cons
 const u64 *find_key(const cm_evk *evk, u64 g);
 void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mods, int limbs, bool inverse, hipStream_t st);
 void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, const int *d_src_rows,
-                    const int *d_mods, int limbs, bool inverse, hipStream_t st);
+                    const int *d_mods, int limbs, bool inverse, hipStream_t st, u64 g = 0);
 void decode_host(const cm_ctx *ctx, const std::vector<double> &m, double *re, double *im, size_t nslots);

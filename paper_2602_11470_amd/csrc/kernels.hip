@@ -6,13 +6,6 @@
 
 #define TPB 256
 
-// position i of the evaluation order holds the value at psi^(2 brev(i) + 1); the Galois map
-// X -> X^g moves the value at exponent e*g to exponent e.
-__device__ __forceinline__ unsigned perm_src(unsigned i, unsigned g, int logn) {
-    unsigned e = 2u * (__brev(i) >> (32 - logn)) + 1u;
-    unsigned s = (e * g) & ((2u << logn) - 1u);
-    return __brev((s - 1u) >> 1) >> (32 - logn);
-}
 
 // ---- signed integers -> residues -------------------------------------------------------------
 __global__ void k_reduce_i64(u64 *out, const long long *coeffs, const int *mod_idx, const ModC *modc, int n) {
@@ -128,7 +121,7 @@ void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, 
 // of own_src (the evaluation-domain input) to the same rows of the output.
 template <int CONV_TG>
 __global__ void k_base_conv(u64 *out, const u64 *in, const ConvDev *tabs, int tab_step, const ModC *modc, int n,
-                            size_t in_stride, size_t out_stride, const u64 *own_src) {
+                            size_t in_stride, size_t out_stride, const u64 *own_src, unsigned own_g, int logn) {
     const int i = blockIdx.x * TPB + threadIdx.x;
     const ConvDev &t = tabs[blockIdx.z * tab_step];
     const int ns = t.ns, nt = t.nt;
@@ -143,7 +136,9 @@ __global__ void k_base_conv(u64 *out, const u64 *in, const ConvDev *tabs, int ta
         if (m < ns) {
             u64 q = modc[t.src_mod[m]].q;
             y[m] = mul_shoup(in[(size_t)t.in_rows[m] * n + i], t.inv_hat[m], t.inv_hat_sh[m], q);
-            if (own_src && r0 == 0) out[(size_t)t.in_rows[m] * n + i] = own_src[(size_t)t.in_rows[m] * n + i];
+            if (own_src && r0 == 0)
+                out[(size_t)t.in_rows[m] * n + i] =
+                    own_src[(size_t)t.in_rows[m] * n + (own_g ? perm_src((unsigned)i, own_g, logn) : (unsigned)i)];
         }
     }
 #pragma unroll
@@ -160,12 +155,12 @@ __global__ void k_base_conv(u64 *out, const u64 *in, const ConvDev *tabs, int ta
     }
 }
 void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_step, int max_nt, u64 *out, const u64 *in,
-                      size_t in_stride, size_t out_stride, const u64 *own_src, hipStream_t st) {
+                      size_t in_stride, size_t out_stride, const u64 *own_src, u64 own_g, hipStream_t st) {
     Prof prof_(ctx, CM_K_BASE_CONV, batch * max_nt, st);
     static int tg = getenv("CM_CONV_TG") ? atoi(getenv("CM_CONV_TG")) : 8;
 #define CONV_LAUNCH(TG)                                                                                              \
     hipLaunchKernelGGL(k_base_conv<TG>, dim3(ctx->n / TPB, (max_nt + TG - 1) / TG, batch), dim3(TPB), 0, st, out, in, \
-                       d_tabs, tab_step, ctx->d_modc, ctx->n, in_stride, out_stride, own_src)
+                       d_tabs, tab_step, ctx->d_modc, ctx->n, in_stride, out_stride, own_src, (unsigned)own_g, ctx->logn)
     if (tg == 2) CONV_LAUNCH(2);
     else if (tg == 8) CONV_LAUNCH(8);
     else if (tg == 12) CONV_LAUNCH(12);
@@ -214,7 +209,7 @@ void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u
 // batch (blockIdx.z) = component; u rows [ext][n], conv rows [level+1][n], out rows [level+1][n]
 __global__ void k_moddown_finish(u64 *out, const u64 *u, const u64 *conv, const u64 *pinv, const u64 *addend,
                                  const ModC *modc, int n, int logn, unsigned g, size_t u_stride,
-                                 size_t conv_stride, size_t out_stride, int addend_comp_only) {
+                                 size_t conv_stride, size_t out_stride, int addend_comp_only, const u64 *accum) {
     unsigned i = blockIdx.x * TPB + threadIdx.x;
     int l = blockIdx.y, c = blockIdx.z;
     u64 q = modc[l].q;
@@ -224,16 +219,17 @@ __global__ void k_moddown_finish(u64 *out, const u64 *u, const u64 *conv, const 
         unsigned s = g ? perm_src(i, g, logn) : i;
         v = addmod(v, addend[c * out_stride + (size_t)l * n + s], q);
     }
+    if (accum) v = addmod(v, accum[c * out_stride + (size_t)l * n + i], q);      // out = accum + result
     out[c * out_stride + (size_t)l * n + i] = v;
 }
 void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
-                           int addend_comps, int level, u64 g, hipStream_t st) {
+                           int addend_comps, int level, u64 g, const u64 *accum, hipStream_t st) {
     Prof prof_(ctx, CM_K_MODDOWN_FINISH, 1, st);
     int ext = level + 1 + ctx->K;
     size_t n = ctx->n;
     hipLaunchKernelGGL(k_moddown_finish, dim3(ctx->n / TPB, level + 1, 2), dim3(TPB), 0, st, out, u, conv, d_pinv,
                        addend, ctx->d_modc, ctx->n, ctx->logn, (unsigned)g, (size_t)ext * n, (size_t)(level + 1) * n,
-                       (size_t)(level + 1) * n, addend_comps - 1);
+                       (size_t)(level + 1) * n, addend_comps - 1, accum);
 }
 
 // ---- rescale ---------------------------------------------------------------------------------

@@ -11,6 +11,8 @@
 // scale of the prime the following rescale removes, so masking leaves the scale unchanged.
 #include <math.h>
 
+#include <utility>
+
 #include "kernels.h"
 
 struct cm_kv {
@@ -208,8 +210,8 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     HIPCHK(hipMemcpyAsync(cq, in->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
     for (int i = 0; i < ilog2(kv->t); i++) {                     // replicate q over the t residues
         u64 g = rot_g(kv, -(1 << i));
-        CMCHK(rotate_into(ctx, find_key(evk, g), cq, lv, g, tmp, st));
-        launch_add(ctx, cq, cq, tmp, 2, limbs, st);
+        CMCHK(rotate_into(ctx, find_key(evk, g), cq, lv, g, tmp, st, cq));      // tmp = cq + Rot(cq)
+        std::swap(cq, tmp);
     }
     u64 *digits = arena_digits(ctx);
     for (int c = 0; c < nk; c++) {
@@ -217,14 +219,15 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
         CMCHK(ks_raise(ctx, T + 2 * ln, lv, digits, st));
         CMCHK(ks_apply(ctx, digits, relin, lv, 0, T, 2, P, st));
         CMCHK(rescale_into(ctx, P, 2, lv, R, st));
+        u64 *r0 = R, *r1 = P;                                    // P is free again: second buffer
         for (int i = 0; i < ilog2(kv->E); i++) {                 // sum over the E dims of every head
             u64 g = rot_g(kv, (long long)(1 << i) * kv->H * kv->t);
-            CMCHK(rotate_into(ctx, find_key(evk, g), R, lv - 1, g, tmp, st));
-            launch_add(ctx, R, R, tmp, 2, lv, st);
+            CMCHK(rotate_into(ctx, find_key(evk, g), r0, lv - 1, g, r1, st, r0));
+            std::swap(r0, r1);
         }
         // keep copy e = c: base mask rotated right by c*H*t
         launch_automorphism(ctx, mask, kv->d_mask_qk, lv, rot_g(kv, -(long long)(c % kv->E) * kv->H * kv->t), st);
-        launch_mac_pt(ctx, acc, R, mask, 2, lv, c > 0, st);
+        launch_mac_pt(ctx, acc, r0, mask, 2, lv, c > 0, st);
     }
     CMCHK(rescale_into(ctx, acc, 2, lv - 1, out->dev, st));
     out->level = lv - 2, out->ncomp = 2;
@@ -266,15 +269,15 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     u64 *acc = inner + (size_t)(kv->r_o - 1) * ctw;
     for (int g = kv->r_o - 2; g >= 0; g--) {
         u64 gg = rot_g(kv, kv->r_i * Ht);
-        CMCHK(rotate_into(ctx, find_key(evk, gg), acc, lv, gg, tmp, st));
-        acc = inner + (size_t)g * ctw;
-        launch_add(ctx, acc, acc, tmp, 2, limbs, st);
+        u64 *nxt = inner + (size_t)g * ctw;                      // inner_g + Rot(acc), written over inner_g
+        CMCHK(rotate_into(ctx, find_key(evk, gg), acc, lv, gg, nxt, st, nxt));
+        acc = nxt;
     }
     CMCHK(rescale_into(ctx, acc, 2, lv, R, st));
     for (int l = 0; l < ilog2(kv->t); l++) {
         u64 g = rot_g(kv, 1 << l);
-        CMCHK(rotate_into(ctx, find_key(evk, g), R, lv - 1, g, tmp, st));
-        launch_add(ctx, R, R, tmp, 2, lv, st);
+        CMCHK(rotate_into(ctx, find_key(evk, g), R, lv - 1, g, tmp, st, R));
+        std::swap(R, tmp);
     }
     HIPCHK(hipMemcpyAsync(out->dev, R, 2 * (size_t)lv * n * 8, hipMemcpyDeviceToDevice, st));
     out->level = lv - 1, out->ncomp = 2;

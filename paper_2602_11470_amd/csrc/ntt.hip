@@ -243,19 +243,28 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
     for (int k = 0; k < 8; k++) o[k] = make_ulonglong2(ar.to_rest_fwd(v[2 * k]), ar.to_rest_fwd(v[2 * k + 1]));
 }
 template <class A>
-__device__ __forceinline__ void rows256_inv_body(u64 *lds, u64 *p, const u64 *ps, const NttTables &t, int mi, int n,
-                                                 int chunk) {
+__device__ __forceinline__ void rows256_inv_body(u64 *lds, u64 *p, const u64 *ps, const u64 *psrow, unsigned g,
+                                                 const NttTables &t, int mi, int n, int chunk) {
     A ar;
     ar.init(t, mi, n);
     const int sub = threadIdx.x & 15, blk = threadIdx.x >> 4;
     const u64 B = (u64)chunk * 16 + blk;
     typename A::T v[16];
-    const ulonglong2 *in = reinterpret_cast<const ulonglong2 *>(ps + blk * 256 + 16 * sub);
+    if (g) {
+        // read through the Galois permutation: the 16 positions of this lane come from one aligned
+        // block of 16 words of the source row
+        const unsigned pos = (unsigned)chunk * 4096 + blk * 256 + 16 * sub;
+        const int logn = 31 - __clz(n);
 #pragma unroll
-    for (int k = 0; k < 8; k++) {
-        ulonglong2 x = in[k];
-        v[2 * k] = ar.from_rest(x.x);
-        v[2 * k + 1] = ar.from_rest(x.y);
+        for (int k = 0; k < 16; k++) v[k] = ar.from_rest(psrow[perm_src(pos + k, g, logn)]);
+    } else {
+        const ulonglong2 *in = reinterpret_cast<const ulonglong2 *>(ps + blk * 256 + 16 * sub);
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            ulonglong2 x = in[k];
+            v[2 * k] = ar.from_rest(x.x);
+            v[2 * k + 1] = ar.from_rest(x.y);
+        }
     }
     radix16_inv(v, ar, 4096 + B * 16 + sub);
 #pragma unroll
@@ -283,17 +292,19 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_fwd(u64 *__restrict__
 __global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_inv(u64 *__restrict__ data, const u64 *__restrict__ src,
                                                               const int *__restrict__ src_rows,
                                                               const int *__restrict__ rows,
-                                                              const int *__restrict__ mod_idx, NttTables t, int n) {
+                                                              const int *__restrict__ mod_idx, NttTables t, int n,
+                                                              unsigned g) {
     __shared__ u64 lds[LDS_WORDS];
     const int per = n >> 12;
     const int limb = blockIdx.x / per, chunk = blockIdx.x % per;
     const int mi = mod_idx[limb];
     u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + (size_t)chunk * 4096;
-    const u64 *ps = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n + (size_t)chunk * 4096 : p;
+    const u64 *psrow = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n : p - (size_t)chunk * 4096;
+    const u64 *ps = psrow + (size_t)chunk * 4096;
     if (t.fpq[mi].q != 0.0)
-        rows256_inv_body<FpArith>(lds, p, ps, t, mi, n, chunk);
+        rows256_inv_body<FpArith>(lds, p, ps, psrow, g, t, mi, n, chunk);
     else
-        rows256_inv_body<IntArith>(lds, p, ps, t, mi, n, chunk);
+        rows256_inv_body<IntArith>(lds, p, ps, psrow, g, t, mi, n, chunk);
 }
 
 // ---- row passes on blocks of 16 words (n = 4096): every lane owns one block ---------------------------------
@@ -309,12 +320,15 @@ __device__ __forceinline__ void rows16_fwd_body(u64 *p, const NttTables &t, int 
     for (int k = 0; k < 16; k++) p[k] = ar.to_rest_fwd(v[k]);
 }
 template <class A>
-__device__ __forceinline__ void rows16_inv_body(u64 *p, const u64 *ps, const NttTables &t, int mi, int n, u64 B) {
+__device__ __forceinline__ void rows16_inv_body(u64 *p, const u64 *ps, const u64 *psrow, unsigned g,
+                                                const NttTables &t, int mi, int n, u64 B) {
     A ar;
     ar.init(t, mi, n);
     typename A::T v[16];
+    const int logn = 31 - __clz(n);
 #pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = ar.from_rest(ps[k]);
+    for (int k = 0; k < 16; k++)
+        v[k] = ar.from_rest(g ? psrow[perm_src((unsigned)(B * 16 + k), g, logn)] : ps[k]);
     radix16_inv(v, ar, 256 + B);
 #pragma unroll
     for (int k = 0; k < 16; k++) p[k] = ar.to_mid(v[k]);
@@ -334,24 +348,29 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_rows16_fwd(u64 *__restrict__ 
 __global__ __launch_bounds__(NTT_THREADS) void ntt_rows16_inv(u64 *__restrict__ data, const u64 *__restrict__ src,
                                                              const int *__restrict__ src_rows,
                                                              const int *__restrict__ rows,
-                                                             const int *__restrict__ mod_idx, NttTables t, int n) {
+                                                             const int *__restrict__ mod_idx, NttTables t, int n,
+                                                             unsigned g) {
     const int per = n >> 12;
     const int limb = blockIdx.x / per, chunk = blockIdx.x % per;
     const int mi = mod_idx[limb];
     const u64 B = (u64)chunk * 256 + threadIdx.x;
     u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + B * 16;
-    const u64 *ps = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n + B * 16 : p;
+    const u64 *psrow = src ? src + (size_t)(src_rows ? src_rows[limb] : limb) * n : p - B * 16;
+    const u64 *ps = psrow + B * 16;
     if (t.fpq[mi].q != 0.0)
-        rows16_inv_body<FpArith>(p, ps, t, mi, n, B);
+        rows16_inv_body<FpArith>(p, ps, psrow, g, t, mi, n, B);
     else
-        rows16_inv_body<IntArith>(p, ps, t, mi, n, B);
+        rows16_inv_body<IntArith>(p, ps, psrow, g, t, mi, n, B);
 }
 
 // data rows d_rows[i] (or i) are transformed in place; with src != nullptr the first pass reads row
 // src_rows[i] (or i) of src instead, so the transform is out of place and src is left untouched.
+// With g != 0 (inverse, out of place only) the source is read through the Galois permutation, i.e.
+// the result is the coefficient form of the mapped polynomial.
 void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, const int *d_src_rows,
-                    const int *d_mod_idx, int limbs, bool inverse, hipStream_t st) {
+                    const int *d_mod_idx, int limbs, bool inverse, hipStream_t st, u64 g) {
     if (limbs <= 0) return;
+    if (g && (!inverse || !src || src == data)) g = 0;
     Prof prof_(ctx, inverse ? CM_K_NTT_INV : CM_K_NTT_FWD, limbs, st);
     const int n = ctx->n, n2 = n >> 8;
     dim3 grid((unsigned)limbs * (n >> 12)), block(NTT_THREADS);
@@ -369,15 +388,17 @@ void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, c
         t.tw = ctx->d_itw, t.twp = ctx->d_itwp, t.twd = ctx->d_itwd, t.twqd = ctx->d_itwqd;
         t.ninv = ctx->d_ninv, t.ninvp = ctx->d_ninvp, t.ninvd = ctx->d_ninvd, t.ninvqd = ctx->d_ninvqd;
         if (n2 == 256)
-            hipLaunchKernelGGL(ntt_rows256_inv, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, t, n);
+            hipLaunchKernelGGL(ntt_rows256_inv, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, t, n,
+                               (unsigned)g);
         else
-            hipLaunchKernelGGL(ntt_rows16_inv, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, t, n);
+            hipLaunchKernelGGL(ntt_rows16_inv, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, t, n,
+                               (unsigned)g);
         hipLaunchKernelGGL(ntt_cols_inv, grid, block, 0, st, data, d_rows, d_mod_idx, t, n, n2);
     }
 }
 void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mod_idx, int limbs,
                      bool inverse, hipStream_t st) {
-    launch_ntt_src(ctx, data, d_rows, nullptr, nullptr, d_mod_idx, limbs, inverse, st);
+    launch_ntt_src(ctx, data, d_rows, nullptr, nullptr, d_mod_idx, limbs, inverse, st, 0);
 }
 void launch_ntt(cm_ctx *ctx, u64 *data, const int *d_mod_idx, int limbs, bool inverse,
                 hipStream_t st) {

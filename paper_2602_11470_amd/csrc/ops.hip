@@ -159,29 +159,29 @@ static bool ct_ok(const cm_ctx *ctx, const cm_ct *c) {
 static bool same_scale(double a, double b) { return fabs(a / b - 1.0) < 1e-9; }
 
 // ---- hybrid key switching -------------------------------------------------------------------------
-cm_status ks_raise(cm_ctx *ctx, const u64 *d, int level, u64 *digits, hipStream_t st) {
+cm_status ks_raise(cm_ctx *ctx, const u64 *d, int level, u64 *digits, hipStream_t st, u64 g) {
     const KsLevelFull &k = ks_level_full(ctx, level);
     Arena A = arena_of(ctx);
     const size_t n = ctx->n;
     // coefficient-domain copy of d (out of place), then all digits in one conversion launch; a
     // digit's own limbs are copied from d itself, which is already in the evaluation domain
-    launch_ntt_src(ctx, A.ksin, nullptr, d, nullptr, iota_idx(ctx), level + 1, true, st);
-    launch_base_conv(ctx, k.d_modup, k.beta, 1, k.modup_max_nt, digits, A.ksin, 0, (size_t)k.ext * n, d, st);
+    launch_ntt_src(ctx, A.ksin, nullptr, d, nullptr, iota_idx(ctx), level + 1, true, st, g);
+    launch_base_conv(ctx, k.d_modup, k.beta, 1, k.modup_max_nt, digits, A.ksin, 0, (size_t)k.ext * n, d, g, st);
     launch_ntt_rows(ctx, digits, k.d_ntt_rows, k.d_ntt_mods, k.n_ntt, false, st);
     return CM_OK;
 }
 
 cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u64 g, const u64 *addend,
-                   int addend_comps, u64 *out, hipStream_t st) {
+                   int addend_comps, u64 *out, hipStream_t st, const u64 *accum) {
     const KsLevelFull &k = ks_level_full(ctx, level);
     Arena A = arena_of(ctx);
     const size_t n = ctx->n;
     u64 *u0 = A.u, *u1 = A.u + (size_t)k.ext * n;
     launch_inner_product(ctx, u0, u1, digits, evk, k.beta, level, g, st);
     launch_ntt_rows(ctx, A.u, k.d_sp_rows, k.d_sp_mods, 2 * ctx->K, true, st);
-    launch_base_conv(ctx, k.d_moddown, 2, 0, level + 1, A.conv, A.u, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr, st);
+    launch_base_conv(ctx, k.d_moddown, 2, 0, level + 1, A.conv, A.u, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr, 0, st);
     launch_ntt(ctx, A.conv, k.d_q_mods3, 2 * (level + 1), false, st);
-    launch_moddown_finish(ctx, out, A.u, A.conv, get_pinv(ctx, level), addend, addend_comps, level, addend ? g : 0, st);
+    launch_moddown_finish(ctx, out, A.u, A.conv, get_pinv(ctx, level), addend, addend_comps, level, addend ? g : 0, accum, st);
     return CM_OK;
 }
 u64 *arena_digits(const cm_ctx *ctx) { return arena_of(ctx).digits; }
@@ -201,11 +201,11 @@ cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, cons
                                  k.beta, level, gs[base + r], st);
         launch_ntt_rows(ctx, A.bu, k.d_bsp_rows, k.d_bsp_mods, m * 2 * ctx->K, true, st);
         launch_base_conv(ctx, k.d_moddown, 2 * m, 0, level + 1, A.bconv, A.bu, (size_t)k.ext * n,
-                         (size_t)(level + 1) * n, nullptr, st);
+                         (size_t)(level + 1) * n, nullptr, 0, st);
         launch_ntt(ctx, A.bconv, k.d_bq_mods, m * 2 * (level + 1), false, st);
         for (int r = 0; r < m; r++)
             launch_moddown_finish(ctx, outs[base + r], A.bu + r * ublk, A.bconv + r * cblk, get_pinv(ctx, level), in, 1,
-                                  level, gs[base + r], st);
+                                  level, gs[base + r], nullptr, st);
     }
     return CM_OK;
 }
@@ -556,12 +556,23 @@ extern "C" cm_status cm_level_drop(cm_ctx *ctx, const cm_ct *a, int32_t level, c
     return CM_OK;
 }
 
-cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64 g, u64 *out, hipStream_t st) {
+cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64 g, u64 *out, hipStream_t st,
+                      const u64 *accum) {
+    // Galois map first, key switch afterwards: the map is applied while reading (the inverse NTT of
+    // c1, the copy of the digits' own limbs, and the c0 added at the end), never as a pass of its own.
+    // The inner product sees already mapped digits, so it runs without permutation; the ModDown
+    // tail gathers c0 through the permutation.
     Arena A = arena_of(ctx);
-    const int limbs = level + 1;
-    launch_automorphism(ctx, A.tmp[0], in, 2 * limbs, g, st);
-    CMCHK(ks_raise(ctx, A.tmp[0] + (size_t)limbs * ctx->n, level, A.digits, st));
-    return ks_apply(ctx, A.digits, key, level, 0, A.tmp[0], 1, out, st);
+    CMCHK(ks_raise(ctx, in + (size_t)(level + 1) * ctx->n, level, A.digits, st, g));
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    const size_t n = ctx->n;
+    u64 *u0 = A.u, *u1 = A.u + (size_t)k.ext * n;
+    launch_inner_product(ctx, u0, u1, A.digits, key, k.beta, level, 0, st);
+    launch_ntt_rows(ctx, A.u, k.d_sp_rows, k.d_sp_mods, 2 * ctx->K, true, st);
+    launch_base_conv(ctx, k.d_moddown, 2, 0, level + 1, A.conv, A.u, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr, 0, st);
+    launch_ntt(ctx, A.conv, k.d_q_mods3, 2 * (level + 1), false, st);
+    launch_moddown_finish(ctx, out, A.u, A.conv, get_pinv(ctx, level), in, 1, level, g, accum, st);
+    return CM_OK;
 }
 extern "C" cm_status cm_rotate(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, int32_t step, cm_ct *out, void *stream) {
     if (!ctx || !evk || !ct_ok(ctx, in) || in->ncomp != 2 || !out || !out->dev) return CM_E_INVAL;
@@ -573,7 +584,13 @@ extern "C" cm_status cm_rotate(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, 
     } else {
         const u64 *key = find_key(evk, g);
         if (!key) return CM_E_NOKEY;
-        CMCHK(rotate_into(ctx, key, in->dev, in->level, g, out->dev, st));
+        if (out->dev == in->dev) {      // the last kernel gathers from `in`: go through a temporary
+            Arena A = arena_of(ctx);
+            CMCHK(rotate_into(ctx, key, in->dev, in->level, g, A.tmp[0], st));
+            HIPCHK(hipMemcpyAsync(out->dev, A.tmp[0], cm_ct_words(ctx, in->level, 2) * 8, hipMemcpyDeviceToDevice, st));
+        } else {
+            CMCHK(rotate_into(ctx, key, in->dev, in->level, g, out->dev, st));
+        }
     }
     out->level = in->level, out->ncomp = 2, out->scale = in->scale;
     return CM_OK;

@@ -8,6 +8,7 @@
 #include <math.h>
 
 #include <thread>
+#include <utility>
 
 #include "kernels.h"
 
@@ -200,12 +201,14 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     for (int r : p->reduce_steps) if (!key_of(r)) return CM_E_NOKEY;
 
     u64 *babies = p->d_work, *inner = babies + (size_t)p->r_i * ctw, *tmp = inner + (size_t)p->r_o * ctw;
-    // 1. preprocess: c <- c + Rot(c, 2^i (t-1))
-    u64 *c = babies;
+    // 1. preprocess: c <- c + Rot(c, 2^i (t-1)).  A rotate-and-add writes to the other of two buffers
+    //    (its last kernel gathers c0 of its input through the permutation, so it cannot run in
+    //    place); start in the one that leaves the result in baby slot 0.
+    u64 *c = (p->pre_steps.size() & 1) ? tmp : babies, *other = (p->pre_steps.size() & 1) ? babies : tmp;
     HIPCHK(hipMemcpyAsync(c, x->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
     for (int r : p->pre_steps) {
-        CMCHK(rotate_into(ctx, key_of(r), c, level, galois_of_step(ctx, r), tmp, st));
-        launch_add(ctx, c, c, tmp, 2, limbs, st);
+        CMCHK(rotate_into(ctx, key_of(r), c, level, galois_of_step(ctx, r), other, st, c));
+        std::swap(c, other);
     }
     // 2. baby steps: rotations of the same ciphertext share its raised digits
     if (p->r_i > 1) {
@@ -226,14 +229,15 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     //    giant steps, Horner form
     u64 *acc = inner + (size_t)(p->r_o - 1) * ctw;
     for (int k = p->r_o - 2; k >= 0; k--) {
-        CMCHK(rotate_into(ctx, key_of(p->giant_step), acc, level, galois_of_step(ctx, p->giant_step), tmp, st));
-        acc = inner + (size_t)k * ctw;
-        launch_add(ctx, acc, acc, tmp, 2, limbs, st);
+        u64 *nxt = inner + (size_t)k * ctw;                  // inner_k + Rot(acc), written over inner_k
+        CMCHK(rotate_into(ctx, key_of(p->giant_step), acc, level, galois_of_step(ctx, p->giant_step), nxt, st, nxt));
+        acc = nxt;
     }
-    // 3. reduce inside the ciphertext
+    // 3. reduce inside the ciphertext (two buffers again; baby slot 0 is free by now)
+    other = acc == babies ? tmp : babies;
     for (int r : p->reduce_steps) {
-        CMCHK(rotate_into(ctx, key_of(r), acc, level, galois_of_step(ctx, r), tmp, st));
-        launch_add(ctx, acc, acc, tmp, 2, limbs, st);
+        CMCHK(rotate_into(ctx, key_of(r), acc, level, galois_of_step(ctx, r), other, st, acc));
+        std::swap(acc, other);
     }
     CMCHK(rescale_into(ctx, acc, 2, level, y->dev, st));
     y->level = level - 1, y->ncomp = 2;
