@@ -125,6 +125,11 @@ struct cm_ctx {
     u64 *d_cdt = nullptr;                          // Gaussian table [CM_GAUSS_K]
     u64 cdt[CM_GAUSS_K];
     int lazy_terms;                                // products that may be summed before one REDC
+    // second stream for bandwidth-bound kernels that can run beside the transform chain, and a
+    // small ring of events to order the two (default priority, timing disabled)
+    hipStream_t aux = nullptr;
+    std::vector<hipEvent_t> sync_ev;
+    size_t sync_next = 0;
     // scratch arena
     u64 *arena = nullptr;
     size_t arena_words = 0;
@@ -162,6 +167,8 @@ struct cm_evk {
     } while (0)
 
 void cm_set_hip_error(int e);
+// order `waiter` after everything enqueued on `signaller` so far
+void stream_after(cm_ctx *ctx, hipStream_t waiter, hipStream_t signaller);
 
 struct Prof {
     cm_ctx *c;

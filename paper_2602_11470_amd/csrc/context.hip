@@ -26,6 +26,12 @@ extern "C" const char *cm_strerror(cm_status s) {
     return "unknown status";
 }
 
+void stream_after(cm_ctx *ctx, hipStream_t waiter, hipStream_t signaller) {
+    hipEvent_t e = ctx->sync_ev[ctx->sync_next++ % ctx->sync_ev.size()];
+    hipEventRecord(e, signaller);
+    hipStreamWaitEvent(waiter, e, 0);
+}
+
 // ---- kernel-family timing ---------------------------------------------------------------------------
 Prof::Prof(cm_ctx *ctx, int fam, double units, hipStream_t s) : c(ctx), st(s), e0(0), live(ctx->prof.on) {
     if (!live) return;
@@ -351,7 +357,7 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
     const int beta = (ctx->L + ctx->alpha) / ctx->alpha;
     size_t limbs = (size_t)(ctx->L + 1) + (size_t)beta * ext + 2 * (size_t)ext + 2 * (size_t)(ctx->L + 1) +
                    9 * (size_t)(ctx->L + 1) + 4 +
-                   (size_t)CM_KS_BATCH * 2 * (ext + ctx->L + 1);      // batched ModDown of hoisted rotations
+                   (size_t)CM_KS_BATCH * 2 * (2 * ext + ctx->L + 1);  // batched ModDown of hoisted rotations
     ctx->arena_words = limbs * n;
     if (hipMalloc((void **)&ctx->arena, ctx->arena_words * sizeof(u64)) != hipSuccess) ctx->arena = nullptr;
     if (!ctx->d_modc || !ctx->d_tw || !ctx->d_twp || !ctx->d_itw || !ctx->d_itwp || !ctx->d_ninv ||
@@ -359,6 +365,13 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
         cm_ctx_destroy(ctx);
         return CM_E_NOMEM;
     }
+    if (hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking) != hipSuccess) ctx->aux = nullptr;
+    for (int i = 0; i < 32 && ctx->aux; i++) {
+        hipEvent_t e;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { hipStreamDestroy(ctx->aux); ctx->aux = nullptr; break; }
+        ctx->sync_ev.push_back(e);
+    }
+    if (!ctx->aux) { cm_ctx_destroy(ctx); return CM_E_NOMEM; }
     // encode tables
     ctx->slot_pos.resize(n / 2);
     u64 g = 1;
@@ -381,6 +394,8 @@ extern "C" void cm_ctx_destroy(cm_ctx *ctx) {
     if (!ctx) return;
     cm_ops_forget_ctx(ctx);
     for (hipEvent_t e : ctx->prof.pool) hipEventDestroy(e);
+    for (hipEvent_t e : ctx->sync_ev) hipEventDestroy(e);
+    if (ctx->aux) hipStreamDestroy(ctx->aux);
     hipFree(ctx->d_modc);
     hipFree(ctx->d_tw);
     hipFree(ctx->d_twp);

@@ -24,7 +24,7 @@ void launch_sample_gauss(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs,
 void launch_evk_assemble(cm_ctx *ctx, u64 *b_out, u64 *a_io, const u64 *e, const u64 *s_mont, const u64 *d_fac, u64 g, hipStream_t st);
 void launch_encrypt(cm_ctx *ctx, u64 *c0, const u64 *a, const u64 *e, const u64 *s_mont, const u64 *pt, int limbs, hipStream_t st);
 void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int ncomp, int ct_limbs, int limbs, hipStream_t st);
-void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, hipStream_t st);
+void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, int k0, int k1, hipStream_t st);
 
 // ops.hip internals shared with vmm.hip
 struct KsLevel {            // cached per level: which rows of the digit array are converted / transformed

@@ -187,8 +187,11 @@ __global__ void k_inner_product(u64 *u0, u64 *u1, const u64 *dig, const u64 *evk
         ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(dig + ((size_t)j * ext + r) * n + base);
         u64 dx = swap ? d.y : d.x, dy = swap ? d.x : d.y;
         const u64 *kb = evk + (((size_t)j * 2 + 0) * nmod + mi) * n + i2;
-        ulonglong2 eb = *reinterpret_cast<const ulonglong2 *>(kb);
-        ulonglong2 ea = *reinterpret_cast<const ulonglong2 *>(kb + (size_t)nmod * n);
+        // the key is streamed once: non-temporal, so that the raised digits (re-read by every
+        // hoisted rotation) are the lines that stay in the last-level cache
+        ulonglong2 eb, ea;
+        eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
+        ea.x = __builtin_nontemporal_load(kb + (size_t)nmod * n), ea.y = __builtin_nontemporal_load(kb + (size_t)nmod * n + 1);
         b0 += (u128)dx * eb.x;
         b1 += (u128)dy * eb.y;
         a0 += (u128)dx * ea.x;
@@ -363,7 +366,8 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 // written exactly once); products are summed 8 at a time in 128 bits before each REDC.
 template <int RC>
 __global__ __launch_bounds__(TPB) void k_vmm_mac(u64 *out, const u64 *babies, const u64 *pts, const ModC *modc, int r_i,
-                                                 int r_o, int limbs, int n, size_t ct_stride, size_t pt_stride) {
+                                                 int r_o, int limbs, int n, size_t ct_stride, size_t pt_stride, int k0,
+                                                 int k1) {
     int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
     const ModC m = modc[l];
     size_t o = (size_t)l * n + i, cs = (size_t)limbs * n;
@@ -375,7 +379,7 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac(u64 *out, const u64 *babies, co
             c0[jj] = ok ? babies[(size_t)(j0 + jj) * ct_stride + o] : 0;
             c1[jj] = ok ? babies[(size_t)(j0 + jj) * ct_stride + cs + o] : 0;
         }
-        for (int k = 0; k < r_o; k++) {
+        for (int k = k0; k < k1; k++) {
             u64 v0 = 0, v1 = 0;
 #pragma unroll
             for (int s8 = 0; s8 < RC; s8 += 8) {
@@ -383,7 +387,7 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac(u64 *out, const u64 *babies, co
 #pragma unroll
                 for (int jj = s8; jj < s8 + 8; jj++) {
                     if (j0 + jj < r_i) {
-                        u64 p = pts[((size_t)(j0 + jj) * r_o + k) * pt_stride + o];
+                        u64 p = __builtin_nontemporal_load(pts + ((size_t)(j0 + jj) * r_o + k) * pt_stride + o);
                         s0 += (u128)c0[jj] * p;
                         s1 += (u128)c1[jj] * p;
                     }
@@ -401,14 +405,14 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac(u64 *out, const u64 *babies, co
         }
     }
 }
-void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, hipStream_t st) {
-    Prof prof_(ctx, CM_K_VMM_MAC, r_i * r_o, st);
+void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, int k0, int k1, hipStream_t st) {
+    Prof prof_(ctx, CM_K_VMM_MAC, r_i * (k1 - k0), st);
     dim3 grid(ctx->n / TPB, limbs), block(TPB);
     static int rc = getenv("CM_MAC_RC") ? atoi(getenv("CM_MAC_RC")) : 8;
     if (r_i > 16 && rc >= 32)
-        hipLaunchKernelGGL(k_vmm_mac<32>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride);
+        hipLaunchKernelGGL(k_vmm_mac<32>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride, k0, k1);
     else if (r_i > 8 && rc >= 16)
-        hipLaunchKernelGGL(k_vmm_mac<16>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride);
+        hipLaunchKernelGGL(k_vmm_mac<16>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride, k0, k1);
     else
-        hipLaunchKernelGGL(k_vmm_mac<8>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride);
+        hipLaunchKernelGGL(k_vmm_mac<8>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride, k0, k1);
 }

@@ -49,16 +49,18 @@ struct IntArith {
     __device__ __forceinline__ T from_rest(u64 raw) const { return raw; }     // canonical [0, q)
     __device__ __forceinline__ T from_mid(u64 raw) const { return raw; }
     __device__ __forceinline__ u64 to_mid(T v) const { return v; }
-    __device__ __forceinline__ void ct(T &X, T &Y, u64 idx) const {           // in, out below 4q
+    typedef u64 W;
+    __device__ __forceinline__ void load_tw(u64 idx, W &a, W &b) const { a = w[idx], b = wp[idx]; }
+    __device__ __forceinline__ void ct(T &X, T &Y, W a, W b) const {           // in, out below 4q
         u64 x = X >= q2 ? X - q2 : X;
-        u64 t = mul_shoup_lazy(Y, w[idx], wp[idx], q);
+        u64 t = mul_shoup_lazy(Y, a, b, q);
         X = x + t;
         Y = x - t + q2;
     }
-    __device__ __forceinline__ void gs(T &X, T &Y, u64 idx) const {           // in, out below 2q
+    __device__ __forceinline__ void gs(T &X, T &Y, W a, W b) const {           // in, out below 2q
         u64 s = X + Y, d = X - Y + q2;
         X = s >= q2 ? s - q2 : s;
-        Y = mul_shoup_lazy(d, w[idx], wp[idx], q);
+        Y = mul_shoup_lazy(d, a, b, q);
     }
     __device__ __forceinline__ u64 to_rest_fwd(T v) const {
         v = v >= q2 ? v - q2 : v;
@@ -91,15 +93,19 @@ struct FpArith {
     }
     __device__ __forceinline__ T from_mid(u64 raw) const { return __longlong_as_double((long long)raw); }
     __device__ __forceinline__ u64 to_mid(T v) const { return (u64)__double_as_longlong(v); }
-    __device__ __forceinline__ void ct(T &X, T &Y, u64 idx) const {           // |in|, |out| <= 1.54 q
-        double x = norm(X), r = mulmod(Y, w[idx], wq[idx]);
+    typedef double W;
+    __device__ __forceinline__ void load_tw(u64 idx, W &a, W &b) const { a = w[idx], b = wq[idx]; }
+    // With table twiddles (0 <= w < q, w/q correctly rounded) |r| <= 1.04 q; with generated ones
+    // (|w| <= 0.9 q, w/q taken as w * (1/q)) |r| <= 1.2 q.  Either way every value stays below 2.1 q.
+    __device__ __forceinline__ void ct(T &X, T &Y, W a, W b) const {
+        double x = norm(X), r = mulmod(Y, a, b);
         X = x + r;
         Y = x - r;
     }
-    __device__ __forceinline__ void gs(T &X, T &Y, u64 idx) const {           // |in|, |out| <= 1.04 q
+    __device__ __forceinline__ void gs(T &X, T &Y, W a, W b) const {
         double s = X + Y, d = X - Y;
         X = norm(s);
-        Y = mulmod(d, w[idx], wq[idx]);
+        Y = mulmod(d, a, b);
     }
     __device__ __forceinline__ u64 canon(double v) const {                     // |v| < 2^52  ->  [0, q)
         double r = __builtin_fma(-__builtin_floor(v * qinv), q, v);
@@ -111,40 +117,92 @@ struct FpArith {
     __device__ __forceinline__ u64 to_rest_inv(T v) const { return canon(mulmod(v, ni, niq)); }
 };
 
-// Four forward stages on 16 register values whose index k is the local position inside one
-// butterfly block of the first of these stages; base0 = 2^s0 + (block index at stage s0).
+// Twiddle providers for four stages starting at stage s0 with base0 = 2^s0 + (block index):
+// stage s0 + a, group g uses table entry (base0 << a) + g.
 template <class A>
-__device__ __forceinline__ void radix16_fwd(typename A::T (&v)[16], const A &ar, u64 base0) {
+struct TableTw {
+    const A &ar;
+    u64 base0;
+    __device__ __forceinline__ void get(int a, int g, typename A::W &w0, typename A::W &w1) const {
+        ar.load_tw((base0 << a) + g, w0, w1);
+    }
+};
+// The same entries computed from ONE table word (FP64 limbs): with T_a = tw[base0 << a],
+//   T_2 = T_3^2, T_1 = T_2^2, T_0 = T_1^2      (the exponent brev(base0) >> a doubles each time)
+//   tw[(base0 << a) + g] = T_a * tw[g]          (the low bits g reverse into the top of the exponent)
+// which removes almost all twiddle traffic of the last four stages, where every lane has its own 15.
+struct GenTw {
+    const FpArith &ar;
+    double T[4];
+    __device__ __forceinline__ GenTw(const FpArith &a_, u64 base0) : ar(a_) {
+        T[3] = ar.w[base0 << 3];
+        T[2] = ar.mulmod(T[3], T[3], T[3] * ar.qinv);
+        T[1] = ar.mulmod(T[2], T[2], T[2] * ar.qinv);
+        T[0] = ar.mulmod(T[1], T[1], T[1] * ar.qinv);
+    }
+    __device__ __forceinline__ void get(int a, int g, double &w0, double &w1) const {
+        w0 = g ? ar.mulmod(T[a], ar.w[g], ar.wq[g]) : T[a];
+        w1 = w0 * ar.qinv;
+    }
+};
+
+// Four forward stages on 16 register values whose index k is the local position inside one
+// butterfly block of the first of these stages.
+template <class A, class TW>
+__device__ __forceinline__ void radix16_fwd_tw(typename A::T (&v)[16], const A &ar, const TW &tw) {
 #pragma unroll
     for (int a = 0; a < 4; a++) {
         const int half = 8 >> a;
 #pragma unroll
         for (int g = 0; g < (1 << a); g++) {
-            u64 idx = (base0 << a) + g;
+            typename A::W w0, w1;
+            tw.get(a, g, w0, w1);
 #pragma unroll
             for (int j = 0; j < half; j++) {
                 int k = g * 2 * half + j;
-                ar.ct(v[k], v[k + half], idx);
+                ar.ct(v[k], v[k + half], w0, w1);
             }
         }
     }
 }
 // The inverse of the above (stages in the opposite order).
-template <class A>
-__device__ __forceinline__ void radix16_inv(typename A::T (&v)[16], const A &ar, u64 base0) {
+template <class A, class TW>
+__device__ __forceinline__ void radix16_inv_tw(typename A::T (&v)[16], const A &ar, const TW &tw) {
 #pragma unroll
     for (int a = 3; a >= 0; a--) {
         const int half = 8 >> a;
 #pragma unroll
         for (int g = 0; g < (1 << a); g++) {
-            u64 idx = (base0 << a) + g;
+            typename A::W w0, w1;
+            tw.get(a, g, w0, w1);
 #pragma unroll
             for (int j = 0; j < half; j++) {
                 int k = g * 2 * half + j;
-                ar.gs(v[k], v[k + half], idx);
+                ar.gs(v[k], v[k + half], w0, w1);
             }
         }
     }
+}
+template <class A>
+__device__ __forceinline__ void radix16_fwd(typename A::T (&v)[16], const A &ar, u64 base0) {
+    radix16_fwd_tw(v, ar, TableTw<A>{ar, base0});
+}
+template <class A>
+__device__ __forceinline__ void radix16_inv(typename A::T (&v)[16], const A &ar, u64 base0) {
+    radix16_inv_tw(v, ar, TableTw<A>{ar, base0});
+}
+// last four stages of the row pass: generated twiddles for FP64 limbs, table for the others
+__device__ __forceinline__ void radix16_fwd_last(double (&v)[16], const FpArith &ar, u64 base0) {
+    radix16_fwd_tw(v, ar, GenTw(ar, base0));
+}
+__device__ __forceinline__ void radix16_fwd_last(u64 (&v)[16], const IntArith &ar, u64 base0) {
+    radix16_fwd_tw(v, ar, TableTw<IntArith>{ar, base0});
+}
+__device__ __forceinline__ void radix16_inv_last(double (&v)[16], const FpArith &ar, u64 base0) {
+    radix16_inv_tw(v, ar, GenTw(ar, base0));
+}
+__device__ __forceinline__ void radix16_inv_last(u64 (&v)[16], const IntArith &ar, u64 base0) {
+    radix16_inv_tw(v, ar, TableTw<IntArith>{ar, base0});
 }
 
 // LDS index with one pad word per 16 so that lanes reading words 16 apart hit distinct banks
@@ -236,7 +294,7 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad(blk * 256 + 16 * sub + k)]);
-    radix16_fwd(v, ar, 4096 + B * 16 + sub);
+    radix16_fwd_last(v, ar, 4096 + B * 16 + sub);
     // lane owns 16 contiguous words: store as 8 x 16 bytes
     ulonglong2 *o = reinterpret_cast<ulonglong2 *>(p + blk * 256 + 16 * sub);
 #pragma unroll
@@ -266,7 +324,7 @@ __device__ __forceinline__ void rows256_inv_body(u64 *lds, u64 *p, const u64 *ps
             v[2 * k + 1] = ar.from_rest(x.y);
         }
     }
-    radix16_inv(v, ar, 4096 + B * 16 + sub);
+    radix16_inv_last(v, ar, 4096 + B * 16 + sub);
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[pad(blk * 256 + 16 * sub + k)] = ar.to_mid(v[k]);
     __syncthreads();

@@ -25,7 +25,7 @@ static Arena arena_of(const cm_ctx *ctx) {
     a.conv = p, p += 2 * q * n;
     for (int i = 0; i < 3; i++) a.tmp[i] = p, p += 3 * q * n;
     a.misc = p, p += 4 * n;
-    a.bu = p, p += (size_t)CM_KS_BATCH * 2 * ext * n;
+    a.bu = p, p += 2 * (size_t)CM_KS_BATCH * 2 * ext * n;      // two batches in flight
     a.bconv = p;
     return a;
 }
@@ -194,18 +194,42 @@ cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, cons
     const KsLevelFull &k = ks_level_full(ctx, level);
     Arena A = arena_of(ctx);
     const size_t n = ctx->n, ublk = 2 * (size_t)k.ext * n, cblk = 2 * (size_t)(level + 1) * n;
-    for (int base = 0; base < cnt; base += CM_KS_BATCH) {
-        const int m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
+    const size_t bufw = (size_t)CM_KS_BATCH * ublk;
+    // The inner products stream the keys (bandwidth-bound) on the second stream while the main
+    // stream runs the ModDown of the previous batch (transform-bound); two result buffers alternate.
+    hipStream_t aux = ctx->aux;
+    const int nbatch = (cnt + CM_KS_BATCH - 1) / CM_KS_BATCH;
+    std::vector<hipEvent_t> inner_done(nbatch), moddown_done(nbatch);
+    auto record = [&](hipStream_t s) {
+        hipEvent_t e = ctx->sync_ev[ctx->sync_next++ % ctx->sync_ev.size()];
+        hipEventRecord(e, s);
+        return e;
+    };
+    auto enqueue_inner = [&](int b) {
+        const int base = b * CM_KS_BATCH, m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
+        u64 *bu = A.bu + (b & 1) * bufw;
+        if (b >= 2) hipStreamWaitEvent(aux, moddown_done[b - 2], 0);     // its buffer has been consumed
         for (int r = 0; r < m; r++)
-            launch_inner_product(ctx, A.bu + r * ublk, A.bu + r * ublk + (size_t)k.ext * n, digits, keys[base + r],
-                                 k.beta, level, gs[base + r], st);
-        launch_ntt_rows(ctx, A.bu, k.d_bsp_rows, k.d_bsp_mods, m * 2 * ctx->K, true, st);
-        launch_base_conv(ctx, k.d_moddown, 2 * m, 0, level + 1, A.bconv, A.bu, (size_t)k.ext * n,
+            launch_inner_product(ctx, bu + r * ublk, bu + r * ublk + (size_t)k.ext * n, digits, keys[base + r],
+                                 k.beta, level, gs[base + r], aux);
+        inner_done[b] = record(aux);
+    };
+    if (nbatch > 16) return CM_E_INVAL;               // the event ring holds 32
+    stream_after(ctx, aux, st);                       // digits are ready
+    if (nbatch > 0) enqueue_inner(0);
+    for (int b = 0; b < nbatch; b++) {
+        if (b + 1 < nbatch) enqueue_inner(b + 1);     // runs beside the ModDown of batch b
+        const int base = b * CM_KS_BATCH, m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
+        u64 *bu = A.bu + (b & 1) * bufw;
+        hipStreamWaitEvent(st, inner_done[b], 0);
+        launch_ntt_rows(ctx, bu, k.d_bsp_rows, k.d_bsp_mods, m * 2 * ctx->K, true, st);
+        launch_base_conv(ctx, k.d_moddown, 2 * m, 0, level + 1, A.bconv, bu, (size_t)k.ext * n,
                          (size_t)(level + 1) * n, nullptr, 0, st);
         launch_ntt(ctx, A.bconv, k.d_bq_mods, m * 2 * (level + 1), false, st);
         for (int r = 0; r < m; r++)
-            launch_moddown_finish(ctx, outs[base + r], A.bu + r * ublk, A.bconv + r * cblk, get_pinv(ctx, level), in, 1,
+            launch_moddown_finish(ctx, outs[base + r], bu + r * ublk, A.bconv + r * cblk, get_pinv(ctx, level), in, 1,
                                   level, gs[base + r], nullptr, st);
+        moddown_done[b] = record(st);
     }
     return CM_OK;
 }
