@@ -90,6 +90,7 @@ struct ConvDev {
     int src_mod[CONV_MAX_SRC], in_rows[CONV_MAX_SRC];
     u64 inv_hat[CONV_MAX_SRC], inv_hat_sh[CONV_MAX_SRC];
     int dst_mod[CONV_MAX_DST], out_rows[CONV_MAX_DST];
+    u64 src_q[CONV_MAX_SRC], dst_q[CONV_MAX_DST], dst_qinv[CONV_MAX_DST];   // moduli and q^{-1} mod 2^64 inline
     u64 hat_mont[CONV_MAX_SRC * CONV_MAX_DST];      // [m * nt + r]
 };
 
@@ -128,6 +129,7 @@ struct cm_ctx {
     // second stream for bandwidth-bound kernels that can run beside the transform chain, and a
     // small ring of events to order the two (default priority, timing disabled)
     hipStream_t aux = nullptr;
+    bool overlap = true;           // CM_SERIAL=1 in the environment runs everything on the caller's stream
     std::vector<hipEvent_t> sync_ev;
     size_t sync_next = 0;
     // scratch arena
@@ -169,6 +171,7 @@ struct cm_evk {
 void cm_set_hip_error(int e);
 // order `waiter` after everything enqueued on `signaller` so far
 void stream_after(cm_ctx *ctx, hipStream_t waiter, hipStream_t signaller);
+inline hipStream_t aux_of(cm_ctx *ctx, hipStream_t st) { return ctx->overlap ? ctx->aux : st; }
 
 struct Prof {
     cm_ctx *c;

@@ -120,8 +120,10 @@ void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, 
 // that a conversion fills the machine.  If own_src is given, group 0 also copies the source rows
 // of own_src (the evaluation-domain input) to the same rows of the output.
 template <int CONV_TG>
-__global__ void k_base_conv(u64 *out, const u64 *in, const ConvDev *tabs, int tab_step, const ModC *modc, int n,
-                            size_t in_stride, size_t out_stride, const u64 *own_src, unsigned own_g, int logn) {
+__global__ __launch_bounds__(TPB) void k_base_conv(u64 *__restrict__ out, const u64 *__restrict__ in,
+                                                   const ConvDev *__restrict__ tabs, int tab_step, int n,
+                                                   size_t in_stride, size_t out_stride,
+                                                   const u64 *__restrict__ own_src, unsigned own_g, int logn) {
     const int i = blockIdx.x * TPB + threadIdx.x;
     const ConvDev &t = tabs[blockIdx.z * tab_step];
     const int ns = t.ns, nt = t.nt;
@@ -134,8 +136,7 @@ __global__ void k_base_conv(u64 *out, const u64 *in, const ConvDev *tabs, int ta
     for (int m = 0; m < CONV_MAX_SRC; m++) {
         y[m] = 0;
         if (m < ns) {
-            u64 q = modc[t.src_mod[m]].q;
-            y[m] = mul_shoup(in[(size_t)t.in_rows[m] * n + i], t.inv_hat[m], t.inv_hat_sh[m], q);
+            y[m] = mul_shoup(in[(size_t)t.in_rows[m] * n + i], t.inv_hat[m], t.inv_hat_sh[m], t.src_q[m]);
             if (own_src && r0 == 0)
                 out[(size_t)t.in_rows[m] * n + i] =
                     own_src[(size_t)t.in_rows[m] * n + (own_g ? perm_src((unsigned)i, own_g, logn) : (unsigned)i)];
@@ -145,12 +146,11 @@ __global__ void k_base_conv(u64 *out, const u64 *in, const ConvDev *tabs, int ta
     for (int rr = 0; rr < CONV_TG; rr++) {
         const int r = r0 + rr;
         if (r < nt) {
-            const ModC md = modc[t.dst_mod[r]];
             u128 acc = 0;
 #pragma unroll
             for (int m = 0; m < CONV_MAX_SRC; m++)
                 if (m < ns) acc += (u128)y[m] * t.hat_mont[m * nt + r];
-            out[(size_t)t.out_rows[r] * n + i] = redc(acc, md.q, md.qinv);
+            out[(size_t)t.out_rows[r] * n + i] = redc(acc, t.dst_q[r], t.dst_qinv[r]);
         }
     }
 }
@@ -160,7 +160,7 @@ void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_ste
     static int tg = getenv("CM_CONV_TG") ? atoi(getenv("CM_CONV_TG")) : 8;
 #define CONV_LAUNCH(TG)                                                                                              \
     hipLaunchKernelGGL(k_base_conv<TG>, dim3(ctx->n / TPB, (max_nt + TG - 1) / TG, batch), dim3(TPB), 0, st, out, in, \
-                       d_tabs, tab_step, ctx->d_modc, ctx->n, in_stride, out_stride, own_src, (unsigned)own_g, ctx->logn)
+                       d_tabs, tab_step, ctx->n, in_stride, out_stride, own_src, (unsigned)own_g, ctx->logn)
     if (tg == 2) CONV_LAUNCH(2);
     else if (tg == 8) CONV_LAUNCH(8);
     else if (tg == 12) CONV_LAUNCH(12);
@@ -173,7 +173,9 @@ void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_ste
 // extended basis.  With g != 0 the digits are read through the Galois permutation (hoisted
 // rotations).  Two adjacent coefficients per lane (16-byte accesses); the permutation keeps
 // aligned pairs together (it maps i^1 to src^1).
-__global__ void k_inner_product(u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, const ModC *modc,
+__global__ __launch_bounds__(TPB) void k_inner_product(u64 *__restrict__ u0, u64 *__restrict__ u1,
+                                                       const u64 *__restrict__ dig, const u64 *__restrict__ evk,
+                                                       const ModC *__restrict__ modc,
                                 int beta, int ext, int level, int L, int nmod, int n, int logn, unsigned g) {
     unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
     int r = blockIdx.y;
@@ -210,8 +212,9 @@ void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u
 
 // ---- ModDown tail: out = (u - conv) * P^{-1} (+ addend, optionally through the Galois map) ------------
 // batch (blockIdx.z) = component; u rows [ext][n], conv rows [level+1][n], out rows [level+1][n]
-__global__ void k_moddown_finish(u64 *out, const u64 *u, const u64 *conv, const u64 *pinv, const u64 *addend,
-                                 const ModC *modc, int n, int logn, unsigned g, size_t u_stride,
+__global__ __launch_bounds__(TPB) void k_moddown_finish(u64 *out, const u64 *__restrict__ u, const u64 *__restrict__ conv,
+                                 const u64 *__restrict__ pinv, const u64 *__restrict__ addend,
+                                 const ModC *__restrict__ modc, int n, int logn, unsigned g, size_t u_stride,
                                  size_t conv_stride, size_t out_stride, int addend_comp_only, const u64 *accum) {
     unsigned i = blockIdx.x * TPB + threadIdx.x;
     int l = blockIdx.y, c = blockIdx.z;
@@ -365,7 +368,8 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 // RC baby ciphertexts are register-resident per pass (one pass when r_i <= RC, so every output is
 // written exactly once); products are summed 8 at a time in 128 bits before each REDC.
 template <int RC>
-__global__ __launch_bounds__(TPB) void k_vmm_mac(u64 *out, const u64 *babies, const u64 *pts, const ModC *modc, int r_i,
+__global__ __launch_bounds__(TPB) void k_vmm_mac(u64 *__restrict__ out, const u64 *__restrict__ babies,
+                                                 const u64 *__restrict__ pts, const ModC *__restrict__ modc, int r_i,
                                                  int r_o, int limbs, int n, size_t ct_stride, size_t pt_stride, int k0,
                                                  int k1) {
     int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;

@@ -51,15 +51,20 @@ struct KsLevelFull : KsLevel {
     int modup_max_nt = 0;
 };
 
-static ConvDev conv_dev(const ConvTable &t, const std::vector<int> &in_rows, const std::vector<int> &out_rows) {
+static ConvDev conv_dev(const cm_ctx *ctx, const ConvTable &t, const std::vector<int> &in_rows,
+                        const std::vector<int> &out_rows) {
     ConvDev d;
     memset(&d, 0, sizeof(d));
     d.ns = t.ns, d.nt = t.nt;
     for (int m = 0; m < t.ns; m++) {
         d.src_mod[m] = t.src[m], d.in_rows[m] = in_rows[m];
         d.inv_hat[m] = t.inv_hat[m], d.inv_hat_sh[m] = t.inv_hat_sh[m];
+        d.src_q[m] = ctx->mod[t.src[m]];
     }
-    for (int r = 0; r < t.nt; r++) d.dst_mod[r] = t.dst[r], d.out_rows[r] = out_rows[r];
+    for (int r = 0; r < t.nt; r++) {
+        d.dst_mod[r] = t.dst[r], d.out_rows[r] = out_rows[r];
+        d.dst_q[r] = ctx->modc[t.dst[r]].q, d.dst_qinv[r] = ctx->modc[t.dst[r]].qinv;
+    }
     for (size_t i = 0; i < t.hat_mont.size(); i++) d.hat_mont[i] = t.hat_mont[i];
     return d;
 }
@@ -85,7 +90,7 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
             ntt_rows.push_back(j * k.ext + row);
             ntt_mods.push_back(idx);
         }
-        mu.push_back(conv_dev(tabs[j], digs[j], out_rows));
+        mu.push_back(conv_dev(ctx, tabs[j], digs[j], out_rows));
         k.modup_max_nt = std::max(k.modup_max_nt, tabs[j].nt);
     }
     k.d_modup = up(mu);
@@ -130,7 +135,7 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
     {
         std::vector<int> sp_in;
         for (int s = 0; s < ctx->K; s++) sp_in.push_back(level + 1 + s);
-        std::vector<ConvDev> md(1, conv_dev(get_moddown(ctx, level), sp_in, q_rows));
+        std::vector<ConvDev> md(1, conv_dev(ctx, get_moddown(ctx, level), sp_in, q_rows));
         k.d_moddown = up(md);
     }
     get_pinv(ctx, level);
@@ -197,7 +202,7 @@ cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, cons
     const size_t bufw = (size_t)CM_KS_BATCH * ublk;
     // The inner products stream the keys (bandwidth-bound) on the second stream while the main
     // stream runs the ModDown of the previous batch (transform-bound); two result buffers alternate.
-    hipStream_t aux = ctx->aux;
+    hipStream_t aux = aux_of(ctx, st);
     const int nbatch = (cnt + CM_KS_BATCH - 1) / CM_KS_BATCH;
     std::vector<hipEvent_t> inner_done(nbatch), moddown_done(nbatch);
     auto record = [&](hipStream_t s) {

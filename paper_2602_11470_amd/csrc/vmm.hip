@@ -236,11 +236,12 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     }
     bounds.push_back(0);
     std::vector<hipEvent_t> done(bounds.size() - 1);
-    stream_after(ctx, ctx->aux, st);               // baby ciphertexts are ready
+    hipStream_t aux = aux_of(ctx, st);
+    stream_after(ctx, aux, st);                    // baby ciphertexts are ready
     for (size_t g = 0; g + 1 < bounds.size(); g++) {
-        launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, limbs, ctw, ptw, bounds[g + 1], bounds[g], ctx->aux);
+        launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, limbs, ctw, ptw, bounds[g + 1], bounds[g], aux);
         done[g] = ctx->sync_ev[ctx->sync_next++ % ctx->sync_ev.size()];
-        hipEventRecord(done[g], ctx->aux);
+        hipEventRecord(done[g], aux);
     }
     size_t waited = 0;
     auto need = [&](int k) {                       // make st wait for the group that holds inner_k
