@@ -409,10 +409,68 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac(u64 *__restrict__ out, const u6
         }
     }
 }
+// The same product with the baby ciphertexts staged in LDS: a workgroup owns 64 coefficients of
+// one limb; its four waves take the k = k0 + wave, k0 + wave + 4, ... and every lane sums over all
+// j for its k, so each output is written once and each plaintext word is read once.  Up to 32
+// baby ciphertexts per pass (32 KiB of LDS); products are summed 8 at a time before a REDC.
+#define MAC_CO 64
+#define MAC_JC 32
+__global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, const u64 *__restrict__ babies,
+                                                     const u64 *__restrict__ pts, const ModC *__restrict__ modc,
+                                                     int r_i, int r_o, int limbs, int n, size_t ct_stride,
+                                                     size_t pt_stride, int k0, int k1) {
+    __shared__ u64 sb[MAC_JC * 2 * MAC_CO];
+    const int l = blockIdx.y, i0 = blockIdx.x * MAC_CO;
+    const int co = threadIdx.x & (MAC_CO - 1), kq = threadIdx.x >> 6;
+    const ModC m = modc[l];
+    const size_t o = (size_t)l * n + i0, cs = (size_t)limbs * n;
+    for (int j0 = 0; j0 < r_i; j0 += MAC_JC) {
+        const int jn = r_i - j0 < MAC_JC ? r_i - j0 : MAC_JC;
+        __syncthreads();
+        for (int e = threadIdx.x; e < jn * 2 * MAC_CO; e += TPB) {
+            int jc = e >> 6, c = e & (MAC_CO - 1);
+            sb[e] = babies[(size_t)(j0 + (jc >> 1)) * ct_stride + (jc & 1) * cs + o + c];
+        }
+        __syncthreads();
+        for (int k = k0 + kq; k < k1; k += 4) {
+            u64 v0 = 0, v1 = 0;
+            for (int j8 = 0; j8 < jn; j8 += 8) {
+                u64 p[8];
+#pragma unroll
+                for (int jj = 0; jj < 8; jj++)
+                    p[jj] = j8 + jj < jn
+                                ? __builtin_nontemporal_load(pts + ((size_t)(j0 + j8 + jj) * r_o + k) * pt_stride + o + co)
+                                : 0;
+                u128 s0 = 0, s1 = 0;
+#pragma unroll
+                for (int jj = 0; jj < 8; jj++) {
+                    if (j8 + jj < jn) {
+                        s0 += (u128)sb[((j8 + jj) * 2 + 0) * MAC_CO + co] * p[jj];
+                        s1 += (u128)sb[((j8 + jj) * 2 + 1) * MAC_CO + co] * p[jj];
+                    }
+                }
+                v0 = addmod(v0, redc(s0, m.q, m.qinv), m.q);
+                v1 = addmod(v1, redc(s1, m.q, m.qinv), m.q);
+            }
+            u64 *dst = out + (size_t)k * ct_stride + o + co;
+            if (j0) {
+                v0 = addmod(v0, dst[0], m.q);
+                v1 = addmod(v1, dst[cs], m.q);
+            }
+            dst[0] = v0;
+            dst[cs] = v1;
+        }
+    }
+}
 void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, int k0, int k1, hipStream_t st) {
     Prof prof_(ctx, CM_K_VMM_MAC, r_i * (k1 - k0), st);
     dim3 grid(ctx->n / TPB, limbs), block(TPB);
-    static int rc = getenv("CM_MAC_RC") ? atoi(getenv("CM_MAC_RC")) : 8;
+    static int rc = getenv("CM_MAC_RC") ? atoi(getenv("CM_MAC_RC")) : 0;
+    if (rc == 0) {
+        hipLaunchKernelGGL(k_vmm_mac_lds, dim3(ctx->n / MAC_CO, limbs), block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o,
+                           limbs, ctx->n, ct_stride, pt_stride, k0, k1);
+        return;
+    }
     if (r_i > 16 && rc >= 32)
         hipLaunchKernelGGL(k_vmm_mac<32>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride, k0, k1);
     else if (r_i > 8 && rc >= 16)

@@ -224,43 +224,16 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
         }
         CMCHK(ks_apply_many(ctx, digits, level, p->r_i - 1, keys.data(), gs.data(), c, dst.data(), st));
     }
-    //    multiply-accumulate: inner_k = sum_j baby_j * p_{j,k}.  It streams every weight plaintext
-    //    once (bandwidth-bound) and runs on the second stream in groups of k, highest first, beside
-    //    the giant-step chain (transform-bound), which consumes inner_k from the highest k down.
+    //    multiply-accumulate: inner_k = sum_j baby_j * p_{j,k}; streams every weight plaintext once
     const int r_o = p->r_o;
-    std::vector<int> bounds;                       // group g = [bounds[g+1], bounds[g])
-    bounds.push_back(r_o);
-    if (r_o > 2) {
-        bounds.push_back(r_o - 2);
-        if (r_o > 6) bounds.push_back((r_o - 2) / 2);
-    }
-    bounds.push_back(0);
-    std::vector<hipEvent_t> done(bounds.size() - 1);
-    hipStream_t aux = aux_of(ctx, st);
-    stream_after(ctx, aux, st);                    // baby ciphertexts are ready
-    for (size_t g = 0; g + 1 < bounds.size(); g++) {
-        launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, limbs, ctw, ptw, bounds[g + 1], bounds[g], aux);
-        done[g] = ctx->sync_ev[ctx->sync_next++ % ctx->sync_ev.size()];
-        hipEventRecord(done[g], aux);
-    }
-    size_t waited = 0;
-    auto need = [&](int k) {                       // make st wait for the group that holds inner_k
-        while (waited + 1 < bounds.size() && k < bounds[waited]) {
-            hipStreamWaitEvent(st, done[waited], 0);
-            waited++;
-            if (k >= bounds[waited]) break;
-        }
-    };
+    launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, limbs, ctw, ptw, 0, r_o, st);
     //    giant steps, Horner form
-    need(r_o - 1);
     u64 *acc = inner + (size_t)(r_o - 1) * ctw;
     for (int k = r_o - 2; k >= 0; k--) {
-        need(k);
         u64 *nxt = inner + (size_t)k * ctw;                  // inner_k + Rot(acc), written over inner_k
         CMCHK(rotate_into(ctx, key_of(p->giant_step), acc, level, galois_of_step(ctx, p->giant_step), nxt, st, nxt));
         acc = nxt;
     }
-    need(0);
     // 3. reduce inside the ciphertext (two buffers again; baby slot 0 is free by now)
     other = acc == babies ? tmp : babies;
     for (int r : p->reduce_steps) {
