@@ -26,6 +26,21 @@ void launch_encrypt(cm_ctx *ctx, u64 *c0, const u64 *a, const u64 *e, const u64 
 void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int ncomp, int ct_limbs, int limbs, hipStream_t st);
 void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, int k0, int k1, hipStream_t st);
 
+// Tail of a ModDown fused into the last pass of the forward transform of its converted limbs:
+// for item r, component c, limb l:  out = (u - NTT(conv)) * P^{-1} (+ addend through the Galois map
+// g_r on the first addend_comps components) (+ accum).  Passed to the kernel by value.
+struct FinishBatch {
+    int items = 0, level = 0, ext = 0, addend_comps = 0;
+    const u64 *u[CM_KS_BATCH];        // [2][ext][n] per item (evaluation domain)
+    u64 *out[CM_KS_BATCH];            // [2][level+1][n] per item
+    const u64 *accum[CM_KS_BATCH];    // nullable; may alias out
+    unsigned g[CM_KS_BATCH];
+    const u64 *addend = nullptr;      // [2][level+1][n], nullable; must not alias any out
+    const u64 *pinv = nullptr;        // [level+1][2]: P^{-1} mod q_l and its Shoup companion
+};
+// forward transform of conv[items*2*(level+1)][n] (mods 0..level repeating) with that tail; n = 65536 only
+void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const FinishBatch &fb, hipStream_t st);
+
 // ops.hip internals shared with vmm.hip
 struct KsLevel {            // cached per level: which rows of the digit array are converted / transformed
     int level, ext, beta;

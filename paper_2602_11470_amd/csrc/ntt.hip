@@ -280,7 +280,8 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_cols_inv(u64 *__restrict__ da
 
 // ---- row passes on contiguous blocks of 256 words (n = 65536): a workgroup owns 16 blocks ---------------
 template <class A>
-__device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTables &t, int mi, int n, int chunk) {
+__device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTables &t, int mi, int n, int chunk,
+                                                 int limb, const FinishBatch &fb) {
     A ar;
     ar.init(t, mi, n);
     const int sub = threadIdx.x & 15, blk = threadIdx.x >> 4;
@@ -295,10 +296,37 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
 #pragma unroll
     for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad(blk * 256 + 16 * sub + k)]);
     radix16_fwd_last(v, ar, 4096 + B * 16 + sub);
-    // lane owns 16 contiguous words: store as 8 x 16 bytes
-    ulonglong2 *o = reinterpret_cast<ulonglong2 *>(p + blk * 256 + 16 * sub);
+    // Each lane now owns 16 contiguous words.  One more trip through LDS hands every lane the words
+    // tid, tid + 256, ... of the tile instead, so that all global traffic below is coalesced.
+    __syncthreads();
 #pragma unroll
-    for (int k = 0; k < 8; k++) o[k] = make_ulonglong2(ar.to_rest_fwd(v[2 * k]), ar.to_rest_fwd(v[2 * k + 1]));
+    for (int k = 0; k < 16; k++) lds[pad(blk * 256 + 16 * sub + k)] = ar.to_rest_fwd(v[k]);
+    __syncthreads();
+    if (fb.items == 0) {
+#pragma unroll
+        for (int k = 0; k < 16; k++) p[threadIdx.x + 256 * k] = lds[pad(threadIdx.x + 256 * k)];
+        return;
+    }
+    // fused ModDown tail: this limb is NTT(conv) of item r, component c, limb l
+    const int per = 2 * (fb.level + 1);
+    const int r = limb / per, c = (limb % per) / (fb.level + 1), l = limb % (fb.level + 1);
+    const u64 q = t.modc[l].q, pi = fb.pinv[2 * l], pis = fb.pinv[2 * l + 1];
+    const unsigned pos0 = (unsigned)chunk * 4096 + threadIdx.x;
+    const size_t row = ((size_t)c * (fb.level + 1) + l) * n;
+    const u64 *up = fb.u[r] + ((size_t)c * fb.ext + l) * n + pos0;
+    const u64 *ad = (fb.addend && c < fb.addend_comps) ? fb.addend + row : nullptr;
+    const u64 *ac = fb.accum[r] ? fb.accum[r] + row + pos0 : nullptr;
+    u64 *op = fb.out[r] + row + pos0;
+    const unsigned g = fb.g[r];
+    const int logn = 31 - __clz(n);
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+        u64 d = submod(up[256 * k], lds[pad(threadIdx.x + 256 * k)], q);
+        u64 x = mul_shoup(d, pi, pis, q);
+        if (ad) x = addmod(x, ad[g ? perm_src(pos0 + 256 * k, g, logn) : pos0 + 256 * k], q);
+        if (ac) x = addmod(x, ac[256 * k], q);
+        op[256 * k] = x;
+    }
 }
 template <class A>
 __device__ __forceinline__ void rows256_inv_body(u64 *lds, u64 *p, const u64 *ps, const u64 *psrow, unsigned g,
@@ -308,21 +336,17 @@ __device__ __forceinline__ void rows256_inv_body(u64 *lds, u64 *p, const u64 *ps
     const int sub = threadIdx.x & 15, blk = threadIdx.x >> 4;
     const u64 B = (u64)chunk * 16 + blk;
     typename A::T v[16];
-    if (g) {
-        // read through the Galois permutation: the 16 positions of this lane come from one aligned
-        // block of 16 words of the source row
-        const unsigned pos = (unsigned)chunk * 4096 + blk * 256 + 16 * sub;
+    // coalesced load (through the Galois permutation if g != 0: a run of 64 positions maps onto one
+    // aligned run of 64), then every lane picks its 16 contiguous words from LDS
+    {
         const int logn = 31 - __clz(n);
+        const unsigned pos0 = (unsigned)chunk * 4096 + threadIdx.x;
 #pragma unroll
-        for (int k = 0; k < 16; k++) v[k] = ar.from_rest(psrow[perm_src(pos + k, g, logn)]);
-    } else {
-        const ulonglong2 *in = reinterpret_cast<const ulonglong2 *>(ps + blk * 256 + 16 * sub);
+        for (int k = 0; k < 16; k++)
+            lds[pad(threadIdx.x + 256 * k)] = g ? psrow[perm_src(pos0 + 256 * k, g, logn)] : ps[threadIdx.x + 256 * k];
+        __syncthreads();
 #pragma unroll
-        for (int k = 0; k < 8; k++) {
-            ulonglong2 x = in[k];
-            v[2 * k] = ar.from_rest(x.x);
-            v[2 * k + 1] = ar.from_rest(x.y);
-        }
+        for (int k = 0; k < 16; k++) v[k] = ar.from_rest(lds[pad(blk * 256 + 16 * sub + k)]);
     }
     radix16_inv_last(v, ar, 4096 + B * 16 + sub);
 #pragma unroll
@@ -336,16 +360,17 @@ __device__ __forceinline__ void rows256_inv_body(u64 *lds, u64 *p, const u64 *ps
 }
 // grid.x = limbs * n/4096
 __global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_fwd(u64 *__restrict__ data, const int *__restrict__ rows,
-                                                              const int *__restrict__ mod_idx, NttTables t, int n) {
+                                                              const int *__restrict__ mod_idx, NttTables t, int n,
+                                                              FinishBatch fb) {
     __shared__ u64 lds[LDS_WORDS];
     const int per = n >> 12;
     const int limb = blockIdx.x / per, chunk = blockIdx.x % per;
     const int mi = mod_idx[limb];
     u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + (size_t)chunk * 4096;
     if (t.fpq[mi].q != 0.0)
-        rows256_fwd_body<FpArith>(lds, p, t, mi, n, chunk);
+        rows256_fwd_body<FpArith>(lds, p, t, mi, n, chunk, limb, fb);
     else
-        rows256_fwd_body<IntArith>(lds, p, t, mi, n, chunk);
+        rows256_fwd_body<IntArith>(lds, p, t, mi, n, chunk, limb, fb);
 }
 __global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_inv(u64 *__restrict__ data, const u64 *__restrict__ src,
                                                               const int *__restrict__ src_rows,
@@ -439,7 +464,7 @@ void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, c
         t.ninv = t.ninvp = nullptr, t.ninvd = t.ninvqd = nullptr;
         hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, t, n, n2);
         if (n2 == 256)
-            hipLaunchKernelGGL(ntt_rows256_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, t, n);
+            hipLaunchKernelGGL(ntt_rows256_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, t, n, FinishBatch());
         else
             hipLaunchKernelGGL(ntt_rows16_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, t, n);
     } else {
@@ -453,6 +478,19 @@ void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, c
                                (unsigned)g);
         hipLaunchKernelGGL(ntt_cols_inv, grid, block, 0, st, data, d_rows, d_mod_idx, t, n, n2);
     }
+}
+void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const FinishBatch &fb, hipStream_t st) {
+    const int limbs = fb.items * 2 * (fb.level + 1), n = ctx->n;
+    if (limbs <= 0) return;
+    Prof prof_(ctx, CM_K_NTT_FWD, limbs, st);
+    dim3 grid((unsigned)limbs * (n >> 12)), block(NTT_THREADS);
+    NttTables t;
+    t.modc = ctx->d_modc, t.fpq = ctx->d_fpq;
+    t.tw = ctx->d_tw, t.twp = ctx->d_twp, t.twd = ctx->d_twd, t.twqd = ctx->d_twqd;
+    t.ninv = t.ninvp = nullptr, t.ninvd = t.ninvqd = nullptr;
+    hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, conv, (const u64 *)nullptr, (const int *)nullptr,
+                       (const int *)nullptr, d_mods, t, n, n >> 8);
+    hipLaunchKernelGGL(ntt_rows256_fwd, grid, block, 0, st, conv, (const int *)nullptr, d_mods, t, n, fb);
 }
 void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mod_idx, int limbs,
                      bool inverse, hipStream_t st) {

@@ -185,6 +185,14 @@ cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u6
     launch_inner_product(ctx, u0, u1, digits, evk, k.beta, level, g, st);
     launch_ntt_rows(ctx, A.u, k.d_sp_rows, k.d_sp_mods, 2 * ctx->K, true, st);
     launch_base_conv(ctx, k.d_moddown, 2, 0, level + 1, A.conv, A.u, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr, 0, st);
+    if (ctx->n == 65536) {
+        FinishBatch fb;
+        fb.items = 1, fb.level = level, fb.ext = k.ext, fb.addend_comps = addend ? addend_comps : 0;
+        fb.u[0] = A.u, fb.out[0] = out, fb.accum[0] = accum, fb.g[0] = addend ? (unsigned)g : 0;
+        fb.addend = addend, fb.pinv = get_pinv(ctx, level);
+        launch_ntt_fwd_finish(ctx, A.conv, k.d_q_mods3, fb, st);
+        return CM_OK;
+    }
     launch_ntt(ctx, A.conv, k.d_q_mods3, 2 * (level + 1), false, st);
     launch_moddown_finish(ctx, out, A.u, A.conv, get_pinv(ctx, level), addend, addend_comps, level, addend ? g : 0, accum, st);
     return CM_OK;
@@ -230,10 +238,19 @@ cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, cons
         launch_ntt_rows(ctx, bu, k.d_bsp_rows, k.d_bsp_mods, m * 2 * ctx->K, true, st);
         launch_base_conv(ctx, k.d_moddown, 2 * m, 0, level + 1, A.bconv, bu, (size_t)k.ext * n,
                          (size_t)(level + 1) * n, nullptr, 0, st);
-        launch_ntt(ctx, A.bconv, k.d_bq_mods, m * 2 * (level + 1), false, st);
-        for (int r = 0; r < m; r++)
-            launch_moddown_finish(ctx, outs[base + r], bu + r * ublk, A.bconv + r * cblk, get_pinv(ctx, level), in, 1,
-                                  level, gs[base + r], nullptr, st);
+        if (ctx->n == 65536) {
+            FinishBatch fb;
+            fb.items = m, fb.level = level, fb.ext = k.ext, fb.addend_comps = 1;
+            for (int r = 0; r < m; r++)
+                fb.u[r] = bu + r * ublk, fb.out[r] = outs[base + r], fb.accum[r] = nullptr, fb.g[r] = (unsigned)gs[base + r];
+            fb.addend = in, fb.pinv = get_pinv(ctx, level);
+            launch_ntt_fwd_finish(ctx, A.bconv, k.d_bq_mods, fb, st);
+        } else {
+            launch_ntt(ctx, A.bconv, k.d_bq_mods, m * 2 * (level + 1), false, st);
+            for (int r = 0; r < m; r++)
+                launch_moddown_finish(ctx, outs[base + r], bu + r * ublk, A.bconv + r * cblk, get_pinv(ctx, level), in, 1,
+                                      level, gs[base + r], nullptr, st);
+        }
         moddown_done[b] = record(st);
     }
     return CM_OK;
@@ -599,6 +616,14 @@ cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64
     launch_inner_product(ctx, u0, u1, A.digits, key, k.beta, level, 0, st);
     launch_ntt_rows(ctx, A.u, k.d_sp_rows, k.d_sp_mods, 2 * ctx->K, true, st);
     launch_base_conv(ctx, k.d_moddown, 2, 0, level + 1, A.conv, A.u, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr, 0, st);
+    if (ctx->n == 65536) {
+        FinishBatch fb;
+        fb.items = 1, fb.level = level, fb.ext = k.ext, fb.addend_comps = 1;
+        fb.u[0] = A.u, fb.out[0] = out, fb.accum[0] = accum, fb.g[0] = (unsigned)g;
+        fb.addend = in, fb.pinv = get_pinv(ctx, level);
+        launch_ntt_fwd_finish(ctx, A.conv, k.d_q_mods3, fb, st);
+        return CM_OK;
+    }
     launch_ntt(ctx, A.conv, k.d_q_mods3, 2 * (level + 1), false, st);
     launch_moddown_finish(ctx, out, A.u, A.conv, get_pinv(ctx, level), in, 1, level, g, accum, st);
     return CM_OK;
