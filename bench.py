@@ -27,6 +27,20 @@ HBM_PEAK_GBS = 8000.0
 D = 4096
 
 
+def measured_traffic():
+    """HBM bytes per unit from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE scaled
+    by the copy-kernel calibration stated there); keys: 'k_inner_product' (per launch) and
+    'ntt_fwd_per_limb'.  Empty if the summary is missing."""
+    out = {}
+    path = os.path.join(ROOT, "profiles", "pmc_hbm_traffic_bench_config2.txt")
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("traffic_bytes "):
+                _, key, val = line.split()
+                out[key.rstrip(":")] = float(val)
+    return out
+
+
 def gpu_setup():
     import torch
     from paper_2602_11470_amd import binding as B, inputs
@@ -156,13 +170,16 @@ def main():
     ext = limbs + K
     ip_bytes = limb_bytes * (2 * beta * ext + beta * ext + 2 * ext)      # key + raised digits + result
     ip_gbs = ip_bytes / ip_launch_s / 1e9
+    tr = measured_traffic()
+    ntt_traffic = tr["ntt_fwd_per_limb"] * ntt_per_launch_limbs if "ntt_fwd_per_limb" in tr else None
     roofs = {
         "ntt_fwd": {"bound": "hbm", "achieved": ntt_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": ntt_gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "ntt_cols_fwd+ntt_rows256_fwd",
+                    "frac": ntt_gbs / HBM_PEAK_GBS, "traffic": ntt_traffic,
+                    "kernel": "ntt_cols_fwd+ntt_rows256_fwd (one launch of the pair)",
                     "limbs_per_launch": ntt_per_launch_limbs, "us_per_launch": ntt_launch_s * 1e6},
         "inner_product": {"bound": "hbm", "achieved": ip_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                          "frac": ip_gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "k_inner_product",
-                          "us_per_launch": ip_launch_s * 1e6},
+                          "frac": ip_gbs / HBM_PEAK_GBS, "traffic": tr.get("k_inner_product"),
+                          "kernel": "k_inner_product", "us_per_launch": ip_launch_s * 1e6},
     }
     roofline = roofs.get(dom, roofs["ntt_fwd"])
     ks_bytes = limb_bytes * (2 * beta * ext + limbs + 2 * limbs)         # key once + input + output

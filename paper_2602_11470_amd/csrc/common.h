@@ -129,7 +129,8 @@ struct cm_ctx {
     // second stream for bandwidth-bound kernels that can run beside the transform chain, and a
     // small ring of events to order the two (default priority, timing disabled)
     hipStream_t aux = nullptr;
-    bool overlap = true;           // CM_SERIAL=1 in the environment runs everything on the caller's stream
+    bool overlap = false;          // CM_OVERLAP=1 in the environment puts the key-streaming inner products of hoisted
+                                   // rotations on a second stream (measured: no gain, the step is bandwidth-bound)
     std::vector<hipEvent_t> sync_ev;
     size_t sync_next = 0;
     // scratch arena

@@ -372,7 +372,7 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
         ctx->sync_ev.push_back(e);
     }
     if (!ctx->aux) { cm_ctx_destroy(ctx); return CM_E_NOMEM; }
-    ctx->overlap = !getenv("CM_SERIAL");
+    ctx->overlap = getenv("CM_OVERLAP") != nullptr;
     // encode tables
     ctx->slot_pos.resize(n / 2);
     u64 g = 1;
