@@ -119,6 +119,43 @@ def test_config2_packed_product_decrypts_to_float64_product(ring2):
     assert np.abs(out4.real[::t] - x @ W).max() < TOL
 
 
+def test_config3_attention_shapes_decrypt_to_float64_products(ring2):
+    """Llama-3-8B attention shapes on the full ring: 32 heads x 128 dims (8 KV heads repeated 4x),
+    t = 8 tokens per K ciphertext, 128 V ciphertexts with 16 baby x 8 giant steps.  A short
+    context (two loaded K ciphertexts plus three appended tokens) keeps the run small; every
+    ciphertext and rotation has its full size."""
+    from oracle import packing
+    from paper_2602_11470_amd import inputs
+    B, octx, gctx, prm = ring2
+    H, E, L = 32, 128, gctx.L
+    lay = packing.KvLayout(gctx.S, H, E, 16)
+    assert lay.t == 8 and lay.capacity == 1024
+    n_loaded, n_app = 16, 3
+    ntok = n_loaded + n_app
+    q, K, V, s = inputs.attention_inputs(3, H, 8, E, ntok)
+    lv = L - 1
+    kv = gctx.kv_create(H, E, lv, r_i=16)
+    gsk = gctx.keygen_secret(1)
+    gkeys = gctx.keygen_rotations(gsk, kv.steps(), 2, with_relin=True)
+    enc = lambda slots, level, seed: gctx.level_drop(gctx.encrypt(gsk, gctx.encode(slots, L), seed), level)
+    for c in range(n_loaded // lay.t):
+        kv.load(B.CM_QK, c, enc(lay.pack_k(K[:n_loaded], c), lv, 100 + c))
+    for k in range(E):
+        kv.load(B.CM_SV, k, enc(lay.pack_v(V[:n_loaded], k), lv, 300 + k))
+    kv.set_tokens(n_loaded)
+    for n in range(n_loaded, ntok):
+        tau = n % lay.t
+        kv.append(gkeys, enc(lay.pack_vec(K[n], tau), L, 600 + n), enc(lay.pack_vec(V[n], tau), L, 700 + n))
+    assert kv.tokens() == ntok
+    gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, enc(lay.pack_vec(q), lv, 10))
+    assert gm.level == lv - 2
+    got = lay.unpack_scores(gctx.decrypt(gsk, gm).real, ntok)
+    assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
+    ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, enc(lay.pack_scores(s), lv, 50))
+    assert ga.level == lv - 1
+    assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
+
+
 def test_config5_ring_rotation(ring2):
     """36 + 6 primes (6 digits of 6): one full key switch element by element."""
     ring2[2].close()                                 # free the first context's device memory
