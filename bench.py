@@ -103,6 +103,16 @@ def time_rotations(g, reps=20):
     return (time.perf_counter() - t0) / reps
 
 
+def calibration_kernel(g):
+    """One launch of a plain streaming kernel of known size outside the timed region: the sum of two
+    distinct top-level ciphertexts (k_add: reads 2 x 24 MiB, writes 24 MiB).  Counter profiles of
+    this script scale FETCH_SIZE / WRITE_SIZE by what they read for this launch."""
+    ctx = g["ctx"]
+    r = ctx.rotate(g["keys"], g["ct"], 7)
+    ctx.add(g["ct"], r)
+    g["torch"].cuda.synchronize()
+
+
 def cpu_baseline():
     """The oracle as it stands on the host cores, on a bounded sample of the same workload: the
     ring of the benchmark, 3 full rotations, one hoisting + 3 hoisted rotations, 8 plaintext
@@ -156,6 +166,7 @@ def main():
         sys.exit(1)
     fam = kernel_profile(g, min(a.steps, 5))
     t_rot = time_rotations(g)
+    calibration_kernel(g)
     n, limbs, K, beta = g["ctx"].n, 24, 4, 6
     limb_bytes = 8 * n
     # dominant kernel family of the step by time
