@@ -447,3 +447,71 @@ class Context:
         c0 = self.automorphism(x.c[0], idx, g)
         return Ct([self.add(c0, self.moddown(u0, x.level), idx), self.moddown(u1, x.level)],
                   x.level, x.scale)
+
+    # ---- accumulation in the raised basis (double hoisting) -----------------------------------
+    # App. C notes that more than half of the rotations of the packed product act on one
+    # ciphertext and can share their ModUp; the paper does not say where their ModDown goes.
+    # The reading taken here postpones it: a hoisted rotation is left in the extended basis
+    # (q_0..q_level, p_0..p_{K-1}) as
+    #       R = (u0 + P * sigma(c0),  u1),        ModDown(R) = rotate_hoisted(x) exactly,
+    # the plaintext products are summed there, and the division by P happens once per giant
+    # step, inside that step's own key switch (ModDown is additive up to rounding).
+    def _P(self):
+        P = 1
+        for m in self.prm.p:
+            P *= m
+        return P
+
+    def pt_from_coeffs_ext(self, coeffs, level, scale) -> Pt:
+        """The plaintext polynomial on all limbs of the extended basis at `level`."""
+        ext = self.ext_idx(level)
+        return Pt(self.ntt(self.from_i64(coeffs, ext), ext), level, scale)
+
+    def encode_ext(self, z, level, scale=None) -> Pt:
+        scale = self.prm.scale if scale is None else scale
+        return self.pt_from_coeffs_ext(self.encode_coeffs(z, scale), level, scale)
+
+    def raise_ct(self, x: Ct):
+        """(P c0, P c1) in the extended basis: residues P*c mod q_i, zero on the special limbs."""
+        assert len(x.c) == 2
+        ext, nq = self.ext_idx(x.level), x.level + 1
+        P = self._P()
+        out = []
+        for c in x.c:
+            full = np.zeros((len(ext), self.n), dtype=np.uint64)
+            full[:nq] = self.mul_scalar(c, [P] * nq, self.q_idx(x.level))
+            out.append(full)
+        return out
+
+    def rotate_hoisted_raised(self, x: Ct, hoisted, r, keys):
+        """The hoisted rotation by r before its ModDown: [u0 + P sigma(c0), u1], each [ext][n]."""
+        g, idx, ext = self.galois(r), self.q_idx(x.level), self.ext_idx(x.level)
+        self.rot_count += 1
+        digits = [self.ntt(self.automorphism_coeff(d, ext, g), ext) for d in hoisted]
+        u0, u1 = self.inner_product(digits, keys[g], x.level)
+        nq = x.level + 1
+        u0[:nq] = self.add(u0[:nq], self.mul_scalar(self.automorphism(x.c[0], idx, g), [self._P()] * nq, idx), idx)
+        return [u0, u1]
+
+    def mac_pt_raised(self, acc, R, pt: Pt, level):
+        """acc += R * pt on the extended basis (acc, R: two [ext][n] arrays; pt from *_ext)."""
+        ext = self.ext_idx(level)
+        self.ptmul_count += 1
+        for a, c in zip(acc, R):
+            self.mac(a, c, pt.m, ext)
+
+    def moddown_ct(self, R, level, scale) -> Ct:
+        return Ct([self.moddown(R[0], level), self.moddown(R[1], level)], level, scale)
+
+    def rotate_add_raised(self, x: Ct, r, keys, E) -> Ct:
+        """Rot(x, r) + ModDown(E) with one ModDown: E (two [ext][n] arrays) joins the key-switch
+        sum before the division by P."""
+        assert len(x.c) == 2
+        g, idx, ext = self.galois(r), self.q_idx(x.level), self.ext_idx(x.level)
+        self.rot_count += 1
+        c0 = self.automorphism(x.c[0], idx, g)
+        c1 = self.automorphism(x.c[1], idx, g)
+        digits = [self.ntt(d, ext) for d in self.modup(self.intt(c1, idx), x.level)]
+        u0, u1 = self.inner_product(digits, keys[g], x.level)
+        u0, u1 = self.add(u0, E[0], ext), self.add(u1, E[1], ext)
+        return Ct([self.add(c0, self.moddown(u0, x.level), idx), self.moddown(u1, x.level)], x.level, x.scale)

@@ -106,6 +106,33 @@ def vmm_pt(ops, plan: VmmPlan, cx, diagonals):
     return ops.rescale(acc)
 
 
+def vmm_pt_double_hoisted(ctx, keys, plan: VmmPlan, cx, diagonals_ext):
+    """Algorithm 1 (App. C) with the baby-step sums kept in the extended basis: the same
+    rotations and plaintext products as vmm_pt, but the r_i - 1 hoisted rotations are not
+    divided by P one by one; their weighted sums inner_k live on (q_0..q_l, p_0..p_{K-1}) and
+    each is divided by P inside the giant step that consumes it.  diagonals_ext[j][k] are the
+    weight plaintexts on the extended basis (Context.encode_ext / pt_from_coeffs_ext)."""
+    c = cx
+    for r in plan.pre_steps:
+        c = ctx.ct_add(c, ctx.rotate(c, r, keys))
+    hoisted = ctx.hoist(c)
+    raised = [ctx.raise_ct(c)] + [ctx.rotate_hoisted_raised(c, hoisted, r, keys) for r in plan.baby_steps[1:]]
+    ext = ctx.ext_idx(c.level)
+    inner = []
+    for k in range(plan.r_o):
+        acc = [np.zeros((len(ext), ctx.n), dtype=np.uint64) for _ in range(2)]
+        for j in range(plan.r_i):
+            ctx.mac_pt_raised(acc, raised[j], diagonals_ext[j][k], c.level)
+        inner.append(acc)
+    scale = c.scale * diagonals_ext[0][0].scale
+    acc = ctx.moddown_ct(inner[plan.r_o - 1], c.level, scale)
+    for k in range(plan.r_o - 2, -1, -1):
+        acc = ctx.rotate_add_raised(acc, plan.giant_step, keys, inner[k])
+    for r in plan.reduce_steps:
+        acc = ctx.ct_add(acc, ctx.rotate(acc, r, keys))
+    return ctx.rescale(acc)
+
+
 def qk_scores(ops, lay: KvLayout, cq, k_cts, masks):
     """Sec. 5.1 with the multi-head layout of Sec. 5.3: scores of one query against the K
     cache.  masks[c] = lay.qk_mask(c) (slot vector or encoded plaintext)."""

@@ -76,3 +76,82 @@ def test_small_ring_attention_and_append(r_i):
     a = vmm.score_times_v(ops, lay, cs, vc)
     assert a.level == L - 2
     assert np.abs(lay.unpack_vec(ctx.decrypt(sk, a).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
+
+
+# ---- accumulation in the raised basis (double hoisting) -----------------------------------------
+def _toy_ctx():
+    prm = params.toy(n=512, n_qi=4, n_p=2, alpha=2, hamming=32)
+    ctx = ckks.Context(prm)
+    sk = ctx.keygen_secret(1)
+    return prm, ctx, sk
+
+
+def test_raised_rotation_divides_back_to_the_hoisted_rotation_exactly():
+    """ModDown(u + P a) = ModDown(u) + a limb for limb (P a vanishes on the special limbs), so the
+    raised forms must reproduce the ordinary operations bit for bit."""
+    prm, ctx, sk = _toy_ctx()
+    keys = ctx.keygen_rotations(sk, [3, 20], 2)
+    z = np.random.default_rng(0).normal(size=ctx.S)
+    for level in (prm.L, 2):
+        x = ctx.level_drop(ctx.encrypt(sk, ctx.encode(z, prm.L), 3), level)
+        back = ctx.moddown_ct(ctx.raise_ct(x), level, x.scale)
+        assert all(np.array_equal(a, b) for a, b in zip(back.c, x.c))
+        h = ctx.hoist(x)
+        for r in (3, 20):
+            want = ctx.rotate_hoisted(x, h, r, keys)
+            got = ctx.moddown_ct(ctx.rotate_hoisted_raised(x, h, r, keys), level, x.scale)
+            assert all(np.array_equal(a, b) for a, b in zip(got.c, want.c))
+        zero = [np.zeros((len(ctx.ext_idx(level)), ctx.n), dtype=np.uint64) for _ in range(2)]
+        want = ctx.rotate(x, 3, keys)
+        got = ctx.rotate_add_raised(x, 3, keys, zero)
+        assert all(np.array_equal(a, b) for a, b in zip(got.c, want.c))
+
+
+def test_rotate_add_raised_is_rotation_plus_the_divided_addend():
+    """Rot(x, r) + ModDown(E) against the two done separately.  ModDown(u) = floor(u / P) - a with
+    a in [0, K) from the uncorrected base conversion, so the two differ per coefficient by one
+    carry and three such terms, at most 2K - 1 in size; they agree after decryption."""
+    prm, ctx, sk = _toy_ctx()
+    keys = ctx.keygen_rotations(sk, [3, 5], 2)
+    rng = np.random.default_rng(1)
+    z, w, v = rng.normal(size=(3, ctx.S))
+    level = prm.L
+    x = ctx.encrypt(sk, ctx.encode(z, level), 3)
+    y = ctx.encrypt(sk, ctx.encode(w, level), 4)
+    E = ctx.rotate_hoisted_raised(y, ctx.hoist(y), 5, keys)
+    got = ctx.rotate_add_raised(x, 3, keys, E)
+    want = ctx.ct_add(ctx.rotate(x, 3, keys), ctx.moddown_ct(E, level, y.scale))
+    a, b = ctx.canonical(got).astype(np.int64), ctx.canonical(want).astype(np.int64)
+    q = np.array(prm.moduli[:level + 1], dtype=np.int64)[None, :, None]
+    diff = (a - b) % q
+    diff = np.minimum(diff, q - diff)
+    assert 1 <= diff.max() <= 2 * prm.K - 1             # additive up to the rounding, and not identical
+    assert np.abs(ctx.decrypt(sk, got).real - (np.roll(z, -3) + np.roll(w, -5))).max() < 1e-6
+    # plaintext product in the raised basis: ModDown(R * p) decrypts to slots * p
+    pt = ctx.encode_ext(v, level)
+    acc = [np.zeros_like(E[0]), np.zeros_like(E[1])]
+    ctx.mac_pt_raised(acc, E, pt, level)
+    prod = ctx.rescale(ctx.moddown_ct(acc, level, y.scale * pt.scale))
+    assert np.abs(ctx.decrypt(sk, prod).real - np.roll(w, -5) * v).max() < 1e-6
+    assert np.array_equal(pt.m[:level + 1], ctx.encode(v, level).m)   # same polynomial on the q limbs
+
+
+@pytest.mark.parametrize("d_in,d_out,level,tau", [(16, 16, 3, 0), (16, 64, 2, 0), (64, 16, 4, 0), (32, 32, 1, 3)])
+def test_double_hoisted_vmm_decrypts_to_x_times_W(d_in, d_out, level, tau):
+    prm, ctx, sk = _toy_ctx()
+    x, W = inputs.vmm_inputs(5, d_in, d_out, "normal", 0.1)
+    plan = packing.make_plan(ctx.S, d_in, d_out, tau=tau)
+    keys = ctx.keygen_rotations(sk, plan.all_steps(), 2)
+    ct = ctx.level_drop(ctx.encrypt(sk, ctx.encode(plan.pack_input(x), prm.L), 3), level)
+    diags = plan.diagonals(W)
+    ext = [[ctx.encode_ext(v, level) for v in row] for row in diags]
+    r0, p0 = ctx.rot_count, ctx.ptmul_count
+    y = vmm.vmm_pt_double_hoisted(ctx, keys, plan, ct, ext)
+    assert ctx.rot_count - r0 == plan.n_rotations and ctx.ptmul_count - p0 == plan.r_i * plan.r_o
+    assert y.level == level - 1
+    got = plan.unpack_output(ctx.decrypt(sk, y).real)
+    assert np.abs(got - x @ W).max() < TOL
+    # against the plain algorithm: same message, limbs differ only by rounding noise
+    plain = vmm.vmm_pt(vmm.CkksOps(ctx, keys), plan, ct, [[ctx.encode(v, level) for v in row] for row in diags])
+    assert abs(y.scale / plain.scale - 1) < 1e-12
+    assert np.abs(ctx.decrypt(sk, y) - ctx.decrypt(sk, plain)).max() < 1e-6
