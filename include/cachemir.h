@@ -167,11 +167,25 @@ cm_status cm_vmm_plan_create(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r
 cm_status cm_vmm_plan_create_from_coeffs(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i,
                                          int32_t tau, int32_t level, double pt_scale,
                                          const int64_t *coeffs, cm_vmm_plan **out);
+/* General form: exactly one of W (as in cm_vmm_plan_create) and coeffs (as in
+ * cm_vmm_plan_create_from_coeffs) is non-null.  flags:
+ *   CM_VMM_RAISED_SUMS  the hoisted baby-step rotations (App. C: the r_i - 1 rotations of one
+ *     ciphertext) are not divided by the special modulus P one by one: they stay on the
+ *     level+1+K limbs of the extended basis as (u0 + P sigma(c0), u1), the plaintext products are
+ *     summed there, and each sum is divided by P inside the giant step that consumes it.  Same
+ *     rotations, same plaintext products, r_i - 1 fewer ModDowns; the weight plaintexts take
+ *     level+1+K limbs each.  The result differs from the plain form by rounding noise only.
+ * Unknown flag bits: CM_E_INVAL. */
+enum { CM_VMM_RAISED_SUMS = 1 };
+cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
+                                int32_t level, double pt_scale, const double *W,
+                                const int64_t *coeffs, uint32_t flags, cm_vmm_plan **out);
 void cm_vmm_plan_destroy(cm_vmm_plan *plan);
 /* Rotation steps the plan uses: returns their number, writes up to cap of them (host). */
 int32_t cm_vmm_plan_steps(const cm_vmm_plan *plan, int32_t *steps, int32_t cap);
-/* r_i, r_o, and the integer coefficients are not kept; the encoded diagonal (j, k) in canonical
- * plain residues to host out[(level+1)*n]. */
+/* r_i, r_o, rotation count.  The integer coefficients are not kept; cm_vmm_plan_diag_export
+ * writes the encoded diagonal (j, k) in canonical plain residues to host out[limbs*n], limbs =
+ * level+1 (plus the K special limbs for a CM_VMM_RAISED_SUMS plan). */
 cm_status cm_vmm_plan_info(const cm_vmm_plan *plan, int32_t *r_i, int32_t *r_o, int32_t *n_rot);
 cm_status cm_vmm_plan_diag_export(cm_ctx *ctx, const cm_vmm_plan *plan, int32_t j, int32_t k,
                                   uint64_t *out);
@@ -214,7 +228,7 @@ cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t whi
 
 /* ---- building blocks exposed for measurement and parity -------------------------------- */
 /* Forward / inverse negacyclic NTT of `limbs` limbs in place (device), limb i under modulus
- * index mod_idx[i] (host array; indices into q_0..q_L,p_0..). */
+ * index mod_idx[i] (host array; indices into q_0..q_L,p_0..); 1 <= limbs <= 1024. */
 cm_status cm_ntt(cm_ctx *ctx, uint64_t *dev, const int32_t *mod_idx, int32_t limbs,
                  int32_t inverse, void *stream);
 /* One hybrid key switch of an evaluation-domain polynomial d[level+1][n] (device) with the key

@@ -18,6 +18,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 CM_QK, CM_SV = 0, 1
+CM_VMM_RAISED_SUMS = 1
 
 
 class cm_params(C.Structure):
@@ -69,6 +70,7 @@ _SIGS = {
     "cm_rotate_hoisted": ([_vp, _vp, _P(cm_ct), _vp, _sz, _P(cm_ct), _vp], _i32),
     "cm_vmm_plan_create": ([_vp, _i32, _i32, _i32, _i32, _i32, _f64, _vp, _P(_vp)], _i32),
     "cm_vmm_plan_create_from_coeffs": ([_vp, _i32, _i32, _i32, _i32, _i32, _f64, _vp, _P(_vp)], _i32),
+    "cm_vmm_plan_create_ex": ([_vp, _i32, _i32, _i32, _i32, _i32, _f64, _vp, _vp, C.c_uint32, _P(_vp)], _i32),
     "cm_vmm_plan_destroy": ([_vp], None),
     "cm_vmm_plan_steps": ([_vp, _vp, _i32], _i32),
     "cm_vmm_plan_info": ([_vp, _P(_i32), _P(_i32), _P(_i32)], _i32),
@@ -284,8 +286,9 @@ class Context:
         _chk(lib.cm_profile_get(self.h, family, C.byref(a), C.byref(b), C.byref(c)))
         return a.value, b.value, c.value
 
-    def vmm_plan(self, d_in, d_out, W=None, level=None, r_i=0, tau=0, pt_scale=0.0, coeffs=None):
-        return VmmPlan(self, d_in, d_out, W, self.L if level is None else level, r_i, tau, pt_scale, coeffs)
+    def vmm_plan(self, d_in, d_out, W=None, level=None, r_i=0, tau=0, pt_scale=0.0, coeffs=None, raised_sums=False):
+        return VmmPlan(self, d_in, d_out, W, self.L if level is None else level, r_i, tau, pt_scale, coeffs,
+                       raised_sums)
 
     def vmm_pt(self, evk, plan, x, out=None):
         out = out or Ct(self, x.level - 1)
@@ -335,17 +338,19 @@ class Evk:
 
 
 class VmmPlan:
-    def __init__(self, ctx, d_in, d_out, W, level, r_i, tau, pt_scale, coeffs):
+    def __init__(self, ctx, d_in, d_out, W, level, r_i, tau, pt_scale, coeffs, raised_sums=False):
         self.ctx, self.h, self.level = ctx, _vp(), level
+        self.limbs = level + 1 + (ctx.K if raised_sums else 0)
+        flags = CM_VMM_RAISED_SUMS if raised_sums else 0
         if coeffs is not None:
             c = _np(coeffs, np.int64)
-            _chk(lib.cm_vmm_plan_create_from_coeffs(ctx.h, d_in, d_out, r_i, tau, level, pt_scale,
-                                                    c.ctypes.data, C.byref(self.h)))
+            _chk(lib.cm_vmm_plan_create_ex(ctx.h, d_in, d_out, r_i, tau, level, pt_scale, None, c.ctypes.data,
+                                           flags, C.byref(self.h)))
         else:
             w = _np(W, np.float64)
             assert w.shape == (d_in, d_out)
-            _chk(lib.cm_vmm_plan_create(ctx.h, d_in, d_out, r_i, tau, level, pt_scale, w.ctypes.data,
-                                        C.byref(self.h)))
+            _chk(lib.cm_vmm_plan_create_ex(ctx.h, d_in, d_out, r_i, tau, level, pt_scale, w.ctypes.data, None,
+                                           flags, C.byref(self.h)))
         a, b, c = _i32(), _i32(), _i32()
         _chk(lib.cm_vmm_plan_info(self.h, C.byref(a), C.byref(b), C.byref(c)))
         self.r_i, self.r_o, self.n_rotations = a.value, b.value, c.value
@@ -357,7 +362,7 @@ class VmmPlan:
         return out.tolist()
 
     def diag_export(self, j, k):
-        out = np.empty((self.level + 1, self.ctx.n), dtype=np.uint64)
+        out = np.empty((self.limbs, self.ctx.n), dtype=np.uint64)
         _chk(lib.cm_vmm_plan_diag_export(self.ctx.h, self.h, j, k, out.ctypes.data))
         return out
 

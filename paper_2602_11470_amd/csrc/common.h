@@ -110,6 +110,7 @@ struct cm_ctx {
     std::vector<u64> psi;
     // device tables, indexed by modulus index
     ModC *d_modc = nullptr;               // [nmod]
+    u64 *d_pmont = nullptr;               // [L+1] P = p_0 .. p_{K-1} mod q_i, multiplier (Montgomery) form
     u64 *d_tw = nullptr, *d_twp = nullptr;      // forward twiddles psi^brev(i) and companions [nmod][n]
     u64 *d_itw = nullptr, *d_itwp = nullptr;    // inverse
     u64 *d_ninv = nullptr, *d_ninvp = nullptr;  // n^{-1} [nmod]

@@ -316,6 +316,15 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
         ninvp[m] = h_shoup(ninv[m], q);
     }
     ctx->d_modc = upload(ctx->modc);
+    {
+        std::vector<u64> pm;
+        for (int i = 0; i <= ctx->L; i++) {
+            u64 q = ctx->mod[i], P = 1;
+            for (int k = 0; k < ctx->K; k++) P = h_mulmod(P, ctx->mod[ctx->L + 1 + k] % q, q);
+            pm.push_back((u64)((((u128)P) << 64) % q));
+        }
+        ctx->d_pmont = upload(pm);
+    }
     ctx->d_tw = upload(tw);
     ctx->d_twp = upload(twp);
     ctx->d_itw = upload(itw);
@@ -360,7 +369,7 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
                    (size_t)CM_KS_BATCH * 2 * (2 * ext + ctx->L + 1);  // batched ModDown of hoisted rotations
     ctx->arena_words = limbs * n;
     if (hipMalloc((void **)&ctx->arena, ctx->arena_words * sizeof(u64)) != hipSuccess) ctx->arena = nullptr;
-    if (!ctx->d_modc || !ctx->d_tw || !ctx->d_twp || !ctx->d_itw || !ctx->d_itwp || !ctx->d_ninv ||
+    if (!ctx->d_modc || !ctx->d_pmont || !ctx->d_tw || !ctx->d_twp || !ctx->d_itw || !ctx->d_itwp || !ctx->d_ninv ||
         !ctx->d_ninvp || !ctx->d_idx || !ctx->d_cdt || !ctx->arena) {
         cm_ctx_destroy(ctx);
         return CM_E_NOMEM;
@@ -398,6 +407,7 @@ extern "C" void cm_ctx_destroy(cm_ctx *ctx) {
     for (hipEvent_t e : ctx->sync_ev) hipEventDestroy(e);
     if (ctx->aux) hipStreamDestroy(ctx->aux);
     hipFree(ctx->d_modc);
+    hipFree(ctx->d_pmont);
     hipFree(ctx->d_tw);
     hipFree(ctx->d_twp);
     hipFree(ctx->d_itw);

@@ -12,7 +12,11 @@ void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs,
 void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st);
 void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_step, int max_nt, u64 *out, const u64 *in,
                       size_t in_stride, size_t out_stride, const u64 *own_src, u64 own_g, hipStream_t st);
-void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g, hipStream_t st);
+// (u0, u1)[ext][n] = sum_j perm_g(dig_j) * evk_j  [+ P * perm_g(c0) on the ciphertext limbs of u0]  [+ extra[2][ext][n]]
+void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g,
+                          hipStream_t st, const u64 *c0 = nullptr, const u64 *extra = nullptr);
+// out[2][ext][n] = (P c0, P c1), zero on the special limbs
+void launch_raise_by_P(cm_ctx *ctx, u64 *out, const u64 *in, int level, hipStream_t st);
 void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
                            int addend_comps, int level, u64 g, const u64 *accum, hipStream_t st);
 void launch_rescale_reduce(cm_ctx *ctx, u64 *red, const u64 *last, int ncomp, int level, hipStream_t st);
@@ -24,7 +28,8 @@ void launch_sample_gauss(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs,
 void launch_evk_assemble(cm_ctx *ctx, u64 *b_out, u64 *a_io, const u64 *e, const u64 *s_mont, const u64 *d_fac, u64 g, hipStream_t st);
 void launch_encrypt(cm_ctx *ctx, u64 *c0, const u64 *a, const u64 *e, const u64 *s_mont, const u64 *pt, int limbs, hipStream_t st);
 void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int ncomp, int ct_limbs, int limbs, hipStream_t st);
-void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, int k0, int k1, hipStream_t st);
+void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, int level,
+                    size_t ct_stride, size_t pt_stride, int k0, int k1, hipStream_t st);
 
 // Tail of a ModDown fused into the last pass of the forward transform of its converted limbs:
 // for item r, component c, limb l:  out = (u - NTT(conv)) * P^{-1} (+ addend through the Galois map
@@ -60,8 +65,17 @@ cm_status ks_raise(cm_ctx *ctx, const u64 *d, int level, u64 *digits, hipStream_
 cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u64 g, const u64 *addend,
                    int addend_comps, u64 *out, hipStream_t st, const u64 *accum = nullptr);
 // out = Rot(in) (+ accum); out may alias in or accum
+// extra: a [2][ext][n] sum in the extended basis that joins the key-switch sum before its ModDown
 cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64 g, u64 *out, hipStream_t st,
-                      const u64 *accum = nullptr);
+                      const u64 *accum = nullptr, const u64 *extra = nullptr);
+// out[2][level+1][n] = ModDown(u[2][ext][n]) (+ perm_g(addend) on the first addend_comps components) (+ accum);
+// the special limbs of u are overwritten
+cm_status moddown_into(cm_ctx *ctx, u64 *u, int level, const u64 *addend, int addend_comps, u64 g, u64 *out,
+                       const u64 *accum, hipStream_t st);
+// raised[r][2][ext][n] = sum_j perm_{g_r}(digits_j) * key_r + P * perm_{g_r}(in.c0): hoisted rotations left in the
+// extended basis
+cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys,
+                               const u64 *gs, const u64 *in, u64 *const *raised, hipStream_t st);
 cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st);
 u64 *arena_digits(const cm_ctx *ctx);
 cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys, const u64 *gs,

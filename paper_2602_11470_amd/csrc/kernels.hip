@@ -176,7 +176,9 @@ void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_ste
 __global__ __launch_bounds__(TPB) void k_inner_product(u64 *__restrict__ u0, u64 *__restrict__ u1,
                                                        const u64 *__restrict__ dig, const u64 *__restrict__ evk,
                                                        const ModC *__restrict__ modc,
-                                int beta, int ext, int level, int L, int nmod, int n, int logn, unsigned g) {
+                                int beta, int ext, int level, int L, int nmod, int n, int logn, unsigned g,
+                                const u64 *__restrict__ c0, const u64 *__restrict__ pmont,
+                                const u64 *__restrict__ extra) {
     unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
     int r = blockIdx.y;
     int mi = r <= level ? r : L + 1 + (r - level - 1);
@@ -199,15 +201,47 @@ __global__ __launch_bounds__(TPB) void k_inner_product(u64 *__restrict__ u0, u64
         a0 += (u128)dx * ea.x;
         a1 += (u128)dy * ea.y;
     }
+    if (c0 && r <= level) {           // + P * sigma_g(c0): the rotation stays in the extended basis
+        ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(c0 + (size_t)r * n + base);
+        const u64 pm = pmont[r];
+        b0 += (u128)(swap ? d.y : d.x) * pm;
+        b1 += (u128)(swap ? d.x : d.y) * pm;
+    }
     size_t o = (size_t)r * n + i2;
-    *reinterpret_cast<ulonglong2 *>(u0 + o) = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
-    *reinterpret_cast<ulonglong2 *>(u1 + o) = make_ulonglong2(redc(a0, m.q, m.qinv), redc(a1, m.q, m.qinv));
+    ulonglong2 r0 = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
+    ulonglong2 r1 = make_ulonglong2(redc(a0, m.q, m.qinv), redc(a1, m.q, m.qinv));
+    if (extra) {                      // + a sum already in the extended basis, [2][ext][n]
+        ulonglong2 e0 = *reinterpret_cast<const ulonglong2 *>(extra + o);
+        ulonglong2 e1 = *reinterpret_cast<const ulonglong2 *>(extra + (size_t)ext * n + o);
+        r0.x = addmod(r0.x, e0.x, m.q), r0.y = addmod(r0.y, e0.y, m.q);
+        r1.x = addmod(r1.x, e1.x, m.q), r1.y = addmod(r1.y, e1.y, m.q);
+    }
+    *reinterpret_cast<ulonglong2 *>(u0 + o) = r0;
+    *reinterpret_cast<ulonglong2 *>(u1 + o) = r1;
 }
-void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g, hipStream_t st) {
+// out[2][ext][n] = (P c0, P c1) on the ciphertext limbs, zero on the special limbs
+__global__ void k_raise_by_P(u64 *__restrict__ out, const u64 *__restrict__ in, const ModC *__restrict__ modc,
+                             const u64 *__restrict__ pmont, int level, int ext, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, r = blockIdx.y, c = blockIdx.z;
+    u64 v = 0;
+    if (r <= level) {
+        const ModC m = modc[r];
+        v = redc((u128)in[((size_t)c * (level + 1) + r) * n + i] * pmont[r], m.q, m.qinv);
+    }
+    out[((size_t)c * ext + r) * n + i] = v;
+}
+void launch_raise_by_P(cm_ctx *ctx, u64 *out, const u64 *in, int level, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, 2 * (level + 1 + ctx->K), st);
+    int ext = level + 1 + ctx->K;
+    hipLaunchKernelGGL(k_raise_by_P, dim3(ctx->n / TPB, ext, 2), dim3(TPB), 0, st, out, in, ctx->d_modc, ctx->d_pmont, level,
+                       ext, ctx->n);
+}
+void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g,
+                          hipStream_t st, const u64 *c0, const u64 *extra) {
     Prof prof_(ctx, CM_K_INNER_PRODUCT, 1, st);
     int ext = level + 1 + ctx->K;
     hipLaunchKernelGGL(k_inner_product, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, u0, u1, dig, evk, ctx->d_modc,
-                       beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g);
+                       beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, c0, ctx->d_pmont, extra);
 }
 
 // ---- ModDown tail: out = (u - conv) * P^{-1} (+ addend, optionally through the Galois map) ------------
@@ -361,55 +395,11 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 }
 
 // ---- packed product: inner_k = sum_j baby_j * p_{j,k} ---------------------------------------------------
-// babies: r_i ciphertexts [2][limbs][n] at stride baby_stride; pts: plaintext (j,k) at
-// (j*r_o + k)*pt_stride, multiplier form; out: r_o ciphertexts at stride baby_stride.
-// A lane keeps its coefficient of all baby ciphertexts of a chunk in registers and streams the
-// plaintexts once; products are summed in 128 bits and reduced once per chunk.
-// RC baby ciphertexts are register-resident per pass (one pass when r_i <= RC, so every output is
-// written exactly once); products are summed 8 at a time in 128 bits before each REDC.
-template <int RC>
-__global__ __launch_bounds__(TPB) void k_vmm_mac(u64 *__restrict__ out, const u64 *__restrict__ babies,
-                                                 const u64 *__restrict__ pts, const ModC *__restrict__ modc, int r_i,
-                                                 int r_o, int limbs, int n, size_t ct_stride, size_t pt_stride, int k0,
-                                                 int k1) {
-    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
-    const ModC m = modc[l];
-    size_t o = (size_t)l * n + i, cs = (size_t)limbs * n;
-    for (int j0 = 0; j0 < r_i; j0 += RC) {
-        u64 c0[RC], c1[RC];
-#pragma unroll
-        for (int jj = 0; jj < RC; jj++) {
-            bool ok = j0 + jj < r_i;
-            c0[jj] = ok ? babies[(size_t)(j0 + jj) * ct_stride + o] : 0;
-            c1[jj] = ok ? babies[(size_t)(j0 + jj) * ct_stride + cs + o] : 0;
-        }
-        for (int k = k0; k < k1; k++) {
-            u64 v0 = 0, v1 = 0;
-#pragma unroll
-            for (int s8 = 0; s8 < RC; s8 += 8) {
-                u128 s0 = 0, s1 = 0;
-#pragma unroll
-                for (int jj = s8; jj < s8 + 8; jj++) {
-                    if (j0 + jj < r_i) {
-                        u64 p = __builtin_nontemporal_load(pts + ((size_t)(j0 + jj) * r_o + k) * pt_stride + o);
-                        s0 += (u128)c0[jj] * p;
-                        s1 += (u128)c1[jj] * p;
-                    }
-                }
-                v0 = addmod(v0, redc(s0, m.q, m.qinv), m.q);
-                v1 = addmod(v1, redc(s1, m.q, m.qinv), m.q);
-            }
-            u64 *dst = out + (size_t)k * ct_stride + o;
-            if (j0) {
-                v0 = addmod(v0, dst[0], m.q);
-                v1 = addmod(v1, dst[cs], m.q);
-            }
-            dst[0] = v0;
-            dst[cs] = v1;
-        }
-    }
-}
-// The same product with the baby ciphertexts staged in LDS: a workgroup owns 64 coefficients of
+// babies: r_i ciphertexts [2][limbs][n] at stride ct_stride; pts: plaintext (j,k) at
+// (j*r_o + k)*pt_stride, multiplier form; out: r_o ciphertexts at stride ct_stride.  Limb l has
+// modulus index l up to `level`, and the special primes follow when limbs = level + 1 + K (sums
+// kept in the extended basis).
+// The baby ciphertexts are staged in LDS: a workgroup owns 64 coefficients of
 // one limb; its four waves take the k = k0 + wave, k0 + wave + 4, ... and every lane sums over all
 // j for its k, so each output is written once and each plaintext word is read once.  Up to 32
 // baby ciphertexts per pass (32 KiB of LDS); products are summed 8 at a time before a REDC.
@@ -418,11 +408,11 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac(u64 *__restrict__ out, const u6
 __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, const u64 *__restrict__ babies,
                                                      const u64 *__restrict__ pts, const ModC *__restrict__ modc,
                                                      int r_i, int r_o, int limbs, int n, size_t ct_stride,
-                                                     size_t pt_stride, int k0, int k1) {
+                                                     size_t pt_stride, int k0, int k1, int level, int L) {
     __shared__ u64 sb[MAC_JC * 2 * MAC_CO];
     const int l = blockIdx.y, i0 = blockIdx.x * MAC_CO;
     const int co = threadIdx.x & (MAC_CO - 1), kq = threadIdx.x >> 6;
-    const ModC m = modc[l];
+    const ModC m = modc[l <= level ? l : L + 1 + (l - level - 1)];
     const size_t o = (size_t)l * n + i0, cs = (size_t)limbs * n;
     for (int j0 = 0; j0 < r_i; j0 += MAC_JC) {
         const int jn = r_i - j0 < MAC_JC ? r_i - j0 : MAC_JC;
@@ -462,19 +452,9 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
         }
     }
 }
-void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, size_t ct_stride, size_t pt_stride, int k0, int k1, hipStream_t st) {
+void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, int level,
+                    size_t ct_stride, size_t pt_stride, int k0, int k1, hipStream_t st) {
     Prof prof_(ctx, CM_K_VMM_MAC, r_i * (k1 - k0), st);
-    dim3 grid(ctx->n / TPB, limbs), block(TPB);
-    static int rc = getenv("CM_MAC_RC") ? atoi(getenv("CM_MAC_RC")) : 0;
-    if (rc == 0) {
-        hipLaunchKernelGGL(k_vmm_mac_lds, dim3(ctx->n / MAC_CO, limbs), block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o,
-                           limbs, ctx->n, ct_stride, pt_stride, k0, k1);
-        return;
-    }
-    if (r_i > 16 && rc >= 32)
-        hipLaunchKernelGGL(k_vmm_mac<32>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride, k0, k1);
-    else if (r_i > 8 && rc >= 16)
-        hipLaunchKernelGGL(k_vmm_mac<16>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride, k0, k1);
-    else
-        hipLaunchKernelGGL(k_vmm_mac<8>, grid, block, 0, st, out, babies, pts, ctx->d_modc, r_i, r_o, limbs, ctx->n, ct_stride, pt_stride, k0, k1);
+    hipLaunchKernelGGL(k_vmm_mac_lds, dim3(ctx->n / MAC_CO, limbs), dim3(TPB), 0, st, out, babies, pts, ctx->d_modc, r_i,
+                       r_o, limbs, ctx->n, ct_stride, pt_stride, k0, k1, level, ctx->L);
 }

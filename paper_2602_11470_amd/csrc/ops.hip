@@ -176,25 +176,39 @@ cm_status ks_raise(cm_ctx *ctx, const u64 *d, int level, u64 *digits, hipStream_
     return CM_OK;
 }
 
-cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u64 g, const u64 *addend,
-                   int addend_comps, u64 *out, hipStream_t st, const u64 *accum) {
+cm_status moddown_into(cm_ctx *ctx, u64 *u, int level, const u64 *addend, int addend_comps, u64 g, u64 *out,
+                       const u64 *accum, hipStream_t st) {
     const KsLevelFull &k = ks_level_full(ctx, level);
     Arena A = arena_of(ctx);
     const size_t n = ctx->n;
-    u64 *u0 = A.u, *u1 = A.u + (size_t)k.ext * n;
-    launch_inner_product(ctx, u0, u1, digits, evk, k.beta, level, g, st);
-    launch_ntt_rows(ctx, A.u, k.d_sp_rows, k.d_sp_mods, 2 * ctx->K, true, st);
-    launch_base_conv(ctx, k.d_moddown, 2, 0, level + 1, A.conv, A.u, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr, 0, st);
+    if (!addend) addend_comps = 0, g = 0;
+    launch_ntt_rows(ctx, u, k.d_sp_rows, k.d_sp_mods, 2 * ctx->K, true, st);
+    launch_base_conv(ctx, k.d_moddown, 2, 0, level + 1, A.conv, u, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr, 0, st);
     if (ctx->n == 65536) {
         FinishBatch fb;
-        fb.items = 1, fb.level = level, fb.ext = k.ext, fb.addend_comps = addend ? addend_comps : 0;
-        fb.u[0] = A.u, fb.out[0] = out, fb.accum[0] = accum, fb.g[0] = addend ? (unsigned)g : 0;
+        fb.items = 1, fb.level = level, fb.ext = k.ext, fb.addend_comps = addend_comps;
+        fb.u[0] = u, fb.out[0] = out, fb.accum[0] = accum, fb.g[0] = (unsigned)g;
         fb.addend = addend, fb.pinv = get_pinv(ctx, level);
         launch_ntt_fwd_finish(ctx, A.conv, k.d_q_mods3, fb, st);
         return CM_OK;
     }
     launch_ntt(ctx, A.conv, k.d_q_mods3, 2 * (level + 1), false, st);
-    launch_moddown_finish(ctx, out, A.u, A.conv, get_pinv(ctx, level), addend, addend_comps, level, addend ? g : 0, accum, st);
+    launch_moddown_finish(ctx, out, u, A.conv, get_pinv(ctx, level), addend, addend_comps, level, g, accum, st);
+    return CM_OK;
+}
+
+cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u64 g, const u64 *addend,
+                   int addend_comps, u64 *out, hipStream_t st, const u64 *accum) {
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    Arena A = arena_of(ctx);
+    launch_inner_product(ctx, A.u, A.u + (size_t)k.ext * ctx->n, digits, evk, k.beta, level, g, st);
+    return moddown_into(ctx, A.u, level, addend, addend_comps, g, out, accum, st);
+}
+cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys,
+                               const u64 *gs, const u64 *in, u64 *const *raised, hipStream_t st) {
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    for (int r = 0; r < cnt; r++)
+        launch_inner_product(ctx, raised[r], raised[r] + (size_t)k.ext * ctx->n, digits, keys[r], k.beta, level, gs[r], st, in);
     return CM_OK;
 }
 u64 *arena_digits(const cm_ctx *ctx) { return arena_of(ctx).digits; }
@@ -277,7 +291,7 @@ extern "C" cm_status cm_keyswitch(cm_ctx *ctx, const cm_evk *evk, int32_t step, 
 }
 
 extern "C" cm_status cm_ntt(cm_ctx *ctx, uint64_t *dev, const int32_t *mod_idx, int32_t limbs, int32_t inverse, void *stream) {
-    if (!ctx || !dev || !mod_idx || limbs < 1 || limbs > 2 * CM_MAX_LIMBS) return CM_E_INVAL;
+    if (!ctx || !dev || !mod_idx || limbs < 1 || limbs > 1024) return CM_E_INVAL;
     for (int i = 0; i < limbs; i++)
         if (mod_idx[i] < 0 || mod_idx[i] >= ctx->nmod) return CM_E_INVAL;
     // consecutive runs of modulus indices map onto the resident 0,1,2,.. table; anything else is staged
@@ -603,7 +617,7 @@ extern "C" cm_status cm_level_drop(cm_ctx *ctx, const cm_ct *a, int32_t level, c
 }
 
 cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64 g, u64 *out, hipStream_t st,
-                      const u64 *accum) {
+                      const u64 *accum, const u64 *extra) {
     // Galois map first, key switch afterwards: the map is applied while reading (the inverse NTT of
     // c1, the copy of the digits' own limbs, and the c0 added at the end), never as a pass of its own.
     // The inner product sees already mapped digits, so it runs without permutation; the ModDown
@@ -611,22 +625,8 @@ cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64
     Arena A = arena_of(ctx);
     CMCHK(ks_raise(ctx, in + (size_t)(level + 1) * ctx->n, level, A.digits, st, g));
     const KsLevelFull &k = ks_level_full(ctx, level);
-    const size_t n = ctx->n;
-    u64 *u0 = A.u, *u1 = A.u + (size_t)k.ext * n;
-    launch_inner_product(ctx, u0, u1, A.digits, key, k.beta, level, 0, st);
-    launch_ntt_rows(ctx, A.u, k.d_sp_rows, k.d_sp_mods, 2 * ctx->K, true, st);
-    launch_base_conv(ctx, k.d_moddown, 2, 0, level + 1, A.conv, A.u, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr, 0, st);
-    if (ctx->n == 65536) {
-        FinishBatch fb;
-        fb.items = 1, fb.level = level, fb.ext = k.ext, fb.addend_comps = 1;
-        fb.u[0] = A.u, fb.out[0] = out, fb.accum[0] = accum, fb.g[0] = (unsigned)g;
-        fb.addend = in, fb.pinv = get_pinv(ctx, level);
-        launch_ntt_fwd_finish(ctx, A.conv, k.d_q_mods3, fb, st);
-        return CM_OK;
-    }
-    launch_ntt(ctx, A.conv, k.d_q_mods3, 2 * (level + 1), false, st);
-    launch_moddown_finish(ctx, out, A.u, A.conv, get_pinv(ctx, level), in, 1, level, g, accum, st);
-    return CM_OK;
+    launch_inner_product(ctx, A.u, A.u + (size_t)k.ext * ctx->n, A.digits, key, k.beta, level, 0, st, nullptr, extra);
+    return moddown_into(ctx, A.u, level, in, 1, g, out, accum, st);
 }
 extern "C" cm_status cm_rotate(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, int32_t step, cm_ct *out, void *stream) {
     if (!ctx || !evk || !ct_ok(ctx, in) || in->ncomp != 2 || !out || !out->dev) return CM_E_INVAL;

@@ -19,8 +19,11 @@ struct cm_vmm_plan {
     double pt_scale;
     std::vector<int> pre_steps, baby_steps, reduce_steps;
     int giant_step;
-    u64 *d_pts = nullptr;      // [r_i*r_o][level+1][n], multiplier form
-    u64 *d_work = nullptr;     // r_i baby + r_o inner + 1 temporary ciphertexts
+    bool raised = false;       // sums of the baby steps stay in the extended basis (one ModDown per giant step)
+    int pt_limbs;              // level+1, or level+1+K when raised
+    int *d_pt_mods = nullptr;  // modulus index of every plaintext limb
+    u64 *d_pts = nullptr;      // [r_i*r_o][pt_limbs][n], multiplier form
+    u64 *d_work = nullptr;     // r_i baby + r_o inner ciphertexts of 2*pt_limbs limbs + 3 temporary ciphertexts
 };
 
 static int ilog2(int x) {
@@ -94,31 +97,52 @@ static void diag_slots(const cm_vmm_plan *p, const std::vector<int> &lab, const 
     }
 }
 
-static cm_status plan_alloc(cm_vmm_plan *p) {
-    const size_t n = p->ctx->n, ptw = (size_t)(p->level + 1) * n, ctw = 2 * ptw;
+static cm_status plan_alloc(cm_vmm_plan *p, bool raised) {
+    cm_ctx *ctx = p->ctx;
+    p->raised = raised;
+    p->pt_limbs = p->level + 1 + (raised ? ctx->K : 0);
+    std::vector<int> mods;
+    for (int i = 0; i <= p->level; i++) mods.push_back(i);
+    for (int k = 0; raised && k < ctx->K; k++) mods.push_back(ctx->L + 1 + k);
+    const size_t n = ctx->n, ptw = (size_t)p->pt_limbs * n, ctw = 2 * (size_t)(p->level + 1) * n;
+    if (hipMalloc((void **)&p->d_pt_mods, mods.size() * sizeof(int)) != hipSuccess) return CM_E_NOMEM;
+    if (hipMemcpy(p->d_pt_mods, mods.data(), mods.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess) return CM_E_HIP;
     if (hipMalloc((void **)&p->d_pts, (size_t)p->M * ptw * 8) != hipSuccess) return CM_E_NOMEM;
-    if (hipMalloc((void **)&p->d_work, (size_t)(p->r_i + p->r_o + 1) * ctw * 8) != hipSuccess) return CM_E_NOMEM;
+    if (hipMalloc((void **)&p->d_work, ((size_t)(p->r_i + p->r_o) * 2 * ptw + 3 * ctw) * 8) != hipSuccess) return CM_E_NOMEM;
     return CM_OK;
 }
 
+// plaintext polynomial of integer coefficients on the plan's limbs, evaluation domain, multiplier form
 static cm_status plan_load_diag(cm_vmm_plan *p, int idx, const int64_t *coeffs) {
-    cm_pt pt;
-    pt.dev = p->d_pts + (size_t)idx * (p->level + 1) * p->ctx->n;
-    pt.mont = 1;
-    return cm_pt_from_coeffs(p->ctx, coeffs, p->level, p->pt_scale, &pt);
+    cm_ctx *ctx = p->ctx;
+    u64 *dst = p->d_pts + (size_t)idx * p->pt_limbs * ctx->n;
+    u64 *stage = p->d_work;                     // free until the first product
+    HIPCHK(hipMemcpy(stage, coeffs, (size_t)ctx->n * 8, hipMemcpyHostToDevice));
+    launch_reduce_i64(ctx, dst, (const long long *)stage, p->d_pt_mods, p->pt_limbs, 0);
+    launch_ntt_rows(ctx, dst, nullptr, p->d_pt_mods, p->pt_limbs, false, 0);
+    launch_to_mont(ctx, dst, p->d_pt_mods, p->pt_limbs, 0);
+    HIPCHK(hipDeviceSynchronize());
+    return CM_OK;
 }
 
-extern "C" cm_status cm_vmm_plan_create(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
-                                        int32_t level, double pt_scale, const double *W, cm_vmm_plan **out) {
-    if (!ctx || !W || !out) return CM_E_INVAL;
+extern "C" cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
+                                           int32_t level, double pt_scale, const double *W, const int64_t *coeffs,
+                                           uint32_t flags, cm_vmm_plan **out) {
+    if (!ctx || (!W == !coeffs) || !out || (flags & ~(uint32_t)CM_VMM_RAISED_SUMS)) return CM_E_INVAL;
     cm_vmm_plan *p = new (std::nothrow) cm_vmm_plan();
     if (!p) return CM_E_NOMEM;
     cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, p);
-    if (s == CM_OK) s = plan_alloc(p);
+    if (s == CM_OK) s = plan_alloc(p, (flags & CM_VMM_RAISED_SUMS) != 0);
     if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
+    if (coeffs) {
+        for (int idx = 0; idx < p->M && s == CM_OK; idx++) s = plan_load_diag(p, idx, coeffs + (size_t)idx * ctx->n);
+        if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
+        *out = p;
+        return CM_OK;
+    }
     const std::vector<int> lab = source_labels(p);
     const int n = ctx->n, batch = 16;
-    std::vector<std::vector<int64_t>> coeffs(batch, std::vector<int64_t>(n));
+    std::vector<std::vector<int64_t>> cf(batch, std::vector<int64_t>(n));
     std::vector<cm_status> st(batch);
     for (int base = 0; base < p->M && s == CM_OK; base += batch) {
         int cnt = p->M - base < batch ? p->M - base : batch;
@@ -128,35 +152,33 @@ extern "C" cm_status cm_vmm_plan_create(cm_ctx *ctx, int32_t d_in, int32_t d_out
                 int idx = base + b, j = idx / p->r_o, k = idx % p->r_o;
                 std::vector<double> slots;
                 diag_slots(p, lab, W, j, k, slots);
-                st[b] = cm_encode_coeffs(ctx, slots.data(), nullptr, slots.size(), p->pt_scale, coeffs[b].data());
+                st[b] = cm_encode_coeffs(ctx, slots.data(), nullptr, slots.size(), p->pt_scale, cf[b].data());
             });
         for (auto &t : th) t.join();
         for (int b = 0; b < cnt && s == CM_OK; b++) {
             s = st[b];
-            if (s == CM_OK) s = plan_load_diag(p, base + b, coeffs[b].data());
+            if (s == CM_OK) s = plan_load_diag(p, base + b, cf[b].data());
         }
     }
     if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
     *out = p;
     return CM_OK;
 }
-
+extern "C" cm_status cm_vmm_plan_create(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
+                                        int32_t level, double pt_scale, const double *W, cm_vmm_plan **out) {
+    if (!W) return CM_E_INVAL;
+    return cm_vmm_plan_create_ex(ctx, d_in, d_out, r_i, tau, level, pt_scale, W, nullptr, 0, out);
+}
 extern "C" cm_status cm_vmm_plan_create_from_coeffs(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i,
                                                     int32_t tau, int32_t level, double pt_scale,
                                                     const int64_t *coeffs, cm_vmm_plan **out) {
-    if (!ctx || !coeffs || !out) return CM_E_INVAL;
-    cm_vmm_plan *p = new (std::nothrow) cm_vmm_plan();
-    if (!p) return CM_E_NOMEM;
-    cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, p);
-    if (s == CM_OK) s = plan_alloc(p);
-    for (int idx = 0; idx < p->M && s == CM_OK; idx++) s = plan_load_diag(p, idx, coeffs + (size_t)idx * ctx->n);
-    if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
-    *out = p;
-    return CM_OK;
+    if (!coeffs) return CM_E_INVAL;
+    return cm_vmm_plan_create_ex(ctx, d_in, d_out, r_i, tau, level, pt_scale, nullptr, coeffs, 0, out);
 }
 
 extern "C" void cm_vmm_plan_destroy(cm_vmm_plan *plan) {
     if (!plan) return;
+    hipFree(plan->d_pt_mods);
     hipFree(plan->d_pts);
     hipFree(plan->d_work);
     delete plan;
@@ -180,10 +202,68 @@ extern "C" cm_status cm_vmm_plan_info(const cm_vmm_plan *p, int32_t *r_i, int32_
 }
 extern "C" cm_status cm_vmm_plan_diag_export(cm_ctx *ctx, const cm_vmm_plan *p, int32_t j, int32_t k, uint64_t *out) {
     if (!ctx || !p || !out || j < 0 || j >= p->r_i || k < 0 || k >= p->r_o) return CM_E_INVAL;
-    cm_pt pt;
-    pt.dev = p->d_pts + (size_t)(j * p->r_o + k) * (p->level + 1) * ctx->n;
-    pt.level = p->level, pt.mont = 1, pt.scale = p->pt_scale;
-    return cm_pt_export(ctx, &pt, out);
+    const size_t words = (size_t)p->pt_limbs * ctx->n;
+    u64 *tmp = nullptr;
+    if (hipMalloc((void **)&tmp, words * 8) != hipSuccess) return CM_E_NOMEM;
+    launch_from_mont(ctx, tmp, p->d_pts + (size_t)(j * p->r_o + k) * words, p->d_pt_mods, p->pt_limbs, 0);
+    launch_ntt_rows(ctx, tmp, nullptr, p->d_pt_mods, p->pt_limbs, true, 0);
+    hipError_t e = hipMemcpy(out, tmp, words * 8, hipMemcpyDeviceToHost);
+    hipFree(tmp);
+    return e == hipSuccess ? CM_OK : CM_E_HIP;
+}
+
+// The same product with the sums of the baby steps kept in the extended basis: hoisted rotations stop
+// before their ModDown (u + P sigma(c0), u1), the plaintext products are summed on level+1+K limbs,
+// and every inner_k is divided by P inside the giant step that consumes it.
+static cm_status vmm_pt_raised(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const cm_ct *x, cm_ct *y,
+                               hipStream_t st) {
+    const int level = p->level, limbs = level + 1, ext = p->pt_limbs;
+    const size_t n = ctx->n, ctw = 2 * (size_t)limbs * n, ptw = (size_t)limbs * n, rw = 2 * (size_t)ext * n;
+    auto key_of = [&](int step) { return find_key(evk, galois_of_step(ctx, step)); };
+    u64 *babies = p->d_work, *inner = babies + (size_t)p->r_i * rw, *t0 = inner + (size_t)p->r_o * rw;
+    u64 *t1 = t0 + ctw, *t2 = t1 + ctw;
+    // 1. preprocess (rotate-and-add between two buffers)
+    u64 *c = t0, *other = t1;
+    HIPCHK(hipMemcpyAsync(c, x->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
+    for (int r : p->pre_steps) {
+        CMCHK(rotate_into(ctx, key_of(r), c, level, galois_of_step(ctx, r), other, st, c));
+        std::swap(c, other);
+    }
+    // 2. baby steps, left in the extended basis
+    launch_raise_by_P(ctx, babies, c, level, st);
+    if (p->r_i > 1) {
+        u64 *digits = arena_digits(ctx);
+        CMCHK(ks_raise(ctx, c + ptw, level, digits, st));
+        std::vector<const u64 *> keys;
+        std::vector<u64> gs;
+        std::vector<u64 *> dst;
+        for (int j = 1; j < p->r_i; j++) {
+            keys.push_back(key_of(p->baby_steps[j]));
+            gs.push_back(galois_of_step(ctx, p->baby_steps[j]));
+            dst.push_back(babies + (size_t)j * rw);
+        }
+        CMCHK(ks_apply_many_raised(ctx, digits, level, p->r_i - 1, keys.data(), gs.data(), c, dst.data(), st));
+    }
+    const int r_o = p->r_o;
+    launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, ext, level, rw, (size_t)ext * n, 0, r_o, st);
+    // giant steps, Horner form: acc <- Rot(acc) + ModDown-ed inner_k in one key switch
+    u64 *acc = c == t0 ? t1 : t0;
+    other = t2;
+    CMCHK(moddown_into(ctx, inner + (size_t)(r_o - 1) * rw, level, nullptr, 0, 0, acc, nullptr, st));
+    for (int k = r_o - 2; k >= 0; k--) {
+        CMCHK(rotate_into(ctx, key_of(p->giant_step), acc, level, galois_of_step(ctx, p->giant_step), other, st, nullptr,
+                          inner + (size_t)k * rw));
+        std::swap(acc, other);
+    }
+    // 3. reduce inside the ciphertext
+    for (int r : p->reduce_steps) {
+        CMCHK(rotate_into(ctx, key_of(r), acc, level, galois_of_step(ctx, r), other, st, acc));
+        std::swap(acc, other);
+    }
+    CMCHK(rescale_into(ctx, acc, 2, level, y->dev, st));
+    y->level = level - 1, y->ncomp = 2;
+    y->scale = x->scale * p->pt_scale / (double)ctx->mod[level];
+    return CM_OK;
 }
 
 extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const cm_ct *x, cm_ct *y,
@@ -200,6 +280,7 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     if (p->r_o > 1 && !key_of(p->giant_step)) return CM_E_NOKEY;
     for (int r : p->reduce_steps) if (!key_of(r)) return CM_E_NOKEY;
 
+    if (p->raised) return vmm_pt_raised(ctx, evk, p, x, y, st);
     u64 *babies = p->d_work, *inner = babies + (size_t)p->r_i * ctw, *tmp = inner + (size_t)p->r_o * ctw;
     // 1. preprocess: c <- c + Rot(c, 2^i (t-1)).  A rotate-and-add writes to the other of two buffers
     //    (its last kernel gathers c0 of its input through the permutation, so it cannot run in
@@ -226,7 +307,7 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     }
     //    multiply-accumulate: inner_k = sum_j baby_j * p_{j,k}; streams every weight plaintext once
     const int r_o = p->r_o;
-    launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, limbs, ctw, ptw, 0, r_o, st);
+    launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, limbs, level, ctw, ptw, 0, r_o, st);
     //    giant steps, Horner form
     u64 *acc = inner + (size_t)(r_o - 1) * ctw;
     for (int k = r_o - 2; k >= 0; k--) {

@@ -80,6 +80,64 @@ def test_vmm_pt_matches_oracle_and_float64(env, d_in, d_out, level, r_i, tau, se
     assert np.abs(plan.unpack_output(out2.real) - x @ W).max() < TOL
 
 
+def _raised_case(e, d_in, d_out, level, r_i, tau, seed):
+    """vmm_pt with the baby-step sums kept in the extended basis against the oracle's form of it."""
+    from oracle import packing, vmm
+    from paper_2602_11470_amd import inputs
+    octx, gctx = e["octx"], e["gctx"]
+    x, W = inputs.vmm_inputs(seed, d_in, d_out, "uniform", 0.05)
+    plan = packing.make_plan(octx.S, d_in, d_out, r_i or None, tau)
+    scale = octx.prm.scale
+    diag_coeffs = [[octx.encode_coeffs(v, scale) for v in row] for row in plan.diagonals(W)]
+    odiags = [[octx.pt_from_coeffs_ext(c, level, scale) for c in row] for row in diag_coeffs]
+    flat = np.stack([c for row in diag_coeffs for c in row])
+    gplan = gctx.vmm_plan(d_in, d_out, level=level, r_i=plan.r_i, tau=tau, coeffs=flat, raised_sums=True)
+    assert (gplan.r_i, gplan.r_o, gplan.n_rotations) == (plan.r_i, plan.r_o, plan.n_rotations)
+    # the plaintexts live on level+1+K limbs
+    ext = octx.ext_idx(level)
+    j, k = plan.r_i - 1, plan.r_o - 1
+    assert np.array_equal(gplan.diag_export(j, k), octx.intt(odiags[j][k].m, ext))
+    okeys = octx.keygen_rotations(e["osk"], plan.all_steps(), 2)
+    gkeys = gctx.keygen_rotations(e["gsk"], gplan.steps(), 2)
+    ox, gx = _enc_both(e, plan.pack_input(x), level, 3)
+    oy = vmm.vmm_pt_double_hoisted(octx, okeys, plan, ox, odiags)
+    gy = gctx.vmm_pt(gkeys, gplan, gx)
+    _same(e, oy, gy)
+    out = gctx.decrypt(e["gsk"], gy)
+    assert np.abs(plan.unpack_output(out.real) - x @ W).max() < TOL
+    # twice in a row on the same buffers: nothing left over from the first run
+    assert np.array_equal(gctx.ct_export(gctx.vmm_pt(gkeys, gplan, gx)), gctx.ct_export(gy))
+
+
+@pytest.mark.parametrize("d_in,d_out,level,r_i,tau,seed", [
+    (64, 64, 4, 0, 0, 0),
+    (64, 64, 2, 1, 0, 1),          # no baby steps: only the raised input
+    (256, 256, 3, 0, 0, 2),
+    (128, 512, 4, 0, 0, 3),
+    (512, 128, 1, 0, 0, 4),
+    (128, 128, 4, 0, 5, 5),
+])
+def test_vmm_pt_raised_sums_matches_oracle_and_float64(env, d_in, d_out, level, r_i, tau, seed):
+    _raised_case(env, d_in, d_out, level, r_i, tau, seed)
+
+
+@pytest.mark.parametrize("level", [5, 4, 2])
+def test_vmm_pt_raised_sums_with_two_primes_per_digit(level):
+    """Digits of two primes and two special primes (level 4: the last digit holds one prime)."""
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from oracle import ckks, params
+    from paper_2602_11470_amd import binding as B
+    prm = params.toy(n=4096, n_qi=5, n_p=2, alpha=2, hamming=64)
+    octx, gctx = ckks.Context(prm), B.Context(4096, 6, 2, 2, 50, 40, 60, 2.0 ** 40, hamming=64)
+    try:
+        assert gctx.moduli().tolist() == prm.moduli
+        e = dict(B=B, octx=octx, gctx=gctx, osk=octx.keygen_secret(1), gsk=gctx.keygen_secret(1), prm=prm)
+        _raised_case(e, 128, 128, level, 0, 0, 7)
+    finally:
+        gctx.close()
+
+
 def test_vmm_pt_missing_key_and_level_errors(env):
     e = env
     B, gctx = e["B"], e["gctx"]
