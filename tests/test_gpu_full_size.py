@@ -69,13 +69,16 @@ def test_config2_chain_keys_and_single_operations(ring2):
     assert np.abs(gctx.decrypt(gsk, gm).real - z * z).max() < 1e-6
 
 
-def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden):
+@pytest.mark.parametrize("raised", [False, True])
+def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden, raised):
     """52 rotations, 512 plaintext multiply-accumulates at (S, d) = (32768, 4096); the expected
-    ciphertext was written by tests/golden/make_vmm_full_size_golden.py from the oracle."""
+    ciphertext was written by tests/golden/make_vmm_full_size_golden.py from the oracle, for the
+    algorithm as printed and for the form that keeps the baby-step sums in the extended basis
+    (the configuration bench.py times)."""
     import importlib.util
     import os
     B, octx, gctx, prm = ring2
-    g = golden("vmm_full_size.txt")
+    g = golden("vmm_full_size_raised.txt" if raised else "vmm_full_size.txt")
     spec = importlib.util.spec_from_file_location(
         "mk", os.path.join(os.path.dirname(__file__), "golden", "make_vmm_full_size_golden.py"))
     mk = importlib.util.module_from_spec(spec)
@@ -83,7 +86,8 @@ def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden)
     from oracle import packing
     plan = packing.make_plan(octx.S, mk.D, mk.D)
     xc, diag = mk.integer_inputs(octx.n, plan)
-    gplan = gctx.vmm_plan(mk.D, mk.D, level=prm.L, r_i=plan.r_i, coeffs=np.stack(diag), pt_scale=prm.scale)
+    gplan = gctx.vmm_plan(mk.D, mk.D, level=prm.L, r_i=plan.r_i, coeffs=np.stack(diag), pt_scale=prm.scale,
+                          raised_sums=raised)
     assert gplan.n_rotations == int(g["rotations"]) == 52 and gplan.r_i * gplan.r_o == int(g["pt_mults"]) == 512
     gsk = gctx.keygen_secret(mk.SEED_SK)
     gkeys = gctx.keygen_rotations(gsk, gplan.steps(), mk.SEED_EVK)
@@ -108,10 +112,19 @@ def test_config2_packed_product_decrypts_to_float64_product(ring2):
     t = gctx.S // d
     slots = np.zeros(gctx.S)
     slots[::t] = x
-    gy = gctx.vmm_pt(gkeys, gplan, gctx.encrypt(gsk, gctx.encode(slots, gctx.L), 3))
+    gx = gctx.encrypt(gsk, gctx.encode(slots, gctx.L), 3)
+    gy = gctx.vmm_pt(gkeys, gplan, gx)
     out = gctx.decrypt(gsk, gy)
     assert np.abs(out.real[::t] - x @ W).max() < TOL
     assert gy.level == gctx.L - 1
+    del gplan
+    # baby-step sums kept in the extended basis: the same message up to rounding noise
+    gplan_r = gctx.vmm_plan(d, d, W=W, raised_sums=True)
+    gyr = gctx.vmm_pt(gkeys, gplan_r, gx)
+    assert gyr.level == gy.level and abs(gyr.scale / gy.scale - 1) < 1e-12
+    outr = gctx.decrypt(gsk, gyr)
+    assert np.abs(outr.real[::t] - x @ W).max() < TOL and np.abs(outr - out).max() < 1e-6
+    del gplan_r
     # the operating level of the paper's projections (level 4): two digits, the last one partial
     gplan4 = gctx.vmm_plan(d, d, W=W, level=4)
     gx4 = gctx.level_drop(gctx.encrypt(gsk, gctx.encode(slots, gctx.L), 3), 4)
