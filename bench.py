@@ -6,9 +6,11 @@ A step = one pass of the whole hot path over one synthetic input: cm_vmm_pt of a
 n = 2^16 with 24 ciphertext primes of 50 bits + 4 special primes of 60 bits (6 key-switch
 digits), at the top level: 52 rotations (21 full key switches + 31 hoisted), 512 plaintext
 multiply-accumulates, one rescale.  Keys, weight plaintexts and the input ciphertext are
-resident in HBM before the timed region.
+resident in HBM before the timed region.  By default the sums of the hoisted baby steps stay in
+the extended basis (one ModDown per giant step); --plain-sums divides every hoisted rotation by
+P on its own.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--plain-sums]
 
 Prints one JSON line (see the design doc for the definitions of the roofline entries).
 """
@@ -113,11 +115,11 @@ def calibration_kernel(g):
     g["torch"].cuda.synchronize()
 
 
-def cpu_baseline():
+def cpu_baseline(raised_sums=True):
     """The oracle as it stands on the host cores, on a bounded sample of the same workload: the
     ring of the benchmark, 3 full rotations, one hoisting + 3 hoisted rotations, 8 plaintext
-    multiply-accumulates and one rescale, each timed and scaled by the step's operation counts
-    (21 / 1 / 31 / 512 / 1)."""
+    multiply-accumulates, one ModDown (raised sums only) and one rescale, each timed and scaled by
+    the step's operation counts (21 / 1 / 31 / 512 / 1 / 1)."""
     from oracle import ckks, params
     prm = params.config2()
     ctx = ckks.Context(prm)
@@ -126,7 +128,7 @@ def cpu_baseline():
     rng = np.random.default_rng(0)
     z = rng.normal(size=ctx.S)
     ct = ctx.encrypt(sk, ctx.encode(z, prm.L), 3)
-    pt = ctx.encode(rng.normal(0, 0.02, ctx.S), prm.L)
+    w = rng.normal(0, 0.02, ctx.S)
 
     def timed(fn, reps):
         t0 = time.perf_counter()
@@ -134,17 +136,29 @@ def cpu_baseline():
             r = fn()
         return (time.perf_counter() - t0) / reps, r
 
-    t_rot, _ = timed(lambda: ctx.rotate(ct, 7, keys), 3)
     t_hoist, h = timed(lambda: ctx.hoist(ct), 1)
-    t_hrot, _ = timed(lambda: ctx.rotate_hoisted(ct, h, 64, keys), 3)
-    acc = ctx.mul_pt(ct, pt)
-    t_mac, _ = timed(lambda: ctx.mac_pt(acc, ct, pt), 8)
-    t_resc, _ = timed(lambda: ctx.rescale(acc), 1)
-    t_vmm = 21 * t_rot + t_hoist + 31 * t_hrot + 512 * t_mac + t_resc
+    if raised_sums:
+        pt = ctx.encode_ext(w, prm.L)
+        t_hrot, R = timed(lambda: ctx.rotate_hoisted_raised(ct, h, 64, keys), 3)
+        acc = [np.zeros_like(R[0]), np.zeros_like(R[1])]
+        t_mac, _ = timed(lambda: ctx.mac_pt_raised(acc, R, pt, prm.L), 8)
+        t_md, x = timed(lambda: ctx.moddown_ct(acc, prm.L, ct.scale * pt.scale), 1)
+        t_rot, _ = timed(lambda: ctx.rotate_add_raised(ct, 7, keys, acc), 3)
+    else:
+        pt = ctx.encode(w, prm.L)
+        t_rot, _ = timed(lambda: ctx.rotate(ct, 7, keys), 3)
+        t_hrot, _ = timed(lambda: ctx.rotate_hoisted(ct, h, 64, keys), 3)
+        x = ctx.mul_pt(ct, pt)
+        t_mac, _ = timed(lambda: ctx.mac_pt(x, ct, pt), 8)
+        t_md = 0.0
+    t_resc, _ = timed(lambda: ctx.rescale(x), 1)
+    t_vmm = 21 * t_rot + t_hoist + 31 * t_hrot + 512 * t_mac + t_md + t_resc
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": 1.0 / t_vmm, "unit": "VMM/s", "cores": cores, "kind": "oracle",
             "sample": "n=2^16, 24+4 primes: 3 rotations, 1 hoisting, 3 hoisted rotations, 8 pt-ct MACs, "
-                      "1 rescale timed; scaled by the step's counts 21/1/31/512/1 (extrapolated)",
+                      + ("1 ModDown, " if raised_sums else "") +
+                      "1 rescale timed; scaled by the step's counts 21/1/31/512/" + ("1/" if raised_sums else "") +
+                      "1 (extrapolated)",
             "key_switch_s": t_rot, "seconds_per_vmm": t_vmm}
 
 
@@ -203,6 +217,7 @@ def main():
         "dtype": "u64", "data": "synthetic",
         "config": {"workload": "config2: encrypted 4096-vector x plaintext 4096x4096, interleaved replicated "
                                "packing, BSGS 32x16, 52 rotations, 512 pt-ct MACs", "ring_degree": n,
+                   "baby_step_sums": "plain" if a.plain_sums else "extended basis",
                    "ciphertext_primes": limbs, "special_primes": K, "dnum": beta, "level": limbs - 1},
         "max_abs_err_vs_float64": err,
         "key_switches_per_s": 1.0 / t_rot, "key_switch_us": t_rot * 1e6,
@@ -214,7 +229,7 @@ def main():
         "roofline_inner_product": roofs["inner_product"],
     }
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline()
+        out["cpu_baseline"] = cpu_baseline(raised_sums=not a.plain_sums)
     print(json.dumps(out))
 
 

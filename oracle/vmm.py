@@ -133,6 +133,43 @@ def vmm_pt_double_hoisted(ctx, keys, plan: VmmPlan, cx, diagonals_ext):
     return ctx.rescale(acc)
 
 
+def vmm_pt_direct_giants(ctx, keys, plan: VmmPlan, cx, diagonals_ext):
+    """The same product with the giant steps unrolled: y' = inner_0 + sum_{k>=1} Rot(inner_k, k G)
+    (G = plan.giant_step) instead of the nested form Rot(... Rot(inner_{r_o-1}, G) + ..., G).  The
+    r_o - 1 rotations no longer depend on each other (they need r_o - 1 keys instead of one); each
+    inner_k is divided by P, raised again without the Galois map, and its rotation stays in the
+    extended basis, so that all of them and inner_0 share a single final ModDown."""
+    c = cx
+    for r in plan.pre_steps:
+        c = ctx.ct_add(c, ctx.rotate(c, r, keys))
+    hoisted = ctx.hoist(c)
+    raised = [ctx.raise_ct(c)] + [ctx.rotate_hoisted_raised(c, hoisted, r, keys) for r in plan.baby_steps[1:]]
+    ext = ctx.ext_idx(c.level)
+    scale = c.scale * diagonals_ext[0][0].scale
+    acc = None
+    for k in range(plan.r_o):
+        inner = [np.zeros((len(ext), ctx.n), dtype=np.uint64) for _ in range(2)]
+        for j in range(plan.r_i):
+            ctx.mac_pt_raised(inner, raised[j], diagonals_ext[j][k], c.level)
+        if k == 0:
+            acc = inner
+            continue
+        ck = ctx.moddown_ct(inner, c.level, scale)
+        R = ctx.rotate_hoisted_raised(ck, ctx.hoist(ck), k * plan.giant_step, keys)
+        acc = [ctx.add(acc[0], R[0], ext), ctx.add(acc[1], R[1], ext)]
+    y = ctx.moddown_ct(acc, c.level, scale)
+    for r in plan.reduce_steps:
+        y = ctx.ct_add(y, ctx.rotate(y, r, keys))
+    return ctx.rescale(y)
+
+
+def direct_giant_steps(plan: VmmPlan):
+    """Rotation amounts of vmm_pt_direct_giants: every multiple of the giant step instead of one."""
+    steps = list(plan.pre_steps) + list(plan.baby_steps[1:])
+    steps += [k * plan.giant_step for k in range(1, plan.r_o)]
+    return steps + list(plan.reduce_steps)
+
+
 def qk_scores(ops, lay: KvLayout, cq, k_cts, masks):
     """Sec. 5.1 with the multi-head layout of Sec. 5.3: scores of one query against the K
     cache.  masks[c] = lay.qk_mask(c) (slot vector or encoded plaintext)."""

@@ -155,3 +155,27 @@ def test_double_hoisted_vmm_decrypts_to_x_times_W(d_in, d_out, level, tau):
     plain = vmm.vmm_pt(vmm.CkksOps(ctx, keys), plan, ct, [[ctx.encode(v, level) for v in row] for row in diags])
     assert abs(y.scale / plain.scale - 1) < 1e-12
     assert np.abs(ctx.decrypt(sk, y) - ctx.decrypt(sk, plain)).max() < 1e-6
+
+
+@pytest.mark.parametrize("d_in,d_out,level,tau", [(64, 64, 3, 0), (16, 64, 2, 0), (64, 16, 4, 0), (32, 32, 1, 3)])
+def test_direct_giant_steps_vmm_decrypts_to_x_times_W(d_in, d_out, level, tau):
+    """Giant steps unrolled (independent rotations by k G, one shared ModDown): same rotation and
+    product counts, same message as the nested form."""
+    prm, ctx, sk = _toy_ctx()
+    x, W = inputs.vmm_inputs(6, d_in, d_out, "normal", 0.1)
+    plan = packing.make_plan(ctx.S, d_in, d_out, tau=tau)
+    assert plan.r_o >= 2
+    steps = vmm.direct_giant_steps(plan)
+    assert len(steps) == plan.n_rotations
+    keys = ctx.keygen_rotations(sk, sorted(set(steps) | set(plan.all_steps())), 2)
+    ct = ctx.level_drop(ctx.encrypt(sk, ctx.encode(plan.pack_input(x), prm.L), 3), level)
+    ext = [[ctx.encode_ext(v, level) for v in row] for row in plan.diagonals(W)]
+    r0, p0 = ctx.rot_count, ctx.ptmul_count
+    y = vmm.vmm_pt_direct_giants(ctx, keys, plan, ct, ext)
+    assert ctx.rot_count - r0 == plan.n_rotations and ctx.ptmul_count - p0 == plan.r_i * plan.r_o
+    assert y.level == level - 1
+    assert np.abs(plan.unpack_output(ctx.decrypt(sk, y).real) - x @ W).max() < TOL
+    nested = vmm.vmm_pt_double_hoisted(ctx, keys, plan, ct, ext)
+    assert abs(y.scale / nested.scale - 1) < 1e-12
+    assert np.abs(ctx.decrypt(sk, y) - ctx.decrypt(sk, nested)).max() < 1e-6
+    assert not np.array_equal(ctx.canonical(y), ctx.canonical(nested))     # different noise, same message
