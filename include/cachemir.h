@@ -175,8 +175,13 @@ cm_status cm_vmm_plan_create_from_coeffs(cm_ctx *ctx, int32_t d_in, int32_t d_ou
  *     summed there, and each sum is divided by P inside the giant step that consumes it.  Same
  *     rotations, same plaintext products, r_i - 1 fewer ModDowns; the weight plaintexts take
  *     level+1+K limbs each.  The result differs from the plain form by rounding noise only.
+ *   CM_VMM_DIRECT_GIANTS  (implies CM_VMM_RAISED_SUMS) the giant steps of Algorithm 1 are unrolled:
+ *     y' = inner_0 + sum_{k>=1} Rot(inner_k, k G) instead of the nested Rot(.. + Rot(inner_{r_o-1}, G), G).
+ *     Same number of rotations, but they are independent: their ModUps run as one batch, and all of
+ *     them share one ModDown.  Needs the r_o - 1 keys of k G (cm_vmm_plan_steps lists them)
+ *     instead of the single key of G.
  * Unknown flag bits: CM_E_INVAL. */
-enum { CM_VMM_RAISED_SUMS = 1 };
+enum { CM_VMM_RAISED_SUMS = 1, CM_VMM_DIRECT_GIANTS = 2 };
 cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
                                 int32_t level, double pt_scale, const double *W,
                                 const int64_t *coeffs, uint32_t flags, cm_vmm_plan **out);

@@ -18,7 +18,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 CM_QK, CM_SV = 0, 1
-CM_VMM_RAISED_SUMS = 1
+CM_VMM_RAISED_SUMS, CM_VMM_DIRECT_GIANTS = 1, 2
 
 
 class cm_params(C.Structure):
@@ -286,9 +286,10 @@ class Context:
         _chk(lib.cm_profile_get(self.h, family, C.byref(a), C.byref(b), C.byref(c)))
         return a.value, b.value, c.value
 
-    def vmm_plan(self, d_in, d_out, W=None, level=None, r_i=0, tau=0, pt_scale=0.0, coeffs=None, raised_sums=False):
+    def vmm_plan(self, d_in, d_out, W=None, level=None, r_i=0, tau=0, pt_scale=0.0, coeffs=None, raised_sums=False,
+                 direct_giants=False):
         return VmmPlan(self, d_in, d_out, W, self.L if level is None else level, r_i, tau, pt_scale, coeffs,
-                       raised_sums)
+                       raised_sums, direct_giants)
 
     def vmm_pt(self, evk, plan, x, out=None):
         out = out or Ct(self, x.level - 1)
@@ -338,10 +339,11 @@ class Evk:
 
 
 class VmmPlan:
-    def __init__(self, ctx, d_in, d_out, W, level, r_i, tau, pt_scale, coeffs, raised_sums=False):
+    def __init__(self, ctx, d_in, d_out, W, level, r_i, tau, pt_scale, coeffs, raised_sums=False, direct_giants=False):
         self.ctx, self.h, self.level = ctx, _vp(), level
+        raised_sums = raised_sums or direct_giants
         self.limbs = level + 1 + (ctx.K if raised_sums else 0)
-        flags = CM_VMM_RAISED_SUMS if raised_sums else 0
+        flags = (CM_VMM_RAISED_SUMS if raised_sums else 0) | (CM_VMM_DIRECT_GIANTS if direct_giants else 0)
         if coeffs is not None:
             c = _np(coeffs, np.int64)
             _chk(lib.cm_vmm_plan_create_ex(ctx.h, d_in, d_out, r_i, tau, level, pt_scale, None, c.ctypes.data,

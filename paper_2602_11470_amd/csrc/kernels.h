@@ -10,8 +10,10 @@ void launch_mul_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int 
 void launch_mac_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, int accumulate, hipStream_t st);
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st);
 void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st);
+// batch item z: table (z % tab_period)*tab_step (tab_period 0 = batch), input (z / in_group)*in_stride, output z*out_stride
 void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_step, int max_nt, u64 *out, const u64 *in,
-                      size_t in_stride, size_t out_stride, const u64 *own_src, u64 own_g, hipStream_t st);
+                      size_t in_stride, size_t out_stride, const u64 *own_src, u64 own_g, hipStream_t st,
+                      int tab_period = 0, int in_group = 1, size_t own_stride = 0);
 // (u0, u1)[ext][n] = sum_j perm_g(dig_j) * evk_j  [+ P * perm_g(c0) on the ciphertext limbs of u0]  [+ extra[2][ext][n]]
 void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g,
                           hipStream_t st, const u64 *c0 = nullptr, const u64 *extra = nullptr);
@@ -72,6 +74,18 @@ cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64
 // the special limbs of u are overwritten
 cm_status moddown_into(cm_ctx *ctx, u64 *u, int level, const u64 *addend, int addend_comps, u64 g, u64 *out,
                        const u64 *accum, hipStream_t st);
+// Tables for raising the second components of cnt ciphertexts at one level in single launches.
+struct KsManyTables {
+    int cnt = 0, level = 0, n_ntt = 0;
+    int *d_src_rows = nullptr, *d_in_mods = nullptr;     // inverse transform: c1 rows of the ciphertext array, moduli
+    int *d_ntt_rows = nullptr, *d_ntt_mods = nullptr;    // converted rows of the [cnt][beta][ext] digit array
+};
+cm_status ks_many_tables_create(cm_ctx *ctx, int level, int cnt, KsManyTables *t);
+void ks_many_tables_destroy(KsManyTables *t);
+// digits[k][beta][ext][n] (evaluation domain) of cts[k][2][level+1][n].c1 for k < cnt; ksin: cnt*(level+1) limbs of scratch
+cm_status ks_raise_many(cm_ctx *ctx, const KsManyTables &t, const u64 *cts, u64 *ksin, u64 *digits, hipStream_t st);
+// outs[r][2][level+1][n] = ModDown(us + r*2*ext*n) for r < cnt (any cnt; runs in batches); special limbs of us are overwritten
+cm_status moddown_many(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *outs, hipStream_t st);
 // raised[r][2][ext][n] = sum_j perm_{g_r}(digits_j) * key_r + P * perm_{g_r}(in.c0): hoisted rotations left in the
 // extended basis
 cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys,

@@ -114,23 +114,26 @@ void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, 
 // ---- fast base conversion ----------------------------------------------------------------------
 // in rows in_rows[m] (coefficient domain, residues under src moduli) -> out rows out_rows[r]:
 //   y_m = a_m * inv_hat_m mod q_m;  out_r = sum_m y_m * hat_{m,r} mod q_r   (no correction term)
-// blockIdx.z = batch item: table z*tab_step, input at z*in_stride, output at z*out_stride (the
-// digits of a raise use one table each and share the input; the two components of a ModDown share
-// the table).  blockIdx.y = group of CONV_TG targets; the cheap y_m are recomputed per group so
+// blockIdx.z = batch item: table (z % tab_period)*tab_step, input at (z / in_group)*in_stride,
+// output at z*out_stride (the digits of a raise use one table each and share the input; the two
+// components of a ModDown share the table; a raise of several polynomials runs its digits over
+// z % beta and its polynomials over z / beta).  blockIdx.y = group of CONV_TG targets; the cheap y_m are recomputed per group so
 // that a conversion fills the machine.  If own_src is given, group 0 also copies the source rows
 // of own_src (the evaluation-domain input) to the same rows of the output.
 template <int CONV_TG>
 __global__ __launch_bounds__(TPB) void k_base_conv(u64 *__restrict__ out, const u64 *__restrict__ in,
-                                                   const ConvDev *__restrict__ tabs, int tab_step, int n,
-                                                   size_t in_stride, size_t out_stride,
-                                                   const u64 *__restrict__ own_src, unsigned own_g, int logn) {
+                                                   const ConvDev *__restrict__ tabs, int tab_step, int tab_period,
+                                                   int in_group, int n, size_t in_stride, size_t out_stride,
+                                                   const u64 *__restrict__ own_src, size_t own_stride, unsigned own_g,
+                                                   int logn) {
     const int i = blockIdx.x * TPB + threadIdx.x;
-    const ConvDev &t = tabs[blockIdx.z * tab_step];
+    const ConvDev &t = tabs[(blockIdx.z % tab_period) * tab_step];
     const int ns = t.ns, nt = t.nt;
     const int r0 = blockIdx.y * CONV_TG;
     if (r0 >= nt) return;
-    in += blockIdx.z * in_stride;
+    in += (blockIdx.z / in_group) * in_stride;
     out += blockIdx.z * out_stride;
+    if (own_src) own_src += (blockIdx.z / in_group) * own_stride;
     u64 y[CONV_MAX_SRC];
 #pragma unroll
     for (int m = 0; m < CONV_MAX_SRC; m++) {
@@ -155,12 +158,15 @@ __global__ __launch_bounds__(TPB) void k_base_conv(u64 *__restrict__ out, const 
     }
 }
 void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_step, int max_nt, u64 *out, const u64 *in,
-                      size_t in_stride, size_t out_stride, const u64 *own_src, u64 own_g, hipStream_t st) {
+                      size_t in_stride, size_t out_stride, const u64 *own_src, u64 own_g, hipStream_t st, int tab_period,
+                      int in_group, size_t own_stride) {
+    if (tab_period <= 0) tab_period = batch;
     Prof prof_(ctx, CM_K_BASE_CONV, batch * max_nt, st);
     static int tg = getenv("CM_CONV_TG") ? atoi(getenv("CM_CONV_TG")) : 8;
 #define CONV_LAUNCH(TG)                                                                                              \
     hipLaunchKernelGGL(k_base_conv<TG>, dim3(ctx->n / TPB, (max_nt + TG - 1) / TG, batch), dim3(TPB), 0, st, out, in, \
-                       d_tabs, tab_step, ctx->n, in_stride, out_stride, own_src, (unsigned)own_g, ctx->logn)
+                       d_tabs, tab_step, tab_period, in_group, ctx->n, in_stride, out_stride, own_src, own_stride,    \
+                       (unsigned)own_g, ctx->logn)
     if (tg == 2) CONV_LAUNCH(2);
     else if (tg == 8) CONV_LAUNCH(8);
     else if (tg == 12) CONV_LAUNCH(12);
@@ -173,12 +179,12 @@ void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_ste
 // extended basis.  With g != 0 the digits are read through the Galois permutation (hoisted
 // rotations).  Two adjacent coefficients per lane (16-byte accesses); the permutation keeps
 // aligned pairs together (it maps i^1 to src^1).
-__global__ __launch_bounds__(TPB) void k_inner_product(u64 *__restrict__ u0, u64 *__restrict__ u1,
+// `extra` may be the output itself (a running sum): every lane reads its own words before it writes them.
+__global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
                                                        const u64 *__restrict__ dig, const u64 *__restrict__ evk,
                                                        const ModC *__restrict__ modc,
                                 int beta, int ext, int level, int L, int nmod, int n, int logn, unsigned g,
-                                const u64 *__restrict__ c0, const u64 *__restrict__ pmont,
-                                const u64 *__restrict__ extra) {
+                                const u64 *__restrict__ c0, const u64 *__restrict__ pmont, const u64 *extra) {
     unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
     int r = blockIdx.y;
     int mi = r <= level ? r : L + 1 + (r - level - 1);

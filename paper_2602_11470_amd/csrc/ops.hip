@@ -46,6 +46,7 @@ struct KsLevelFull : KsLevel {
     int *d_last_rows[4] = {nullptr, nullptr, nullptr, nullptr};   // [ncomp]: rows c*(level+1)+level of a ciphertext
     int *d_bsp_rows = nullptr, *d_bsp_mods = nullptr;   // special rows of CM_KS_BATCH stacked [2][ext] blocks
     int *d_bq_mods = nullptr;                           // 0..level repeated 2*CM_KS_BATCH times
+    std::vector<int> h_ntt_rows, h_ntt_mods;            // host copies of d_ntt_rows / d_ntt_mods
     ConvDev *d_modup = nullptr; // one table per digit
     ConvDev *d_moddown = nullptr;
     int modup_max_nt = 0;
@@ -96,6 +97,7 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
     k.d_modup = up(mu);
     k.d_ntt_rows = up(ntt_rows);
     k.d_ntt_mods = up(ntt_mods);
+    k.h_ntt_rows = ntt_rows, k.h_ntt_mods = ntt_mods;
     k.n_ntt = (int)ntt_rows.size();
     std::vector<int> sp_rows, sp_mods, q_rows, q3, last(3, level), red;
     for (int c = 0; c < 2; c++)
@@ -213,6 +215,68 @@ cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cn
 }
 u64 *arena_digits(const cm_ctx *ctx) { return arena_of(ctx).digits; }
 
+// ModDown of m <= CM_KS_BATCH stacked sums bu[r][2][ext][n] in one batch of launches:
+// outs[r] = ModDown(bu[r]) (+ perm_{gs[r]}(addend) on component 0)
+static void moddown_batch(cm_ctx *ctx, const KsLevelFull &k, u64 *bu, int m, const u64 *addend, const u64 *gs,
+                          u64 *const *outs, hipStream_t st) {
+    Arena A = arena_of(ctx);
+    const int level = k.level;
+    const size_t n = ctx->n, ublk = 2 * (size_t)k.ext * n, cblk = 2 * (size_t)(level + 1) * n;
+    launch_ntt_rows(ctx, bu, k.d_bsp_rows, k.d_bsp_mods, m * 2 * ctx->K, true, st);
+    launch_base_conv(ctx, k.d_moddown, 2 * m, 0, level + 1, A.bconv, bu, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr,
+                     0, st);
+    if (ctx->n == 65536) {
+        FinishBatch fb;
+        fb.items = m, fb.level = level, fb.ext = k.ext, fb.addend_comps = addend ? 1 : 0;
+        for (int r = 0; r < m; r++)
+            fb.u[r] = bu + r * ublk, fb.out[r] = outs[r], fb.accum[r] = nullptr, fb.g[r] = addend ? (unsigned)gs[r] : 0;
+        fb.addend = addend, fb.pinv = get_pinv(ctx, level);
+        launch_ntt_fwd_finish(ctx, A.bconv, k.d_bq_mods, fb, st);
+    } else {
+        launch_ntt(ctx, A.bconv, k.d_bq_mods, m * 2 * (level + 1), false, st);
+        for (int r = 0; r < m; r++)
+            launch_moddown_finish(ctx, outs[r], bu + r * ublk, A.bconv + r * cblk, get_pinv(ctx, level), addend,
+                                  addend ? 1 : 0, level, addend ? gs[r] : 0, nullptr, st);
+    }
+}
+cm_status moddown_many(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *outs, hipStream_t st) {
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    const size_t ublk = 2 * (size_t)k.ext * ctx->n;
+    for (int base = 0; base < cnt; base += CM_KS_BATCH) {
+        const int m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
+        moddown_batch(ctx, k, us + base * ublk, m, nullptr, nullptr, outs + base, st);
+    }
+    return CM_OK;
+}
+
+cm_status ks_many_tables_create(cm_ctx *ctx, int level, int cnt, KsManyTables *t) {
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    std::vector<int> src_rows, in_mods, rows, mods;
+    for (int c = 0; c < cnt; c++) {
+        for (int l = 0; l <= level; l++) src_rows.push_back(c * 2 * (level + 1) + (level + 1) + l), in_mods.push_back(l);
+        for (size_t i = 0; i < k.h_ntt_rows.size(); i++)
+            rows.push_back(c * k.beta * k.ext + k.h_ntt_rows[i]), mods.push_back(k.h_ntt_mods[i]);
+    }
+    t->cnt = cnt, t->level = level, t->n_ntt = (int)k.h_ntt_rows.size();
+    t->d_src_rows = up(src_rows), t->d_in_mods = up(in_mods), t->d_ntt_rows = up(rows), t->d_ntt_mods = up(mods);
+    if (cnt > 0 && (!t->d_src_rows || !t->d_in_mods || !t->d_ntt_rows || !t->d_ntt_mods)) return CM_E_NOMEM;
+    return CM_OK;
+}
+void ks_many_tables_destroy(KsManyTables *t) {
+    hipFree(t->d_src_rows); hipFree(t->d_in_mods); hipFree(t->d_ntt_rows); hipFree(t->d_ntt_mods);
+    *t = KsManyTables();
+}
+cm_status ks_raise_many(cm_ctx *ctx, const KsManyTables &t, const u64 *cts, u64 *ksin, u64 *digits, hipStream_t st) {
+    if (t.cnt <= 0) return CM_OK;
+    const KsLevelFull &k = ks_level_full(ctx, t.level);
+    const size_t n = ctx->n, ln = (size_t)(t.level + 1) * n;
+    launch_ntt_src(ctx, ksin, nullptr, cts, t.d_src_rows, t.d_in_mods, t.cnt * (t.level + 1), true, st, 0);
+    launch_base_conv(ctx, k.d_modup, t.cnt * k.beta, 1, k.modup_max_nt, digits, ksin, ln, (size_t)k.ext * n, cts + ln, 0, st,
+                     k.beta, k.beta, 2 * ln);
+    launch_ntt_rows(ctx, digits, t.d_ntt_rows, t.d_ntt_mods, t.cnt * t.n_ntt, false, st);
+    return CM_OK;
+}
+
 // cnt hoisted rotations of one ciphertext `in` ([2][level+1][n]) whose raised digits are given:
 // outs[r] = ModDown(sum_j perm_{g_r}(digits_j) * key_r) + perm_{g_r}(in.c0).  The ModDown of up to
 // CM_KS_BATCH rotations runs as one batch so that its transforms and conversions fill the machine.
@@ -249,22 +313,7 @@ cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, cons
         const int base = b * CM_KS_BATCH, m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
         u64 *bu = A.bu + (b & 1) * bufw;
         hipStreamWaitEvent(st, inner_done[b], 0);
-        launch_ntt_rows(ctx, bu, k.d_bsp_rows, k.d_bsp_mods, m * 2 * ctx->K, true, st);
-        launch_base_conv(ctx, k.d_moddown, 2 * m, 0, level + 1, A.bconv, bu, (size_t)k.ext * n,
-                         (size_t)(level + 1) * n, nullptr, 0, st);
-        if (ctx->n == 65536) {
-            FinishBatch fb;
-            fb.items = m, fb.level = level, fb.ext = k.ext, fb.addend_comps = 1;
-            for (int r = 0; r < m; r++)
-                fb.u[r] = bu + r * ublk, fb.out[r] = outs[base + r], fb.accum[r] = nullptr, fb.g[r] = (unsigned)gs[base + r];
-            fb.addend = in, fb.pinv = get_pinv(ctx, level);
-            launch_ntt_fwd_finish(ctx, A.bconv, k.d_bq_mods, fb, st);
-        } else {
-            launch_ntt(ctx, A.bconv, k.d_bq_mods, m * 2 * (level + 1), false, st);
-            for (int r = 0; r < m; r++)
-                launch_moddown_finish(ctx, outs[base + r], bu + r * ublk, A.bconv + r * cblk, get_pinv(ctx, level), in, 1,
-                                      level, gs[base + r], nullptr, st);
-        }
+        moddown_batch(ctx, k, bu, m, in, gs + base, outs + base, st);
         moddown_done[b] = record(st);
     }
     return CM_OK;

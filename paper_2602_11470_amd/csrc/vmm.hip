@@ -20,6 +20,9 @@ struct cm_vmm_plan {
     std::vector<int> pre_steps, baby_steps, reduce_steps;
     int giant_step;
     bool raised = false;       // sums of the baby steps stay in the extended basis (one ModDown per giant step)
+    bool direct = false;       // giant steps unrolled: independent rotations by k*giant_step, one shared ModDown
+    KsManyTables many;         // direct: tables for raising the r_o - 1 inner sums at once
+    u64 *d_many = nullptr;     // direct: r_o - 1 ciphertexts, their coefficient-domain c1 and their raised digits
     int pt_limbs;              // level+1, or level+1+K when raised
     int *d_pt_mods = nullptr;  // modulus index of every plaintext limb
     u64 *d_pts = nullptr;      // [r_i*r_o][pt_limbs][n], multiplier form
@@ -97,9 +100,9 @@ static void diag_slots(const cm_vmm_plan *p, const std::vector<int> &lab, const 
     }
 }
 
-static cm_status plan_alloc(cm_vmm_plan *p, bool raised) {
+static cm_status plan_alloc(cm_vmm_plan *p, bool raised, bool direct) {
     cm_ctx *ctx = p->ctx;
-    p->raised = raised;
+    p->raised = raised, p->direct = direct;
     p->pt_limbs = p->level + 1 + (raised ? ctx->K : 0);
     std::vector<int> mods;
     for (int i = 0; i <= p->level; i++) mods.push_back(i);
@@ -109,6 +112,13 @@ static cm_status plan_alloc(cm_vmm_plan *p, bool raised) {
     if (hipMemcpy(p->d_pt_mods, mods.data(), mods.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess) return CM_E_HIP;
     if (hipMalloc((void **)&p->d_pts, (size_t)p->M * ptw * 8) != hipSuccess) return CM_E_NOMEM;
     if (hipMalloc((void **)&p->d_work, ((size_t)(p->r_i + p->r_o) * 2 * ptw + 3 * ctw) * 8) != hipSuccess) return CM_E_NOMEM;
+    if (direct && p->r_o > 1) {
+        const KsLevel &k = ks_level(ctx, p->level);
+        const size_t cnt = p->r_o - 1, per = ctw + (size_t)(p->level + 1) * n + (size_t)k.beta * k.ext * n;
+        cm_status s = ks_many_tables_create(ctx, p->level, (int)cnt, &p->many);
+        if (s != CM_OK) return s;
+        if (hipMalloc((void **)&p->d_many, cnt * per * 8) != hipSuccess) return CM_E_NOMEM;
+    }
     return CM_OK;
 }
 
@@ -128,11 +138,13 @@ static cm_status plan_load_diag(cm_vmm_plan *p, int idx, const int64_t *coeffs) 
 extern "C" cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
                                            int32_t level, double pt_scale, const double *W, const int64_t *coeffs,
                                            uint32_t flags, cm_vmm_plan **out) {
-    if (!ctx || (!W == !coeffs) || !out || (flags & ~(uint32_t)CM_VMM_RAISED_SUMS)) return CM_E_INVAL;
+    if (!ctx || (!W == !coeffs) || !out || (flags & ~(uint32_t)(CM_VMM_RAISED_SUMS | CM_VMM_DIRECT_GIANTS)))
+        return CM_E_INVAL;
+    const bool direct = (flags & CM_VMM_DIRECT_GIANTS) != 0, raised = direct || (flags & CM_VMM_RAISED_SUMS) != 0;
     cm_vmm_plan *p = new (std::nothrow) cm_vmm_plan();
     if (!p) return CM_E_NOMEM;
     cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, p);
-    if (s == CM_OK) s = plan_alloc(p, (flags & CM_VMM_RAISED_SUMS) != 0);
+    if (s == CM_OK) s = plan_alloc(p, raised, direct);
     if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
     if (coeffs) {
         for (int idx = 0; idx < p->M && s == CM_OK; idx++) s = plan_load_diag(p, idx, coeffs + (size_t)idx * ctx->n);
@@ -178,6 +190,8 @@ extern "C" cm_status cm_vmm_plan_create_from_coeffs(cm_ctx *ctx, int32_t d_in, i
 
 extern "C" void cm_vmm_plan_destroy(cm_vmm_plan *plan) {
     if (!plan) return;
+    ks_many_tables_destroy(&plan->many);
+    hipFree(plan->d_many);
     hipFree(plan->d_pt_mods);
     hipFree(plan->d_pts);
     hipFree(plan->d_work);
@@ -188,7 +202,8 @@ extern "C" int32_t cm_vmm_plan_steps(const cm_vmm_plan *p, int32_t *steps, int32
     if (!p) return 0;
     std::vector<int> all(p->pre_steps);
     for (int j = 1; j < p->r_i; j++) all.push_back(p->baby_steps[j]);
-    if (p->r_o > 1) all.push_back(p->giant_step);
+    for (int k = 1; k < p->r_o; k++)
+        if (k == 1 || p->direct) all.push_back(k * p->giant_step);
     all.insert(all.end(), p->reduce_steps.begin(), p->reduce_steps.end());
     for (int i = 0; i < (int)all.size() && i < cap && steps; i++) steps[i] = all[i];
     return (int32_t)all.size();
@@ -246,14 +261,31 @@ static cm_status vmm_pt_raised(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     }
     const int r_o = p->r_o;
     launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, ext, level, rw, (size_t)ext * n, 0, r_o, st);
-    // giant steps, Horner form: acc <- Rot(acc) + ModDown-ed inner_k in one key switch
     u64 *acc = c == t0 ? t1 : t0;
     other = t2;
-    CMCHK(moddown_into(ctx, inner + (size_t)(r_o - 1) * rw, level, nullptr, 0, 0, acc, nullptr, st));
-    for (int k = r_o - 2; k >= 0; k--) {
-        CMCHK(rotate_into(ctx, key_of(p->giant_step), acc, level, galois_of_step(ctx, p->giant_step), other, st, nullptr,
-                          inner + (size_t)k * rw));
-        std::swap(acc, other);
+    if (p->direct) {
+        // giant steps unrolled: inner_k -> ciphertext -> raised digits (all k at once); every rotation by
+        // k*G stays in the extended basis and joins inner_0; one ModDown for the whole sum
+        const KsLevel &kl = ks_level(ctx, level);
+        const int cnt = r_o - 1;
+        u64 *cts = p->d_many, *ksin = cts + (size_t)cnt * ctw, *digs = ksin + (size_t)cnt * limbs * n;
+        std::vector<u64 *> outs;
+        for (int k = 0; k < cnt; k++) outs.push_back(cts + (size_t)k * ctw);
+        CMCHK(moddown_many(ctx, inner + rw, level, cnt, outs.data(), st));
+        CMCHK(ks_raise_many(ctx, p->many, cts, ksin, digs, st));
+        for (int k = 1; k < r_o; k++)
+            launch_inner_product(ctx, inner, inner + (size_t)ext * n, digs + (size_t)(k - 1) * kl.beta * kl.ext * n,
+                                 key_of(k * p->giant_step), kl.beta, level, galois_of_step(ctx, k * p->giant_step), st,
+                                 cts + (size_t)(k - 1) * ctw, inner);
+        CMCHK(moddown_into(ctx, inner, level, nullptr, 0, 0, acc, nullptr, st));
+    } else {
+        // giant steps, Horner form: acc <- Rot(acc) + ModDown-ed inner_k in one key switch
+        CMCHK(moddown_into(ctx, inner + (size_t)(r_o - 1) * rw, level, nullptr, 0, 0, acc, nullptr, st));
+        for (int k = r_o - 2; k >= 0; k--) {
+            CMCHK(rotate_into(ctx, key_of(p->giant_step), acc, level, galois_of_step(ctx, p->giant_step), other, st,
+                              nullptr, inner + (size_t)k * rw));
+            std::swap(acc, other);
+        }
     }
     // 3. reduce inside the ciphertext
     for (int r : p->reduce_steps) {
@@ -277,7 +309,8 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     auto key_of = [&](int step) { return find_key(evk, galois_of_step(ctx, step)); };
     for (int r : p->pre_steps) if (!key_of(r)) return CM_E_NOKEY;
     for (int j = 1; j < p->r_i; j++) if (!key_of(p->baby_steps[j])) return CM_E_NOKEY;
-    if (p->r_o > 1 && !key_of(p->giant_step)) return CM_E_NOKEY;
+    for (int k = 1; k < p->r_o; k++)
+        if ((k == 1 || p->direct) && !key_of(k * p->giant_step)) return CM_E_NOKEY;
     for (int r : p->reduce_steps) if (!key_of(r)) return CM_E_NOKEY;
 
     if (p->raised) return vmm_pt_raised(ctx, evk, p, x, y, st);

@@ -80,8 +80,9 @@ def test_vmm_pt_matches_oracle_and_float64(env, d_in, d_out, level, r_i, tau, se
     assert np.abs(plan.unpack_output(out2.real) - x @ W).max() < TOL
 
 
-def _raised_case(e, d_in, d_out, level, r_i, tau, seed):
-    """vmm_pt with the baby-step sums kept in the extended basis against the oracle's form of it."""
+def _raised_case(e, d_in, d_out, level, r_i, tau, seed, direct=False):
+    """vmm_pt with the baby-step sums kept in the extended basis (and, with direct, the giant steps
+    unrolled) against the oracle's form of it."""
     from oracle import packing, vmm
     from paper_2602_11470_amd import inputs
     octx, gctx = e["octx"], e["gctx"]
@@ -91,16 +92,19 @@ def _raised_case(e, d_in, d_out, level, r_i, tau, seed):
     diag_coeffs = [[octx.encode_coeffs(v, scale) for v in row] for row in plan.diagonals(W)]
     odiags = [[octx.pt_from_coeffs_ext(c, level, scale) for c in row] for row in diag_coeffs]
     flat = np.stack([c for row in diag_coeffs for c in row])
-    gplan = gctx.vmm_plan(d_in, d_out, level=level, r_i=plan.r_i, tau=tau, coeffs=flat, raised_sums=True)
+    gplan = gctx.vmm_plan(d_in, d_out, level=level, r_i=plan.r_i, tau=tau, coeffs=flat, raised_sums=True,
+                          direct_giants=direct)
     assert (gplan.r_i, gplan.r_o, gplan.n_rotations) == (plan.r_i, plan.r_o, plan.n_rotations)
+    steps = vmm.direct_giant_steps(plan) if direct else plan.all_steps()
+    assert sorted(set(gplan.steps())) == sorted(set(steps)) and (not direct or len(gplan.steps()) == plan.n_rotations)
     # the plaintexts live on level+1+K limbs
     ext = octx.ext_idx(level)
     j, k = plan.r_i - 1, plan.r_o - 1
     assert np.array_equal(gplan.diag_export(j, k), octx.intt(odiags[j][k].m, ext))
-    okeys = octx.keygen_rotations(e["osk"], plan.all_steps(), 2)
+    okeys = octx.keygen_rotations(e["osk"], steps, 2)
     gkeys = gctx.keygen_rotations(e["gsk"], gplan.steps(), 2)
     ox, gx = _enc_both(e, plan.pack_input(x), level, 3)
-    oy = vmm.vmm_pt_double_hoisted(octx, okeys, plan, ox, odiags)
+    oy = (vmm.vmm_pt_direct_giants if direct else vmm.vmm_pt_double_hoisted)(octx, okeys, plan, ox, odiags)
     gy = gctx.vmm_pt(gkeys, gplan, gx)
     _same(e, oy, gy)
     out = gctx.decrypt(e["gsk"], gy)
@@ -121,8 +125,21 @@ def test_vmm_pt_raised_sums_matches_oracle_and_float64(env, d_in, d_out, level, 
     _raised_case(env, d_in, d_out, level, r_i, tau, seed)
 
 
+@pytest.mark.parametrize("d_in,d_out,level,r_i,tau,seed", [
+    (64, 64, 4, 0, 0, 0),          # one giant step
+    (64, 64, 2, 1, 0, 1),          # no baby steps, one giant step
+    (512, 512, 3, 4, 0, 2),        # 128 diagonals as 4 baby x 32 giant steps: 31 independent rotations (4 ModDown batches)
+    (128, 512, 4, 0, 0, 3),
+    (512, 128, 1, 0, 0, 4),
+    (128, 128, 4, 2, 5, 5),
+])
+def test_vmm_pt_direct_giants_matches_oracle_and_float64(env, d_in, d_out, level, r_i, tau, seed):
+    _raised_case(env, d_in, d_out, level, r_i, tau, seed, direct=True)
+
+
+@pytest.mark.parametrize("direct", [False, True])
 @pytest.mark.parametrize("level", [5, 4, 2])
-def test_vmm_pt_raised_sums_with_two_primes_per_digit(level):
+def test_vmm_pt_raised_sums_with_two_primes_per_digit(level, direct):
     """Digits of two primes and two special primes (level 4: the last digit holds one prime)."""
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
@@ -133,7 +150,7 @@ def test_vmm_pt_raised_sums_with_two_primes_per_digit(level):
     try:
         assert gctx.moduli().tolist() == prm.moduli
         e = dict(B=B, octx=octx, gctx=gctx, osk=octx.keygen_secret(1), gsk=gctx.keygen_secret(1), prm=prm)
-        _raised_case(e, 128, 128, level, 0, 0, 7)
+        _raised_case(e, 128, 128, level, 0, 0, 7, direct)
     finally:
         gctx.close()
 
