@@ -43,12 +43,12 @@ def measured_traffic():
     return out
 
 
-def gpu_setup(raised_sums=True):
+def gpu_setup(raised_sums=True, direct_giants=True):
     import torch
     from paper_2602_11470_amd import binding as B, inputs
     ctx = B.llama_ring(24, 4)
     x, W = inputs.vmm_inputs(1, D, D)
-    plan = ctx.vmm_plan(D, D, W=W, raised_sums=raised_sums)
+    plan = ctx.vmm_plan(D, D, W=W, raised_sums=raised_sums, direct_giants=direct_giants)
     sk = ctx.keygen_secret(1)
     keys = ctx.keygen_rotations(sk, plan.steps(), 2)
     t = ctx.S // D
@@ -168,6 +168,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--nested-giants", action="store_true",
+                    help="giant steps in the nested (Horner) form with one key, as Algorithm 1 prints them")
     ap.add_argument("--plain-sums", action="store_true",
                     help="divide every hoisted rotation by P on its own (31 more ModDowns per step)")
     a = ap.parse_args()
@@ -175,7 +177,7 @@ def main():
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
-    g = gpu_setup(raised_sums=not a.plain_sums)
+    g = gpu_setup(raised_sums=not a.plain_sums, direct_giants=not (a.plain_sums or a.nested_giants))
     sec, err = time_steps(g, a.steps, a.warmup)
     if not err < 1e-4:
         print(f"bench.py: decrypted result off by {err}", file=sys.stderr)

@@ -30,8 +30,12 @@ void launch_sample_gauss(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs,
 void launch_evk_assemble(cm_ctx *ctx, u64 *b_out, u64 *a_io, const u64 *e, const u64 *s_mont, const u64 *d_fac, u64 g, hipStream_t st);
 void launch_encrypt(cm_ctx *ctx, u64 *c0, const u64 *a, const u64 *e, const u64 *s_mont, const u64 *pt, int limbs, hipStream_t st);
 void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int ncomp, int ct_limbs, int limbs, hipStream_t st);
+// pts: all r_i*r_o plaintexts in the blocked layout written by launch_pt_block
 void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, int level,
-                    size_t ct_stride, size_t pt_stride, int k0, int k1, hipStream_t st);
+                    size_t ct_stride, int k0, int k1, hipStream_t st);
+// copies plaintext (j,k) from plain[limbs][n] into the blocked array (to_blocked) or back
+void launch_pt_block(cm_ctx *ctx, u64 *blocked, u64 *plain, int limbs, int r_i, int r_o, int j, int k, bool to_blocked,
+                     hipStream_t st);
 
 // Tail of a ModDown fused into the last pass of the forward transform of its converted limbs:
 // for item r, component c, limb l:  out = (u - NTT(conv)) * P^{-1} (+ addend through the Galois map

@@ -401,25 +401,30 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 }
 
 // ---- packed product: inner_k = sum_j baby_j * p_{j,k} ---------------------------------------------------
-// babies: r_i ciphertexts [2][limbs][n] at stride ct_stride; pts: plaintext (j,k) at
-// (j*r_o + k)*pt_stride, multiplier form; out: r_o ciphertexts at stride ct_stride.  Limb l has
+// babies: r_i ciphertexts [2][limbs][n] at stride ct_stride; out: r_o ciphertexts at stride
+// ct_stride; pts: the r_i*r_o plaintexts in multiplier form, blocked for streaming:
+//     word c of chunk ch (64 coefficients) of limb l of plaintext (j,k) at
+//     (((l*(n/64) + ch)*r_o + k)*r_i + j)*64 + c
+// so that the workgroup that owns (l, ch) reads one contiguous run of r_o*r_i*512 bytes, and the
+// wave that owns k one run of r_i*512 bytes.  Limb l has
 // modulus index l up to `level`, and the special primes follow when limbs = level + 1 + K (sums
 // kept in the extended basis).
 // The baby ciphertexts are staged in LDS: a workgroup owns 64 coefficients of
 // one limb; its four waves take the k = k0 + wave, k0 + wave + 4, ... and every lane sums over all
 // j for its k, so each output is written once and each plaintext word is read once.  Up to 32
-// baby ciphertexts per pass (32 KiB of LDS); products are summed 8 at a time before a REDC.
+// baby ciphertexts per pass (32 KiB of LDS).
 #define MAC_CO 64
 #define MAC_JC 32
 __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, const u64 *__restrict__ babies,
                                                      const u64 *__restrict__ pts, const ModC *__restrict__ modc,
                                                      int r_i, int r_o, int limbs, int n, size_t ct_stride,
-                                                     size_t pt_stride, int k0, int k1, int level, int L) {
+                                                     int k0, int k1, int level, int L) {
     __shared__ u64 sb[MAC_JC * 2 * MAC_CO];
     const int l = blockIdx.y, i0 = blockIdx.x * MAC_CO;
     const int co = threadIdx.x & (MAC_CO - 1), kq = threadIdx.x >> 6;
     const ModC m = modc[l <= level ? l : L + 1 + (l - level - 1)];
     const size_t o = (size_t)l * n + i0, cs = (size_t)limbs * n;
+    const u64 *pblk = pts + ((size_t)l * (n / MAC_CO) + blockIdx.x) * r_o * r_i * MAC_CO + co;
     for (int j0 = 0; j0 < r_i; j0 += MAC_JC) {
         const int jn = r_i - j0 < MAC_JC ? r_i - j0 : MAC_JC;
         __syncthreads();
@@ -428,16 +433,21 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
             sb[e] = babies[(size_t)(j0 + (jc >> 1)) * ct_stride + (jc & 1) * cs + o + c];
         }
         __syncthreads();
+        // A sum of products is reduced when one more group of 8 could pass q * 2^64 (the bound of
+        // REDC): after every group for the 60-bit special primes, once per pass below 2^59.
+        const int redc_every = (m.q >> 59) ? 8 : MAC_JC;
         for (int k = k0 + kq; k < k1; k += 4) {
             u64 v0 = 0, v1 = 0;
+            const u64 *pk = pblk + ((size_t)k * r_i + j0) * MAC_CO;
+            u64 p[8], pn[8];
+#pragma unroll
+            for (int jj = 0; jj < 8; jj++) p[jj] = jj < jn ? __builtin_nontemporal_load(pk + (size_t)jj * MAC_CO) : 0;
+            u128 s0 = 0, s1 = 0;
             for (int j8 = 0; j8 < jn; j8 += 8) {
-                u64 p[8];
+                // the next group is in flight while this one is multiplied
 #pragma unroll
                 for (int jj = 0; jj < 8; jj++)
-                    p[jj] = j8 + jj < jn
-                                ? __builtin_nontemporal_load(pts + ((size_t)(j0 + j8 + jj) * r_o + k) * pt_stride + o + co)
-                                : 0;
-                u128 s0 = 0, s1 = 0;
+                    pn[jj] = j8 + 8 + jj < jn ? __builtin_nontemporal_load(pk + (size_t)(j8 + 8 + jj) * MAC_CO) : 0;
 #pragma unroll
                 for (int jj = 0; jj < 8; jj++) {
                     if (j8 + jj < jn) {
@@ -445,8 +455,13 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
                         s1 += (u128)sb[((j8 + jj) * 2 + 1) * MAC_CO + co] * p[jj];
                     }
                 }
-                v0 = addmod(v0, redc(s0, m.q, m.qinv), m.q);
-                v1 = addmod(v1, redc(s1, m.q, m.qinv), m.q);
+                if ((j8 + 8) % redc_every == 0 || j8 + 8 >= jn) {
+                    v0 = addmod(v0, redc(s0, m.q, m.qinv), m.q);
+                    v1 = addmod(v1, redc(s1, m.q, m.qinv), m.q);
+                    s0 = s1 = 0;
+                }
+#pragma unroll
+                for (int jj = 0; jj < 8; jj++) p[jj] = pn[jj];
             }
             u64 *dst = out + (size_t)k * ct_stride + o + co;
             if (j0) {
@@ -459,8 +474,21 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
     }
 }
 void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, int level,
-                    size_t ct_stride, size_t pt_stride, int k0, int k1, hipStream_t st) {
+                    size_t ct_stride, int k0, int k1, hipStream_t st) {
     Prof prof_(ctx, CM_K_VMM_MAC, r_i * (k1 - k0), st);
     hipLaunchKernelGGL(k_vmm_mac_lds, dim3(ctx->n / MAC_CO, limbs), dim3(TPB), 0, st, out, babies, pts, ctx->d_modc, r_i,
-                       r_o, limbs, ctx->n, ct_stride, pt_stride, k0, k1, level, ctx->L);
+                       r_o, limbs, ctx->n, ct_stride, k0, k1, level, ctx->L);
+}
+// plaintext (j,k) between its plain form src[limbs][n] and its place in the blocked array
+__global__ void k_pt_block(u64 *blocked, u64 *plain, int n, int r_i, int r_o, int j, int k, int to_blocked) {
+    const int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
+    const size_t b = ((((size_t)l * (n / MAC_CO) + i / MAC_CO) * r_o + k) * r_i + j) * MAC_CO + i % MAC_CO;
+    const size_t p = (size_t)l * n + i;
+    if (to_blocked) blocked[b] = plain[p];
+    else plain[p] = blocked[b];
+}
+void launch_pt_block(cm_ctx *ctx, u64 *blocked, u64 *plain, int limbs, int r_i, int r_o, int j, int k, bool to_blocked,
+                     hipStream_t st) {
+    hipLaunchKernelGGL(k_pt_block, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, blocked, plain, ctx->n, r_i, r_o, j, k,
+                       to_blocked ? 1 : 0);
 }

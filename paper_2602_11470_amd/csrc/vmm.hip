@@ -25,7 +25,7 @@ struct cm_vmm_plan {
     u64 *d_many = nullptr;     // direct: r_o - 1 ciphertexts, their coefficient-domain c1 and their raised digits
     int pt_limbs;              // level+1, or level+1+K when raised
     int *d_pt_mods = nullptr;  // modulus index of every plaintext limb
-    u64 *d_pts = nullptr;      // [r_i*r_o][pt_limbs][n], multiplier form
+    u64 *d_pts = nullptr;      // r_i*r_o plaintexts of pt_limbs limbs, multiplier form, blocked by 64 coefficients
     u64 *d_work = nullptr;     // r_i baby + r_o inner ciphertexts of 2*pt_limbs limbs + 3 temporary ciphertexts
 };
 
@@ -125,12 +125,12 @@ static cm_status plan_alloc(cm_vmm_plan *p, bool raised, bool direct) {
 // plaintext polynomial of integer coefficients on the plan's limbs, evaluation domain, multiplier form
 static cm_status plan_load_diag(cm_vmm_plan *p, int idx, const int64_t *coeffs) {
     cm_ctx *ctx = p->ctx;
-    u64 *dst = p->d_pts + (size_t)idx * p->pt_limbs * ctx->n;
-    u64 *stage = p->d_work;                     // free until the first product
+    u64 *stage = p->d_work, *plain = stage + ctx->n;          // the work area is free until the first product
     HIPCHK(hipMemcpy(stage, coeffs, (size_t)ctx->n * 8, hipMemcpyHostToDevice));
-    launch_reduce_i64(ctx, dst, (const long long *)stage, p->d_pt_mods, p->pt_limbs, 0);
-    launch_ntt_rows(ctx, dst, nullptr, p->d_pt_mods, p->pt_limbs, false, 0);
-    launch_to_mont(ctx, dst, p->d_pt_mods, p->pt_limbs, 0);
+    launch_reduce_i64(ctx, plain, (const long long *)stage, p->d_pt_mods, p->pt_limbs, 0);
+    launch_ntt_rows(ctx, plain, nullptr, p->d_pt_mods, p->pt_limbs, false, 0);
+    launch_to_mont(ctx, plain, p->d_pt_mods, p->pt_limbs, 0);
+    launch_pt_block(ctx, p->d_pts, plain, p->pt_limbs, p->r_i, p->r_o, idx / p->r_o, idx % p->r_o, true, 0);
     HIPCHK(hipDeviceSynchronize());
     return CM_OK;
 }
@@ -220,7 +220,8 @@ extern "C" cm_status cm_vmm_plan_diag_export(cm_ctx *ctx, const cm_vmm_plan *p, 
     const size_t words = (size_t)p->pt_limbs * ctx->n;
     u64 *tmp = nullptr;
     if (hipMalloc((void **)&tmp, words * 8) != hipSuccess) return CM_E_NOMEM;
-    launch_from_mont(ctx, tmp, p->d_pts + (size_t)(j * p->r_o + k) * words, p->d_pt_mods, p->pt_limbs, 0);
+    launch_pt_block(ctx, p->d_pts, tmp, p->pt_limbs, p->r_i, p->r_o, j, k, false, 0);
+    launch_from_mont(ctx, tmp, tmp, p->d_pt_mods, p->pt_limbs, 0);
     launch_ntt_rows(ctx, tmp, nullptr, p->d_pt_mods, p->pt_limbs, true, 0);
     hipError_t e = hipMemcpy(out, tmp, words * 8, hipMemcpyDeviceToHost);
     hipFree(tmp);
@@ -260,7 +261,7 @@ static cm_status vmm_pt_raised(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
         CMCHK(ks_apply_many_raised(ctx, digits, level, p->r_i - 1, keys.data(), gs.data(), c, dst.data(), st));
     }
     const int r_o = p->r_o;
-    launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, ext, level, rw, (size_t)ext * n, 0, r_o, st);
+    launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, ext, level, rw, 0, r_o, st);
     u64 *acc = c == t0 ? t1 : t0;
     other = t2;
     if (p->direct) {
@@ -340,7 +341,7 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     }
     //    multiply-accumulate: inner_k = sum_j baby_j * p_{j,k}; streams every weight plaintext once
     const int r_o = p->r_o;
-    launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, limbs, level, ctw, ptw, 0, r_o, st);
+    launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, limbs, level, ctw, 0, r_o, st);
     //    giant steps, Horner form
     u64 *acc = inner + (size_t)(r_o - 1) * ctw;
     for (int k = r_o - 2; k >= 0; k--) {
