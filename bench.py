@@ -162,6 +162,50 @@ def cpu_baseline(raised_sums=True):
             "key_switch_s": t_rot, "seconds_per_vmm": t_vmm}
 
 
+def attention_workload(a):
+    """Config 3 (not the default line): one query against an encrypted cache of 1024 tokens, 32 heads
+    x 128 dims on the config-2 ring; cache ciphertexts one level below the top.  q K^T = 3 + 128 x
+    (relinearisation + 7 rotations) key switches; scores V = 15 hoisted + 7 giant + 3 rotations and
+    8 relinearisations.  Cache contents are random slot vectors (timing does not depend on values;
+    parity of this path is in tests/)."""
+    import torch
+    from paper_2602_11470_amd import binding as B
+    ctx = B.llama_ring(24, 4)
+    H, E, L = 32, 128, ctx.L
+    lv = L - 1
+    kv = ctx.kv_create(H, E, lv, r_i=16)
+    sk = ctx.keygen_secret(1)
+    keys = ctx.keygen_rotations(sk, kv.steps(), 2, with_relin=True)
+    rng = np.random.default_rng(3)
+    enc = lambda seed: ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), L), seed), lv)
+    for c in range(128):
+        kv.load(B.CM_QK, c, enc(100 + c))
+        kv.load(B.CM_SV, c, enc(300 + c))
+    kv.set_tokens(1024)
+    q, sc = enc(10), enc(11)
+    res = {}
+    for name, which, x in (("qk", B.CM_QK, q), ("sv", B.CM_SV, sc)):
+        for _ in range(max(1, a.warmup // 2)):
+            ctx.vmm_kv(keys, kv, which, x)
+        torch.cuda.synchronize()
+        reps = max(1, a.steps // 5)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ctx.vmm_kv(keys, kv, which, x)
+        torch.cuda.synchronize()
+        res[name] = (time.perf_counter() - t0) / reps
+    ks_qk = 3 + 128 * 8
+    print(json.dumps({
+        "metric": "encrypted-cache attention products/s (config 3: q K^T and scores V, 32 heads x 128 dims, "
+                  "context 1024, n=2^16, 24x50-bit + 4x60-bit primes)",
+        "value": 1.0 / (res["qk"] + res["sv"]), "unit": "attention steps/s", "n_gpus": 1,
+        "higher_is_better": True, "dtype": "u64", "data": "synthetic", "vs_baseline": None,
+        "config": {"workload": "config3: q K^T (128 K ciphertexts) + scores V (128 V ciphertexts, 16 baby x 8 giant)",
+                   "cache_level": lv},
+        "qk_ms": res["qk"] * 1e3, "sv_ms": res["sv"] * 1e3,
+        "qk_key_switches": ks_qk, "qk_key_switches_per_s": ks_qk / res["qk"]}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -172,11 +216,16 @@ def main():
                     help="giant steps in the nested (Horner) form with one key, as Algorithm 1 prints them")
     ap.add_argument("--plain-sums", action="store_true",
                     help="divide every hoisted rotation by P on its own (31 more ModDowns per step)")
+    ap.add_argument("--workload", choices=["projection", "attention"], default="projection",
+                    help="projection = config 2 (the benchmark line); attention = config 3, a line of its own")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if a.workload == "attention":
+        attention_workload(a)
+        return
     g = gpu_setup(raised_sums=not a.plain_sums, direct_giants=not (a.plain_sums or a.nested_giants))
     sec, err = time_steps(g, a.steps, a.warmup)
     if not err < 1e-4:

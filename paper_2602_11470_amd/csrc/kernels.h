@@ -38,15 +38,15 @@ void launch_pt_block(cm_ctx *ctx, u64 *blocked, u64 *plain, int limbs, int r_i, 
                      hipStream_t st);
 
 // Tail of a ModDown fused into the last pass of the forward transform of its converted limbs:
-// for item r, component c, limb l:  out = (u - NTT(conv)) * P^{-1} (+ addend through the Galois map
-// g_r on the first addend_comps components) (+ accum).  Passed to the kernel by value.
+// for item r, component c, limb l:  out = (u - NTT(conv)) * P^{-1} (+ addend_r through the Galois map
+// g_r on the first addend_comps components) (+ accum_r).  Passed to the kernel by value.
 struct FinishBatch {
     int items = 0, level = 0, ext = 0, addend_comps = 0;
     const u64 *u[CM_KS_BATCH];        // [2][ext][n] per item (evaluation domain)
     u64 *out[CM_KS_BATCH];            // [2][level+1][n] per item
     const u64 *accum[CM_KS_BATCH];    // nullable; may alias out
     unsigned g[CM_KS_BATCH];
-    const u64 *addend = nullptr;      // [2][level+1][n], nullable; must not alias any out
+    const u64 *addend[CM_KS_BATCH];   // [2][level+1][n] per item, nullable; must not alias any out
     const u64 *pinv = nullptr;        // [level+1][2]: P^{-1} mod q_l and its Shoup companion
 };
 // forward transform of conv[items*2*(level+1)][n] (mods 0..level repeating) with that tail; n = 65536 only
@@ -78,24 +78,36 @@ cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64
 // the special limbs of u are overwritten
 cm_status moddown_into(cm_ctx *ctx, u64 *u, int level, const u64 *addend, int addend_comps, u64 g, u64 *out,
                        const u64 *accum, hipStream_t st);
-// Tables for raising the second components of cnt ciphertexts at one level in single launches.
+// Tables for raising component `comp` of cnt stacked ciphertexts of ncomp components at one level in
+// single launches.
 struct KsManyTables {
-    int cnt = 0, level = 0, n_ntt = 0;
+    int cnt = 0, level = 0, n_ntt = 0, ncomp = 2, comp = 1;
     int *d_src_rows = nullptr, *d_in_mods = nullptr;     // inverse transform: c1 rows of the ciphertext array, moduli
     int *d_ntt_rows = nullptr, *d_ntt_mods = nullptr;    // converted rows of the [cnt][beta][ext] digit array
 };
-cm_status ks_many_tables_create(cm_ctx *ctx, int level, int cnt, KsManyTables *t);
+cm_status ks_many_tables_create(cm_ctx *ctx, int level, int cnt, KsManyTables *t, int ncomp = 2, int comp = 1);
 void ks_many_tables_destroy(KsManyTables *t);
-// digits[k][beta][ext][n] (evaluation domain) of cts[k][2][level+1][n].c1 for k < cnt; ksin: cnt*(level+1) limbs of scratch
-cm_status ks_raise_many(cm_ctx *ctx, const KsManyTables &t, const u64 *cts, u64 *ksin, u64 *digits, hipStream_t st);
+// digits[k][beta][ext][n] (evaluation domain) of component t.comp of cts[k][t.ncomp][level+1][n] for k < m <= t.cnt
+// (through the Galois map g if g != 0); ksin: m*(level+1) limbs of scratch
+cm_status ks_raise_many(cm_ctx *ctx, const KsManyTables &t, const u64 *cts, u64 *ksin, u64 *digits, hipStream_t st,
+                        int m = -1, u64 g = 0);
 // outs[r][2][level+1][n] = ModDown(us + r*2*ext*n) for r < cnt (any cnt; runs in batches); special limbs of us are overwritten
 cm_status moddown_many(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *outs, hipStream_t st);
+// one batch (m <= CM_KS_BATCH): outs[r] = ModDown(us + r*2*ext*n) + perm_g(addends[r]) on the first addend_comps
+// components (+ accums[r]); addends / accums nullable arrays of nullable pointers
+cm_status moddown_batch_into(cm_ctx *ctx, u64 *us, int level, int m, const u64 *const *addends, int addend_comps, u64 g,
+                             const u64 *const *accums, u64 *const *outs, hipStream_t st);
 // raised[r][2][ext][n] = sum_j perm_{g_r}(digits_j) * key_r + P * perm_{g_r}(in.c0): hoisted rotations left in the
 // extended basis
 cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys,
                                const u64 *gs, const u64 *in, u64 *const *raised, hipStream_t st);
-cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st);
+// out[comp][level][n] = in[comp][level+1][n] divided by q_level; up to 2*CM_KS_BATCH stacked components when the
+// caller gives scratch last[ncomp][n] and red[ncomp][level][n] (up to three without)
+cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st, u64 *last = nullptr,
+                       u64 *red = nullptr);
 u64 *arena_digits(const cm_ctx *ctx);
+// room for CM_KS_BATCH key-switch sums [2][L+1+K][n] (what moddown_batch_into consumes)
+u64 *arena_batch_sums(const cm_ctx *ctx);
 cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys, const u64 *gs,
                         const u64 *in, u64 *const *outs, hipStream_t st);
 const u64 *find_key(const cm_evk *evk, u64 g);

@@ -26,6 +26,9 @@ struct cm_kv {
     u64 *d_mask_v = nullptr;                // base: slots (0, h, 0) all h;        level+1
     u64 *d_work = nullptr;
     size_t work_words = 0;
+    // query-times-K runs CM_KS_BATCH key ciphertexts at a time: tables for raising the third
+    // component of their tensor products (level) and the second of their rotated sums (level-1)
+    KsManyTables relin_tabs, rot_tabs;
 };
 
 static int ilog2(int x) {
@@ -66,15 +69,24 @@ extern "C" cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32
     kv->scale = scale > 0 ? scale : ctx->prm.scale;
     kv->nk_max = (max_tokens + kv->t - 1) / kv->t;
     const size_t n = ctx->n, ctw = 2 * (size_t)(level + 1) * n;
-    // work: r_i babies + r_o inner + tensor (1.5 ct) + 5 temporaries, all sized for level+1 inputs of append
+    // work: r_i babies + r_o inner + tensor (1.5 ct) + 5 temporaries, all sized for level+1 inputs of append;
+    // or the batch buffers of query-times-K (see kv_qk), whichever is larger
     const size_t ctw_up = 2 * (size_t)(level + 2) * n;
     kv->work_words = (size_t)(kv->r_i + kv->r_o + 8) * ctw_up;
+    {
+        const KsLevel &kl = ks_level(ctx, level);
+        const size_t ln = (size_t)(level + 1) * n, B = CM_KS_BATCH;
+        const size_t qk = 5 * ctw + B * (3 * ln + 3 * ctw + ln + (size_t)kl.beta * kl.ext * n + 2 * n + 2 * (size_t)level * n);
+        if (qk > kv->work_words) kv->work_words = qk;
+    }
     bool ok = hipMalloc((void **)&kv->d_k, (size_t)kv->nk_max * ctw * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_v, (size_t)kv->E * ctw * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_mask_qk, (size_t)level * n * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_mask_k, (size_t)(level + 2) * n * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_mask_v, (size_t)(level + 2) * n * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_work, kv->work_words * 8) == hipSuccess;
+    if (ok) ok = ks_many_tables_create(ctx, level, CM_KS_BATCH, &kv->relin_tabs, 3, 2) == CM_OK &&
+                 ks_many_tables_create(ctx, level - 1, CM_KS_BATCH, &kv->rot_tabs, 2, 1) == CM_OK;
     if (!ok) { cm_kv_destroy(kv); return CM_E_NOMEM; }
     hipMemset(kv->d_k, 0, (size_t)kv->nk_max * ctw * 8);      // an all-zero ciphertext encrypts 0
     hipMemset(kv->d_v, 0, (size_t)kv->E * ctw * 8);
@@ -91,6 +103,8 @@ extern "C" void cm_kv_destroy(cm_kv *kv) {
     if (!kv) return;
     hipFree(kv->d_k), hipFree(kv->d_v), hipFree(kv->d_mask_qk), hipFree(kv->d_mask_k), hipFree(kv->d_mask_v);
     hipFree(kv->d_work);
+    ks_many_tables_destroy(&kv->relin_tabs);
+    ks_many_tables_destroy(&kv->rot_tabs);
     delete kv;
 }
 // Parity hook: replace a base mask by given integer coefficients (kind 0: query-times-K mask at
@@ -206,28 +220,55 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     for (int i = 0; i < ilog2(kv->E); i++) if (!find_key(evk, rot_g(kv, (long long)(1 << i) * kv->H * kv->t))) return CM_E_NOKEY;
     const int nk = (kv->ntok + kv->t - 1) / kv->t;
     if (nk < 1) return CM_E_LAYOUT;
-    u64 *cq = kv->d_work, *tmp = cq + ctw, *T = tmp + ctw, *P = T + 3 * ln, *R = P + ctw, *acc = R + ctw, *mask = acc + ctw;
+    // The key ciphertexts are independent until the final sum, so CM_KS_BATCH of them go through every
+    // step together: their raises, their ModDowns and their rescales are single batches of launches.
+    const KsLevel &kl = ks_level(ctx, lv), &kl1 = ks_level(ctx, lv - 1);
+    const size_t B = CM_KS_BATCH, ln1 = (size_t)lv * n, ctw1 = 2 * ln1;
+    u64 *cq = kv->d_work, *tmp = cq + ctw, *acc = tmp + ctw, *mask = acc + ctw;
+    u64 *TB = mask + ctw, *PB = TB + B * 3 * ln, *RB0 = PB + B * ctw, *RB1 = RB0 + B * ctw, *ksin = RB1 + B * ctw;
+    u64 *digits = ksin + B * ln, *last = digits + B * (size_t)kl.beta * kl.ext * n, *red = last + B * 2 * n;
+    u64 *bu = arena_batch_sums(ctx);
     HIPCHK(hipMemcpyAsync(cq, in->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
     for (int i = 0; i < ilog2(kv->t); i++) {                     // replicate q over the t residues
         u64 g = rot_g(kv, -(1 << i));
         CMCHK(rotate_into(ctx, find_key(evk, g), cq, lv, g, tmp, st, cq));      // tmp = cq + Rot(cq)
         std::swap(cq, tmp);
     }
-    u64 *digits = arena_digits(ctx);
-    for (int c = 0; c < nk; c++) {
-        launch_tensor(ctx, T, cq, kv->d_k + (size_t)c * ctw, limbs, 0, st);
-        CMCHK(ks_raise(ctx, T + 2 * ln, lv, digits, st));
-        CMCHK(ks_apply(ctx, digits, relin, lv, 0, T, 2, P, st));
-        CMCHK(rescale_into(ctx, P, 2, lv, R, st));
-        u64 *r0 = R, *r1 = P;                                    // P is free again: second buffer
+    for (int c0 = 0; c0 < nk; c0 += CM_KS_BATCH) {
+        const int m = nk - c0 < CM_KS_BATCH ? nk - c0 : CM_KS_BATCH;
+        const u64 *adds[CM_KS_BATCH], *accs[CM_KS_BATCH];
+        u64 *outs[CM_KS_BATCH];
+        // tensor products, relinearised together
+        for (int r = 0; r < m; r++) launch_tensor(ctx, TB + r * 3 * ln, cq, kv->d_k + (size_t)(c0 + r) * ctw, limbs, 0, st);
+        CMCHK(ks_raise_many(ctx, kv->relin_tabs, TB, ksin, digits, st, m, 0));
+        const size_t ublk = 2 * (size_t)kl.ext * n, dblk = (size_t)kl.beta * kl.ext * n;
+        for (int r = 0; r < m; r++) {
+            launch_inner_product(ctx, bu + r * ublk, bu + r * ublk + (size_t)kl.ext * n, digits + r * dblk, relin, kl.beta, lv,
+                                 0, st);
+            adds[r] = TB + r * 3 * ln, outs[r] = PB + r * ctw;
+        }
+        CMCHK(moddown_batch_into(ctx, bu, lv, m, adds, 2, 0, nullptr, outs, st));
+        CMCHK(rescale_into(ctx, PB, 2 * m, lv, RB0, st, last, red));       // stacked: [m][2][lv+1] -> [m][2][lv]
+        u64 *r0 = RB0, *r1 = RB1;
+        const size_t ublk1 = 2 * (size_t)kl1.ext * n, dblk1 = (size_t)kl1.beta * kl1.ext * n;
         for (int i = 0; i < ilog2(kv->E); i++) {                 // sum over the E dims of every head
             u64 g = rot_g(kv, (long long)(1 << i) * kv->H * kv->t);
-            CMCHK(rotate_into(ctx, find_key(evk, g), r0, lv - 1, g, r1, st, r0));
+            const u64 *key = find_key(evk, g);
+            CMCHK(ks_raise_many(ctx, kv->rot_tabs, r0, ksin, digits, st, m, g));
+            for (int r = 0; r < m; r++) {
+                launch_inner_product(ctx, bu + r * ublk1, bu + r * ublk1 + (size_t)kl1.ext * n, digits + r * dblk1, key,
+                                     kl1.beta, lv - 1, 0, st);
+                adds[r] = accs[r] = r0 + r * ctw1, outs[r] = r1 + r * ctw1;
+            }
+            CMCHK(moddown_batch_into(ctx, bu, lv - 1, m, adds, 1, g, accs, outs, st));
             std::swap(r0, r1);
         }
-        // keep copy e = c: base mask rotated right by c*H*t
-        launch_automorphism(ctx, mask, kv->d_mask_qk, lv, rot_g(kv, -(long long)(c % kv->E) * kv->H * kv->t), st);
-        launch_mac_pt(ctx, acc, r0, mask, 2, lv, c > 0, st);
+        for (int r = 0; r < m; r++) {
+            // keep copy e = c: base mask rotated right by c*H*t
+            const int c = c0 + r;
+            launch_automorphism(ctx, mask, kv->d_mask_qk, lv, rot_g(kv, -(long long)(c % kv->E) * kv->H * kv->t), st);
+            launch_mac_pt(ctx, acc, r0 + r * ctw1, mask, 2, lv, c > 0, st);
+        }
     }
     CMCHK(rescale_into(ctx, acc, 2, lv - 1, out->dev, st));
     out->level = lv - 2, out->ncomp = 2;

@@ -314,7 +314,7 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
     const unsigned pos0 = (unsigned)chunk * 4096 + threadIdx.x;
     const size_t row = ((size_t)c * (fb.level + 1) + l) * n;
     const u64 *up = fb.u[r] + ((size_t)c * fb.ext + l) * n + pos0;
-    const u64 *ad = (fb.addend && c < fb.addend_comps) ? fb.addend + row : nullptr;
+    const u64 *ad = (fb.addend[r] && c < fb.addend_comps) ? fb.addend[r] + row : nullptr;
     const u64 *ac = fb.accum[r] ? fb.accum[r] + row + pos0 : nullptr;
     u64 *op = fb.out[r] + row + pos0;
     const unsigned g = fb.g[r];

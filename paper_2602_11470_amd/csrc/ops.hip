@@ -41,9 +41,9 @@ static T *up(const std::vector<T> &v) {
 
 struct KsLevelFull : KsLevel {
     int *d_q_mods3 = nullptr;   // 0..level repeated three times
-    int *d_last_mods = nullptr; // level, level, level
-    int *d_red_mods = nullptr;  // 0..level-1 repeated three times
-    int *d_last_rows[4] = {nullptr, nullptr, nullptr, nullptr};   // [ncomp]: rows c*(level+1)+level of a ciphertext
+    int *d_last_mods = nullptr; // level, repeated for up to RESCALE_MAX_COMPS components
+    int *d_red_mods = nullptr;  // 0..level-1, repeated likewise
+    int *d_last_rows = nullptr; // rows c*(level+1)+level of stacked components
     int *d_bsp_rows = nullptr, *d_bsp_mods = nullptr;   // special rows of CM_KS_BATCH stacked [2][ext] blocks
     int *d_bq_mods = nullptr;                           // 0..level repeated 2*CM_KS_BATCH times
     std::vector<int> h_ntt_rows, h_ntt_mods;            // host copies of d_ntt_rows / d_ntt_mods
@@ -52,6 +52,7 @@ struct KsLevelFull : KsLevel {
     int modup_max_nt = 0;
 };
 
+#define RESCALE_MAX_COMPS (2 * CM_KS_BATCH)
 static ConvDev conv_dev(const cm_ctx *ctx, const ConvTable &t, const std::vector<int> &in_rows,
                         const std::vector<int> &out_rows) {
     ConvDev d;
@@ -99,17 +100,17 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
     k.d_ntt_mods = up(ntt_mods);
     k.h_ntt_rows = ntt_rows, k.h_ntt_mods = ntt_mods;
     k.n_ntt = (int)ntt_rows.size();
-    std::vector<int> sp_rows, sp_mods, q_rows, q3, last(3, level), red;
+    std::vector<int> sp_rows, sp_mods, q_rows, q3, last(RESCALE_MAX_COMPS, level), red;
     for (int c = 0; c < 2; c++)
         for (int s = 0; s < ctx->K; s++) {
             sp_rows.push_back(c * k.ext + level + 1 + s);
             sp_mods.push_back(ctx->L + 1 + s);
         }
     for (int i = 0; i <= level; i++) q_rows.push_back(i);
-    for (int c = 0; c < 3; c++) {
+    for (int c = 0; c < 3; c++)
         for (int i = 0; i <= level; i++) q3.push_back(i);
+    for (int c = 0; c < RESCALE_MAX_COMPS; c++)
         for (int i = 0; i < level; i++) red.push_back(i);
-    }
     if (red.empty()) red.push_back(0);
     k.d_sp_rows = up(sp_rows);
     k.d_sp_mods = up(sp_mods);
@@ -129,10 +130,10 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
             }
         k.d_bsp_rows = up(br), k.d_bsp_mods = up(bm), k.d_bq_mods = up(bq);
     }
-    for (int nc = 1; nc <= 3; nc++) {
+    {
         std::vector<int> lr;
-        for (int c = 0; c < nc; c++) lr.push_back(c * (level + 1) + level);
-        k.d_last_rows[nc] = up(lr);
+        for (int c = 0; c < RESCALE_MAX_COMPS; c++) lr.push_back(c * (level + 1) + level);
+        k.d_last_rows = up(lr);
     }
     {
         std::vector<int> sp_in;
@@ -151,7 +152,7 @@ static void drop_ks_levels(cm_ctx *ctx) {
         if (it->first.first != ctx) { ++it; continue; }
         KsLevelFull &k = it->second;
         hipFree(k.d_modup); hipFree(k.d_moddown); hipFree(k.d_bsp_rows); hipFree(k.d_bsp_mods); hipFree(k.d_bq_mods);
-        for (int *p : k.d_last_rows) hipFree(p);
+        hipFree(k.d_last_rows);
         hipFree(k.d_ntt_rows); hipFree(k.d_ntt_mods); hipFree(k.d_sp_rows); hipFree(k.d_sp_mods);
         hipFree(k.d_q_rows); hipFree(k.d_q_mods3); hipFree(k.d_last_mods); hipFree(k.d_red_mods);
         it = g_ks.erase(it);
@@ -190,7 +191,7 @@ cm_status moddown_into(cm_ctx *ctx, u64 *u, int level, const u64 *addend, int ad
         FinishBatch fb;
         fb.items = 1, fb.level = level, fb.ext = k.ext, fb.addend_comps = addend_comps;
         fb.u[0] = u, fb.out[0] = out, fb.accum[0] = accum, fb.g[0] = (unsigned)g;
-        fb.addend = addend, fb.pinv = get_pinv(ctx, level);
+        fb.addend[0] = addend, fb.pinv = get_pinv(ctx, level);
         launch_ntt_fwd_finish(ctx, A.conv, k.d_q_mods3, fb, st);
         return CM_OK;
     }
@@ -214,46 +215,61 @@ cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cn
     return CM_OK;
 }
 u64 *arena_digits(const cm_ctx *ctx) { return arena_of(ctx).digits; }
+u64 *arena_batch_sums(const cm_ctx *ctx) { return arena_of(ctx).bu; }
 
 // ModDown of m <= CM_KS_BATCH stacked sums bu[r][2][ext][n] in one batch of launches:
-// outs[r] = ModDown(bu[r]) (+ perm_{gs[r]}(addend) on component 0)
-static void moddown_batch(cm_ctx *ctx, const KsLevelFull &k, u64 *bu, int m, const u64 *addend, const u64 *gs,
-                          u64 *const *outs, hipStream_t st) {
+// outs[r] = ModDown(bu[r]) (+ perm_{gs[r]}(addends[r]) on the first addend_comps components) (+ accums[r])
+static void moddown_batch(cm_ctx *ctx, const KsLevelFull &k, u64 *bu, int m, const u64 *const *addends, int addend_comps,
+                          const u64 *gs, const u64 *const *accums, u64 *const *outs, hipStream_t st) {
     Arena A = arena_of(ctx);
     const int level = k.level;
     const size_t n = ctx->n, ublk = 2 * (size_t)k.ext * n, cblk = 2 * (size_t)(level + 1) * n;
     launch_ntt_rows(ctx, bu, k.d_bsp_rows, k.d_bsp_mods, m * 2 * ctx->K, true, st);
     launch_base_conv(ctx, k.d_moddown, 2 * m, 0, level + 1, A.bconv, bu, (size_t)k.ext * n, (size_t)(level + 1) * n, nullptr,
                      0, st);
+    auto add_of = [&](int r) { return addends ? addends[r] : nullptr; };
+    auto acc_of = [&](int r) { return accums ? accums[r] : nullptr; };
     if (ctx->n == 65536) {
         FinishBatch fb;
-        fb.items = m, fb.level = level, fb.ext = k.ext, fb.addend_comps = addend ? 1 : 0;
-        for (int r = 0; r < m; r++)
-            fb.u[r] = bu + r * ublk, fb.out[r] = outs[r], fb.accum[r] = nullptr, fb.g[r] = addend ? (unsigned)gs[r] : 0;
-        fb.addend = addend, fb.pinv = get_pinv(ctx, level);
+        fb.items = m, fb.level = level, fb.ext = k.ext, fb.addend_comps = addends ? addend_comps : 0;
+        for (int r = 0; r < CM_KS_BATCH; r++) fb.addend[r] = nullptr, fb.accum[r] = nullptr;
+        for (int r = 0; r < m; r++) {
+            fb.u[r] = bu + r * ublk, fb.out[r] = outs[r], fb.accum[r] = acc_of(r), fb.addend[r] = add_of(r);
+            fb.g[r] = add_of(r) && gs ? (unsigned)gs[r] : 0;
+        }
+        fb.pinv = get_pinv(ctx, level);
         launch_ntt_fwd_finish(ctx, A.bconv, k.d_bq_mods, fb, st);
     } else {
         launch_ntt(ctx, A.bconv, k.d_bq_mods, m * 2 * (level + 1), false, st);
         for (int r = 0; r < m; r++)
-            launch_moddown_finish(ctx, outs[r], bu + r * ublk, A.bconv + r * cblk, get_pinv(ctx, level), addend,
-                                  addend ? 1 : 0, level, addend ? gs[r] : 0, nullptr, st);
+            launch_moddown_finish(ctx, outs[r], bu + r * ublk, A.bconv + r * cblk, get_pinv(ctx, level), add_of(r),
+                                  add_of(r) ? addend_comps : 0, level, add_of(r) && gs ? gs[r] : 0, acc_of(r), st);
     }
+}
+cm_status moddown_batch_into(cm_ctx *ctx, u64 *us, int level, int m, const u64 *const *addends, int addend_comps, u64 g,
+                             const u64 *const *accums, u64 *const *outs, hipStream_t st) {
+    if (m < 1 || m > CM_KS_BATCH) return CM_E_INVAL;
+    u64 gs[CM_KS_BATCH];
+    for (int r = 0; r < m; r++) gs[r] = g;
+    moddown_batch(ctx, ks_level_full(ctx, level), us, m, addends, addend_comps, gs, accums, outs, st);
+    return CM_OK;
 }
 cm_status moddown_many(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *outs, hipStream_t st) {
     const KsLevelFull &k = ks_level_full(ctx, level);
     const size_t ublk = 2 * (size_t)k.ext * ctx->n;
     for (int base = 0; base < cnt; base += CM_KS_BATCH) {
         const int m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
-        moddown_batch(ctx, k, us + base * ublk, m, nullptr, nullptr, outs + base, st);
+        moddown_batch(ctx, k, us + base * ublk, m, nullptr, 0, nullptr, nullptr, outs + base, st);
     }
     return CM_OK;
 }
 
-cm_status ks_many_tables_create(cm_ctx *ctx, int level, int cnt, KsManyTables *t) {
+cm_status ks_many_tables_create(cm_ctx *ctx, int level, int cnt, KsManyTables *t, int ncomp, int comp) {
     const KsLevelFull &k = ks_level_full(ctx, level);
     std::vector<int> src_rows, in_mods, rows, mods;
+    t->ncomp = ncomp, t->comp = comp;
     for (int c = 0; c < cnt; c++) {
-        for (int l = 0; l <= level; l++) src_rows.push_back(c * 2 * (level + 1) + (level + 1) + l), in_mods.push_back(l);
+        for (int l = 0; l <= level; l++) src_rows.push_back((c * ncomp + comp) * (level + 1) + l), in_mods.push_back(l);
         for (size_t i = 0; i < k.h_ntt_rows.size(); i++)
             rows.push_back(c * k.beta * k.ext + k.h_ntt_rows[i]), mods.push_back(k.h_ntt_mods[i]);
     }
@@ -266,14 +282,18 @@ void ks_many_tables_destroy(KsManyTables *t) {
     hipFree(t->d_src_rows); hipFree(t->d_in_mods); hipFree(t->d_ntt_rows); hipFree(t->d_ntt_mods);
     *t = KsManyTables();
 }
-cm_status ks_raise_many(cm_ctx *ctx, const KsManyTables &t, const u64 *cts, u64 *ksin, u64 *digits, hipStream_t st) {
-    if (t.cnt <= 0) return CM_OK;
+cm_status ks_raise_many(cm_ctx *ctx, const KsManyTables &t, const u64 *cts, u64 *ksin, u64 *digits, hipStream_t st, int m,
+                        u64 g) {
+    if (m < 0) m = t.cnt;
+    if (m == 0) return CM_OK;
+    if (m > t.cnt) return CM_E_INVAL;
     const KsLevelFull &k = ks_level_full(ctx, t.level);
     const size_t n = ctx->n, ln = (size_t)(t.level + 1) * n;
-    launch_ntt_src(ctx, ksin, nullptr, cts, t.d_src_rows, t.d_in_mods, t.cnt * (t.level + 1), true, st, 0);
-    launch_base_conv(ctx, k.d_modup, t.cnt * k.beta, 1, k.modup_max_nt, digits, ksin, ln, (size_t)k.ext * n, cts + ln, 0, st,
-                     k.beta, k.beta, 2 * ln);
-    launch_ntt_rows(ctx, digits, t.d_ntt_rows, t.d_ntt_mods, t.cnt * t.n_ntt, false, st);
+    // the tables list the items in order, so the first m items are a prefix of every table
+    launch_ntt_src(ctx, ksin, nullptr, cts, t.d_src_rows, t.d_in_mods, m * (t.level + 1), true, st, g);
+    launch_base_conv(ctx, k.d_modup, m * k.beta, 1, k.modup_max_nt, digits, ksin, ln, (size_t)k.ext * n,
+                     cts + (size_t)t.comp * ln, g, st, k.beta, k.beta, (size_t)t.ncomp * ln);
+    launch_ntt_rows(ctx, digits, t.d_ntt_rows, t.d_ntt_mods, m * t.n_ntt, false, st);
     return CM_OK;
 }
 
@@ -313,7 +333,9 @@ cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, cons
         const int base = b * CM_KS_BATCH, m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
         u64 *bu = A.bu + (b & 1) * bufw;
         hipStreamWaitEvent(st, inner_done[b], 0);
-        moddown_batch(ctx, k, bu, m, in, gs + base, outs + base, st);
+        const u64 *adds[CM_KS_BATCH];
+        for (int r = 0; r < m; r++) adds[r] = in;
+        moddown_batch(ctx, k, bu, m, adds, 1, gs + base, nullptr, outs + base, st);
         moddown_done[b] = record(st);
     }
     return CM_OK;
@@ -625,14 +647,16 @@ extern "C" cm_status cm_relinearize(cm_ctx *ctx, const cm_evk *evk, const cm_ct 
     return CM_OK;
 }
 
-cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st) {
-    // out[comp][level][n]; must not alias in
+cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st, u64 *last, u64 *red) {
+    // out[comp][level][n]; must not alias in.  More than three components (several stacked
+    // ciphertexts) need caller scratch: last[ncomp][n], red[ncomp][level][n].
     const KsLevelFull &k = ks_level_full(ctx, level);
     Arena A = arena_of(ctx);
-    const size_t n = ctx->n;
-    launch_ntt_src(ctx, A.misc, nullptr, in, k.d_last_rows[ncomp], k.d_last_mods, ncomp, true, st);
-    u64 *red = A.tmp[2];
-    launch_rescale_reduce(ctx, red, A.misc, ncomp, level, st);
+    if (ncomp < 1 || ncomp > RESCALE_MAX_COMPS || (ncomp > 3 && (!last || !red))) return CM_E_INVAL;
+    if (!last) last = A.misc;
+    if (!red) red = A.tmp[2];
+    launch_ntt_src(ctx, last, nullptr, in, k.d_last_rows, k.d_last_mods, ncomp, true, st);
+    launch_rescale_reduce(ctx, red, last, ncomp, level, st);
     launch_ntt(ctx, red, k.d_red_mods, ncomp * level, false, st);
     launch_rescale_finish(ctx, out, in, red, get_qlinv(ctx, level), ncomp, level, st);
     return CM_OK;
