@@ -12,6 +12,8 @@ P on its own.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--plain-sums]
 
+    python bench.py --workload attention        (config 3, a JSON line of its own)
+
 Prints one JSON line (see the design doc for the definitions of the roofline entries).
 """
 import argparse
@@ -206,6 +208,38 @@ def attention_workload(a):
         "qk_key_switches": ks_qk, "qk_key_switches_per_s": ks_qk / res["qk"]}))
 
 
+def sweep_workload(a):
+    """Square projections of the paper's three model widths (Table 4) and its level sweep, in the
+    default form (raised sums, unrolled giant steps): ms per product.  A JSON line of its own."""
+    import torch
+    from paper_2602_11470_amd import binding as B, inputs
+    ctx = B.llama_ring(24, 4)
+    sk = ctx.keygen_secret(1)
+    rows = []
+    for d, level in ((4096, 23), (4096, 13), (4096, 4), (4096, 1), (2048, 23), (1024, 23)):
+        x, W = inputs.vmm_inputs(1, d, d)
+        plan = ctx.vmm_plan(d, d, W=W, level=level, direct_giants=True)
+        keys = ctx.keygen_rotations(sk, plan.steps(), 2)
+        slots = np.zeros(ctx.S)
+        slots[::ctx.S // d] = x
+        ct = ctx.level_drop(ctx.encrypt(sk, ctx.encode(slots, ctx.L), 3), level)
+        y = ctx.vmm_pt(keys, plan, ct)
+        for _ in range(a.warmup):
+            ctx.vmm_pt(keys, plan, ct, out=y)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            ctx.vmm_pt(keys, plan, ct, out=y)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / a.steps * 1e3
+        err = float(np.abs(ctx.decrypt(sk, y).real[::ctx.S // d] - x @ W).max())
+        rows.append({"d": d, "level": level, "rotations": plan.n_rotations, "pt_mults": plan.r_i * plan.r_o,
+                     "ms": ms, "max_abs_err": err})
+        del plan, keys
+    print(json.dumps({"metric": "ms per homomorphic VMM, widths of Table 4 and levels 23/13/4/1 (n=2^16, 24+4 primes)",
+                      "unit": "ms", "n_gpus": 1, "data": "synthetic", "dtype": "u64", "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -216,8 +250,9 @@ def main():
                     help="giant steps in the nested (Horner) form with one key, as Algorithm 1 prints them")
     ap.add_argument("--plain-sums", action="store_true",
                     help="divide every hoisted rotation by P on its own (31 more ModDowns per step)")
-    ap.add_argument("--workload", choices=["projection", "attention"], default="projection",
-                    help="projection = config 2 (the benchmark line); attention = config 3, a line of its own")
+    ap.add_argument("--workload", choices=["projection", "attention", "sweep"], default="projection",
+                    help="projection = config 2 (the benchmark line); attention = config 3; sweep = other widths "
+                         "and levels; the last two print a line of their own")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -225,6 +260,9 @@ def main():
         sys.exit(2)
     if a.workload == "attention":
         attention_workload(a)
+        return
+    if a.workload == "sweep":
+        sweep_workload(a)
         return
     g = gpu_setup(raised_sums=not a.plain_sums, direct_giants=not (a.plain_sums or a.nested_giants))
     sec, err = time_steps(g, a.steps, a.warmup)
@@ -259,7 +297,7 @@ def main():
                           "frac": ip_gbs / HBM_PEAK_GBS, "traffic": tr.get("k_inner_product"),
                           "kernel": "k_inner_product", "us_per_launch": ip_launch_s * 1e6},
     }
-    roofline = roofs.get(dom, roofs["ntt_fwd"])
+    roofline = roofs.get(dom, roofs["inner_product"])
     ks_bytes = limb_bytes * (2 * beta * ext + limbs + 2 * limbs)         # key once + input + output
     out = {
         "metric": "homomorphic VMMs/s (d=4096 projection, n=2^16, 24x50-bit + 4x60-bit primes, top level)",
@@ -276,8 +314,10 @@ def main():
         "key_switch_frac_of_hbm_peak": ks_bytes / t_rot / 1e9 / HBM_PEAK_GBS,
         "limb_ntts_per_s": ntt["units"] / (ntt["ms"] * 1e-3),
         "kernel_ms_per_step": {k: round(v["ms"], 4) for k, v in fam.items()},
+        "dominant_kernel_family": dom,
         "roofline": roofline,
         "roofline_inner_product": roofs["inner_product"],
+        "roofline_ntt_fwd": roofs["ntt_fwd"],
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(raised_sums=not a.plain_sums)

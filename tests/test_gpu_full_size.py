@@ -132,6 +132,36 @@ def test_config2_packed_product_decrypts_to_float64_product(ring2):
     assert np.abs(out4.real[::t] - x @ W).max() < TOL
 
 
+@pytest.mark.parametrize("d,level,rotations", [
+    (2048, 23, 30),      # TinyLlama-1.1B width (Table 4: 30 rotations)
+    (1024, 23, 20),      # GPT2-base width 768 padded to 1024 (Table 4: 20 rotations)
+    (4096, 13, 52),      # the paper's starting level
+    (4096, 1, 52),       # lowest level a product can run at (one digit, partial)
+])
+def test_other_widths_and_levels_decrypt_to_float64_product(ring2, d, level, rotations):
+    """Square projections of the paper's other models and of its level sweep on the full ring, in
+    the form bench.py times (raised sums, unrolled giant steps)."""
+    from paper_2602_11470_amd import inputs
+    B, octx, gctx, prm = ring2
+    x, W = inputs.vmm_inputs(7, d, d)
+    if d == 1024:                      # a 768-wide layer zero-padded to the next power of two
+        x[768:] = 0.0
+        W[768:, :] = 0.0
+        W[:, 768:] = 0.0
+    gplan = gctx.vmm_plan(d, d, W=W, level=level, direct_giants=True)
+    assert gplan.n_rotations == rotations
+    gsk = gctx.keygen_secret(1)
+    gkeys = gctx.keygen_rotations(gsk, gplan.steps(), 2)
+    t = gctx.S // d
+    slots = np.zeros(gctx.S)
+    slots[::t] = x
+    gx = gctx.level_drop(gctx.encrypt(gsk, gctx.encode(slots, gctx.L), 3), level)
+    gy = gctx.vmm_pt(gkeys, gplan, gx)
+    assert gy.level == level - 1
+    out = gctx.decrypt(gsk, gy)
+    assert np.abs(out.real[::t] - x @ W).max() < TOL
+
+
 def test_config3_attention_shapes_decrypt_to_float64_products(ring2):
     """Llama-3-8B attention shapes on the full ring: 32 heads x 128 dims (8 KV heads repeated 4x),
     t = 8 tokens per K ciphertext, 128 V ciphertexts with 16 baby x 8 giant steps.  A short

@@ -155,6 +155,39 @@ def test_vmm_pt_raised_sums_with_two_primes_per_digit(level, direct):
         gctx.close()
 
 
+@pytest.mark.parametrize("direct", [False, True])
+def test_vmm_pt_replays_from_a_captured_graph(env, direct):
+    """cm_vmm_pt only enqueues kernels and device copies on the caller's stream, so it can be
+    captured into a HIP graph: every replay (with eager work in between) reproduces the eager
+    result bit for bit."""
+    import torch
+    from paper_2602_11470_amd import inputs
+    e = env
+    gctx = e["gctx"]
+    x, W = inputs.vmm_inputs(9, 256, 256, "uniform", 0.05)
+    gplan = gctx.vmm_plan(256, 256, W=W, level=3, raised_sums=direct, direct_giants=direct)
+    gkeys = gctx.keygen_rotations(e["gsk"], gplan.steps(), 2)
+    slots = np.zeros(gctx.S)
+    slots[::gctx.S // 256] = x
+    _, gx = _enc_both(e, slots, 3, 4)
+    eager = gctx.vmm_pt(gkeys, gplan, gx)                      # also warms the per-level tables
+    torch.cuda.synchronize()
+    ref = gctx.ct_export(eager).copy()
+    out = gctx.vmm_pt(gkeys, gplan, gx)
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        gctx.vmm_pt(gkeys, gplan, gx, out=out)
+    for _ in range(3):
+        out.buf.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(gctx.ct_export(out), ref)
+        gctx.vmm_pt(gkeys, gplan, gx, out=eager)               # eager work between the replays
+        torch.cuda.synchronize()
+    assert np.abs(gctx.decrypt(e["gsk"], out).real[::gctx.S // 256] - x @ W).max() < TOL
+
+
 def test_vmm_pt_missing_key_and_level_errors(env):
     e = env
     B, gctx = e["B"], e["gctx"]
