@@ -17,6 +17,23 @@ void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_ste
 // (u0, u1)[ext][n] = sum_j perm_g(dig_j) * evk_j  [+ P * perm_g(c0) on the ciphertext limbs of u0]  [+ extra[2][ext][n]]
 void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g,
                           hipStream_t st, const u64 *c0 = nullptr, const u64 *extra = nullptr);
+// Up to IP_MAX_ITEMS inner products in one launch.  Output z < nz (out[z] = [2][ext][n]) is
+// extra[z] (nullable, may be out[z] itself) + the sum of items z*nsum .. z*nsum + nsum - 1, each
+// sum_j perm_g(dig_j) * key_j [+ P * perm_g(c0) on the ciphertext limbs of the first component].
+#define IP_MAX_ITEMS 32
+struct IpItem {
+    const u64 *dig, *key, *c0;
+    unsigned g, pad_;
+};
+struct IpBatch {
+    int nz = 0, nsum = 1;
+    IpItem it[IP_MAX_ITEMS];
+    u64 *out[IP_MAX_ITEMS];
+    const u64 *extra[IP_MAX_ITEMS];
+};
+void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st);
+// out[z] = sum_j it[z].dig_j * it[0].key_j for z < nz: one key for all arrays (read once), no Galois map, no c0, no extra
+void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st);
 // out[2][ext][n] = (P c0, P c1), zero on the special limbs
 void launch_raise_by_P(cm_ctx *ctx, u64 *out, const u64 *in, int level, hipStream_t st);
 void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,

@@ -225,6 +225,105 @@ __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
     *reinterpret_cast<ulonglong2 *>(u0 + o) = r0;
     *reinterpret_cast<ulonglong2 *>(u1 + o) = r1;
 }
+// Several inner products in one launch: blockIdx.z = output; output z sums nsum consecutive items
+// (each with its own digits, key, Galois element and optional c0) and an optional addend.
+__global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const ModC *__restrict__ modc, int beta, int ext,
+                                                             int level, int L, int nmod, int n, int logn,
+                                                             const u64 *__restrict__ pmont) {
+    const unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
+    const int r = blockIdx.y, z = blockIdx.z;
+    const int mi = r <= level ? r : L + 1 + (r - level - 1);
+    const ModC m = modc[mi];
+    const size_t o = (size_t)r * n + i2;
+    ulonglong2 r0 = make_ulonglong2(0, 0), r1 = make_ulonglong2(0, 0);
+    if (b.extra[z]) {
+        r0 = *reinterpret_cast<const ulonglong2 *>(b.extra[z] + o);
+        r1 = *reinterpret_cast<const ulonglong2 *>(b.extra[z] + (size_t)ext * n + o);
+    }
+    for (int s = 0; s < b.nsum; s++) {
+        const IpItem it = b.it[z * b.nsum + s];
+        const unsigned src = it.g ? perm_src(i2, it.g, logn) : i2;
+        const unsigned base = src & ~1u;
+        const bool swap = src & 1u;
+        u128 a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+        for (int j = 0; j < beta; j++) {
+            ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(it.dig + ((size_t)j * ext + r) * n + base);
+            u64 dx = swap ? d.y : d.x, dy = swap ? d.x : d.y;
+            const u64 *kb = it.key + (((size_t)j * 2 + 0) * nmod + mi) * n + i2;
+            ulonglong2 eb, ea;
+            eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
+            ea.x = __builtin_nontemporal_load(kb + (size_t)nmod * n), ea.y = __builtin_nontemporal_load(kb + (size_t)nmod * n + 1);
+            b0 += (u128)dx * eb.x;
+            b1 += (u128)dy * eb.y;
+            a0 += (u128)dx * ea.x;
+            a1 += (u128)dy * ea.y;
+        }
+        if (it.c0 && r <= level) {
+            ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(it.c0 + (size_t)r * n + base);
+            const u64 pm = pmont[r];
+            b0 += (u128)(swap ? d.y : d.x) * pm;
+            b1 += (u128)(swap ? d.x : d.y) * pm;
+        }
+        r0.x = addmod(r0.x, redc(b0, m.q, m.qinv), m.q), r0.y = addmod(r0.y, redc(b1, m.q, m.qinv), m.q);
+        r1.x = addmod(r1.x, redc(a0, m.q, m.qinv), m.q), r1.y = addmod(r1.y, redc(a1, m.q, m.qinv), m.q);
+    }
+    *reinterpret_cast<ulonglong2 *>(b.out[z] + o) = r0;
+    *reinterpret_cast<ulonglong2 *>(b.out[z] + (size_t)ext * n + o) = r1;
+}
+// The same key applied to nz digit arrays (no Galois map, no c0): a lane keeps its key words in
+// registers and runs over the arrays, so the key is read from HBM once per launch.
+#define IP_SHARED_MAX_BETA 8
+__global__ __launch_bounds__(TPB) void k_inner_product_shared_key(IpBatch b, const ModC *__restrict__ modc, int beta,
+                                                                  int ext, int level, int L, int nmod, int n) {
+    const unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
+    const int r = blockIdx.y;
+    const int mi = r <= level ? r : L + 1 + (r - level - 1);
+    const ModC m = modc[mi];
+    const size_t o = (size_t)r * n + i2;
+    ulonglong2 eb[IP_SHARED_MAX_BETA], ea[IP_SHARED_MAX_BETA];
+    const u64 *key = b.it[0].key;
+#pragma unroll
+    for (int j = 0; j < IP_SHARED_MAX_BETA; j++) {
+        if (j < beta) {
+            const u64 *kb = key + (((size_t)j * 2 + 0) * nmod + mi) * n + i2;
+            eb[j].x = __builtin_nontemporal_load(kb), eb[j].y = __builtin_nontemporal_load(kb + 1);
+            ea[j].x = __builtin_nontemporal_load(kb + (size_t)nmod * n), ea[j].y = __builtin_nontemporal_load(kb + (size_t)nmod * n + 1);
+        }
+    }
+    for (int z = 0; z < b.nz; z++) {
+        const u64 *dig = b.it[z].dig;
+        u128 a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+#pragma unroll
+        for (int j = 0; j < IP_SHARED_MAX_BETA; j++) {
+            if (j < beta) {
+                ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(dig + ((size_t)j * ext + r) * n + i2);
+                b0 += (u128)d.x * eb[j].x;
+                b1 += (u128)d.y * eb[j].y;
+                a0 += (u128)d.x * ea[j].x;
+                a1 += (u128)d.y * ea[j].y;
+            }
+        }
+        *reinterpret_cast<ulonglong2 *>(b.out[z] + o) = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
+        *reinterpret_cast<ulonglong2 *>(b.out[z] + (size_t)ext * n + o) = make_ulonglong2(redc(a0, m.q, m.qinv), redc(a1, m.q, m.qinv));
+    }
+}
+void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st) {
+    int ext = level + 1 + ctx->K;
+    if (beta > IP_SHARED_MAX_BETA) {          // more digits than a lane keeps: one plain launch per array
+        for (int z = 0; z < b.nz; z++)
+            launch_inner_product(ctx, b.out[z], b.out[z] + (size_t)ext * ctx->n, b.it[z].dig, b.it[0].key, beta, level, 0, st);
+        return;
+    }
+    Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz, st);
+    hipLaunchKernelGGL(k_inner_product_shared_key, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, b, ctx->d_modc, beta, ext,
+                       level, ctx->L, ctx->nmod, ctx->n);
+}
+void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st) {
+    Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz * b.nsum, st);
+    int ext = level + 1 + ctx->K;
+    hipLaunchKernelGGL(k_inner_product_batch, dim3(ctx->n / (2 * TPB), ext, b.nz), dim3(TPB), 0, st, b, ctx->d_modc, beta, ext,
+                       level, ctx->L, ctx->nmod, ctx->n, ctx->logn, ctx->d_pmont);
+}
 // out[2][ext][n] = (P c0, P c1) on the ciphertext limbs, zero on the special limbs
 __global__ void k_raise_by_P(u64 *__restrict__ out, const u64 *__restrict__ in, const ModC *__restrict__ modc,
                              const u64 *__restrict__ pmont, int level, int ext, int n) {

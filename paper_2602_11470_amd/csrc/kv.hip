@@ -242,11 +242,14 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
         for (int r = 0; r < m; r++) launch_tensor(ctx, TB + r * 3 * ln, cq, kv->d_k + (size_t)(c0 + r) * ctw, limbs, 0, st);
         CMCHK(ks_raise_many(ctx, kv->relin_tabs, TB, ksin, digits, st, m, 0));
         const size_t ublk = 2 * (size_t)kl.ext * n, dblk = (size_t)kl.beta * kl.ext * n;
+        IpBatch ip;
+        ip.nz = m, ip.nsum = 1;
         for (int r = 0; r < m; r++) {
-            launch_inner_product(ctx, bu + r * ublk, bu + r * ublk + (size_t)kl.ext * n, digits + r * dblk, relin, kl.beta, lv,
-                                 0, st);
+            ip.it[r].dig = digits + r * dblk, ip.it[r].key = relin, ip.it[r].c0 = nullptr, ip.it[r].g = 0;
+            ip.out[r] = bu + r * ublk, ip.extra[r] = nullptr;
             adds[r] = TB + r * 3 * ln, outs[r] = PB + r * ctw;
         }
+        launch_inner_product_shared_key(ctx, ip, kl.beta, lv, st);
         CMCHK(moddown_batch_into(ctx, bu, lv, m, adds, 2, 0, nullptr, outs, st));
         CMCHK(rescale_into(ctx, PB, 2 * m, lv, RB0, st, last, red));       // stacked: [m][2][lv+1] -> [m][2][lv]
         u64 *r0 = RB0, *r1 = RB1;
@@ -256,10 +259,10 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
             const u64 *key = find_key(evk, g);
             CMCHK(ks_raise_many(ctx, kv->rot_tabs, r0, ksin, digits, st, m, g));
             for (int r = 0; r < m; r++) {
-                launch_inner_product(ctx, bu + r * ublk1, bu + r * ublk1 + (size_t)kl1.ext * n, digits + r * dblk1, key,
-                                     kl1.beta, lv - 1, 0, st);
+                ip.it[r].dig = digits + r * dblk1, ip.it[r].key = key, ip.out[r] = bu + r * ublk1;
                 adds[r] = accs[r] = r0 + r * ctw1, outs[r] = r1 + r * ctw1;
             }
+            launch_inner_product_shared_key(ctx, ip, kl1.beta, lv - 1, st);
             CMCHK(moddown_batch_into(ctx, bu, lv - 1, m, adds, 1, g, accs, outs, st));
             std::swap(r0, r1);
         }

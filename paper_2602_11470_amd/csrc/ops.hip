@@ -210,8 +210,15 @@ cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u6
 cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys,
                                const u64 *gs, const u64 *in, u64 *const *raised, hipStream_t st) {
     const KsLevelFull &k = ks_level_full(ctx, level);
-    for (int r = 0; r < cnt; r++)
-        launch_inner_product(ctx, raised[r], raised[r] + (size_t)k.ext * ctx->n, digits, keys[r], k.beta, level, gs[r], st, in);
+    for (int base = 0; base < cnt; base += IP_MAX_ITEMS) {
+        IpBatch b;
+        b.nz = cnt - base < IP_MAX_ITEMS ? cnt - base : IP_MAX_ITEMS, b.nsum = 1;
+        for (int r = 0; r < b.nz; r++) {
+            b.it[r].dig = digits, b.it[r].key = keys[base + r], b.it[r].c0 = in, b.it[r].g = (unsigned)gs[base + r];
+            b.out[r] = raised[base + r], b.extra[r] = nullptr;
+        }
+        launch_inner_product_batch(ctx, b, k.beta, level, st);
+    }
     return CM_OK;
 }
 u64 *arena_digits(const cm_ctx *ctx) { return arena_of(ctx).digits; }

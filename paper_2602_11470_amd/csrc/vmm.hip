@@ -274,10 +274,17 @@ static cm_status vmm_pt_raised(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
         for (int k = 0; k < cnt; k++) outs.push_back(cts + (size_t)k * ctw);
         CMCHK(moddown_many(ctx, inner + rw, level, cnt, outs.data(), st));
         CMCHK(ks_raise_many(ctx, p->many, cts, ksin, digs, st));
-        for (int k = 1; k < r_o; k++)
-            launch_inner_product(ctx, inner, inner + (size_t)ext * n, digs + (size_t)(k - 1) * kl.beta * kl.ext * n,
-                                 key_of(k * p->giant_step), kl.beta, level, galois_of_step(ctx, k * p->giant_step), st,
-                                 cts + (size_t)(k - 1) * ctw, inner);
+        for (int k0 = 1; k0 < r_o; k0 += IP_MAX_ITEMS) {          // all rotations summed onto inner_0 by one launch
+            IpBatch b;
+            b.nz = 1, b.nsum = r_o - k0 < IP_MAX_ITEMS ? r_o - k0 : IP_MAX_ITEMS;
+            for (int s = 0; s < b.nsum; s++) {
+                const int k = k0 + s;
+                b.it[s].dig = digs + (size_t)(k - 1) * kl.beta * kl.ext * n, b.it[s].key = key_of(k * p->giant_step);
+                b.it[s].c0 = cts + (size_t)(k - 1) * ctw, b.it[s].g = (unsigned)galois_of_step(ctx, k * p->giant_step);
+            }
+            b.out[0] = inner, b.extra[0] = inner;
+            launch_inner_product_batch(ctx, b, kl.beta, level, st);
+        }
         CMCHK(moddown_into(ctx, inner, level, nullptr, 0, 0, acc, nullptr, st));
     } else {
         // giant steps, Horner form: acc <- Rot(acc) + ModDown-ed inner_k in one key switch
