@@ -162,6 +162,33 @@ def test_other_widths_and_levels_decrypt_to_float64_product(ring2, d, level, rot
     assert np.abs(out.real[::t] - x @ W).max() < TOL
 
 
+@pytest.mark.parametrize("d_in,d_out", [(4096, 16384), (16384, 4096)])
+def test_config4_mlp_projection_shapes_decrypt_to_float64_product(ring2, d_in, d_out):
+    """The MLP projections of Llama-3-8B (4096 -> 14336 -> 4096) with the long side zero-padded to
+    16384 = 4 x 4096: 2048 weight diagonals (64 baby x 32 giant steps), 98 rotations, at the paper's
+    operating level 4, in the form bench.py times."""
+    from oracle import packing
+    from paper_2602_11470_amd import inputs
+    B, octx, gctx, prm = ring2
+    level, real = 4, 14336
+    x, W = inputs.vmm_inputs(8, d_in, d_out)
+    if d_in > d_out:
+        x[real:] = 0.0
+        W[real:, :] = 0.0
+    else:
+        W[:, real:] = 0.0
+    plan = packing.make_plan(octx.S, d_in, d_out)
+    gplan = gctx.vmm_plan(d_in, d_out, W=W, level=level, direct_giants=True)
+    assert (gplan.r_i, gplan.r_o, gplan.n_rotations) == (plan.r_i, plan.r_o, plan.n_rotations) == (64, 32, 98)
+    gsk = gctx.keygen_secret(1)
+    gkeys = gctx.keygen_rotations(gsk, gplan.steps(), 2)
+    gx = gctx.level_drop(gctx.encrypt(gsk, gctx.encode(plan.pack_input(x), gctx.L), 3), level)
+    gy = gctx.vmm_pt(gkeys, gplan, gx)
+    assert gy.level == level - 1
+    out = plan.unpack_output(gctx.decrypt(gsk, gy).real)
+    assert np.abs(out - x @ W).max() < TOL
+
+
 def test_config3_attention_shapes_decrypt_to_float64_products(ring2):
     """Llama-3-8B attention shapes on the full ring: 32 heads x 128 dims (8 KV heads repeated 4x),
     t = 8 tokens per K ciphertext, 128 V ciphertexts with 16 baby x 8 giant steps.  A short
@@ -199,9 +226,97 @@ def test_config3_attention_shapes_decrypt_to_float64_products(ring2):
     assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
 
 
+def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
+    """Two decode steps of one Llama-3-8B-shaped layer's linear path on the 36 + 6 prime ring: k / v /
+    q projections (8 KV heads replicated to 32 by repeating weight columns, columns ordered as the
+    cache wants them), append of the encrypted k / v to a cache that already holds 16 tokens,
+    q K^T against it, scores V, and the output projection; every stage decrypted and compared with
+    float64.  (RoPE and softmax sit between these stages in the model and are outside this path:
+    the scores fed to scores V are a fresh encryption, and the extraction mask that RoPE fuses
+    (Sec. 4.2: a product leaves partial sums in the other residues) is a plain mask product here.)"""
+    from oracle import packing
+    from paper_2602_11470_amd import inputs
+    ring2[2].close()
+    B, octx, gctx, prm = _llama(36, 6)
+    try:
+        H, E, d, L = 32, 128, 4096, gctx.L
+        lay = packing.KvLayout(gctx.S, H, E, 16)
+        t = lay.t
+        rng = np.random.default_rng(5)
+        Wq, Wo = rng.normal(0, 0.02, (d, d)), rng.normal(0, 0.02, (d, d))
+        Wk8, Wv8 = rng.normal(0, 0.02, (d, 8 * E)), rng.normal(0, 0.02, (d, 8 * E))
+        # column a = e*H + h of the packed weights is column [h, e] of the model's (KV head h // 4)
+        a = np.arange(d)
+        e_of, h_of = a // H, a % H
+        Wq_p = Wq[:, h_of * E + e_of]
+        Wk_p, Wv_p = Wk8[:, (h_of // 4) * E + e_of], Wv8[:, (h_of // 4) * E + e_of]
+        Wo_p = Wo[h_of * E + e_of, :]                      # rows follow the attention output layout
+        gsk = gctx.keygen_secret(1)
+        cache_lv = L - 2
+        kv = gctx.kv_create(H, E, cache_lv, r_i=16)
+        plan_q = gctx.vmm_plan(d, d, W=Wq_p, level=L, direct_giants=True)
+        plan_o = gctx.vmm_plan(d, d, W=Wo_p, level=cache_lv - 2, direct_giants=True)
+        residue0 = np.zeros(gctx.S)
+        residue0[::t] = 1.0
+
+        def extract(ct):
+            """Keep residue 0 of every block: mask encoded at the scale of the prime the rescale removes."""
+            mask = gctx.encode(residue0, ct.level, float(prm.moduli[ct.level]), mont=True)
+            return gctx.rescale(gctx.mul_pt(ct, mask))
+        steps = set(kv.steps()) | set(plan_q.steps()) | set(plan_o.steps())
+        gkeys = gctx.keygen_rotations(gsk, sorted(steps), 2, with_relin=True)
+        enc = lambda slots, level, seed, scale=0.0: gctx.level_drop(
+            gctx.encrypt(gsk, gctx.encode(slots, L, scale), seed), level)
+        n0 = 16
+        _, K, V, _ = inputs.attention_inputs(4, H, 8, E, n0)
+        # a cache holds one scale: the tokens already there carry the scale a projection leaves
+        proj_scale = prm.scale * prm.scale / float(prm.moduli[L])
+        for c in range(n0 // t):
+            kv.load(B.CM_QK, c, enc(lay.pack_k(K, c), cache_lv, 100 + c, proj_scale))
+        for k in range(E):
+            kv.load(B.CM_SV, k, enc(lay.pack_v(V, k), cache_lv, 300 + k, proj_scale))
+        kv.set_tokens(n0)
+        K, V = list(K), list(V)
+        for step in range(2):
+            n = n0 + step
+            tau = n % t
+            x = rng.normal(size=d)
+            slots = np.zeros(gctx.S)
+            slots[::t] = x
+            gx = enc(slots, L, 500 + step)
+            # k and v land on residue tau, ready for the append
+            plan_k = gctx.vmm_plan(d, d, W=Wk_p, level=L, tau=tau, direct_giants=True)
+            plan_v = gctx.vmm_plan(d, d, W=Wv_p, level=L, tau=tau, direct_giants=True)
+            gk = gctx.vmm_pt(gkeys, plan_k, gx)
+            gv = gctx.vmm_pt(gkeys, plan_v, gx)
+            k_ref = (x @ Wk8).reshape(8, E).repeat(4, axis=0)          # [h, e]
+            v_ref = (x @ Wv8).reshape(8, E).repeat(4, axis=0)
+            assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, gk).real, tau) - k_ref).max() < TOL
+            kv.append(gkeys, gk, gv)
+            K.append(k_ref), V.append(v_ref)
+            del plan_k, plan_v
+            assert kv.tokens() == n + 1
+            gq = gctx.vmm_pt(gkeys, plan_q, gx)
+            q_ref = (x @ Wq).reshape(H, E)
+            assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, gq).real) - q_ref).max() < TOL
+            gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, extract(gq))          # level L-1 -> L-2 = the cache's
+            Ka, Va = np.stack(K), np.stack(V)
+            m_ref = np.einsum("he,nhe->hn", q_ref, Ka)
+            assert np.abs(lay.unpack_scores(gctx.decrypt(gsk, gm).real, n + 1) - m_ref).max() < 20 * TOL   # |m| ~ 10
+            sc = np.abs(m_ref)
+            sc /= sc.sum(axis=1, keepdims=True)
+            ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, enc(lay.pack_scores(sc), cache_lv, 700 + step))
+            att_ref = np.einsum("hn,nhe->he", sc, Va)
+            assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, ga).real) - att_ref).max() < TOL
+            gy = gctx.vmm_pt(gkeys, plan_o, extract(ga))
+            y_ref = att_ref.reshape(-1) @ Wo
+            assert np.abs(gctx.decrypt(gsk, gy).real[::t] - y_ref).max() < TOL
+    finally:
+        gctx.close()
+
+
 def test_config5_ring_rotation(ring2):
     """36 + 6 primes (6 digits of 6): one full key switch element by element."""
-    ring2[2].close()                                 # free the first context's device memory
     B, octx, gctx, prm = _llama(36, 6)
     try:
         assert gctx.moduli().tolist() == prm.moduli
