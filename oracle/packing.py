@@ -196,6 +196,35 @@ class KvLayout:
         return np.array([[slots[self.slot(e, h, tau)] for e in range(self.E)]
                          for h in range(self.H)])
 
+    # ---- rotary position embedding with the extraction fused (Sec. 4.2, App. D) --------------
+    # The embedding turns the pair of dims (2m, 2m+1) of every head by the angle
+    # theta(m, n) = n * base^(-2m/E) of token n.  In this layout the two dims of a pair sit one
+    # block row apart, H*t slots (the appendix writes the single-head case, where that is one block
+    # of t slots, as "rotate by 1").  Reading of the rotation signs (the printed ones do not fit the
+    # left-rotation convention of Sec. 2.1): the odd dim comes to the even one by a LEFT rotation of
+    # the product with p2, the even dim to the odd one by a RIGHT rotation of the product with p1.
+    def rope_angle(self, e, n, base=10000.0):
+        return n * base ** (-2.0 * (e // 2) / self.E)
+
+    def rope_plaintexts(self, n, tau=0, base=10000.0):
+        """(p0, p1, p2): cos on the valid slots; sin on the valid slots of even dims; -sin on those
+        of odd dims.  Every other slot is zero, which is the extraction."""
+        p0, p1, p2 = np.zeros(self.S), np.zeros(self.S), np.zeros(self.S)
+        for e in range(self.E):
+            th = self.rope_angle(e, n, base)
+            for h in range(self.H):
+                i = self.slot(e, h, tau)
+                p0[i] = np.cos(th)
+                if e % 2 == 0:
+                    p1[i] = np.sin(th)
+                else:
+                    p2[i] = -np.sin(th)
+        return p0, p1, p2
+
+    @property
+    def rope_step(self):
+        return self.H * self.t
+
     def pack_k(self, K, c):
         """K[token, h, e] -> slots of K ciphertext c (tokens past the end are zero)."""
         out = np.zeros(self.S)

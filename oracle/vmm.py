@@ -202,6 +202,17 @@ def score_times_v(ops, lay: KvLayout, cs, v_cts):
     return acc
 
 
+def rope(ops, lay: KvLayout, c, plaintexts):
+    """App. D: c p0 + Rot(c p2, +H t) + Rot(c p1, -H t), then the rescale; three plaintext products,
+    two rotations, one level.  `plaintexts` = lay.rope_plaintexts(n, tau) (slot vectors or encoded
+    plaintexts); slots outside the valid ones come out zero whatever they held."""
+    p0, p1, p2 = plaintexts
+    y = ops.mul_pt(c, p0)
+    y = ops.add(y, ops.rotate(ops.mul_pt(c, p2), lay.rope_step))
+    y = ops.add(y, ops.rotate(ops.mul_pt(c, p1), -lay.rope_step))
+    return ops.rescale(y)
+
+
 def kv_append(ops, lay: KvLayout, k_cts, v_cts, n, ck_new, cv_new, k_mask, v_masks):
     """Append token n = c*t + tau (Sec. 5.1 'K Cache Update', Sec. 5.2 'V Cache Update').
     ck_new / cv_new carry the new vectors at residue tau (other slots may hold partial sums);

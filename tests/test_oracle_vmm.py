@@ -179,3 +179,61 @@ def test_direct_giant_steps_vmm_decrypts_to_x_times_W(d_in, d_out, level, tau):
     assert abs(y.scale / nested.scale - 1) < 1e-12
     assert np.abs(ctx.decrypt(sk, y) - ctx.decrypt(sk, nested)).max() < 1e-6
     assert not np.array_equal(ctx.canonical(y), ctx.canonical(nested))     # different noise, same message
+
+
+# ---- rotary embedding with fused extraction (Sec. 4.2, App. D) -------------------------------------
+def _rope_reference(v, n, base=10000.0):
+    """Textbook rotary embedding on v[h, e]: each pair (2m, 2m+1) turned by n * base^(-2m/E)."""
+    H, E = v.shape
+    out = np.empty_like(v)
+    for m in range(E // 2):
+        th = n * base ** (-2.0 * m / E)
+        c, s_ = np.cos(th), np.sin(th)
+        out[:, 2 * m] = v[:, 2 * m] * c - v[:, 2 * m + 1] * s_
+        out[:, 2 * m + 1] = v[:, 2 * m + 1] * c + v[:, 2 * m] * s_
+    return out
+
+
+@pytest.mark.parametrize("tau,n", [(0, 0), (0, 5), (3, 1234)])
+def test_rope_on_slots_is_the_textbook_rotation_and_cleans_other_slots(tau, n):
+    lay = packing.KvLayout(512, 4, 8)          # t = 16
+    rng = np.random.default_rng(n)
+    v = rng.normal(size=(4, 8))
+    slots = rng.normal(size=512)               # garbage everywhere (partial sums of a product) ...
+    for h in range(4):
+        for e in range(8):
+            slots[lay.slot(e, h, tau)] = v[h, e]   # ... except the valid slots
+    ops = vmm.SlotOps()
+    out = vmm.rope(ops, lay, slots, lay.rope_plaintexts(n, tau))
+    assert (ops.rotations, ops.pt_mults) == (2, 3)
+    want = _rope_reference(v, n)
+    assert np.abs(lay.unpack_vec(out, tau) - want).max() < 1e-12
+    valid = np.zeros(512, dtype=bool)
+    valid[[lay.slot(e, h, tau) for e in range(8) for h in range(4)]] = True
+    assert np.abs(out[~valid]).max() == 0.0
+    # norms of the pairs are kept (a rotation), and n = 0 is the identity on the valid slots
+    assert np.allclose((want ** 2).reshape(4, 4, 2).sum(-1), (v ** 2).reshape(4, 4, 2).sum(-1))
+    if n == 0:
+        assert np.abs(lay.unpack_vec(out, tau) - v).max() == 0.0
+
+
+def test_rope_on_ciphertexts_decrypts_to_the_rotation():
+    prm = params.toy(n=512, n_qi=3, n_p=1, alpha=1)
+    ctx = ckks.Context(prm)
+    lay = packing.KvLayout(ctx.S, 4, 8)
+    sk = ctx.keygen_secret(1)
+    keys = ctx.keygen_rotations(sk, [lay.rope_step, -lay.rope_step], 2)
+    rng = np.random.default_rng(3)
+    v = rng.normal(size=(4, 8))
+    slots = rng.normal(size=ctx.S)
+    for h in range(4):
+        for e in range(8):
+            slots[lay.slot(e, h, 2)] = v[h, e]
+    ct = ctx.encrypt(sk, ctx.encode(slots, prm.L), 3)
+    # plaintexts at the scale of the prime the rescale removes: the ciphertext scale is unchanged
+    ops = vmm.CkksOps(ctx, keys, pt_scale=float(prm.moduli[prm.L]))
+    y = vmm.rope(ops, lay, ct, lay.rope_plaintexts(77, 2))
+    assert y.level == prm.L - 1 and abs(y.scale / ct.scale - 1) < 1e-12
+    out = ctx.decrypt(sk, y).real
+    assert np.abs(lay.unpack_vec(out, 2) - _rope_reference(v, 77)).max() < 1e-6
+    assert np.abs(out).max() < 10 and np.abs(out[1::lay.t]).max() < 1e-6      # residue 1 was garbage, now clean
