@@ -231,6 +231,24 @@ cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k
 cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t which,
                     const cm_ct *in, cm_ct *out, void *stream);
 
+/* ---- rotary embedding with the extraction fused (Sec. 4.2, App. D) ------------------------ */
+/* The element-wise layer after the q / k projections: for token `token`, every pair of dims
+ * (2m, 2m+1) of every head is turned by token * base^(-2m/dim), and every slot that is not a
+ * valid slot (e, h, tau) = (e*heads + h)*t + tau comes out zero, whatever partial sums the
+ * projection left there.  Three plaintext products, two rotations (by +-heads*t slots), one
+ * level; the plaintexts are encoded at the scale of the prime the rescale removes, so y keeps
+ * the scale of x.  coeffs (nullable, host [3][n]): integer coefficients of p0, p1, p2 to use
+ * instead of the library's own encoding, for callers that need bit-identical plaintexts on two
+ * implementations.  x at `level`, y one level lower; y must not alias x. */
+typedef struct cm_rope cm_rope;
+cm_status cm_rope_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t level, int32_t token,
+                         int32_t tau, double base, const int64_t *coeffs, cm_rope **out);
+void cm_rope_destroy(cm_rope *rope);
+/* Rotation steps it needs: returns 2, writes up to cap of them (host). */
+int32_t cm_rope_steps(const cm_rope *rope, int32_t *steps, int32_t cap);
+cm_status cm_rope_apply(cm_ctx *ctx, const cm_evk *evk, const cm_rope *rope, const cm_ct *x,
+                        cm_ct *y, void *stream);
+
 /* ---- building blocks exposed for measurement and parity -------------------------------- */
 /* Forward / inverse negacyclic NTT of `limbs` limbs in place (device), limb i under modulus
  * index mod_idx[i] (host array; indices into q_0..q_L,p_0..); 1 <= limbs <= 1024. */

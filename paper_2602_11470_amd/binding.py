@@ -76,6 +76,10 @@ _SIGS = {
     "cm_vmm_plan_info": ([_vp, _P(_i32), _P(_i32), _P(_i32)], _i32),
     "cm_vmm_plan_diag_export": ([_vp, _vp, _i32, _i32, _vp], _i32),
     "cm_vmm_pt": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
+    "cm_rope_create": ([_vp, _i32, _i32, _i32, _i32, _i32, _f64, _vp, _P(_vp)], _i32),
+    "cm_rope_destroy": ([_vp], None),
+    "cm_rope_steps": ([_vp, _vp, _i32], _i32),
+    "cm_rope_apply": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_kv_create": ([_vp, _i32, _i32, _i32, _i32, _f64, _i32, _P(_vp)], _i32),
     "cm_kv_destroy": ([_vp], None),
     "cm_kv_steps": ([_vp, _vp, _i32], _i32),
@@ -296,6 +300,14 @@ class Context:
         _chk(lib.cm_vmm_pt(self.h, evk.h, plan.h, C.byref(x.d), C.byref(out.d), _stream()))
         return out
 
+    def rope(self, heads, dim, level, token, tau=0, base=10000.0, coeffs=None):
+        return Rope(self, heads, dim, level, token, tau, base, coeffs)
+
+    def rope_apply(self, evk, rope, x, out=None):
+        out = out or Ct(self, x.level - 1)
+        _chk(lib.cm_rope_apply(self.h, evk.h, rope.h, C.byref(x.d), C.byref(out.d), _stream()))
+        return out
+
     def kv_create(self, heads, dim, level, scale=0.0, max_tokens=None, r_i=0):
         return KvCache(self, heads, dim, r_i, level, scale, max_tokens)
 
@@ -371,6 +383,24 @@ class VmmPlan:
     def __del__(self):
         if getattr(self, "h", None) and lib is not None:
             lib.cm_vmm_plan_destroy(self.h)
+            self.h = None
+
+
+class Rope:
+    def __init__(self, ctx, heads, dim, level, token, tau, base, coeffs):
+        self.ctx, self.h = ctx, _vp()
+        c = _np(coeffs, np.int64) if coeffs is not None else None
+        _chk(lib.cm_rope_create(ctx.h, heads, dim, level, token, tau, base, c.ctypes.data if c is not None else None,
+                                C.byref(self.h)))
+
+    def steps(self):
+        out = np.empty(2, dtype=np.int32)
+        lib.cm_rope_steps(self.h, out.ctypes.data, 2)
+        return out.tolist()
+
+    def __del__(self):
+        if getattr(self, "h", None) and lib is not None:
+            lib.cm_rope_destroy(self.h)
             self.h = None
 
 

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libcachemir.so")
 BUILD = os.path.join(HERE, "_build")
-SOURCES = ["context.hip", "ntt.hip", "kernels.hip", "ops.hip", "vmm.hip", "kv.hip"]
+SOURCES = ["context.hip", "ntt.hip", "kernels.hip", "ops.hip", "vmm.hip", "kv.hip", "rope.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wno-unused-result",
          # the FP64 butterflies rely on exact products: no fused contraction the source does not spell
          "-ffp-contract=off",
@@ -40,7 +40,7 @@ def build(force=True, verbose=False):
             raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
         return o
 
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     r = subprocess.run([_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", OUT] + objs,
                        capture_output=True, text=True)

@@ -188,6 +188,48 @@ def test_vmm_pt_replays_from_a_captured_graph(env, direct):
     assert np.abs(gctx.decrypt(e["gsk"], out).real[::gctx.S // 256] - x @ W).max() < TOL
 
 
+@pytest.mark.parametrize("token,tau,level", [(0, 0, 4), (77, 5, 3), (4095, 2, 1)])
+def test_rope_with_fused_extraction_matches_oracle_and_the_textbook_rotation(env, token, tau, level):
+    """App. D on 16 heads x 16 dims (t = 8): limbs against the oracle from identical integer
+    plaintexts, decrypted result against the rotation of every dim pair, other slots clean."""
+    from oracle import packing, vmm
+    e = env
+    octx, gctx, prm = e["octx"], e["gctx"], e["prm"]
+    lay = packing.KvLayout(octx.S, 16, 16)
+    rng = np.random.default_rng(token)
+    v = rng.normal(size=(16, 16))
+    slots = rng.normal(size=octx.S)                      # partial sums everywhere ...
+    for h in range(16):
+        for d in range(16):
+            slots[lay.slot(d, h, tau)] = v[h, d]         # ... except the valid slots
+    ox, gx = _enc_both(e, slots, level, 3)
+    scale = float(prm.moduli[level])
+    coeffs = [octx.encode_coeffs(p, scale) for p in lay.rope_plaintexts(token, tau)]
+    grope = gctx.rope(16, 16, level, token, tau, coeffs=np.stack(coeffs))
+    assert sorted(grope.steps()) == sorted([lay.rope_step, -lay.rope_step])
+    okeys = octx.keygen_rotations(e["osk"], grope.steps(), 2)
+    gkeys = gctx.keygen_rotations(e["gsk"], grope.steps(), 2)
+    oy = vmm.rope(vmm.CkksOps(octx, okeys), lay, ox, [octx.pt_from_coeffs(c, level, scale) for c in coeffs])
+    gy = gctx.rope_apply(gkeys, grope, gx)
+    _same(e, oy, gy)
+    want = np.empty_like(v)
+    for m in range(8):
+        th = token * 10000.0 ** (-2.0 * m / 16)
+        want[:, 2 * m] = v[:, 2 * m] * np.cos(th) - v[:, 2 * m + 1] * np.sin(th)
+        want[:, 2 * m + 1] = v[:, 2 * m + 1] * np.cos(th) + v[:, 2 * m] * np.sin(th)
+    # the library's own plaintexts: same message
+    gy2 = gctx.rope_apply(gkeys, gctx.rope(16, 16, level, token, tau), gx)
+    for g in (gy, gy2):
+        out = gctx.decrypt(e["gsk"], g).real
+        assert np.abs(lay.unpack_vec(out, tau) - want).max() < TOL
+        valid = np.zeros(octx.S, dtype=bool)
+        valid[[lay.slot(d, h, tau) for d in range(16) for h in range(16)]] = True
+        assert np.abs(out[~valid]).max() < TOL
+    with pytest.raises(e["B"].CachemirError) as err:
+        gctx.rope_apply(gctx.keygen_rotations(e["gsk"], [lay.rope_step], 2), grope, gx)
+    assert err.value.status == -4
+
+
 def test_vmm_pt_missing_key_and_level_errors(env):
     e = env
     B, gctx = e["B"], e["gctx"]
