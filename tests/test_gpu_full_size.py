@@ -230,10 +230,11 @@ def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
     """Two decode steps of one Llama-3-8B-shaped layer's linear path on the 36 + 6 prime ring: k / v /
     q projections (8 KV heads replicated to 32 by repeating weight columns, columns ordered as the
     cache wants them), append of the encrypted k / v to a cache that already holds 16 tokens,
-    q K^T against it, scores V, and the output projection; every stage decrypted and compared with
-    float64.  (RoPE and softmax sit between these stages in the model and are outside this path:
-    the scores fed to scores V are a fresh encryption, and the extraction mask that RoPE fuses
-    (Sec. 4.2: a product leaves partial sums in the other residues) is a plain mask product here.)"""
+    the rotary embedding of q and k with the extraction fused (Sec. 4.2), q K^T against the cache,
+    scores V, and the output projection; every stage decrypted and compared with float64.
+    (Softmax and the normalisations sit between these stages in the model and are outside this
+    path: the scores fed to scores V are a fresh encryption, and the extraction the model merges
+    into its layer norm is a plain mask product before the output projection.)"""
     from oracle import packing
     from paper_2602_11470_amd import inputs
     ring2[2].close()
@@ -252,7 +253,7 @@ def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
         Wk_p, Wv_p = Wk8[:, (h_of // 4) * E + e_of], Wv8[:, (h_of // 4) * E + e_of]
         Wo_p = Wo[h_of * E + e_of, :]                      # rows follow the attention output layout
         gsk = gctx.keygen_secret(1)
-        cache_lv = L - 2
+        cache_lv = L - 3                     # projection, rotary embedding, append mask: one level each
         kv = gctx.kv_create(H, E, cache_lv, r_i=16)
         plan_q = gctx.vmm_plan(d, d, W=Wq_p, level=L, direct_giants=True)
         plan_o = gctx.vmm_plan(d, d, W=Wo_p, level=cache_lv - 2, direct_giants=True)
@@ -263,7 +264,7 @@ def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
             """Keep residue 0 of every block: mask encoded at the scale of the prime the rescale removes."""
             mask = gctx.encode(residue0, ct.level, float(prm.moduli[ct.level]), mont=True)
             return gctx.rescale(gctx.mul_pt(ct, mask))
-        steps = set(kv.steps()) | set(plan_q.steps()) | set(plan_o.steps())
+        steps = set(kv.steps()) | set(plan_q.steps()) | set(plan_o.steps()) | {H * t, -H * t}
         gkeys = gctx.keygen_rotations(gsk, sorted(steps), 2, with_relin=True)
         enc = lambda slots, level, seed, scale=0.0: gctx.level_drop(
             gctx.encrypt(gsk, gctx.encode(slots, L, scale), seed), level)
@@ -277,6 +278,15 @@ def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
             kv.load(B.CM_SV, k, enc(lay.pack_v(V, k), cache_lv, 300 + k, proj_scale))
         kv.set_tokens(n0)
         K, V = list(K), list(V)
+
+        def rope_ref(v, n):
+            out = np.empty_like(v)
+            for m in range(E // 2):
+                th = n * 10000.0 ** (-2.0 * m / E)
+                out[:, 2 * m] = v[:, 2 * m] * np.cos(th) - v[:, 2 * m + 1] * np.sin(th)
+                out[:, 2 * m + 1] = v[:, 2 * m + 1] * np.cos(th) + v[:, 2 * m] * np.sin(th)
+            return out
+
         for step in range(2):
             n = n0 + step
             tau = n % t
@@ -289,17 +299,18 @@ def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
             plan_v = gctx.vmm_plan(d, d, W=Wv_p, level=L, tau=tau, direct_giants=True)
             gk = gctx.vmm_pt(gkeys, plan_k, gx)
             gv = gctx.vmm_pt(gkeys, plan_v, gx)
-            k_ref = (x @ Wk8).reshape(8, E).repeat(4, axis=0)          # [h, e]
+            k_ref = rope_ref((x @ Wk8).reshape(8, E).repeat(4, axis=0), n)          # [h, e]
             v_ref = (x @ Wv8).reshape(8, E).repeat(4, axis=0)
+            gk = gctx.rope_apply(gkeys, gctx.rope(H, E, L - 1, n, tau), gk)         # level L-2, other slots clean
             assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, gk).real, tau) - k_ref).max() < TOL
-            kv.append(gkeys, gk, gv)
+            kv.append(gkeys, gk, gctx.level_drop(gv, L - 2))
             K.append(k_ref), V.append(v_ref)
             del plan_k, plan_v
             assert kv.tokens() == n + 1
-            gq = gctx.vmm_pt(gkeys, plan_q, gx)
-            q_ref = (x @ Wq).reshape(H, E)
+            gq = gctx.rope_apply(gkeys, gctx.rope(H, E, L - 1, n, 0), gctx.vmm_pt(gkeys, plan_q, gx))
+            q_ref = rope_ref((x @ Wq).reshape(H, E), n)
             assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, gq).real) - q_ref).max() < TOL
-            gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, extract(gq))          # level L-1 -> L-2 = the cache's
+            gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, gctx.level_drop(gq, cache_lv))
             Ka, Va = np.stack(K), np.stack(V)
             m_ref = np.einsum("he,nhe->hn", q_ref, Ka)
             assert np.abs(lay.unpack_scores(gctx.decrypt(gsk, gm).real, n + 1) - m_ref).max() < 20 * TOL   # |m| ~ 10
