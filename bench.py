@@ -107,6 +107,28 @@ def time_rotations(g, reps=20):
     return (time.perf_counter() - t0) / reps
 
 
+def ntt_rates(g, reps=20):
+    """Limb transforms per second for batches of 24, 28 and 168 limbs (forward and inverse), timed
+    with the library's per-launch HIP events around cm_ntt."""
+    torch, ctx = g["torch"], g["ctx"]
+    out = {}
+    for limbs in (24, 28, 168):
+        mods = [i % 28 for i in range(limbs)]
+        data = torch.randint(0, 1 << 40, (limbs, ctx.n), dtype=torch.int64, device="cuda")
+        for inverse in (False, True):
+            for _ in range(2):
+                ctx.ntt(data, mods, inverse)
+            torch.cuda.synchronize()
+            ctx.profile_enable(True)
+            for _ in range(reps):
+                ctx.ntt(data, mods, inverse)
+            torch.cuda.synchronize()
+            launches, units, ms = ctx.profile_get(1 if inverse else 0)
+            ctx.profile_enable(False)
+            out[f"{'inv' if inverse else 'fwd'}_{limbs}"] = units / (ms * 1e-3)
+    return out
+
+
 def calibration_kernel(g):
     """One launch of a plain streaming kernel of known size outside the timed region: the sum of two
     distinct top-level ciphertexts (k_add: reads 2 x 24 MiB, writes 24 MiB).  Counter profiles of
@@ -272,6 +294,7 @@ def main():
     fam = kernel_profile(g, min(a.steps, 5))
     t_rot = time_rotations(g)
     calibration_kernel(g)
+    rates = ntt_rates(g)
     n, limbs, K, beta = g["ctx"].n, 24, 4, 6
     limb_bytes = 8 * n
     # dominant kernel family of the step by time
@@ -318,6 +341,7 @@ def main():
         "key_switch_algorithmic_gbs": ks_bytes / t_rot / 1e9,
         "key_switch_frac_of_hbm_peak": ks_bytes / t_rot / 1e9 / HBM_PEAK_GBS,
         "limb_ntts_per_s": ntt["units"] / (ntt["ms"] * 1e-3),
+        "limb_ntts_per_s_by_batch": {k: round(v) for k, v in rates.items()},
         "kernel_ms_per_step": {k: round(v["ms"], 4) for k, v in fam.items()},
         "dominant_kernel_family": dom,
         "roofline": roofline,
