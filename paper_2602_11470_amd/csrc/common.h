@@ -65,7 +65,8 @@ __device__ __forceinline__ unsigned perm_src(unsigned i, unsigned g, int logn) {
 
 // modulus as doubles for the FP64 butterflies (moduli below 2^50 only; q = 0 otherwise)
 struct FpQ {
-    double q, qinv;
+    double q, qinv;       // modulus and 1/q as doubles; q = 0 where the modulus is too large for the FP64 paths
+    double rinv, rinvq;   // 2^-64 mod q and that over q: takes a product with a multiplier-form operand back
 };
 
 // ---- context -----------------------------------------------------------------------------

@@ -341,7 +341,12 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
             const bool fp = q < (1ULL << 50) && !getenv("CM_NTT_INT");
             fpq[m].q = fp ? (double)q : 0.0;
             fpq[m].qinv = fp ? 1.0 / (double)q : 0.0;
+            fpq[m].rinv = fpq[m].rinvq = 0.0;
             if (!fp) continue;
+            {
+                const u64 r = (u64)((((u128)1) << 64) % q), rinv = h_invmod(r, q);
+                fpq[m].rinv = (double)rinv, fpq[m].rinvq = (double)rinv / (double)q;
+            }
             for (int i = 0; i < n; i++) {
                 size_t o = (size_t)m * n + i;
                 twd[o] = (double)tw[o], twqd[o] = (double)tw[o] / (double)q;

@@ -514,14 +514,44 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 // baby ciphertexts per pass (32 KiB of LDS).
 #define MAC_CO 64
 #define MAC_JC 32
+// Limbs whose modulus is below 2^50 run the products in FP64 (the arithmetic of the transforms'
+// butterflies): residues as exact integers in doubles, a modular product
+//     h = y a;  l = fma(y, a, -h);  c = rint(y (a / q));  r = fma(-c, q, h) + l        (|r| < q)
+// with a / q taken as a * (1 / q), once per plaintext word for both ciphertext components; partial
+// sums are renormalised every four terms (|sum| < 4.6 q < 2^53 stays exact).  That is 8.5
+// instructions per product against 17 for the 128-bit integer form.  The plaintexts are stored in
+// multiplier form (times 2^64), so the finished sum is multiplied by 2^-64 mod q.
+struct MacFp {
+    double q, qinv;
+    __device__ __forceinline__ double mulmod(double y, double a, double aq) const {
+        double h = y * a;
+        double l = __builtin_fma(y, a, -h);
+        double c = __builtin_rint(y * aq);
+        return __builtin_fma(-c, q, h) + l;
+    }
+    __device__ __forceinline__ double norm(double x) const { return __builtin_fma(-__builtin_rint(x * qinv), q, x); }
+    __device__ __forceinline__ static double from_u64(u64 raw) {                 // raw < 2^52
+        return __longlong_as_double((long long)(raw | 0x4330000000000000ULL)) - 4503599627370496.0;
+    }
+    __device__ __forceinline__ u64 canon(double v) const {                       // |v| < 2^52 -> [0, q)
+        double r = __builtin_fma(-__builtin_floor(v * qinv), q, v);
+        r = r < 0.0 ? r + q : r;
+        r = r >= q ? r - q : r;
+        return (u64)__double_as_longlong(r + 4503599627370496.0) & 0x000FFFFFFFFFFFFFULL;
+    }
+};
 __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, const u64 *__restrict__ babies,
                                                      const u64 *__restrict__ pts, const ModC *__restrict__ modc,
-                                                     int r_i, int r_o, int limbs, int n, size_t ct_stride,
-                                                     int k0, int k1, int level, int L) {
+                                                     const FpQ *__restrict__ fpq, int r_i, int r_o, int limbs, int n,
+                                                     size_t ct_stride, int k0, int k1, int level, int L) {
     __shared__ u64 sb[MAC_JC * 2 * MAC_CO];
     const int l = blockIdx.y, i0 = blockIdx.x * MAC_CO;
     const int co = threadIdx.x & (MAC_CO - 1), kq = threadIdx.x >> 6;
-    const ModC m = modc[l <= level ? l : L + 1 + (l - level - 1)];
+    const int mi = l <= level ? l : L + 1 + (l - level - 1);
+    const ModC m = modc[mi];
+    const FpQ fq = fpq[mi];
+    const bool fp = fq.q != 0.0;
+    const MacFp F{fq.q, fq.qinv};
     const size_t o = (size_t)l * n + i0, cs = (size_t)limbs * n;
     const u64 *pblk = pts + ((size_t)l * (n / MAC_CO) + blockIdx.x) * r_o * r_i * MAC_CO + co;
     for (int j0 = 0; j0 < r_i; j0 += MAC_JC) {
@@ -529,38 +559,58 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
         __syncthreads();
         for (int e = threadIdx.x; e < jn * 2 * MAC_CO; e += TPB) {
             int jc = e >> 6, c = e & (MAC_CO - 1);
-            sb[e] = babies[(size_t)(j0 + (jc >> 1)) * ct_stride + (jc & 1) * cs + o + c];
+            u64 v = babies[(size_t)(j0 + (jc >> 1)) * ct_stride + (jc & 1) * cs + o + c];
+            sb[e] = fp ? (u64)__double_as_longlong(MacFp::from_u64(v)) : v;
         }
         __syncthreads();
         // A sum of products is reduced when one more group of 8 could pass q * 2^64 (the bound of
-        // REDC): after every group for the 60-bit special primes, once per pass below 2^59.
-        const int redc_every = (m.q >> 59) ? 8 : MAC_JC;
+        // REDC): after every group for the 60-bit special primes.
         for (int k = k0 + kq; k < k1; k += 4) {
-            u64 v0 = 0, v1 = 0;
             const u64 *pk = pblk + ((size_t)k * r_i + j0) * MAC_CO;
             u64 p[8], pn[8];
 #pragma unroll
             for (int jj = 0; jj < 8; jj++) p[jj] = jj < jn ? __builtin_nontemporal_load(pk + (size_t)jj * MAC_CO) : 0;
-            u128 s0 = 0, s1 = 0;
-            for (int j8 = 0; j8 < jn; j8 += 8) {
-                // the next group is in flight while this one is multiplied
+            u64 v0, v1;
+            if (fp) {
+                double s0 = 0.0, s1 = 0.0;
+                for (int j8 = 0; j8 < jn; j8 += 8) {
+                    // the next group is in flight while this one is multiplied
 #pragma unroll
-                for (int jj = 0; jj < 8; jj++)
-                    pn[jj] = j8 + 8 + jj < jn ? __builtin_nontemporal_load(pk + (size_t)(j8 + 8 + jj) * MAC_CO) : 0;
+                    for (int jj = 0; jj < 8; jj++)
+                        pn[jj] = j8 + 8 + jj < jn ? __builtin_nontemporal_load(pk + (size_t)(j8 + 8 + jj) * MAC_CO) : 0;
 #pragma unroll
-                for (int jj = 0; jj < 8; jj++) {
-                    if (j8 + jj < jn) {
-                        s0 += (u128)sb[((j8 + jj) * 2 + 0) * MAC_CO + co] * p[jj];
-                        s1 += (u128)sb[((j8 + jj) * 2 + 1) * MAC_CO + co] * p[jj];
+                    for (int jj = 0; jj < 8; jj++) {
+                        if (j8 + jj < jn) {
+                            const double a = MacFp::from_u64(p[jj]), aq = a * F.qinv;
+                            s0 += F.mulmod(__longlong_as_double((long long)sb[((j8 + jj) * 2 + 0) * MAC_CO + co]), a, aq);
+                            s1 += F.mulmod(__longlong_as_double((long long)sb[((j8 + jj) * 2 + 1) * MAC_CO + co]), a, aq);
+                        }
+                        if ((jj & 3) == 3) s0 = F.norm(s0), s1 = F.norm(s1);
                     }
+#pragma unroll
+                    for (int jj = 0; jj < 8; jj++) p[jj] = pn[jj];
                 }
-                if ((j8 + 8) % redc_every == 0 || j8 + 8 >= jn) {
+                v0 = F.canon(F.mulmod(s0, fq.rinv, fq.rinvq));
+                v1 = F.canon(F.mulmod(s1, fq.rinv, fq.rinvq));
+            } else {
+                v0 = v1 = 0;
+                for (int j8 = 0; j8 < jn; j8 += 8) {
+#pragma unroll
+                    for (int jj = 0; jj < 8; jj++)
+                        pn[jj] = j8 + 8 + jj < jn ? __builtin_nontemporal_load(pk + (size_t)(j8 + 8 + jj) * MAC_CO) : 0;
+                    u128 s0 = 0, s1 = 0;
+#pragma unroll
+                    for (int jj = 0; jj < 8; jj++) {
+                        if (j8 + jj < jn) {
+                            s0 += (u128)sb[((j8 + jj) * 2 + 0) * MAC_CO + co] * p[jj];
+                            s1 += (u128)sb[((j8 + jj) * 2 + 1) * MAC_CO + co] * p[jj];
+                        }
+                    }
                     v0 = addmod(v0, redc(s0, m.q, m.qinv), m.q);
                     v1 = addmod(v1, redc(s1, m.q, m.qinv), m.q);
-                    s0 = s1 = 0;
-                }
 #pragma unroll
-                for (int jj = 0; jj < 8; jj++) p[jj] = pn[jj];
+                    for (int jj = 0; jj < 8; jj++) p[jj] = pn[jj];
+                }
             }
             u64 *dst = out + (size_t)k * ct_stride + o + co;
             if (j0) {
@@ -575,8 +625,8 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
 void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, int r_i, int r_o, int limbs, int level,
                     size_t ct_stride, int k0, int k1, hipStream_t st) {
     Prof prof_(ctx, CM_K_VMM_MAC, r_i * (k1 - k0), st);
-    hipLaunchKernelGGL(k_vmm_mac_lds, dim3(ctx->n / MAC_CO, limbs), dim3(TPB), 0, st, out, babies, pts, ctx->d_modc, r_i,
-                       r_o, limbs, ctx->n, ct_stride, k0, k1, level, ctx->L);
+    hipLaunchKernelGGL(k_vmm_mac_lds, dim3(ctx->n / MAC_CO, limbs), dim3(TPB), 0, st, out, babies, pts, ctx->d_modc,
+                       ctx->d_fpq, r_i, r_o, limbs, ctx->n, ct_stride, k0, k1, level, ctx->L);
 }
 // plaintext (j,k) between its plain form src[limbs][n] and its place in the blocked array
 __global__ void k_pt_block(u64 *blocked, u64 *plain, int n, int r_i, int r_o, int j, int k, int to_blocked) {
