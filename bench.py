@@ -14,7 +14,10 @@ P on its own.
 
     python bench.py --workload attention        (config 3, a JSON line of its own)
 
-Prints one JSON line (see the design doc for the definitions of the roofline entries).
+Prints one JSON line.  `roofline` describes the kernel family with the most time in the step:
+achieved = algorithmic bytes per unit / measured time per unit (HIP events around every launch of
+the family on its stream), peak = 8 TB/s HBM, traffic = measured HBM bytes from the committed
+counter summary under profiles/.
 """
 import argparse
 import json
