@@ -7,6 +7,12 @@ void launch_to_mont(cm_ctx *ctx, u64 *data, const int *d_mod_idx, int limbs, hip
 void launch_from_mont(cm_ctx *ctx, u64 *out, const u64 *in, const int *d_mod_idx, int limbs, hipStream_t st);
 void launch_add(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int ncomp, int limbs, hipStream_t st);
 void launch_mul_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, hipStream_t st);
+// out[z][2][limbs][n] = src[z] * (pt rotated by the Galois element g[z]) for z < cnt <= CM_KS_BATCH
+struct MulPtBatch {
+    const u64 *src[CM_KS_BATCH];
+    unsigned g[CM_KS_BATCH];
+};
+void launch_mul_pt_rot_batch(cm_ctx *ctx, u64 *out, const MulPtBatch &b, int cnt, const u64 *pt_mont, int limbs, hipStream_t st);
 void launch_mac_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, int accumulate, hipStream_t st);
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st);
 void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st);

@@ -63,6 +63,23 @@ void launch_mul_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int 
     hipLaunchKernelGGL(k_mul_pt, dim3(ctx->n / TPB, ncomp * limbs), dim3(TPB), 0, st, out, a, pt_mont, ctx->d_modc, limbs, ctx->n);
 }
 
+// out[z][2][limbs][n] = src_z * perm_{g_z}(pt): up to 8 ciphertexts times slot rotations of one
+// plaintext (the rotation is the Galois permutation of its evaluation-domain words), one launch
+__global__ void k_mul_pt_rot_batch(u64 *__restrict__ out, MulPtBatch b, const u64 *__restrict__ pt_mont,
+                                   const ModC *__restrict__ modc, int limbs, int n, int logn) {
+    const unsigned i = blockIdx.x * TPB + threadIdx.x;
+    const int r = blockIdx.y, z = blockIdx.z, l = r % limbs;
+    const ModC m = modc[l];
+    const unsigned g = b.g[z];
+    const unsigned s = g ? perm_src(i, g, logn) : i;
+    out[((size_t)z * 2 * limbs + r) * n + i] = redc((u128)b.src[z][(size_t)r * n + i] * pt_mont[(size_t)l * n + s], m.q, m.qinv);
+}
+void launch_mul_pt_rot_batch(cm_ctx *ctx, u64 *out, const MulPtBatch &b, int cnt, const u64 *pt_mont, int limbs, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, cnt * 2 * limbs, st);
+    hipLaunchKernelGGL(k_mul_pt_rot_batch, dim3(ctx->n / TPB, 2 * limbs, cnt), dim3(TPB), 0, st, out, b, pt_mont, ctx->d_modc,
+                       limbs, ctx->n, ctx->logn);
+}
+
 // acc (+)= a * pt_mont over ncomp components; accumulate != 0 adds into out
 __global__ void k_mac_pt(u64 *out, const u64 *a, const u64 *pt_mont, const ModC *modc, int limbs, int n, int accumulate) {
     int i = blockIdx.x * TPB + threadIdx.x, r = blockIdx.y;

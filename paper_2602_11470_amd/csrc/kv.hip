@@ -78,6 +78,10 @@ extern "C" cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32
         const size_t ln = (size_t)(level + 1) * n, B = CM_KS_BATCH;
         const size_t qk = 5 * ctw + B * (3 * ln + 3 * ctw + ln + (size_t)kl.beta * kl.ext * n + 2 * n + 2 * (size_t)level * n);
         if (qk > kv->work_words) kv->work_words = qk;
+        // append: mask, one product and its rescale, r_o - 1 shifted inputs, then the batch buffers
+        const size_t ap = (size_t)(level + 2) * n + (size_t)(2 + kv->r_o) * ctw_up +
+                          B * (ctw_up + ctw + 2 * n + 2 * (size_t)(level + 1) * n);
+        if (ap > kv->work_words) kv->work_words = ap;
     }
     bool ok = hipMalloc((void **)&kv->d_k, (size_t)kv->nk_max * ctw * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_v, (size_t)kv->E * ctw * 8) == hipSuccess &&
@@ -193,16 +197,24 @@ extern "C" cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, con
         CMCHK(rotate_into(ctx, find_key(evk, rot_g(kv, step)), v_new->dev, lv, rot_g(kv, step),
                           shifted + (size_t)(g - 1) * ctw_up, st));
     }
-    for (int k = 0; k < kv->E; k++) {
-        int g = k / kv->r_i;
-        long long a = (long long)(((c - k) % kv->E + kv->E) % kv->E) * kv->H * kv->t + tau +
-                      (long long)g * kv->r_i * kv->H * kv->t;
-        launch_automorphism(ctx, mask, kv->d_mask_v, lv + 1, rot_g(kv, -a), st);
-        const u64 *src = g == 0 ? v_new->dev : shifted + (size_t)(g - 1) * ctw_up;
-        launch_mul_pt(ctx, prod, src, mask, 2, lv + 1, st);
-        CMCHK(rescale_into(ctx, prod, 2, lv, res, st));
-        u64 *vk = kv->d_v + (size_t)k * ctw;
-        launch_add(ctx, vk, vk, res, 2, kv->level + 1, st);
+    // CM_KS_BATCH value ciphertexts at a time: their masked products in one launch, one stacked rescale,
+    // one stacked addition (consecutive value ciphertexts are contiguous)
+    u64 *prods = shifted + (size_t)(kv->r_o > 1 ? kv->r_o - 1 : 0) * ctw_up, *ress = prods + (size_t)CM_KS_BATCH * ctw_up;
+    u64 *last = ress + (size_t)CM_KS_BATCH * ctw, *red = last + (size_t)CM_KS_BATCH * 2 * n;
+    for (int kb = 0; kb < kv->E; kb += CM_KS_BATCH) {
+        const int m = kv->E - kb < CM_KS_BATCH ? kv->E - kb : CM_KS_BATCH;
+        MulPtBatch mb;
+        for (int r = 0; r < m; r++) {
+            const int k = kb + r, g = k / kv->r_i;
+            long long a = (long long)(((c - k) % kv->E + kv->E) % kv->E) * kv->H * kv->t + tau +
+                          (long long)g * kv->r_i * kv->H * kv->t;
+            mb.src[r] = g == 0 ? v_new->dev : shifted + (size_t)(g - 1) * ctw_up;
+            mb.g[r] = (unsigned)rot_g(kv, -a);
+        }
+        launch_mul_pt_rot_batch(ctx, prods, mb, m, kv->d_mask_v, lv + 1, st);
+        CMCHK(rescale_into(ctx, prods, 2 * m, lv, ress, st, last, red));
+        u64 *vk = kv->d_v + (size_t)kb * ctw;
+        launch_add(ctx, vk, vk, ress, 2 * m, kv->level + 1, st);
     }
     kv->ntok++;
     kv->scale = k_new->scale * (double)ctx->mod[lv] / (double)ctx->mod[lv];
