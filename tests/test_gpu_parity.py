@@ -151,6 +151,30 @@ def test_rotate_hoisted(both, level):
         _same(b, b["octx"].rotate_hoisted(o, h, s, b["okeys"]), gout)
 
 
+def test_degenerate_rotations_and_empty_lists(both):
+    """Rotation by 0 and by a whole turn (S slots) is the identity, limb for limb, and needs no key;
+    in place works; a hoisted rotation of no steps returns nothing; steps 0 inside a list copy."""
+    b = both
+    gctx, S = b["gctx"], b["octx"].S
+    z = np.random.default_rng(8).uniform(-1, 1, S)
+    _, g = _pair(b, z, 3, 61)
+    ref = gctx.ct_export(g).copy()
+    assert np.array_equal(gctx.ct_export(gctx.rotate(b["gkeys"], g, 0)), ref)
+    assert np.array_equal(gctx.ct_export(gctx.rotate(b["gkeys"], g, S)), ref)
+    assert np.array_equal(gctx.ct_export(gctx.rotate(b["gkeys"], g, -S)), ref)
+    assert gctx.rotate_hoisted(b["gkeys"], g, []) == []
+    outs = gctx.rotate_hoisted(b["gkeys"], g, [0, 7, S])
+    assert np.array_equal(gctx.ct_export(outs[0]), ref) and np.array_equal(gctx.ct_export(outs[2]), ref)
+    o7 = gctx.rotate(b["gkeys"], g, 7)
+    assert np.abs(gctx.decrypt(b["gsk"], outs[1]) - gctx.decrypt(b["gsk"], o7)).max() < 1e-6
+    inplace = gctx.rotate(b["gkeys"], g, 7, out=g)                  # the library goes through a temporary
+    assert np.array_equal(gctx.ct_export(inplace), gctx.ct_export(o7))
+    # S - 1 is the same Galois element as -1; there and back gives the message again (not the limbs: noise)
+    back = gctx.rotate(b["gkeys"], gctx.rotate(b["gkeys"], gctx.rotate(b["gkeys"], o7, 0), S - 1), 1)
+    assert np.abs(gctx.decrypt(b["gsk"], back) - np.roll(z, -7)).max() < 1e-5
+    assert not np.array_equal(gctx.ct_export(back), gctx.ct_export(o7))
+
+
 def test_keyswitch_alone(both):
     import torch
     b = both

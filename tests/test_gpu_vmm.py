@@ -230,6 +230,74 @@ def test_rope_with_fused_extraction_matches_oracle_and_the_textbook_rotation(env
     assert err.value.status == -4
 
 
+@pytest.mark.parametrize("d_in,d_out", [(2048, 2048), (64, 64), (2, 2048), (2048, 2)])
+def test_vmm_pt_degenerate_shapes(env, d_in, d_out):
+    """d = S (one slot per element: no preprocess and no reduce rotations), the narrowest square
+    product the ring allows (d^2 >= S: two diagonals), and the widest expansion / contraction; all
+    three forms."""
+    from oracle import packing, vmm
+    from paper_2602_11470_amd import inputs
+    e = env
+    octx, gctx = e["octx"], e["gctx"]
+    level = 2
+    x, W = inputs.vmm_inputs(11, d_in, d_out, "uniform", 0.5 if max(d_in, d_out) < 4 else 0.02)
+    plan = packing.make_plan(octx.S, d_in, d_out)
+    scale = octx.prm.scale
+    diag_coeffs = [[octx.encode_coeffs(v, scale) for v in row] for row in plan.diagonals(W)]
+    flat = np.stack([c for row in diag_coeffs for c in row])
+    steps = sorted(set(vmm.direct_giant_steps(plan)) | set(plan.all_steps()))
+    okeys = octx.keygen_rotations(e["osk"], steps, 2) if steps else {}
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2)
+    ox, gx = _enc_both(e, plan.pack_input(x), level, 3)
+    for form in ("plain", "raised", "direct"):
+        gplan = gctx.vmm_plan(d_in, d_out, level=level, r_i=plan.r_i, coeffs=flat,
+                              raised_sums=form != "plain", direct_giants=form == "direct")
+        assert gplan.n_rotations == plan.n_rotations
+        if form == "plain":
+            odiags = [[octx.pt_from_coeffs(c, level, scale) for c in row] for row in diag_coeffs]
+            oy = vmm.vmm_pt(vmm.CkksOps(octx, okeys), plan, ox, odiags)
+        else:
+            odiags = [[octx.pt_from_coeffs_ext(c, level, scale) for c in row] for row in diag_coeffs]
+            fn = vmm.vmm_pt_direct_giants if form == "direct" else vmm.vmm_pt_double_hoisted
+            oy = fn(octx, okeys, plan, ox, odiags)
+        gy = gctx.vmm_pt(gkeys, gplan, gx)
+        _same(e, oy, gy)
+        assert np.abs(plan.unpack_output(gctx.decrypt(e["gsk"], gy).real) - x @ W).max() < TOL
+
+
+def test_kv_single_token_and_full_cache(env):
+    """One token in the cache (a ragged first key ciphertext), then the cache filled to its
+    capacity E t: scores and weighted values against float64, and one append too many refused."""
+    from oracle import packing
+    from paper_2602_11470_amd import inputs
+    e = env
+    B, octx, gctx, L = e["B"], e["octx"], e["gctx"], e["prm"].L
+    H, E = 64, 4                                             # t = 8, capacity 32 tokens
+    lay = packing.KvLayout(octx.S, H, E)
+    q, K, V, s = inputs.attention_inputs(6, H, H, E, lay.capacity)
+    kv = gctx.kv_create(H, E, L - 1)
+    gkeys = gctx.keygen_rotations(e["gsk"], kv.steps(), 2, with_relin=True)
+    enc = lambda slots, level, seed: _enc_both(e, slots, level, seed)[1]
+    for n in range(lay.capacity):
+        tau = n % lay.t
+        kv.append(gkeys, enc(lay.pack_vec(K[n], tau), L, 100 + n), enc(lay.pack_vec(V[n], tau), L, 200 + n))
+        if n in (0, lay.capacity - 1):
+            ntok = n + 1
+            gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, enc(lay.pack_vec(q), L - 1, 7))
+            got = lay.unpack_scores(gctx.decrypt(e["gsk"], gm).real, ntok)
+            assert np.abs(got - np.einsum("he,nhe->hn", q, K[:ntok])).max() < TOL
+            sn = s[:, :ntok] / s[:, :ntok].sum(axis=1, keepdims=True)
+            ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, enc(lay.pack_scores(sn), L - 1, 8))
+            assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", sn, V[:ntok])).max() < TOL
+    with pytest.raises(B.CachemirError) as err:
+        kv.append(gkeys, enc(lay.pack_vec(K[0], 0), L, 1), enc(lay.pack_vec(V[0], 0), L, 2))
+    assert err.value.status == -5
+    empty = gctx.kv_create(H, E, L - 1)
+    with pytest.raises(B.CachemirError) as err:
+        gctx.vmm_kv(gkeys, empty, B.CM_QK, enc(lay.pack_vec(q), L - 1, 7))
+    assert err.value.status == -5
+
+
 def test_vmm_pt_missing_key_and_level_errors(env):
     e = env
     B, gctx = e["B"], e["gctx"]
@@ -248,6 +316,14 @@ def test_vmm_pt_missing_key_and_level_errors(env):
     with pytest.raises(B.CachemirError) as err:
         gctx.vmm_plan(96, 96, W=np.zeros((96, 96)), level=3)       # not a power of two
     assert err.value.status == -5
+    with pytest.raises(B.CachemirError) as err:
+        gctx.vmm_plan(32, 32, W=np.zeros((32, 32)), level=3)       # d^2 < S: less than one diagonal
+    assert err.value.status == -5
+    h, w = B._vp(), np.zeros((64, 64))
+    status = B.lib.cm_vmm_plan_create_ex(gctx.h, 64, 64, 0, 0, 3, 0.0, w.ctypes.data, None, 8, B.C.byref(h))
+    assert status == -1 and not h.value                            # unknown flag bit
+    status = B.lib.cm_vmm_plan_create_ex(gctx.h, 64, 64, 0, 0, 3, 0.0, None, None, 0, B.C.byref(h))
+    assert status == -1                                            # neither W nor coefficients
 
 
 @pytest.mark.parametrize("r_i", [0, 4])
