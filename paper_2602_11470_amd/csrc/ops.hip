@@ -2,6 +2,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
+
 #include "kernels.h"
 
 // stream identifiers of the counter-based generator
@@ -96,6 +98,17 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
         k.modup_max_nt = std::max(k.modup_max_nt, tabs[j].nt);
     }
     k.d_modup = up(mu);
+    {
+        // Transform the converted limbs modulus by modulus rather than digit by digit: the limbs that
+        // share a twiddle table are then adjacent in the launch and the table is reused from L2
+        // instead of being refetched by every XCD for every digit.
+        std::vector<int> order(ntt_rows.size());
+        for (size_t i = 0; i < order.size(); i++) order[i] = (int)i;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return ntt_mods[a] < ntt_mods[b]; });
+        std::vector<int> r2, m2;
+        for (int i : order) r2.push_back(ntt_rows[i]), m2.push_back(ntt_mods[i]);
+        ntt_rows.swap(r2), ntt_mods.swap(m2);
+    }
     k.d_ntt_rows = up(ntt_rows);
     k.d_ntt_mods = up(ntt_mods);
     k.h_ntt_rows = ntt_rows, k.h_ntt_mods = ntt_mods;
