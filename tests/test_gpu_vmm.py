@@ -265,6 +265,47 @@ def test_vmm_pt_degenerate_shapes(env, d_in, d_out):
         assert np.abs(plan.unpack_output(gctx.decrypt(e["gsk"], gy).real) - x @ W).max() < TOL
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_vmm_pt_seeded_sweep_of_shapes_levels_and_forms(env, seed):
+    """Shapes, levels, baby-step counts, residues and forms drawn from a seeded generator; every
+    case limb for limb against the oracle, and run twice (a race would show as a difference)."""
+    from oracle import packing, vmm
+    from paper_2602_11470_amd import inputs
+    e = env
+    octx, gctx = e["octx"], e["gctx"]
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([64, 128, 256, 512, 1024]))
+    alpha = int(rng.choice([1, 1, 2, 4]))
+    shape = rng.choice(["square", "expand", "contract"]) if alpha > 1 and d * alpha <= octx.S else "square"
+    d_in, d_out = (d, d) if shape == "square" else (d, d * alpha) if shape == "expand" else (d * alpha, d)
+    level = int(rng.integers(1, 5))
+    plan0 = packing.make_plan(octx.S, d_in, d_out)
+    r_i = int(rng.choice([r for r in (1, 2, 4, 8, 16, 32) if plan0.M % r == 0 and r <= plan0.M]))
+    tau = int(rng.integers(0, plan0.t2))
+    form = str(rng.choice(["plain", "raised", "direct"]))
+    plan = packing.make_plan(octx.S, d_in, d_out, r_i, tau)
+    x, W = inputs.vmm_inputs(seed, d_in, d_out, "uniform", 0.05)
+    scale = octx.prm.scale
+    diag_coeffs = [[octx.encode_coeffs(v, scale) for v in row] for row in plan.diagonals(W)]
+    flat = np.stack([c for row in diag_coeffs for c in row])
+    steps = sorted(set(vmm.direct_giant_steps(plan) if form == "direct" else plan.all_steps()))
+    okeys = octx.keygen_rotations(e["osk"], steps, 2) if steps else {}
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2)
+    ox, gx = _enc_both(e, plan.pack_input(x), level, 3)
+    gplan = gctx.vmm_plan(d_in, d_out, level=level, r_i=r_i, tau=tau, coeffs=flat,
+                          raised_sums=form != "plain", direct_giants=form == "direct")
+    if form == "plain":
+        odiags = [[octx.pt_from_coeffs(c, level, scale) for c in row] for row in diag_coeffs]
+        oy = vmm.vmm_pt(vmm.CkksOps(octx, okeys), plan, ox, odiags)
+    else:
+        odiags = [[octx.pt_from_coeffs_ext(c, level, scale) for c in row] for row in diag_coeffs]
+        oy = (vmm.vmm_pt_direct_giants if form == "direct" else vmm.vmm_pt_double_hoisted)(octx, okeys, plan, ox, odiags)
+    gy = gctx.vmm_pt(gkeys, gplan, gx)
+    _same(e, oy, gy)
+    assert np.array_equal(gctx.ct_export(gctx.vmm_pt(gkeys, gplan, gx)), gctx.ct_export(gy))
+    assert np.abs(plan.unpack_output(gctx.decrypt(e["gsk"], gy).real) - x @ W).max() < TOL, (d_in, d_out, level, r_i, tau, form)
+
+
 def test_kv_single_token_and_full_cache(env):
     """One token in the cache (a ragged first key ciphertext), then the cache filled to its
     capacity E t: scores and weighted values against float64, and one append too many refused."""
