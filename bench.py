@@ -199,7 +199,7 @@ def attention_workload(a):
     from paper_2602_11470_amd import binding as B
     ctx = B.llama_ring(24, 4)
     H, E, L = 32, 128, ctx.L
-    lv = L - 1
+    lv = a.cache_level if a.cache_level > 0 else L - 1
     kv = ctx.kv_create(H, E, lv, r_i=16)
     sk = ctx.keygen_secret(1)
     keys = ctx.keygen_rotations(sk, kv.steps(), 2, with_relin=True)
@@ -210,7 +210,8 @@ def attention_workload(a):
         kv.load(B.CM_SV, c, enc(300 + c))
     # appends of new tokens (inputs one level above the cache), timed on a nearly full cache
     kv.set_tokens(1024 - 8)
-    new_k, new_v = ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), L), 20), ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), L), 21)
+    new_k = ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), L), 20), lv + 1)
+    new_v = ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), L), 21), lv + 1)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(8):
@@ -284,6 +285,7 @@ def main():
                     help="giant steps in the nested (Horner) form with one key, as Algorithm 1 prints them")
     ap.add_argument("--plain-sums", action="store_true",
                     help="divide every hoisted rotation by P on its own (31 more ModDowns per step)")
+    ap.add_argument("--cache-level", type=int, default=0, help="attention workload: level of the cache (default L-1)")
     ap.add_argument("--workload", choices=["projection", "attention", "sweep"], default="projection",
                     help="projection = config 2 (the benchmark line); attention = config 3; sweep = other widths "
                          "and levels; the last two print a line of their own")
