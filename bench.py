@@ -271,8 +271,30 @@ def sweep_workload(a):
         rows.append({"d": d, "level": level, "rotations": plan.n_rotations, "pt_mults": plan.r_i * plan.r_o,
                      "ms": ms, "max_abs_err": err})
         del plan, keys
+    # the q / k / v projections of one token: one input, three weight matrices of one shape; the
+    # preprocess rotations and the hoisted baby steps run once (cm_vmm_pt_multi)
+    d, level = 4096, ctx.L
+    x, _ = inputs.vmm_inputs(1, d, d)
+    plans = [ctx.vmm_plan(d, d, W=inputs.vmm_inputs(2 + i, d, d)[1], level=level, direct_giants=True) for i in range(3)]
+    keys = ctx.keygen_rotations(sk, plans[0].steps(), 2)
+    slots = np.zeros(ctx.S)
+    slots[::ctx.S // d] = x
+    ct = ctx.encrypt(sk, ctx.encode(slots, ctx.L), 3)
+    outs = ctx.vmm_pt_multi(keys, plans, ct)
+    qkv = {}
+    for name, fn in (("three single products", lambda: [ctx.vmm_pt(keys, p, ct, out=o) for p, o in zip(plans, outs)]),
+                     ("one shared-baby-step call", lambda: ctx.vmm_pt_multi(keys, plans, ct, outs))):
+        for _ in range(a.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            fn()
+        torch.cuda.synchronize()
+        qkv[name] = (time.perf_counter() - t0) / a.steps * 1e3
     print(json.dumps({"metric": "ms per homomorphic VMM, widths of Table 4 and levels 23/13/4/1 (n=2^16, 24+4 primes)",
-                      "unit": "ms", "n_gpus": 1, "data": "synthetic", "dtype": "u64", "rows": rows}))
+                      "unit": "ms", "n_gpus": 1, "data": "synthetic", "dtype": "u64", "rows": rows,
+                      "qkv_projections_ms": qkv}))
 
 
 def main():

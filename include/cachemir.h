@@ -199,6 +199,14 @@ cm_status cm_vmm_plan_diag_export(cm_ctx *ctx, const cm_vmm_plan *plan, int32_t 
 cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *plan, const cm_ct *x,
                     cm_ct *y, void *stream);
 
+/* Several products of the same input (the q / k / v projections of a token, or gate and up):
+ * ys[i] = x W_i for plans of one shape (same d_in, d_out, level, r_i; the output residue tau may
+ * differ), all created with CM_VMM_RAISED_SUMS.  The preprocess rotations and the hoisted baby
+ * steps depend on x only, so they run once; each plan then does its own products and giant
+ * steps.  Every ys[i] is bit for bit what cm_vmm_pt(plans[i], x) gives.  plans must be distinct. */
+cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *const *plans,
+                          int32_t nplans, const cm_ct *x, cm_ct *const *ys, void *stream);
+
 /* ---- encrypted KV cache (Sec. 5) -------------------------------------------------------- */
 enum { CM_QK = 0, CM_SV = 1 };
 /* Cache for `heads` heads of `dim` dims (heads*dim*t = S) holding up to max_tokens tokens

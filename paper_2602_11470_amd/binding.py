@@ -76,6 +76,7 @@ _SIGS = {
     "cm_vmm_plan_info": ([_vp, _P(_i32), _P(_i32), _P(_i32)], _i32),
     "cm_vmm_plan_diag_export": ([_vp, _vp, _i32, _i32, _vp], _i32),
     "cm_vmm_pt": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
+    "cm_vmm_pt_multi": ([_vp, _vp, _vp, _i32, _P(cm_ct), _vp, _vp], _i32),
     "cm_rope_create": ([_vp, _i32, _i32, _i32, _i32, _i32, _f64, _vp, _P(_vp)], _i32),
     "cm_rope_destroy": ([_vp], None),
     "cm_rope_steps": ([_vp, _vp, _i32], _i32),
@@ -299,6 +300,14 @@ class Context:
         out = out or Ct(self, x.level - 1)
         _chk(lib.cm_vmm_pt(self.h, evk.h, plan.h, C.byref(x.d), C.byref(out.d), _stream()))
         return out
+
+    def vmm_pt_multi(self, evk, plans, x, outs=None):
+        """Products of one input with several plans of the same shape; the baby steps run once."""
+        outs = outs or [Ct(self, x.level - 1) for _ in plans]
+        hp = (_vp * len(plans))(*[p.h for p in plans])
+        yp = (C.POINTER(cm_ct) * len(plans))(*[C.pointer(o.d) for o in outs])
+        _chk(lib.cm_vmm_pt_multi(self.h, evk.h, hp, len(plans), C.byref(x.d), yp, _stream()))
+        return outs
 
     def rope(self, heads, dim, level, token, tau=0, base=10000.0, coeffs=None):
         return Rope(self, heads, dim, level, token, tau, base, coeffs)

@@ -231,13 +231,13 @@ extern "C" cm_status cm_vmm_plan_diag_export(cm_ctx *ctx, const cm_vmm_plan *p, 
 // The same product with the sums of the baby steps kept in the extended basis: hoisted rotations stop
 // before their ModDown (u + P sigma(c0), u1), the plaintext products are summed on level+1+K limbs,
 // and every inner_k is divided by P inside the giant step that consumes it.
-static cm_status vmm_pt_raised(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const cm_ct *x, cm_ct *y,
-                               hipStream_t st) {
+// First half: preprocess and baby steps of x into the plan's own work area (babies[r_i][2][ext][n]).
+static cm_status vmm_raised_babies(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const cm_ct *x, hipStream_t st) {
     const int level = p->level, limbs = level + 1, ext = p->pt_limbs;
     const size_t n = ctx->n, ctw = 2 * (size_t)limbs * n, ptw = (size_t)limbs * n, rw = 2 * (size_t)ext * n;
     auto key_of = [&](int step) { return find_key(evk, galois_of_step(ctx, step)); };
     u64 *babies = p->d_work, *inner = babies + (size_t)p->r_i * rw, *t0 = inner + (size_t)p->r_o * rw;
-    u64 *t1 = t0 + ctw, *t2 = t1 + ctw;
+    u64 *t1 = t0 + ctw;
     // 1. preprocess (rotate-and-add between two buffers)
     u64 *c = t0, *other = t1;
     HIPCHK(hipMemcpyAsync(c, x->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
@@ -260,10 +260,20 @@ static cm_status vmm_pt_raised(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
         }
         CMCHK(ks_apply_many_raised(ctx, digits, level, p->r_i - 1, keys.data(), gs.data(), c, dst.data(), st));
     }
+    return CM_OK;
+}
+// Second half: products with the plan's own weights against the given baby ciphertexts (its own, or
+// those of another plan of the same shape that saw the same input), giant steps, reduce, rescale.
+static cm_status vmm_raised_finish(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const u64 *babies, const cm_ct *x,
+                                   cm_ct *y, hipStream_t st) {
+    const int level = p->level, limbs = level + 1, ext = p->pt_limbs;
+    const size_t n = ctx->n, ctw = 2 * (size_t)limbs * n, rw = 2 * (size_t)ext * n;
+    auto key_of = [&](int step) { return find_key(evk, galois_of_step(ctx, step)); };
+    u64 *inner = p->d_work + (size_t)p->r_i * rw, *t0 = inner + (size_t)p->r_o * rw;
+    u64 *t1 = t0 + ctw, *t2 = t1 + ctw;
     const int r_o = p->r_o;
     launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, ext, level, rw, 0, r_o, st);
-    u64 *acc = c == t0 ? t1 : t0;
-    other = t2;
+    u64 *acc = t1, *other = t2;
     if (p->direct) {
         // giant steps unrolled: inner_k -> ciphertext -> raised digits (all k at once); every rotation by
         // k*G stays in the extended basis and joins inner_0; one ModDown for the whole sum
@@ -305,6 +315,41 @@ static cm_status vmm_pt_raised(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     y->scale = x->scale * p->pt_scale / (double)ctx->mod[level];
     return CM_OK;
 }
+static cm_status vmm_pt_raised(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const cm_ct *x, cm_ct *y,
+                               hipStream_t st) {
+    CMCHK(vmm_raised_babies(ctx, evk, p, x, st));
+    return vmm_raised_finish(ctx, evk, p, p->d_work, x, y, st);
+}
+
+static cm_status plan_keys_present(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p) {
+    auto key_of = [&](int step) { return find_key(evk, galois_of_step(ctx, step)); };
+    for (int r : p->pre_steps) if (!key_of(r)) return CM_E_NOKEY;
+    for (int j = 1; j < p->r_i; j++) if (!key_of(p->baby_steps[j])) return CM_E_NOKEY;
+    for (int k = 1; k < p->r_o; k++)
+        if ((k == 1 || p->direct) && !key_of(k * p->giant_step)) return CM_E_NOKEY;
+    for (int r : p->reduce_steps) if (!key_of(r)) return CM_E_NOKEY;
+    return CM_OK;
+}
+
+extern "C" cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *const *plans, int32_t nplans,
+                                     const cm_ct *x, cm_ct *const *ys, void *stream) {
+    if (!ctx || !evk || !plans || nplans < 1 || !x || !x->dev || x->ncomp != 2 || !ys) return CM_E_INVAL;
+    const cm_vmm_plan *p0 = plans[0];
+    for (int i = 0; i < nplans; i++) {
+        const cm_vmm_plan *p = plans[i];
+        if (!p || p->ctx != ctx || !ys[i] || !ys[i]->dev || !p->raised) return CM_E_INVAL;
+        if (p->level != p0->level || p->d_in != p0->d_in || p->d_out != p0->d_out || p->r_i != p0->r_i) return CM_E_LAYOUT;
+        for (int j = 0; j < i; j++)
+            if (plans[j] == p) return CM_E_INVAL;         // a plan's work area holds one product at a time
+        cm_status s = plan_keys_present(ctx, evk, p);
+        if (s != CM_OK) return s;
+    }
+    if (x->level != p0->level) return CM_E_LEVEL;
+    hipStream_t st = (hipStream_t)stream;
+    CMCHK(vmm_raised_babies(ctx, evk, p0, x, st));
+    for (int i = 0; i < nplans; i++) CMCHK(vmm_raised_finish(ctx, evk, plans[i], p0->d_work, x, ys[i], st));
+    return CM_OK;
+}
 
 extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const cm_ct *x, cm_ct *y,
                                void *stream) {
@@ -314,13 +359,8 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     const int level = p->level, limbs = level + 1;
     const size_t n = ctx->n, ctw = 2 * (size_t)limbs * n, ptw = (size_t)limbs * n;
     // every key must be there before anything is enqueued
+    CMCHK(plan_keys_present(ctx, evk, p));
     auto key_of = [&](int step) { return find_key(evk, galois_of_step(ctx, step)); };
-    for (int r : p->pre_steps) if (!key_of(r)) return CM_E_NOKEY;
-    for (int j = 1; j < p->r_i; j++) if (!key_of(p->baby_steps[j])) return CM_E_NOKEY;
-    for (int k = 1; k < p->r_o; k++)
-        if ((k == 1 || p->direct) && !key_of(k * p->giant_step)) return CM_E_NOKEY;
-    for (int r : p->reduce_steps) if (!key_of(r)) return CM_E_NOKEY;
-
     if (p->raised) return vmm_pt_raised(ctx, evk, p, x, y, st);
     u64 *babies = p->d_work, *inner = babies + (size_t)p->r_i * ctw, *tmp = inner + (size_t)p->r_o * ctw;
     // 1. preprocess: c <- c + Rot(c, 2^i (t-1)).  A rotate-and-add writes to the other of two buffers

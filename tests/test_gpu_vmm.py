@@ -306,6 +306,43 @@ def test_vmm_pt_seeded_sweep_of_shapes_levels_and_forms(env, seed):
     assert np.abs(plan.unpack_output(gctx.decrypt(e["gsk"], gy).real) - x @ W).max() < TOL, (d_in, d_out, level, r_i, tau, form)
 
 
+@pytest.mark.parametrize("direct", [False, True])
+def test_vmm_pt_multi_shares_baby_steps_and_equals_single_products(env, direct):
+    """Three projections of one input (different weights, one of them landing on another residue):
+    each output of the shared-baby-step call is bit for bit the single product's."""
+    from paper_2602_11470_amd import inputs
+    e = env
+    B, gctx = e["B"], e["gctx"]
+    d, level = 256, 3
+    x, _ = inputs.vmm_inputs(20, d, d, "uniform", 0.05)
+    Ws = [inputs.vmm_inputs(21 + i, d, d, "uniform", 0.05)[1] for i in range(3)]
+    plans = [gctx.vmm_plan(d, d, W=W, level=level, tau=(3 if i == 1 else 0), raised_sums=True, direct_giants=direct)
+             for i, W in enumerate(Ws)]
+    steps = sorted(set(sum((p.steps() for p in plans), [])))
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2)
+    slots = np.zeros(gctx.S)
+    t = gctx.S // d
+    slots[::t] = x
+    _, gx = _enc_both(e, slots, level, 4)
+    singles = [gctx.ct_export(gctx.vmm_pt(gkeys, p, gx)).copy() for p in plans]
+    outs = gctx.vmm_pt_multi(gkeys, plans, gx)
+    for i, (o, ref) in enumerate(zip(outs, singles)):
+        assert np.array_equal(gctx.ct_export(o), ref)
+        tau = 3 if i == 1 else 0
+        assert np.abs(gctx.decrypt(e["gsk"], o).real[tau::t] - x @ Ws[i]).max() < TOL
+    plain = gctx.vmm_plan(d, d, W=Ws[0], level=level)
+    with pytest.raises(B.CachemirError) as err:
+        gctx.vmm_pt_multi(gkeys, [plans[0], plain], gx)           # needs the raised form
+    assert err.value.status == -1
+    with pytest.raises(B.CachemirError) as err:
+        gctx.vmm_pt_multi(gkeys, [plans[0], plans[0]], gx)        # one work area per plan
+    assert err.value.status == -1
+    other = gctx.vmm_plan(d, d, W=Ws[0], level=level, r_i=4, raised_sums=True)
+    with pytest.raises(B.CachemirError) as err:
+        gctx.vmm_pt_multi(gkeys, [plans[0], other], gx)           # different baby steps
+    assert err.value.status in (-5, -4)
+
+
 def test_kv_single_token_and_full_cache(env):
     """One token in the cache (a ragged first key ciphertext), then the cache filled to its
     capacity E t: scores and weighted values against float64, and one append too many refused."""
