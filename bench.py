@@ -251,12 +251,20 @@ def sweep_workload(a):
     ctx = B.llama_ring(24, 4)
     sk = ctx.keygen_secret(1)
     rows = []
-    for d, level in ((4096, 23), (4096, 13), (4096, 4), (4096, 1), (2048, 23), (1024, 23)):
-        x, W = inputs.vmm_inputs(1, d, d)
-        plan = ctx.vmm_plan(d, d, W=W, level=level, direct_giants=True)
+    shapes = ((4096, 4096, 23), (4096, 4096, 13), (4096, 4096, 4), (4096, 4096, 1), (2048, 2048, 23), (1024, 1024, 23),
+              (4096, 16384, 23), (16384, 4096, 23))          # the last two: MLP up / down (14336 padded to 16384)
+    for d_in, d_out, level in shapes:
+        x, W = inputs.vmm_inputs(1, d_in, d_out)
+        plan = ctx.vmm_plan(d_in, d_out, W=W, level=level, direct_giants=True)
         keys = ctx.keygen_rotations(sk, plan.steps(), 2)
+        d = min(d_in, d_out)
+        t, tp = ctx.S // d, ctx.S // max(d_in, d_out)
         slots = np.zeros(ctx.S)
-        slots[::ctx.S // d] = x
+        if d_in <= d_out:
+            slots[::t] = x                                       # x[b] at slot b t
+        else:
+            for s_ in range(d_in // d):
+                slots[s_ * tp::t] = x[s_ * d:(s_ + 1) * d]       # x[b + s d] at slot b t + s t'
         ct = ctx.level_drop(ctx.encrypt(sk, ctx.encode(slots, ctx.L), 3), level)
         y = ctx.vmm_pt(keys, plan, ct)
         for _ in range(a.warmup):
@@ -267,8 +275,14 @@ def sweep_workload(a):
             ctx.vmm_pt(keys, plan, ct, out=y)
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) / a.steps * 1e3
-        err = float(np.abs(ctx.decrypt(sk, y).real[::ctx.S // d] - x @ W).max())
-        rows.append({"d": d, "level": level, "rotations": plan.n_rotations, "pt_mults": plan.r_i * plan.r_o,
+        out = ctx.decrypt(sk, y).real
+        ref = x @ W
+        if d_out <= d_in:
+            got = out[::t]                                       # y[c] at slot c t
+        else:
+            got = np.concatenate([out[s_ * tp::t] for s_ in range(d_out // d)])   # y[b + s d] at b t + s t'
+        err = float(np.abs(got - ref).max())
+        rows.append({"d_in": d_in, "d_out": d_out, "level": level, "rotations": plan.n_rotations, "pt_mults": plan.r_i * plan.r_o,
                      "ms": ms, "max_abs_err": err})
         del plan, keys
     # the q / k / v projections of one token: one input, three weight matrices of one shape; the
