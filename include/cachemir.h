@@ -22,7 +22,12 @@
  *  - `stream` is a hipStream_t passed as void* (0 = the null stream).  Calls that take a
  *    stream only enqueue work; the others synchronise.
  *  - A context's scratch arena is shared by all calls on it: calls on one context must not
- *    overlap in time.
+ *    overlap in time (enqueue them on one stream, or order the streams).  A plan, a cache and
+ *    a rotary-embedding object each hold one work area of their own with the same rule.
+ *  - The hot calls (cm_rotate*, cm_vmm_pt*, cm_vmm_kv, cm_kv_append, cm_rope_apply and the
+ *    element-wise ones) allocate nothing and only enqueue kernels and device copies once the
+ *    per-level tables exist (the first call at a level builds them), so they can be captured
+ *    into a HIP graph after one eager call.
  */
 #ifndef CACHEMIR_H
 #define CACHEMIR_H
