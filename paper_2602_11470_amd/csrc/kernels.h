@@ -13,8 +13,13 @@ struct MulPtBatch {
     unsigned g[CM_KS_BATCH];
 };
 void launch_mul_pt_rot_batch(cm_ctx *ctx, u64 *out, const MulPtBatch &b, int cnt, const u64 *pt_mont, int limbs, hipStream_t st);
+// acc[2][limbs][n] (+)= sum_{z<cnt} src[z] * (pt rotated by b.g[z]), src[z] = src + z*2*limbs*n (b.src unused)
+void launch_mac_pt_rot_batch(cm_ctx *ctx, u64 *acc, const u64 *src, const MulPtBatch &b, int cnt, const u64 *pt_mont,
+                             int limbs, int accumulate, hipStream_t st);
 void launch_mac_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, int accumulate, hipStream_t st);
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st);
+// out[z][3][limbs][n] = a (x) b[z], b[z] = b + z*2*limbs*n, z < cnt
+void launch_tensor_batch(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int limbs, hipStream_t st);
 void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st);
 // batch item z: table (z % tab_period)*tab_step (tab_period 0 = batch), input (z / in_group)*in_stride, output z*out_stride
 void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_step, int max_nt, u64 *out, const u64 *in,

@@ -112,6 +112,46 @@ __global__ void k_tensor(u64 *out, const u64 *a, const u64 *b, const ModC *modc,
     out[o + cs] = d1;
     out[o + 2 * cs] = d2;
 }
+// out[z][3][limbs][n] = a (x) b[z] for cnt ciphertexts b stacked at stride 2*limbs*n: one launch
+__global__ void k_tensor_batch(u64 *__restrict__ out, const u64 *__restrict__ a, const u64 *__restrict__ b,
+                               const ModC *__restrict__ modc, int limbs, int n) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y, z = blockIdx.z;
+    const ModC m = modc[l];
+    size_t o = (size_t)l * n + i, cs = (size_t)limbs * n;
+    u64 a0 = to_mont(a[o], m), a1 = to_mont(a[o + cs], m);
+    const u64 *bz = b + (size_t)z * 2 * cs;
+    u64 *oz = out + (size_t)z * 3 * cs;
+    u64 b0 = bz[o], b1 = bz[o + cs];
+    oz[o] = redc((u128)a0 * b0, m.q, m.qinv);
+    oz[o + cs] = redc((u128)a0 * b1 + (u128)a1 * b0, m.q, m.qinv);
+    oz[o + 2 * cs] = redc((u128)a1 * b1, m.q, m.qinv);
+}
+void launch_tensor_batch(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int limbs, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, 3 * limbs * cnt, st);
+    hipLaunchKernelGGL(k_tensor_batch, dim3(ctx->n / TPB, limbs, cnt), dim3(TPB), 0, st, out, a, b, ctx->d_modc, limbs, ctx->n);
+}
+// acc[2][limbs][n] (+)= sum_z src[z] * (pt rotated by g[z]); src stacked at stride 2*limbs*n: one launch, acc written once
+__global__ void k_mac_pt_rot_batch(u64 *acc, const u64 *__restrict__ src, MulPtBatch b, int cnt,
+                                   const u64 *__restrict__ pt_mont, const ModC *__restrict__ modc, int limbs, int n, int logn,
+                                   int accumulate) {
+    const unsigned i = blockIdx.x * TPB + threadIdx.x;
+    const int r = blockIdx.y, l = r % limbs;
+    const ModC m = modc[l];
+    const size_t o = (size_t)r * n + i;
+    u64 v = accumulate ? acc[o] : 0;
+    for (int z = 0; z < cnt; z++) {
+        const unsigned g = b.g[z];
+        const unsigned s = g ? perm_src(i, g, logn) : i;
+        v = addmod(v, redc((u128)src[(size_t)z * 2 * limbs * n + o] * pt_mont[(size_t)l * n + s], m.q, m.qinv), m.q);
+    }
+    acc[o] = v;
+}
+void launch_mac_pt_rot_batch(cm_ctx *ctx, u64 *acc, const u64 *src, const MulPtBatch &b, int cnt, const u64 *pt_mont,
+                             int limbs, int accumulate, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, cnt * 2 * limbs, st);
+    hipLaunchKernelGGL(k_mac_pt_rot_batch, dim3(ctx->n / TPB, 2 * limbs), dim3(TPB), 0, st, acc, src, b, cnt, pt_mont,
+                       ctx->d_modc, limbs, ctx->n, ctx->logn, accumulate);
+}
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st) {
     Prof prof_(ctx, CM_K_ELEMENTWISE, 3 * limbs, st);
     hipLaunchKernelGGL(k_tensor, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, a, b, ctx->d_modc, limbs, ctx->n, accumulate);

@@ -251,7 +251,7 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
         const u64 *adds[CM_KS_BATCH], *accs[CM_KS_BATCH];
         u64 *outs[CM_KS_BATCH];
         // tensor products, relinearised together
-        for (int r = 0; r < m; r++) launch_tensor(ctx, TB + r * 3 * ln, cq, kv->d_k + (size_t)(c0 + r) * ctw, limbs, 0, st);
+        launch_tensor_batch(ctx, TB, cq, kv->d_k + (size_t)c0 * ctw, m, limbs, st);
         CMCHK(ks_raise_many(ctx, kv->relin_tabs, TB, ksin, digits, st, m, 0));
         const size_t ublk = 2 * (size_t)kl.ext * n, dblk = (size_t)kl.beta * kl.ext * n;
         IpBatch ip;
@@ -278,11 +278,11 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
             CMCHK(moddown_batch_into(ctx, bu, lv - 1, m, adds, 1, g, accs, outs, st));
             std::swap(r0, r1);
         }
-        for (int r = 0; r < m; r++) {
-            // keep copy e = c: base mask rotated right by c*H*t
-            const int c = c0 + r;
-            launch_automorphism(ctx, mask, kv->d_mask_qk, lv, rot_g(kv, -(long long)(c % kv->E) * kv->H * kv->t), st);
-            launch_mac_pt(ctx, acc, r0 + r * ctw1, mask, 2, lv, c > 0, st);
+        {
+            // keep copy e = c of every key ciphertext's sums: base mask rotated right by c*H*t; one launch
+            MulPtBatch mb;
+            for (int r = 0; r < m; r++) mb.src[r] = nullptr, mb.g[r] = (unsigned)rot_g(kv, -(long long)((c0 + r) % kv->E) * kv->H * kv->t);
+            launch_mac_pt_rot_batch(ctx, acc, r0, mb, m, kv->d_mask_qk, lv, c0 > 0, st);
         }
     }
     CMCHK(rescale_into(ctx, acc, 2, lv - 1, out->dev, st));
