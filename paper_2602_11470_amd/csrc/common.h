@@ -165,6 +165,17 @@ struct cm_evk {
             return CM_E_HIP;                       \
         }                                          \
     } while (0)
+// Kernel launches report a bad configuration only through the runtime's last-error slot: the hot
+// entry points end with this check (no synchronisation).
+#define RETURN_LAUNCH_STATUS()                     \
+    do {                                           \
+        hipError_t e_ = hipPeekAtLastError();      \
+        if (e_ != hipSuccess) {                    \
+            cm_set_hip_error((int)e_);             \
+            return CM_E_HIP;                       \
+        }                                          \
+        return CM_OK;                              \
+    } while (0)
 #define CMCHK(x)                \
     do {                        \
         cm_status s_ = (x);     \

@@ -171,6 +171,7 @@ static u64 rot_g(const cm_kv *kv, long long step) {
 
 extern "C" cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_new, const cm_ct *v_new,
                                   void *stream) {
+    (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !kv || kv->ctx != ctx || !k_new || !v_new || !k_new->dev || !v_new->dev) return CM_E_INVAL;
     if (k_new->ncomp != 2 || v_new->ncomp != 2) return CM_E_INVAL;
     const int lv = kv->level + 1;
@@ -219,7 +220,7 @@ extern "C" cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, con
     kv->ntok++;
     kv->scale = k_new->scale * (double)ctx->mod[lv] / (double)ctx->mod[lv];
     kv->scale_set = true;
-    return CM_OK;
+    RETURN_LAUNCH_STATUS();
 }
 
 static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st) {
@@ -288,7 +289,7 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     CMCHK(rescale_into(ctx, acc, 2, lv - 1, out->dev, st));
     out->level = lv - 2, out->ncomp = 2;
     out->scale = in->scale * kv->scale / (double)ctx->mod[lv];      // the mask scale cancels the second rescale
-    return CM_OK;
+    RETURN_LAUNCH_STATUS();
 }
 
 static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st) {
@@ -338,11 +339,12 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     HIPCHK(hipMemcpyAsync(out->dev, R, 2 * (size_t)lv * n * 8, hipMemcpyDeviceToDevice, st));
     out->level = lv - 1, out->ncomp = 2;
     out->scale = in->scale * kv->scale / (double)ctx->mod[lv];
-    return CM_OK;
+    RETURN_LAUNCH_STATUS();
 }
 
 extern "C" cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t which, const cm_ct *in,
                                cm_ct *out, void *stream) {
+    (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !kv || kv->ctx != ctx || !in || !in->dev || !out || !out->dev || in->ncomp != 2) return CM_E_INVAL;
     if (in->level != kv->level) return CM_E_LEVEL;
     if (which == CM_QK) return kv_qk(ctx, evk, kv, in, out, (hipStream_t)stream);

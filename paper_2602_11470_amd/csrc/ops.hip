@@ -368,6 +368,7 @@ const u64 *find_key(const cm_evk *evk, u64 g) {
 
 extern "C" cm_status cm_keyswitch(cm_ctx *ctx, const cm_evk *evk, int32_t step, int32_t relin, const uint64_t *d,
                                   int32_t level, uint64_t *ks0, uint64_t *ks1, void *stream) {
+    (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !d || !ks0 || !ks1 || level < 0 || level > ctx->L) return CM_E_INVAL;
     hipStream_t st = (hipStream_t)stream;
     const u64 *key = find_key(evk, relin ? 0 : galois_of_step(ctx, step));
@@ -378,7 +379,7 @@ extern "C" cm_status cm_keyswitch(cm_ctx *ctx, const cm_evk *evk, int32_t step, 
     size_t bytes = (size_t)(level + 1) * ctx->n * 8;
     HIPCHK(hipMemcpyAsync(ks0, A.tmp[0], bytes, hipMemcpyDeviceToDevice, st));
     HIPCHK(hipMemcpyAsync(ks1, A.tmp[0] + (size_t)(level + 1) * ctx->n, bytes, hipMemcpyDeviceToDevice, st));
-    return CM_OK;
+    RETURN_LAUNCH_STATUS();
 }
 
 extern "C" cm_status cm_ntt(cm_ctx *ctx, uint64_t *dev, const int32_t *mod_idx, int32_t limbs, int32_t inverse, void *stream) {
@@ -722,6 +723,7 @@ cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64
     return moddown_into(ctx, A.u, level, in, 1, g, out, accum, st);
 }
 extern "C" cm_status cm_rotate(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, int32_t step, cm_ct *out, void *stream) {
+    (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !ct_ok(ctx, in) || in->ncomp != 2 || !out || !out->dev) return CM_E_INVAL;
     hipStream_t st = (hipStream_t)stream;
     const u64 g = galois_of_step(ctx, step);
@@ -740,10 +742,11 @@ extern "C" cm_status cm_rotate(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, 
         }
     }
     out->level = in->level, out->ncomp = 2, out->scale = in->scale;
-    return CM_OK;
+    RETURN_LAUNCH_STATUS();
 }
 extern "C" cm_status cm_rotate_hoisted(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, const int32_t *steps,
                                        size_t nsteps, cm_ct *outs, void *stream) {
+    (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !ct_ok(ctx, in) || in->ncomp != 2 || !steps || !outs) return CM_E_INVAL;
     hipStream_t st = (hipStream_t)stream;
     for (size_t i = 0; i < nsteps; i++) {
@@ -767,5 +770,5 @@ extern "C" cm_status cm_rotate_hoisted(cm_ctx *ctx, const cm_evk *evk, const cm_
         outs[i].level = in->level, outs[i].ncomp = 2, outs[i].scale = in->scale;
     }
     CMCHK(ks_apply_many(ctx, A.digits, in->level, (int)keys.size(), keys.data(), gs.data(), in->dev, dst.data(), st));
-    return CM_OK;
+    RETURN_LAUNCH_STATUS();
 }

@@ -89,6 +89,7 @@ extern "C" int32_t cm_rope_steps(const cm_rope *r, int32_t *steps, int32_t cap) 
     return 2;
 }
 extern "C" cm_status cm_rope_apply(cm_ctx *ctx, const cm_evk *evk, const cm_rope *r, const cm_ct *x, cm_ct *y, void *stream) {
+    (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !r || r->ctx != ctx || !x || !x->dev || x->ncomp != 2 || !y || !y->dev || y->dev == x->dev)
         return CM_E_INVAL;
     if (x->level != r->level) return CM_E_LEVEL;
@@ -106,5 +107,5 @@ extern "C" cm_status cm_rope_apply(cm_ctx *ctx, const cm_evk *evk, const cm_rope
     CMCHK(rescale_into(ctx, a, 2, level, y->dev, st));
     y->level = level - 1, y->ncomp = 2;
     y->scale = x->scale;                                          // plaintext scale = the prime just removed
-    return CM_OK;
+    RETURN_LAUNCH_STATUS();
 }

@@ -313,7 +313,7 @@ static cm_status vmm_raised_finish(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_
     CMCHK(rescale_into(ctx, acc, 2, level, y->dev, st));
     y->level = level - 1, y->ncomp = 2;
     y->scale = x->scale * p->pt_scale / (double)ctx->mod[level];
-    return CM_OK;
+    RETURN_LAUNCH_STATUS();
 }
 static cm_status vmm_pt_raised(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const cm_ct *x, cm_ct *y,
                                hipStream_t st) {
@@ -333,6 +333,7 @@ static cm_status plan_keys_present(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_
 
 extern "C" cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *const *plans, int32_t nplans,
                                      const cm_ct *x, cm_ct *const *ys, void *stream) {
+    (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !plans || nplans < 1 || !x || !x->dev || x->ncomp != 2 || !ys) return CM_E_INVAL;
     const cm_vmm_plan *p0 = plans[0];
     for (int i = 0; i < nplans; i++) {
@@ -353,6 +354,7 @@ extern "C" cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vm
 
 extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const cm_ct *x, cm_ct *y,
                                void *stream) {
+    (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !p || !x || !x->dev || !y || !y->dev || x->ncomp != 2 || p->ctx != ctx) return CM_E_INVAL;
     if (x->level != p->level) return CM_E_LEVEL;
     hipStream_t st = (hipStream_t)stream;
@@ -405,5 +407,5 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     CMCHK(rescale_into(ctx, acc, 2, level, y->dev, st));
     y->level = level - 1, y->ncomp = 2;
     y->scale = x->scale * p->pt_scale / (double)ctx->mod[level];
-    return CM_OK;
+    RETURN_LAUNCH_STATUS();
 }
