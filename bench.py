@@ -385,6 +385,8 @@ def main():
         "config": {"workload": "config2: encrypted 4096-vector x plaintext 4096x4096, interleaved replicated "
                                "packing, BSGS 32x16, 52 rotations, 512 pt-ct MACs", "ring_degree": n,
                    "baby_step_sums": "plain" if a.plain_sums else "extended basis",
+                   "giant_steps": "nested (one key)" if (a.plain_sums or a.nested_giants) else "unrolled (one key per step)",
+                   "rotation_keys": len(set(g["plan"].steps())),
                    "ciphertext_primes": limbs, "special_primes": K, "dnum": beta, "level": limbs - 1},
         "max_abs_err_vs_float64": err,
         "key_switches_per_s": 1.0 / t_rot, "key_switch_us": t_rot * 1e6,
