@@ -217,7 +217,7 @@ __device__ __forceinline__ void cols_fwd_body(u64 *lds, u64 *p, const u64 *ps, c
     const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
     typename A::T v[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = ar.from_rest(ps[(size_t)(sub + 16 * k) * n2 + c]);
+    for (int k = 0; k < 16; k++) v[k] = ar.from_rest(ps[(unsigned)((sub + 16 * k) * n2 + c)]);
     radix16_fwd(v, ar, 1);
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[pad((sub + 16 * k) * 16 + c)] = ar.to_mid(v[k]);
@@ -226,7 +226,7 @@ __device__ __forceinline__ void cols_fwd_body(u64 *lds, u64 *p, const u64 *ps, c
     for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad((16 * sub + k) * 16 + c)]);
     radix16_fwd(v, ar, 16 + sub);
 #pragma unroll
-    for (int k = 0; k < 16; k++) p[(size_t)(16 * sub + k) * n2 + c] = ar.to_mid(v[k]);
+    for (int k = 0; k < 16; k++) p[(unsigned)((16 * sub + k) * n2 + c)] = ar.to_mid(v[k]);
 }
 template <class A>
 __device__ __forceinline__ void cols_inv_body(u64 *lds, u64 *p, const NttTables &t, int mi, int n, int n2) {
@@ -235,7 +235,7 @@ __device__ __forceinline__ void cols_inv_body(u64 *lds, u64 *p, const NttTables 
     const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
     typename A::T v[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(p[(size_t)(16 * sub + k) * n2 + c]);
+    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(p[(unsigned)((16 * sub + k) * n2 + c)]);
     radix16_inv(v, ar, 16 + sub);
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[pad((16 * sub + k) * 16 + c)] = ar.to_mid(v[k]);
@@ -244,7 +244,7 @@ __device__ __forceinline__ void cols_inv_body(u64 *lds, u64 *p, const NttTables 
     for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad((sub + 16 * k) * 16 + c)]);
     radix16_inv(v, ar, 1);
 #pragma unroll
-    for (int k = 0; k < 16; k++) p[(size_t)(sub + 16 * k) * n2 + c] = ar.to_rest_inv(v[k]);
+    for (int k = 0; k < 16; k++) p[(unsigned)((sub + 16 * k) * n2 + c)] = ar.to_rest_inv(v[k]);
 }
 
 // grid.x = limbs * (n2/16)
