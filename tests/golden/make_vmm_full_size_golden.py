@@ -1,5 +1,5 @@
-"""Writes tests/golden/vmm_full_size.txt (and, with the argument `raised`,
-tests/golden/vmm_full_size_raised.txt) by running ONLY the oracle.
+"""Writes tests/golden/vmm_full_size.txt (with the argument `raised`: vmm_full_size_raised.txt; with
+`direct`: vmm_full_size_direct.txt) by running ONLY the oracle.
 
 Full-size parity case of the packed product: ring n = 2^16 with 24 x 50-bit + 4 x 60-bit primes
 (benchmark configuration 2), d = 4096 square plan (32 baby x 16 giant steps, 52 rotations, 512
@@ -11,6 +11,7 @@ The fixture stores a SHA-256 of the canonical output ciphertext and the first co
 every limb.  Run from the repository root:
     python tests/golden/make_vmm_full_size_golden.py            (Algorithm 1 as printed)
     python tests/golden/make_vmm_full_size_golden.py raised     (baby-step sums kept in the extended basis)
+    python tests/golden/make_vmm_full_size_golden.py direct     (that, with the giant steps unrolled)
 (about ten minutes each on 8 cores, ~20 GiB of memory).
 """
 import hashlib
@@ -37,30 +38,35 @@ def integer_inputs(n, plan):
     return xc, diag
 
 
-def main(raised=False):
+def main(form="plain"):
+    raised, direct = form in ("raised", "direct"), form == "direct"
     t0 = time.time()
     prm = params.config2()
     ctx = ckks.Context(prm)
     plan = packing.make_plan(ctx.S, D, D)
     xc, diag = integer_inputs(ctx.n, plan)
     sk = ctx.keygen_secret(SEED_SK)
-    keys = ctx.keygen_rotations(sk, plan.all_steps(), SEED_EVK)
+    keys = ctx.keygen_rotations(sk, vmm.direct_giant_steps(plan) if direct else plan.all_steps(), SEED_EVK)
     print("keys", len(keys), time.time() - t0, flush=True)
     ct = ctx.encrypt(sk, ctx.pt_from_coeffs(xc, prm.L, prm.scale), SEED_ENC)
     make_pt = ctx.pt_from_coeffs_ext if raised else ctx.pt_from_coeffs
     pts = [[make_pt(diag[j * plan.r_o + k], prm.L, prm.scale) for k in range(plan.r_o)] for j in range(plan.r_i)]
     print("plaintexts", time.time() - t0, flush=True)
-    if raised:
+    if direct:
+        y = vmm.vmm_pt_direct_giants(ctx, keys, plan, ct, pts)
+    elif raised:
         y = vmm.vmm_pt_double_hoisted(ctx, keys, plan, ct, pts)
     else:
         y = vmm.vmm_pt(vmm.CkksOps(ctx, keys), plan, ct, pts)
     can = ctx.canonical(y)
     print("vmm", time.time() - t0, ctx.rot_count, ctx.ptmul_count, flush=True)
-    out = os.path.join(ROOT, "tests", "golden", "vmm_full_size_raised.txt" if raised else "vmm_full_size.txt")
+    out = os.path.join(ROOT, "tests", "golden", {"plain": "vmm_full_size.txt", "raised": "vmm_full_size_raised.txt",
+                                                  "direct": "vmm_full_size_direct.txt"}[form])
     with open(out, "w") as f:
         f.write("# Oracle output of the full-size packed product (Algorithm 1 of App. C at the Table 2 shape\n"
                 "# (S, d) = (32768, 4096)) on integer plaintexts; written by make_vmm_full_size_golden.py"
-                + (" raised\n# (sums of the baby steps kept in the extended basis).\n" if raised else ".\n"))
+                + (f" {form}\n# (sums of the baby steps kept in the extended basis"
+                   + (", giant steps unrolled" if direct else "") + ").\n" if raised else ".\n"))
         f.write(f"shape: {' '.join(map(str, can.shape))}\n")
         f.write(f"level: {y.level}\n")
         f.write(f"rotations: {ctx.rot_count}\n")
@@ -73,4 +79,4 @@ def main(raised=False):
 
 
 if __name__ == "__main__":
-    main(raised=len(sys.argv) > 1 and sys.argv[1] == "raised")
+    main(sys.argv[1] if len(sys.argv) > 1 else "plain")

@@ -69,8 +69,8 @@ def test_config2_chain_keys_and_single_operations(ring2):
     assert np.abs(gctx.decrypt(gsk, gm).real - z * z).max() < 1e-6
 
 
-@pytest.mark.parametrize("raised", [False, True])
-def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden, raised):
+@pytest.mark.parametrize("form", ["plain", "raised", "direct"])
+def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden, form):
     """52 rotations, 512 plaintext multiply-accumulates at (S, d) = (32768, 4096); the expected
     ciphertext was written by tests/golden/make_vmm_full_size_golden.py from the oracle, for the
     algorithm as printed and for the form that keeps the baby-step sums in the extended basis
@@ -78,7 +78,8 @@ def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden,
     import importlib.util
     import os
     B, octx, gctx, prm = ring2
-    g = golden("vmm_full_size_raised.txt" if raised else "vmm_full_size.txt")
+    raised, direct = form != "plain", form == "direct"
+    g = golden({"plain": "vmm_full_size.txt", "raised": "vmm_full_size_raised.txt", "direct": "vmm_full_size_direct.txt"}[form])
     spec = importlib.util.spec_from_file_location(
         "mk", os.path.join(os.path.dirname(__file__), "golden", "make_vmm_full_size_golden.py"))
     mk = importlib.util.module_from_spec(spec)
@@ -87,7 +88,7 @@ def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden,
     plan = packing.make_plan(octx.S, mk.D, mk.D)
     xc, diag = mk.integer_inputs(octx.n, plan)
     gplan = gctx.vmm_plan(mk.D, mk.D, level=prm.L, r_i=plan.r_i, coeffs=np.stack(diag), pt_scale=prm.scale,
-                          raised_sums=raised)
+                          raised_sums=raised, direct_giants=direct)
     assert gplan.n_rotations == int(g["rotations"]) == 52 and gplan.r_i * gplan.r_o == int(g["pt_mults"]) == 512
     gsk = gctx.keygen_secret(mk.SEED_SK)
     gkeys = gctx.keygen_rotations(gsk, gplan.steps(), mk.SEED_EVK)
