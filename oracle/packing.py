@@ -16,7 +16,13 @@ Readings taken where the printed algorithm and the text disagree:
   * rotation amounts printed as j t' and t r_i count blocks; in slots they are j t' t and
     r_i t' t, and r_o = d / (t' r_i), the only choice with r_i r_o t' = d;
   * the weight plaintexts are built by pushing index labels through the same rotations
-    instead of using the printed closed forms.
+    instead of using the printed closed forms;
+  * token-batched products (Sec. 5.4, the prompt phase): the text only says that a ciphertext
+    "holds t tokens without preprocessing".  Read as: residue tau of block b holds element b of
+    token tau, the preprocess and reduce steps disappear, and the product is the diagonal
+    method over all d diagonals with every rotation a whole number of blocks (baby step j t,
+    giant step r_i t), each weight diagonal repeated over the residues.  Square shapes only: a
+    wider or taller matrix is a set of square ones.
 """
 from dataclasses import dataclass
 from typing import List
@@ -37,6 +43,7 @@ class VmmPlan:
     mode: str       # "square" (d->d), "expand" (d -> alpha d), "contract" (alpha d -> d)
     r_i: int
     tau: int = 0    # residue the valid output lands on (0 unless preparing a cache append)
+    tokens: bool = False   # token-batched: residue tau holds token tau, t tokens per ciphertext
 
     def __post_init__(self):
         self.t = self.S // self.d
@@ -45,6 +52,10 @@ class VmmPlan:
         assert self.mode in ("square", "expand", "contract")
         assert (self.alpha == 1) == (self.mode == "square")
         self.t1, self.t2 = (self.tp, self.t) if self.mode == "contract" else (self.t, self.tp)
+        if self.tokens:
+            # nothing is replicated or summed inside a block; rotations move whole blocks
+            assert self.mode == "square"
+            self.tp = self.t1 = self.t2 = 1
         self.M = self.d // self.tp                      # number of diagonals
         assert self.M >= 1 and self.M % self.r_i == 0
         self.r_o = self.M // self.r_i
@@ -106,8 +117,20 @@ class VmmPlan:
         m[[self.out_slot(c) for c in range(self.d_out)]] = 1.0
         return m
 
+    def pack_tokens(self, X):
+        """Token-batched input: X[tau, b] at slot b*t + tau."""
+        X = np.asarray(X)
+        assert self.tokens and X.shape == (self.t, self.d)
+        return X.T.reshape(-1).copy()
+
+    def unpack_tokens(self, slots):
+        return np.asarray(slots).reshape(self.d, self.t).T
+
     def block_col(self):
-        """Output index owned by each block of t2 consecutive slots."""
+        """Output index owned by each block of t2 consecutive slots (of t slots when
+        token-batched)."""
+        if self.tokens:
+            return np.arange(self.d)
         B = np.arange(self.S // self.t2)
         if self.mode == "expand":
             return B // self.alpha + (B % self.alpha) * self.d
@@ -116,6 +139,8 @@ class VmmPlan:
     def source_labels(self):
         """Input index held by every slot after the preprocess step (labels pushed through
         the same rotate-and-add; two labelled slots never meet)."""
+        if self.tokens:
+            return np.arange(self.S) // self.t
         lab = np.full(self.S, -1, dtype=np.int64)
         for a in range(self.d_in):
             lab[self.in_slot(a)] = a
@@ -138,7 +163,7 @@ class VmmPlan:
         for j in range(self.r_i):
             row = np.roll(lab, -self.baby_steps[j])
             for k in range(self.r_o):
-                col = col_of_block[((i - k * self.giant_step) % S) // self.t2]
+                col = col_of_block[((i - k * self.giant_step) % S) // (self.t if self.tokens else self.t2)]
                 out[j][k] = W[row, col]
         return out
 
@@ -148,7 +173,10 @@ def default_r_i(M):
     return 1 << ((_log2(M) + 1) // 2)
 
 
-def make_plan(S, d_in, d_out, r_i=None, tau=0):
+def make_plan(S, d_in, d_out, r_i=None, tau=0, tokens=False):
+    if tokens:
+        assert d_in == d_out
+        return VmmPlan(S, d_in, 1, "square", default_r_i(d_in) if r_i is None else r_i, 0, True)
     if d_in == d_out:
         d, alpha, mode = d_in, 1, "square"
     elif d_out > d_in:
@@ -221,6 +249,12 @@ class KvLayout:
                     p2[i] = -np.sin(th)
         return p0, p1, p2
 
+    def rope_plaintexts_group(self, c, base=10000.0):
+        """The same for a ciphertext that holds the t tokens c*t .. c*t + t-1, token c*t + tau at
+        residue tau (the prompt phase, Sec. 5.4): every residue gets the angles of its own token."""
+        ps = [self.rope_plaintexts(c * self.t + tau, tau, base) for tau in range(self.t)]
+        return tuple(sum(p[i] for p in ps) for i in range(3))
+
     @property
     def rope_step(self):
         return self.H * self.t
@@ -281,6 +315,11 @@ class KvLayout:
         for h in range(self.H):
             m[self.slot((c - k) % self.E, h, tau)] = 1.0
         return np.roll(m, self.v_shift(k))
+
+    def v_append_group_mask(self, k, c):
+        """Slots of stored V ciphertext k that the t tokens of group c occupy (Sec. 5.4: the
+        masked products of the V-cache update, all residues at once): block row e = (c - k) mod E."""
+        return sum(self.v_append_mask(k, c * self.t + tau) for tau in range(self.t))
 
     def qk_steps(self):
         return [-(1 << i) for i in range(_log2(self.t))] + \

@@ -229,3 +229,17 @@ def kv_append(ops, lay: KvLayout, k_cts, v_cts, n, ck_new, cv_new, k_mask, v_mas
     for k in range(lay.E):
         vnew = ops.rescale(ops.mul_pt(shifted[k // lay.r_i], v_masks[k]))
         v_cts[k] = vnew if v_cts[k] is None else ops.add(v_cts[k], vnew)
+
+
+def kv_append_group(ops, lay: KvLayout, k_cts, v_cts, c, ck_grp, cv_grp, k_mask, v_masks):
+    """Sec. 5.4, cache generation in the prompt phase: the t tokens c*t .. c*t + t-1 at once.
+    ck_grp / cv_grp hold token c*t + tau at residue tau of every (e, h) block, which is already
+    the layout of K ciphertext c; k_mask is all ones (the product only keeps levels and scales
+    equal to the one-token update), v_masks[k] = lay.v_append_group_mask(k, c)."""
+    assert c == len(k_cts)
+    k_cts.append(ops.rescale(ops.mul_pt(ck_grp, k_mask)))
+    shifted = [cv_grp] + [ops.rotate(cv_grp, -(g * lay.r_i * lay.H * lay.t))
+                          for g in range(1, lay.r_o)]
+    for k in range(lay.E):
+        vnew = ops.rescale(ops.mul_pt(shifted[k // lay.r_i], v_masks[k]))
+        v_cts[k] = vnew if v_cts[k] is None else ops.add(v_cts[k], vnew)

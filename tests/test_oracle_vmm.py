@@ -237,3 +237,100 @@ def test_rope_on_ciphertexts_decrypts_to_the_rotation():
     out = ctx.decrypt(sk, y).real
     assert np.abs(lay.unpack_vec(out, 2) - _rope_reference(v, 77)).max() < 1e-6
     assert np.abs(out).max() < 10 and np.abs(out[1::lay.t]).max() < 1e-6      # residue 1 was garbage, now clean
+
+
+# ---- the prompt phase (Sec. 5.4): t tokens per ciphertext, cache generation by token group ----------
+@pytest.mark.parametrize("d,r_i", [(16, None), (16, 1), (16, 16), (64, None), (8, 2)])
+def test_token_batched_product_on_slots_is_X_times_W(d, r_i):
+    """Every residue of a block carries its own token, so one product gives the t rows of X W;
+    r_i + r_o - 2 block rotations, d plaintext products, nothing else."""
+    S = 128
+    plan = packing.make_plan(S, d, d, r_i=r_i, tokens=True)
+    assert plan.pre_steps == [] and plan.reduce_steps == [] and plan.M == d and plan.t == S // d
+    assert all(s % plan.t == 0 for s in plan.all_steps())          # whole blocks only
+    rng = np.random.default_rng(d)
+    X, W = rng.normal(size=(plan.t, d)), rng.normal(size=(d, d))
+    ops = vmm.SlotOps()
+    y = vmm.vmm_pt(ops, plan, plan.pack_tokens(X), plan.diagonals(W))
+    assert np.abs(plan.unpack_tokens(y) - X @ W).max() < 1e-12
+    assert ops.rotations == plan.r_i + plan.r_o - 2 and ops.pt_mults == d
+    # layout: token tau of element b at slot b*t + tau
+    assert plan.pack_tokens(X)[5 * plan.t + 1] == X[1, 5]
+    # a permutation matrix moves blocks and leaves the residues alone
+    P = np.roll(np.eye(d), 3, axis=1)                               # y[c] = x[c - 3]
+    y = vmm.vmm_pt(vmm.SlotOps(), plan, plan.pack_tokens(X), plan.diagonals(P))
+    assert np.array_equal(plan.unpack_tokens(y), np.roll(X, 3, axis=1))
+
+
+@pytest.mark.parametrize("form", ["plain", "raised", "direct"])
+def test_token_batched_product_on_ciphertexts_decrypts_to_X_times_W(form):
+    prm, ctx, sk = _toy_ctx()
+    level = 3
+    plan = packing.make_plan(ctx.S, 64, 64, tokens=True)           # t = 4 tokens, r_i = r_o = 8
+    rng = np.random.default_rng(8)
+    X, W = rng.normal(size=(plan.t, 64)) * 0.5, rng.normal(size=(64, 64)) * 0.1
+    steps = sorted(set(vmm.direct_giant_steps(plan)) | set(plan.all_steps()))
+    keys = ctx.keygen_rotations(sk, steps, 2)
+    ct = ctx.level_drop(ctx.encrypt(sk, ctx.encode(plan.pack_tokens(X), prm.L), 3), level)
+    diags = plan.diagonals(W)
+    r0, p0 = ctx.rot_count, ctx.ptmul_count
+    if form == "plain":
+        y = vmm.vmm_pt(vmm.CkksOps(ctx, keys), plan, ct, [[ctx.encode(v, level) for v in row] for row in diags])
+    else:
+        ext = [[ctx.encode_ext(v, level) for v in row] for row in diags]
+        fn = vmm.vmm_pt_double_hoisted if form == "raised" else vmm.vmm_pt_direct_giants
+        y = fn(ctx, keys, plan, ct, ext)
+    assert ctx.rot_count - r0 == 14 and ctx.ptmul_count - p0 == 64
+    assert y.level == level - 1
+    out = ctx.decrypt(sk, y)
+    assert np.abs(plan.unpack_tokens(out.real) - X @ W).max() < TOL
+    assert np.abs(out.imag).max() < TOL
+
+
+@pytest.mark.parametrize("r_i", [0, 4])
+def test_group_append_builds_the_cache_layouts_and_matches_token_by_token(r_i):
+    """Slot level: appending whole groups gives exactly pack_k / pack_v of the plain matrices (the
+    definition of the layouts, Sec. 5.1-5.2), and so does appending the same tokens one by one."""
+    lay = packing.KvLayout(512, 4, 8, r_i)                          # t = 16
+    groups = 3
+    ntok = groups * lay.t
+    rng = np.random.default_rng(r_i)
+    K, V = rng.normal(size=(ntok, 4, 8)), rng.normal(size=(ntok, 4, 8))
+    ops = vmm.SlotOps()
+    kc, vc = [], [None] * lay.E
+    for c in range(groups):
+        kg = sum(lay.pack_vec(K[c * lay.t + tau], tau) for tau in range(lay.t))
+        vg = sum(lay.pack_vec(V[c * lay.t + tau], tau) for tau in range(lay.t))
+        assert np.array_equal(kg, lay.pack_k(K[:(c + 1) * lay.t], c))      # a group IS a K ciphertext
+        r0, p0 = ops.rotations, ops.pt_mults
+        vmm.kv_append_group(ops, lay, kc, vc, c, kg, vg, np.ones(lay.S),
+                            [lay.v_append_group_mask(k, c) for k in range(lay.E)])
+        assert (ops.rotations - r0, ops.pt_mults - p0) == (lay.r_o - 1, lay.E + 1)
+    for c in range(groups):
+        assert np.array_equal(kc[c], lay.pack_k(K, c))
+    for k in range(lay.E):
+        assert np.array_equal(vc[k], lay.pack_v(V, k))
+    k1, v1 = [], [None] * lay.E
+    for n in range(ntok):
+        tau = n % lay.t
+        vmm.kv_append(vmm.SlotOps(), lay, k1, v1, n, lay.pack_vec(K[n], tau), lay.pack_vec(V[n], tau),
+                      lay.residue_mask(tau), [lay.v_append_mask(k, n) for k in range(lay.E)])
+    assert all(np.array_equal(a, b) for a, b in zip(kc, k1))
+    assert all(np.array_equal(a, b) for a, b in zip(vc, v1))
+    # the masks of one group tile the whole ciphertext: every slot is taken by exactly one V ciphertext
+    # (before the stored rotation), because block row e of group c goes to V ciphertext (c - e) mod E
+    tot = sum(np.roll(lay.v_append_group_mask(k, 1), -lay.v_shift(k)) for k in range(lay.E))
+    assert np.array_equal(tot, np.ones(lay.S))
+
+
+def test_group_rope_turns_every_residue_by_its_own_token():
+    lay = packing.KvLayout(512, 4, 8)          # t = 16
+    c = 5
+    rng = np.random.default_rng(4)
+    vs = rng.normal(size=(lay.t, 4, 8))
+    slots = sum(lay.pack_vec(vs[tau], tau) for tau in range(lay.t))
+    ops = vmm.SlotOps()
+    out = vmm.rope(ops, lay, slots, lay.rope_plaintexts_group(c))
+    assert (ops.rotations, ops.pt_mults) == (2, 3)
+    for tau in range(lay.t):
+        assert np.abs(lay.unpack_vec(out, tau) - _rope_reference(vs[tau], c * lay.t + tau)).max() < 1e-12
