@@ -185,8 +185,13 @@ cm_status cm_vmm_plan_create_from_coeffs(cm_ctx *ctx, int32_t d_in, int32_t d_ou
  *     Same number of rotations, but they are independent: their ModUps run as one batch, and all of
  *     them share one ModDown.  Needs the r_o - 1 keys of k G (cm_vmm_plan_steps lists them)
  *     instead of the single key of G.
+ *   CM_VMM_TOKEN_BATCH  the prompt phase (Sec. 5.4): the ciphertext holds t = S/d tokens, element b
+ *     of token tau at slot b*t + tau, and y holds the t rows of X W in the same layout.  No
+ *     preprocess and no reduce rotations; all d diagonals (each repeated over the residues), baby
+ *     step j*t, giant step r_i*t, r_i*r_o = d; d_in == d_out (a wider or taller matrix is a set of
+ *     square ones, cm_vmm_pt_multi shares their baby steps), tau = 0.  Combines with the other two.
  * Unknown flag bits: CM_E_INVAL. */
-enum { CM_VMM_RAISED_SUMS = 1, CM_VMM_DIRECT_GIANTS = 2 };
+enum { CM_VMM_RAISED_SUMS = 1, CM_VMM_DIRECT_GIANTS = 2, CM_VMM_TOKEN_BATCH = 4 };
 cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
                                 int32_t level, double pt_scale, const double *W,
                                 const int64_t *coeffs, uint32_t flags, cm_vmm_plan **out);
@@ -233,12 +238,23 @@ cm_status cm_kv_export(cm_ctx *ctx, const cm_kv *kv, int32_t which, int32_t idx,
  * (host, n of them; encoding scale = the prime the following rescale removes): kind 0 = slots
  * (0, h, tau) for all h, tau, at level-1 (keeps one copy of the replicated scores, Sec. 5.1 step
  * 3); kind 1 = slots of residue 0 at level+1 (K append); kind 2 = slots (0, h, 0) at level+1 (V
- * append, Sec. 5.2).  For callers that need bit-identical plaintexts on two implementations. */
+ * append, Sec. 5.2); kind 3 = every slot and kind 4 = slots (0, h, tau) for all h, tau, both at
+ * level+1 (cm_kv_append_group).  For callers that need bit-identical plaintexts on two
+ * implementations. */
 cm_status cm_kv_set_mask(cm_kv *kv, int32_t kind, const int64_t *coeffs);
 /* Append the next token: k_new / v_new hold the new vectors at residue tau = ntok mod t, one
  * level above the cache; they are masked (one plaintext product each) and added. */
 cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_new,
                        const cm_ct *v_new, void *stream);
+/* Cache generation in the prompt phase (Sec. 5.4): append the next t tokens at once.  k_grp /
+ * v_grp hold token ntok + tau at residue tau of every (e, h) block (what a CM_VMM_TOKEN_BATCH
+ * product with (e, h)-ordered columns, then the rotary embedding with tau = -1, leaves), one level
+ * above the cache; ntok must be a multiple of t (else CM_E_LAYOUT).  k_grp becomes K ciphertext
+ * ntok/t (one product with the all-ones mask keeps level and scale equal to the one-token
+ * append); every V ciphertext takes one block row of v_grp by one masked product, all residues
+ * together.  Same rotation keys as cm_kv_append. */
+cm_status cm_kv_append_group(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_grp,
+                             const cm_ct *v_grp, void *stream);
 /* which = CM_QK: in = query at (e, h, 0) slots, cache level; out = scores, two levels lower.
  * which = CM_SV: in = scores; out = attention output at (e, h, 0), one level lower. */
 cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t which,
@@ -252,7 +268,9 @@ cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t whi
  * level; the plaintexts are encoded at the scale of the prime the rescale removes, so y keeps
  * the scale of x.  coeffs (nullable, host [3][n]): integer coefficients of p0, p1, p2 to use
  * instead of the library's own encoding, for callers that need bit-identical plaintexts on two
- * implementations.  x at `level`, y one level lower; y must not alias x. */
+ * implementations.  x at `level`, y one level lower; y must not alias x.
+ * tau = -1: x holds t tokens, token `token` + r at residue r (the prompt phase, Sec. 5.4), and
+ * every residue is turned by the angles of its own token. */
 typedef struct cm_rope cm_rope;
 cm_status cm_rope_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t level, int32_t token,
                          int32_t tau, double base, const int64_t *coeffs, cm_rope **out);

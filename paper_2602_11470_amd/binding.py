@@ -18,7 +18,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 CM_QK, CM_SV = 0, 1
-CM_VMM_RAISED_SUMS, CM_VMM_DIRECT_GIANTS = 1, 2
+CM_VMM_RAISED_SUMS, CM_VMM_DIRECT_GIANTS, CM_VMM_TOKEN_BATCH = 1, 2, 4
 
 
 class cm_params(C.Structure):
@@ -90,6 +90,7 @@ _SIGS = {
     "cm_kv_export": ([_vp, _vp, _i32, _i32, _vp], _i32),
     "cm_kv_set_mask": ([_vp, _i32, _vp], _i32),
     "cm_kv_append": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
+    "cm_kv_append_group": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_vmm_kv": ([_vp, _vp, _vp, _i32, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_profile_enable": ([_vp, _i32], _i32),
     "cm_profile_get": ([_vp, _i32, _P(_f64), _P(_f64), _P(_f64)], _i32),
@@ -292,9 +293,9 @@ class Context:
         return a.value, b.value, c.value
 
     def vmm_plan(self, d_in, d_out, W=None, level=None, r_i=0, tau=0, pt_scale=0.0, coeffs=None, raised_sums=False,
-                 direct_giants=False):
+                 direct_giants=False, token_batch=False):
         return VmmPlan(self, d_in, d_out, W, self.L if level is None else level, r_i, tau, pt_scale, coeffs,
-                       raised_sums, direct_giants)
+                       raised_sums, direct_giants, token_batch)
 
     def vmm_pt(self, evk, plan, x, out=None):
         out = out or Ct(self, x.level - 1)
@@ -360,11 +361,13 @@ class Evk:
 
 
 class VmmPlan:
-    def __init__(self, ctx, d_in, d_out, W, level, r_i, tau, pt_scale, coeffs, raised_sums=False, direct_giants=False):
+    def __init__(self, ctx, d_in, d_out, W, level, r_i, tau, pt_scale, coeffs, raised_sums=False, direct_giants=False,
+                 token_batch=False):
         self.ctx, self.h, self.level = ctx, _vp(), level
         raised_sums = raised_sums or direct_giants
         self.limbs = level + 1 + (ctx.K if raised_sums else 0)
-        flags = (CM_VMM_RAISED_SUMS if raised_sums else 0) | (CM_VMM_DIRECT_GIANTS if direct_giants else 0)
+        flags = (CM_VMM_RAISED_SUMS if raised_sums else 0) | (CM_VMM_DIRECT_GIANTS if direct_giants else 0) | \
+                (CM_VMM_TOKEN_BATCH if token_batch else 0)
         if coeffs is not None:
             c = _np(coeffs, np.int64)
             _chk(lib.cm_vmm_plan_create_ex(ctx.h, d_in, d_out, r_i, tau, level, pt_scale, None, c.ctypes.data,
@@ -446,6 +449,9 @@ class KvCache:
 
     def append(self, evk, k_new, v_new):
         _chk(lib.cm_kv_append(self.ctx.h, evk.h, self.h, C.byref(k_new.d), C.byref(v_new.d), _stream()))
+
+    def append_group(self, evk, k_grp, v_grp):
+        _chk(lib.cm_kv_append_group(self.ctx.h, evk.h, self.h, C.byref(k_grp.d), C.byref(v_grp.d), _stream()))
 
     def __del__(self):
         if getattr(self, "h", None) and lib is not None:

@@ -24,6 +24,8 @@ struct cm_kv {
     u64 *d_mask_qk = nullptr;               // base: slots (0, h, tau) all h, tau; level-1; multiplier form
     u64 *d_mask_k = nullptr;                // base: slots with residue 0;         level+1
     u64 *d_mask_v = nullptr;                // base: slots (0, h, 0) all h;        level+1
+    u64 *d_mask_kg = nullptr;               // every slot;                         level+1  (token-group append)
+    u64 *d_mask_vg = nullptr;               // base: slots (0, h, tau) all h, tau; level+1  (token-group append)
     u64 *d_work = nullptr;
     size_t work_words = 0;
     // query-times-K runs CM_KS_BATCH key ciphertexts at a time: tables for raising the third
@@ -45,10 +47,12 @@ static cm_status encode_mask(cm_kv *kv, int kind, u64 *dst, int level, const int
     const double scale = (double)ctx->mod[level];
     if (coeffs_or_null) return cm_pt_from_coeffs(ctx, coeffs_or_null, level, scale, &pt);
     std::vector<double> m(kv->S, 0.0);
-    if (kind == 0)
+    if (kind == 0 || kind == 4)
         for (int i = 0; i < kv->H * kv->t; i++) m[i] = 1.0;
     else if (kind == 1)
         for (int i = 0; i < kv->S; i += kv->t) m[i] = 1.0;
+    else if (kind == 3)
+        m.assign(kv->S, 1.0);
     else
         for (int h = 0; h < kv->H; h++) m[h * kv->t] = 1.0;
     return cm_encode(ctx, m.data(), nullptr, m.size(), level, scale, &pt);
@@ -88,6 +92,8 @@ extern "C" cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32
               hipMalloc((void **)&kv->d_mask_qk, (size_t)level * n * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_mask_k, (size_t)(level + 2) * n * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_mask_v, (size_t)(level + 2) * n * 8) == hipSuccess &&
+              hipMalloc((void **)&kv->d_mask_kg, (size_t)(level + 2) * n * 8) == hipSuccess &&
+              hipMalloc((void **)&kv->d_mask_vg, (size_t)(level + 2) * n * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_work, kv->work_words * 8) == hipSuccess;
     if (ok) ok = ks_many_tables_create(ctx, level, CM_KS_BATCH, &kv->relin_tabs, 3, 2) == CM_OK &&
                  ks_many_tables_create(ctx, level - 1, CM_KS_BATCH, &kv->rot_tabs, 2, 1) == CM_OK;
@@ -98,6 +104,8 @@ extern "C" cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32
     if (s == CM_OK && level + 1 <= ctx->L) {
         s = encode_mask(kv, 1, kv->d_mask_k, level + 1, nullptr);
         if (s == CM_OK) s = encode_mask(kv, 2, kv->d_mask_v, level + 1, nullptr);
+        if (s == CM_OK) s = encode_mask(kv, 3, kv->d_mask_kg, level + 1, nullptr);
+        if (s == CM_OK) s = encode_mask(kv, 4, kv->d_mask_vg, level + 1, nullptr);
     }
     if (s != CM_OK) { cm_kv_destroy(kv); return s; }
     *out = kv;
@@ -106,17 +114,20 @@ extern "C" cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32
 extern "C" void cm_kv_destroy(cm_kv *kv) {
     if (!kv) return;
     hipFree(kv->d_k), hipFree(kv->d_v), hipFree(kv->d_mask_qk), hipFree(kv->d_mask_k), hipFree(kv->d_mask_v);
+    hipFree(kv->d_mask_kg), hipFree(kv->d_mask_vg);
     hipFree(kv->d_work);
     ks_many_tables_destroy(&kv->relin_tabs);
     ks_many_tables_destroy(&kv->rot_tabs);
     delete kv;
 }
 // Parity hook: replace a base mask by given integer coefficients (kind 0: query-times-K mask at
-// level-1; 1: residue mask at level+1; 2: value mask at level+1), host coeffs[n].
+// level-1; 1: residue mask at level+1; 2: value mask at level+1; 3 and 4: the all-ones and value
+// masks of the token-group append at level+1), host coeffs[n].
 extern "C" cm_status cm_kv_set_mask(cm_kv *kv, int32_t kind, const int64_t *coeffs) {
-    if (!kv || !coeffs || kind < 0 || kind > 2) return CM_E_INVAL;
+    if (!kv || !coeffs || kind < 0 || kind > 4) return CM_E_INVAL;
     if (kind > 0 && kv->level + 1 > kv->ctx->L) return CM_E_LEVEL;
-    u64 *dst = kind == 0 ? kv->d_mask_qk : kind == 1 ? kv->d_mask_k : kv->d_mask_v;
+    u64 *dst = kind == 0 ? kv->d_mask_qk : kind == 1 ? kv->d_mask_k : kind == 2 ? kv->d_mask_v
+             : kind == 3 ? kv->d_mask_kg : kv->d_mask_vg;
     return encode_mask(kv, kind, dst, kind == 0 ? kv->level - 1 : kv->level + 1, coeffs);
 }
 
@@ -169,14 +180,18 @@ static u64 rot_g(const cm_kv *kv, long long step) {
     return galois_of_step(kv->ctx, (int)(((step % S) + S) % S));
 }
 
-extern "C" cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_new, const cm_ct *v_new,
-                                  void *stream) {
+// One token (k_new / v_new hold it at residue ntok mod t), or, group = true, the t tokens of the
+// next K ciphertext at once (Sec. 5.4: token c*t + tau at residue tau, which is already the layout
+// of K ciphertext c; the V masks take whole block rows, all residues together).
+static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_new, const cm_ct *v_new,
+                           bool group, void *stream) {
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !kv || kv->ctx != ctx || !k_new || !v_new || !k_new->dev || !v_new->dev) return CM_E_INVAL;
     if (k_new->ncomp != 2 || v_new->ncomp != 2) return CM_E_INVAL;
     const int lv = kv->level + 1;
     if (lv > ctx->L || k_new->level != lv || v_new->level != lv) return CM_E_LEVEL;
     if (kv->ntok >= kv->max_tokens) return CM_E_LAYOUT;
+    if (group && (kv->ntok % kv->t || kv->ntok + kv->t > kv->max_tokens)) return CM_E_LAYOUT;
     if (kv->scale_set && (fabs(k_new->scale / kv->scale - 1) > 1e-9 || fabs(v_new->scale / kv->scale - 1) > 1e-9))
         return CM_E_SCALE;
     if (fabs(k_new->scale / v_new->scale - 1) > 1e-9) return CM_E_SCALE;
@@ -186,9 +201,9 @@ extern "C" cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, con
     const size_t n = ctx->n, ctw_up = 2 * (size_t)(lv + 1) * n, ctw = kv_ctw(kv);
     const int tok = kv->ntok, c = tok / kv->t, tau = tok % kv->t;
     u64 *mask = kv->d_work, *prod = mask + (size_t)(lv + 1) * n, *res = prod + ctw_up, *shifted = res + ctw_up;
-    // K: K_c += rescale(k_new * mask_tau), mask_tau = residue-0 mask rotated right by tau
-    launch_automorphism(ctx, mask, kv->d_mask_k, lv + 1, rot_g(kv, -tau), st);
-    launch_mul_pt(ctx, prod, k_new->dev, mask, 2, lv + 1, st);
+    // K: K_c += rescale(k_new * mask_tau), mask_tau = residue-0 mask rotated right by tau (a group: all ones)
+    if (!group) launch_automorphism(ctx, mask, kv->d_mask_k, lv + 1, rot_g(kv, -tau), st);
+    launch_mul_pt(ctx, prod, k_new->dev, group ? kv->d_mask_kg : mask, 2, lv + 1, st);
     CMCHK(rescale_into(ctx, prod, 2, lv, res, st));
     u64 *kc = kv->d_k + (size_t)c * ctw;
     launch_add(ctx, kc, kc, res, 2, kv->level + 1, st);
@@ -212,15 +227,23 @@ extern "C" cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, con
             mb.src[r] = g == 0 ? v_new->dev : shifted + (size_t)(g - 1) * ctw_up;
             mb.g[r] = (unsigned)rot_g(kv, -a);
         }
-        launch_mul_pt_rot_batch(ctx, prods, mb, m, kv->d_mask_v, lv + 1, st);
+        launch_mul_pt_rot_batch(ctx, prods, mb, m, group ? kv->d_mask_vg : kv->d_mask_v, lv + 1, st);
         CMCHK(rescale_into(ctx, prods, 2 * m, lv, ress, st, last, red));
         u64 *vk = kv->d_v + (size_t)kb * ctw;
         launch_add(ctx, vk, vk, ress, 2 * m, kv->level + 1, st);
     }
-    kv->ntok++;
+    kv->ntok += group ? kv->t : 1;
     kv->scale = k_new->scale * (double)ctx->mod[lv] / (double)ctx->mod[lv];
     kv->scale_set = true;
     RETURN_LAUNCH_STATUS();
+}
+extern "C" cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_new, const cm_ct *v_new,
+                                  void *stream) {
+    return kv_append(ctx, evk, kv, k_new, v_new, false, stream);
+}
+extern "C" cm_status cm_kv_append_group(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_grp,
+                                        const cm_ct *v_grp, void *stream) {
+    return kv_append(ctx, evk, kv, k_grp, v_grp, true, stream);
 }
 
 static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st) {

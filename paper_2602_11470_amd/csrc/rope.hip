@@ -44,7 +44,7 @@ extern "C" cm_status cm_rope_create(cm_ctx *ctx, int32_t heads, int32_t dim, int
     const int S = ctx->n / 2;
     if (!pow2(heads) || !pow2(dim) || heads * dim > S) return CM_E_LAYOUT;
     const int t = S / (heads * dim);
-    if (tau < 0 || tau >= t) return CM_E_LAYOUT;
+    if (tau < -1 || tau >= t) return CM_E_LAYOUT;
     cm_rope *r = new (std::nothrow) cm_rope();
     if (!r) return CM_E_NOMEM;
     r->ctx = ctx, r->S = S, r->H = heads, r->E = dim, r->t = t, r->level = level, r->token = token, r->tau = tau, r->base = base;
@@ -57,15 +57,17 @@ extern "C" cm_status cm_rope_create(cm_ctx *ctx, int32_t heads, int32_t dim, int
     cm_status s = CM_OK;
     std::vector<double> p[3];
     for (auto &v : p) v.assign(S, 0.0);
-    for (int e = 0; e < dim && !coeffs; e++) {
-        const double th = (double)token * pow(base, -2.0 * (double)(e / 2) / (double)dim);
-        for (int h = 0; h < heads; h++) {
-            const size_t i = ((size_t)e * heads + h) * t + tau;
-            p[0][i] = cos(th);
-            if (e % 2 == 0) p[1][i] = sin(th);
-            else p[2][i] = -sin(th);
+    // tau = -1: a group of t tokens, token + r at residue r
+    for (int r0 = (tau < 0 ? 0 : tau); r0 < (tau < 0 ? t : tau + 1) && !coeffs; r0++)
+        for (int e = 0; e < dim; e++) {
+            const double th = (double)(token + (tau < 0 ? r0 : 0)) * pow(base, -2.0 * (double)(e / 2) / (double)dim);
+            for (int h = 0; h < heads; h++) {
+                const size_t i = ((size_t)e * heads + h) * t + r0;
+                p[0][i] = cos(th);
+                if (e % 2 == 0) p[1][i] = sin(th);
+                else p[2][i] = -sin(th);
+            }
         }
-    }
     for (int k = 0; k < 3 && s == CM_OK; k++) {
         cm_pt pt;
         pt.dev = r->d_pts + k * ln, pt.mont = 1;

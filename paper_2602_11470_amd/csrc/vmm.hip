@@ -5,6 +5,11 @@
 // t' = S/(alpha d) for the longer one.  Rotation amounts of the printed algorithm are read in
 // slots as: preprocess 2^i (t-1); baby step j t' t; giant step r_i t' t; reduce 2^l; and
 // r_o = d/(t' r_i), the choice for which r_i r_o t' = d.
+//
+// Token-batched plans (the prompt phase, Sec. 5.4): residue tau of block b holds element b of
+// token tau, so nothing is replicated before and nothing summed after; the product is the
+// diagonal method over all d diagonals, every rotation a whole number of blocks (baby step j t,
+// giant step r_i t), every weight diagonal repeated over the residues.
 #include <math.h>
 
 #include <thread>
@@ -16,6 +21,7 @@ struct cm_vmm_plan {
     cm_ctx *ctx = nullptr;
     int S, d, alpha, t, tp, t1, t2, r_i, r_o, M, tau, d_in, d_out, level;
     bool expand, contract;
+    bool tokens = false;       // token-batched: t tokens per ciphertext, square shapes only
     double pt_scale;
     std::vector<int> pre_steps, baby_steps, reduce_steps;
     int giant_step;
@@ -37,7 +43,7 @@ static int ilog2(int x) {
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 static cm_status plan_shape(cm_ctx *ctx, int d_in, int d_out, int r_i, int tau, int level, double pt_scale,
-                            cm_vmm_plan *p) {
+                            bool tokens, cm_vmm_plan *p) {
     if (d_in < 1 || d_out < 1 || level < 1 || level > ctx->L) return level < 1 ? CM_E_LEVEL : CM_E_INVAL;
     p->ctx = ctx;
     p->S = ctx->n / 2;
@@ -50,6 +56,11 @@ static cm_status plan_shape(cm_ctx *ctx, int d_in, int d_out, int r_i, int tau, 
     p->t = p->S / p->d, p->tp = p->S / big;
     p->t1 = p->contract ? p->tp : p->t;
     p->t2 = p->contract ? p->t : p->tp;
+    p->tokens = tokens;
+    if (tokens) {
+        if (d_in != d_out) return CM_E_LAYOUT;
+        p->tp = p->t1 = p->t2 = 1;          // rotations count blocks of t; no preprocess, no reduce
+    }
     p->M = p->d / p->tp;
     if (p->M < 1) return CM_E_LAYOUT;
     if (r_i == 0) r_i = 1 << ((ilog2(p->M) + 1) / 2);
@@ -75,6 +86,10 @@ static int in_slot(const cm_vmm_plan *p, int a) {
 static std::vector<int> source_labels(const cm_vmm_plan *p) {
     const int S = p->S;
     std::vector<int> lab(S, -1), nxt(S);
+    if (p->tokens) {
+        for (int i = 0; i < S; i++) lab[i] = i / p->t;
+        return lab;
+    }
     for (int a = 0; a < p->d_in; a++) lab[in_slot(p, a)] = a;
     for (int r : p->pre_steps) {
         for (int i = 0; i < S; i++) {
@@ -94,7 +109,7 @@ static void diag_slots(const cm_vmm_plan *p, const std::vector<int> &lab, const 
     out.resize(S);
     for (int i = 0; i < S; i++) {
         int row = lab[(i + p->baby_steps[j]) % S];
-        int blk = (int)((((long long)i - (long long)k * p->giant_step) % S + S) % S) / p->t2;
+        int blk = (int)((((long long)i - (long long)k * p->giant_step) % S + S) % S) / (p->tokens ? p->t : p->t2);
         int col = p->expand ? blk / p->alpha + (blk % p->alpha) * p->d : blk;
         out[i] = W[(size_t)row * p->d_out + col];
     }
@@ -138,12 +153,13 @@ static cm_status plan_load_diag(cm_vmm_plan *p, int idx, const int64_t *coeffs) 
 extern "C" cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
                                            int32_t level, double pt_scale, const double *W, const int64_t *coeffs,
                                            uint32_t flags, cm_vmm_plan **out) {
-    if (!ctx || (!W == !coeffs) || !out || (flags & ~(uint32_t)(CM_VMM_RAISED_SUMS | CM_VMM_DIRECT_GIANTS)))
+    if (!ctx || (!W == !coeffs) || !out ||
+        (flags & ~(uint32_t)(CM_VMM_RAISED_SUMS | CM_VMM_DIRECT_GIANTS | CM_VMM_TOKEN_BATCH)))
         return CM_E_INVAL;
     const bool direct = (flags & CM_VMM_DIRECT_GIANTS) != 0, raised = direct || (flags & CM_VMM_RAISED_SUMS) != 0;
     cm_vmm_plan *p = new (std::nothrow) cm_vmm_plan();
     if (!p) return CM_E_NOMEM;
-    cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, p);
+    cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, (flags & CM_VMM_TOKEN_BATCH) != 0, p);
     if (s == CM_OK) s = plan_alloc(p, raised, direct);
     if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
     if (coeffs) {
@@ -339,7 +355,9 @@ extern "C" cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vm
     for (int i = 0; i < nplans; i++) {
         const cm_vmm_plan *p = plans[i];
         if (!p || p->ctx != ctx || !ys[i] || !ys[i]->dev || !p->raised) return CM_E_INVAL;
-        if (p->level != p0->level || p->d_in != p0->d_in || p->d_out != p0->d_out || p->r_i != p0->r_i) return CM_E_LAYOUT;
+        if (p->level != p0->level || p->d_in != p0->d_in || p->d_out != p0->d_out || p->r_i != p0->r_i ||
+            p->tokens != p0->tokens)
+            return CM_E_LAYOUT;
         for (int j = 0; j < i; j++)
             if (plans[j] == p) return CM_E_INVAL;         // a plan's work area holds one product at a time
         cm_status s = plan_keys_present(ctx, evk, p);

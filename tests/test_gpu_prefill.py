@@ -1,0 +1,211 @@
+"""GPU parity of the prompt phase (Sec. 5.4): the packed product with t tokens per ciphertext,
+the rotary embedding of a token group and cache generation by token group, against the oracle
+limb for limb and against the float64 results within 1e-4."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+CM_E_LAYOUT = -5
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from oracle import ckks, params
+    from paper_2602_11470_amd import binding as B
+    prm = params.config1()
+    octx, gctx = ckks.Context(prm), B.config1()
+    yield dict(B=B, octx=octx, gctx=gctx, osk=octx.keygen_secret(1), gsk=gctx.keygen_secret(1), prm=prm)
+    gctx.close()
+
+
+def _enc_both(e, slots, level, seed, scale=None):
+    octx, gctx = e["octx"], e["gctx"]
+    scale = octx.prm.scale if scale is None else scale
+    coeffs = octx.encode_coeffs(slots, scale)
+    top = octx.prm.L
+    o = octx.level_drop(octx.encrypt(e["osk"], octx.pt_from_coeffs(coeffs, top, scale), seed), level)
+    g = gctx.encrypt(e["gsk"], gctx.pt_from_coeffs(coeffs, top, scale), seed)
+    if level != top:
+        g = gctx.level_drop(g, level)
+    return o, g
+
+
+def _same(e, o, g):
+    assert g.level == o.level and abs(g.scale / o.scale - 1) < 1e-12
+    assert np.array_equal(e["gctx"].ct_export(g), e["octx"].canonical(o))
+
+
+@pytest.mark.parametrize("form", ["plain", "raised", "direct"])
+@pytest.mark.parametrize("d,level,r_i", [(64, 4, 0), (256, 2, 0), (128, 3, 4), (32, 1, 32)])
+def test_token_batched_product_matches_oracle_and_X_times_W(env, form, d, level, r_i):
+    """t = 2048/d tokens in one ciphertext; d diagonals; rotations by whole blocks only."""
+    from oracle import packing, vmm
+    e = env
+    octx, gctx = e["octx"], e["gctx"]
+    plan = packing.make_plan(octx.S, d, d, r_i or None, tokens=True)
+    rng = np.random.default_rng(d + level)
+    X, W = rng.uniform(-1, 1, size=(plan.t, d)), rng.uniform(-1, 1, size=(d, d)) * 0.05
+    scale = octx.prm.scale
+    diag_coeffs = [[octx.encode_coeffs(v, scale) for v in row] for row in plan.diagonals(W)]
+    flat = np.stack([c for row in diag_coeffs for c in row])
+    direct = form == "direct"
+    gplan = gctx.vmm_plan(d, d, level=level, r_i=plan.r_i, coeffs=flat, raised_sums=form != "plain",
+                          direct_giants=direct, token_batch=True)
+    assert (gplan.r_i, gplan.r_o, gplan.n_rotations) == (plan.r_i, plan.r_o, plan.r_i + plan.r_o - 2)
+    steps = vmm.direct_giant_steps(plan) if direct else plan.all_steps()
+    assert sorted(set(gplan.steps())) == sorted(set(steps))
+    okeys = octx.keygen_rotations(e["osk"], steps, 2)
+    gkeys = gctx.keygen_rotations(e["gsk"], gplan.steps(), 2)
+    ox, gx = _enc_both(e, plan.pack_tokens(X), level, 3)
+    if form == "plain":
+        odiags = [[octx.pt_from_coeffs(c, level, scale) for c in row] for row in diag_coeffs]
+        oy = vmm.vmm_pt(vmm.CkksOps(octx, okeys), plan, ox, odiags)
+    else:
+        odiags = [[octx.pt_from_coeffs_ext(c, level, scale) for c in row] for row in diag_coeffs]
+        oy = (vmm.vmm_pt_direct_giants if direct else vmm.vmm_pt_double_hoisted)(octx, okeys, plan, ox, odiags)
+    gy = gctx.vmm_pt(gkeys, gplan, gx)
+    _same(e, oy, gy)
+    out = gctx.decrypt(e["gsk"], gy)
+    assert np.abs(plan.unpack_tokens(out.real) - X @ W).max() < TOL
+    if form == "direct" and d == 64:
+        # the library's own diagonal extraction and encoder
+        gplan2 = gctx.vmm_plan(d, d, W=W, level=level, r_i=plan.r_i, direct_giants=True, token_batch=True)
+        out2 = gctx.decrypt(e["gsk"], gctx.vmm_pt(gkeys, gplan2, gx))
+        assert np.abs(plan.unpack_tokens(out2.real) - X @ W).max() < TOL
+
+
+def test_token_batched_plan_rejects_other_shapes(env):
+    B, gctx = env["B"], env["gctx"]
+    W = np.zeros((64, 128))
+    with pytest.raises(B.CachemirError) as ei:
+        gctx.vmm_plan(64, 128, W=W, level=2, token_batch=True)
+    assert ei.value.status == CM_E_LAYOUT
+    with pytest.raises(B.CachemirError) as ei:
+        gctx.vmm_plan(64, 64, W=np.zeros((64, 64)), level=2, tau=1, token_batch=True)
+    assert ei.value.status == CM_E_LAYOUT
+
+
+def test_group_rope_matches_oracle_and_the_textbook_rotation(env):
+    from oracle import packing, vmm
+    e = env
+    octx, gctx = e["octx"], e["gctx"]
+    H, E, level, c = 16, 16, 3, 5
+    lay = packing.KvLayout(octx.S, H, E)                 # t = 8
+    rng = np.random.default_rng(11)
+    vs = rng.normal(size=(lay.t, H, E))
+    slots = sum(lay.pack_vec(vs[tau], tau) for tau in range(lay.t))
+    steps = [lay.rope_step, -lay.rope_step]
+    okeys = octx.keygen_rotations(e["osk"], steps, 2)
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2)
+    ql = float(octx.mod[level])
+    coeffs = [octx.encode_coeffs(p, ql) for p in lay.rope_plaintexts_group(c)]
+    opts = [octx.pt_from_coeffs(cf, level, ql) for cf in coeffs]
+    rope = gctx.rope(H, E, level, c * lay.t, tau=-1, coeffs=np.stack(coeffs))
+    ox, gx = _enc_both(e, slots, level, 3)
+    oy = vmm.rope(vmm.CkksOps(octx, okeys, pt_scale=ql), lay, ox, opts)
+    gy = gctx.rope_apply(gkeys, rope, gx)
+    _same(e, oy, gy)
+    # the library's own plaintexts: every residue turned by its own token's angles
+    rope2 = gctx.rope(H, E, level, c * lay.t, tau=-1)
+    out = gctx.decrypt(e["gsk"], gctx.rope_apply(gkeys, rope2, gx)).real
+    for tau in (0, 3, lay.t - 1):
+        v, n = vs[tau], c * lay.t + tau
+        want = np.empty_like(v)
+        for m in range(E // 2):
+            th = n * 10000.0 ** (-2.0 * m / E)
+            want[:, 2 * m] = v[:, 2 * m] * np.cos(th) - v[:, 2 * m + 1] * np.sin(th)
+            want[:, 2 * m + 1] = v[:, 2 * m + 1] * np.cos(th) + v[:, 2 * m] * np.sin(th)
+        assert np.abs(lay.unpack_vec(out, tau) - want).max() < TOL
+
+
+@pytest.mark.parametrize("r_i", [0, 4])
+def test_group_append_then_single_tokens_then_attention(env, r_i):
+    """Two whole groups (the prompt), then three tokens one by one (decoding), then q K^T and s V
+    against that cache: every cache ciphertext and both products equal the oracle's."""
+    from oracle import packing, vmm
+    from oracle.ckks import Pt
+    from paper_2602_11470_amd import inputs
+    e = env
+    B, octx, gctx = e["B"], e["octx"], e["gctx"]
+    H, E, L = 16, 16, octx.prm.L
+    lay = packing.KvLayout(octx.S, H, E, r_i)            # t = 8
+    groups, extra = 2, 3
+    ntok = groups * lay.t + extra
+    q, K, V, s = inputs.attention_inputs(9, H, 4, E, ntok)
+    lv = L - 1
+    kv = gctx.kv_create(H, E, lv, r_i=r_i)
+    steps = lay.qk_steps() + lay.sv_steps() + lay.append_steps()
+    okeys = octx.keygen_rotations(e["osk"], steps, 2, with_relin=True)
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2, with_relin=True)
+    ops = vmm.CkksOps(octx, okeys)
+
+    def base(kind, level):
+        m = np.zeros(octx.S)
+        if kind in (0, 4):
+            m[:H * lay.t] = 1
+        elif kind == 1:
+            m[::lay.t] = 1
+        elif kind == 3:
+            m[:] = 1
+        else:
+            m[[h * lay.t for h in range(H)]] = 1
+        return octx.encode_coeffs(m, float(octx.mod[level]))
+
+    bases = {0: base(0, lv - 1), 1: base(1, lv + 1), 2: base(2, lv + 1), 3: base(3, lv + 1), 4: base(4, lv + 1)}
+    for kind, cf in bases.items():
+        kv.set_mask(kind, cf)
+
+    def omask(kind, shift_right, level):
+        idx = octx.q_idx(level)
+        coeff = octx.automorphism_coeff(octx.from_i64(bases[kind], idx), idx, octx.galois(-shift_right))
+        return Pt(octx.ntt(coeff, idx), level, float(octx.mod[level]))
+
+    # the rotated group base is the layout's group mask (checked on decoded slots)
+    m = omask(4, lay.slot(3, 0, 0) + lay.v_shift(5), lv + 1)
+    dec = octx.decode_coeffs(np.array(octx.centred_coeffs(octx.intt(m.m, octx.q_idx(lv + 1)), 1), dtype=float) / m.scale)
+    assert np.abs(dec - lay.v_append_group_mask(5, (3 + 5) % E)).max() < 1e-6
+
+    okc, ovc = [], [None] * E
+    for c in range(groups):
+        kg = sum(lay.pack_vec(K[c * lay.t + tau], tau) for tau in range(lay.t))
+        vg = sum(lay.pack_vec(V[c * lay.t + tau], tau) for tau in range(lay.t))
+        ok_g, gk_g = _enc_both(e, kg, L, 100 + c)
+        ov_g, gv_g = _enc_both(e, vg, L, 500 + c)
+        vmasks = [omask(4, lay.slot((c - k) % E, 0, 0) + lay.v_shift(k), lv + 1) for k in range(E)]
+        vmm.kv_append_group(ops, lay, okc, ovc, c, ok_g, ov_g, omask(3, 0, lv + 1), vmasks)
+        kv.append_group(gkeys, gk_g, gv_g)
+        assert kv.tokens() == (c + 1) * lay.t
+    for n in range(groups * lay.t, ntok):
+        c, tau = n // lay.t, n % lay.t
+        ok_new, gk_new = _enc_both(e, lay.pack_vec(K[n], tau), L, 100 + n)
+        ov_new, gv_new = _enc_both(e, lay.pack_vec(V[n], tau), L, 500 + n)
+        vmasks = [omask(2, lay.slot((c - k) % E, 0, tau) + lay.v_shift(k), lv + 1) for k in range(E)]
+        vmm.kv_append(ops, lay, okc, ovc, n, ok_new, ov_new, omask(1, tau, lv + 1), vmasks)
+        kv.append(gkeys, gk_new, gv_new)
+    # a group cannot start in the middle of a K ciphertext
+    with pytest.raises(B.CachemirError) as ei:
+        kv.append_group(gkeys, gk_g, gv_g)
+    assert ei.value.status == CM_E_LAYOUT and kv.tokens() == ntok
+    for c in range(len(okc)):
+        assert np.array_equal(kv.export(B.CM_QK, c), octx.canonical(okc[c]))
+    for k in range(E):
+        assert np.array_equal(kv.export(B.CM_SV, k), octx.canonical(ovc[k]))
+    # the cache decrypts to the layouts of Sec. 5.1-5.2
+    assert np.abs(octx.decrypt(e["osk"], okc[1]).real - lay.pack_k(K, 1)).max() < TOL
+    assert np.abs(octx.decrypt(e["osk"], ovc[E - 1]).real - lay.pack_v(V, E - 1)).max() < TOL
+
+    oq, gq = _enc_both(e, lay.pack_vec(q), lv, 10)
+    om = vmm.qk_scores(ops, lay, oq, okc, [omask(0, (c % E) * H * lay.t, lv - 1) for c in range(len(okc))])
+    gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, gq)
+    _same(e, om, gm)
+    got = lay.unpack_scores(gctx.decrypt(e["gsk"], gm).real, ntok)
+    assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
+    os_, gs = _enc_both(e, lay.pack_scores(s), lv, 50)
+    oa = vmm.score_times_v(ops, lay, os_, ovc)
+    ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)
+    _same(e, oa, ga)
+    assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
