@@ -13,6 +13,7 @@ P on its own.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--plain-sums]
 
     python bench.py --workload attention        (config 3, a JSON line of its own)
+    python bench.py --workload prefill          (prompt phase: token-batched product, group append)
 
 Prints one JSON line.  `roofline` describes the kernel family with the most time in the step:
 achieved = algorithmic bytes per unit / measured time per unit (HIP events around every launch of
@@ -311,6 +312,57 @@ def sweep_workload(a):
                       "qkv_projections_ms": qkv}))
 
 
+def prefill_workload(a):
+    """The prompt phase (Sec. 5.4) on the config-2 ring: one 4096 x 4096 product over a ciphertext of
+    t = 8 tokens (4096 diagonals as 64 baby x 64 giant steps, 126 rotations), the rotary embedding of a
+    token group and the append of a token group to the 32 x 128 cache.  A JSON line of its own."""
+    import torch
+    from paper_2602_11470_amd import binding as B
+    ctx = B.llama_ring(24, 4)
+    sk = ctx.keygen_secret(1)
+    d, t = 4096, ctx.S // 4096
+    rng = np.random.default_rng(5)
+    X, W = rng.uniform(-1, 1, size=(t, d)), rng.uniform(-1, 1, size=(d, d)) / 64
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e3
+
+    rows = []
+    for level in (ctx.L, 4):
+        plan = ctx.vmm_plan(d, d, W=W, level=level, direct_giants=True, token_batch=True)
+        keys = ctx.keygen_rotations(sk, plan.steps(), 2)
+        ct = ctx.level_drop(ctx.encrypt(sk, ctx.encode(X.T.reshape(-1), ctx.L), 3), level)   # X[tau, b] at b t + tau
+        y = ctx.vmm_pt(keys, plan, ct)
+        ms = timed(lambda: ctx.vmm_pt(keys, plan, ct, out=y), max(2, a.steps // 4))
+        err = float(np.abs(ctx.decrypt(sk, y).real.reshape(d, t).T - X @ W).max())
+        rows.append({"level": level, "tokens_per_ciphertext": t, "rotations": plan.n_rotations, "pt_mults": plan.r_i * plan.r_o,
+                     "ms": ms, "ms_per_token": ms / t, "max_abs_err": err})
+        del plan, keys
+    H, E, lv = 32, 128, ctx.L - 3
+    kv = ctx.kv_create(H, E, lv, r_i=16)
+    rope = ctx.rope(H, E, lv + 2, 0, tau=-1)
+    keys = ctx.keygen_rotations(sk, sorted(set(kv.steps()) | set(rope.steps())), 2, with_relin=True)
+    kg = ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), ctx.L), 20), lv + 2)
+    vg = ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), ctx.L), 21), lv + 1)
+    kr = ctx.rope_apply(keys, rope, kg)
+    rope_ms = timed(lambda: ctx.rope_apply(keys, rope, kg, out=kr), a.steps)
+
+    def append():
+        kv.set_tokens(0)
+        kv.append_group(keys, kr, vg)
+    append_ms = timed(append, a.steps)
+    print(json.dumps({"metric": "prompt phase, ms per ciphertext of 8 tokens (n=2^16, 24+4 primes)", "unit": "ms", "n_gpus": 1,
+                      "data": "synthetic", "dtype": "u64", "token_batched_4096x4096": rows,
+                      "rope_group_ms": rope_ms, "append_group_ms": append_ms,
+                      "append_group_ms_per_token": append_ms / (ctx.S // (H * E))}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -322,7 +374,7 @@ def main():
     ap.add_argument("--plain-sums", action="store_true",
                     help="divide every hoisted rotation by P on its own (31 more ModDowns per step)")
     ap.add_argument("--cache-level", type=int, default=0, help="attention workload: level of the cache (default L-1)")
-    ap.add_argument("--workload", choices=["projection", "attention", "sweep"], default="projection",
+    ap.add_argument("--workload", choices=["projection", "attention", "sweep", "prefill"], default="projection",
                     help="projection = config 2 (the benchmark line); attention = config 3; sweep = other widths "
                          "and levels; the last two print a line of their own")
     a = ap.parse_args()
@@ -332,6 +384,9 @@ def main():
         sys.exit(2)
     if a.workload == "attention":
         attention_workload(a)
+        return
+    if a.workload == "prefill":
+        prefill_workload(a)
         return
     if a.workload == "sweep":
         sweep_workload(a)

@@ -227,6 +227,57 @@ def test_config3_attention_shapes_decrypt_to_float64_products(ring2):
     assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
 
 
+def test_prompt_phase_on_the_full_ring_builds_a_cache_the_decode_products_can_use(ring2):
+    """Sec. 5.4 at Llama-3-8B shapes: two ciphertexts of t = 8 tokens each go through the token-batched
+    4096 x 4096 k and v projections (4096 diagonals, 64 baby x 64 giant steps, columns ordered (e, h)),
+    the rotary embedding of a token group and the group append; then the decode-phase q K^T and
+    scores V run against that cache.  Everything is compared with the float64 computation."""
+    from oracle import packing
+    B, octx, gctx, prm = ring2
+    H, E, d = 32, 128, 4096
+    lay = packing.KvLayout(gctx.S, H, E, 16)
+    t, lvx = lay.t, 6
+    lv = lvx - 3                                       # cache level: product, embedding, append mask
+    rng = np.random.default_rng(21)
+    groups = 2
+    ntok = groups * t
+    X = rng.uniform(-1, 1, size=(ntok, d))
+    Wk, Wv = rng.uniform(-1, 1, size=(d, d)) / 64, rng.uniform(-1, 1, size=(d, d)) / 64
+    gsk = gctx.keygen_secret(1)
+    pk = gctx.vmm_plan(d, d, W=Wk, level=lvx, direct_giants=True, token_batch=True)
+    pv = gctx.vmm_plan(d, d, W=Wv, level=lvx, direct_giants=True, token_batch=True)
+    assert (pk.r_i, pk.r_o, pk.n_rotations) == (64, 64, 126)
+    kv = gctx.kv_create(H, E, lv, r_i=16)
+    ropes = [gctx.rope(H, E, lvx - 1, c * t, tau=-1) for c in range(groups)]
+    steps = sorted(set(pk.steps()) | set(kv.steps()) | set(ropes[0].steps()))
+    gkeys = gctx.keygen_rotations(gsk, steps, 2, with_relin=True)
+    enc = lambda slots, level, seed: gctx.level_drop(gctx.encrypt(gsk, gctx.encode(slots, gctx.L), seed), level)
+    for c in range(groups):
+        Xc = X[c * t:(c + 1) * t]
+        gx = enc(Xc.T.reshape(-1), lvx, 40 + c)                  # X[tau, b] at slot b t + tau
+        gk, gv = gctx.vmm_pt_multi(gkeys, [pk, pv], gx)
+        if c == 0:
+            assert np.abs(gctx.decrypt(gsk, gk).real.reshape(d, t).T - Xc @ Wk).max() < TOL
+        kv.append_group(gkeys, gctx.rope_apply(gkeys, ropes[c], gk), gctx.level_drop(gv, lvx - 2))
+    assert kv.tokens() == ntok
+    # float64 reference: column e*H + h of the products is element [h, e]
+    K = (X @ Wk).reshape(ntok, E, H).transpose(0, 2, 1)
+    V = (X @ Wv).reshape(ntok, E, H).transpose(0, 2, 1)
+    Kr = np.empty_like(K)
+    for n in range(ntok):
+        for m in range(E // 2):
+            th = n * 10000.0 ** (-2.0 * m / E)
+            Kr[n, :, 2 * m] = K[n, :, 2 * m] * np.cos(th) - K[n, :, 2 * m + 1] * np.sin(th)
+            Kr[n, :, 2 * m + 1] = K[n, :, 2 * m + 1] * np.cos(th) + K[n, :, 2 * m] * np.sin(th)
+    q = rng.normal(size=(H, E)) * 0.3
+    s = rng.uniform(0, 1, size=(H, ntok)) / ntok
+    gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, enc(lay.pack_vec(q), lv, 10))
+    got = lay.unpack_scores(gctx.decrypt(gsk, gm).real, ntok)
+    assert np.abs(got - np.einsum("he,nhe->hn", q, Kr)).max() < TOL
+    ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, enc(lay.pack_scores(s), lv, 50))
+    assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
+
+
 def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
     """Two decode steps of one Llama-3-8B-shaped layer's linear path on the 36 + 6 prime ring: k / v /
     q projections (8 KV heads replicated to 32 by repeating weight columns, columns ordered as the
