@@ -183,7 +183,8 @@ cm_status cm_vmm_plan_create_from_coeffs(cm_ctx *ctx, int32_t d_in, int32_t d_ou
  *   CM_VMM_DIRECT_GIANTS  (implies CM_VMM_RAISED_SUMS) the giant steps of Algorithm 1 are unrolled:
  *     y' = inner_0 + sum_{k>=1} Rot(inner_k, k G) instead of the nested Rot(.. + Rot(inner_{r_o-1}, G), G).
  *     Same number of rotations, but they are independent: their ModUps run as one batch, and all of
- *     them share one ModDown.  Needs the r_o - 1 keys of k G (cm_vmm_plan_steps lists them)
+ *     them share one ModDown.  Only the second component of inner_k is divided by P (for the digits);
+ *     the first joins the sum through the Galois map on all limbs of the extended basis.  Needs the r_o - 1 keys of k G (cm_vmm_plan_steps lists them)
  *     instead of the single key of G.
  *   CM_VMM_TOKEN_BATCH  the prompt phase (Sec. 5.4): the ciphertext holds t = S/d tokens, element b
  *     of token tau at slot b*t + tau, and y holds the t rows of X W in the same layout.  No

@@ -137,8 +137,9 @@ def vmm_pt_direct_giants(ctx, keys, plan: VmmPlan, cx, diagonals_ext):
     """The same product with the giant steps unrolled: y' = inner_0 + sum_{k>=1} Rot(inner_k, k G)
     (G = plan.giant_step) instead of the nested form Rot(... Rot(inner_{r_o-1}, G) + ..., G).  The
     r_o - 1 rotations no longer depend on each other (they need r_o - 1 keys instead of one); each
-    inner_k is divided by P, raised again without the Galois map, and its rotation stays in the
-    extended basis, so that all of them and inner_0 share a single final ModDown."""
+    inner_k is rotated where it is, in the extended basis (only its second component is divided by
+    P, for the digits of the key switch; ckks.rotate_raised), so that all of them and inner_0 share
+    a single final ModDown."""
     c = cx
     for r in plan.pre_steps:
         c = ctx.ct_add(c, ctx.rotate(c, r, keys))
@@ -154,8 +155,7 @@ def vmm_pt_direct_giants(ctx, keys, plan: VmmPlan, cx, diagonals_ext):
         if k == 0:
             acc = inner
             continue
-        ck = ctx.moddown_ct(inner, c.level, scale)
-        R = ctx.rotate_hoisted_raised(ck, ctx.hoist(ck), k * plan.giant_step, keys)
+        R = ctx.rotate_raised(inner, c.level, k * plan.giant_step, keys)
         acc = [ctx.add(acc[0], R[0], ext), ctx.add(acc[1], R[1], ext)]
     y = ctx.moddown_ct(acc, c.level, scale)
     for r in plan.reduce_steps:

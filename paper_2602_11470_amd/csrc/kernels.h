@@ -33,8 +33,9 @@ void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u
 // sum_j perm_g(dig_j) * key_j [+ P * perm_g(c0) on the ciphertext limbs of the first component].
 #define IP_MAX_ITEMS 32
 struct IpItem {
-    const u64 *dig, *key, *c0;
-    unsigned g, pad_;
+    const u64 *dig = nullptr, *key = nullptr, *c0 = nullptr;
+    unsigned g = 0;
+    unsigned c0_ext = 0;      // c0 is already in the extended basis ([ext][n], all limbs): added as it is, no factor P
 };
 struct IpBatch {
     int nz = 0, nsum = 1;
@@ -48,7 +49,7 @@ void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, in
 // out[2][ext][n] = (P c0, P c1), zero on the special limbs
 void launch_raise_by_P(cm_ctx *ctx, u64 *out, const u64 *in, int level, hipStream_t st);
 void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
-                           int addend_comps, int level, u64 g, const u64 *accum, hipStream_t st);
+                           int addend_comps, int level, u64 g, const u64 *accum, hipStream_t st, int ncomp = 2);
 void launch_rescale_reduce(cm_ctx *ctx, u64 *red, const u64 *last, int ncomp, int level, hipStream_t st);
 void launch_rescale_finish(cm_ctx *ctx, u64 *out, const u64 *in, const u64 *red, const u64 *d_qlinv, int ncomp, int level, hipStream_t st);
 u64 rng_key(u64 seed, u64 stream);
@@ -70,6 +71,7 @@ void launch_pt_block(cm_ctx *ctx, u64 *blocked, u64 *plain, int limbs, int r_i, 
 // g_r on the first addend_comps components) (+ accum_r).  Passed to the kernel by value.
 struct FinishBatch {
     int items = 0, level = 0, ext = 0, addend_comps = 0;
+    int ncomp = 2, comp0 = 0;         // components handled per item, and the first of them (1, 1: second component only)
     const u64 *u[CM_KS_BATCH];        // [2][ext][n] per item (evaluation domain)
     u64 *out[CM_KS_BATCH];            // [2][level+1][n] per item
     const u64 *accum[CM_KS_BATCH];    // nullable; may alias out
@@ -77,7 +79,7 @@ struct FinishBatch {
     const u64 *addend[CM_KS_BATCH];   // [2][level+1][n] per item, nullable; must not alias any out
     const u64 *pinv = nullptr;        // [level+1][2]: P^{-1} mod q_l and its Shoup companion
 };
-// forward transform of conv[items*2*(level+1)][n] (mods 0..level repeating) with that tail; n = 65536 only
+// forward transform of conv[items*ncomp*(level+1)][n] (mods 0..level repeating) with that tail; n = 65536 only
 void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const FinishBatch &fb, hipStream_t st);
 
 // ops.hip internals shared with vmm.hip
@@ -120,6 +122,9 @@ void ks_many_tables_destroy(KsManyTables *t);
 cm_status ks_raise_many(cm_ctx *ctx, const KsManyTables &t, const u64 *cts, u64 *ksin, u64 *digits, hipStream_t st,
                         int m = -1, u64 g = 0);
 // outs[r][2][level+1][n] = ModDown(us + r*2*ext*n) for r < cnt (any cnt; runs in batches); special limbs of us are overwritten
+// second components only: outs[r] + (level+1)*n <- ModDown(us[r][1]); the first components of us (all their limbs)
+// and of outs are left as they are
+cm_status moddown_many_second(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *outs, hipStream_t st);
 cm_status moddown_many(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *outs, hipStream_t st);
 // one batch (m <= CM_KS_BATCH): outs[r] = ModDown(us + r*2*ext*n) + perm_g(addends[r]) on the first addend_comps
 // components (+ accums[r]); addends / accums nullable arrays of nullable pointers

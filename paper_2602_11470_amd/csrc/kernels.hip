@@ -315,7 +315,10 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
             a0 += (u128)dx * ea.x;
             a1 += (u128)dy * ea.y;
         }
-        if (it.c0 && r <= level) {
+        if (it.c0 && it.c0_ext) {            // a first component that never left the extended basis
+            ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(it.c0 + (size_t)r * n + base);
+            r0.x = addmod(r0.x, swap ? d.y : d.x, m.q), r0.y = addmod(r0.y, swap ? d.x : d.y, m.q);
+        } else if (it.c0 && r <= level) {
             ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(it.c0 + (size_t)r * n + base);
             const u64 pm = pmont[r];
             b0 += (u128)(swap ? d.y : d.x) * pm;
@@ -425,11 +428,11 @@ __global__ __launch_bounds__(TPB) void k_moddown_finish(u64 *out, const u64 *__r
     out[c * out_stride + (size_t)l * n + i] = v;
 }
 void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
-                           int addend_comps, int level, u64 g, const u64 *accum, hipStream_t st) {
+                           int addend_comps, int level, u64 g, const u64 *accum, hipStream_t st, int ncomp) {
     Prof prof_(ctx, CM_K_MODDOWN_FINISH, 1, st);
     int ext = level + 1 + ctx->K;
     size_t n = ctx->n;
-    hipLaunchKernelGGL(k_moddown_finish, dim3(ctx->n / TPB, level + 1, 2), dim3(TPB), 0, st, out, u, conv, d_pinv,
+    hipLaunchKernelGGL(k_moddown_finish, dim3(ctx->n / TPB, level + 1, ncomp), dim3(TPB), 0, st, out, u, conv, d_pinv,
                        addend, ctx->d_modc, ctx->n, ctx->logn, (unsigned)g, (size_t)ext * n, (size_t)(level + 1) * n,
                        (size_t)(level + 1) * n, addend_comps - 1, accum);
 }

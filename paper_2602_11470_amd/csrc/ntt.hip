@@ -308,8 +308,8 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
         return;
     }
     // fused ModDown tail: this limb is NTT(conv) of item r, component c, limb l
-    const int per = 2 * (fb.level + 1);
-    const int r = limb / per, c = (limb % per) / (fb.level + 1), l = limb % (fb.level + 1);
+    const int per = fb.ncomp * (fb.level + 1);
+    const int r = limb / per, c = fb.comp0 + (limb % per) / (fb.level + 1), l = limb % (fb.level + 1);
     const u64 q = t.modc[l].q, pi = fb.pinv[2 * l], pis = fb.pinv[2 * l + 1];
     const unsigned pos0 = (unsigned)chunk * 4096 + threadIdx.x;
     const size_t row = ((size_t)c * (fb.level + 1) + l) * n;
@@ -480,7 +480,7 @@ void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, c
     }
 }
 void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const FinishBatch &fb, hipStream_t st) {
-    const int limbs = fb.items * 2 * (fb.level + 1), n = ctx->n;
+    const int limbs = fb.items * fb.ncomp * (fb.level + 1), n = ctx->n;
     if (limbs <= 0) return;
     Prof prof_(ctx, CM_K_NTT_FWD, limbs, st);
     dim3 grid((unsigned)limbs * (n >> 12)), block(NTT_THREADS);

@@ -47,6 +47,7 @@ struct KsLevelFull : KsLevel {
     int *d_red_mods = nullptr;  // 0..level-1, repeated likewise
     int *d_last_rows = nullptr; // rows c*(level+1)+level of stacked components
     int *d_bsp_rows = nullptr, *d_bsp_mods = nullptr;   // special rows of CM_KS_BATCH stacked [2][ext] blocks
+    int *d_bsp1_rows = nullptr;                         // those of the second components only
     int *d_bq_mods = nullptr;                           // 0..level repeated 2*CM_KS_BATCH times
     std::vector<int> h_ntt_rows, h_ntt_mods;            // host copies of d_ntt_rows / d_ntt_mods
     ConvDev *d_modup = nullptr; // one table per digit
@@ -142,6 +143,10 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
                 for (int i = 0; i <= level; i++) bq.push_back(i);
             }
         k.d_bsp_rows = up(br), k.d_bsp_mods = up(bm), k.d_bq_mods = up(bq);
+        std::vector<int> b1;
+        for (int r = 0; r < CM_KS_BATCH; r++)
+            for (int sp = 0; sp < ctx->K; sp++) b1.push_back((r * 2 + 1) * k.ext + level + 1 + sp);
+        k.d_bsp1_rows = up(b1);
     }
     {
         std::vector<int> lr;
@@ -164,7 +169,7 @@ static void drop_ks_levels(cm_ctx *ctx) {
     for (auto it = g_ks.begin(); it != g_ks.end();) {
         if (it->first.first != ctx) { ++it; continue; }
         KsLevelFull &k = it->second;
-        hipFree(k.d_modup); hipFree(k.d_moddown); hipFree(k.d_bsp_rows); hipFree(k.d_bsp_mods); hipFree(k.d_bq_mods);
+        hipFree(k.d_modup); hipFree(k.d_moddown); hipFree(k.d_bsp_rows); hipFree(k.d_bsp1_rows); hipFree(k.d_bsp_mods); hipFree(k.d_bq_mods);
         hipFree(k.d_last_rows);
         hipFree(k.d_ntt_rows); hipFree(k.d_ntt_mods); hipFree(k.d_sp_rows); hipFree(k.d_sp_mods);
         hipFree(k.d_q_rows); hipFree(k.d_q_mods3); hipFree(k.d_last_mods); hipFree(k.d_red_mods);
@@ -280,6 +285,36 @@ cm_status moddown_many(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *out
     for (int base = 0; base < cnt; base += CM_KS_BATCH) {
         const int m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
         moddown_batch(ctx, k, us + base * ublk, m, nullptr, 0, nullptr, nullptr, outs + base, st);
+    }
+    return CM_OK;
+}
+
+cm_status moddown_many_second(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *outs, hipStream_t st) {
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    Arena A = arena_of(ctx);
+    const size_t n = ctx->n, ublk = 2 * (size_t)k.ext * n;
+    for (int base = 0; base < cnt; base += CM_KS_BATCH) {
+        const int m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
+        u64 *bu = us + base * ublk;
+        // special limbs of the second components to the coefficient domain, converted to q_0..q_level, transformed,
+        // and the tail (u - conv) P^{-1} fused into the last pass of that transform
+        launch_ntt_rows(ctx, bu, k.d_bsp1_rows, k.d_bsp_mods, m * ctx->K, true, st);
+        launch_base_conv(ctx, k.d_moddown, m, 0, level + 1, A.bconv, bu + (size_t)k.ext * n, ublk, (size_t)(level + 1) * n,
+                         nullptr, 0, st);
+        if (ctx->n != 65536) {                              // no fused tail at the small ring sizes
+            launch_ntt(ctx, A.bconv, k.d_bq_mods, m * (level + 1), false, st);
+            for (int r = 0; r < m; r++)
+                launch_moddown_finish(ctx, outs[base + r] + (size_t)(level + 1) * n, bu + r * ublk + (size_t)k.ext * n,
+                                      A.bconv + (size_t)r * (level + 1) * n, get_pinv(ctx, level), nullptr, 0, level, 0,
+                                      nullptr, st, 1);
+            continue;
+        }
+        FinishBatch fb;
+        fb.items = m, fb.level = level, fb.ext = k.ext, fb.addend_comps = 0, fb.ncomp = 1, fb.comp0 = 1;
+        for (int r = 0; r < CM_KS_BATCH; r++) fb.addend[r] = nullptr, fb.accum[r] = nullptr, fb.u[r] = nullptr, fb.out[r] = nullptr, fb.g[r] = 0;
+        for (int r = 0; r < m; r++) fb.u[r] = bu + r * ublk, fb.out[r] = outs[base + r];
+        fb.pinv = get_pinv(ctx, level);
+        launch_ntt_fwd_finish(ctx, A.bconv, k.d_bq_mods, fb, st);
     }
     return CM_OK;
 }

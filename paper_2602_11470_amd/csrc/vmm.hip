@@ -291,14 +291,16 @@ static cm_status vmm_raised_finish(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_
     launch_vmm_mac(ctx, inner, babies, p->d_pts, p->r_i, r_o, ext, level, rw, 0, r_o, st);
     u64 *acc = t1, *other = t2;
     if (p->direct) {
-        // giant steps unrolled: inner_k -> ciphertext -> raised digits (all k at once); every rotation by
-        // k*G stays in the extended basis and joins inner_0; one ModDown for the whole sum
+        // giant steps unrolled: the second component of inner_k is divided by P and raised digit by digit
+        // (all k at once); its first component is never divided: it goes through the Galois map on all
+        // limbs of the extended basis and joins the sum as it is.  Every rotation by k*G stays in the
+        // extended basis and joins inner_0; one ModDown for the whole sum.
         const KsLevel &kl = ks_level(ctx, level);
         const int cnt = r_o - 1;
         u64 *cts = p->d_many, *ksin = cts + (size_t)cnt * ctw, *digs = ksin + (size_t)cnt * limbs * n;
         std::vector<u64 *> outs;
         for (int k = 0; k < cnt; k++) outs.push_back(cts + (size_t)k * ctw);
-        CMCHK(moddown_many(ctx, inner + rw, level, cnt, outs.data(), st));
+        CMCHK(moddown_many_second(ctx, inner + rw, level, cnt, outs.data(), st));
         CMCHK(ks_raise_many(ctx, p->many, cts, ksin, digs, st));
         for (int k0 = 1; k0 < r_o; k0 += IP_MAX_ITEMS) {          // all rotations summed onto inner_0 by one launch
             IpBatch b;
@@ -306,7 +308,8 @@ static cm_status vmm_raised_finish(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_
             for (int s = 0; s < b.nsum; s++) {
                 const int k = k0 + s;
                 b.it[s].dig = digs + (size_t)(k - 1) * kl.beta * kl.ext * n, b.it[s].key = key_of(k * p->giant_step);
-                b.it[s].c0 = cts + (size_t)(k - 1) * ctw, b.it[s].g = (unsigned)galois_of_step(ctx, k * p->giant_step);
+                b.it[s].c0 = inner + (size_t)k * rw, b.it[s].c0_ext = 1;
+                b.it[s].g = (unsigned)galois_of_step(ctx, k * p->giant_step);
             }
             b.out[0] = inner, b.extra[0] = inner;
             launch_inner_product_batch(ctx, b, kl.beta, level, st);

@@ -136,6 +136,39 @@ def test_rotate_add_raised_is_rotation_plus_the_divided_addend():
     assert np.array_equal(pt.m[:level + 1], ctx.encode(v, level).m)   # same polynomial on the q limbs
 
 
+def test_rotation_inside_the_raised_basis():
+    """rotate_raised: exact where exactness is forced (a raised ciphertext P ct vanishes on the
+    special limbs, so nothing is lost by not dividing its first component), and within the
+    rounding of one ModDown otherwise: second component identical, first within 2K."""
+    prm, ctx, sk = _toy_ctx()
+    keys = ctx.keygen_rotations(sk, [3, 5], 2)
+    rng = np.random.default_rng(2)
+    z, w = rng.normal(size=(2, ctx.S))
+    for level in (prm.L, 2):
+        x = ctx.level_drop(ctx.encrypt(sk, ctx.encode(z, prm.L), 3), level)
+        got = ctx.rotate_raised(ctx.raise_ct(x), level, 3, keys)
+        want = ctx.rotate_hoisted_raised(x, ctx.hoist(x), 3, keys)
+        assert all(np.array_equal(a, b) for a, b in zip(got, want))
+        # a raised sum with full special limbs: a hoisted rotation of another ciphertext times a plaintext
+        y = ctx.level_drop(ctx.encrypt(sk, ctx.encode(w, prm.L), 4), level)
+        R = [np.zeros((len(ctx.ext_idx(level)), ctx.n), dtype=np.uint64) for _ in range(2)]
+        ctx.mac_pt_raised(R, ctx.rotate_hoisted_raised(y, ctx.hoist(y), 5, keys), ctx.encode_ext(z, level), level)
+        assert R[0][level + 1:].any()
+        scale = y.scale * prm.scale
+        got = ctx.moddown_ct(ctx.rotate_raised(R, level, 3, keys), level, scale)
+        down = ctx.moddown_ct(R, level, scale)
+        want = ctx.rotate_hoisted(down, ctx.hoist(down), 3, keys)        # Galois map after the raise, as here
+        assert np.array_equal(got.c[1], want.c[1])
+        q = np.array(prm.moduli[:level + 1], dtype=np.int64)[:, None]
+        diff = (got.c[0].astype(np.int64) - want.c[0].astype(np.int64)) % q
+        # evaluation-domain limbs: compare coefficients
+        dc = (ctx.intt(got.c[0], ctx.q_idx(level)).astype(np.int64) - ctx.intt(want.c[0], ctx.q_idx(level)).astype(np.int64)) % q
+        dc = np.minimum(dc, q - dc)
+        assert diff.any() and 1 <= dc.max() <= 2 * prm.K
+        m = ctx.decrypt(sk, ctx.rescale(got)).real
+        assert np.abs(m - np.roll(np.roll(w, -5) * z, -3)).max() < 1e-6
+
+
 @pytest.mark.parametrize("d_in,d_out,level,tau", [(16, 16, 3, 0), (16, 64, 2, 0), (64, 16, 4, 0), (32, 32, 1, 3)])
 def test_double_hoisted_vmm_decrypts_to_x_times_W(d_in, d_out, level, tau):
     prm, ctx, sk = _toy_ctx()
