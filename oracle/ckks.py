@@ -493,21 +493,36 @@ class Context:
         u0[:nq] = self.add(u0[:nq], self.mul_scalar(self.automorphism(x.c[0], idx, g), [self._P()] * nq, idx), idx)
         return [u0, u1]
 
-    def rotate_raised(self, R, level, r, keys):
-        """Rotation of a ciphertext that is held in the extended basis (R ~ P * ct) and stays there:
-        only the second component is divided by P (its digits feed the key switch); the first one
-        goes through the Galois map on all limbs and joins the key-switch sum as it is,
+    def hoist_raised(self, R, level):
+        """Shared part of several rotations of a ciphertext held in the extended basis (R ~ P ct):
+        the second component alone is divided by P, and its digits are raised."""
+        return self.modup(self.intt(self.moddown(R[1], level), self.q_idx(level)), level)
+
+    def rotate_raised_hoisted(self, R, hoisted, level, r, keys):
+        """Rotation of a ciphertext that is held in the extended basis and stays there: the first
+        component goes through the Galois map on all limbs and joins the key-switch sum as it is,
               [u0 + sigma(R0), u1],   u = sum_d sigma(digits_d(ModDown(R1))) * key_d.
         P * ModDown(R0) and R0 differ by the lift of R0 mod P, less than K P, so after the ModDown
         that ends the sum the result is Rot(ModDown(R), r) up to a few units of rounding in the
         first component (and exactly that when R0 vanishes on the special limbs)."""
         g, ext = self.galois(r), self.ext_idx(level)
         self.rot_count += 1
-        c1 = self.moddown(R[1], level)
-        hoisted = self.modup(self.intt(c1, self.q_idx(level)), level)
         digits = [self.ntt(self.automorphism_coeff(d, ext, g), ext) for d in hoisted]
         u0, u1 = self.inner_product(digits, keys[g], level)
         return [self.add(u0, self.automorphism(R[0], ext, g), ext), u1]
+
+    def rotate_raised(self, R, level, r, keys):
+        return self.rotate_raised_hoisted(R, self.hoist_raised(R, level), level, r, keys)
+
+    def rotsum_raised(self, R, level, amounts, keys):
+        """R + sum_a Rot(R, a) in the extended basis, all rotations sharing one set of raised digits."""
+        ext = self.ext_idx(level)
+        hoisted = self.hoist_raised(R, level)
+        acc = [R[0].copy(), R[1].copy()]
+        for a in amounts:
+            T = self.rotate_raised_hoisted(R, hoisted, level, a, keys)
+            acc = [self.add(acc[0], T[0], ext), self.add(acc[1], T[1], ext)]
+        return acc
 
     def mac_pt_raised(self, acc, R, pt: Pt, level):
         """acc += R * pt on the extended basis (acc, R: two [ext][n] arrays; pt from *_ext)."""

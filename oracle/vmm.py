@@ -163,6 +163,58 @@ def vmm_pt_direct_giants(ctx, keys, plan: VmmPlan, cx, diagonals_ext):
     return ctx.rescale(y)
 
 
+LADDER_GROUP = 3
+
+
+def ladder_groups(steps):
+    """A rotate-and-add ladder c <- c + Rot(c, s_l), l = 0, 1, ..., multiplies by prod_l (1 + Rot_{s_l});
+    a run of g consecutive steps equals c + sum over the 2^g - 1 non-empty subsets B of the run of
+    Rot(c, sum_{l in B} s_l): rotations of ONE ciphertext.  Returns, for runs of up to LADDER_GROUP
+    steps, the list of those rotation amounts (subset with bit pattern b at position b - 1)."""
+    out = []
+    for i in range(0, len(steps), LADDER_GROUP):
+        run = steps[i:i + LADDER_GROUP]
+        out.append([sum(s for l, s in enumerate(run) if (b >> l) & 1) for b in range(1, 1 << len(run))])
+    return out
+
+
+def vmm_pt_unrolled(ctx, keys, plan: VmmPlan, cx, diagonals_ext):
+    """Algorithm 1 (App. C) computed entirely in the extended basis: the giant steps unrolled as in
+    vmm_pt_direct_giants, and the two rotate-and-add ladders (preprocess, reduce) unrolled in runs
+    of three steps into hoisted rotations of one ciphertext (ladder_groups).  More rotations (7 per
+    run of three instead of 3) but each run has one ModUp, and the whole product one ModDown of
+    both components, at its end; second components alone are divided by P where digits are needed."""
+    level = cx.level
+    ext = ctx.ext_idx(level)
+    R = ctx.raise_ct(cx)
+    for amounts in ladder_groups(plan.pre_steps):
+        R = ctx.rotsum_raised(R, level, amounts, keys)
+    # baby steps: hoisted rotations of the (raised) preprocessed ciphertext
+    hoisted = ctx.hoist_raised(R, level)
+    raised = [R] + [ctx.rotate_raised_hoisted(R, hoisted, level, r, keys) for r in plan.baby_steps[1:]]
+    acc = None
+    for k in range(plan.r_o):
+        inner = [np.zeros((len(ext), ctx.n), dtype=np.uint64) for _ in range(2)]
+        for j in range(plan.r_i):
+            ctx.mac_pt_raised(inner, raised[j], diagonals_ext[j][k], level)
+        if k == 0:
+            acc = inner
+            continue
+        Rk = ctx.rotate_raised(inner, level, k * plan.giant_step, keys)
+        acc = [ctx.add(acc[0], Rk[0], ext), ctx.add(acc[1], Rk[1], ext)]
+    for amounts in ladder_groups(plan.reduce_steps):
+        acc = ctx.rotsum_raised(acc, level, amounts, keys)
+    y = ctx.moddown_ct(acc, level, cx.scale * diagonals_ext[0][0].scale)
+    return ctx.rescale(y)
+
+
+def unrolled_steps(plan: VmmPlan):
+    """Rotation amounts of vmm_pt_unrolled, in the order they are used."""
+    steps = [a for grp in ladder_groups(plan.pre_steps) for a in grp] + list(plan.baby_steps[1:])
+    steps += [k * plan.giant_step for k in range(1, plan.r_o)]
+    return steps + [a for grp in ladder_groups(plan.reduce_steps) for a in grp]
+
+
 def direct_giant_steps(plan: VmmPlan):
     """Rotation amounts of vmm_pt_direct_giants: every multiple of the giant step instead of one."""
     steps = list(plan.pre_steps) + list(plan.baby_steps[1:])

@@ -1,5 +1,5 @@
 """Writes tests/golden/vmm_full_size.txt (with the argument `raised`: vmm_full_size_raised.txt; with
-`direct`: vmm_full_size_direct.txt) by running ONLY the oracle.
+`direct`: vmm_full_size_direct.txt; with `unrolled`: vmm_full_size_unrolled.txt) by running ONLY the oracle.
 
 Full-size parity case of the packed product: ring n = 2^16 with 24 x 50-bit + 4 x 60-bit primes
 (benchmark configuration 2), d = 4096 square plan (32 baby x 16 giant steps, 52 rotations, 512
@@ -12,6 +12,7 @@ every limb.  Run from the repository root:
     python tests/golden/make_vmm_full_size_golden.py            (Algorithm 1 as printed)
     python tests/golden/make_vmm_full_size_golden.py raised     (baby-step sums kept in the extended basis)
     python tests/golden/make_vmm_full_size_golden.py direct     (that, with the giant steps unrolled)
+    python tests/golden/make_vmm_full_size_golden.py unrolled   (that, with the two ladders unrolled too: 60 rotations)
 (about ten minutes each on 8 cores, ~20 GiB of memory).
 """
 import hashlib
@@ -39,20 +40,23 @@ def integer_inputs(n, plan):
 
 
 def main(form="plain"):
-    raised, direct = form in ("raised", "direct"), form == "direct"
+    raised, direct, unrolled = form in ("raised", "direct", "unrolled"), form == "direct", form == "unrolled"
     t0 = time.time()
     prm = params.config2()
     ctx = ckks.Context(prm)
     plan = packing.make_plan(ctx.S, D, D)
     xc, diag = integer_inputs(ctx.n, plan)
     sk = ctx.keygen_secret(SEED_SK)
-    keys = ctx.keygen_rotations(sk, vmm.direct_giant_steps(plan) if direct else plan.all_steps(), SEED_EVK)
+    steps = vmm.unrolled_steps(plan) if unrolled else vmm.direct_giant_steps(plan) if direct else plan.all_steps()
+    keys = ctx.keygen_rotations(sk, steps, SEED_EVK)
     print("keys", len(keys), time.time() - t0, flush=True)
     ct = ctx.encrypt(sk, ctx.pt_from_coeffs(xc, prm.L, prm.scale), SEED_ENC)
     make_pt = ctx.pt_from_coeffs_ext if raised else ctx.pt_from_coeffs
     pts = [[make_pt(diag[j * plan.r_o + k], prm.L, prm.scale) for k in range(plan.r_o)] for j in range(plan.r_i)]
     print("plaintexts", time.time() - t0, flush=True)
-    if direct:
+    if unrolled:
+        y = vmm.vmm_pt_unrolled(ctx, keys, plan, ct, pts)
+    elif direct:
         y = vmm.vmm_pt_direct_giants(ctx, keys, plan, ct, pts)
     elif raised:
         y = vmm.vmm_pt_double_hoisted(ctx, keys, plan, ct, pts)
@@ -61,12 +65,14 @@ def main(form="plain"):
     can = ctx.canonical(y)
     print("vmm", time.time() - t0, ctx.rot_count, ctx.ptmul_count, flush=True)
     out = os.path.join(ROOT, "tests", "golden", {"plain": "vmm_full_size.txt", "raised": "vmm_full_size_raised.txt",
-                                                  "direct": "vmm_full_size_direct.txt"}[form])
+                                                  "direct": "vmm_full_size_direct.txt",
+                                                  "unrolled": "vmm_full_size_unrolled.txt"}[form])
     with open(out, "w") as f:
         f.write("# Oracle output of the full-size packed product (Algorithm 1 of App. C at the Table 2 shape\n"
                 "# (S, d) = (32768, 4096)) on integer plaintexts; written by make_vmm_full_size_golden.py"
                 + (f" {form}\n# (sums of the baby steps kept in the extended basis"
-                   + (", giant steps unrolled" if direct else "") + ").\n" if raised else ".\n"))
+                   + (", giant steps unrolled" if direct or unrolled else "")
+                   + (", rotate-and-add ladders unrolled" if unrolled else "") + ").\n" if raised else ".\n"))
         f.write(f"shape: {' '.join(map(str, can.shape))}\n")
         f.write(f"level: {y.level}\n")
         f.write(f"rotations: {ctx.rot_count}\n")

@@ -367,3 +367,69 @@ def test_group_rope_turns_every_residue_by_its_own_token():
     assert (ops.rotations, ops.pt_mults) == (2, 3)
     for tau in range(lay.t):
         assert np.abs(lay.unpack_vec(out, tau) - _rope_reference(vs[tau], c * lay.t + tau)).max() < 1e-12
+
+
+# ---- the whole product in the extended basis: ladders unrolled into hoisted rotations -----------------
+@pytest.mark.parametrize("steps", [[], [3], [7, 14], [7, 14, 28], [1, -2, 4, -8], [5, 10, 20, 40, 80, 160, 320]])
+def test_ladder_groups_reproduce_the_rotate_and_add_ladder_on_slots(steps):
+    rng = np.random.default_rng(len(steps))
+    v = rng.normal(size=1024)
+    want = v.copy()
+    for s in steps:
+        want = want + np.roll(want, -s)
+    got = v.copy()
+    groups = vmm.ladder_groups(steps)
+    for amounts in groups:
+        assert 1 <= len(amounts) <= 7 and len(set(a % 1024 for a in amounts)) == len(amounts)
+        got = got + sum(np.roll(got, -a) for a in amounts)
+    assert np.abs(got - want).max() < 1e-9
+    assert len(groups) == (len(steps) + 2) // 3
+    assert sum(len(g) for g in groups) == sum(2 ** len(steps[i:i + 3]) - 1 for i in range(0, len(steps), 3))
+
+
+def test_rotsum_raised_against_separate_rotations():
+    """One amount from a freshly raised ciphertext: exact (ModDown(u + P a) = ModDown(u) + a).
+    Several amounts from a sum with full special limbs: the message of x + sum_a Rot(x, a)."""
+    prm, ctx, sk = _toy_ctx()
+    keys = ctx.keygen_rotations(sk, [3, 5, 8], 2)
+    rng = np.random.default_rng(5)
+    z, w = rng.normal(size=(2, ctx.S))
+    level = 3
+    x = ctx.level_drop(ctx.encrypt(sk, ctx.encode(z, prm.L), 3), level)
+    got = ctx.moddown_ct(ctx.rotsum_raised(ctx.raise_ct(x), level, [5], keys), level, x.scale)
+    want = ctx.ct_add(x, ctx.rotate_hoisted(x, ctx.hoist(x), 5, keys))
+    assert all(np.array_equal(a, b) for a, b in zip(got.c, want.c))
+    r0 = ctx.rot_count
+    R = ctx.rotsum_raised(ctx.raise_ct(x), level, [3, 5, 8], keys)       # special limbs now full
+    assert ctx.rot_count - r0 == 3 and R[0][level + 1:].any()
+    R2 = ctx.rotsum_raised(R, level, [3, 8], keys)
+    m = ctx.decrypt(sk, ctx.moddown_ct(R2, level, x.scale)).real
+    s1 = z + np.roll(z, -3) + np.roll(z, -5) + np.roll(z, -8)
+    assert np.abs(m - (s1 + np.roll(s1, -3) + np.roll(s1, -8))).max() < 1e-6
+
+
+@pytest.mark.parametrize("d_in,d_out,level,tau", [(64, 64, 3, 0), (16, 64, 2, 0), (64, 16, 4, 0), (32, 32, 1, 3),
+                                                  (16, 16, 3, 9), (256, 256, 2, 0)])
+def test_unrolled_vmm_decrypts_to_x_times_W(d_in, d_out, level, tau):
+    """(16, 16) on 256 slots has four-step ladders (runs of three and one); (256, 256) has none."""
+    prm, ctx, sk = _toy_ctx()
+    x, W = inputs.vmm_inputs(7, d_in, d_out, "normal", 0.1)
+    plan = packing.make_plan(ctx.S, d_in, d_out, tau=tau)
+    steps = vmm.unrolled_steps(plan)
+    npre, nred = len(plan.pre_steps), len(plan.reduce_steps)
+    ladder = lambda L: sum(2 ** len(range(i, min(i + 3, L))) - 1 for i in range(0, L, 3))
+    assert len(steps) == ladder(npre) + plan.r_i - 1 + plan.r_o - 1 + ladder(nred)
+    keys = ctx.keygen_rotations(sk, sorted(set(steps) | set(vmm.direct_giant_steps(plan))), 2)
+    ct = ctx.level_drop(ctx.encrypt(sk, ctx.encode(plan.pack_input(x), prm.L), 3), level)
+    ext = [[ctx.encode_ext(v, level) for v in row] for row in plan.diagonals(W)]
+    r0, p0 = ctx.rot_count, ctx.ptmul_count
+    y = vmm.vmm_pt_unrolled(ctx, keys, plan, ct, ext)
+    assert ctx.rot_count - r0 == len(steps) and ctx.ptmul_count - p0 == plan.r_i * plan.r_o
+    assert y.level == level - 1
+    assert np.abs(plan.unpack_output(ctx.decrypt(sk, y).real) - x @ W).max() < TOL
+    other = vmm.vmm_pt_direct_giants(ctx, keys, plan, ct, ext)
+    assert abs(y.scale / other.scale - 1) < 1e-12
+    assert np.abs(ctx.decrypt(sk, y) - ctx.decrypt(sk, other)).max() < 1e-6
+    if npre == 0 and nred == 0:
+        # nothing to unroll: the same computation, bit for bit
+        assert np.array_equal(ctx.canonical(y), ctx.canonical(other))
