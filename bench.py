@@ -4,13 +4,15 @@
 A step = one pass of the whole hot path over one synthetic input: cm_vmm_pt of an encrypted
 4096-vector (interleaved replicated packing) against a plaintext 4096x4096 matrix on the ring
 n = 2^16 with 24 ciphertext primes of 50 bits + 4 special primes of 60 bits (6 key-switch
-digits), at the top level: 52 rotations (21 full key switches + 31 hoisted), 512 plaintext
-multiply-accumulates, one rescale.  Keys, weight plaintexts and the input ciphertext are
-resident in HBM before the timed region.  By default the sums of the hoisted baby steps stay in
-the extended basis (one ModDown per giant step); --plain-sums divides every hoisted rotation by
-P on its own.
+digits), at the top level: 512 plaintext multiply-accumulates, one rescale, and the rotations of
+Algorithm 1 — 52 as printed (21 full key switches + 31 hoisted); 60 in the default form, which
+unrolls the giant steps and the two rotate-and-add ladders into hoisted rotations and keeps the
+whole product in the extended basis (one ModDown of both components at the end).  Keys, weight
+plaintexts and the input ciphertext are resident in HBM before the timed region.  --ladders keeps
+the ladders (52 rotations), --nested-giants also the nested giant steps, --plain-sums divides
+every hoisted rotation by P on its own (Algorithm 1 as printed).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--plain-sums]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--ladders | --nested-giants | --plain-sums]
 
     python bench.py --workload attention        (config 3, a JSON line of its own)
     python bench.py --workload prefill          (prompt phase: token-batched product, group append)
@@ -49,12 +51,13 @@ def measured_traffic():
     return out
 
 
-def gpu_setup(raised_sums=True, direct_giants=True):
+def gpu_setup(raised_sums=True, direct_giants=True, unrolled_ladders=True):
     import torch
     from paper_2602_11470_amd import binding as B, inputs
     ctx = B.llama_ring(24, 4)
     x, W = inputs.vmm_inputs(1, D, D)
-    plan = ctx.vmm_plan(D, D, W=W, raised_sums=raised_sums, direct_giants=direct_giants)
+    plan = ctx.vmm_plan(D, D, W=W, raised_sums=raised_sums, direct_giants=direct_giants,
+                        unrolled_ladders=unrolled_ladders)
     sk = ctx.keygen_secret(1)
     keys = ctx.keygen_rotations(sk, plan.steps(), 2)
     t = ctx.S // D
@@ -186,7 +189,7 @@ def cpu_baseline(raised_sums=True):
             "sample": "n=2^16, 24+4 primes: 3 rotations, 1 hoisting, 3 hoisted rotations, 8 pt-ct MACs, "
                       + ("1 ModDown, " if raised_sums else "") +
                       "1 rescale timed; scaled by the step's counts 21/1/31/512/" + ("1/" if raised_sums else "") +
-                      "1 (extrapolated)",
+                      "1 of Algorithm 1 with its ladders (extrapolated)",
             "key_switch_s": t_rot, "seconds_per_vmm": t_vmm}
 
 
@@ -256,7 +259,7 @@ def sweep_workload(a):
               (4096, 16384, 23), (16384, 4096, 23))          # the last two: MLP up / down (14336 padded to 16384)
     for d_in, d_out, level in shapes:
         x, W = inputs.vmm_inputs(1, d_in, d_out)
-        plan = ctx.vmm_plan(d_in, d_out, W=W, level=level, direct_giants=True)
+        plan = ctx.vmm_plan(d_in, d_out, W=W, level=level, unrolled_ladders=True)
         keys = ctx.keygen_rotations(sk, plan.steps(), 2)
         d = min(d_in, d_out)
         t, tp = ctx.S // d, ctx.S // max(d_in, d_out)
@@ -290,7 +293,7 @@ def sweep_workload(a):
     # preprocess rotations and the hoisted baby steps run once (cm_vmm_pt_multi)
     d, level = 4096, ctx.L
     x, _ = inputs.vmm_inputs(1, d, d)
-    plans = [ctx.vmm_plan(d, d, W=inputs.vmm_inputs(2 + i, d, d)[1], level=level, direct_giants=True) for i in range(3)]
+    plans = [ctx.vmm_plan(d, d, W=inputs.vmm_inputs(2 + i, d, d)[1], level=level, unrolled_ladders=True) for i in range(3)]
     keys = ctx.keygen_rotations(sk, plans[0].steps(), 2)
     slots = np.zeros(ctx.S)
     slots[::ctx.S // d] = x
@@ -369,6 +372,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ladders", action="store_true",
+                    help="preprocess and reduce as the rotate-and-add ladders of Algorithm 1 (3 + 3 dependent rotations)")
     ap.add_argument("--nested-giants", action="store_true",
                     help="giant steps in the nested (Horner) form with one key, as Algorithm 1 prints them")
     ap.add_argument("--plain-sums", action="store_true",
@@ -391,7 +396,8 @@ def main():
     if a.workload == "sweep":
         sweep_workload(a)
         return
-    g = gpu_setup(raised_sums=not a.plain_sums, direct_giants=not (a.plain_sums or a.nested_giants))
+    nested = a.plain_sums or a.nested_giants
+    g = gpu_setup(raised_sums=not a.plain_sums, direct_giants=not nested, unrolled_ladders=not (nested or a.ladders))
     sec, err = time_steps(g, a.steps, a.warmup)
     if not err < 1e-4:
         print(f"bench.py: decrypted result off by {err}", file=sys.stderr)
@@ -426,7 +432,7 @@ def main():
         "inner_product": {"bound": "hbm", "achieved": ip_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": ip_gbs / HBM_PEAK_GBS, "traffic": tr.get("k_inner_product"),
                           "kernel": "k_inner_product_batch / k_inner_product (per inner product; one launch of the "
-                                    "batched kernel = 31 or 15 of them)",
+                                    "batched kernel = 31, 15 or 7 of them)",
                           "inner_products_per_step": ip["units"], "launches_per_step": ip["launches"],
                           "us_per_launch": ip_launch_s * 1e6},
     }
@@ -438,9 +444,11 @@ def main():
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64", "data": "synthetic",
         "config": {"workload": "config2: encrypted 4096-vector x plaintext 4096x4096, interleaved replicated "
-                               "packing, BSGS 32x16, 52 rotations, 512 pt-ct MACs", "ring_degree": n,
+                               f"packing, BSGS 32x16, {g['plan'].n_rotations} rotations, 512 pt-ct MACs", "ring_degree": n,
                    "baby_step_sums": "plain" if a.plain_sums else "extended basis",
-                   "giant_steps": "nested (one key)" if (a.plain_sums or a.nested_giants) else "unrolled (one key per step)",
+                   "giant_steps": "nested (one key)" if nested else "unrolled (one key per step)",
+                   "ladders": "rotate-and-add, 3 + 3 dependent rotations" if (nested or a.ladders) else
+                              "unrolled: 7 + 7 hoisted rotations, whole product in the extended basis",
                    "rotation_keys": len(set(g["plan"].steps())),
                    "ciphertext_primes": limbs, "special_primes": K, "dnum": beta, "level": limbs - 1},
         "max_abs_err_vs_float64": err,

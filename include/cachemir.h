@@ -191,8 +191,15 @@ cm_status cm_vmm_plan_create_from_coeffs(cm_ctx *ctx, int32_t d_in, int32_t d_ou
  *     preprocess and no reduce rotations; all d diagonals (each repeated over the residues), baby
  *     step j*t, giant step r_i*t, r_i*r_o = d; d_in == d_out (a wider or taller matrix is a set of
  *     square ones, cm_vmm_pt_multi shares their baby steps), tau = 0.  Combines with the other two.
+ *   CM_VMM_UNROLLED_LADDERS  (implies CM_VMM_DIRECT_GIANTS) the two rotate-and-add ladders of
+ *     Algorithm 1 (preprocess: c <- c + Rot(c, 2^i (t-1)); reduce: c <- c + Rot(c, +-2^l)) are unrolled
+ *     in runs of three steps: a run equals c + the rotations of c by the seven non-empty subset sums
+ *     of its steps, which are rotations of ONE ciphertext and share its raised digits.  The whole
+ *     product then stays in the extended basis: one ModDown of both components at its end, second
+ *     components alone divided by P where digits are needed.  More rotations and keys (7 per run of
+ *     three steps instead of 3; cm_vmm_plan_steps lists them), fewer ModUps and ModDowns.
  * Unknown flag bits: CM_E_INVAL. */
-enum { CM_VMM_RAISED_SUMS = 1, CM_VMM_DIRECT_GIANTS = 2, CM_VMM_TOKEN_BATCH = 4 };
+enum { CM_VMM_RAISED_SUMS = 1, CM_VMM_DIRECT_GIANTS = 2, CM_VMM_TOKEN_BATCH = 4, CM_VMM_UNROLLED_LADDERS = 8 };
 cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
                                 int32_t level, double pt_scale, const double *W,
                                 const int64_t *coeffs, uint32_t flags, cm_vmm_plan **out);

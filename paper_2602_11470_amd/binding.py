@@ -18,7 +18,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 CM_QK, CM_SV = 0, 1
-CM_VMM_RAISED_SUMS, CM_VMM_DIRECT_GIANTS, CM_VMM_TOKEN_BATCH = 1, 2, 4
+CM_VMM_RAISED_SUMS, CM_VMM_DIRECT_GIANTS, CM_VMM_TOKEN_BATCH, CM_VMM_UNROLLED_LADDERS = 1, 2, 4, 8
 
 
 class cm_params(C.Structure):
@@ -293,9 +293,9 @@ class Context:
         return a.value, b.value, c.value
 
     def vmm_plan(self, d_in, d_out, W=None, level=None, r_i=0, tau=0, pt_scale=0.0, coeffs=None, raised_sums=False,
-                 direct_giants=False, token_batch=False):
+                 direct_giants=False, token_batch=False, unrolled_ladders=False):
         return VmmPlan(self, d_in, d_out, W, self.L if level is None else level, r_i, tau, pt_scale, coeffs,
-                       raised_sums, direct_giants, token_batch)
+                       raised_sums, direct_giants, token_batch, unrolled_ladders)
 
     def vmm_pt(self, evk, plan, x, out=None):
         out = out or Ct(self, x.level - 1)
@@ -362,12 +362,13 @@ class Evk:
 
 class VmmPlan:
     def __init__(self, ctx, d_in, d_out, W, level, r_i, tau, pt_scale, coeffs, raised_sums=False, direct_giants=False,
-                 token_batch=False):
+                 token_batch=False, unrolled_ladders=False):
         self.ctx, self.h, self.level = ctx, _vp(), level
+        direct_giants = direct_giants or unrolled_ladders
         raised_sums = raised_sums or direct_giants
         self.limbs = level + 1 + (ctx.K if raised_sums else 0)
         flags = (CM_VMM_RAISED_SUMS if raised_sums else 0) | (CM_VMM_DIRECT_GIANTS if direct_giants else 0) | \
-                (CM_VMM_TOKEN_BATCH if token_batch else 0)
+                (CM_VMM_TOKEN_BATCH if token_batch else 0) | (CM_VMM_UNROLLED_LADDERS if unrolled_ladders else 0)
         if coeffs is not None:
             c = _np(coeffs, np.int64)
             _chk(lib.cm_vmm_plan_create_ex(ctx.h, d_in, d_out, r_i, tau, level, pt_scale, None, c.ctypes.data,

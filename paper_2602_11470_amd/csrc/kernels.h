@@ -125,6 +125,9 @@ cm_status ks_raise_many(cm_ctx *ctx, const KsManyTables &t, const u64 *cts, u64 
 // second components only: outs[r] + (level+1)*n <- ModDown(us[r][1]); the first components of us (all their limbs)
 // and of outs are left as they are
 cm_status moddown_many_second(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *outs, hipStream_t st);
+// out + (level+1)*n <- ModDown(R[1]) for one R = [2][ext][n], which is left untouched (its special limbs are
+// transformed into a buffer of their own)
+cm_status moddown_second_keep(cm_ctx *ctx, const u64 *R, int level, u64 *out, hipStream_t st);
 cm_status moddown_many(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *outs, hipStream_t st);
 // one batch (m <= CM_KS_BATCH): outs[r] = ModDown(us + r*2*ext*n) + perm_g(addends[r]) on the first addend_comps
 // components (+ accums[r]); addends / accums nullable arrays of nullable pointers
@@ -133,7 +136,7 @@ cm_status moddown_batch_into(cm_ctx *ctx, u64 *us, int level, int m, const u64 *
 // raised[r][2][ext][n] = sum_j perm_{g_r}(digits_j) * key_r + P * perm_{g_r}(in.c0): hoisted rotations left in the
 // extended basis
 cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys,
-                               const u64 *gs, const u64 *in, u64 *const *raised, hipStream_t st);
+                               const u64 *gs, const u64 *in, u64 *const *raised, hipStream_t st, bool in_ext = false);
 // out[comp][level][n] = in[comp][level+1][n] divided by q_level; up to 2*CM_KS_BATCH stacked components when the
 // caller gives scratch last[ncomp][n] and red[ncomp][level][n] (up to three without)
 cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st, u64 *last = nullptr,

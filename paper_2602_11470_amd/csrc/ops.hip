@@ -48,6 +48,8 @@ struct KsLevelFull : KsLevel {
     int *d_last_rows = nullptr; // rows c*(level+1)+level of stacked components
     int *d_bsp_rows = nullptr, *d_bsp_mods = nullptr;   // special rows of CM_KS_BATCH stacked [2][ext] blocks
     int *d_bsp1_rows = nullptr;                         // those of the second components only
+    int *d_sp1_rows = nullptr;                          // special rows of the second component of one [2][ext] block
+    ConvDev *d_moddown0 = nullptr;                      // the ModDown conversion reading its K input limbs from rows 0..K-1
     int *d_bq_mods = nullptr;                           // 0..level repeated 2*CM_KS_BATCH times
     std::vector<int> h_ntt_rows, h_ntt_mods;            // host copies of d_ntt_rows / d_ntt_mods
     ConvDev *d_modup = nullptr; // one table per digit
@@ -158,6 +160,11 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
         for (int s = 0; s < ctx->K; s++) sp_in.push_back(level + 1 + s);
         std::vector<ConvDev> md(1, conv_dev(ctx, get_moddown(ctx, level), sp_in, q_rows));
         k.d_moddown = up(md);
+        std::vector<int> sp0, sp1;
+        for (int s = 0; s < ctx->K; s++) sp0.push_back(s), sp1.push_back(k.ext + level + 1 + s);
+        std::vector<ConvDev> md0(1, conv_dev(ctx, get_moddown(ctx, level), sp0, q_rows));
+        k.d_moddown0 = up(md0);
+        k.d_sp1_rows = up(sp1);
     }
     get_pinv(ctx, level);
     get_qlinv(ctx, level);
@@ -169,7 +176,7 @@ static void drop_ks_levels(cm_ctx *ctx) {
     for (auto it = g_ks.begin(); it != g_ks.end();) {
         if (it->first.first != ctx) { ++it; continue; }
         KsLevelFull &k = it->second;
-        hipFree(k.d_modup); hipFree(k.d_moddown); hipFree(k.d_bsp_rows); hipFree(k.d_bsp1_rows); hipFree(k.d_bsp_mods); hipFree(k.d_bq_mods);
+        hipFree(k.d_modup); hipFree(k.d_moddown); hipFree(k.d_bsp_rows); hipFree(k.d_bsp1_rows); hipFree(k.d_sp1_rows); hipFree(k.d_moddown0); hipFree(k.d_bsp_mods); hipFree(k.d_bq_mods);
         hipFree(k.d_last_rows);
         hipFree(k.d_ntt_rows); hipFree(k.d_ntt_mods); hipFree(k.d_sp_rows); hipFree(k.d_sp_mods);
         hipFree(k.d_q_rows); hipFree(k.d_q_mods3); hipFree(k.d_last_mods); hipFree(k.d_red_mods);
@@ -226,13 +233,14 @@ cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u6
     return moddown_into(ctx, A.u, level, addend, addend_comps, g, out, accum, st);
 }
 cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys,
-                               const u64 *gs, const u64 *in, u64 *const *raised, hipStream_t st) {
+                               const u64 *gs, const u64 *in, u64 *const *raised, hipStream_t st, bool in_ext) {
     const KsLevelFull &k = ks_level_full(ctx, level);
     for (int base = 0; base < cnt; base += IP_MAX_ITEMS) {
         IpBatch b;
         b.nz = cnt - base < IP_MAX_ITEMS ? cnt - base : IP_MAX_ITEMS, b.nsum = 1;
         for (int r = 0; r < b.nz; r++) {
             b.it[r].dig = digits, b.it[r].key = keys[base + r], b.it[r].c0 = in, b.it[r].g = (unsigned)gs[base + r];
+            b.it[r].c0_ext = in_ext ? 1 : 0;
             b.out[r] = raised[base + r], b.extra[r] = nullptr;
         }
         launch_inner_product_batch(ctx, b, k.beta, level, st);
@@ -316,6 +324,27 @@ cm_status moddown_many_second(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *con
         fb.pinv = get_pinv(ctx, level);
         launch_ntt_fwd_finish(ctx, A.bconv, k.d_bq_mods, fb, st);
     }
+    return CM_OK;
+}
+
+cm_status moddown_second_keep(cm_ctx *ctx, const u64 *R, int level, u64 *out, hipStream_t st) {
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    Arena A = arena_of(ctx);
+    const size_t n = ctx->n;
+    // the K special limbs of the second component, to the coefficient domain in a buffer of their own
+    launch_ntt_src(ctx, A.conv, nullptr, R, k.d_sp1_rows, k.d_sp_mods, ctx->K, true, st, 0);
+    launch_base_conv(ctx, k.d_moddown0, 1, 0, level + 1, A.bconv, A.conv, 0, 0, nullptr, 0, st);
+    if (ctx->n != 65536) {
+        launch_ntt(ctx, A.bconv, k.d_bq_mods, level + 1, false, st);
+        launch_moddown_finish(ctx, out + (size_t)(level + 1) * n, R + (size_t)k.ext * n, A.bconv, get_pinv(ctx, level), nullptr, 0,
+                              level, 0, nullptr, st, 1);
+        return CM_OK;
+    }
+    FinishBatch fb;
+    fb.items = 1, fb.level = level, fb.ext = k.ext, fb.addend_comps = 0, fb.ncomp = 1, fb.comp0 = 1;
+    for (int r = 0; r < CM_KS_BATCH; r++) fb.addend[r] = nullptr, fb.accum[r] = nullptr, fb.u[r] = nullptr, fb.out[r] = nullptr, fb.g[r] = 0;
+    fb.u[0] = R, fb.out[0] = out, fb.pinv = get_pinv(ctx, level);
+    launch_ntt_fwd_finish(ctx, A.bconv, k.d_bq_mods, fb, st);
     return CM_OK;
 }
 

@@ -27,6 +27,8 @@ struct cm_vmm_plan {
     int giant_step;
     bool raised = false;       // sums of the baby steps stay in the extended basis (one ModDown per giant step)
     bool direct = false;       // giant steps unrolled: independent rotations by k*giant_step, one shared ModDown
+    bool unrolled = false;     // the two rotate-and-add ladders unrolled too; the whole product in the extended basis
+    std::vector<std::vector<int>> pre_groups, reduce_groups;   // rotation amounts of each run of <= 3 ladder steps
     KsManyTables many;         // direct: tables for raising the r_o - 1 inner sums at once
     u64 *d_many = nullptr;     // direct: r_o - 1 ciphertexts, their coefficient-domain c1 and their raised digits
     int pt_limbs;              // level+1, or level+1+K when raised
@@ -115,9 +117,28 @@ static void diag_slots(const cm_vmm_plan *p, const std::vector<int> &lab, const 
     }
 }
 
-static cm_status plan_alloc(cm_vmm_plan *p, bool raised, bool direct) {
+// A ladder c <- c + Rot(c, s_l) over a run of steps equals c + the rotations of c by every non-empty
+// subset sum of the run; runs of at most three steps (seven rotations of one ciphertext).
+static std::vector<std::vector<int>> ladder_groups(const std::vector<int> &steps) {
+    std::vector<std::vector<int>> out;
+    for (size_t i = 0; i < steps.size(); i += 3) {
+        const size_t g = steps.size() - i < 3 ? steps.size() - i : 3;
+        std::vector<int> amounts;
+        for (unsigned b = 1; b < (1u << g); b++) {
+            int a = 0;
+            for (size_t l = 0; l < g; l++)
+                if ((b >> l) & 1) a += steps[i + l];
+            amounts.push_back(a);
+        }
+        out.push_back(amounts);
+    }
+    return out;
+}
+
+static cm_status plan_alloc(cm_vmm_plan *p, bool raised, bool direct, bool unrolled) {
     cm_ctx *ctx = p->ctx;
-    p->raised = raised, p->direct = direct;
+    p->raised = raised, p->direct = direct, p->unrolled = unrolled;
+    if (unrolled) p->pre_groups = ladder_groups(p->pre_steps), p->reduce_groups = ladder_groups(p->reduce_steps);
     p->pt_limbs = p->level + 1 + (raised ? ctx->K : 0);
     std::vector<int> mods;
     for (int i = 0; i <= p->level; i++) mods.push_back(i);
@@ -126,7 +147,8 @@ static cm_status plan_alloc(cm_vmm_plan *p, bool raised, bool direct) {
     if (hipMalloc((void **)&p->d_pt_mods, mods.size() * sizeof(int)) != hipSuccess) return CM_E_NOMEM;
     if (hipMemcpy(p->d_pt_mods, mods.data(), mods.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess) return CM_E_HIP;
     if (hipMalloc((void **)&p->d_pts, (size_t)p->M * ptw * 8) != hipSuccess) return CM_E_NOMEM;
-    if (hipMalloc((void **)&p->d_work, ((size_t)(p->r_i + p->r_o) * 2 * ptw + 3 * ctw) * 8) != hipSuccess) return CM_E_NOMEM;
+    // r_i baby + r_o inner ciphertexts, 3 temporaries on the ciphertext limbs, one more on the plaintext limbs
+    if (hipMalloc((void **)&p->d_work, ((size_t)(p->r_i + p->r_o + 1) * 2 * ptw + 3 * ctw) * 8) != hipSuccess) return CM_E_NOMEM;
     if (direct && p->r_o > 1) {
         const KsLevel &k = ks_level(ctx, p->level);
         const size_t cnt = p->r_o - 1, per = ctw + (size_t)(p->level + 1) * n + (size_t)k.beta * k.ext * n;
@@ -154,13 +176,14 @@ extern "C" cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_
                                            int32_t level, double pt_scale, const double *W, const int64_t *coeffs,
                                            uint32_t flags, cm_vmm_plan **out) {
     if (!ctx || (!W == !coeffs) || !out ||
-        (flags & ~(uint32_t)(CM_VMM_RAISED_SUMS | CM_VMM_DIRECT_GIANTS | CM_VMM_TOKEN_BATCH)))
+        (flags & ~(uint32_t)(CM_VMM_RAISED_SUMS | CM_VMM_DIRECT_GIANTS | CM_VMM_TOKEN_BATCH | CM_VMM_UNROLLED_LADDERS)))
         return CM_E_INVAL;
-    const bool direct = (flags & CM_VMM_DIRECT_GIANTS) != 0, raised = direct || (flags & CM_VMM_RAISED_SUMS) != 0;
+    const bool unrolled = (flags & CM_VMM_UNROLLED_LADDERS) != 0;
+    const bool direct = unrolled || (flags & CM_VMM_DIRECT_GIANTS) != 0, raised = direct || (flags & CM_VMM_RAISED_SUMS) != 0;
     cm_vmm_plan *p = new (std::nothrow) cm_vmm_plan();
     if (!p) return CM_E_NOMEM;
     cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, (flags & CM_VMM_TOKEN_BATCH) != 0, p);
-    if (s == CM_OK) s = plan_alloc(p, raised, direct);
+    if (s == CM_OK) s = plan_alloc(p, raised, direct, unrolled);
     if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
     if (coeffs) {
         for (int idx = 0; idx < p->M && s == CM_OK; idx++) s = plan_load_diag(p, idx, coeffs + (size_t)idx * ctx->n);
@@ -214,13 +237,20 @@ extern "C" void cm_vmm_plan_destroy(cm_vmm_plan *plan) {
     delete plan;
 }
 
-extern "C" int32_t cm_vmm_plan_steps(const cm_vmm_plan *p, int32_t *steps, int32_t cap) {
-    if (!p) return 0;
-    std::vector<int> all(p->pre_steps);
+static std::vector<int> plan_all_steps(const cm_vmm_plan *p) {
+    std::vector<int> all;
+    if (p->unrolled) for (const auto &g : p->pre_groups) all.insert(all.end(), g.begin(), g.end());
+    else all = p->pre_steps;
     for (int j = 1; j < p->r_i; j++) all.push_back(p->baby_steps[j]);
     for (int k = 1; k < p->r_o; k++)
         if (k == 1 || p->direct) all.push_back(k * p->giant_step);
-    all.insert(all.end(), p->reduce_steps.begin(), p->reduce_steps.end());
+    if (p->unrolled) for (const auto &g : p->reduce_groups) all.insert(all.end(), g.begin(), g.end());
+    else all.insert(all.end(), p->reduce_steps.begin(), p->reduce_steps.end());
+    return all;
+}
+extern "C" int32_t cm_vmm_plan_steps(const cm_vmm_plan *p, int32_t *steps, int32_t cap) {
+    if (!p) return 0;
+    std::vector<int> all = plan_all_steps(p);
     for (int i = 0; i < (int)all.size() && i < cap && steps; i++) steps[i] = all[i];
     return (int32_t)all.size();
 }
@@ -228,7 +258,15 @@ extern "C" cm_status cm_vmm_plan_info(const cm_vmm_plan *p, int32_t *r_i, int32_
     if (!p) return CM_E_INVAL;
     if (r_i) *r_i = p->r_i;
     if (r_o) *r_o = p->r_o;
-    if (n_rot) *n_rot = (int)p->pre_steps.size() + (p->r_i - 1) + (p->r_o - 1) + (int)p->reduce_steps.size();
+    if (n_rot) {
+        size_t ladders = p->pre_steps.size() + p->reduce_steps.size();
+        if (p->unrolled) {
+            ladders = 0;
+            for (const auto &g : p->pre_groups) ladders += g.size();
+            for (const auto &g : p->reduce_groups) ladders += g.size();
+        }
+        *n_rot = (int)ladders + (p->r_i - 1) + (p->r_o - 1);
+    }
     return CM_OK;
 }
 extern "C" cm_status cm_vmm_plan_diag_export(cm_ctx *ctx, const cm_vmm_plan *p, int32_t j, int32_t k, uint64_t *out) {
@@ -254,6 +292,54 @@ static cm_status vmm_raised_babies(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_
     auto key_of = [&](int step) { return find_key(evk, galois_of_step(ctx, step)); };
     u64 *babies = p->d_work, *inner = babies + (size_t)p->r_i * rw, *t0 = inner + (size_t)p->r_o * rw;
     u64 *t1 = t0 + ctw;
+    if (p->unrolled) {
+        // The whole product stays in the extended basis.  R = (P c0, P c1); every run of the preprocess ladder adds
+        // the hoisted rotations of R by its subset sums (one raise of ModDown(R1), one launch summing all of them
+        // with sigma(R0) and R itself), between two buffers so that the last run ends in baby slot 0.
+        u64 *spare = t0 + 3 * ctw;
+        const size_t ngroups = p->pre_groups.size();
+        u64 *cur = (ngroups & 1) ? spare : babies, *nxt = (ngroups & 1) ? babies : spare;
+        launch_raise_by_P(ctx, cur, x->dev, level, st);
+        const KsLevel &kl = ks_level(ctx, level);
+        for (size_t gi = 0; gi < ngroups; gi++) {
+            const u64 *c1 = x->dev + ptw;                     // ModDown(P c1) = c1 exactly
+            if (gi) {
+                CMCHK(moddown_second_keep(ctx, cur, level, t0, st));
+                c1 = t0 + ptw;
+            }
+            u64 *digits = arena_digits(ctx);
+            CMCHK(ks_raise(ctx, c1, level, digits, st));
+            IpBatch b;
+            b.nz = 1, b.nsum = (int)p->pre_groups[gi].size();
+            for (int s = 0; s < b.nsum; s++) {
+                const int a = p->pre_groups[gi][s];
+                b.it[s].dig = digits, b.it[s].key = key_of(a), b.it[s].c0 = cur, b.it[s].c0_ext = 1;
+                b.it[s].g = (unsigned)galois_of_step(ctx, a);
+            }
+            b.out[0] = nxt, b.extra[0] = cur;
+            launch_inner_product_batch(ctx, b, kl.beta, level, st);
+            std::swap(cur, nxt);
+        }
+        if (p->r_i > 1) {
+            const u64 *c1 = x->dev + ptw;
+            if (ngroups) {
+                CMCHK(moddown_second_keep(ctx, babies, level, t0, st));
+                c1 = t0 + ptw;
+            }
+            u64 *digits = arena_digits(ctx);
+            CMCHK(ks_raise(ctx, c1, level, digits, st));
+            std::vector<const u64 *> keys;
+            std::vector<u64> gs;
+            std::vector<u64 *> dst;
+            for (int j = 1; j < p->r_i; j++) {
+                keys.push_back(key_of(p->baby_steps[j]));
+                gs.push_back(galois_of_step(ctx, p->baby_steps[j]));
+                dst.push_back(babies + (size_t)j * rw);
+            }
+            CMCHK(ks_apply_many_raised(ctx, digits, level, p->r_i - 1, keys.data(), gs.data(), babies, dst.data(), st, true));
+        }
+        return CM_OK;
+    }
     // 1. preprocess (rotate-and-add between two buffers)
     u64 *c = t0, *other = t1;
     HIPCHK(hipMemcpyAsync(c, x->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
@@ -314,7 +400,26 @@ static cm_status vmm_raised_finish(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_
             b.out[0] = inner, b.extra[0] = inner;
             launch_inner_product_batch(ctx, b, kl.beta, level, st);
         }
-        CMCHK(moddown_into(ctx, inner, level, nullptr, 0, 0, acc, nullptr, st));
+        u64 *total = inner;
+        if (p->unrolled) {
+            // the reduce ladder, run by run, still in the extended basis (between inner_0 and the spare buffer)
+            u64 *spare = t0 + 3 * ctw, *nxt = spare;
+            for (const auto &grp : p->reduce_groups) {
+                CMCHK(moddown_second_keep(ctx, total, level, t0, st));
+                u64 *digits = arena_digits(ctx);
+                CMCHK(ks_raise(ctx, t0 + (size_t)limbs * n, level, digits, st));
+                IpBatch b;
+                b.nz = 1, b.nsum = (int)grp.size();
+                for (int s = 0; s < b.nsum; s++) {
+                    b.it[s].dig = digits, b.it[s].key = key_of(grp[s]), b.it[s].c0 = total, b.it[s].c0_ext = 1;
+                    b.it[s].g = (unsigned)galois_of_step(ctx, grp[s]);
+                }
+                b.out[0] = nxt, b.extra[0] = total;
+                launch_inner_product_batch(ctx, b, kl.beta, level, st);
+                std::swap(total, nxt);
+            }
+        }
+        CMCHK(moddown_into(ctx, total, level, nullptr, 0, 0, acc, nullptr, st));
     } else {
         // giant steps, Horner form: acc <- Rot(acc) + ModDown-ed inner_k in one key switch
         CMCHK(moddown_into(ctx, inner + (size_t)(r_o - 1) * rw, level, nullptr, 0, 0, acc, nullptr, st));
@@ -326,6 +431,7 @@ static cm_status vmm_raised_finish(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_
     }
     // 3. reduce inside the ciphertext
     for (int r : p->reduce_steps) {
+        if (p->unrolled) break;                               // done above, before the ModDown
         CMCHK(rotate_into(ctx, key_of(r), acc, level, galois_of_step(ctx, r), other, st, acc));
         std::swap(acc, other);
     }
@@ -342,11 +448,7 @@ static cm_status vmm_pt_raised(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
 
 static cm_status plan_keys_present(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p) {
     auto key_of = [&](int step) { return find_key(evk, galois_of_step(ctx, step)); };
-    for (int r : p->pre_steps) if (!key_of(r)) return CM_E_NOKEY;
-    for (int j = 1; j < p->r_i; j++) if (!key_of(p->baby_steps[j])) return CM_E_NOKEY;
-    for (int k = 1; k < p->r_o; k++)
-        if ((k == 1 || p->direct) && !key_of(k * p->giant_step)) return CM_E_NOKEY;
-    for (int r : p->reduce_steps) if (!key_of(r)) return CM_E_NOKEY;
+    for (int r : plan_all_steps(p)) if (!key_of(r)) return CM_E_NOKEY;
     return CM_OK;
 }
 
@@ -359,7 +461,7 @@ extern "C" cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vm
         const cm_vmm_plan *p = plans[i];
         if (!p || p->ctx != ctx || !ys[i] || !ys[i]->dev || !p->raised) return CM_E_INVAL;
         if (p->level != p0->level || p->d_in != p0->d_in || p->d_out != p0->d_out || p->r_i != p0->r_i ||
-            p->tokens != p0->tokens)
+            p->tokens != p0->tokens || p->unrolled != p0->unrolled)
             return CM_E_LAYOUT;
         for (int j = 0; j < i; j++)
             if (plans[j] == p) return CM_E_INVAL;         // a plan's work area holds one product at a time

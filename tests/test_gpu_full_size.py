@@ -69,17 +69,19 @@ def test_config2_chain_keys_and_single_operations(ring2):
     assert np.abs(gctx.decrypt(gsk, gm).real - z * z).max() < 1e-6
 
 
-@pytest.mark.parametrize("form", ["plain", "raised", "direct"])
+@pytest.mark.parametrize("form", ["plain", "raised", "direct", "unrolled"])
 def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden, form):
-    """52 rotations, 512 plaintext multiply-accumulates at (S, d) = (32768, 4096); the expected
-    ciphertext was written by tests/golden/make_vmm_full_size_golden.py from the oracle, for the
-    algorithm as printed and for the form that keeps the baby-step sums in the extended basis
-    (the configuration bench.py times)."""
+    """52 rotations (60 with the ladders unrolled), 512 plaintext multiply-accumulates at (S, d) =
+    (32768, 4096); the expected ciphertext was written by tests/golden/make_vmm_full_size_golden.py
+    from the oracle, for the algorithm as printed, for the form that keeps the baby-step sums in the
+    extended basis, for that with the giant steps unrolled, and for that with the two ladders
+    unrolled as well (the configuration bench.py times)."""
     import importlib.util
     import os
     B, octx, gctx, prm = ring2
-    raised, direct = form != "plain", form == "direct"
-    g = golden({"plain": "vmm_full_size.txt", "raised": "vmm_full_size_raised.txt", "direct": "vmm_full_size_direct.txt"}[form])
+    raised, direct, unrolled = form != "plain", form == "direct", form == "unrolled"
+    g = golden({"plain": "vmm_full_size.txt", "raised": "vmm_full_size_raised.txt", "direct": "vmm_full_size_direct.txt",
+                "unrolled": "vmm_full_size_unrolled.txt"}[form])
     spec = importlib.util.spec_from_file_location(
         "mk", os.path.join(os.path.dirname(__file__), "golden", "make_vmm_full_size_golden.py"))
     mk = importlib.util.module_from_spec(spec)
@@ -88,8 +90,9 @@ def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden,
     plan = packing.make_plan(octx.S, mk.D, mk.D)
     xc, diag = mk.integer_inputs(octx.n, plan)
     gplan = gctx.vmm_plan(mk.D, mk.D, level=prm.L, r_i=plan.r_i, coeffs=np.stack(diag), pt_scale=prm.scale,
-                          raised_sums=raised, direct_giants=direct)
-    assert gplan.n_rotations == int(g["rotations"]) == 52 and gplan.r_i * gplan.r_o == int(g["pt_mults"]) == 512
+                          raised_sums=raised, direct_giants=direct, unrolled_ladders=unrolled)
+    assert gplan.n_rotations == int(g["rotations"]) == (60 if unrolled else 52)
+    assert gplan.r_i * gplan.r_o == int(g["pt_mults"]) == 512
     gsk = gctx.keygen_secret(mk.SEED_SK)
     gkeys = gctx.keygen_rotations(gsk, gplan.steps(), mk.SEED_EVK)
     gx = gctx.encrypt(gsk, gctx.pt_from_coeffs(xc, prm.L, prm.scale), mk.SEED_ENC)
@@ -149,8 +152,8 @@ def test_other_widths_and_levels_decrypt_to_float64_product(ring2, d, level, rot
         x[768:] = 0.0
         W[768:, :] = 0.0
         W[:, 768:] = 0.0
-    gplan = gctx.vmm_plan(d, d, W=W, level=level, direct_giants=True)
-    assert gplan.n_rotations == rotations
+    gplan = gctx.vmm_plan(d, d, W=W, level=level, unrolled_ladders=True)
+    assert gplan.r_i - 1 + gplan.r_o - 1 + 2 * int(np.log2(gctx.S // d)) == rotations     # as Algorithm 1 counts them
     gsk = gctx.keygen_secret(1)
     gkeys = gctx.keygen_rotations(gsk, gplan.steps(), 2)
     t = gctx.S // d
@@ -179,8 +182,9 @@ def test_config4_mlp_projection_shapes_decrypt_to_float64_product(ring2, d_in, d
     else:
         W[:, real:] = 0.0
     plan = packing.make_plan(octx.S, d_in, d_out)
-    gplan = gctx.vmm_plan(d_in, d_out, W=W, level=level, direct_giants=True)
-    assert (gplan.r_i, gplan.r_o, gplan.n_rotations) == (plan.r_i, plan.r_o, plan.n_rotations) == (64, 32, 98)
+    gplan = gctx.vmm_plan(d_in, d_out, W=W, level=level, unrolled_ladders=True)
+    assert (gplan.r_i, gplan.r_o, plan.n_rotations) == (plan.r_i, plan.r_o, 98)
+    assert gplan.n_rotations == 98 - (3 + 1) + (7 + 1)            # the three-step ladder becomes seven hoisted rotations
     gsk = gctx.keygen_secret(1)
     gkeys = gctx.keygen_rotations(gsk, gplan.steps(), 2)
     gx = gctx.level_drop(gctx.encrypt(gsk, gctx.encode(plan.pack_input(x), gctx.L), 3), level)
@@ -307,8 +311,8 @@ def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
         gsk = gctx.keygen_secret(1)
         cache_lv = L - 3                     # projection, rotary embedding, append mask: one level each
         kv = gctx.kv_create(H, E, cache_lv, r_i=16)
-        plan_q = gctx.vmm_plan(d, d, W=Wq_p, level=L, direct_giants=True)
-        plan_o = gctx.vmm_plan(d, d, W=Wo_p, level=cache_lv - 2, direct_giants=True)
+        plan_q = gctx.vmm_plan(d, d, W=Wq_p, level=L, unrolled_ladders=True)
+        plan_o = gctx.vmm_plan(d, d, W=Wo_p, level=cache_lv - 2, unrolled_ladders=True)
         residue0 = np.zeros(gctx.S)
         residue0[::t] = 1.0
 
@@ -347,8 +351,8 @@ def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
             slots[::t] = x
             gx = enc(slots, L, 500 + step)
             # k and v land on residue tau, ready for the append
-            plan_k = gctx.vmm_plan(d, d, W=Wk_p, level=L, tau=tau, direct_giants=True)
-            plan_v = gctx.vmm_plan(d, d, W=Wv_p, level=L, tau=tau, direct_giants=True)
+            plan_k = gctx.vmm_plan(d, d, W=Wk_p, level=L, tau=tau, unrolled_ladders=True)
+            plan_v = gctx.vmm_plan(d, d, W=Wv_p, level=L, tau=tau, unrolled_ladders=True)
             gk = gctx.vmm_pt(gkeys, plan_k, gx)
             gv = gctx.vmm_pt(gkeys, plan_v, gx)
             k_ref = rope_ref((x @ Wk8).reshape(8, E).repeat(4, axis=0), n)          # [h, e]

@@ -80,9 +80,9 @@ def test_vmm_pt_matches_oracle_and_float64(env, d_in, d_out, level, r_i, tau, se
     assert np.abs(plan.unpack_output(out2.real) - x @ W).max() < TOL
 
 
-def _raised_case(e, d_in, d_out, level, r_i, tau, seed, direct=False):
+def _raised_case(e, d_in, d_out, level, r_i, tau, seed, direct=False, unrolled=False):
     """vmm_pt with the baby-step sums kept in the extended basis (and, with direct, the giant steps
-    unrolled) against the oracle's form of it."""
+    unrolled; with unrolled, the two ladders as well) against the oracle's form of it."""
     from oracle import packing, vmm
     from paper_2602_11470_amd import inputs
     octx, gctx = e["octx"], e["gctx"]
@@ -93,10 +93,13 @@ def _raised_case(e, d_in, d_out, level, r_i, tau, seed, direct=False):
     odiags = [[octx.pt_from_coeffs_ext(c, level, scale) for c in row] for row in diag_coeffs]
     flat = np.stack([c for row in diag_coeffs for c in row])
     gplan = gctx.vmm_plan(d_in, d_out, level=level, r_i=plan.r_i, tau=tau, coeffs=flat, raised_sums=True,
-                          direct_giants=direct)
-    assert (gplan.r_i, gplan.r_o, gplan.n_rotations) == (plan.r_i, plan.r_o, plan.n_rotations)
-    steps = vmm.direct_giant_steps(plan) if direct else plan.all_steps()
-    assert sorted(set(gplan.steps())) == sorted(set(steps)) and (not direct or len(gplan.steps()) == plan.n_rotations)
+                          direct_giants=direct, unrolled_ladders=unrolled)
+    steps = vmm.unrolled_steps(plan) if unrolled else vmm.direct_giant_steps(plan) if direct else plan.all_steps()
+    assert (gplan.r_i, gplan.r_o) == (plan.r_i, plan.r_o)
+    assert gplan.n_rotations == (len(steps) if unrolled else plan.n_rotations)
+    assert sorted(set(gplan.steps())) == sorted(set(steps)) and (not direct or unrolled or len(gplan.steps()) == plan.n_rotations)
+    if unrolled:
+        assert gplan.steps() == steps
     # the plaintexts live on level+1+K limbs
     ext = octx.ext_idx(level)
     j, k = plan.r_i - 1, plan.r_o - 1
@@ -104,7 +107,8 @@ def _raised_case(e, d_in, d_out, level, r_i, tau, seed, direct=False):
     okeys = octx.keygen_rotations(e["osk"], steps, 2)
     gkeys = gctx.keygen_rotations(e["gsk"], gplan.steps(), 2)
     ox, gx = _enc_both(e, plan.pack_input(x), level, 3)
-    oy = (vmm.vmm_pt_direct_giants if direct else vmm.vmm_pt_double_hoisted)(octx, okeys, plan, ox, odiags)
+    fn = vmm.vmm_pt_unrolled if unrolled else vmm.vmm_pt_direct_giants if direct else vmm.vmm_pt_double_hoisted
+    oy = fn(octx, okeys, plan, ox, odiags)
     gy = gctx.vmm_pt(gkeys, gplan, gx)
     _same(e, oy, gy)
     out = gctx.decrypt(e["gsk"], gy)
@@ -137,6 +141,19 @@ def test_vmm_pt_direct_giants_matches_oracle_and_float64(env, d_in, d_out, level
     _raised_case(env, d_in, d_out, level, r_i, tau, seed, direct=True)
 
 
+@pytest.mark.parametrize("d_in,d_out,level,r_i,tau,seed", [
+    (64, 64, 4, 0, 0, 0),          # t = 32: five-step ladders before and after, runs of three and two
+    (64, 64, 2, 1, 0, 1),          # no baby steps
+    (512, 512, 3, 4, 0, 2),        # t = 4: two-step ladders; 31 unrolled giant steps
+    (128, 512, 4, 0, 0, 3),        # expanding: preprocess ladder of four steps, reduce ladder of two
+    (512, 128, 1, 0, 0, 4),        # contracting
+    (128, 128, 4, 2, 5, 5),        # output on residue 5: right rotations in the reduce ladder
+    (2048, 2048, 3, 0, 0, 6),      # t = 1: no ladders at all
+])
+def test_vmm_pt_unrolled_ladders_matches_oracle_and_float64(env, d_in, d_out, level, r_i, tau, seed):
+    _raised_case(env, d_in, d_out, level, r_i, tau, seed, direct=True, unrolled=True)
+
+
 @pytest.mark.parametrize("direct", [False, True])
 @pytest.mark.parametrize("level", [5, 4, 2])
 def test_vmm_pt_raised_sums_with_two_primes_per_digit(level, direct):
@@ -155,7 +172,7 @@ def test_vmm_pt_raised_sums_with_two_primes_per_digit(level, direct):
         gctx.close()
 
 
-@pytest.mark.parametrize("direct", [False, True])
+@pytest.mark.parametrize("direct", [False, True, "unrolled"])
 def test_vmm_pt_replays_from_a_captured_graph(env, direct):
     """cm_vmm_pt only enqueues kernels and device copies on the caller's stream, so it can be
     captured into a HIP graph: every replay (with eager work in between) reproduces the eager
@@ -165,7 +182,8 @@ def test_vmm_pt_replays_from_a_captured_graph(env, direct):
     e = env
     gctx = e["gctx"]
     x, W = inputs.vmm_inputs(9, 256, 256, "uniform", 0.05)
-    gplan = gctx.vmm_plan(256, 256, W=W, level=3, raised_sums=direct, direct_giants=direct)
+    gplan = gctx.vmm_plan(256, 256, W=W, level=3, raised_sums=bool(direct), direct_giants=bool(direct),
+                          unrolled_ladders=direct == "unrolled")
     gkeys = gctx.keygen_rotations(e["gsk"], gplan.steps(), 2)
     slots = np.zeros(gctx.S)
     slots[::gctx.S // 256] = x
@@ -251,7 +269,7 @@ def test_vmm_pt_degenerate_shapes(env, d_in, d_out):
     ox, gx = _enc_both(e, plan.pack_input(x), level, 3)
     for form in ("plain", "raised", "direct"):
         gplan = gctx.vmm_plan(d_in, d_out, level=level, r_i=plan.r_i, coeffs=flat,
-                              raised_sums=form != "plain", direct_giants=form == "direct")
+                              raised_sums=form != "plain", direct_giants=form == "direct", unrolled_ladders=form == "unrolled")
         assert gplan.n_rotations == plan.n_rotations
         if form == "plain":
             odiags = [[octx.pt_from_coeffs(c, level, scale) for c in row] for row in diag_coeffs]
@@ -265,7 +283,7 @@ def test_vmm_pt_degenerate_shapes(env, d_in, d_out):
         assert np.abs(plan.unpack_output(gctx.decrypt(e["gsk"], gy).real) - x @ W).max() < TOL
 
 
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(16))
 def test_vmm_pt_seeded_sweep_of_shapes_levels_and_forms(env, seed):
     """Shapes, levels, baby-step counts, residues and forms drawn from a seeded generator; every
     case limb for limb against the oracle, and run twice (a race would show as a difference)."""
@@ -283,30 +301,34 @@ def test_vmm_pt_seeded_sweep_of_shapes_levels_and_forms(env, seed):
     r_i = int(rng.choice([r for r in (1, 2, 4, 8, 16, 32) if plan0.M % r == 0 and r <= plan0.M]))
     tau = int(rng.integers(0, plan0.t2))
     form = str(rng.choice(["plain", "raised", "direct"]))
+    if seed >= 10:
+        form = "unrolled"
     plan = packing.make_plan(octx.S, d_in, d_out, r_i, tau)
     x, W = inputs.vmm_inputs(seed, d_in, d_out, "uniform", 0.05)
     scale = octx.prm.scale
     diag_coeffs = [[octx.encode_coeffs(v, scale) for v in row] for row in plan.diagonals(W)]
     flat = np.stack([c for row in diag_coeffs for c in row])
-    steps = sorted(set(vmm.direct_giant_steps(plan) if form == "direct" else plan.all_steps()))
+    steps = sorted(set(vmm.unrolled_steps(plan) if form == "unrolled" else
+                       vmm.direct_giant_steps(plan) if form == "direct" else plan.all_steps()))
     okeys = octx.keygen_rotations(e["osk"], steps, 2) if steps else {}
     gkeys = gctx.keygen_rotations(e["gsk"], steps, 2)
     ox, gx = _enc_both(e, plan.pack_input(x), level, 3)
     gplan = gctx.vmm_plan(d_in, d_out, level=level, r_i=r_i, tau=tau, coeffs=flat,
-                          raised_sums=form != "plain", direct_giants=form == "direct")
+                          raised_sums=form != "plain", direct_giants=form == "direct", unrolled_ladders=form == "unrolled")
     if form == "plain":
         odiags = [[octx.pt_from_coeffs(c, level, scale) for c in row] for row in diag_coeffs]
         oy = vmm.vmm_pt(vmm.CkksOps(octx, okeys), plan, ox, odiags)
     else:
         odiags = [[octx.pt_from_coeffs_ext(c, level, scale) for c in row] for row in diag_coeffs]
-        oy = (vmm.vmm_pt_direct_giants if form == "direct" else vmm.vmm_pt_double_hoisted)(octx, okeys, plan, ox, odiags)
+        fn = {"raised": vmm.vmm_pt_double_hoisted, "direct": vmm.vmm_pt_direct_giants, "unrolled": vmm.vmm_pt_unrolled}[form]
+        oy = fn(octx, okeys, plan, ox, odiags)
     gy = gctx.vmm_pt(gkeys, gplan, gx)
     _same(e, oy, gy)
     assert np.array_equal(gctx.ct_export(gctx.vmm_pt(gkeys, gplan, gx)), gctx.ct_export(gy))
     assert np.abs(plan.unpack_output(gctx.decrypt(e["gsk"], gy).real) - x @ W).max() < TOL, (d_in, d_out, level, r_i, tau, form)
 
 
-@pytest.mark.parametrize("direct", [False, True])
+@pytest.mark.parametrize("direct", [False, True, "unrolled"])
 def test_vmm_pt_multi_shares_baby_steps_and_equals_single_products(env, direct):
     """Three projections of one input (different weights, one of them landing on another residue):
     each output of the shared-baby-step call is bit for bit the single product's."""
@@ -316,8 +338,8 @@ def test_vmm_pt_multi_shares_baby_steps_and_equals_single_products(env, direct):
     d, level = 256, 3
     x, _ = inputs.vmm_inputs(20, d, d, "uniform", 0.05)
     Ws = [inputs.vmm_inputs(21 + i, d, d, "uniform", 0.05)[1] for i in range(3)]
-    plans = [gctx.vmm_plan(d, d, W=W, level=level, tau=(3 if i == 1 else 0), raised_sums=True, direct_giants=direct)
-             for i, W in enumerate(Ws)]
+    plans = [gctx.vmm_plan(d, d, W=W, level=level, tau=(3 if i == 1 else 0), raised_sums=True, direct_giants=bool(direct),
+                           unrolled_ladders=direct == "unrolled") for i, W in enumerate(Ws)]
     steps = sorted(set(sum((p.steps() for p in plans), [])))
     gkeys = gctx.keygen_rotations(e["gsk"], steps, 2)
     slots = np.zeros(gctx.S)
@@ -398,7 +420,7 @@ def test_vmm_pt_missing_key_and_level_errors(env):
         gctx.vmm_plan(32, 32, W=np.zeros((32, 32)), level=3)       # d^2 < S: less than one diagonal
     assert err.value.status == -5
     h, w = B._vp(), np.zeros((64, 64))
-    status = B.lib.cm_vmm_plan_create_ex(gctx.h, 64, 64, 0, 0, 3, 0.0, w.ctypes.data, None, 8, B.C.byref(h))
+    status = B.lib.cm_vmm_plan_create_ex(gctx.h, 64, 64, 0, 0, 3, 0.0, w.ctypes.data, None, 1 << 10, B.C.byref(h))
     assert status == -1 and not h.value                            # unknown flag bit
     status = B.lib.cm_vmm_plan_create_ex(gctx.h, 64, 64, 0, 0, 3, 0.0, None, None, 0, B.C.byref(h))
     assert status == -1                                            # neither W nor coefficients
