@@ -193,8 +193,9 @@ cm_status cm_vmm_plan_create_from_coeffs(cm_ctx *ctx, int32_t d_in, int32_t d_ou
  *     square ones, cm_vmm_pt_multi shares their baby steps), tau = 0.  Combines with the other two.
  *   CM_VMM_UNROLLED_LADDERS  (implies CM_VMM_DIRECT_GIANTS) the two rotate-and-add ladders of
  *     Algorithm 1 (preprocess: c <- c + Rot(c, 2^i (t-1)); reduce: c <- c + Rot(c, +-2^l)) are unrolled
- *     in runs of three steps: a run equals c + the rotations of c by the seven non-empty subset sums
- *     of its steps, which are rotations of ONE ciphertext and share its raised digits.  The whole
+ *     in ceil(L/3) runs of as equal length as possible: a run of g steps equals c + the rotations of
+ *     c by the 2^g - 1 non-empty subset sums of its steps, which are rotations of ONE ciphertext and
+ *     share its raised digits.  The whole
  *     product then stays in the extended basis: one ModDown of both components at its end, second
  *     components alone divided by P where digits are needed.  More rotations and keys (7 per run of
  *     three steps instead of 3; cm_vmm_plan_steps lists them), fewer ModUps and ModDowns.

@@ -169,11 +169,17 @@ LADDER_GROUP = 3
 def ladder_groups(steps):
     """A rotate-and-add ladder c <- c + Rot(c, s_l), l = 0, 1, ..., multiplies by prod_l (1 + Rot_{s_l});
     a run of g consecutive steps equals c + sum over the 2^g - 1 non-empty subsets B of the run of
-    Rot(c, sum_{l in B} s_l): rotations of ONE ciphertext.  Returns, for runs of up to LADDER_GROUP
-    steps, the list of those rotation amounts (subset with bit pattern b at position b - 1)."""
-    out = []
-    for i in range(0, len(steps), LADDER_GROUP):
-        run = steps[i:i + LADDER_GROUP]
+    Rot(c, sum_{l in B} s_l): rotations of ONE ciphertext.  The ladder is cut into ceil(L / LADDER_GROUP)
+    runs of as equal length as possible, the longer ones first (four steps: 2 + 2, six rotations, not
+    3 + 1, eight).  Returns the list of rotation amounts of every run (subset with bit pattern b at
+    position b - 1)."""
+    out, L = [], len(steps)
+    runs = -(-L // LADDER_GROUP)
+    i = 0
+    for r in range(runs):
+        g = L // runs + (1 if r < L % runs else 0)
+        run = steps[i:i + g]
+        i += g
         out.append([sum(s for l, s in enumerate(run) if (b >> l) & 1) for b in range(1, 1 << len(run))])
     return out
 

@@ -118,11 +118,14 @@ static void diag_slots(const cm_vmm_plan *p, const std::vector<int> &lab, const 
 }
 
 // A ladder c <- c + Rot(c, s_l) over a run of steps equals c + the rotations of c by every non-empty
-// subset sum of the run; runs of at most three steps (seven rotations of one ciphertext).
+// subset sum of the run.  The ladder is cut into ceil(L/3) runs of as equal length as possible, the
+// longer ones first (at most seven rotations of one ciphertext per run).
 static std::vector<std::vector<int>> ladder_groups(const std::vector<int> &steps) {
     std::vector<std::vector<int>> out;
-    for (size_t i = 0; i < steps.size(); i += 3) {
-        const size_t g = steps.size() - i < 3 ? steps.size() - i : 3;
+    const size_t L = steps.size(), runs = (L + 2) / 3;
+    size_t i = 0;
+    for (size_t r = 0; r < runs; r++) {
+        const size_t g = L / runs + (r < L % runs ? 1 : 0);
         std::vector<int> amounts;
         for (unsigned b = 1; b < (1u << g); b++) {
             int a = 0;
@@ -130,6 +133,7 @@ static std::vector<std::vector<int>> ladder_groups(const std::vector<int> &steps
                 if ((b >> l) & 1) a += steps[i + l];
             amounts.push_back(a);
         }
+        i += g;
         out.push_back(amounts);
     }
     return out;

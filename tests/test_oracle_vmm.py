@@ -384,7 +384,8 @@ def test_ladder_groups_reproduce_the_rotate_and_add_ladder_on_slots(steps):
         got = got + sum(np.roll(got, -a) for a in amounts)
     assert np.abs(got - want).max() < 1e-9
     assert len(groups) == (len(steps) + 2) // 3
-    assert sum(len(g) for g in groups) == sum(2 ** len(steps[i:i + 3]) - 1 for i in range(0, len(steps), 3))
+    sizes = [len(g).bit_length() for g in groups]                  # 2^g - 1 amounts -> g steps
+    assert sum(sizes) == len(steps) and (not sizes or max(sizes) - min(sizes) <= 1) and sizes == sorted(sizes, reverse=True)
 
 
 def test_rotsum_raised_against_separate_rotations():
@@ -411,13 +412,13 @@ def test_rotsum_raised_against_separate_rotations():
 @pytest.mark.parametrize("d_in,d_out,level,tau", [(64, 64, 3, 0), (16, 64, 2, 0), (64, 16, 4, 0), (32, 32, 1, 3),
                                                   (16, 16, 3, 9), (256, 256, 2, 0)])
 def test_unrolled_vmm_decrypts_to_x_times_W(d_in, d_out, level, tau):
-    """(16, 16) on 256 slots has four-step ladders (runs of three and one); (256, 256) has none."""
+    """(16, 16) on 256 slots has four-step ladders (two runs of two); (256, 256) has none."""
     prm, ctx, sk = _toy_ctx()
     x, W = inputs.vmm_inputs(7, d_in, d_out, "normal", 0.1)
     plan = packing.make_plan(ctx.S, d_in, d_out, tau=tau)
     steps = vmm.unrolled_steps(plan)
     npre, nred = len(plan.pre_steps), len(plan.reduce_steps)
-    ladder = lambda L: sum(2 ** len(range(i, min(i + 3, L))) - 1 for i in range(0, L, 3))
+    ladder = lambda L: sum(len(g) for g in vmm.ladder_groups(list(range(L))))
     assert len(steps) == ladder(npre) + plan.r_i - 1 + plan.r_o - 1 + ladder(nred)
     keys = ctx.keygen_rotations(sk, sorted(set(steps) | set(vmm.direct_giant_steps(plan))), 2)
     ct = ctx.level_drop(ctx.encrypt(sk, ctx.encode(plan.pack_input(x), prm.L), 3), level)
