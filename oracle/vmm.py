@@ -243,6 +243,33 @@ def qk_scores(ops, lay: KvLayout, cq, k_cts, masks):
     return ops.rescale(acc)
 
 
+def qk_unrolled_steps(lay: KvLayout):
+    """Rotation amounts of qk_scores_unrolled: the replication ladder of the query as it is, the
+    sum over the E dims in runs (ladder_groups)."""
+    ladder = [(1 << i) * lay.H * lay.t for i in range(_log2(lay.E))]
+    return [-(1 << i) for i in range(_log2(lay.t))] + [a for grp in ladder_groups(ladder) for a in grp]
+
+
+def qk_scores_unrolled(ctx, keys, lay: KvLayout, cq, k_cts, masks):
+    """qk_scores with the sum over the E dims of every head computed in the extended basis: the
+    relinearised, rescaled product is raised to (P c0, P c1), every run of the ladder adds the
+    hoisted rotations by its subset sums (ckks.rotsum_raised), and one ModDown ends the ladder.
+    log2(E) = 7 dependent key switches per key ciphertext become 3 ModUps and 13 inner products.
+    masks[c]: the encoded plaintext of lay.qk_mask(c) at the level of the sums."""
+    for i in range(_log2(lay.t)):                       # replicate q over the t residues
+        cq = ctx.ct_add(cq, ctx.rotate(cq, -(1 << i), keys))
+    groups = ladder_groups([(1 << i) * lay.H * lay.t for i in range(_log2(lay.E))])
+    acc = None
+    for c, kc in enumerate(k_cts):
+        p = ctx.rescale(ctx.relinearize(ctx.mul_ct(cq, kc), keys))
+        R = ctx.raise_ct(p)
+        for amounts in groups:
+            R = ctx.rotsum_raised(R, p.level, amounts, keys)
+        p = ctx.mul_pt(ctx.moddown_ct(R, p.level, p.scale), masks[c])
+        acc = p if acc is None else ctx.ct_add(acc, p)
+    return ctx.rescale(acc)
+
+
 def score_times_v(ops, lay: KvLayout, cs, v_cts):
     """Sec. 5.2/5.3: Att[h, e] = sum_n s[h, n] V[n, h, e]; result at (e, h, 0), the input
     layout of the next plaintext product (other residues hold partial sums)."""

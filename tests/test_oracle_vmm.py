@@ -434,3 +434,36 @@ def test_unrolled_vmm_decrypts_to_x_times_W(d_in, d_out, level, tau):
     if npre == 0 and nred == 0:
         # nothing to unroll: the same computation, bit for bit
         assert np.array_equal(ctx.canonical(y), ctx.canonical(other))
+
+
+def test_unrolled_qk_scores_decrypt_to_q_times_K_transposed():
+    """The sum over the E dims in the extended basis: same scores as the ladder form (and as the
+    float64 product); for E = 8 one run of three steps, seven hoisted rotations per key ciphertext
+    instead of three dependent ones; for E = 16 two runs of two."""
+    prm = params.toy(n=512, n_qi=4, n_p=1, alpha=1)
+    ctx = ckks.Context(prm)
+    L = prm.L
+    sk = ctx.keygen_secret(1)
+    for H, E in ((4, 8), (2, 16)):
+        lay = packing.KvLayout(ctx.S, H, E)             # t = 8
+        ntok = 2 * lay.t + 3
+        q, K, V, s = inputs.attention_inputs(4, H, 2, E, ntok)
+        steps = vmm.qk_unrolled_steps(lay)
+        if E == 8:
+            assert steps == [-1, -2, -4, 32, 64, 96, 128, 160, 192, 224]
+        else:
+            assert steps == [-1, -2, -4, 16, 32, 48, 64, 128, 192]
+        keys = ctx.keygen_rotations(sk, sorted(set(steps) | set(lay.qk_steps())), 2, with_relin=True)
+        enc = lambda v, lv, seed: ctx.level_drop(ctx.encrypt(sk, ctx.encode(v, L), seed), lv)
+        kc = [enc(lay.pack_k(K, c), L - 1, 100 + c) for c in range(3)]
+        cq = enc(lay.pack_vec(q), L - 1, 10)
+        masks = [ctx.encode(lay.qk_mask(c), L - 2) for c in range(3)]
+        r0 = ctx.rot_count
+        m = vmm.qk_scores_unrolled(ctx, keys, lay, cq, kc, masks)
+        assert ctx.rot_count - r0 == 3 + 3 * (len(steps) - 3)
+        assert m.level == L - 3
+        got = lay.unpack_scores(ctx.decrypt(sk, m).real, ntok)
+        assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
+        ladder = vmm.qk_scores(vmm.CkksOps(ctx, keys), lay, cq, kc, masks)
+        assert abs(m.scale / ladder.scale - 1) < 1e-12
+        assert np.abs(ctx.decrypt(sk, m) - ctx.decrypt(sk, ladder)).max() < 1e-6
