@@ -233,6 +233,14 @@ enum { CM_QK = 0, CM_SV = 1 };
  * score-times-V product (0 = dim, no giant steps). */
 cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level,
                        double scale, int32_t max_tokens, cm_kv **out);
+/* flags: CM_KV_UNROLLED_LADDERS — in query-times-K the sum over the dims of every head (Sec. 5.1 step 2,
+ * a rotate-and-add ladder of log2(dim) dependent rotations per key ciphertext) is computed in the
+ * extended basis: the ladder is cut into ceil(L/3) runs, a run of g steps adds the 2^g - 1 hoisted
+ * rotations by its subset sums (one ModUp per run), one ModDown ends it.  More rotation keys
+ * (cm_kv_steps lists them), fewer ModUps and ModDowns.  Unknown bits: CM_E_INVAL. */
+enum { CM_KV_UNROLLED_LADDERS = 1 };
+cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level,
+                          double scale, int32_t max_tokens, uint32_t flags, cm_kv **out);
 void cm_kv_destroy(cm_kv *kv);
 int32_t cm_kv_steps(const cm_kv *kv, int32_t *steps, int32_t cap);
 int32_t cm_kv_tokens(const cm_kv *kv);

@@ -19,6 +19,7 @@ lib = C.CDLL(LIB_PATH)
 
 CM_QK, CM_SV = 0, 1
 CM_VMM_RAISED_SUMS, CM_VMM_DIRECT_GIANTS, CM_VMM_TOKEN_BATCH, CM_VMM_UNROLLED_LADDERS = 1, 2, 4, 8
+CM_KV_UNROLLED_LADDERS = 1
 
 
 class cm_params(C.Structure):
@@ -90,6 +91,7 @@ _SIGS = {
     "cm_kv_export": ([_vp, _vp, _i32, _i32, _vp], _i32),
     "cm_kv_set_mask": ([_vp, _i32, _vp], _i32),
     "cm_kv_append": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
+    "cm_kv_create_ex": ([_vp, _i32, _i32, _i32, _i32, _f64, _i32, C.c_uint32, _P(_vp)], _i32),
     "cm_kv_append_group": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_vmm_kv": ([_vp, _vp, _vp, _i32, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_profile_enable": ([_vp, _i32], _i32),
@@ -318,8 +320,8 @@ class Context:
         _chk(lib.cm_rope_apply(self.h, evk.h, rope.h, C.byref(x.d), C.byref(out.d), _stream()))
         return out
 
-    def kv_create(self, heads, dim, level, scale=0.0, max_tokens=None, r_i=0):
-        return KvCache(self, heads, dim, r_i, level, scale, max_tokens)
+    def kv_create(self, heads, dim, level, scale=0.0, max_tokens=None, r_i=0, unrolled_ladders=False):
+        return KvCache(self, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders)
 
     def vmm_kv(self, evk, kv, which, x):
         out = Ct(self, x.level - (2 if which == CM_QK else 1))
@@ -418,11 +420,12 @@ class Rope:
 
 
 class KvCache:
-    def __init__(self, ctx, heads, dim, r_i, level, scale, max_tokens):
+    def __init__(self, ctx, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders=False):
         self.ctx, self.h, self.level = ctx, _vp(), level
         t = ctx.S // (heads * dim)
         max_tokens = dim * t if max_tokens is None else max_tokens
-        _chk(lib.cm_kv_create(ctx.h, heads, dim, r_i, level, scale, max_tokens, C.byref(self.h)))
+        _chk(lib.cm_kv_create_ex(ctx.h, heads, dim, r_i, level, scale, max_tokens,
+                                 CM_KV_UNROLLED_LADDERS if unrolled_ladders else 0, C.byref(self.h)))
 
     def steps(self):
         n = lib.cm_kv_steps(self.h, None, 0)

@@ -45,9 +45,11 @@ struct IpBatch {
 };
 void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st);
 // out[z] = sum_j it[z].dig_j * it[0].key_j for z < nz: one key for all arrays (read once), no Galois map, no c0, no extra
-void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st);
+// g != 0: digits and it[z].c0 (a first component in the extended basis, added as it is) through the Galois map; extra[z]
+// ([2][ext][n], may be out[z]) is added
+void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st, u64 g = 0);
 // out[2][ext][n] = (P c0, P c1), zero on the special limbs
-void launch_raise_by_P(cm_ctx *ctx, u64 *out, const u64 *in, int level, hipStream_t st);
+void launch_raise_by_P(cm_ctx *ctx, u64 *out, const u64 *in, int level, hipStream_t st, int count = 1);   // count stacked ciphertexts
 void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
                            int addend_comps, int level, u64 g, const u64 *accum, hipStream_t st, int ncomp = 2);
 void launch_rescale_reduce(cm_ctx *ctx, u64 *red, const u64 *last, int ncomp, int level, hipStream_t st);
@@ -128,6 +130,8 @@ cm_status moddown_many_second(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *con
 // out + (level+1)*n <- ModDown(R[1]) for one R = [2][ext][n], which is left untouched (its special limbs are
 // transformed into a buffer of their own)
 cm_status moddown_second_keep(cm_ctx *ctx, const u64 *R, int level, u64 *out, hipStream_t st);
+// the same for m <= CM_KS_BATCH stacked R[r] = [2][ext][n]: outs[r] + (level+1)*n <- ModDown(R[r][1])
+cm_status moddown_second_keep_many(cm_ctx *ctx, const u64 *Rs, int level, int m, u64 *const *outs, hipStream_t st);
 cm_status moddown_many(cm_ctx *ctx, u64 *us, int level, int cnt, u64 *const *outs, hipStream_t st);
 // one batch (m <= CM_KS_BATCH): outs[r] = ModDown(us + r*2*ext*n) + perm_g(addends[r]) on the first addend_comps
 // components (+ accums[r]); addends / accums nullable arrays of nullable pointers

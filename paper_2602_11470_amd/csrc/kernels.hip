@@ -330,16 +330,23 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
     *reinterpret_cast<ulonglong2 *>(b.out[z] + o) = r0;
     *reinterpret_cast<ulonglong2 *>(b.out[z] + (size_t)ext * n + o) = r1;
 }
-// The same key applied to nz digit arrays (no Galois map, no c0): a lane keeps its key words in
-// registers and runs over the arrays, so the key is read from HBM once per launch.
+// The same key applied to nz digit arrays: a lane keeps its key words in registers and runs over the
+// arrays, so the key is read from HBM once per launch.  With g != 0 the digits (and the optional
+// it[z].c0, a first component already in the extended basis, added as it is) are read through the
+// Galois map; extra[z] ([2][ext][n], may be out[z] itself) is added, which lets several launches with
+// different keys accumulate into one output.
 #define IP_SHARED_MAX_BETA 8
 __global__ __launch_bounds__(TPB) void k_inner_product_shared_key(IpBatch b, const ModC *__restrict__ modc, int beta,
-                                                                  int ext, int level, int L, int nmod, int n) {
+                                                                  int ext, int level, int L, int nmod, int n, int logn,
+                                                                  unsigned g) {
     const unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
     const int r = blockIdx.y;
     const int mi = r <= level ? r : L + 1 + (r - level - 1);
     const ModC m = modc[mi];
     const size_t o = (size_t)r * n + i2;
+    const unsigned src = g ? perm_src(i2, g, logn) : i2;
+    const unsigned base = src & ~1u;
+    const bool swap = src & 1u;
     ulonglong2 eb[IP_SHARED_MAX_BETA], ea[IP_SHARED_MAX_BETA];
     const u64 *key = b.it[0].key;
 #pragma unroll
@@ -356,27 +363,42 @@ __global__ __launch_bounds__(TPB) void k_inner_product_shared_key(IpBatch b, con
 #pragma unroll
         for (int j = 0; j < IP_SHARED_MAX_BETA; j++) {
             if (j < beta) {
-                ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(dig + ((size_t)j * ext + r) * n + i2);
-                b0 += (u128)d.x * eb[j].x;
-                b1 += (u128)d.y * eb[j].y;
-                a0 += (u128)d.x * ea[j].x;
-                a1 += (u128)d.y * ea[j].y;
+                ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(dig + ((size_t)j * ext + r) * n + base);
+                const u64 dx = swap ? d.y : d.x, dy = swap ? d.x : d.y;
+                b0 += (u128)dx * eb[j].x;
+                b1 += (u128)dy * eb[j].y;
+                a0 += (u128)dx * ea[j].x;
+                a1 += (u128)dy * ea[j].y;
             }
         }
-        *reinterpret_cast<ulonglong2 *>(b.out[z] + o) = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
-        *reinterpret_cast<ulonglong2 *>(b.out[z] + (size_t)ext * n + o) = make_ulonglong2(redc(a0, m.q, m.qinv), redc(a1, m.q, m.qinv));
+        ulonglong2 r0 = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
+        ulonglong2 r1 = make_ulonglong2(redc(a0, m.q, m.qinv), redc(a1, m.q, m.qinv));
+        if (b.it[z].c0) {
+            ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(b.it[z].c0 + (size_t)r * n + base);
+            r0.x = addmod(r0.x, swap ? d.y : d.x, m.q), r0.y = addmod(r0.y, swap ? d.x : d.y, m.q);
+        }
+        if (b.extra[z]) {
+            ulonglong2 e0 = *reinterpret_cast<const ulonglong2 *>(b.extra[z] + o);
+            ulonglong2 e1 = *reinterpret_cast<const ulonglong2 *>(b.extra[z] + (size_t)ext * n + o);
+            r0.x = addmod(r0.x, e0.x, m.q), r0.y = addmod(r0.y, e0.y, m.q);
+            r1.x = addmod(r1.x, e1.x, m.q), r1.y = addmod(r1.y, e1.y, m.q);
+        }
+        *reinterpret_cast<ulonglong2 *>(b.out[z] + o) = r0;
+        *reinterpret_cast<ulonglong2 *>(b.out[z] + (size_t)ext * n + o) = r1;
     }
 }
-void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st) {
+void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st, u64 g) {
     int ext = level + 1 + ctx->K;
-    if (beta > IP_SHARED_MAX_BETA) {          // more digits than a lane keeps: one plain launch per array
-        for (int z = 0; z < b.nz; z++)
-            launch_inner_product(ctx, b.out[z], b.out[z] + (size_t)ext * ctx->n, b.it[z].dig, b.it[0].key, beta, level, 0, st);
+    if (beta > IP_SHARED_MAX_BETA) {          // more digits than a lane keeps: the general batch kernel, one output per array
+        IpBatch c = b;
+        c.nsum = 1;
+        for (int z = 0; z < b.nz; z++) c.it[z].key = b.it[0].key, c.it[z].g = (unsigned)g, c.it[z].c0_ext = c.it[z].c0 ? 1 : 0;
+        launch_inner_product_batch(ctx, c, beta, level, st);
         return;
     }
     Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz, st);
     hipLaunchKernelGGL(k_inner_product_shared_key, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, b, ctx->d_modc, beta, ext,
-                       level, ctx->L, ctx->nmod, ctx->n);
+                       level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g);
 }
 void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st) {
     Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz * b.nsum, st);
@@ -386,8 +408,9 @@ void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int lev
 }
 // out[2][ext][n] = (P c0, P c1) on the ciphertext limbs, zero on the special limbs
 __global__ void k_raise_by_P(u64 *__restrict__ out, const u64 *__restrict__ in, const ModC *__restrict__ modc,
-                             const u64 *__restrict__ pmont, int level, int ext, int n) {
-    int i = blockIdx.x * TPB + threadIdx.x, r = blockIdx.y, c = blockIdx.z;
+                             const u64 *__restrict__ pmont, int level, int ext, int n, size_t in_stride, size_t out_stride) {
+    int i = blockIdx.x * TPB + threadIdx.x, r = blockIdx.y, c = blockIdx.z & 1;
+    in += (blockIdx.z >> 1) * in_stride, out += (blockIdx.z >> 1) * out_stride;      // stacked ciphertexts
     u64 v = 0;
     if (r <= level) {
         const ModC m = modc[r];
@@ -395,11 +418,11 @@ __global__ void k_raise_by_P(u64 *__restrict__ out, const u64 *__restrict__ in, 
     }
     out[((size_t)c * ext + r) * n + i] = v;
 }
-void launch_raise_by_P(cm_ctx *ctx, u64 *out, const u64 *in, int level, hipStream_t st) {
-    Prof prof_(ctx, CM_K_ELEMENTWISE, 2 * (level + 1 + ctx->K), st);
+void launch_raise_by_P(cm_ctx *ctx, u64 *out, const u64 *in, int level, hipStream_t st, int count) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, count * 2 * (level + 1 + ctx->K), st);
     int ext = level + 1 + ctx->K;
-    hipLaunchKernelGGL(k_raise_by_P, dim3(ctx->n / TPB, ext, 2), dim3(TPB), 0, st, out, in, ctx->d_modc, ctx->d_pmont, level,
-                       ext, ctx->n);
+    hipLaunchKernelGGL(k_raise_by_P, dim3(ctx->n / TPB, ext, 2 * count), dim3(TPB), 0, st, out, in, ctx->d_modc, ctx->d_pmont,
+                       level, ext, ctx->n, 2 * (size_t)(level + 1) * ctx->n, 2 * (size_t)ext * ctx->n);
 }
 void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u64 *evk, int beta, int level, u64 g,
                           hipStream_t st, const u64 *c0, const u64 *extra) {

@@ -31,7 +31,31 @@ struct cm_kv {
     // query-times-K runs CM_KS_BATCH key ciphertexts at a time: tables for raising the third
     // component of their tensor products (level) and the second of their rotated sums (level-1)
     KsManyTables relin_tabs, rot_tabs;
+    // sum over the head dims of query-times-K in the extended basis: the ladder cut into runs, every run the hoisted
+    // rotations by its subset sums
+    bool unrolled = false;
+    std::vector<std::vector<long long>> dim_groups;
 };
+
+// ceil(L/3) runs of as equal length as possible, the longer ones first; a run lists its non-empty subset sums
+static std::vector<std::vector<long long>> ladder_groups(const std::vector<long long> &steps) {
+    std::vector<std::vector<long long>> out;
+    const size_t L = steps.size(), runs = (L + 2) / 3;
+    size_t i = 0;
+    for (size_t r = 0; r < runs; r++) {
+        const size_t g = L / runs + (r < L % runs ? 1 : 0);
+        std::vector<long long> amounts;
+        for (unsigned b = 1; b < (1u << g); b++) {
+            long long a = 0;
+            for (size_t l = 0; l < g; l++)
+                if ((b >> l) & 1) a += steps[i + l];
+            amounts.push_back(a);
+        }
+        i += g;
+        out.push_back(amounts);
+    }
+    return out;
+}
 
 static int ilog2(int x) {
     int l = 0;
@@ -60,7 +84,11 @@ static cm_status encode_mask(cm_kv *kv, int kind, u64 *dst, int level, const int
 
 extern "C" cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level, double scale,
                                   int32_t max_tokens, cm_kv **out) {
-    if (!ctx || !out || heads < 1 || dim < 1 || max_tokens < 1) return CM_E_INVAL;
+    return cm_kv_create_ex(ctx, heads, dim, r_i, level, scale, max_tokens, 0, out);
+}
+extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level, double scale,
+                                     int32_t max_tokens, uint32_t flags, cm_kv **out) {
+    if (!ctx || !out || heads < 1 || dim < 1 || max_tokens < 1 || (flags & ~(uint32_t)CM_KV_UNROLLED_LADDERS)) return CM_E_INVAL;
     if (level < 2 || level > ctx->L) return CM_E_LEVEL;
     const int S = ctx->n / 2;
     if (!pow2(heads) || !pow2(dim) || heads * dim > S) return CM_E_LAYOUT;
@@ -72,6 +100,12 @@ extern "C" cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32
     kv->r_i = r_i, kv->r_o = dim / r_i, kv->level = level, kv->max_tokens = max_tokens, kv->ntok = 0;
     kv->scale = scale > 0 ? scale : ctx->prm.scale;
     kv->nk_max = (max_tokens + kv->t - 1) / kv->t;
+    kv->unrolled = (flags & CM_KV_UNROLLED_LADDERS) != 0;
+    if (kv->unrolled) {
+        std::vector<long long> ladder;
+        for (int i = 0; i < ilog2(dim); i++) ladder.push_back((long long)(1 << i) * heads * kv->t);
+        kv->dim_groups = ladder_groups(ladder);
+    }
     const size_t n = ctx->n, ctw = 2 * (size_t)(level + 1) * n;
     // work: r_i babies + r_o inner + tensor (1.5 ct) + 5 temporaries, all sized for level+1 inputs of append;
     // or the batch buffers of query-times-K (see kv_qk), whichever is larger
@@ -81,7 +115,9 @@ extern "C" cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32
         const KsLevel &kl = ks_level(ctx, level);
         const size_t ln = (size_t)(level + 1) * n, B = CM_KS_BATCH;
         const size_t qk = 5 * ctw + B * (3 * ln + 3 * ctw + ln + (size_t)kl.beta * kl.ext * n + 2 * n + 2 * (size_t)level * n);
-        if (qk > kv->work_words) kv->work_words = qk;
+        // unrolled: two more sets of CM_KS_BATCH sums in the extended basis of level-1
+        const size_t qku = qk + (kv->unrolled ? 2 * B * 2 * (size_t)(level + ctx->K) * n : 0);
+        if (qku > kv->work_words) kv->work_words = qku;
         // append: mask, one product and its rescale, r_o - 1 shifted inputs, then the batch buffers
         const size_t ap = (size_t)(level + 2) * n + (size_t)(2 + kv->r_o) * ctw_up +
                           B * (ctw_up + ctw + 2 * n + 2 * (size_t)(level + 1) * n);
@@ -134,7 +170,12 @@ extern "C" cm_status cm_kv_set_mask(cm_kv *kv, int32_t kind, const int64_t *coef
 static std::vector<int> kv_all_steps(const cm_kv *kv) {
     std::vector<int> s;
     for (int i = 0; i < ilog2(kv->t); i++) s.push_back(-(1 << i));                         // replicate q
-    for (int i = 0; i < ilog2(kv->E); i++) s.push_back((1 << i) * kv->H * kv->t);          // sum over dims
+    if (kv->unrolled) {
+        for (const auto &grp : kv->dim_groups)
+            for (long long a : grp) s.push_back((int)a);                                       // sum over dims, run by run
+    } else {
+        for (int i = 0; i < ilog2(kv->E); i++) s.push_back((1 << i) * kv->H * kv->t);      // sum over dims
+    }
     for (int j = 1; j < kv->r_i; j++) s.push_back(j * kv->H * kv->t);                      // score baby steps
     if (kv->r_o > 1) s.push_back(kv->r_i * kv->H * kv->t);                                 // score giant step
     for (int l = 0; l < ilog2(kv->t); l++) s.push_back(1 << l);                            // reduce residues
@@ -253,7 +294,12 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     const u64 *relin = find_key(evk, 0);
     if (!relin) return CM_E_NOKEY;
     for (int i = 0; i < ilog2(kv->t); i++) if (!find_key(evk, rot_g(kv, -(1 << i)))) return CM_E_NOKEY;
-    for (int i = 0; i < ilog2(kv->E); i++) if (!find_key(evk, rot_g(kv, (long long)(1 << i) * kv->H * kv->t))) return CM_E_NOKEY;
+    if (kv->unrolled) {
+        for (const auto &grp : kv->dim_groups)
+            for (long long a : grp) if (!find_key(evk, rot_g(kv, a))) return CM_E_NOKEY;
+    } else {
+        for (int i = 0; i < ilog2(kv->E); i++) if (!find_key(evk, rot_g(kv, (long long)(1 << i) * kv->H * kv->t))) return CM_E_NOKEY;
+    }
     const int nk = (kv->ntok + kv->t - 1) / kv->t;
     if (nk < 1) return CM_E_LAYOUT;
     // The key ciphertexts are independent until the final sum, so CM_KS_BATCH of them go through every
@@ -264,6 +310,8 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     u64 *TB = mask + ctw, *PB = TB + B * 3 * ln, *RB0 = PB + B * ctw, *RB1 = RB0 + B * ctw, *ksin = RB1 + B * ctw;
     u64 *digits = ksin + B * ln, *last = digits + B * (size_t)kl.beta * kl.ext * n, *red = last + B * 2 * n;
     u64 *bu = arena_batch_sums(ctx);
+    const size_t rw1 = 2 * (size_t)kl1.ext * n;                   // one sum in the extended basis of level-1
+    u64 *XA = red + B * 2 * (size_t)lv * n, *XB = XA + B * rw1;   // unrolled form only
     HIPCHK(hipMemcpyAsync(cq, in->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
     for (int i = 0; i < ilog2(kv->t); i++) {                     // replicate q over the t residues
         u64 g = rot_g(kv, -(1 << i));
@@ -290,7 +338,35 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
         CMCHK(rescale_into(ctx, PB, 2 * m, lv, RB0, st, last, red));       // stacked: [m][2][lv+1] -> [m][2][lv]
         u64 *r0 = RB0, *r1 = RB1;
         const size_t ublk1 = 2 * (size_t)kl1.ext * n, dblk1 = (size_t)kl1.beta * kl1.ext * n;
-        for (int i = 0; i < ilog2(kv->E); i++) {                 // sum over the E dims of every head
+        if (kv->unrolled) {
+            // sum over the E dims in the extended basis: R = (P c0, P c1); every run adds the hoisted rotations of R by
+            // its subset sums (one raise of ModDown(R1) per run, one launch per rotation amount over all m ciphertexts,
+            // the key read once per launch); one ModDown of both components at the end
+            launch_raise_by_P(ctx, XA, r0, lv - 1, st, m);
+            u64 *cur = XA, *nxt = XB;
+            for (size_t gi = 0; gi < kv->dim_groups.size(); gi++) {
+                if (gi) {                                       // the first run's second components are the exact c1
+                    for (int r = 0; r < m; r++) outs[r] = r0 + r * ctw1;
+                    CMCHK(moddown_second_keep_many(ctx, cur, lv - 1, m, outs, st));
+                }
+                CMCHK(ks_raise_many(ctx, kv->rot_tabs, r0, ksin, digits, st, m, 0));
+                bool first = true;
+                for (long long a : kv->dim_groups[gi]) {
+                    const u64 g = rot_g(kv, a);
+                    for (int r = 0; r < m; r++) {
+                        ip.it[r].dig = digits + r * dblk1, ip.it[r].key = find_key(evk, g);
+                        ip.it[r].c0 = cur + r * rw1, ip.it[r].c0_ext = 1;
+                        ip.out[r] = nxt + r * rw1, ip.extra[r] = first ? cur + r * rw1 : nxt + r * rw1;
+                    }
+                    launch_inner_product_shared_key(ctx, ip, kl1.beta, lv - 1, st, g);
+                    first = false;
+                }
+                std::swap(cur, nxt);
+            }
+            for (int r = 0; r < m; r++) outs[r] = r0 + r * ctw1, ip.it[r].c0 = nullptr, ip.it[r].c0_ext = 0, ip.extra[r] = nullptr;
+            CMCHK(moddown_batch_into(ctx, cur, lv - 1, m, nullptr, 0, 0, nullptr, outs, st));
+        }
+        for (int i = 0; i < ilog2(kv->E) && !kv->unrolled; i++) {                 // sum over the E dims of every head
             u64 g = rot_g(kv, (long long)(1 << i) * kv->H * kv->t);
             const u64 *key = find_key(evk, g);
             CMCHK(ks_raise_many(ctx, kv->rot_tabs, r0, ksin, digits, st, m, g));

@@ -332,8 +332,8 @@ cm_status moddown_second_keep(cm_ctx *ctx, const u64 *R, int level, u64 *out, hi
     Arena A = arena_of(ctx);
     const size_t n = ctx->n;
     // the K special limbs of the second component, to the coefficient domain in a buffer of their own
-    launch_ntt_src(ctx, A.conv, nullptr, R, k.d_sp1_rows, k.d_sp_mods, ctx->K, true, st, 0);
-    launch_base_conv(ctx, k.d_moddown0, 1, 0, level + 1, A.bconv, A.conv, 0, 0, nullptr, 0, st);
+    launch_ntt_src(ctx, A.tmp[0], nullptr, R, k.d_sp1_rows, k.d_sp_mods, ctx->K, true, st, 0);
+    launch_base_conv(ctx, k.d_moddown0, 1, 0, level + 1, A.bconv, A.tmp[0], 0, 0, nullptr, 0, st);
     if (ctx->n != 65536) {
         launch_ntt(ctx, A.bconv, k.d_bq_mods, level + 1, false, st);
         launch_moddown_finish(ctx, out + (size_t)(level + 1) * n, R + (size_t)k.ext * n, A.bconv, get_pinv(ctx, level), nullptr, 0,
@@ -344,6 +344,33 @@ cm_status moddown_second_keep(cm_ctx *ctx, const u64 *R, int level, u64 *out, hi
     fb.items = 1, fb.level = level, fb.ext = k.ext, fb.addend_comps = 0, fb.ncomp = 1, fb.comp0 = 1;
     for (int r = 0; r < CM_KS_BATCH; r++) fb.addend[r] = nullptr, fb.accum[r] = nullptr, fb.u[r] = nullptr, fb.out[r] = nullptr, fb.g[r] = 0;
     fb.u[0] = R, fb.out[0] = out, fb.pinv = get_pinv(ctx, level);
+    launch_ntt_fwd_finish(ctx, A.bconv, k.d_bq_mods, fb, st);
+    return CM_OK;
+}
+
+cm_status moddown_second_keep_many(cm_ctx *ctx, const u64 *Rs, int level, int m, u64 *const *outs, hipStream_t st) {
+    if (m < 1 || m > CM_KS_BATCH) return CM_E_INVAL;
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    Arena A = arena_of(ctx);
+    const size_t n = ctx->n, ublk = 2 * (size_t)k.ext * n;
+    // the K special limbs of every second component, to the coefficient domain in a buffer of their own
+    // (the three temporaries of the arena are contiguous: 9 (L+1) limbs, room for CM_KS_BATCH * K)
+    launch_ntt_src(ctx, A.tmp[0], nullptr, Rs, k.d_bsp1_rows, k.d_bsp_mods, m * ctx->K, true, st, 0);
+    launch_base_conv(ctx, k.d_moddown0, m, 0, level + 1, A.bconv, A.tmp[0], (size_t)ctx->K * n, (size_t)(level + 1) * n, nullptr,
+                     0, st);
+    if (ctx->n != 65536) {
+        launch_ntt(ctx, A.bconv, k.d_bq_mods, m * (level + 1), false, st);
+        for (int r = 0; r < m; r++)
+            launch_moddown_finish(ctx, outs[r] + (size_t)(level + 1) * n, Rs + r * ublk + (size_t)k.ext * n,
+                                  A.bconv + (size_t)r * (level + 1) * n, get_pinv(ctx, level), nullptr, 0, level, 0, nullptr,
+                                  st, 1);
+        return CM_OK;
+    }
+    FinishBatch fb;
+    fb.items = m, fb.level = level, fb.ext = k.ext, fb.addend_comps = 0, fb.ncomp = 1, fb.comp0 = 1;
+    for (int r = 0; r < CM_KS_BATCH; r++) fb.addend[r] = nullptr, fb.accum[r] = nullptr, fb.u[r] = nullptr, fb.out[r] = nullptr, fb.g[r] = 0;
+    for (int r = 0; r < m; r++) fb.u[r] = Rs + r * ublk, fb.out[r] = outs[r];
+    fb.pinv = get_pinv(ctx, level);
     launch_ntt_fwd_finish(ctx, A.bconv, k.d_bq_mods, fb, st);
     return CM_OK;
 }

@@ -194,7 +194,8 @@ def test_config4_mlp_projection_shapes_decrypt_to_float64_product(ring2, d_in, d
     assert np.abs(out - x @ W).max() < TOL
 
 
-def test_config3_attention_shapes_decrypt_to_float64_products(ring2):
+@pytest.mark.parametrize("unrolled", [False, True])
+def test_config3_attention_shapes_decrypt_to_float64_products(ring2, unrolled):
     """Llama-3-8B attention shapes on the full ring: 32 heads x 128 dims (8 KV heads repeated 4x),
     t = 8 tokens per K ciphertext, 128 V ciphertexts with 16 baby x 8 giant steps.  A short
     context (two loaded K ciphertexts plus three appended tokens) keeps the run small; every
@@ -209,7 +210,7 @@ def test_config3_attention_shapes_decrypt_to_float64_products(ring2):
     ntok = n_loaded + n_app
     q, K, V, s = inputs.attention_inputs(3, H, 8, E, ntok)
     lv = L - 1
-    kv = gctx.kv_create(H, E, lv, r_i=16)
+    kv = gctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=unrolled)
     gsk = gctx.keygen_secret(1)
     gkeys = gctx.keygen_rotations(gsk, kv.steps(), 2, with_relin=True)
     enc = lambda slots, level, seed: gctx.level_drop(gctx.encrypt(gsk, gctx.encode(slots, L), seed), level)

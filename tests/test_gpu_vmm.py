@@ -528,3 +528,50 @@ def test_kv_with_library_masks_decrypts_correctly(env):
     _, gs = _enc_both(e, lay.pack_scores(s), L - 1, 50)
     ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)
     assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
+
+
+@pytest.mark.parametrize("H,E,nk", [(16, 16, 3), (4, 64, 10), (2, 128, 2)])
+def test_kv_qk_with_unrolled_ladders_matches_oracle_and_float64(env, H, E, nk):
+    """q K^T with the sum over the head dims in the extended basis (CM_KV_UNROLLED_LADDERS): E = 16 is two
+    runs of two ladder steps, 64 two runs of three, 128 runs of three, two and two; ten key ciphertexts
+    make two batches (8 + 2).  Limbs against the oracle's form of it, scores against float64."""
+    from oracle import packing, vmm
+    from oracle.ckks import Pt
+    from paper_2602_11470_amd import inputs
+    e = env
+    B, octx, gctx = e["B"], e["octx"], e["gctx"]
+    L = octx.prm.L
+    lay = packing.KvLayout(octx.S, H, E)
+    ntok = nk * lay.t - 2
+    q, K, V, s = inputs.attention_inputs(17, H, max(1, H // 4), E, ntok)
+    q = q * 0.3
+    lv = L - 1
+    kv = gctx.kv_create(H, E, lv, unrolled_ladders=True)
+    steps = vmm.qk_unrolled_steps(lay)
+    assert set(steps) <= set(kv.steps())
+    okeys = octx.keygen_rotations(e["osk"], steps, 2, with_relin=True)
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2, with_relin=True)
+    m0 = np.zeros(octx.S)
+    m0[:H * lay.t] = 1
+    base = octx.encode_coeffs(m0, float(octx.mod[lv - 1]))
+    kv.set_mask(0, base)
+
+    def omask(c):
+        idx = octx.q_idx(lv - 1)
+        coeff = octx.automorphism_coeff(octx.from_i64(base, idx), idx, octx.galois(-(c % E) * H * lay.t))
+        return Pt(octx.ntt(coeff, idx), lv - 1, float(octx.mod[lv - 1]))
+
+    okc = []
+    for c in range(nk):
+        ok, gk = _enc_both(e, lay.pack_k(K, c), lv, 100 + c)
+        okc.append(ok)
+        kv.load(B.CM_QK, c, gk)
+    kv.set_tokens(ntok)
+    oq, gq = _enc_both(e, lay.pack_vec(q), lv, 10)
+    om = vmm.qk_scores_unrolled(octx, okeys, lay, oq, okc, [omask(c) for c in range(nk)])
+    gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, gq)
+    _same(e, om, gm)
+    got = lay.unpack_scores(gctx.decrypt(e["gsk"], gm).real, ntok)
+    assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
+    # twice in a row on the same buffers
+    assert np.array_equal(gctx.ct_export(gctx.vmm_kv(gkeys, kv, B.CM_QK, gq)), gctx.ct_export(gm))
