@@ -309,8 +309,8 @@ def kv_append(ops, lay: KvLayout, k_cts, v_cts, n, ck_new, cv_new, k_mask, v_mas
         k_cts.append(knew)
     else:
         k_cts[c] = ops.add(k_cts[c], knew)
-    shifted = [cv_new] + [ops.rotate(cv_new, -(g * lay.r_i * lay.H * lay.t))
-                          for g in range(1, lay.r_o)]
+    # the shifts are rotations of one ciphertext: they share its raised digits (hoisting)
+    shifted = [cv_new] + ops.rotate_many(cv_new, [-(g * lay.r_i * lay.H * lay.t) for g in range(1, lay.r_o)])
     for k in range(lay.E):
         vnew = ops.rescale(ops.mul_pt(shifted[k // lay.r_i], v_masks[k]))
         v_cts[k] = vnew if v_cts[k] is None else ops.add(v_cts[k], vnew)
@@ -323,8 +323,7 @@ def kv_append_group(ops, lay: KvLayout, k_cts, v_cts, c, ck_grp, cv_grp, k_mask,
     equal to the one-token update), v_masks[k] = lay.v_append_group_mask(k, c)."""
     assert c == len(k_cts)
     k_cts.append(ops.rescale(ops.mul_pt(ck_grp, k_mask)))
-    shifted = [cv_grp] + [ops.rotate(cv_grp, -(g * lay.r_i * lay.H * lay.t))
-                          for g in range(1, lay.r_o)]
+    shifted = [cv_grp] + ops.rotate_many(cv_grp, [-(g * lay.r_i * lay.H * lay.t) for g in range(1, lay.r_o)])
     for k in range(lay.E):
         vnew = ops.rescale(ops.mul_pt(shifted[k // lay.r_i], v_masks[k]))
         v_cts[k] = vnew if v_cts[k] is None else ops.add(v_cts[k], vnew)

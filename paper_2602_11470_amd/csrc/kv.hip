@@ -249,10 +249,17 @@ static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_c
     u64 *kc = kv->d_k + (size_t)c * ctw;
     launch_add(ctx, kc, kc, res, 2, kv->level + 1, st);
     // V: the new vector shifted right by each giant step, then one masked product per V ciphertext
-    for (int g = 1; g < kv->r_o; g++) {
-        long long step = -(long long)g * kv->r_i * kv->H * kv->t;
-        CMCHK(rotate_into(ctx, find_key(evk, rot_g(kv, step)), v_new->dev, lv, rot_g(kv, step),
-                          shifted + (size_t)(g - 1) * ctw_up, st));
+    if (kv->r_o > 1) {                                       // rotations of one ciphertext: one raise for all of them
+        u64 *digits = arena_digits(ctx);
+        CMCHK(ks_raise(ctx, v_new->dev + (size_t)(lv + 1) * n, lv, digits, st));
+        std::vector<const u64 *> keys;
+        std::vector<u64> gs;
+        std::vector<u64 *> dst;
+        for (int g = 1; g < kv->r_o; g++) {
+            const u64 gal = rot_g(kv, -(long long)g * kv->r_i * kv->H * kv->t);
+            keys.push_back(find_key(evk, gal)), gs.push_back(gal), dst.push_back(shifted + (size_t)(g - 1) * ctw_up);
+        }
+        CMCHK(ks_apply_many(ctx, digits, lv, kv->r_o - 1, keys.data(), gs.data(), v_new->dev, dst.data(), st));
     }
     // CM_KS_BATCH value ciphertexts at a time: their masked products in one launch, one stacked rescale,
     // one stacked addition (consecutive value ciphertexts are contiguous)
