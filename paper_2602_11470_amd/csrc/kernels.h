@@ -19,6 +19,8 @@ void launch_mac_pt_rot_batch(cm_ctx *ctx, u64 *acc, const u64 *src, const MulPtB
 void launch_mac_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int ncomp, int limbs, int accumulate, hipStream_t st);
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st);
 // out[z][3][limbs][n] = a (x) b[z], b[z] = b + z*2*limbs*n, z < cnt
+// out[z][3][limbs][n] = sum_{j < cnt} a[j] (x) b[z*cnt + j] for z < groups (a, b stacked ciphertexts [2][limbs][n])
+void launch_tensor_sum(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int groups, int limbs, hipStream_t st);
 void launch_tensor_batch(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int limbs, hipStream_t st);
 void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st);
 // batch item z: table (z % tab_period)*tab_step (tab_period 0 = batch), input (z / in_group)*in_stride, output z*out_stride
@@ -40,8 +42,8 @@ struct IpItem {
 struct IpBatch {
     int nz = 0, nsum = 1;
     IpItem it[IP_MAX_ITEMS];
-    u64 *out[IP_MAX_ITEMS];
-    const u64 *extra[IP_MAX_ITEMS];
+    u64 *out[IP_MAX_ITEMS] = {};
+    const u64 *extra[IP_MAX_ITEMS] = {};      // nullable; the kernels test it, so it must never be left unset
 };
 void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st);
 // out[z] = sum_j it[z].dig_j * it[0].key_j for z < nz: one key for all arrays (read once), no Galois map, no c0, no extra

@@ -152,6 +152,30 @@ void launch_mac_pt_rot_batch(cm_ctx *ctx, u64 *acc, const u64 *src, const MulPtB
     hipLaunchKernelGGL(k_mac_pt_rot_batch, dim3(ctx->n / TPB, 2 * limbs), dim3(TPB), 0, st, acc, src, b, cnt, pt_mont,
                        ctx->d_modc, limbs, ctx->n, ctx->logn, accumulate);
 }
+// out[z][3][limbs][n] = sum_{j < cnt} a[j] (x) b[z*cnt + j]: a and b stacked at stride 2*limbs*n; every output written once
+__global__ void k_tensor_sum(u64 *__restrict__ out, const u64 *__restrict__ a, const u64 *__restrict__ b,
+                             const ModC *__restrict__ modc, int limbs, int n, int cnt) {
+    int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y, z = blockIdx.z;
+    const ModC m = modc[l];
+    const size_t o = (size_t)l * n + i, cs = (size_t)limbs * n;
+    u64 d0 = 0, d1 = 0, d2 = 0;
+    for (int j = 0; j < cnt; j++) {
+        const u64 *aj = a + (size_t)j * 2 * cs, *bj = b + ((size_t)z * cnt + j) * 2 * cs;
+        const u64 a0 = to_mont(aj[o], m), a1 = to_mont(aj[o + cs], m);
+        const u64 b0 = __builtin_nontemporal_load(bj + o), b1 = __builtin_nontemporal_load(bj + o + cs);
+        d0 = addmod(d0, redc((u128)a0 * b0, m.q, m.qinv), m.q);
+        d1 = addmod(d1, redc((u128)a0 * b1 + (u128)a1 * b0, m.q, m.qinv), m.q);
+        d2 = addmod(d2, redc((u128)a1 * b1, m.q, m.qinv), m.q);
+    }
+    u64 *oz = out + (size_t)z * 3 * cs;
+    oz[o] = d0;
+    oz[o + cs] = d1;
+    oz[o + 2 * cs] = d2;
+}
+void launch_tensor_sum(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int groups, int limbs, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, 3 * limbs * groups, st);
+    hipLaunchKernelGGL(k_tensor_sum, dim3(ctx->n / TPB, limbs, groups), dim3(TPB), 0, st, out, a, b, ctx->d_modc, limbs, ctx->n, cnt);
+}
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st) {
     Prof prof_(ctx, CM_K_ELEMENTWISE, 3 * limbs, st);
     hipLaunchKernelGGL(k_tensor, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, a, b, ctx->d_modc, limbs, ctx->n, accumulate);

@@ -118,6 +118,9 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
         // unrolled: two more sets of CM_KS_BATCH sums in the extended basis of level-1
         const size_t qku = qk + (kv->unrolled ? 2 * B * 2 * (size_t)(level + ctx->K) * n : 0);
         if (qku > kv->work_words) kv->work_words = qku;
+        // scores-times-V: babies, inner sums, CM_KS_BATCH tensor sums, two temporaries, the batch's raise buffers
+        const size_t sv = (size_t)(kv->r_i + kv->r_o + 2) * ctw + B * (3 * ln + ln + (size_t)kl.beta * kl.ext * n);
+        if (sv > kv->work_words) kv->work_words = sv;
         // append: mask, one product and its rescale, r_o - 1 shifted inputs, then the batch buffers
         const size_t ap = (size_t)(level + 2) * n + (size_t)(2 + kv->r_o) * ctw_up +
                           B * (ctw_up + ctw + 2 * n + 2 * (size_t)(level + 1) * n);
@@ -407,8 +410,10 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     for (int j = 1; j < kv->r_i; j++) if (!find_key(evk, rot_g(kv, j * Ht))) return CM_E_NOKEY;
     if (kv->r_o > 1 && !find_key(evk, rot_g(kv, kv->r_i * Ht))) return CM_E_NOKEY;
     for (int l = 0; l < ilog2(kv->t); l++) if (!find_key(evk, rot_g(kv, 1 << l))) return CM_E_NOKEY;
+    const KsLevel &kl = ks_level(ctx, lv);
+    const size_t B = CM_KS_BATCH, dblk = (size_t)kl.beta * kl.ext * n, ublk = 2 * (size_t)kl.ext * n;
     u64 *babies = kv->d_work, *inner = babies + (size_t)kv->r_i * ctw, *T = inner + (size_t)kv->r_o * ctw,
-        *tmp = T + 3 * ln, *R = tmp + ctw;
+        *tmp = T + B * 3 * ln, *R = tmp + ctw, *ksin = R + ctw, *bdigits = ksin + B * ln;
     u64 *digits = arena_digits(ctx);
     HIPCHK(hipMemcpyAsync(babies, in->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
     if (kv->r_i > 1) {
@@ -423,11 +428,24 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
         }
         CMCHK(ks_apply_many(ctx, digits, lv, kv->r_i - 1, keys.data(), gs.data(), babies, dst.data(), st));
     }
-    for (int g = 0; g < kv->r_o; g++) {
-        for (int j = 0; j < kv->r_i; j++)
-            launch_tensor(ctx, T, babies + (size_t)j * ctw, kv->d_v + (size_t)(g * kv->r_i + j) * ctw, limbs, j > 0, st);
-        CMCHK(ks_raise(ctx, T + 2 * ln, lv, digits, st));
-        CMCHK(ks_apply(ctx, digits, relin, lv, 0, T, 2, inner + (size_t)g * ctw, st));
+    // inner_g = relinearise(sum_j baby_j (x) V_{g r_i + j}): the sums of up to CM_KS_BATCH groups by one launch, their
+    // third components raised together, one inner-product launch with the relinearisation key read once, one ModDown
+    for (int g0 = 0; g0 < kv->r_o; g0 += CM_KS_BATCH) {
+        const int m = kv->r_o - g0 < CM_KS_BATCH ? kv->r_o - g0 : CM_KS_BATCH;
+        launch_tensor_sum(ctx, T, babies, kv->d_v + (size_t)g0 * kv->r_i * ctw, kv->r_i, m, limbs, st);
+        CMCHK(ks_raise_many(ctx, kv->relin_tabs, T, ksin, bdigits, st, m, 0));
+        u64 *bu = arena_batch_sums(ctx);
+        IpBatch ip;
+        ip.nz = m, ip.nsum = 1;
+        const u64 *adds[CM_KS_BATCH];
+        u64 *outs[CM_KS_BATCH];
+        for (int r = 0; r < m; r++) {
+            ip.it[r].dig = bdigits + r * dblk, ip.it[r].key = relin, ip.it[r].c0 = nullptr, ip.it[r].g = 0;
+            ip.out[r] = bu + r * ublk, ip.extra[r] = nullptr;
+            adds[r] = T + (size_t)r * 3 * ln, outs[r] = inner + (size_t)(g0 + r) * ctw;
+        }
+        launch_inner_product_shared_key(ctx, ip, kl.beta, lv, st);
+        CMCHK(moddown_batch_into(ctx, bu, lv, m, adds, 2, 0, nullptr, outs, st));
     }
     u64 *acc = inner + (size_t)(kv->r_o - 1) * ctw;
     for (int g = kv->r_o - 2; g >= 0; g--) {
