@@ -259,6 +259,21 @@ class KvLayout:
     def rope_step(self):
         return self.H * self.t
 
+    # ---- inner rotation (Sec. 5.4): residues moved cyclically inside every block of t ---------------
+    # InnerRot_delta(x)[b, tau'] = x[b, (tau' - delta) mod t].  A slot rotation by -delta does that for
+    # the residues that do not wrap (tau < t - delta before the move); those that wrap come from a
+    # rotation by t - delta.  Masking BEFORE the rotations (zero plaintext for the unrotated term)
+    # gives it the shape of the rotary embedding: two rotations, one level.
+    def inner_rotation_steps(self, delta):
+        assert 0 < delta < self.t
+        return [-delta, self.t - delta]
+
+    def inner_rotation_plaintexts(self, delta):
+        """(p0, p1, p2) for vmm.masked_two_rotations with steps (up, down) = inner_rotation_steps:
+        p0 = 0; p2 = residues below t - delta (moved by -delta); p1 = the others (moved by t - delta)."""
+        r = np.arange(self.S) % self.t
+        return np.zeros(self.S), (r >= self.t - delta).astype(float), (r < self.t - delta).astype(float)
+
     def pack_k(self, K, c):
         """K[token, h, e] -> slots of K ciphertext c (tokens past the end are zero)."""
         out = np.zeros(self.S)

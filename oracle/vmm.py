@@ -228,10 +228,13 @@ def direct_giant_steps(plan: VmmPlan):
     return steps + list(plan.reduce_steps)
 
 
-def qk_scores(ops, lay: KvLayout, cq, k_cts, masks):
+def qk_scores(ops, lay: KvLayout, cq, k_cts, masks, replicate=True):
     """Sec. 5.1 with the multi-head layout of Sec. 5.3: scores of one query against the K
-    cache.  masks[c] = lay.qk_mask(c) (slot vector or encoded plaintext)."""
-    for i in range(_log2(lay.t)):                       # replicate q over the t residues
+    cache.  masks[c] = lay.qk_mask(c) (slot vector or encoded plaintext).  replicate=False: cq is a
+    query GROUP (Sec. 5.4: token tau at residue tau, possibly after an inner rotation), nothing is
+    replicated, and slot (c, h, tau') of the result is the score of the query at residue tau' against
+    key token c t + tau'."""
+    for i in range(_log2(lay.t) if replicate else 0):   # replicate q over the t residues
         cq = ops.add(cq, ops.rotate(cq, -(1 << i)))
     acc = None
     for c, kc in enumerate(k_cts):
@@ -250,13 +253,13 @@ def qk_unrolled_steps(lay: KvLayout):
     return [-(1 << i) for i in range(_log2(lay.t))] + [a for grp in ladder_groups(ladder) for a in grp]
 
 
-def qk_scores_unrolled(ctx, keys, lay: KvLayout, cq, k_cts, masks):
+def qk_scores_unrolled(ctx, keys, lay: KvLayout, cq, k_cts, masks, replicate=True):
     """qk_scores with the sum over the E dims of every head computed in the extended basis: the
     relinearised, rescaled product is raised to (P c0, P c1), every run of the ladder adds the
     hoisted rotations by its subset sums (ckks.rotsum_raised), and one ModDown ends the ladder.
     log2(E) = 7 dependent key switches per key ciphertext become 3 ModUps and 13 inner products.
     masks[c]: the encoded plaintext of lay.qk_mask(c) at the level of the sums."""
-    for i in range(_log2(lay.t)):                       # replicate q over the t residues
+    for i in range(_log2(lay.t) if replicate else 0):   # replicate q over the t residues
         cq = ctx.ct_add(cq, ctx.rotate(cq, -(1 << i), keys))
     groups = ladder_groups([(1 << i) * lay.H * lay.t for i in range(_log2(lay.E))])
     acc = None
@@ -287,15 +290,29 @@ def score_times_v(ops, lay: KvLayout, cs, v_cts):
     return acc
 
 
+def masked_two_rotations(ops, c, plaintexts, up, down):
+    """c p0 + Rot(c p2, up) + Rot(c p1, down), then the rescale: three plaintext products, two
+    rotations, one level."""
+    p0, p1, p2 = plaintexts
+    y = ops.mul_pt(c, p0)
+    y = ops.add(y, ops.rotate(ops.mul_pt(c, p2), up))
+    y = ops.add(y, ops.rotate(ops.mul_pt(c, p1), down))
+    return ops.rescale(y)
+
+
 def rope(ops, lay: KvLayout, c, plaintexts):
     """App. D: c p0 + Rot(c p2, +H t) + Rot(c p1, -H t), then the rescale; three plaintext products,
     two rotations, one level.  `plaintexts` = lay.rope_plaintexts(n, tau) (slot vectors or encoded
     plaintexts); slots outside the valid ones come out zero whatever they held."""
-    p0, p1, p2 = plaintexts
-    y = ops.mul_pt(c, p0)
-    y = ops.add(y, ops.rotate(ops.mul_pt(c, p2), lay.rope_step))
-    y = ops.add(y, ops.rotate(ops.mul_pt(c, p1), -lay.rope_step))
-    return ops.rescale(y)
+    return masked_two_rotations(ops, c, plaintexts, lay.rope_step, -lay.rope_step)
+
+
+def inner_rotate(ops, lay: KvLayout, c, delta, plaintexts):
+    """Sec. 5.4, the 'inner rotations' of the prompt-phase Q K^T: residue tau of every block moves to
+    residue (tau + delta) mod t, so that a query group meets the keys of other residues.
+    `plaintexts` = lay.inner_rotation_plaintexts(delta)."""
+    up, down = lay.inner_rotation_steps(delta)
+    return masked_two_rotations(ops, c, plaintexts, up, down)
 
 
 def kv_append(ops, lay: KvLayout, k_cts, v_cts, n, ck_new, cv_new, k_mask, v_masks):

@@ -467,3 +467,36 @@ def test_unrolled_qk_scores_decrypt_to_q_times_K_transposed():
         ladder = vmm.qk_scores(vmm.CkksOps(ctx, keys), lay, cq, kc, masks)
         assert abs(m.scale / ladder.scale - 1) < 1e-12
         assert np.abs(ctx.decrypt(sk, m) - ctx.decrypt(sk, ladder)).max() < 1e-6
+
+
+def test_inner_rotations_let_a_query_group_meet_every_key_residue():
+    """Sec. 5.4 on slots: t queries in one vector (token tau at residue tau); for every delta the
+    inner rotation followed by the un-replicated q K^T gives, at (c, h, tau'), the score of query
+    (tau' - delta) mod t against key token c t + tau'; over all delta every pair appears once."""
+    lay = packing.KvLayout(256, 4, 8)                   # t = 8
+    rng = np.random.default_rng(6)
+    Q = rng.normal(size=(lay.t, 4, 8))
+    K = rng.normal(size=(2 * lay.t, 4, 8))
+    qg = sum(lay.pack_vec(Q[tau], tau) for tau in range(lay.t))
+    kc = [lay.pack_k(K, c) for c in range(2)]
+    masks = [lay.qk_mask(c) for c in range(2)]
+    full = np.einsum("ahe,nhe->ahn", Q, K)              # [query, head, key]
+    seen = np.zeros((lay.t, 2 * lay.t), dtype=int)
+    for delta in range(lay.t):
+        ops = vmm.SlotOps()
+        x = qg if delta == 0 else vmm.inner_rotate(ops, lay, qg, delta, lay.inner_rotation_plaintexts(delta))
+        if delta:
+            assert (ops.rotations, ops.pt_mults) == (2, 3)
+            want = np.zeros(lay.S)
+            for tau in range(lay.t):
+                want += lay.pack_vec(Q[tau], (tau + delta) % lay.t)
+            assert np.array_equal(x, want)
+        r0 = ops.rotations
+        sc = vmm.qk_scores(ops, lay, x, kc, masks, replicate=False)
+        assert ops.rotations - r0 == 2 * 3              # only the sums over the 8 dims
+        got = lay.unpack_scores(sc, 2 * lay.t)          # [head, key]
+        for n in range(2 * lay.t):
+            a = (n % lay.t - delta) % lay.t
+            assert np.abs(got[:, n] - full[a, :, n]).max() < 1e-12
+            seen[a, n] += 1
+    assert np.array_equal(seen, np.ones_like(seen))
