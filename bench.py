@@ -360,13 +360,18 @@ def prefill_workload(a):
     kr = ctx.rope_apply(keys, rope, kg)
     rope_ms = timed(lambda: ctx.rope_apply(keys, rope, kg, out=kr), a.steps)
 
+    irot = ctx.inner_rot(ctx.S // (H * E), 3, lv + 2)
+    ikeys = ctx.keygen_rotations(sk, irot.steps(), 2)
+    qi = ctx.rope_apply(ikeys, irot, kg)
+    inner_ms = timed(lambda: ctx.rope_apply(ikeys, irot, kg, out=qi), a.steps)
+
     def append():
         kv.set_tokens(0)
         kv.append_group(keys, kr, vg)
     append_ms = timed(append, a.steps)
     print(json.dumps({"metric": "prompt phase, ms per ciphertext of 8 tokens (n=2^16, 24+4 primes)", "unit": "ms", "n_gpus": 1,
                       "data": "synthetic", "dtype": "u64", "token_batched_4096x4096": rows,
-                      "rope_group_ms": rope_ms, "append_group_ms": append_ms,
+                      "rope_group_ms": rope_ms, "inner_rotation_ms": inner_ms, "append_group_ms": append_ms,
                       "append_group_ms_per_token": append_ms / (ctx.S // (H * E))}))
 
 

@@ -227,7 +227,10 @@ cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *con
                           int32_t nplans, const cm_ct *x, cm_ct *const *ys, void *stream);
 
 /* ---- encrypted KV cache (Sec. 5) -------------------------------------------------------- */
-enum { CM_QK = 0, CM_SV = 1 };
+/* CM_QK_GROUP: query-times-K for a query GROUP (Sec. 5.4: token tau at residue tau of every (e, h)
+ * block, possibly after an inner rotation): nothing is replicated, and slot (c, h, tau') of the
+ * result is the score of the query at residue tau' against key token c*t + tau'. */
+enum { CM_QK = 0, CM_SV = 1, CM_QK_GROUP = 2 };
 /* Cache for `heads` heads of `dim` dims (heads*dim*t = S) holding up to max_tokens tokens
  * (<= dim*t) at ciphertext level `level` and scale `scale`.  r_i = baby steps of the
  * score-times-V product (0 = dim, no giant steps). */
@@ -296,6 +299,14 @@ void cm_rope_destroy(cm_rope *rope);
 int32_t cm_rope_steps(const cm_rope *rope, int32_t *steps, int32_t cap);
 cm_status cm_rope_apply(cm_ctx *ctx, const cm_evk *evk, const cm_rope *rope, const cm_ct *x,
                         cm_ct *y, void *stream);
+/* Inner rotation (Sec. 5.4, the prompt-phase Q K^T): y[b*t + tau'] = x[b*t + (tau' - delta) mod t]
+ * for every block b of t consecutive slots, 0 < delta < t, t a power of two.  Two masked products
+ * (mask before rotation, encoded at the scale of the prime the rescale removes), rotations by
+ * -delta and t - delta, one level: the same object and calls as the embedding (cm_rope_steps,
+ * cm_rope_apply, cm_rope_destroy).  coeffs (nullable, host [3][n]): integer coefficients of the zero
+ * plaintext, the mask of the residues >= t - delta and the mask of the residues < t - delta. */
+cm_status cm_inner_rot_create(cm_ctx *ctx, int32_t t, int32_t delta, int32_t level,
+                              const int64_t *coeffs, cm_rope **out);
 
 /* ---- building blocks exposed for measurement and parity -------------------------------- */
 /* Forward / inverse negacyclic NTT of `limbs` limbs in place (device), limb i under modulus

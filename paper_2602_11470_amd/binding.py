@@ -17,7 +17,7 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} not built: run python -m paper_2602_11470_amd.build")
 lib = C.CDLL(LIB_PATH)
 
-CM_QK, CM_SV = 0, 1
+CM_QK, CM_SV, CM_QK_GROUP = 0, 1, 2
 CM_VMM_RAISED_SUMS, CM_VMM_DIRECT_GIANTS, CM_VMM_TOKEN_BATCH, CM_VMM_UNROLLED_LADDERS = 1, 2, 4, 8
 CM_KV_UNROLLED_LADDERS = 1
 
@@ -79,6 +79,7 @@ _SIGS = {
     "cm_vmm_pt": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_vmm_pt_multi": ([_vp, _vp, _vp, _i32, _P(cm_ct), _vp, _vp], _i32),
     "cm_rope_create": ([_vp, _i32, _i32, _i32, _i32, _i32, _f64, _vp, _P(_vp)], _i32),
+    "cm_inner_rot_create": ([_vp, _i32, _i32, _i32, _vp, _P(_vp)], _i32),
     "cm_rope_destroy": ([_vp], None),
     "cm_rope_steps": ([_vp, _vp, _i32], _i32),
     "cm_rope_apply": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
@@ -315,6 +316,10 @@ class Context:
     def rope(self, heads, dim, level, token, tau=0, base=10000.0, coeffs=None):
         return Rope(self, heads, dim, level, token, tau, base, coeffs)
 
+    def inner_rot(self, t, delta, level, coeffs=None):
+        """Inner rotation by delta of the residues of every block of t slots; applied with rope_apply."""
+        return Rope(self, 0, 0, level, 0, 0, 0.0, coeffs, inner=(t, delta))
+
     def rope_apply(self, evk, rope, x, out=None):
         out = out or Ct(self, x.level - 1)
         _chk(lib.cm_rope_apply(self.h, evk.h, rope.h, C.byref(x.d), C.byref(out.d), _stream()))
@@ -324,7 +329,7 @@ class Context:
         return KvCache(self, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders)
 
     def vmm_kv(self, evk, kv, which, x):
-        out = Ct(self, x.level - (2 if which == CM_QK else 1))
+        out = Ct(self, x.level - (1 if which == CM_SV else 2))
         _chk(lib.cm_vmm_kv(self.h, evk.h, kv.h, which, C.byref(x.d), C.byref(out.d), _stream()))
         return out
 
@@ -402,11 +407,16 @@ class VmmPlan:
 
 
 class Rope:
-    def __init__(self, ctx, heads, dim, level, token, tau, base, coeffs):
+    """The rotary embedding of a layout, or (inner=(t, delta)) the inner rotation of the residues of every block."""
+
+    def __init__(self, ctx, heads, dim, level, token, tau, base, coeffs, inner=None):
         self.ctx, self.h = ctx, _vp()
         c = _np(coeffs, np.int64) if coeffs is not None else None
-        _chk(lib.cm_rope_create(ctx.h, heads, dim, level, token, tau, base, c.ctypes.data if c is not None else None,
-                                C.byref(self.h)))
+        cp = c.ctypes.data if c is not None else None
+        if inner is not None:
+            _chk(lib.cm_inner_rot_create(ctx.h, inner[0], inner[1], level, cp, C.byref(self.h)))
+        else:
+            _chk(lib.cm_rope_create(ctx.h, heads, dim, level, token, tau, base, cp, C.byref(self.h)))
 
     def steps(self):
         out = np.empty(2, dtype=np.int32)

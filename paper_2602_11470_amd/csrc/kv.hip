@@ -297,13 +297,14 @@ extern "C" cm_status cm_kv_append_group(cm_ctx *ctx, const cm_evk *evk, cm_kv *k
     return kv_append(ctx, evk, kv, k_grp, v_grp, true, stream);
 }
 
-static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st) {
+static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st,
+                       bool replicate) {
     const int lv = kv->level, limbs = lv + 1;
     if (lv < 2) return CM_E_LEVEL;
     const size_t n = ctx->n, ctw = kv_ctw(kv), ln = (size_t)limbs * n;
     const u64 *relin = find_key(evk, 0);
     if (!relin) return CM_E_NOKEY;
-    for (int i = 0; i < ilog2(kv->t); i++) if (!find_key(evk, rot_g(kv, -(1 << i)))) return CM_E_NOKEY;
+    for (int i = 0; i < ilog2(kv->t) && replicate; i++) if (!find_key(evk, rot_g(kv, -(1 << i)))) return CM_E_NOKEY;
     if (kv->unrolled) {
         for (const auto &grp : kv->dim_groups)
             for (long long a : grp) if (!find_key(evk, rot_g(kv, a))) return CM_E_NOKEY;
@@ -323,7 +324,7 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     const size_t rw1 = 2 * (size_t)kl1.ext * n;                   // one sum in the extended basis of level-1
     u64 *XA = red + B * 2 * (size_t)lv * n, *XB = XA + B * rw1;   // unrolled form only
     HIPCHK(hipMemcpyAsync(cq, in->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
-    for (int i = 0; i < ilog2(kv->t); i++) {                     // replicate q over the t residues
+    for (int i = 0; i < ilog2(kv->t) && replicate; i++) {        // replicate q over the t residues
         u64 g = rot_g(kv, -(1 << i));
         CMCHK(rotate_into(ctx, find_key(evk, g), cq, lv, g, tmp, st, cq));      // tmp = cq + Rot(cq)
         std::swap(cq, tmp);
@@ -471,7 +472,7 @@ extern "C" cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, 
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !kv || kv->ctx != ctx || !in || !in->dev || !out || !out->dev || in->ncomp != 2) return CM_E_INVAL;
     if (in->level != kv->level) return CM_E_LEVEL;
-    if (which == CM_QK) return kv_qk(ctx, evk, kv, in, out, (hipStream_t)stream);
+    if (which == CM_QK || which == CM_QK_GROUP) return kv_qk(ctx, evk, kv, in, out, (hipStream_t)stream, which == CM_QK);
     if (which == CM_SV) return kv_sv(ctx, evk, kv, in, out, (hipStream_t)stream);
     return CM_E_INVAL;
 }

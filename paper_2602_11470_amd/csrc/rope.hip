@@ -18,6 +18,7 @@
 struct cm_rope {
     cm_ctx *ctx = nullptr;
     int S, H, E, t, level, token, tau;
+    int step_up, step_dn;      // y = x p0 + Rot(x p2, step_up) + Rot(x p1, step_dn)
     double base;
     u64 *d_pts = nullptr;      // [3][level+1][n], multiplier form
     u64 *d_work = nullptr;     // three ciphertexts
@@ -48,6 +49,7 @@ extern "C" cm_status cm_rope_create(cm_ctx *ctx, int32_t heads, int32_t dim, int
     cm_rope *r = new (std::nothrow) cm_rope();
     if (!r) return CM_E_NOMEM;
     r->ctx = ctx, r->S = S, r->H = heads, r->E = dim, r->t = t, r->level = level, r->token = token, r->tau = tau, r->base = base;
+    r->step_up = heads * t, r->step_dn = -(heads * t);
     const size_t n = ctx->n, ln = (size_t)(level + 1) * n;
     if (hipMalloc((void **)&r->d_pts, 3 * ln * 8) != hipSuccess || hipMalloc((void **)&r->d_work, 6 * ln * 8) != hipSuccess) {
         cm_rope_destroy(r);
@@ -78,6 +80,39 @@ extern "C" cm_status cm_rope_create(cm_ctx *ctx, int32_t heads, int32_t dim, int
     *out = r;
     return CM_OK;
 }
+// Inner rotation (Sec. 5.4): residue tau of every block of t slots moves to residue (tau + delta) mod t.  The same
+// shape as the embedding: p0 = 0, p2 = the residues below t - delta (rotated by -delta), p1 = the others (rotated by
+// t - delta); masks encoded at the scale of the prime the rescale removes.
+extern "C" cm_status cm_inner_rot_create(cm_ctx *ctx, int32_t t, int32_t delta, int32_t level, const int64_t *coeffs,
+                                         cm_rope **out) {
+    if (!ctx || !out) return CM_E_INVAL;
+    if (level < 1 || level > ctx->L) return CM_E_LEVEL;
+    const int S = ctx->n / 2;
+    if (!pow2(t) || t < 2 || t > S || delta < 1 || delta >= t) return CM_E_LAYOUT;
+    cm_rope *r = new (std::nothrow) cm_rope();
+    if (!r) return CM_E_NOMEM;
+    r->ctx = ctx, r->S = S, r->H = 1, r->E = S / t, r->t = t, r->level = level, r->token = 0, r->tau = 0, r->base = 0;
+    r->step_up = -delta, r->step_dn = t - delta;
+    const size_t n = ctx->n, ln = (size_t)(level + 1) * n;
+    if (hipMalloc((void **)&r->d_pts, 3 * ln * 8) != hipSuccess || hipMalloc((void **)&r->d_work, 6 * ln * 8) != hipSuccess) {
+        cm_rope_destroy(r);
+        return CM_E_NOMEM;
+    }
+    const double scale = (double)ctx->mod[level];
+    std::vector<double> p[3];
+    for (auto &v : p) v.assign(S, 0.0);
+    for (int i = 0; i < S && !coeffs; i++) p[(i % t) < t - delta ? 2 : 1][i] = 1.0;
+    cm_status s = CM_OK;
+    for (int k = 0; k < 3 && s == CM_OK; k++) {
+        cm_pt pt;
+        pt.dev = r->d_pts + k * ln, pt.mont = 1;
+        s = coeffs ? cm_pt_from_coeffs(ctx, coeffs + (size_t)k * n, level, scale, &pt)
+                   : cm_encode(ctx, p[k].data(), nullptr, p[k].size(), level, scale, &pt);
+    }
+    if (s != CM_OK) { cm_rope_destroy(r); return s; }
+    *out = r;
+    return CM_OK;
+}
 extern "C" void cm_rope_destroy(cm_rope *r) {
     if (!r) return;
     hipFree(r->d_pts);
@@ -86,7 +121,7 @@ extern "C" void cm_rope_destroy(cm_rope *r) {
 }
 extern "C" int32_t cm_rope_steps(const cm_rope *r, int32_t *steps, int32_t cap) {
     if (!r) return 0;
-    const int s[2] = {r->H * r->t, -(r->H * r->t)};
+    const int s[2] = {r->step_up, r->step_dn};
     for (int i = 0; i < 2 && i < cap && steps; i++) steps[i] = s[i];
     return 2;
 }
@@ -96,16 +131,16 @@ extern "C" cm_status cm_rope_apply(cm_ctx *ctx, const cm_evk *evk, const cm_rope
         return CM_E_INVAL;
     if (x->level != r->level) return CM_E_LEVEL;
     hipStream_t st = (hipStream_t)stream;
-    const int level = r->level, limbs = level + 1, step = r->H * r->t;
-    const u64 g_up = galois_of_step(ctx, step), g_dn = galois_of_step(ctx, -step);
+    const int level = r->level, limbs = level + 1;
+    const u64 g_up = galois_of_step(ctx, r->step_up), g_dn = galois_of_step(ctx, r->step_dn);
     const u64 *k_up = find_key(evk, g_up), *k_dn = find_key(evk, g_dn);
     if (!k_up || !k_dn) return CM_E_NOKEY;
     const size_t ctw = 2 * (size_t)limbs * ctx->n;
     u64 *a = r->d_work, *b = a + ctw, *c = b + ctw;
     hipLaunchKernelGGL(k_mul_pt3, dim3(ctx->n / 256, 2 * limbs), dim3(256), 0, st, a, c, b, x->dev, r->d_pts, ctx->d_modc, limbs,
                        ctx->n);                                   // a = x p0, c = x p1, b = x p2
-    CMCHK(rotate_into(ctx, k_up, b, level, g_up, a, st, a));      // a += Rot(x p2, +H t)
-    CMCHK(rotate_into(ctx, k_dn, c, level, g_dn, a, st, a));      // a += Rot(x p1, -H t)
+    CMCHK(rotate_into(ctx, k_up, b, level, g_up, a, st, a));      // a += Rot(x p2, step_up)
+    CMCHK(rotate_into(ctx, k_dn, c, level, g_dn, a, st, a));      // a += Rot(x p1, step_dn)
     CMCHK(rescale_into(ctx, a, 2, level, y->dev, st));
     y->level = level - 1, y->ncomp = 2;
     y->scale = x->scale;                                          // plaintext scale = the prime just removed

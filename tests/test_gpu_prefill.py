@@ -209,3 +209,74 @@ def test_group_append_then_single_tokens_then_attention(env, r_i):
     ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)
     _same(e, oa, ga)
     assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
+
+
+@pytest.mark.parametrize("unrolled", [False, True])
+def test_inner_rotation_and_group_scores_match_oracle_and_all_query_key_pairs(env, unrolled):
+    """Prompt-phase Q K^T (Sec. 5.4): a group of t queries, inner rotations by delta, then the
+    un-replicated q K^T; limbs against the oracle, and every score against the float64 product of
+    the query at residue (tau' - delta) mod t with key token c t + tau'."""
+    from oracle import packing, vmm
+    from oracle.ckks import Pt
+    e = env
+    B, octx, gctx = e["B"], e["octx"], e["gctx"]
+    H, E, L = 16, 16, octx.prm.L
+    lay = packing.KvLayout(octx.S, H, E)                 # t = 8
+    nk = 2
+    rng = np.random.default_rng(31)
+    Q = rng.normal(size=(lay.t, H, E)) * 0.3
+    K = rng.normal(size=(nk * lay.t, H, E))
+    lv = L - 2                                           # cache level; the query group arrives one level higher
+    kv = gctx.kv_create(H, E, lv, unrolled_ladders=unrolled)
+    dim_steps = vmm.qk_unrolled_steps(lay)[3:] if unrolled else lay.qk_steps()[3:]
+    deltas = (1, 5)
+    steps = sorted(set(dim_steps) | {s for d in deltas for s in lay.inner_rotation_steps(d)})
+    okeys = octx.keygen_rotations(e["osk"], steps, 2, with_relin=True)
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2, with_relin=True)
+    m0 = np.zeros(octx.S)
+    m0[:H * lay.t] = 1
+    base = octx.encode_coeffs(m0, float(octx.mod[lv - 1]))
+    kv.set_mask(0, base)
+
+    def omask(c):
+        idx = octx.q_idx(lv - 1)
+        coeff = octx.automorphism_coeff(octx.from_i64(base, idx), idx, octx.galois(-(c % E) * H * lay.t))
+        return Pt(octx.ntt(coeff, idx), lv - 1, float(octx.mod[lv - 1]))
+
+    okc = []
+    for c in range(nk):
+        ok, gk = _enc_both(e, lay.pack_k(K, c), lv, 100 + c)
+        okc.append(ok)
+        kv.load(B.CM_QK, c, gk)
+    kv.set_tokens(nk * lay.t)
+    qg = sum(lay.pack_vec(Q[tau], tau) for tau in range(lay.t))
+    oq, gq = _enc_both(e, qg, lv + 1, 10)
+    full = np.einsum("ahe,nhe->ahn", Q, K)
+    ql = float(octx.mod[lv + 1])
+    for delta in deltas:
+        coeffs = [octx.encode_coeffs(p, ql) for p in lay.inner_rotation_plaintexts(delta)]
+        opts = [octx.pt_from_coeffs(cf, lv + 1, ql) for cf in coeffs]
+        rot = gctx.inner_rot(lay.t, delta, lv + 1, coeffs=np.stack(coeffs))
+        assert rot.steps() == lay.inner_rotation_steps(delta)
+        ox = vmm.inner_rotate(vmm.CkksOps(octx, okeys, pt_scale=ql), lay, oq, delta, opts)
+        gx = gctx.rope_apply(gkeys, rot, gq)
+        _same(e, ox, gx)
+        masks = [omask(c) for c in range(nk)]
+        if unrolled:
+            om = vmm.qk_scores_unrolled(octx, okeys, lay, ox, okc, masks, replicate=False)
+        else:
+            om = vmm.qk_scores(vmm.CkksOps(octx, okeys), lay, ox, okc, masks, replicate=False)
+        gm = gctx.vmm_kv(gkeys, kv, B.CM_QK_GROUP, gx)
+        _same(e, om, gm)
+        got = lay.unpack_scores(gctx.decrypt(e["gsk"], gm).real, nk * lay.t)
+        for n in range(nk * lay.t):
+            assert np.abs(got[:, n] - full[(n % lay.t - delta) % lay.t, :, n]).max() < TOL
+    # the library's own masks
+    rot2 = gctx.inner_rot(lay.t, 3, lv + 1)
+    gk3 = gctx.keygen_rotations(e["gsk"], rot2.steps(), 2)
+    out = gctx.decrypt(e["gsk"], gctx.rope_apply(gk3, rot2, gq)).real
+    want = sum(lay.pack_vec(Q[tau], (tau + 3) % lay.t) for tau in range(lay.t))
+    assert np.abs(out - want).max() < TOL
+    with pytest.raises(B.CachemirError) as ei:
+        gctx.inner_rot(lay.t, lay.t, lv + 1)
+    assert ei.value.status == CM_E_LAYOUT
