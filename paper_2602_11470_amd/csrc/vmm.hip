@@ -34,7 +34,7 @@ struct cm_vmm_plan {
     int pt_limbs;              // level+1, or level+1+K when raised
     int *d_pt_mods = nullptr;  // modulus index of every plaintext limb
     u64 *d_pts = nullptr;      // r_i*r_o plaintexts of pt_limbs limbs, multiplier form, blocked by 64 coefficients
-    u64 *d_work = nullptr;     // r_i baby + r_o inner ciphertexts of 2*pt_limbs limbs + 3 temporary ciphertexts
+    u64 *d_work = nullptr;     // r_i baby + r_o inner ciphertexts of 2*pt_limbs limbs, 3 temporary ciphertexts, one more sum
 };
 
 static int ilog2(int x) {
