@@ -263,7 +263,10 @@ class Context:
         """Evaluation key from the secret `s_from` to sk, one pair per digit of the full chain:
         b_j = -a_j s + e_j + [P mod q_i] s_from on the limbs q_i of digit j, nothing added on
         the other limbs (P * (Q/Q_j) * ((Q/Q_j)^-1 mod Q_j) is 1 there... times P, and 0
-        elsewhere)."""
+        elsewhere).  The uniform half a_j is drawn directly in the evaluation domain (position i of the
+        stored order takes draw i of its stream): the transform is a bijection, so this is the same
+        distribution as drawing coefficients, and an implementation may then regenerate a_j from the
+        seed wherever it is used instead of storing it."""
         prm, all_idx = self.prm, list(range(len(self.mod)))
         P = 1
         for m in prm.p:
@@ -271,7 +274,7 @@ class Context:
         digits = prm.digits(prm.L)
         bs, as_ = [], []
         for j, D in enumerate(digits):
-            a = self.ntt(self._uniform(all_idx, seed, ST_EVK_A, ident, j), all_idx)
+            a = self._uniform(all_idx, seed, ST_EVK_A, ident, j)
             e = self.ntt(self.from_i64(self._gauss(seed, ST_EVK_E, ident, j), all_idx), all_idx)
             b = self.sub(e, self.mul(a, sk["ntt"], all_idx), all_idx)
             fac = [P % int(self.mod[i]) if i in D else 0 for i in all_idx]

@@ -167,6 +167,10 @@ def test_evaluation_key_structure(small):
             want = [(int(e[c]) + (P * int(s_from[i, c]) if i in D else 0)) % q
                     for c in range(ctx.n)]
             assert lhs[i].tolist() == want
+    # the uniform half is the generator's stream itself, position by position in the stored order
+    # (what lets an implementation regenerate it from the seed instead of storing it)
+    for j in range(len(digits)):
+        assert np.array_equal(evk.a[j], ctx._uniform(all_idx, 9, ckks.ST_EVK_A, g, j))
 
 
 @pytest.mark.parametrize("level", [4, 2, 0])
