@@ -76,6 +76,8 @@ class Context:
         self.n, self.S = prm.n, prm.n // 2
         self.mod = np.array(prm.moduli, dtype=np.uint64)
         self.psi = np.array(prm.psi, dtype=np.uint64)
+        logn = prm.n.bit_length() - 1
+        self.brev = np.array([int(format(k, f"0{logn}b")[::-1], 2) for k in range(prm.n)], dtype=np.int64)
         self.cdt = gauss_cdt(prm.sigma)
         self.rot_count = 0      # instrumentation for the op-count pins
         self.ptmul_count = 0
@@ -263,8 +265,9 @@ class Context:
         """Evaluation key from the secret `s_from` to sk, one pair per digit of the full chain:
         b_j = -a_j s + e_j + [P mod q_i] s_from on the limbs q_i of digit j, nothing added on
         the other limbs (P * (Q/Q_j) * ((Q/Q_j)^-1 mod Q_j) is 1 there... times P, and 0
-        elsewhere).  The uniform half a_j is drawn directly in the evaluation domain (position i of the
-        stored order takes draw i of its stream): the transform is a bijection, so this is the same
+        elsewhere).  The uniform half a_j is drawn directly in the evaluation domain: its value at
+        psi^(2k+1) is draw brev(k) of its stream (the draws fill the bit-reversed order in which an
+        in-place transform leaves its output).  The transform is a bijection, so this is the same
         distribution as drawing coefficients, and an implementation may then regenerate a_j from the
         seed wherever it is used instead of storing it."""
         prm, all_idx = self.prm, list(range(len(self.mod)))
@@ -274,7 +277,7 @@ class Context:
         digits = prm.digits(prm.L)
         bs, as_ = [], []
         for j, D in enumerate(digits):
-            a = self._uniform(all_idx, seed, ST_EVK_A, ident, j)
+            a = self._uniform(all_idx, seed, ST_EVK_A, ident, j)[:, self.brev]
             e = self.ntt(self.from_i64(self._gauss(seed, ST_EVK_E, ident, j), all_idx), all_idx)
             b = self.sub(e, self.mul(a, sk["ntt"], all_idx), all_idx)
             fac = [P % int(self.mod[i]) if i in D else 0 for i in all_idx]

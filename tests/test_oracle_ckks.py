@@ -167,10 +167,14 @@ def test_evaluation_key_structure(small):
             want = [(int(e[c]) + (P * int(s_from[i, c]) if i in D else 0)) % q
                     for c in range(ctx.n)]
             assert lhs[i].tolist() == want
-    # the uniform half is the generator's stream itself, position by position in the stored order
+    # the uniform half is the generator's stream itself: the value at psi^(2k+1) is draw brev(k)
     # (what lets an implementation regenerate it from the seed instead of storing it)
+    logn = ctx.n.bit_length() - 1
+    brev = [int(format(k, f"0{logn}b")[::-1], 2) for k in range(ctx.n)]
     for j in range(len(digits)):
-        assert np.array_equal(evk.a[j], ctx._uniform(all_idx, 9, ckks.ST_EVK_A, g, j))
+        u = ctx._uniform(all_idx, 9, ckks.ST_EVK_A, g, j)
+        assert all(np.array_equal(evk.a[j][:, k], u[:, brev[k]]) for k in (0, 1, 2, 5, ctx.n - 1))
+        assert np.array_equal(evk.a[j][:, brev], u)
 
 
 @pytest.mark.parametrize("level", [4, 2, 0])
