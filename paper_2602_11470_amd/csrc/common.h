@@ -112,6 +112,7 @@ struct cm_ctx {
     // device tables, indexed by modulus index
     ModC *d_modc = nullptr;               // [nmod]
     u64 *d_pmont = nullptr;               // [L+1] P = p_0 .. p_{K-1} mod q_i, multiplier (Montgomery) form
+    u64 *d_ubound = nullptr;              // [nmod] q * floor(2^64 / q): uniform draws at or above it are rejected
     u64 *d_tw = nullptr, *d_twp = nullptr;      // forward twiddles psi^brev(i) and companions [nmod][n]
     u64 *d_itw = nullptr, *d_itwp = nullptr;    // inverse
     u64 *d_ninv = nullptr, *d_ninvp = nullptr;  // n^{-1} [nmod]
@@ -150,10 +151,12 @@ struct cm_sk {
 };
 
 struct EvkEntry {
-    u64 *d = nullptr;              // [digits][2][nmod][n] Montgomery form, evaluation domain
+    u64 *d = nullptr;              // b halves [digits][nmod][n] (multiplier form, evaluation domain), then the
+                                   // [digits][nmod] generator keys of the streams of the a halves (not stored)
 };
 struct cm_evk {
     int digits;
+    u64 seed = 0;                  // the seed every key of the set was generated from
     std::map<u64, EvkEntry> keys;  // Galois element (0 = relinearisation)
 };
 

@@ -324,6 +324,9 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
             pm.push_back((u64)((((u128)P) << 64) % q));
         }
         ctx->d_pmont = upload(pm);
+        std::vector<u64> ub;
+        for (int i = 0; i < ctx->nmod; i++) ub.push_back(ctx->mod[i] * (0xFFFFFFFFFFFFFFFFULL / ctx->mod[i]));
+        ctx->d_ubound = upload(ub);
     }
     ctx->d_tw = upload(tw);
     ctx->d_twp = upload(twp);
@@ -374,7 +377,7 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
                    (size_t)CM_KS_BATCH * 2 * (2 * ext + ctx->L + 1);  // batched ModDown of hoisted rotations
     ctx->arena_words = limbs * n;
     if (hipMalloc((void **)&ctx->arena, ctx->arena_words * sizeof(u64)) != hipSuccess) ctx->arena = nullptr;
-    if (!ctx->d_modc || !ctx->d_pmont || !ctx->d_tw || !ctx->d_twp || !ctx->d_itw || !ctx->d_itwp || !ctx->d_ninv ||
+    if (!ctx->d_modc || !ctx->d_pmont || !ctx->d_ubound || !ctx->d_tw || !ctx->d_twp || !ctx->d_itw || !ctx->d_itwp || !ctx->d_ninv ||
         !ctx->d_ninvp || !ctx->d_idx || !ctx->d_cdt || !ctx->arena) {
         cm_ctx_destroy(ctx);
         return CM_E_NOMEM;
@@ -413,6 +416,7 @@ extern "C" void cm_ctx_destroy(cm_ctx *ctx) {
     if (ctx->aux) hipStreamDestroy(ctx->aux);
     hipFree(ctx->d_modc);
     hipFree(ctx->d_pmont);
+    hipFree(ctx->d_ubound);
     hipFree(ctx->d_tw);
     hipFree(ctx->d_twp);
     hipFree(ctx->d_itw);

@@ -60,7 +60,8 @@ u64 rng_key(u64 seed, u64 stream);
 u64 rng_draw(u64 key, u64 ctr);
 void launch_sample_uniform(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs, u64 seed, u64 stream_base, hipStream_t st);
 void launch_sample_gauss(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs, u64 seed, u64 stream, hipStream_t st);
-void launch_evk_assemble(cm_ctx *ctx, u64 *b_out, u64 *a_io, const u64 *e, const u64 *s_mont, const u64 *d_fac, u64 g, hipStream_t st);
+void launch_evk_assemble(cm_ctx *ctx, u64 *b_out, const u64 *a_in, const u64 *e, const u64 *s_mont, const u64 *d_fac, u64 g,
+                         hipStream_t st);
 void launch_encrypt(cm_ctx *ctx, u64 *c0, const u64 *a, const u64 *e, const u64 *s_mont, const u64 *pt, int limbs, hipStream_t st);
 void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int ncomp, int ct_limbs, int limbs, hipStream_t st);
 // pts: all r_i*r_o plaintexts in the blocked layout written by launch_pt_block

@@ -261,11 +261,32 @@ void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_ste
 // rotations).  Two adjacent coefficients per lane (16-byte accesses); the permutation keeps
 // aligned pairs together (it maps i^1 to src^1).
 // `extra` may be the output itself (a running sum): every lane reads its own words before it writes them.
+// The counter-based generator (its finaliser; the streams are defined with the samplers below).
+#define GOLD 0x9E3779B97F4A7C15ULL
+__host__ __device__ __forceinline__ u64 mix64(u64 z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+// An evaluation key in HBM is its b half only: b_j in multiplier form, [digit][nmod][n], followed by the [digit][nmod]
+// keys of the generator streams of a_j.  The uniform half is drawn directly in the evaluation domain, so word i of
+// limb mi of a_j is draw i of that stream (rejected at or above bound = q floor(2^64/q), then reduced): the inner
+// products regenerate it instead of reading it, which takes a third off their traffic.  REDC(v * 2^128 mod q)
+// = (v mod q) 2^64 mod q is the multiplier form at once, for any 64-bit v.
+__device__ __forceinline__ u64 evk_a_word(u64 stream_key, unsigned i, u64 bound, const ModC &m) {
+    u64 att = 0, v;
+    do {
+        v = mix64(stream_key + (((att << 32) | (u64)i) + 1) * GOLD);
+        att++;
+    } while (v >= bound);
+    return redc((u128)v * m.r2, m.q, m.qinv);
+}
 __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
                                                        const u64 *__restrict__ dig, const u64 *__restrict__ evk,
                                                        const ModC *__restrict__ modc,
                                 int beta, int ext, int level, int L, int nmod, int n, int logn, unsigned g,
-                                const u64 *__restrict__ c0, const u64 *__restrict__ pmont, const u64 *extra) {
+                                const u64 *__restrict__ c0, const u64 *__restrict__ pmont, const u64 *extra, int kdig,
+                                const u64 *__restrict__ ubound) {
     unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
     int r = blockIdx.y;
     int mi = r <= level ? r : L + 1 + (r - level - 1);
@@ -273,16 +294,18 @@ __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
     unsigned src = g ? perm_src(i2, g, logn) : i2;
     unsigned base = src & ~1u;
     bool swap = src & 1u;
+    const u64 bound = ubound[mi];
     u128 a0 = 0, a1 = 0, b0 = 0, b1 = 0;
     for (int j = 0; j < beta; j++) {
         ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(dig + ((size_t)j * ext + r) * n + base);
         u64 dx = swap ? d.y : d.x, dy = swap ? d.x : d.y;
-        const u64 *kb = evk + (((size_t)j * 2 + 0) * nmod + mi) * n + i2;
+        const u64 *kb = evk + ((size_t)j * nmod + mi) * n + i2;
         // the key is streamed once: non-temporal, so that the raised digits (re-read by every
         // hoisted rotation) are the lines that stay in the last-level cache
         ulonglong2 eb, ea;
         eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
-        ea.x = __builtin_nontemporal_load(kb + (size_t)nmod * n), ea.y = __builtin_nontemporal_load(kb + (size_t)nmod * n + 1);
+        const u64 sk_ = evk[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
+        ea.x = evk_a_word(sk_, i2, bound, m), ea.y = evk_a_word(sk_, i2 + 1, bound, m);
         b0 += (u128)dx * eb.x;
         b1 += (u128)dy * eb.y;
         a0 += (u128)dx * ea.x;
@@ -310,12 +333,14 @@ __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
 // (each with its own digits, key, Galois element and optional c0) and an optional addend.
 __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const ModC *__restrict__ modc, int beta, int ext,
                                                              int level, int L, int nmod, int n, int logn,
-                                                             const u64 *__restrict__ pmont) {
+                                                             const u64 *__restrict__ pmont, int kdig,
+                                                             const u64 *__restrict__ ubound) {
     const unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
     const int r = blockIdx.y, z = blockIdx.z;
     const int mi = r <= level ? r : L + 1 + (r - level - 1);
     const ModC m = modc[mi];
     const size_t o = (size_t)r * n + i2;
+    const u64 bound = ubound[mi];
     ulonglong2 r0 = make_ulonglong2(0, 0), r1 = make_ulonglong2(0, 0);
     if (b.extra[z]) {
         r0 = *reinterpret_cast<const ulonglong2 *>(b.extra[z] + o);
@@ -330,10 +355,11 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
         for (int j = 0; j < beta; j++) {
             ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(it.dig + ((size_t)j * ext + r) * n + base);
             u64 dx = swap ? d.y : d.x, dy = swap ? d.x : d.y;
-            const u64 *kb = it.key + (((size_t)j * 2 + 0) * nmod + mi) * n + i2;
+            const u64 *kb = it.key + ((size_t)j * nmod + mi) * n + i2;
             ulonglong2 eb, ea;
             eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
-            ea.x = __builtin_nontemporal_load(kb + (size_t)nmod * n), ea.y = __builtin_nontemporal_load(kb + (size_t)nmod * n + 1);
+            const u64 sk_ = it.key[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
+            ea.x = evk_a_word(sk_, i2, bound, m), ea.y = evk_a_word(sk_, i2 + 1, bound, m);
             b0 += (u128)dx * eb.x;
             b1 += (u128)dy * eb.y;
             a0 += (u128)dx * ea.x;
@@ -362,7 +388,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
 #define IP_SHARED_MAX_BETA 8
 __global__ __launch_bounds__(TPB) void k_inner_product_shared_key(IpBatch b, const ModC *__restrict__ modc, int beta,
                                                                   int ext, int level, int L, int nmod, int n, int logn,
-                                                                  unsigned g) {
+                                                                  unsigned g, int kdig, const u64 *__restrict__ ubound) {
     const unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
     const int r = blockIdx.y;
     const int mi = r <= level ? r : L + 1 + (r - level - 1);
@@ -373,12 +399,14 @@ __global__ __launch_bounds__(TPB) void k_inner_product_shared_key(IpBatch b, con
     const bool swap = src & 1u;
     ulonglong2 eb[IP_SHARED_MAX_BETA], ea[IP_SHARED_MAX_BETA];
     const u64 *key = b.it[0].key;
+    const u64 bound = ubound[mi];
 #pragma unroll
     for (int j = 0; j < IP_SHARED_MAX_BETA; j++) {
         if (j < beta) {
-            const u64 *kb = key + (((size_t)j * 2 + 0) * nmod + mi) * n + i2;
+            const u64 *kb = key + ((size_t)j * nmod + mi) * n + i2;
             eb[j].x = __builtin_nontemporal_load(kb), eb[j].y = __builtin_nontemporal_load(kb + 1);
-            ea[j].x = __builtin_nontemporal_load(kb + (size_t)nmod * n), ea[j].y = __builtin_nontemporal_load(kb + (size_t)nmod * n + 1);
+            const u64 sk_ = key[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
+            ea[j].x = evk_a_word(sk_, i2, bound, m), ea[j].y = evk_a_word(sk_, i2 + 1, bound, m);
         }
     }
     for (int z = 0; z < b.nz; z++) {
@@ -422,13 +450,13 @@ void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, in
     }
     Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz, st);
     hipLaunchKernelGGL(k_inner_product_shared_key, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, b, ctx->d_modc, beta, ext,
-                       level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g);
+                       level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, (ctx->L + ctx->alpha) / ctx->alpha, ctx->d_ubound);
 }
 void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st) {
     Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz * b.nsum, st);
     int ext = level + 1 + ctx->K;
     hipLaunchKernelGGL(k_inner_product_batch, dim3(ctx->n / (2 * TPB), ext, b.nz), dim3(TPB), 0, st, b, ctx->d_modc, beta, ext,
-                       level, ctx->L, ctx->nmod, ctx->n, ctx->logn, ctx->d_pmont);
+                       level, ctx->L, ctx->nmod, ctx->n, ctx->logn, ctx->d_pmont, (ctx->L + ctx->alpha) / ctx->alpha, ctx->d_ubound);
 }
 // out[2][ext][n] = (P c0, P c1) on the ciphertext limbs, zero on the special limbs
 __global__ void k_raise_by_P(u64 *__restrict__ out, const u64 *__restrict__ in, const ModC *__restrict__ modc,
@@ -453,7 +481,8 @@ void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u
     Prof prof_(ctx, CM_K_INNER_PRODUCT, 1, st);
     int ext = level + 1 + ctx->K;
     hipLaunchKernelGGL(k_inner_product, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, u0, u1, dig, evk, ctx->d_modc,
-                       beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, c0, ctx->d_pmont, extra);
+                       beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, c0, ctx->d_pmont, extra,
+                       (ctx->L + ctx->alpha) / ctx->alpha, ctx->d_ubound);
 }
 
 // ---- ModDown tail: out = (u - conv) * P^{-1} (+ addend, optionally through the Galois map) ------------
@@ -509,12 +538,6 @@ void launch_rescale_finish(cm_ctx *ctx, u64 *out, const u64 *in, const u64 *red,
 }
 
 // ---- counter-based sampling (must reproduce the generator's published definition bit for bit) --------
-#define GOLD 0x9E3779B97F4A7C15ULL
-__host__ __device__ __forceinline__ u64 mix64(u64 z) {
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
-    return z ^ (z >> 31);
-}
 u64 rng_key(u64 seed, u64 stream) { return mix64(mix64(seed) ^ stream); }
 u64 rng_draw(u64 key, u64 ctr) { return mix64(key + (ctr + 1) * GOLD); }
 
@@ -557,13 +580,13 @@ void launch_sample_gauss(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs,
 // ---- keys and encryption ---------------------------------------------------------------------------
 // b = e - a s + fac_l * s_from, then (b, a) stored in multiplier form.  s_mont: secret, evaluation
 // domain, multiplier form, rows = all moduli.  s_from = s through the Galois map g (g != 0) or s^2.
-__global__ void k_evk_assemble(u64 *b_out, u64 *a_io, const u64 *e, const u64 *s_mont, const u64 *fac,
+__global__ void k_evk_assemble(u64 *b_out, const u64 *a_in, const u64 *e, const u64 *s_mont, const u64 *fac,
                                const ModC *modc, int n, int logn, unsigned g) {
     unsigned i = blockIdx.x * TPB + threadIdx.x;
     int l = blockIdx.y;
     const ModC m = modc[l];
     size_t o = (size_t)l * n + i;
-    u64 a = a_io[o];
+    u64 a = a_in[o];
     u64 b = submod(e[o], redc((u128)a * s_mont[o], m.q, m.qinv), m.q);
     u64 f = fac[l];
     if (f) {
@@ -572,10 +595,9 @@ __global__ void k_evk_assemble(u64 *b_out, u64 *a_io, const u64 *e, const u64 *s
         b = addmod(b, redc((u128)f * sf, m.q, m.qinv), m.q);
     }
     b_out[o] = to_mont(b, m);
-    a_io[o] = to_mont(a, m);
 }
-void launch_evk_assemble(cm_ctx *ctx, u64 *b_out, u64 *a_io, const u64 *e, const u64 *s_mont, const u64 *d_fac, u64 g, hipStream_t st) {
-    hipLaunchKernelGGL(k_evk_assemble, dim3(ctx->n / TPB, ctx->nmod), dim3(TPB), 0, st, b_out, a_io, e, s_mont, d_fac,
+void launch_evk_assemble(cm_ctx *ctx, u64 *b_out, const u64 *a_in, const u64 *e, const u64 *s_mont, const u64 *d_fac, u64 g, hipStream_t st) {
+    hipLaunchKernelGGL(k_evk_assemble, dim3(ctx->n / TPB, ctx->nmod), dim3(TPB), 0, st, b_out, a_in, e, s_mont, d_fac,
                        ctx->d_modc, ctx->n, ctx->logn, (unsigned)g);
 }
 // c0 = e - a s + m

@@ -549,15 +549,18 @@ extern "C" cm_status cm_sk_coeffs(const cm_ctx *ctx, const cm_sk *sk, int8_t *ou
 static cm_status make_key(cm_ctx *ctx, const cm_sk *sk, u64 g, u64 seed, EvkEntry *entry, int digits) {
     const size_t n = ctx->n, nm = ctx->nmod;
     Arena A = arena_of(ctx);
-    HIPCHK(hipMalloc((void **)&entry->d, (size_t)digits * 2 * nm * n * 8));
+    // b_j for every digit, then the generator keys of the streams of a_j (a_j itself is regenerated where it is used)
+    HIPCHK(hipMalloc((void **)&entry->d, ((size_t)digits * nm * n + (size_t)digits * nm) * 8));
+    std::vector<u64> stream_keys;
     auto digs = digits_at(ctx, ctx->L);
     u64 *d_fac = nullptr;
     HIPCHK(hipMalloc((void **)&d_fac, nm * 8));
     for (int j = 0; j < digits; j++) {
-        u64 *b = entry->d + ((size_t)j * 2 + 0) * nm * n, *a = b + nm * n, *e = A.tmp[0];
+        u64 *b = entry->d + (size_t)j * nm * n, *a = A.tmp[1], *e = A.tmp[0];
+        // a_j: drawn in the evaluation domain (no transform); limb mi uses the stream stream_id(.., j, 0) | mi
         launch_sample_uniform(ctx, a, iota_idx(ctx), (int)nm, seed, stream_id(ST_EVK_A, g, j, 0), 0);
+        for (size_t mi = 0; mi < nm; mi++) stream_keys.push_back(rng_key(seed, stream_id(ST_EVK_A, g, j, 0) | (u64)mi));
         launch_sample_gauss(ctx, e, iota_idx(ctx), (int)nm, seed, stream_id(ST_EVK_E, g, j, 0), 0);
-        launch_ntt(ctx, a, iota_idx(ctx), (int)nm, false, 0);
         launch_ntt(ctx, e, iota_idx(ctx), (int)nm, false, 0);
         // P * (Q/Q_j) * ((Q/Q_j)^{-1} mod Q_j) is P on the digit's own limbs and 0 on all others
         std::vector<u64> fac(nm, 0);
@@ -571,6 +574,7 @@ static cm_status make_key(cm_ctx *ctx, const cm_sk *sk, u64 g, u64 seed, EvkEntr
         HIPCHK(hipDeviceSynchronize());
     }
     hipFree(d_fac);
+    HIPCHK(hipMemcpy(entry->d + (size_t)digits * nm * n, stream_keys.data(), stream_keys.size() * 8, hipMemcpyHostToDevice));
     return CM_OK;
 }
 
@@ -581,6 +585,7 @@ extern "C" cm_status cm_keygen_rotations(cm_ctx *ctx, const cm_sk *sk, const int
     cm_evk *evk = new (std::nothrow) cm_evk();
     if (!evk) return CM_E_NOMEM;
     evk->digits = (ctx->L + ctx->alpha) / ctx->alpha;
+    evk->seed = seed;
     std::vector<u64> ids;
     for (size_t i = 0; i < nsteps; i++) ids.push_back(galois_of_step(ctx, steps[i]));
     if (with_relin) ids.push_back(0);
@@ -610,7 +615,13 @@ extern "C" cm_status cm_evk_export(cm_ctx *ctx, const cm_evk *evk, int32_t step,
     if (!key) return CM_E_NOKEY;
     const size_t n = ctx->n, nm = ctx->nmod;
     Arena A = arena_of(ctx);
-    launch_from_mont(ctx, A.tmp[0], key + ((size_t)digit * 2 + comp) * nm * n, iota_idx(ctx), (int)nm, 0);
+    if (comp == 0) {
+        launch_from_mont(ctx, A.tmp[0], key + (size_t)digit * nm * n, iota_idx(ctx), (int)nm, 0);
+    } else {
+        // a_j is not stored: its limbs are the uniform streams of (seed, key id, digit), in the evaluation domain
+        const u64 g = relin ? 0 : galois_of_step(ctx, step);
+        launch_sample_uniform(ctx, A.tmp[0], iota_idx(ctx), (int)nm, evk->seed, stream_id(ST_EVK_A, g, digit, 0), 0);
+    }
     launch_ntt(ctx, A.tmp[0], iota_idx(ctx), (int)nm, true, 0);
     HIPCHK(hipMemcpy(out, A.tmp[0], nm * n * 8, hipMemcpyDeviceToHost));
     return CM_OK;
