@@ -270,16 +270,18 @@ __host__ __device__ __forceinline__ u64 mix64(u64 z) {
 }
 // An evaluation key in HBM is its b half only: b_j in multiplier form, [digit][nmod][n], followed by the [digit][nmod]
 // keys of the generator streams of a_j.  The uniform half is drawn directly in the evaluation domain, so word i of
-// limb mi of a_j is draw i of that stream (rejected at or above bound = q floor(2^64/q), then reduced): the inner
-// products regenerate it instead of reading it, which takes a third off their traffic.  REDC(v * 2^128 mod q)
-// = (v mod q) 2^64 mod q is the multiplier form at once, for any 64-bit v.
-__device__ __forceinline__ u64 evk_a_word(u64 stream_key, unsigned i, u64 bound, const ModC &m) {
-    u64 att = 0, v;
-    do {
-        v = mix64(stream_key + (((att << 32) | (u64)i) + 1) * GOLD);
-        att++;
-    } while (v >= bound);
-    return redc((u128)v * m.r2, m.q, m.qinv);
+// limb mi of a_j is draw i of that stream (rejected at or above bound = q floor(2^64/q), then taken mod q): the inner
+// products regenerate it instead of reading it, which takes a third off their traffic.  The draw enters the sums as
+// the raw 64-bit word v (v = a mod q): sum_j d_j v_j < beta q 2^64 fits 128 bits, REDC gives (sum 2^-64) mod q below
+// (beta + 1) q, and a second REDC against 2^128 mod q gives sum mod q in [0, q) -- two reductions per output instead of
+// one per key word.  ctr_gold = (i + 1) GOLD is the counter term of attempt 0, shared by all digits of a lane.
+__device__ __forceinline__ u64 evk_a_draw(u64 stream_key, u64 ctr_gold, unsigned i, u64 bound) {
+    u64 v = mix64(stream_key + ctr_gold);
+    for (u64 att = 1; v >= bound; att++) v = mix64(stream_key + (((att << 32) | (u64)i) + 1) * GOLD);
+    return v;
+}
+__device__ __forceinline__ u64 redc_raw(u128 T, const ModC &m) {
+    return redc((u128)redc(T, m.q, m.qinv) * m.r2, m.q, m.qinv);
 }
 __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
                                                        const u64 *__restrict__ dig, const u64 *__restrict__ evk,
@@ -294,7 +296,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
     unsigned src = g ? perm_src(i2, g, logn) : i2;
     unsigned base = src & ~1u;
     bool swap = src & 1u;
-    const u64 bound = ubound[mi];
+    const u64 bound = ubound[mi], cg0 = ((u64)i2 + 1) * GOLD, cg1 = cg0 + GOLD;
     u128 a0 = 0, a1 = 0, b0 = 0, b1 = 0;
     for (int j = 0; j < beta; j++) {
         ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(dig + ((size_t)j * ext + r) * n + base);
@@ -305,7 +307,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
         ulonglong2 eb, ea;
         eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
         const u64 sk_ = evk[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
-        ea.x = evk_a_word(sk_, i2, bound, m), ea.y = evk_a_word(sk_, i2 + 1, bound, m);
+        ea.x = evk_a_draw(sk_, cg0, i2, bound), ea.y = evk_a_draw(sk_, cg1, i2 + 1, bound);
         b0 += (u128)dx * eb.x;
         b1 += (u128)dy * eb.y;
         a0 += (u128)dx * ea.x;
@@ -319,7 +321,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
     }
     size_t o = (size_t)r * n + i2;
     ulonglong2 r0 = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
-    ulonglong2 r1 = make_ulonglong2(redc(a0, m.q, m.qinv), redc(a1, m.q, m.qinv));
+    ulonglong2 r1 = make_ulonglong2(redc_raw(a0, m), redc_raw(a1, m));
     if (extra) {                      // + a sum already in the extended basis, [2][ext][n]
         ulonglong2 e0 = *reinterpret_cast<const ulonglong2 *>(extra + o);
         ulonglong2 e1 = *reinterpret_cast<const ulonglong2 *>(extra + (size_t)ext * n + o);
@@ -340,7 +342,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
     const int mi = r <= level ? r : L + 1 + (r - level - 1);
     const ModC m = modc[mi];
     const size_t o = (size_t)r * n + i2;
-    const u64 bound = ubound[mi];
+    const u64 bound = ubound[mi], cg0 = ((u64)i2 + 1) * GOLD, cg1 = cg0 + GOLD;
     ulonglong2 r0 = make_ulonglong2(0, 0), r1 = make_ulonglong2(0, 0);
     if (b.extra[z]) {
         r0 = *reinterpret_cast<const ulonglong2 *>(b.extra[z] + o);
@@ -359,7 +361,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
             ulonglong2 eb, ea;
             eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
             const u64 sk_ = it.key[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
-            ea.x = evk_a_word(sk_, i2, bound, m), ea.y = evk_a_word(sk_, i2 + 1, bound, m);
+            ea.x = evk_a_draw(sk_, cg0, i2, bound), ea.y = evk_a_draw(sk_, cg1, i2 + 1, bound);
             b0 += (u128)dx * eb.x;
             b1 += (u128)dy * eb.y;
             a0 += (u128)dx * ea.x;
@@ -375,7 +377,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
             b1 += (u128)(swap ? d.x : d.y) * pm;
         }
         r0.x = addmod(r0.x, redc(b0, m.q, m.qinv), m.q), r0.y = addmod(r0.y, redc(b1, m.q, m.qinv), m.q);
-        r1.x = addmod(r1.x, redc(a0, m.q, m.qinv), m.q), r1.y = addmod(r1.y, redc(a1, m.q, m.qinv), m.q);
+        r1.x = addmod(r1.x, redc_raw(a0, m), m.q), r1.y = addmod(r1.y, redc_raw(a1, m), m.q);
     }
     *reinterpret_cast<ulonglong2 *>(b.out[z] + o) = r0;
     *reinterpret_cast<ulonglong2 *>(b.out[z] + (size_t)ext * n + o) = r1;
@@ -399,14 +401,14 @@ __global__ __launch_bounds__(TPB) void k_inner_product_shared_key(IpBatch b, con
     const bool swap = src & 1u;
     ulonglong2 eb[IP_SHARED_MAX_BETA], ea[IP_SHARED_MAX_BETA];
     const u64 *key = b.it[0].key;
-    const u64 bound = ubound[mi];
+    const u64 bound = ubound[mi], cg0 = ((u64)i2 + 1) * GOLD, cg1 = cg0 + GOLD;
 #pragma unroll
     for (int j = 0; j < IP_SHARED_MAX_BETA; j++) {
         if (j < beta) {
             const u64 *kb = key + ((size_t)j * nmod + mi) * n + i2;
             eb[j].x = __builtin_nontemporal_load(kb), eb[j].y = __builtin_nontemporal_load(kb + 1);
             const u64 sk_ = key[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
-            ea[j].x = evk_a_word(sk_, i2, bound, m), ea[j].y = evk_a_word(sk_, i2 + 1, bound, m);
+            ea[j].x = evk_a_draw(sk_, cg0, i2, bound), ea[j].y = evk_a_draw(sk_, cg1, i2 + 1, bound);
         }
     }
     for (int z = 0; z < b.nz; z++) {
@@ -424,7 +426,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_shared_key(IpBatch b, con
             }
         }
         ulonglong2 r0 = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
-        ulonglong2 r1 = make_ulonglong2(redc(a0, m.q, m.qinv), redc(a1, m.q, m.qinv));
+        ulonglong2 r1 = make_ulonglong2(redc_raw(a0, m), redc_raw(a1, m));
         if (b.it[z].c0) {
             ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(b.it[z].c0 + (size_t)r * n + base);
             r0.x = addmod(r0.x, swap ? d.y : d.x, m.q), r0.y = addmod(r0.y, swap ? d.x : d.y, m.q);
