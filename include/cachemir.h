@@ -108,12 +108,16 @@ void cm_sk_destroy(cm_sk *sk);
 /* host out[n]: secret coefficients in {-1,0,1}. */
 cm_status cm_sk_coeffs(const cm_ctx *ctx, const cm_sk *sk, int8_t *out);
 /* Keys for left rotations by steps[i] slots (negative = right), and for s^2 -> s if
- * with_relin.  Steps with equal Galois element share a key. */
+ * with_relin.  Steps with equal Galois element share a key.  A key is (b_j, a_j) per digit with
+ * b_j = -a_j s + e_j + P s_from on the digit's own limbs; a_j is uniform and drawn directly in the
+ * evaluation domain (its value at psi^(2k+1) is draw brev(k) of the counter-based generator's stream
+ * for (seed, key, digit, limb)), so only the b_j are kept in device memory, (L+1+K) n words per
+ * digit, and the kernels regenerate a_j where they use it. */
 cm_status cm_keygen_rotations(cm_ctx *ctx, const cm_sk *sk, const int32_t *steps, size_t nsteps,
                               int32_t with_relin, uint64_t seed, cm_evk **out);
 void cm_evk_destroy(cm_evk *evk);
 /* Canonical (coefficient-domain, plain residues) copy of one key polynomial to host
- * out[(L+1+K)*n]: step = rotation step (ignored if relin != 0), comp 0 = b, 1 = a. */
+ * out[(L+1+K)*n]: step = rotation step (ignored if relin != 0), comp 0 = b, 1 = a (regenerated). */
 cm_status cm_evk_export(cm_ctx *ctx, const cm_evk *evk, int32_t step, int32_t relin,
                         int32_t digit, int32_t comp, uint64_t *out);
 
