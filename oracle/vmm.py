@@ -290,6 +290,40 @@ def score_times_v(ops, lay: KvLayout, cs, v_cts):
     return acc
 
 
+def sv_unrolled_steps(lay: KvLayout):
+    """Rotation amounts of score_times_v_unrolled: baby steps, every multiple of the giant step, the
+    runs of the residue ladder."""
+    Ht = lay.H * lay.t
+    steps = [j * Ht for j in range(1, lay.r_i)] + [g * lay.r_i * Ht for g in range(1, lay.r_o)]
+    return steps + [a for grp in ladder_groups([1 << l for l in range(_log2(lay.t))]) for a in grp]
+
+
+def score_times_v_unrolled(ctx, keys, lay: KvLayout, cs, v_cts):
+    """score_times_v without dependent rotations after the products: the giant steps unrolled
+    (sum_g Rot(inner_g, g G), each rotation left in the extended basis next to P inner_0) and the
+    reduce ladder over the residues run there too, in runs of hoisted rotations (ckks.rotsum_raised),
+    before one ModDown and the rescale (the ladder form rescales first and reduces one level lower;
+    the message is the same)."""
+    Ht, lv = lay.H * lay.t, cs.level
+    ext = ctx.ext_idx(lv)
+    h = ctx.hoist(cs)
+    babies = [cs] + [ctx.rotate_hoisted(cs, h, j * Ht, keys) for j in range(1, lay.r_i)]
+    inner = []
+    for g in range(lay.r_o):
+        acc = None
+        for j in range(lay.r_i):
+            t = ctx.mul_ct(babies[j], v_cts[g * lay.r_i + j])
+            acc = t if acc is None else ctx.ct_add(acc, t)
+        inner.append(ctx.relinearize(acc, keys))
+    T = ctx.raise_ct(inner[0])
+    for g in range(1, lay.r_o):
+        R = ctx.rotate_hoisted_raised(inner[g], ctx.hoist(inner[g]), g * lay.r_i * Ht, keys)
+        T = [ctx.add(T[0], R[0], ext), ctx.add(T[1], R[1], ext)]
+    for amounts in ladder_groups([1 << l for l in range(_log2(lay.t))]):
+        T = ctx.rotsum_raised(T, lv, amounts, keys)
+    return ctx.rescale(ctx.moddown_ct(T, lv, inner[0].scale))
+
+
 def masked_two_rotations(ops, c, plaintexts, up, down):
     """c p0 + Rot(c p2, up) + Rot(c p1, down), then the rescale: three plaintext products, two
     rotations, one level."""

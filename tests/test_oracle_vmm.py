@@ -500,3 +500,27 @@ def test_inner_rotations_let_a_query_group_meet_every_key_residue():
             assert np.abs(got[:, n] - full[a, :, n]).max() < 1e-12
             seen[a, n] += 1
     assert np.array_equal(seen, np.ones_like(seen))
+
+
+@pytest.mark.parametrize("r_i", [0, 4])
+def test_unrolled_scores_times_v_decrypts_to_s_times_V(r_i):
+    prm = params.toy(n=512, n_qi=4, n_p=1, alpha=1)
+    ctx = ckks.Context(prm)
+    L = prm.L
+    lay = packing.KvLayout(ctx.S, 4, 8, r_i)             # t = 8
+    ntok = 3 * lay.t - 1
+    q, K, V, s = inputs.attention_inputs(5, 4, 2, 8, ntok)
+    sk = ctx.keygen_secret(1)
+    steps = vmm.sv_unrolled_steps(lay)
+    assert len(steps) == (lay.r_i - 1) + (lay.r_o - 1) + 7
+    keys = ctx.keygen_rotations(sk, sorted(set(steps) | set(lay.sv_steps())), 2, with_relin=True)
+    enc = lambda v, lv, seed: ctx.level_drop(ctx.encrypt(sk, ctx.encode(v, L), seed), lv)
+    vc = [enc(lay.pack_v(V, k), L - 1, 300 + k) for k in range(lay.E)]
+    cs = enc(lay.pack_scores(s), L - 1, 50)
+    r0 = ctx.rot_count
+    a = vmm.score_times_v_unrolled(ctx, keys, lay, cs, vc)
+    assert ctx.rot_count - r0 == len(steps) and a.level == L - 2
+    assert np.abs(lay.unpack_vec(ctx.decrypt(sk, a).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
+    ladder = vmm.score_times_v(vmm.CkksOps(ctx, keys), lay, cs, vc)
+    assert abs(a.scale / ladder.scale - 1) < 1e-12
+    assert np.abs(ctx.decrypt(sk, a) - ctx.decrypt(sk, ladder)).max() < 1e-6
