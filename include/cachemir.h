@@ -243,8 +243,11 @@ cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int
 /* flags: CM_KV_UNROLLED_LADDERS — in query-times-K the sum over the dims of every head (Sec. 5.1 step 2,
  * a rotate-and-add ladder of log2(dim) dependent rotations per key ciphertext) is computed in the
  * extended basis: the ladder is cut into ceil(L/3) runs, a run of g steps adds the 2^g - 1 hoisted
- * rotations by its subset sums (one ModUp per run), one ModDown ends it.  More rotation keys
- * (cm_kv_steps lists them), fewer ModUps and ModDowns.  Unknown bits: CM_E_INVAL. */
+ * rotations by its subset sums (one ModUp per run), one ModDown ends it.  scores-times-V takes the
+ * same form: its giant steps are unrolled (sum_g Rot(inner_g, g G), one key per multiple of the giant
+ * step) and its ladder over the residues runs in the extended basis before the one ModDown and the
+ * rescale.  More rotation keys (cm_kv_steps lists them), fewer ModUps and ModDowns.  Unknown bits:
+ * CM_E_INVAL. */
 enum { CM_KV_UNROLLED_LADDERS = 1 };
 cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level,
                           double scale, int32_t max_tokens, uint32_t flags, cm_kv **out);

@@ -35,6 +35,10 @@ struct cm_kv {
     // rotations by its subset sums
     bool unrolled = false;
     std::vector<std::vector<long long>> dim_groups;
+    // scores-times-V in the same form: giant steps unrolled (one key per multiple of the giant step), the ladder over
+    // the residues in runs; tables for raising the second components of up to CM_KS_BATCH inner sums at once
+    std::vector<std::vector<long long>> res_groups;
+    KsManyTables giant_tabs;
 };
 
 // ceil(L/3) runs of as equal length as possible, the longer ones first; a run lists its non-empty subset sums
@@ -105,6 +109,9 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
         std::vector<long long> ladder;
         for (int i = 0; i < ilog2(dim); i++) ladder.push_back((long long)(1 << i) * heads * kv->t);
         kv->dim_groups = ladder_groups(ladder);
+        std::vector<long long> res;
+        for (int l = 0; l < ilog2(kv->t); l++) res.push_back(1LL << l);
+        kv->res_groups = ladder_groups(res);
     }
     const size_t n = ctx->n, ctw = 2 * (size_t)(level + 1) * n;
     // work: r_i babies + r_o inner + tensor (1.5 ct) + 5 temporaries, all sized for level+1 inputs of append;
@@ -119,7 +126,8 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
         const size_t qku = qk + (kv->unrolled ? 2 * B * 2 * (size_t)(level + ctx->K) * n : 0);
         if (qku > kv->work_words) kv->work_words = qku;
         // scores-times-V: babies, inner sums, CM_KS_BATCH tensor sums, two temporaries, the batch's raise buffers
-        const size_t sv = (size_t)(kv->r_i + kv->r_o + 2) * ctw + B * (3 * ln + ln + (size_t)kl.beta * kl.ext * n);
+        const size_t sv = (size_t)(kv->r_i + kv->r_o + 2) * ctw + B * (3 * ln + ln + (size_t)kl.beta * kl.ext * n) +
+                          (kv->unrolled ? 2 * 2 * (size_t)kl.ext * n : 0);
         if (sv > kv->work_words) kv->work_words = sv;
         // append: mask, one product and its rescale, r_o - 1 shifted inputs, then the batch buffers
         const size_t ap = (size_t)(level + 2) * n + (size_t)(2 + kv->r_o) * ctw_up +
@@ -135,7 +143,8 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
               hipMalloc((void **)&kv->d_mask_vg, (size_t)(level + 2) * n * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_work, kv->work_words * 8) == hipSuccess;
     if (ok) ok = ks_many_tables_create(ctx, level, CM_KS_BATCH, &kv->relin_tabs, 3, 2) == CM_OK &&
-                 ks_many_tables_create(ctx, level - 1, CM_KS_BATCH, &kv->rot_tabs, 2, 1) == CM_OK;
+                 ks_many_tables_create(ctx, level - 1, CM_KS_BATCH, &kv->rot_tabs, 2, 1) == CM_OK &&
+                 (!kv->unrolled || ks_many_tables_create(ctx, level, CM_KS_BATCH, &kv->giant_tabs, 2, 1) == CM_OK);
     if (!ok) { cm_kv_destroy(kv); return CM_E_NOMEM; }
     hipMemset(kv->d_k, 0, (size_t)kv->nk_max * ctw * 8);      // an all-zero ciphertext encrypts 0
     hipMemset(kv->d_v, 0, (size_t)kv->E * ctw * 8);
@@ -157,6 +166,7 @@ extern "C" void cm_kv_destroy(cm_kv *kv) {
     hipFree(kv->d_work);
     ks_many_tables_destroy(&kv->relin_tabs);
     ks_many_tables_destroy(&kv->rot_tabs);
+    ks_many_tables_destroy(&kv->giant_tabs);
     delete kv;
 }
 // Parity hook: replace a base mask by given integer coefficients (kind 0: query-times-K mask at
@@ -180,8 +190,14 @@ static std::vector<int> kv_all_steps(const cm_kv *kv) {
         for (int i = 0; i < ilog2(kv->E); i++) s.push_back((1 << i) * kv->H * kv->t);      // sum over dims
     }
     for (int j = 1; j < kv->r_i; j++) s.push_back(j * kv->H * kv->t);                      // score baby steps
-    if (kv->r_o > 1) s.push_back(kv->r_i * kv->H * kv->t);                                 // score giant step
-    for (int l = 0; l < ilog2(kv->t); l++) s.push_back(1 << l);                            // reduce residues
+    if (kv->unrolled) {
+        for (int g = 1; g < kv->r_o; g++) s.push_back(g * kv->r_i * kv->H * kv->t);        // every multiple of the giant step
+        for (const auto &grp : kv->res_groups)
+            for (long long a : grp) s.push_back((int)a);                                       // reduce residues, run by run
+    } else {
+        if (kv->r_o > 1) s.push_back(kv->r_i * kv->H * kv->t);                             // score giant step
+        for (int l = 0; l < ilog2(kv->t); l++) s.push_back(1 << l);                        // reduce residues
+    }
     for (int g = 1; g < kv->r_o; g++) s.push_back(-(g * kv->r_i * kv->H * kv->t));         // append shifts
     return s;
 }
@@ -409,8 +425,14 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     if (!relin) return CM_E_NOKEY;
     const long long Ht = (long long)kv->H * kv->t;
     for (int j = 1; j < kv->r_i; j++) if (!find_key(evk, rot_g(kv, j * Ht))) return CM_E_NOKEY;
-    if (kv->r_o > 1 && !find_key(evk, rot_g(kv, kv->r_i * Ht))) return CM_E_NOKEY;
-    for (int l = 0; l < ilog2(kv->t); l++) if (!find_key(evk, rot_g(kv, 1 << l))) return CM_E_NOKEY;
+    if (kv->unrolled) {
+        for (int g = 1; g < kv->r_o; g++) if (!find_key(evk, rot_g(kv, (long long)g * kv->r_i * Ht))) return CM_E_NOKEY;
+        for (const auto &grp : kv->res_groups)
+            for (long long a : grp) if (!find_key(evk, rot_g(kv, a))) return CM_E_NOKEY;
+    } else {
+        if (kv->r_o > 1 && !find_key(evk, rot_g(kv, kv->r_i * Ht))) return CM_E_NOKEY;
+        for (int l = 0; l < ilog2(kv->t); l++) if (!find_key(evk, rot_g(kv, 1 << l))) return CM_E_NOKEY;
+    }
     const KsLevel &kl = ks_level(ctx, lv);
     const size_t B = CM_KS_BATCH, dblk = (size_t)kl.beta * kl.ext * n, ublk = 2 * (size_t)kl.ext * n;
     u64 *babies = kv->d_work, *inner = babies + (size_t)kv->r_i * ctw, *T = inner + (size_t)kv->r_o * ctw,
@@ -447,6 +469,46 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
         }
         launch_inner_product_shared_key(ctx, ip, kl.beta, lv, st);
         CMCHK(moddown_batch_into(ctx, bu, lv, m, adds, 2, 0, nullptr, outs, st));
+    }
+    if (kv->unrolled) {
+        // sum_g Rot(inner_g, g G) next to P inner_0, then the ladder over the residues, all in the extended basis;
+        // one ModDown, then the rescale
+        const size_t rw = 2 * (size_t)kl.ext * n;
+        u64 *cur = bdigits + B * dblk, *nxt = cur + rw;
+        launch_raise_by_P(ctx, cur, inner, lv, st);
+        for (int g0 = 1; g0 < kv->r_o; g0 += CM_KS_BATCH) {
+            const int m = kv->r_o - g0 < CM_KS_BATCH ? kv->r_o - g0 : CM_KS_BATCH;
+            CMCHK(ks_raise_many(ctx, kv->giant_tabs, inner + (size_t)g0 * ctw, ksin, bdigits, st, m, 0));
+            IpBatch b;
+            b.nz = 1, b.nsum = m;
+            for (int r = 0; r < m; r++) {
+                const u64 gal = rot_g(kv, (long long)(g0 + r) * kv->r_i * Ht);
+                b.it[r].dig = bdigits + r * dblk, b.it[r].key = find_key(evk, gal), b.it[r].g = (unsigned)gal;
+                b.it[r].c0 = inner + (size_t)(g0 + r) * ctw, b.it[r].c0_ext = 0;
+            }
+            b.out[0] = nxt, b.extra[0] = cur;
+            launch_inner_product_batch(ctx, b, kl.beta, lv, st);
+            std::swap(cur, nxt);
+        }
+        for (const auto &grp : kv->res_groups) {
+            CMCHK(moddown_second_keep(ctx, cur, lv, tmp, st));
+            CMCHK(ks_raise(ctx, tmp + ln, lv, digits, st));
+            IpBatch b;
+            b.nz = 1, b.nsum = (int)grp.size();
+            for (int r = 0; r < b.nsum; r++) {
+                const u64 gal = rot_g(kv, grp[r]);
+                b.it[r].dig = digits, b.it[r].key = find_key(evk, gal), b.it[r].g = (unsigned)gal;
+                b.it[r].c0 = cur, b.it[r].c0_ext = 1;
+            }
+            b.out[0] = nxt, b.extra[0] = cur;
+            launch_inner_product_batch(ctx, b, kl.beta, lv, st);
+            std::swap(cur, nxt);
+        }
+        CMCHK(moddown_into(ctx, cur, lv, nullptr, 0, 0, tmp, nullptr, st));
+        CMCHK(rescale_into(ctx, tmp, 2, lv, out->dev, st));
+        out->level = lv - 1, out->ncomp = 2;
+        out->scale = in->scale * kv->scale / (double)ctx->mod[lv];
+        RETURN_LAUNCH_STATUS();
     }
     u64 *acc = inner + (size_t)(kv->r_o - 1) * ctw;
     for (int g = kv->r_o - 2; g >= 0; g--) {

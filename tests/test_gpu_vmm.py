@@ -575,3 +575,35 @@ def test_kv_qk_with_unrolled_ladders_matches_oracle_and_float64(env, H, E, nk):
     assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
     # twice in a row on the same buffers
     assert np.array_equal(gctx.ct_export(gctx.vmm_kv(gkeys, kv, B.CM_QK, gq)), gctx.ct_export(gm))
+
+
+@pytest.mark.parametrize("H,E,r_i", [(16, 16, 4), (16, 16, 0), (2, 128, 8)])
+def test_kv_sv_with_unrolled_giant_steps_and_ladder_matches_oracle_and_float64(env, H, E, r_i):
+    """scores V with CM_KV_UNROLLED_LADDERS: giant steps unrolled and the residue ladder in the extended
+    basis; (2, 128, 8) has 16 giant-step groups, i.e. 15 rotations raised in two batches."""
+    from oracle import packing, vmm
+    from paper_2602_11470_amd import inputs
+    e = env
+    B, octx, gctx = e["B"], e["octx"], e["gctx"]
+    L = octx.prm.L
+    lay = packing.KvLayout(octx.S, H, E, r_i)
+    ntok = 3 * lay.t - 2
+    q, K, V, s = inputs.attention_inputs(23, H, max(1, H // 4), E, ntok)
+    lv = L - 1
+    kv = gctx.kv_create(H, E, lv, r_i=r_i, unrolled_ladders=True)
+    steps = vmm.sv_unrolled_steps(lay)
+    assert set(steps) <= set(kv.steps())
+    okeys = octx.keygen_rotations(e["osk"], steps, 2, with_relin=True)
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2, with_relin=True)
+    ovc = []
+    for k in range(E):
+        ov, gv = _enc_both(e, lay.pack_v(V, k), lv, 300 + k)
+        ovc.append(ov)
+        kv.load(B.CM_SV, k, gv)
+    kv.set_tokens(ntok)
+    os_, gs = _enc_both(e, lay.pack_scores(s), lv, 50)
+    oa = vmm.score_times_v_unrolled(octx, okeys, lay, os_, ovc)
+    ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)
+    _same(e, oa, ga)
+    assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
+    assert np.array_equal(gctx.ct_export(gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)), gctx.ct_export(ga))
