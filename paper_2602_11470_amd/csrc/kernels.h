@@ -55,7 +55,8 @@ void launch_raise_by_P(cm_ctx *ctx, u64 *out, const u64 *in, int level, hipStrea
 void launch_moddown_finish(cm_ctx *ctx, u64 *out, const u64 *u, const u64 *conv, const u64 *d_pinv, const u64 *addend,
                            int addend_comps, int level, u64 g, const u64 *accum, hipStream_t st, int ncomp = 2);
 void launch_rescale_reduce(cm_ctx *ctx, u64 *red, const u64 *last, int ncomp, int level, hipStream_t st);
-void launch_rescale_finish(cm_ctx *ctx, u64 *out, const u64 *in, const u64 *red, const u64 *d_qlinv, int ncomp, int level, hipStream_t st);
+void launch_rescale_finish(cm_ctx *ctx, u64 *out, const u64 *in, const u64 *red, const u64 *d_qlinv, int ncomp, int level, hipStream_t st,
+                           bool accumulate = false);
 u64 rng_key(u64 seed, u64 stream);
 u64 rng_draw(u64 key, u64 ctr);
 void launch_sample_uniform(cm_ctx *ctx, u64 *out, const int *d_mod_idx, int limbs, u64 seed, u64 stream_base, hipStream_t st);
@@ -147,7 +148,7 @@ cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cn
 // out[comp][level][n] = in[comp][level+1][n] divided by q_level; up to 2*CM_KS_BATCH stacked components when the
 // caller gives scratch last[ncomp][n] and red[ncomp][level][n] (up to three without)
 cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st, u64 *last = nullptr,
-                       u64 *red = nullptr);
+                       u64 *red = nullptr, bool accumulate = false);
 u64 *arena_digits(const cm_ctx *ctx);
 // room for CM_KS_BATCH key-switch sums [2][L+1+K][n] (what moddown_batch_into consumes)
 u64 *arena_batch_sums(const cm_ctx *ctx);

@@ -524,19 +524,25 @@ __global__ void k_rescale_reduce(u64 *red, const u64 *last, const ModC *modc, in
     red[((size_t)c * level + l) * n + i] = redc((u128)to_mont(v, m), m.q, m.qinv);
 }
 // out[comp][l][n] = (in[comp][l] - red[comp][l]) * q_level^{-1}; in has level+1 rows per component
-__global__ void k_rescale_finish(u64 *out, const u64 *in, const u64 *red, const u64 *qlinv, const ModC *modc, int level, int n) {
+// accumulate: out += the result (out holds a running sum of the same shape)
+__global__ void k_rescale_finish(u64 *out, const u64 *in, const u64 *red, const u64 *qlinv, const ModC *modc, int level, int n,
+                                 int accumulate) {
     int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y, c = blockIdx.z;
     u64 q = modc[l].q;
     u64 d = submod(in[((size_t)c * (level + 1) + l) * n + i], red[((size_t)c * level + l) * n + i], q);
-    out[((size_t)c * level + l) * n + i] = mul_shoup(d, qlinv[2 * l], qlinv[2 * l + 1], q);
+    u64 v = mul_shoup(d, qlinv[2 * l], qlinv[2 * l + 1], q);
+    const size_t o = ((size_t)c * level + l) * n + i;
+    out[o] = accumulate ? addmod(out[o], v, q) : v;
 }
 void launch_rescale_reduce(cm_ctx *ctx, u64 *red, const u64 *last, int ncomp, int level, hipStream_t st) {
     Prof prof_(ctx, CM_K_RESCALE, ncomp * level, st);
     hipLaunchKernelGGL(k_rescale_reduce, dim3(ctx->n / TPB, level, ncomp), dim3(TPB), 0, st, red, last, ctx->d_modc, level, ctx->n);
 }
-void launch_rescale_finish(cm_ctx *ctx, u64 *out, const u64 *in, const u64 *red, const u64 *d_qlinv, int ncomp, int level, hipStream_t st) {
+void launch_rescale_finish(cm_ctx *ctx, u64 *out, const u64 *in, const u64 *red, const u64 *d_qlinv, int ncomp, int level, hipStream_t st,
+                           bool accumulate) {
     Prof prof_(ctx, CM_K_RESCALE, ncomp * level, st);
-    hipLaunchKernelGGL(k_rescale_finish, dim3(ctx->n / TPB, level, ncomp), dim3(TPB), 0, st, out, in, red, d_qlinv, ctx->d_modc, level, ctx->n);
+    hipLaunchKernelGGL(k_rescale_finish, dim3(ctx->n / TPB, level, ncomp), dim3(TPB), 0, st, out, in, red, d_qlinv, ctx->d_modc, level, ctx->n,
+                       accumulate ? 1 : 0);
 }
 
 // ---- counter-based sampling (must reproduce the generator's published definition bit for bit) --------

@@ -264,9 +264,7 @@ static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_c
     // K: K_c += rescale(k_new * mask_tau), mask_tau = residue-0 mask rotated right by tau (a group: all ones)
     if (!group) launch_automorphism(ctx, mask, kv->d_mask_k, lv + 1, rot_g(kv, -tau), st);
     launch_mul_pt(ctx, prod, k_new->dev, group ? kv->d_mask_kg : mask, 2, lv + 1, st);
-    CMCHK(rescale_into(ctx, prod, 2, lv, res, st));
-    u64 *kc = kv->d_k + (size_t)c * ctw;
-    launch_add(ctx, kc, kc, res, 2, kv->level + 1, st);
+    CMCHK(rescale_into(ctx, prod, 2, lv, kv->d_k + (size_t)c * ctw, st, nullptr, nullptr, true));
     // V: the new vector shifted right by each giant step, then one masked product per V ciphertext
     if (kv->r_o > 1) {                                       // rotations of one ciphertext: one raise for all of them
         u64 *digits = arena_digits(ctx);
@@ -295,9 +293,8 @@ static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_c
             mb.g[r] = (unsigned)rot_g(kv, -a);
         }
         launch_mul_pt_rot_batch(ctx, prods, mb, m, group ? kv->d_mask_vg : kv->d_mask_v, lv + 1, st);
-        CMCHK(rescale_into(ctx, prods, 2 * m, lv, ress, st, last, red));
-        u64 *vk = kv->d_v + (size_t)kb * ctw;
-        launch_add(ctx, vk, vk, ress, 2 * m, kv->level + 1, st);
+        // consecutive value ciphertexts are contiguous: the rescale adds its result onto them
+        CMCHK(rescale_into(ctx, prods, 2 * m, lv, kv->d_v + (size_t)kb * ctw, st, last, red, true));
     }
     kv->ntok += group ? kv->t : 1;
     kv->scale = k_new->scale * (double)ctx->mod[lv] / (double)ctx->mod[lv];

@@ -770,9 +770,10 @@ extern "C" cm_status cm_relinearize(cm_ctx *ctx, const cm_evk *evk, const cm_ct 
     return CM_OK;
 }
 
-cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st, u64 *last, u64 *red) {
+cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st, u64 *last, u64 *red,
+                       bool accumulate) {
     // out[comp][level][n]; must not alias in.  More than three components (several stacked
-    // ciphertexts) need caller scratch: last[ncomp][n], red[ncomp][level][n].
+    // ciphertexts) need caller scratch: last[ncomp][n], red[ncomp][level][n].  accumulate: out += the result.
     const KsLevelFull &k = ks_level_full(ctx, level);
     Arena A = arena_of(ctx);
     if (ncomp < 1 || ncomp > RESCALE_MAX_COMPS || (ncomp > 3 && (!last || !red))) return CM_E_INVAL;
@@ -781,7 +782,7 @@ cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *ou
     launch_ntt_src(ctx, last, nullptr, in, k.d_last_rows, k.d_last_mods, ncomp, true, st);
     launch_rescale_reduce(ctx, red, last, ncomp, level, st);
     launch_ntt(ctx, red, k.d_red_mods, ncomp * level, false, st);
-    launch_rescale_finish(ctx, out, in, red, get_qlinv(ctx, level), ncomp, level, st);
+    launch_rescale_finish(ctx, out, in, red, get_qlinv(ctx, level), ncomp, level, st, accumulate);
     return CM_OK;
 }
 extern "C" cm_status cm_rescale(cm_ctx *ctx, const cm_ct *a, cm_ct *out, void *stream) {
