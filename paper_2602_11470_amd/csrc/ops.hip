@@ -781,6 +781,20 @@ cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *ou
     if (!red) red = A.tmp[2];
     launch_ntt_src(ctx, last, nullptr, in, k.d_last_rows, k.d_last_mods, ncomp, true, st);
     launch_rescale_reduce(ctx, red, last, ncomp, level, st);
+    if (ctx->n == 65536 && ncomp % 2 == 0) {
+        // the tail (in - NTT(red)) q_level^{-1} (+ out) rides on the last pass of the transform of red: the same tail as a
+        // ModDown's, with `level` output rows and level+1 input rows per component and q_level^{-1} for P^{-1}
+        FinishBatch fb;
+        fb.items = ncomp / 2, fb.level = level - 1, fb.ext = level + 1, fb.addend_comps = 0, fb.ncomp = 2, fb.comp0 = 0;
+        for (int r = 0; r < CM_KS_BATCH; r++) fb.addend[r] = nullptr, fb.accum[r] = nullptr, fb.u[r] = nullptr, fb.out[r] = nullptr, fb.g[r] = 0;
+        for (int r = 0; r < fb.items; r++) {
+            fb.u[r] = in + (size_t)r * 2 * (level + 1) * ctx->n, fb.out[r] = out + (size_t)r * 2 * level * ctx->n;
+            fb.accum[r] = accumulate ? fb.out[r] : nullptr;
+        }
+        fb.pinv = get_qlinv(ctx, level);
+        launch_ntt_fwd_finish(ctx, red, k.d_red_mods, fb, st);
+        return CM_OK;
+    }
     launch_ntt(ctx, red, k.d_red_mods, ncomp * level, false, st);
     launch_rescale_finish(ctx, out, in, red, get_qlinv(ctx, level), ncomp, level, st, accumulate);
     return CM_OK;
