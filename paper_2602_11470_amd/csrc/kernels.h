@@ -46,6 +46,15 @@ struct IpBatch {
     const u64 *extra[IP_MAX_ITEMS] = {};      // nullable; the kernels test it, so it must never be left unset
 };
 void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st);
+// na = 2 or 3 keys (Galois elements g[a] != 0) applied to the nz digit arrays b.it[z].dig and summed into out[z] together with
+// extra[z] and, per key, the first component b.it[z].c0 (extended basis) through that key's Galois map.  Returns false
+// (nothing launched) if the lane cannot hold the keys: more than 6 digits.
+#define IP_MULTI_KEYS 3
+struct IpKeys {
+    const u64 *key[IP_MULTI_KEYS] = {};
+    unsigned g[IP_MULTI_KEYS] = {};
+};
+bool launch_inner_product_multi_key(cm_ctx *ctx, const IpBatch &b, const IpKeys &ks, int na, int beta, int level, hipStream_t st);
 // out[z] = sum_j it[z].dig_j * it[0].key_j for z < nz: one key for all arrays (read once), no Galois map, no c0, no extra
 // g != 0: digits and it[z].c0 (a first component in the extended basis, added as it is) through the Galois map; extra[z]
 // ([2][ext][n], may be out[z]) is added

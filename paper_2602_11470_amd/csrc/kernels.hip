@@ -454,6 +454,83 @@ void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, in
     hipLaunchKernelGGL(k_inner_product_shared_key, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, b, ctx->d_modc, beta, ext,
                        level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, (ctx->L + ctx->alpha) / ctx->alpha, ctx->d_ubound);
 }
+// NA keys (rotation amounts) applied to the same nz digit arrays, summed: out[z] = extra[z] + sum_a [ sum_j
+// sigma_a(dig_z,j) key_a,j + (sigma_a(c0_z), 0) ].  A lane keeps the words of all NA keys in registers (at most
+// IP_MULTI_BETA digits) and writes every output once: against one launch per amount this saves the read-modify-write
+// of the running sum, a third of the traffic of the rotation step of an unrolled ladder.
+#define IP_MULTI_BETA 6
+template <int NA>
+__global__ __launch_bounds__(TPB) void k_inner_product_multi_key(IpBatch b, IpKeys ks, const ModC *__restrict__ modc, int beta,
+                                                                 int ext, int level, int L, int nmod, int n, int logn, int kdig,
+                                                                 const u64 *__restrict__ ubound) {
+    const unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
+    const int r = blockIdx.y;
+    const int mi = r <= level ? r : L + 1 + (r - level - 1);
+    const ModC m = modc[mi];
+    const size_t o = (size_t)r * n + i2;
+    const u64 bound = ubound[mi], cg0 = ((u64)i2 + 1) * GOLD, cg1 = cg0 + GOLD;
+    ulonglong2 eb[NA][IP_MULTI_BETA], ea[NA][IP_MULTI_BETA];
+    unsigned base[NA];
+    bool swap[NA];
+#pragma unroll
+    for (int a = 0; a < NA; a++) {
+        const unsigned src = perm_src(i2, ks.g[a], logn);
+        base[a] = src & ~1u, swap[a] = src & 1u;
+#pragma unroll
+        for (int j = 0; j < IP_MULTI_BETA; j++) {
+            if (j < beta) {
+                const u64 *kb = ks.key[a] + ((size_t)j * nmod + mi) * n + i2;
+                eb[a][j].x = __builtin_nontemporal_load(kb), eb[a][j].y = __builtin_nontemporal_load(kb + 1);
+                const u64 sk_ = ks.key[a][(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
+                ea[a][j].x = evk_a_draw(sk_, cg0, i2, bound), ea[a][j].y = evk_a_draw(sk_, cg1, i2 + 1, bound);
+            }
+        }
+    }
+    for (int z = 0; z < b.nz; z++) {
+        const u64 *dig = b.it[z].dig;
+        ulonglong2 r0 = make_ulonglong2(0, 0), r1 = make_ulonglong2(0, 0);
+        if (b.extra[z]) {
+            r0 = *reinterpret_cast<const ulonglong2 *>(b.extra[z] + o);
+            r1 = *reinterpret_cast<const ulonglong2 *>(b.extra[z] + (size_t)ext * n + o);
+        }
+#pragma unroll
+        for (int a = 0; a < NA; a++) {
+            u128 a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+#pragma unroll
+            for (int j = 0; j < IP_MULTI_BETA; j++) {
+                if (j < beta) {
+                    ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(dig + ((size_t)j * ext + r) * n + base[a]);
+                    const u64 dx = swap[a] ? d.y : d.x, dy = swap[a] ? d.x : d.y;
+                    b0 += (u128)dx * eb[a][j].x;
+                    b1 += (u128)dy * eb[a][j].y;
+                    a0 += (u128)dx * ea[a][j].x;
+                    a1 += (u128)dy * ea[a][j].y;
+                }
+            }
+            r0.x = addmod(r0.x, redc(b0, m.q, m.qinv), m.q), r0.y = addmod(r0.y, redc(b1, m.q, m.qinv), m.q);
+            r1.x = addmod(r1.x, redc_raw(a0, m), m.q), r1.y = addmod(r1.y, redc_raw(a1, m), m.q);
+            if (b.it[z].c0) {
+                ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(b.it[z].c0 + (size_t)r * n + base[a]);
+                r0.x = addmod(r0.x, swap[a] ? d.y : d.x, m.q), r0.y = addmod(r0.y, swap[a] ? d.x : d.y, m.q);
+            }
+        }
+        *reinterpret_cast<ulonglong2 *>(b.out[z] + o) = r0;
+        *reinterpret_cast<ulonglong2 *>(b.out[z] + (size_t)ext * n + o) = r1;
+    }
+}
+bool launch_inner_product_multi_key(cm_ctx *ctx, const IpBatch &b, const IpKeys &ks, int na, int beta, int level, hipStream_t st) {
+    if (beta > IP_MULTI_BETA || na < 2 || na > IP_MULTI_KEYS) return false;
+    const int ext = level + 1 + ctx->K, kdig = (ctx->L + ctx->alpha) / ctx->alpha;
+    const dim3 grid(ctx->n / (2 * TPB), ext), block(TPB);
+    Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz * na, st);
+    if (na == 2)
+        hipLaunchKernelGGL(k_inner_product_multi_key<2>, grid, block, 0, st, b, ks, ctx->d_modc, beta, ext, level, ctx->L, ctx->nmod,
+                           ctx->n, ctx->logn, kdig, ctx->d_ubound);
+    else
+        hipLaunchKernelGGL(k_inner_product_multi_key<3>, grid, block, 0, st, b, ks, ctx->d_modc, beta, ext, level, ctx->L, ctx->nmod,
+                           ctx->n, ctx->logn, kdig, ctx->d_ubound);
+    return true;
+}
 void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st) {
     Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz * b.nsum, st);
     int ext = level + 1 + ctx->K;

@@ -375,14 +375,25 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
                 }
                 CMCHK(ks_raise_many(ctx, kv->rot_tabs, r0, ksin, digits, st, m, 0));
                 bool first = true;
-                for (long long a : kv->dim_groups[gi]) {
-                    const u64 g = rot_g(kv, a);
+                const auto &grp = kv->dim_groups[gi];
+                for (size_t a0 = 0; a0 < grp.size();) {
+                    // up to IP_MULTI_KEYS rotation amounts per launch (their keys in registers, the running sum written
+                    // once); the remainder, or everything if there are too many digits for that, one amount per launch
+                    const int na = (int)(grp.size() - a0 < (size_t)IP_MULTI_KEYS ? grp.size() - a0 : IP_MULTI_KEYS);
                     for (int r = 0; r < m; r++) {
-                        ip.it[r].dig = digits + r * dblk1, ip.it[r].key = find_key(evk, g);
+                        ip.it[r].dig = digits + r * dblk1;
                         ip.it[r].c0 = cur + r * rw1, ip.it[r].c0_ext = 1;
                         ip.out[r] = nxt + r * rw1, ip.extra[r] = first ? cur + r * rw1 : nxt + r * rw1;
                     }
-                    launch_inner_product_shared_key(ctx, ip, kl1.beta, lv - 1, st, g);
+                    IpKeys ks;
+                    for (int a = 0; a < na; a++) ks.g[a] = (unsigned)rot_g(kv, grp[a0 + a]), ks.key[a] = find_key(evk, ks.g[a]);
+                    if (na >= 2 && launch_inner_product_multi_key(ctx, ip, ks, na, kl1.beta, lv - 1, st)) {
+                        a0 += na;
+                    } else {
+                        for (int r = 0; r < m; r++) ip.it[r].key = ks.key[0];
+                        launch_inner_product_shared_key(ctx, ip, kl1.beta, lv - 1, st, ks.g[0]);
+                        a0 += 1;
+                    }
                     first = false;
                 }
                 std::swap(cur, nxt);
