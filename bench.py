@@ -321,7 +321,7 @@ def sweep_workload(a):
 
 def prefill_workload(a):
     """The prompt phase (Sec. 5.4) on the config-2 ring: one 4096 x 4096 product over a ciphertext of
-    t = 8 tokens (4096 diagonals as 64 baby x 64 giant steps, 126 rotations), the rotary embedding of a
+    t = 8 tokens (4096 diagonals as 128 baby x 32 giant steps, 158 rotations), the rotary embedding of a
     token group and the append of a token group to the 32 x 128 cache.  A JSON line of its own."""
     import torch
     from paper_2602_11470_amd import binding as B

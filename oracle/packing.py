@@ -176,7 +176,9 @@ def default_r_i(M):
 def make_plan(S, d_in, d_out, r_i=None, tau=0, tokens=False):
     if tokens:
         assert d_in == d_out
-        return VmmPlan(S, d_in, 1, "square", default_r_i(d_in) if r_i is None else r_i, 0, True)
+        # twice the square-root rule: the baby steps are hoisted rotations of one ciphertext, several times cheaper
+        # than the giant steps, each of which raises a ciphertext of its own
+        return VmmPlan(S, d_in, 1, "square", min(d_in, 2 * default_r_i(d_in)) if r_i is None else r_i, 0, True)
     if d_in == d_out:
         d, alpha, mode = d_in, 1, "square"
     elif d_out > d_in:

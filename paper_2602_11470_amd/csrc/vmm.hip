@@ -65,7 +65,11 @@ static cm_status plan_shape(cm_ctx *ctx, int d_in, int d_out, int r_i, int tau, 
     }
     p->M = p->d / p->tp;
     if (p->M < 1) return CM_E_LAYOUT;
-    if (r_i == 0) r_i = 1 << ((ilog2(p->M) + 1) / 2);
+    if (r_i == 0) {
+        r_i = 1 << ((ilog2(p->M) + 1) / 2);
+        // token-batched plans: twice that; their hoisted baby steps are several times cheaper than the giant steps
+        if (tokens && 2 * r_i <= p->M) r_i *= 2;
+    }
     if (!pow2(r_i) || p->M % r_i) return CM_E_LAYOUT;
     p->r_i = r_i, p->r_o = p->M / r_i;
     if (tau < 0 || tau >= p->t2) return CM_E_LAYOUT;

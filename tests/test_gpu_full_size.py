@@ -234,7 +234,7 @@ def test_config3_attention_shapes_decrypt_to_float64_products(ring2, unrolled):
 
 def test_prompt_phase_on_the_full_ring_builds_a_cache_the_decode_products_can_use(ring2):
     """Sec. 5.4 at Llama-3-8B shapes: two ciphertexts of t = 8 tokens each go through the token-batched
-    4096 x 4096 k and v projections (4096 diagonals, 64 baby x 64 giant steps, columns ordered (e, h)),
+    4096 x 4096 k and v projections (4096 diagonals, 128 baby x 32 giant steps, columns ordered (e, h)),
     the rotary embedding of a token group and the group append; then the decode-phase q K^T and
     scores V run against that cache.  Everything is compared with the float64 computation."""
     from oracle import packing
@@ -251,7 +251,7 @@ def test_prompt_phase_on_the_full_ring_builds_a_cache_the_decode_products_can_us
     gsk = gctx.keygen_secret(1)
     pk = gctx.vmm_plan(d, d, W=Wk, level=lvx, direct_giants=True, token_batch=True)
     pv = gctx.vmm_plan(d, d, W=Wv, level=lvx, direct_giants=True, token_batch=True)
-    assert (pk.r_i, pk.r_o, pk.n_rotations) == (64, 64, 126)
+    assert (pk.r_i, pk.r_o, pk.n_rotations) == (128, 32, 158)
     kv = gctx.kv_create(H, E, lv, r_i=16)
     ropes = [gctx.rope(H, E, lvx - 1, c * t, tau=-1) for c in range(groups)]
     steps = sorted(set(pk.steps()) | set(kv.steps()) | set(ropes[0].steps()))

@@ -299,7 +299,7 @@ def test_token_batched_product_on_slots_is_X_times_W(d, r_i):
 def test_token_batched_product_on_ciphertexts_decrypts_to_X_times_W(form):
     prm, ctx, sk = _toy_ctx()
     level = 3
-    plan = packing.make_plan(ctx.S, 64, 64, tokens=True)           # t = 4 tokens, r_i = r_o = 8
+    plan = packing.make_plan(ctx.S, 64, 64, tokens=True)           # t = 4 tokens, r_i = 16, r_o = 4
     rng = np.random.default_rng(8)
     X, W = rng.normal(size=(plan.t, 64)) * 0.5, rng.normal(size=(64, 64)) * 0.1
     steps = sorted(set(vmm.direct_giant_steps(plan)) | set(plan.all_steps()))
@@ -313,7 +313,8 @@ def test_token_batched_product_on_ciphertexts_decrypts_to_X_times_W(form):
         ext = [[ctx.encode_ext(v, level) for v in row] for row in diags]
         fn = vmm.vmm_pt_double_hoisted if form == "raised" else vmm.vmm_pt_direct_giants
         y = fn(ctx, keys, plan, ct, ext)
-    assert ctx.rot_count - r0 == 14 and ctx.ptmul_count - p0 == 64
+    assert (plan.r_i, plan.r_o) == (16, 4)
+    assert ctx.rot_count - r0 == 18 and ctx.ptmul_count - p0 == 64
     assert y.level == level - 1
     out = ctx.decrypt(sk, y)
     assert np.abs(plan.unpack_tokens(out.real) - X @ W).max() < TOL
