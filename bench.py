@@ -5,12 +5,13 @@ A step = one pass of the whole hot path over one synthetic input: cm_vmm_pt of a
 4096-vector (interleaved replicated packing) against a plaintext 4096x4096 matrix on the ring
 n = 2^16 with 24 ciphertext primes of 50 bits + 4 special primes of 60 bits (6 key-switch
 digits), at the top level: 512 plaintext multiply-accumulates, one rescale, and the rotations of
-Algorithm 1 — 52 as printed (21 full key switches + 31 hoisted); 60 in the default form, which
-unrolls the giant steps and the two rotate-and-add ladders into hoisted rotations and keeps the
-whole product in the extended basis (one ModDown of both components at the end).  Keys, weight
+Algorithm 1 — 52 as printed with 32 baby x 16 giant steps (21 full key switches + 31 hoisted); 84 in
+the default form, which unrolls the giant steps and the two rotate-and-add ladders into hoisted
+rotations, keeps the whole product in the extended basis (one ModDown of both components at the
+end) and, its baby steps being cheap, splits 64 x 8.  Keys, weight
 plaintexts and the input ciphertext are resident in HBM before the timed region.  --ladders keeps
-the ladders (52 rotations), --nested-giants also the nested giant steps, --plain-sums divides
-every hoisted rotation by P on its own (Algorithm 1 as printed).
+the ladders, --nested-giants also the nested giant steps, --plain-sums divides every hoisted
+rotation by P on its own (Algorithm 1 as printed, 32 x 16, 52 rotations).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--ladders | --nested-giants | --plain-sums]
 
@@ -424,7 +425,7 @@ def main():
     ntt_launch_s = ntt["ms"] / ntt["launches"] * 1e-3
     # forward NTT: algorithmic bytes = read + write each limb once (1 MiB per 2^16-point limb)
     ntt_gbs = ntt_per_launch_limbs * 2 * limb_bytes / ntt_launch_s / 1e9
-    # inner products: a launch of the batched kernel carries several (31 hoisted rotations, 15 giant
+    # inner products: a launch of the batched kernel carries several (63 hoisted rotations, 7 giant
     # steps), so the figure is per inner product: family time / inner products
     ip = fam["inner_product"]
     ip_launch_s = ip["ms"] / ip["units"] * 1e-3
@@ -442,7 +443,7 @@ def main():
         "inner_product": {"bound": "hbm", "achieved": ip_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": ip_gbs / HBM_PEAK_GBS, "traffic": tr.get("k_inner_product"),
                           "kernel": "k_inner_product_batch / k_inner_product (per inner product; one launch of the "
-                                    "batched kernel = 31, 15 or 7 of them)",
+                                    "batched kernel = 32, 31 or 7 of them)",
                           "inner_products_per_step": ip["units"], "launches_per_step": ip["launches"],
                           "us_per_launch": ip_launch_s * 1e6},
     }
@@ -454,7 +455,8 @@ def main():
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64", "data": "synthetic",
         "config": {"workload": "config2: encrypted 4096-vector x plaintext 4096x4096, interleaved replicated "
-                               f"packing, BSGS 32x16, {g['plan'].n_rotations} rotations, 512 pt-ct MACs", "ring_degree": n,
+                               f"packing, BSGS {g['plan'].r_i}x{g['plan'].r_o}, {g['plan'].n_rotations} rotations, 512 pt-ct MACs",
+                   "ring_degree": n,
                    "baby_step_sums": "plain" if a.plain_sums else "extended basis",
                    "giant_steps": "nested (one key)" if nested else "unrolled (one key per step)",
                    "ladders": "rotate-and-add, 3 + 3 dependent rotations" if (nested or a.ladders) else

@@ -163,7 +163,9 @@ cm_status cm_rotate_hoisted(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, con
 /* ---- packed plaintext product (Sec. 4.1, Algorithm 1) ---------------------------------- */
 /* W: host, row-major d_in x d_out.  One of d_in == d_out, d_out = alpha*d_in, d_in =
  * alpha*d_out (alpha a power of two); S/min(d) and S/max(d) must be integers.  r_i = baby
- * steps (0 = default near sqrt of the diagonal count); tau = residue the outputs land on
+ * steps (0 = default: the power of two at or just above sqrt of the diagonal count, twice that
+ * for the forms that keep the baby steps in the extended basis and for token-batched plans, whose
+ * baby steps are several times cheaper than their giant steps); tau = residue the outputs land on
  * (0, or the slot residue of a token about to be appended to the cache).  The weight diagonals
  * are encoded at `pt_scale` (0 = the context scale) for input level `level` and stay on the
  * device.  Layouts: input element a at slot a*t (d_in <= d_out) or (a%d)*t + (a/d)*t'

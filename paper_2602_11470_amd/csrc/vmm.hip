@@ -45,7 +45,7 @@ static int ilog2(int x) {
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 static cm_status plan_shape(cm_ctx *ctx, int d_in, int d_out, int r_i, int tau, int level, double pt_scale,
-                            bool tokens, cm_vmm_plan *p) {
+                            bool tokens, bool cheap_babies, cm_vmm_plan *p) {
     if (d_in < 1 || d_out < 1 || level < 1 || level > ctx->L) return level < 1 ? CM_E_LEVEL : CM_E_INVAL;
     p->ctx = ctx;
     p->S = ctx->n / 2;
@@ -67,8 +67,9 @@ static cm_status plan_shape(cm_ctx *ctx, int d_in, int d_out, int r_i, int tau, 
     if (p->M < 1) return CM_E_LAYOUT;
     if (r_i == 0) {
         r_i = 1 << ((ilog2(p->M) + 1) / 2);
-        // token-batched plans: twice that; their hoisted baby steps are several times cheaper than the giant steps
-        if (tokens && 2 * r_i <= p->M) r_i *= 2;
+        // twice that where the baby steps stay in the extended basis (one inner product each, no ModUp or ModDown of
+        // their own): they are then several times cheaper than the giant steps, each of which raises a ciphertext
+        if (cheap_babies && 2 * r_i <= p->M) r_i *= 2;
     }
     if (!pow2(r_i) || p->M % r_i) return CM_E_LAYOUT;
     p->r_i = r_i, p->r_o = p->M / r_i;
@@ -190,7 +191,8 @@ extern "C" cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_
     const bool direct = unrolled || (flags & CM_VMM_DIRECT_GIANTS) != 0, raised = direct || (flags & CM_VMM_RAISED_SUMS) != 0;
     cm_vmm_plan *p = new (std::nothrow) cm_vmm_plan();
     if (!p) return CM_E_NOMEM;
-    cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, (flags & CM_VMM_TOKEN_BATCH) != 0, p);
+    cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, (flags & CM_VMM_TOKEN_BATCH) != 0,
+                             raised || (flags & CM_VMM_TOKEN_BATCH) != 0, p);
     if (s == CM_OK) s = plan_alloc(p, raised, direct, unrolled);
     if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
     if (coeffs) {

@@ -71,7 +71,7 @@ def test_config2_chain_keys_and_single_operations(ring2):
 
 @pytest.mark.parametrize("form", ["plain", "raised", "direct", "unrolled"])
 def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden, form):
-    """52 rotations (60 with the ladders unrolled), 512 plaintext multiply-accumulates at (S, d) =
+    """52 rotations (84 in the unrolled form with its 64 x 8 split), 512 plaintext multiply-accumulates at (S, d) =
     (32768, 4096); the expected ciphertext was written by tests/golden/make_vmm_full_size_golden.py
     from the oracle, for the algorithm as printed, for the form that keeps the baby-step sums in the
     extended basis, for that with the giant steps unrolled, and for that with the two ladders
@@ -86,12 +86,12 @@ def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden,
         "mk", os.path.join(os.path.dirname(__file__), "golden", "make_vmm_full_size_golden.py"))
     mk = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mk)
-    from oracle import packing
-    plan = packing.make_plan(octx.S, mk.D, mk.D)
+    plan = mk.plan_for(octx.S, form)
     xc, diag = mk.integer_inputs(octx.n, plan)
     gplan = gctx.vmm_plan(mk.D, mk.D, level=prm.L, r_i=plan.r_i, coeffs=np.stack(diag), pt_scale=prm.scale,
                           raised_sums=raised, direct_giants=direct, unrolled_ladders=unrolled)
-    assert gplan.n_rotations == int(g["rotations"]) == (60 if unrolled else 52)
+    assert gplan.n_rotations == int(g["rotations"]) == (84 if unrolled else 52)
+    assert (gplan.r_i, gplan.r_o) == ((64, 8) if unrolled else (32, 16))
     assert gplan.r_i * gplan.r_o == int(g["pt_mults"]) == 512
     gsk = gctx.keygen_secret(mk.SEED_SK)
     gkeys = gctx.keygen_rotations(gsk, gplan.steps(), mk.SEED_EVK)
@@ -121,9 +121,10 @@ def test_config2_packed_product_decrypts_to_float64_product(ring2):
     out = gctx.decrypt(gsk, gy)
     assert np.abs(out.real[::t] - x @ W).max() < TOL
     assert gy.level == gctx.L - 1
+    r_i = gplan.r_i
     del gplan
-    # baby-step sums kept in the extended basis: the same message up to rounding noise
-    gplan_r = gctx.vmm_plan(d, d, W=W, raised_sums=True)
+    # baby-step sums kept in the extended basis (same split, same keys): the same message up to rounding noise
+    gplan_r = gctx.vmm_plan(d, d, W=W, raised_sums=True, r_i=r_i)
     gyr = gctx.vmm_pt(gkeys, gplan_r, gx)
     assert gyr.level == gy.level and abs(gyr.scale / gy.scale - 1) < 1e-12
     outr = gctx.decrypt(gsk, gyr)
@@ -152,8 +153,11 @@ def test_other_widths_and_levels_decrypt_to_float64_product(ring2, d, level, rot
         x[768:] = 0.0
         W[768:, :] = 0.0
         W[:, 768:] = 0.0
+    from oracle import packing
+    plan = packing.make_plan(octx.S, d, d)
+    assert plan.n_rotations == rotations                       # as Algorithm 1 counts them with the square-root split
     gplan = gctx.vmm_plan(d, d, W=W, level=level, unrolled_ladders=True)
-    assert gplan.r_i - 1 + gplan.r_o - 1 + 2 * int(np.log2(gctx.S // d)) == rotations     # as Algorithm 1 counts them
+    assert (gplan.r_i, gplan.r_o) == (2 * plan.r_i, plan.r_o // 2)     # the library doubles the cheap baby steps
     gsk = gctx.keygen_secret(1)
     gkeys = gctx.keygen_rotations(gsk, gplan.steps(), 2)
     t = gctx.S // d
@@ -183,8 +187,9 @@ def test_config4_mlp_projection_shapes_decrypt_to_float64_product(ring2, d_in, d
         W[:, real:] = 0.0
     plan = packing.make_plan(octx.S, d_in, d_out)
     gplan = gctx.vmm_plan(d_in, d_out, W=W, level=level, unrolled_ladders=True)
-    assert (gplan.r_i, gplan.r_o, plan.n_rotations) == (plan.r_i, plan.r_o, 98)
-    assert gplan.n_rotations == 98 - (3 + 1) + (7 + 1)            # the three-step ladder becomes seven hoisted rotations
+    assert (plan.r_i, plan.r_o, plan.n_rotations) == (64, 32, 98)
+    assert (gplan.r_i, gplan.r_o) == (128, 16)                    # the library doubles the cheap baby steps
+    assert gplan.n_rotations == 127 + 15 + (7 + 1)                # and the three-step ladder becomes seven hoisted rotations
     gsk = gctx.keygen_secret(1)
     gkeys = gctx.keygen_rotations(gsk, gplan.steps(), 2)
     gx = gctx.level_drop(gctx.encrypt(gsk, gctx.encode(plan.pack_input(x), gctx.L), 3), level)
