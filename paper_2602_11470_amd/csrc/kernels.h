@@ -49,6 +49,18 @@ void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int lev
 // na = 2 or 3 keys (Galois elements g[a] != 0) applied to the nz digit arrays b.it[z].dig and summed into out[z] together with
 // extra[z] and, per key, the first component b.it[z].c0 (extended basis) through that key's Galois map.  Returns false
 // (nothing launched) if the lane cannot hold the keys: more than 6 digits.
+// Up to IP_FAN_MAX keys applied to ONE digit array dig[beta][ext][n], one output per key: out[a] = sum_j sigma_a(dig_j)
+// key_a,j + (sigma_a(c0) or P sigma_a(c0), 0); ginv[a] = the inverse of key a's Galois element modulo 2n.  The digits
+// are read once per 8 keys.  Returns false (nothing launched) for more than 8 digits.
+#define IP_FAN_MAX 64
+struct IpFan {
+    int n = 0;
+    const u64 *key[IP_FAN_MAX] = {};
+    u64 *out[IP_FAN_MAX] = {};
+    unsigned ginv[IP_FAN_MAX] = {};
+};
+bool launch_inner_product_fanout(cm_ctx *ctx, const IpFan &f, const u64 *dig, const u64 *c0, bool c0_ext, int beta, int level,
+                                 hipStream_t st);
 #define IP_MULTI_KEYS 3
 struct IpKeys {
     const u64 *key[IP_MULTI_KEYS] = {};

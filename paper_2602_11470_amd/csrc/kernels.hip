@@ -454,6 +454,77 @@ void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, in
     hipLaunchKernelGGL(k_inner_product_shared_key, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, b, ctx->d_modc, beta, ext,
                        level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, (ctx->L + ctx->alpha) / ctx->alpha, ctx->d_ubound);
 }
+// One digit array, many keys, one output per key (the hoisted rotations of ONE ciphertext, each kept on its own): a lane
+// keeps the digit words of two SOURCE positions (and the first component's) in registers and walks over the keys; for
+// key a it writes its result at the position the Galois map sends its source to (the inverse map; pairs go to pairs,
+// aligned runs of 64 to aligned runs of 64, so key reads and result writes stay coalesced).  Same sums as
+// k_inner_product_batch, but the digits are read once per IP_FAN_CHUNK keys instead of once per key.
+#define IP_FAN_CHUNK 8
+__global__ __launch_bounds__(TPB) void k_inner_product_fanout(IpFan f, const u64 *__restrict__ dig, const u64 *__restrict__ c0,
+                                                              int c0_ext, const ModC *__restrict__ modc, int beta, int ext,
+                                                              int level, int L, int nmod, int n, int logn,
+                                                              const u64 *__restrict__ pmont, int kdig,
+                                                              const u64 *__restrict__ ubound) {
+    const unsigned s2 = (blockIdx.x * TPB + threadIdx.x) * 2;
+    const int r = blockIdx.y;
+    const int mi = r <= level ? r : L + 1 + (r - level - 1);
+    const ModC m = modc[mi];
+    const u64 bound = ubound[mi];
+    ulonglong2 d[IP_SHARED_MAX_BETA];
+#pragma unroll
+    for (int j = 0; j < IP_SHARED_MAX_BETA; j++)
+        if (j < beta) d[j] = *reinterpret_cast<const ulonglong2 *>(dig + ((size_t)j * ext + r) * n + s2);
+    // the first component's contribution to the first output component: sigma(c0) as it is (extended basis) or
+    // P sigma(c0) on the ciphertext limbs
+    ulonglong2 cv = make_ulonglong2(0, 0);
+    const bool have_c0 = c0 && (c0_ext || r <= level);
+    if (have_c0) {
+        cv = *reinterpret_cast<const ulonglong2 *>(c0 + (size_t)r * n + s2);
+        if (!c0_ext) {
+            const u64 pm = pmont[r];
+            cv.x = redc((u128)cv.x * pm, m.q, m.qinv), cv.y = redc((u128)cv.y * pm, m.q, m.qinv);
+        }
+    }
+    const int a_end = min(f.n, (int)(blockIdx.z + 1) * IP_FAN_CHUNK);
+    for (int a = blockIdx.z * IP_FAN_CHUNK; a < a_end; a++) {
+        const unsigned dst = perm_src(s2, f.ginv[a], logn);       // where this rotation puts source s2; s2 + 1 goes to dst ^ 1
+        const unsigned base = dst & ~1u;
+        const bool swap = dst & 1u;
+        const u64 *key = f.key[a];
+        const u64 cg0 = ((u64)base + 1) * GOLD, cg1 = cg0 + GOLD;
+        u128 a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+#pragma unroll
+        for (int j = 0; j < IP_SHARED_MAX_BETA; j++) {
+            if (j < beta) {
+                const u64 dx = swap ? d[j].y : d[j].x, dy = swap ? d[j].x : d[j].y;      // sources of positions base, base + 1
+                const u64 *kb = key + ((size_t)j * nmod + mi) * n + base;
+                ulonglong2 eb, ea;
+                eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
+                const u64 sk_ = key[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
+                ea.x = evk_a_draw(sk_, cg0, base, bound), ea.y = evk_a_draw(sk_, cg1, base + 1, bound);
+                b0 += (u128)dx * eb.x;
+                b1 += (u128)dy * eb.y;
+                a0 += (u128)dx * ea.x;
+                a1 += (u128)dy * ea.y;
+            }
+        }
+        ulonglong2 r0 = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
+        if (have_c0) r0.x = addmod(r0.x, swap ? cv.y : cv.x, m.q), r0.y = addmod(r0.y, swap ? cv.x : cv.y, m.q);
+        const size_t o = (size_t)r * n + base;
+        *reinterpret_cast<ulonglong2 *>(f.out[a] + o) = r0;
+        *reinterpret_cast<ulonglong2 *>(f.out[a] + (size_t)ext * n + o) = make_ulonglong2(redc_raw(a0, m), redc_raw(a1, m));
+    }
+}
+bool launch_inner_product_fanout(cm_ctx *ctx, const IpFan &f, const u64 *dig, const u64 *c0, bool c0_ext, int beta, int level,
+                                 hipStream_t st) {
+    if (beta > IP_SHARED_MAX_BETA || f.n < 1 || f.n > IP_FAN_MAX) return false;
+    Prof prof_(ctx, CM_K_INNER_PRODUCT, f.n, st);
+    const int ext = level + 1 + ctx->K;
+    hipLaunchKernelGGL(k_inner_product_fanout, dim3(ctx->n / (2 * TPB), ext, (f.n + IP_FAN_CHUNK - 1) / IP_FAN_CHUNK), dim3(TPB), 0, st,
+                       f, dig, c0, c0_ext ? 1 : 0, ctx->d_modc, beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, ctx->d_pmont,
+                       (ctx->L + ctx->alpha) / ctx->alpha, ctx->d_ubound);
+    return true;
+}
 // NA keys (rotation amounts) applied to the same nz digit arrays, summed: out[z] = extra[z] + sum_a [ sum_j
 // sigma_a(dig_z,j) key_a,j + (sigma_a(c0_z), 0) ].  A lane keeps the words of all NA keys in registers (at most
 // IP_MULTI_BETA digits) and writes every output once: against one launch per amount this saves the read-modify-write

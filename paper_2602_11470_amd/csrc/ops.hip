@@ -235,6 +235,22 @@ cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u6
 cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys,
                                const u64 *gs, const u64 *in, u64 *const *raised, hipStream_t st, bool in_ext) {
     const KsLevelFull &k = ks_level_full(ctx, level);
+    if (k.beta <= 8) {
+        // one digit array, many keys: the lanes keep the digits and walk over the keys (inverse Galois maps)
+        const u64 two_n = 2 * (u64)ctx->n;
+        for (int base = 0; base < cnt; base += IP_FAN_MAX) {
+            IpFan f;
+            f.n = cnt - base < IP_FAN_MAX ? cnt - base : IP_FAN_MAX;
+            for (int r = 0; r < f.n; r++) {
+                f.key[r] = keys[base + r], f.out[r] = raised[base + r];
+                u64 g = gs[base + r] % two_n, x = g;                 // inverse of the odd g modulo the power of two 2n
+                for (int it = 0; it < 6; it++) x = (x * (2 - g * x)) % two_n;      // Newton: doubles the correct low bits
+                f.ginv[r] = (unsigned)x;
+            }
+            launch_inner_product_fanout(ctx, f, digits, in, in_ext, k.beta, level, st);
+        }
+        return CM_OK;
+    }
     for (int base = 0; base < cnt; base += IP_MAX_ITEMS) {
         IpBatch b;
         b.nz = cnt - base < IP_MAX_ITEMS ? cnt - base : IP_MAX_ITEMS, b.nsum = 1;
