@@ -105,6 +105,8 @@ def kernel_profile(g, steps):
 
 
 def time_rotations(g, reps=20):
+    """Seconds per un-hoisted rotation, and seconds per launch of its inner-product kernel (k_inner_product, which moves
+    the stored key half, the digits and the result of one key switch and shares nothing)."""
     torch, ctx = g["torch"], g["ctx"]
     r = ctx.rotate(g["keys"], g["ct"], 7)
     torch.cuda.synchronize()
@@ -112,7 +114,14 @@ def time_rotations(g, reps=20):
     for _ in range(reps):
         ctx.rotate(g["keys"], g["ct"], 7, out=r)
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / reps
+    sec = (time.perf_counter() - t0) / reps
+    ctx.profile_enable(True)
+    for _ in range(5):
+        ctx.rotate(g["keys"], g["ct"], 7, out=r)
+    torch.cuda.synchronize()
+    launches, _, ms = ctx.profile_get(3)
+    ctx.profile_enable(False)
+    return sec, ms / launches * 1e-3
 
 
 def ntt_rates(g, reps=20):
@@ -413,7 +422,7 @@ def main():
         print(f"bench.py: decrypted result off by {err}", file=sys.stderr)
         sys.exit(1)
     fam = kernel_profile(g, min(a.steps, 5))
-    t_rot = time_rotations(g)
+    t_rot, t_ip_single = time_rotations(g)
     calibration_kernel(g)
     rates = ntt_rates(g)
     n, limbs, K, beta = g["ctx"].n, 24, 4, 6
@@ -430,9 +439,28 @@ def main():
     ip = fam["inner_product"]
     ip_launch_s = ip["ms"] / ip["units"] * 1e-3
     ext = limbs + K
-    # the stored half of the key (the uniform half is regenerated from its seed in the kernel) + raised digits + result
-    ip_bytes = limb_bytes * (beta * ext + beta * ext + 2 * ext)
+    # Algorithmic bytes of the family per step.  W = one polynomial on the extended basis; an inner product on its own
+    # moves the stored half of its key (the uniform half is regenerated from its seed in the kernel), the raised digits
+    # and the two-component result.  In the default form the launches share operands: the baby steps read the digits
+    # and the first component once for all keys; the giant steps and each ladder run write one sum.
+    W_ = limb_bytes * ext
+    plan = g["plan"]
+    default_form = not (nested or a.ladders)
+    if default_form:
+        runs = 2 * -(-int(np.log2(g["t"])) // 3)                                  # preprocess and reduce ladders, runs of <= 3 steps
+        ladder_amounts = plan.n_rotations - (plan.r_i - 1) - (plan.r_o - 1)
+        ip_family_bytes = ((beta * W_ + W_) + (plan.r_i - 1) * (beta * W_ + 2 * W_)                 # baby steps
+                           + (plan.r_o - 1) * (2 * beta * W_ + W_) + 4 * W_                       # giant steps into one sum
+                           + runs * (beta * W_ + W_ + 4 * W_) + ladder_amounts * beta * W_)       # ladder runs
+    else:
+        ip_family_bytes = ip["units"] * (2 * beta * W_ + 2 * W_)           # every inner product on its own
+    ip_bytes = ip_family_bytes / ip["units"]                                      # per inner product, on average
     ip_gbs = ip_bytes / ip_launch_s / 1e9
+    mac = fam["vmm_mac"]
+    mac_bytes = limb_bytes * ext * (plan.r_i * plan.r_o + 2 * plan.r_i + 2 * plan.r_o) if not a.plain_sums else \
+        limb_bytes * limbs * (plan.r_i * plan.r_o + 2 * plan.r_i + 2 * plan.r_o)
+    mac_s = mac["ms"] / mac["launches"] * 1e-3
+    mac_gbs = mac_bytes / mac_s / 1e9
     tr = measured_traffic()
     ntt_traffic = tr["ntt_fwd_per_limb"] * ntt_per_launch_limbs if "ntt_fwd_per_limb" in tr else None
     roofs = {
@@ -441,11 +469,23 @@ def main():
                     "kernel": "ntt_cols_fwd+ntt_rows256_fwd (one launch of the pair)",
                     "limbs_per_launch": ntt_per_launch_limbs, "us_per_launch": ntt_launch_s * 1e6},
         "inner_product": {"bound": "hbm", "achieved": ip_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                          "frac": ip_gbs / HBM_PEAK_GBS, "traffic": tr.get("k_inner_product"),
-                          "kernel": "k_inner_product_batch / k_inner_product (per inner product; one launch of the "
-                                    "batched kernel = 32, 31 or 7 of them)",
+                          "frac": ip_gbs / HBM_PEAK_GBS,
+                          "traffic": (tr["inner_product_family_per_step"] / ip["units"]
+                                      if default_form and "inner_product_family_per_step" in tr else None),
+                          "kernel": "k_inner_product_fanout (the hoisted baby steps, digits read once per 8 keys) + "
+                                    "k_inner_product_batch (giant steps, ladder runs): per inner product, averaged over "
+                                    "the inner products of a step",
+                          "algorithmic_bytes_per_inner_product": ip_bytes,
                           "inner_products_per_step": ip["units"], "launches_per_step": ip["launches"],
                           "us_per_launch": ip_launch_s * 1e6},
+        "inner_product_single": {"bound": "hbm", "achieved": (2 * beta * W_ + 2 * W_) / t_ip_single / 1e9, "peak": HBM_PEAK_GBS,
+                                 "unit": "GB/s", "frac": (2 * beta * W_ + 2 * W_) / t_ip_single / 1e9 / HBM_PEAK_GBS,
+                                 "traffic": tr.get("k_inner_product"),
+                                 "kernel": "k_inner_product (the inner product of one un-hoisted key switch)",
+                                 "us_per_launch": t_ip_single * 1e6},
+        "vmm_mac": {"bound": "hbm", "achieved": mac_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mac_gbs / HBM_PEAK_GBS,
+                    "traffic": tr.get("k_vmm_mac_lds"), "kernel": "k_vmm_mac_lds (one launch per step)",
+                    "algorithmic_bytes_per_launch": mac_bytes, "us_per_launch": mac_s * 1e6},
     }
     roofline = roofs.get(dom, roofs["inner_product"])
     ks_bytes = limb_bytes * (beta * ext + limbs + 2 * limbs)             # stored key half once + input + output
@@ -473,6 +513,8 @@ def main():
         "dominant_kernel_family": dom,
         "roofline": roofline,
         "roofline_inner_product": roofs["inner_product"],
+        "roofline_vmm_mac": roofs["vmm_mac"],
+        "roofline_key_switch_inner_product": roofs["inner_product_single"],
         "roofline_ntt_fwd": roofs["ntt_fwd"],
     }
     if not a.no_cpu_baseline:
