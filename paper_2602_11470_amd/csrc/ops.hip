@@ -232,20 +232,25 @@ cm_status ks_apply(cm_ctx *ctx, const u64 *digits, const u64 *evk, int level, u6
     launch_inner_product(ctx, A.u, A.u + (size_t)k.ext * ctx->n, digits, evk, k.beta, level, g, st);
     return moddown_into(ctx, A.u, level, addend, addend_comps, g, out, accum, st);
 }
+// inverse of the odd g modulo the power of two 2n (Newton's iteration doubles the correct low bits)
+static unsigned galois_inverse(const cm_ctx *ctx, u64 g) {
+    const u64 two_n = 2 * (u64)ctx->n;
+    g %= two_n;
+    u64 x = g;
+    for (int it = 0; it < 6; it++) x = (x * (2 - g * x)) % two_n;
+    return (unsigned)x;
+}
 cm_status ks_apply_many_raised(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys,
                                const u64 *gs, const u64 *in, u64 *const *raised, hipStream_t st, bool in_ext) {
     const KsLevelFull &k = ks_level_full(ctx, level);
     if (k.beta <= 8) {
         // one digit array, many keys: the lanes keep the digits and walk over the keys (inverse Galois maps)
-        const u64 two_n = 2 * (u64)ctx->n;
         for (int base = 0; base < cnt; base += IP_FAN_MAX) {
             IpFan f;
             f.n = cnt - base < IP_FAN_MAX ? cnt - base : IP_FAN_MAX;
             for (int r = 0; r < f.n; r++) {
                 f.key[r] = keys[base + r], f.out[r] = raised[base + r];
-                u64 g = gs[base + r] % two_n, x = g;                 // inverse of the odd g modulo the power of two 2n
-                for (int it = 0; it < 6; it++) x = (x * (2 - g * x)) % two_n;      // Newton: doubles the correct low bits
-                f.ginv[r] = (unsigned)x;
+                f.ginv[r] = galois_inverse(ctx, gs[base + r]);
             }
             launch_inner_product_fanout(ctx, f, digits, in, in_ext, k.beta, level, st);
         }
@@ -447,9 +452,17 @@ cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, cons
         const int base = b * CM_KS_BATCH, m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
         u64 *bu = A.bu + (b & 1) * bufw;
         if (b >= 2) hipStreamWaitEvent(aux, moddown_done[b - 2], 0);     // its buffer has been consumed
-        for (int r = 0; r < m; r++)
-            launch_inner_product(ctx, bu + r * ublk, bu + r * ublk + (size_t)k.ext * n, digits, keys[base + r],
-                                 k.beta, level, gs[base + r], aux);
+        if (k.beta <= 8) {
+            // one digit array, m keys: the source-stationary kernel reads the digits once for the batch
+            IpFan f;
+            f.n = m;
+            for (int r = 0; r < m; r++) f.key[r] = keys[base + r], f.out[r] = bu + r * ublk, f.ginv[r] = galois_inverse(ctx, gs[base + r]);
+            launch_inner_product_fanout(ctx, f, digits, nullptr, false, k.beta, level, aux);
+        } else {
+            for (int r = 0; r < m; r++)
+                launch_inner_product(ctx, bu + r * ublk, bu + r * ublk + (size_t)k.ext * n, digits, keys[base + r],
+                                     k.beta, level, gs[base + r], aux);
+        }
         inner_done[b] = record(aux);
     };
     if (nbatch > 16) return CM_E_INVAL;               // the event ring holds 32
