@@ -16,7 +16,7 @@ rotation by P on its own (Algorithm 1 as printed, 32 x 16, 52 rotations).
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--ladders | --nested-giants | --plain-sums]
 
     python bench.py --workload attention        (config 3, a JSON line of its own)
-    python bench.py --workload prefill          (prompt phase: token-batched product, group append)
+    python bench.py --workload prefill          (prompt phase: token-batched product, group append, group attention)
 
 Prints one JSON line.  `roofline` describes the kernel family with the most time in the step:
 achieved = algorithmic bytes per unit / measured time per unit (HIP events around every launch of
@@ -379,10 +379,29 @@ def prefill_workload(a):
         kv.set_tokens(0)
         kv.append_group(keys, kr, vg)
     append_ms = timed(append, a.steps)
+    del kv, keys
+    # attention of a query group against a prompt of 128 tokens (16 K ciphertexts, all 128 V ciphertexts), for one
+    # delta: q K^T without replication, scores V without the sum over the residues; a group takes t of each plus
+    # 2 (t - 1) inner rotations
+    tk = ctx.S // (H * E)
+    kva = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=True)
+    akeys = ctx.keygen_rotations(sk, [s_ for s_ in kva.steps() if s_ % tk == 0], 2, with_relin=True)
+    encl = lambda seed: ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), ctx.L), seed), lv)
+    for c in range(128):
+        if c < 16:
+            kva.load(B.CM_QK, c, encl(100 + c))
+        kva.load(B.CM_SV, c, encl(300 + c))
+    kva.set_tokens(16 * tk)
+    qg, sg = encl(10), encl(11)
+    qk_ms = timed(lambda: ctx.vmm_kv(akeys, kva, B.CM_QK_GROUP, qg), max(2, a.steps // 4))
+    sv_ms = timed(lambda: ctx.vmm_kv(akeys, kva, B.CM_SV_GROUP, sg), max(2, a.steps // 4))
     print(json.dumps({"metric": "prompt phase, ms per ciphertext of 8 tokens (n=2^16, 24+4 primes)", "unit": "ms", "n_gpus": 1,
                       "data": "synthetic", "dtype": "u64", "token_batched_4096x4096": rows,
                       "rope_group_ms": rope_ms, "inner_rotation_ms": inner_ms, "append_group_ms": append_ms,
-                      "append_group_ms_per_token": append_ms / (ctx.S // (H * E))}))
+                      "append_group_ms_per_token": append_ms / tk,
+                      "group_attention_prompt_128": {"cache_level": lv, "qk_group_ms_per_delta": qk_ms,
+                                                     "sv_group_ms_per_delta": sv_ms,
+                                                     "ms_per_group": tk * (qk_ms + sv_ms) + 2 * (tk - 1) * inner_ms}}))
 
 
 def main():

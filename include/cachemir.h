@@ -235,8 +235,12 @@ cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *con
 /* ---- encrypted KV cache (Sec. 5) -------------------------------------------------------- */
 /* CM_QK_GROUP: query-times-K for a query GROUP (Sec. 5.4: token tau at residue tau of every (e, h)
  * block, possibly after an inner rotation): nothing is replicated, and slot (c, h, tau') of the
- * result is the score of the query at residue tau' against key token c*t + tau'. */
-enum { CM_QK = 0, CM_SV = 1, CM_QK_GROUP = 2 };
+ * result is the score of the query at residue tau' against key token c*t + tau'.
+ * CM_SV_GROUP: scores-times-V for such scores: the residues are NOT summed; slot (e, h, tau') of the
+ * result is sum_c s[c, h, tau'] V[c*t + tau', h, e], the contribution of the keys at residue tau' to
+ * the query whose scores sit there.  An inner rotation by t - delta takes it back to the query's own
+ * residue; the sum over delta is the attention output of the whole group. */
+enum { CM_QK = 0, CM_SV = 1, CM_QK_GROUP = 2, CM_SV_GROUP = 3 };
 /* Cache for `heads` heads of `dim` dims (heads*dim*t = S) holding up to max_tokens tokens
  * (<= dim*t) at ciphertext level `level` and scale `scale`.  r_i = baby steps of the
  * score-times-V product (0 = dim, no giant steps). */
@@ -285,7 +289,8 @@ cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k
 cm_status cm_kv_append_group(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_grp,
                              const cm_ct *v_grp, void *stream);
 /* which = CM_QK: in = query at (e, h, 0) slots, cache level; out = scores, two levels lower.
- * which = CM_SV: in = scores; out = attention output at (e, h, 0), one level lower. */
+ * which = CM_SV: in = scores; out = attention output at (e, h, 0), one level lower.
+ * CM_QK_GROUP / CM_SV_GROUP: the same levels; no keys for the residue rotations are needed. */
 cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t which,
                     const cm_ct *in, cm_ct *out, void *stream);
 

@@ -273,9 +273,12 @@ def qk_scores_unrolled(ctx, keys, lay: KvLayout, cq, k_cts, masks, replicate=Tru
     return ctx.rescale(acc)
 
 
-def score_times_v(ops, lay: KvLayout, cs, v_cts):
+def score_times_v(ops, lay: KvLayout, cs, v_cts, reduce=True):
     """Sec. 5.2/5.3: Att[h, e] = sum_n s[h, n] V[n, h, e]; result at (e, h, 0), the input
-    layout of the next plaintext product (other residues hold partial sums)."""
+    layout of the next plaintext product (other residues hold partial sums).  reduce=False
+    (Sec. 5.4, scores of a query group): the residues are not summed, slot (e, h, tau) holds
+    sum_c s[c, h, tau] V[c t + tau, h, e], the contribution of the keys at residue tau to the query
+    whose scores sit at residue tau."""
     babies = [cs] + ops.rotate_many(cs, [j * lay.H * lay.t for j in range(1, lay.r_i)])
     inner = []
     for g in range(lay.r_o):
@@ -285,7 +288,7 @@ def score_times_v(ops, lay: KvLayout, cs, v_cts):
     for g in range(lay.r_o - 2, -1, -1):
         acc = ops.add(inner[g], ops.rotate(acc, lay.r_i * lay.H * lay.t))
     acc = ops.rescale(acc)
-    for l in range(_log2(lay.t)):
+    for l in range(_log2(lay.t) if reduce else 0):
         acc = ops.add(acc, ops.rotate(acc, 1 << l))
     return acc
 
@@ -298,12 +301,12 @@ def sv_unrolled_steps(lay: KvLayout):
     return steps + [a for grp in ladder_groups([1 << l for l in range(_log2(lay.t))]) for a in grp]
 
 
-def score_times_v_unrolled(ctx, keys, lay: KvLayout, cs, v_cts):
+def score_times_v_unrolled(ctx, keys, lay: KvLayout, cs, v_cts, reduce=True):
     """score_times_v without dependent rotations after the products: the giant steps unrolled
     (sum_g Rot(inner_g, g G), each rotation left in the extended basis next to P inner_0) and the
     reduce ladder over the residues run there too, in runs of hoisted rotations (ckks.rotsum_raised),
     before one ModDown and the rescale (the ladder form rescales first and reduces one level lower;
-    the message is the same)."""
+    the message is the same).  reduce=False: no ladder over the residues (see score_times_v)."""
     Ht, lv = lay.H * lay.t, cs.level
     ext = ctx.ext_idx(lv)
     h = ctx.hoist(cs)
@@ -319,7 +322,7 @@ def score_times_v_unrolled(ctx, keys, lay: KvLayout, cs, v_cts):
     for g in range(1, lay.r_o):
         R = ctx.rotate_hoisted_raised(inner[g], ctx.hoist(inner[g]), g * lay.r_i * Ht, keys)
         T = [ctx.add(T[0], R[0], ext), ctx.add(T[1], R[1], ext)]
-    for amounts in ladder_groups([1 << l for l in range(_log2(lay.t))]):
+    for amounts in ladder_groups([1 << l for l in range(_log2(lay.t) if reduce else 0)]):
         T = ctx.rotsum_raised(T, lv, amounts, keys)
     return ctx.rescale(ctx.moddown_ct(T, lv, inner[0].scale))
 

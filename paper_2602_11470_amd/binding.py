@@ -17,7 +17,7 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} not built: run python -m paper_2602_11470_amd.build")
 lib = C.CDLL(LIB_PATH)
 
-CM_QK, CM_SV, CM_QK_GROUP = 0, 1, 2
+CM_QK, CM_SV, CM_QK_GROUP, CM_SV_GROUP = 0, 1, 2, 3
 CM_VMM_RAISED_SUMS, CM_VMM_DIRECT_GIANTS, CM_VMM_TOKEN_BATCH, CM_VMM_UNROLLED_LADDERS = 1, 2, 4, 8
 CM_KV_UNROLLED_LADDERS = 1
 
@@ -329,7 +329,7 @@ class Context:
         return KvCache(self, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders)
 
     def vmm_kv(self, evk, kv, which, x):
-        out = Ct(self, x.level - (1 if which == CM_SV else 2))
+        out = Ct(self, x.level - (1 if which in (CM_SV, CM_SV_GROUP) else 2))
         _chk(lib.cm_vmm_kv(self.h, evk.h, kv.h, which, C.byref(x.d), C.byref(out.d), _stream()))
         return out
 

@@ -426,7 +426,8 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     RETURN_LAUNCH_STATUS();
 }
 
-static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st) {
+static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st,
+                       bool reduce) {
     const int lv = kv->level, limbs = lv + 1;
     const size_t n = ctx->n, ctw = kv_ctw(kv), ln = (size_t)limbs * n;
     const u64 *relin = find_key(evk, 0);
@@ -436,10 +437,10 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     if (kv->unrolled) {
         for (int g = 1; g < kv->r_o; g++) if (!find_key(evk, rot_g(kv, (long long)g * kv->r_i * Ht))) return CM_E_NOKEY;
         for (const auto &grp : kv->res_groups)
-            for (long long a : grp) if (!find_key(evk, rot_g(kv, a))) return CM_E_NOKEY;
+            for (long long a : grp) if (reduce && !find_key(evk, rot_g(kv, a))) return CM_E_NOKEY;
     } else {
         if (kv->r_o > 1 && !find_key(evk, rot_g(kv, kv->r_i * Ht))) return CM_E_NOKEY;
-        for (int l = 0; l < ilog2(kv->t); l++) if (!find_key(evk, rot_g(kv, 1 << l))) return CM_E_NOKEY;
+        for (int l = 0; l < ilog2(kv->t) && reduce; l++) if (!find_key(evk, rot_g(kv, 1 << l))) return CM_E_NOKEY;
     }
     const KsLevel &kl = ks_level(ctx, lv);
     const size_t B = CM_KS_BATCH, dblk = (size_t)kl.beta * kl.ext * n, ublk = 2 * (size_t)kl.ext * n;
@@ -499,6 +500,7 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
             std::swap(cur, nxt);
         }
         for (const auto &grp : kv->res_groups) {
+            if (!reduce) break;                                  // scores of a query group: the residues stay apart
             CMCHK(moddown_second_keep(ctx, cur, lv, tmp, st));
             CMCHK(ks_raise(ctx, tmp + ln, lv, digits, st));
             IpBatch b;
@@ -526,7 +528,7 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
         acc = nxt;
     }
     CMCHK(rescale_into(ctx, acc, 2, lv, R, st));
-    for (int l = 0; l < ilog2(kv->t); l++) {
+    for (int l = 0; l < ilog2(kv->t) && reduce; l++) {
         u64 g = rot_g(kv, 1 << l);
         CMCHK(rotate_into(ctx, find_key(evk, g), R, lv - 1, g, tmp, st, R));
         std::swap(R, tmp);
@@ -543,6 +545,6 @@ extern "C" cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, 
     if (!ctx || !evk || !kv || kv->ctx != ctx || !in || !in->dev || !out || !out->dev || in->ncomp != 2) return CM_E_INVAL;
     if (in->level != kv->level) return CM_E_LEVEL;
     if (which == CM_QK || which == CM_QK_GROUP) return kv_qk(ctx, evk, kv, in, out, (hipStream_t)stream, which == CM_QK);
-    if (which == CM_SV) return kv_sv(ctx, evk, kv, in, out, (hipStream_t)stream);
+    if (which == CM_SV || which == CM_SV_GROUP) return kv_sv(ctx, evk, kv, in, out, (hipStream_t)stream, which == CM_SV);
     return CM_E_INVAL;
 }

@@ -288,6 +288,58 @@ def test_prompt_phase_on_the_full_ring_builds_a_cache_the_decode_products_can_us
     assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
 
 
+def test_prompt_phase_attention_of_a_query_group_on_the_full_ring(ring2):
+    """Sec. 5.4 at Llama-3-8B attention shapes (32 heads x 128 dims, t = 8), extended-basis ladders: a
+    group of 8 queries is inner-rotated by delta and meets two K ciphertexts without replication; the
+    scores of a group meet V without the sum over the residues and are inner-rotated back by
+    t - delta; the sum over the deltas taken is, per query, the float64 product of those scores with V."""
+    from oracle import packing
+    B, octx, gctx, prm = ring2
+    H, E = 32, 128
+    lay = packing.KvLayout(gctx.S, H, E, 16)
+    t, nk = lay.t, 2
+    ntok = nk * t
+    lv = 5                                              # cache level; the query group arrives one level higher
+    rng = np.random.default_rng(23)
+    Q = rng.normal(size=(t, H, E)) * 0.3
+    K = rng.normal(size=(ntok, H, E))
+    V = rng.normal(size=(ntok, H, E))
+    deltas = (0, 3)
+    kv = gctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=True)
+    gsk = gctx.keygen_secret(1)
+    rots = {d: (gctx.inner_rot(t, d, lv + 1), gctx.inner_rot(t, t - d, lv - 1)) for d in deltas if d}
+    steps = {a for a in kv.steps() if a % t == 0}      # nothing moves a residue except the inner rotations
+    for fwd, bwd in rots.values():
+        steps |= set(fwd.steps()) | set(bwd.steps())
+    gkeys = gctx.keygen_rotations(gsk, sorted(steps), 2, with_relin=True)
+    enc = lambda slots, level, seed: gctx.level_drop(gctx.encrypt(gsk, gctx.encode(slots, gctx.L), seed), level)
+    for c in range(nk):
+        kv.load(B.CM_QK, c, enc(lay.pack_k(K, c), lv, 100 + c))
+    for k in range(E):
+        kv.load(B.CM_SV, k, enc(lay.pack_v(V, k), lv, 300 + k))
+    kv.set_tokens(ntok)
+    gq = enc(sum(lay.pack_vec(Q[tau], tau) for tau in range(t)), lv + 1, 10)
+    full = np.einsum("ahe,nhe->ahn", Q, K)              # [query, head, key]
+    out, want = None, np.zeros((t, H, E))
+    for delta in deltas:
+        gx = gctx.rope_apply(gkeys, rots[delta][0], gq) if delta else gctx.level_drop(gq, lv)
+        gm = gctx.vmm_kv(gkeys, kv, B.CM_QK_GROUP, gx)
+        got = lay.unpack_scores(gctx.decrypt(gsk, gm).real, ntok)
+        for n in range(ntok):
+            assert np.abs(got[:, n] - full[(n % t - delta) % t, :, n]).max() < TOL
+        # scores of the group after the (plaintext-side) non-linearity: fresh values at the same slots
+        s = rng.uniform(0, 1, size=(H, ntok)) / ntok
+        ga = gctx.vmm_kv(gkeys, kv, B.CM_SV_GROUP, enc(lay.pack_scores(s), lv, 50 + delta))
+        assert ga.level == lv - 1
+        gb = gctx.rope_apply(gkeys, rots[delta][1], ga) if delta else gctx.level_drop(ga, lv - 2)
+        out = gb if out is None else gctx.add(out, gb)
+        for n in range(ntok):                           # s[h, n] belongs to query (n % t - delta) mod t
+            want[(n % t - delta) % t] += s[:, n][:, None] * V[n]
+    res = gctx.decrypt(gsk, out).real
+    for tau in range(t):
+        assert np.abs(lay.unpack_vec(res, tau) - want[tau]).max() < TOL
+
+
 def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
     """Two decode steps of one Llama-3-8B-shaped layer's linear path on the 36 + 6 prime ring: k / v /
     q projections (8 KV heads replicated to 32 by repeating weight columns, columns ordered as the

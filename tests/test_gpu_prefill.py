@@ -8,6 +8,7 @@ pytestmark = pytest.mark.gpu
 
 TOL = 1e-4
 CM_E_LAYOUT = -5
+CM_E_NOKEY = -4
 
 
 @pytest.fixture(scope="module")
@@ -280,3 +281,60 @@ def test_inner_rotation_and_group_scores_match_oracle_and_all_query_key_pairs(en
     with pytest.raises(B.CachemirError) as ei:
         gctx.inner_rot(lay.t, lay.t, lv + 1)
     assert ei.value.status == CM_E_LAYOUT
+
+
+@pytest.mark.parametrize("unrolled,r_i", [(False, 0), (False, 4), (True, 4), (True, 0)])
+def test_group_scores_times_v_and_the_rotation_back_match_oracle(env, unrolled, r_i):
+    """Prompt-phase scores V (Sec. 5.4): the scores of a query group (those of the query at residue
+    (tau' - delta) mod t against key token c t + tau' at (c, h, tau')) meet V without the sum over
+    the residues; an inner rotation by t - delta then takes every partial result to its query's
+    residue.  Limbs against the oracle, values against float64."""
+    from oracle import packing, vmm
+    e = env
+    B, octx, gctx = e["B"], e["octx"], e["gctx"]
+    H, E, L = 16, 16, octx.prm.L
+    lay = packing.KvLayout(octx.S, H, E, r_i)            # t = 8
+    nk, delta = 3, 3
+    ntok = nk * lay.t
+    rng = np.random.default_rng(41 + r_i)
+    V = rng.normal(size=(ntok, H, E))
+    s = rng.uniform(0, 1, size=(H, ntok)) / ntok         # s[h, c t + tau']: the score sitting at (c, h, tau')
+    lv = L - 1
+    kv = gctx.kv_create(H, E, lv, r_i=r_i, unrolled_ladders=unrolled)
+    back = lay.t - delta
+    all_sv = vmm.sv_unrolled_steps(lay) if unrolled else lay.sv_steps()
+    steps = sorted({a for a in all_sv if a % lay.t == 0} | set(lay.inner_rotation_steps(back)))
+    okeys = octx.keygen_rotations(e["osk"], steps, 2, with_relin=True)
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2, with_relin=True)   # no key for a residue rotation
+    ovc = []
+    for k in range(E):
+        ov, gv = _enc_both(e, lay.pack_v(V, k), lv, 300 + k)
+        ovc.append(ov)
+        kv.load(B.CM_SV, k, gv)
+    kv.set_tokens(ntok)
+    os_, gs = _enc_both(e, lay.pack_scores(s), lv, 50)
+    if unrolled:
+        oa = vmm.score_times_v_unrolled(octx, okeys, lay, os_, ovc, reduce=False)
+    else:
+        oa = vmm.score_times_v(vmm.CkksOps(octx, okeys), lay, os_, ovc, reduce=False)
+    ga = gctx.vmm_kv(gkeys, kv, B.CM_SV_GROUP, gs)
+    _same(e, oa, ga)
+    part = gctx.decrypt(e["gsk"], ga).real
+    want = np.stack([sum(s[:, c * lay.t + tau][:, None] * V[c * lay.t + tau] for c in range(nk)) for tau in range(lay.t)])
+    for tau in range(lay.t):
+        assert np.abs(lay.unpack_vec(part, tau) - want[tau]).max() < TOL
+    # back to the query's residue
+    ql = float(octx.mod[lv - 1])
+    coeffs = [octx.encode_coeffs(p, ql) for p in lay.inner_rotation_plaintexts(back)]
+    opts = [octx.pt_from_coeffs(cf, lv - 1, ql) for cf in coeffs]
+    rot = gctx.inner_rot(lay.t, back, lv - 1, coeffs=np.stack(coeffs))
+    ob = vmm.inner_rotate(vmm.CkksOps(octx, okeys, pt_scale=ql), lay, oa, back, opts)
+    gb = gctx.rope_apply(gkeys, rot, ga)
+    _same(e, ob, gb)
+    moved = gctx.decrypt(e["gsk"], gb).real
+    for tau in range(lay.t):
+        assert np.abs(lay.unpack_vec(moved, (tau - delta) % lay.t) - want[tau]).max() < TOL
+    # the one-query call still needs the residue keys
+    with pytest.raises(B.CachemirError) as ei:
+        gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)
+    assert ei.value.status == CM_E_NOKEY

@@ -525,3 +525,67 @@ def test_unrolled_scores_times_v_decrypts_to_s_times_V(r_i):
     ladder = vmm.score_times_v(vmm.CkksOps(ctx, keys), lay, cs, vc)
     assert abs(a.scale / ladder.scale - 1) < 1e-12
     assert np.abs(ctx.decrypt(sk, a) - ctx.decrypt(sk, ladder)).max() < 1e-6
+
+
+@pytest.mark.parametrize("r_i", [0, 2])
+def test_group_attention_on_slots_is_Q_K_transposed_times_V_for_every_query(r_i):
+    """Sec. 5.4 end to end on slots: for every delta the query group is inner-rotated, meets the keys
+    (un-replicated q K^T), the scores meet V WITHOUT the sum over the residues, and the partial result
+    (at the key's residue) is inner-rotated back by t - delta to the query's residue; the sum over
+    delta is, for each of the t queries, the plain product of its scores with V."""
+    lay = packing.KvLayout(256, 4, 8, r_i)              # t = 8
+    rng = np.random.default_rng(16)
+    nk = 3
+    Q = rng.normal(size=(lay.t, 4, 8))
+    K = rng.normal(size=(nk * lay.t, 4, 8))
+    V = rng.normal(size=(nk * lay.t, 4, 8))
+    qg = sum(lay.pack_vec(Q[tau], tau) for tau in range(lay.t))
+    kc = [lay.pack_k(K, c) for c in range(nk)]
+    vc = [lay.pack_v(V, k) for k in range(lay.E)]
+    masks = [lay.qk_mask(c) for c in range(nk)]
+    ops = vmm.SlotOps()
+    out = np.zeros(lay.S)
+    for delta in range(lay.t):
+        x = qg if delta == 0 else vmm.inner_rotate(ops, lay, qg, delta, lay.inner_rotation_plaintexts(delta))
+        sc = vmm.qk_scores(ops, lay, x, kc, masks, replicate=False)
+        r0 = ops.rotations
+        part = vmm.score_times_v(ops, lay, sc, vc, reduce=False)
+        assert ops.rotations - r0 == lay.r_i - 1 + lay.r_o - 1
+        # a partial result by hand: keys of residue tau' only, query (tau' - delta) mod t
+        for tau in (0, 5):
+            a = (tau - delta) % lay.t
+            want = sum(np.einsum("he,he->h", Q[a], K[c * lay.t + tau])[:, None] * V[c * lay.t + tau] for c in range(nk))
+            assert np.abs(lay.unpack_vec(part, tau) - want).max() < 1e-9
+        back = (lay.t - delta) % lay.t
+        out = out + (part if back == 0 else vmm.inner_rotate(ops, lay, part, back, lay.inner_rotation_plaintexts(back)))
+    att = np.einsum("ahn,nhe->ahe", np.einsum("ahe,nhe->ahn", Q, K), V)
+    for tau in range(lay.t):
+        assert np.abs(lay.unpack_vec(out, tau) - att[tau]).max() < 1e-9
+
+
+def test_group_scores_times_v_on_ciphertexts_in_both_forms():
+    """reduce=False on ciphertexts: the ladder form and the extended-basis form decrypt to the
+    per-residue sums, at the level and scale of the reduced call."""
+    prm = params.toy(n=512, n_qi=4, n_p=1, alpha=1)
+    ctx = ckks.Context(prm)
+    L = prm.L
+    lay = packing.KvLayout(ctx.S, 4, 8, 4)               # t = 8
+    ntok = 3 * lay.t
+    q, K, V, s = inputs.attention_inputs(7, 4, 2, 8, ntok)
+    sk = ctx.keygen_secret(1)
+    steps = [a for a in vmm.sv_unrolled_steps(lay) if a % lay.t == 0]
+    assert len(steps) == (lay.r_i - 1) + (lay.r_o - 1)
+    keys = ctx.keygen_rotations(sk, sorted(set(steps) | {a for a in lay.sv_steps() if a % lay.t == 0}), 2, with_relin=True)
+    enc = lambda v, lv, seed: ctx.level_drop(ctx.encrypt(sk, ctx.encode(v, L), seed), lv)
+    vc = [enc(lay.pack_v(V, k), L - 1, 300 + k) for k in range(lay.E)]
+    cs = enc(lay.pack_scores(s), L - 1, 50)
+    r0 = ctx.rot_count
+    a = vmm.score_times_v_unrolled(ctx, keys, lay, cs, vc, reduce=False)
+    assert ctx.rot_count - r0 == len(steps) and a.level == L - 2
+    b = vmm.score_times_v(vmm.CkksOps(ctx, keys), lay, cs, vc, reduce=False)
+    assert b.level == L - 2 and abs(a.scale / b.scale - 1) < 1e-12
+    da, db = ctx.decrypt(sk, a).real, ctx.decrypt(sk, b).real
+    for tau in range(lay.t):
+        want = sum(s[:, c * lay.t + tau][:, None] * V[c * lay.t + tau] for c in range(ntok // lay.t))
+        assert np.abs(lay.unpack_vec(da, tau) - want).max() < TOL
+        assert np.abs(lay.unpack_vec(db, tau) - want).max() < TOL
