@@ -337,8 +337,18 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
                                                              int level, int L, int nmod, int n, int logn,
                                                              const u64 *__restrict__ pmont, int kdig,
                                                              const u64 *__restrict__ ubound) {
-    const unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
-    const int r = blockIdx.y, z = blockIdx.z;
+    // Workgroups go to the eight XCDs round-robin by their linear index.  The rotated reads of the digits gather over
+    // a whole limb, and every key of a sum gathers over the same limb again: with a limb's workgroups on ONE XCD (each
+    // XCD takes a contiguous eighth of the (limb, block) sequence) those re-reads can hit that XCD's L2.
+    unsigned bx = blockIdx.x;
+    int r = blockIdx.y;
+    if (gridDim.x % 8 == 0) {
+        const unsigned lin = blockIdx.x + gridDim.x * blockIdx.y, per = gridDim.x * gridDim.y / 8;
+        const unsigned v = (lin & 7u) * per + (lin >> 3);
+        bx = v % gridDim.x, r = v / gridDim.x;
+    }
+    const unsigned i2 = (bx * TPB + threadIdx.x) * 2;
+    const int z = blockIdx.z;
     const int mi = r <= level ? r : L + 1 + (r - level - 1);
     const ModC m = modc[mi];
     const size_t o = (size_t)r * n + i2;
@@ -465,8 +475,18 @@ __global__ __launch_bounds__(TPB) void k_inner_product_fanout(IpFan f, const u64
                                                               int level, int L, int nmod, int n, int logn,
                                                               const u64 *__restrict__ pmont, int kdig,
                                                               const u64 *__restrict__ ubound) {
-    const unsigned s2 = (blockIdx.x * TPB + threadIdx.x) * 2;
-    const int r = blockIdx.y;
+    // The key chunks of one (limb, block) read the same digits: they are given consecutive places in the sequence of
+    // ONE XCD (workgroups go to the XCDs round-robin by linear index), so that the digits come from HBM once and from
+    // that XCD's L2 for the other chunks.
+    unsigned bx = blockIdx.x, bz = blockIdx.z;
+    int r = blockIdx.y;
+    if (gridDim.x % 8 == 0) {
+        const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), s = lin >> 3, xs = gridDim.x / 8;
+        bz = s % gridDim.z;
+        const unsigned rest = s / gridDim.z;
+        bx = (lin & 7u) + 8u * (rest % xs), r = rest / xs;
+    }
+    const unsigned s2 = (bx * TPB + threadIdx.x) * 2;
     const int mi = r <= level ? r : L + 1 + (r - level - 1);
     const ModC m = modc[mi];
     const u64 bound = ubound[mi];
@@ -485,8 +505,8 @@ __global__ __launch_bounds__(TPB) void k_inner_product_fanout(IpFan f, const u64
             cv.x = redc((u128)cv.x * pm, m.q, m.qinv), cv.y = redc((u128)cv.y * pm, m.q, m.qinv);
         }
     }
-    const int a_end = min(f.n, (int)(blockIdx.z + 1) * IP_FAN_CHUNK);
-    for (int a = blockIdx.z * IP_FAN_CHUNK; a < a_end; a++) {
+    const int a_end = min(f.n, (int)(bz + 1) * IP_FAN_CHUNK);
+    for (int a = bz * IP_FAN_CHUNK; a < a_end; a++) {
         const unsigned dst = perm_src(s2, f.ginv[a], logn);       // where this rotation puts source s2; s2 + 1 goes to dst ^ 1
         const unsigned base = dst & ~1u;
         const bool swap = dst & 1u;
