@@ -215,7 +215,7 @@ def attention_workload(a):
     ctx = B.llama_ring(24, 4)
     H, E, L = 32, 128, ctx.L
     lv = a.cache_level if a.cache_level > 0 else L - 1
-    kv = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=not a.ladders)
+    kv = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=not a.ladders, shared_dims=1 if a.ladders else a.shared_dims)
     sk = ctx.keygen_secret(1)
     keys = ctx.keygen_rotations(sk, kv.steps(), 2, with_relin=True)
     rng = np.random.default_rng(3)
@@ -248,7 +248,9 @@ def attention_workload(a):
         res[name] = (time.perf_counter() - t0) / reps
     # per key ciphertext: one relinearisation and the sum over the 128 dims, as 7 dependent rotations or,
     # unrolled (runs of 3 + 2 + 2 ladder steps), 13 hoisted ones on 3 ModUps
-    ks_qk = 3 + 128 * (8 if a.ladders else 14)
+    sh = 1 if a.ladders else a.shared_dims
+    per_ct = {1: 13, 2: 14, 4: 10, 8: 6, 16: 7, 32: 3, 64: 1, 128: 0}[sh]    # hoisted rotations of the runs of the ladder left per key ciphertext
+    ks_qk = 3 + 128 * (8 if a.ladders else 1 + per_ct) + sh - 1
     print(json.dumps({
         "metric": "encrypted-cache attention products/s (config 3: q K^T and scores V, 32 heads x 128 dims, "
                   "context 1024, n=2^16, 24x50-bit + 4x60-bit primes)",
@@ -256,7 +258,9 @@ def attention_workload(a):
         "higher_is_better": True, "dtype": "u64", "data": "synthetic", "vs_baseline": None,
         "config": {"workload": "config3: q K^T (128 K ciphertexts) + scores V (128 V ciphertexts, 16 baby x 8 giant)",
                    "cache_level": lv,
-                   "dim_sum": "rotate-and-add ladder" if a.ladders else "unrolled in the extended basis (3 ModUps, 13 rotations)"},
+                   "dim_sum": "rotate-and-add ladder" if a.ladders else
+                              "unrolled in the extended basis (3 ModUps, 13 rotations)" if sh == 1 else
+                              "mask before the last %d terms: %d rotations per key ciphertext + %d shared" % (sh, per_ct, sh - 1)},
         "qk_ms": res["qk"] * 1e3, "sv_ms": res["sv"] * 1e3, "append_ms": append_ms,
         "qk_key_switches": ks_qk, "qk_key_switches_per_s": ks_qk / res["qk"]}))
 
@@ -410,6 +414,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--shared-dims", type=int, default=1,
+                    help="attention workload: terms of the sum over the dims taken after the copy mask by shared rotations")
     ap.add_argument("--ladders", action="store_true",
                     help="preprocess and reduce as the rotate-and-add ladders of Algorithm 1 (3 + 3 dependent rotations)")
     ap.add_argument("--nested-giants", action="store_true",

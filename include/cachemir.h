@@ -257,6 +257,20 @@ cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int
 enum { CM_KV_UNROLLED_LADDERS = 1 };
 cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level,
                           double scale, int32_t max_tokens, uint32_t flags, cm_kv **out);
+/* Sec. 5.1 sums the product of every key ciphertext over all dim copies and then keeps copy e = c by a mask.
+ * Because Rot(a b) = Rot(a) Rot(b), the mask can be applied before the last `shared` terms of that sum
+ * (dim = shared * E2, B = heads * t slots per copy):
+ *   sum_c mask_c sum_{k < dim} Rot(P_c, k B) = sum_{k1 < shared} Rot( sum_c mask_{c+k1} T_c, k1 B ),
+ *   T_c = sum_{k2 < E2} Rot(P_c, k2 shared B),
+ * which takes shared - 1 rotations for the WHOLE cache (plus nk * shared plaintext products by the dim
+ * slot rotations of the mask) instead of log2(shared) ladder steps per key ciphertext.  Same scores,
+ * same levels.  shared = 1 (the default) is the printed order; shared = dim removes every
+ * per-ciphertext rotation and pays off for long contexts.  Only for caches created with
+ * CM_KV_UNROLLED_LADDERS (else CM_E_INVAL); shared a power of two <= dim (else CM_E_LAYOUT).
+ * Allocates max_tokens / t + shared + dim ciphertext-sized buffers (CM_E_NOMEM leaves shared = 1)
+ * and changes the rotation amounts cm_kv_steps lists.  Not to be called while a product of this cache
+ * is in flight. */
+cm_status cm_kv_set_shared_dims(cm_kv *kv, int32_t shared);
 void cm_kv_destroy(cm_kv *kv);
 int32_t cm_kv_steps(const cm_kv *kv, int32_t *steps, int32_t cap);
 int32_t cm_kv_tokens(const cm_kv *kv);

@@ -273,6 +273,76 @@ def qk_scores_unrolled(ctx, keys, lay: KvLayout, cq, k_cts, masks, replicate=Tru
     return ctx.rescale(acc)
 
 
+def qk_shared_steps(lay: KvLayout, shared):
+    """Rotation amounts of qk_scores_shared: the replication ladder of the query, the runs of the
+    per-ciphertext part of the sum over the dims (strides shared * 2^i blocks), the shared - 1 shared rotations."""
+    Ht = lay.H * lay.t
+    ladder = [(shared << i) * Ht for i in range(_log2(lay.E // shared))]
+    steps = [-(1 << i) for i in range(_log2(lay.t))] + [a for grp in ladder_groups(ladder) for a in grp]
+    return steps + [k * Ht for k in range(1, shared)]
+
+
+def qk_scores_shared_ops(ops, lay: KvLayout, cq, k_cts, masks, shared, replicate=True):
+    """q K^T with the mask applied BEFORE the last `shared` terms of the sum over the dims (Sec. 5.1 sums
+    over all E copies of every key ciphertext's product and then keeps copy e = c).  With E = shared * E2
+    and B = H t slots per copy,
+        mask_c * sum_{k < E} Rot(P_c, k B) = sum_{k1 < shared} Rot( mask_{c + k1} * T_c, k1 B ),
+        T_c = sum_{k2 < E2} Rot(P_c, k2 shared B),
+    because Rot(a b) = Rot(a) Rot(b) and a right rotation of mask_c by k1 copies is mask_{c + k1}.  Summed
+    over c, the outer rotations act on A_k1 = sum_c mask_{c + k1} T_c: shared - 1 rotations for the whole
+    cache instead of log2(shared) per key ciphertext.  masks[b] = lay.qk_mask(b) for b < E.  The same
+    scores as qk_scores; shared = 1 is qk_scores itself."""
+    B = lay.H * lay.t
+    for i in range(_log2(lay.t) if replicate else 0):
+        cq = ops.add(cq, ops.rotate(cq, -(1 << i)))
+    T = []
+    for kc in k_cts:
+        p = ops.rescale(ops.relin(ops.mul_ct(cq, kc)))
+        for i in range(_log2(lay.E // shared)):
+            p = ops.add(p, ops.rotate(p, (shared << i) * B))
+        T.append(p)
+    acc = None
+    for k1 in range(shared):
+        a = _sum(ops, [ops.mul_pt(T[c], masks[(c + k1) % lay.E]) for c in range(len(T))])
+        a = a if k1 == 0 else ops.rotate(a, k1 * B)
+        acc = a if acc is None else ops.add(acc, a)
+    return ops.rescale(acc)
+
+
+def qk_scores_shared(ctx, keys, lay: KvLayout, cq, k_cts, masks, shared, replicate=True):
+    """qk_scores_shared_ops in the extended basis: the per-ciphertext part of the sum as in
+    qk_scores_unrolled (runs of hoisted rotations, one ModDown per key ciphertext), then
+    P A_0 + sum_k1 RotRaised(A_k1, k1 B) and one ModDown for the whole cache.  masks[b]: the encoded
+    plaintext of lay.qk_mask(b) at the level of the sums, b < E."""
+    B = lay.H * lay.t
+    for i in range(_log2(lay.t) if replicate else 0):
+        cq = ctx.ct_add(cq, ctx.rotate(cq, -(1 << i), keys))
+    groups = ladder_groups([(shared << i) * B for i in range(_log2(lay.E // shared))])
+    T = []
+    for kc in k_cts:
+        p = ctx.rescale(ctx.relinearize(ctx.mul_ct(cq, kc), keys))
+        if groups:
+            R = ctx.raise_ct(p)
+            for amounts in groups:
+                R = ctx.rotsum_raised(R, p.level, amounts, keys)
+            p = ctx.moddown_ct(R, p.level, p.scale)
+        T.append(p)
+    lv = T[0].level
+    ext = ctx.ext_idx(lv)
+    acc = None
+    for k1 in range(shared):
+        a = None
+        for c in range(len(T)):
+            t = ctx.mul_pt(T[c], masks[(c + k1) % lay.E])
+            a = t if a is None else ctx.ct_add(a, t)
+        if k1 == 0:
+            acc, scale = ctx.raise_ct(a), a.scale
+        else:
+            R = ctx.rotate_hoisted_raised(a, ctx.hoist(a), k1 * B, keys)
+            acc = [ctx.add(acc[0], R[0], ext), ctx.add(acc[1], R[1], ext)]
+    return ctx.rescale(ctx.moddown_ct(acc, lv, scale))
+
+
 def score_times_v(ops, lay: KvLayout, cs, v_cts, reduce=True):
     """Sec. 5.2/5.3: Att[h, e] = sum_n s[h, n] V[n, h, e]; result at (e, h, 0), the input
     layout of the next plaintext product (other residues hold partial sums).  reduce=False

@@ -89,6 +89,7 @@ _SIGS = {
     "cm_kv_tokens": ([_vp], _i32),
     "cm_kv_load": ([_vp, _vp, _i32, _i32, _P(cm_ct), _vp], _i32),
     "cm_kv_set_tokens": ([_vp, _i32], _i32),
+    "cm_kv_set_shared_dims": ([_vp, _i32], _i32),
     "cm_kv_export": ([_vp, _vp, _i32, _i32, _vp], _i32),
     "cm_kv_set_mask": ([_vp, _i32, _vp], _i32),
     "cm_kv_append": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
@@ -325,8 +326,8 @@ class Context:
         _chk(lib.cm_rope_apply(self.h, evk.h, rope.h, C.byref(x.d), C.byref(out.d), _stream()))
         return out
 
-    def kv_create(self, heads, dim, level, scale=0.0, max_tokens=None, r_i=0, unrolled_ladders=False):
-        return KvCache(self, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders)
+    def kv_create(self, heads, dim, level, scale=0.0, max_tokens=None, r_i=0, unrolled_ladders=False, shared_dims=1):
+        return KvCache(self, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders, shared_dims)
 
     def vmm_kv(self, evk, kv, which, x):
         out = Ct(self, x.level - (1 if which in (CM_SV, CM_SV_GROUP) else 2))
@@ -430,12 +431,17 @@ class Rope:
 
 
 class KvCache:
-    def __init__(self, ctx, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders=False):
+    def __init__(self, ctx, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders=False, shared_dims=1):
         self.ctx, self.h, self.level = ctx, _vp(), level
         t = ctx.S // (heads * dim)
         max_tokens = dim * t if max_tokens is None else max_tokens
         _chk(lib.cm_kv_create_ex(ctx.h, heads, dim, r_i, level, scale, max_tokens,
                                  CM_KV_UNROLLED_LADDERS if unrolled_ladders else 0, C.byref(self.h)))
+        if shared_dims != 1:
+            self.set_shared_dims(shared_dims)
+
+    def set_shared_dims(self, shared):
+        _chk(lib.cm_kv_set_shared_dims(self.h, shared))
 
     def steps(self):
         n = lib.cm_kv_steps(self.h, None, 0)

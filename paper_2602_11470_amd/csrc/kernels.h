@@ -23,6 +23,15 @@ void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs,
 void launch_tensor_sum(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int groups, int limbs, hipStream_t st);
 void launch_tensor_batch(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int limbs, hipStream_t st);
 void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st);
+// A[k][2][limbs][n] = sum_{c < nk} T[c] * M[(c + k) mod E], k < shared (2 <= shared <= E, powers of two); T, A stacked
+// ciphertexts, M[E][limbs][n] in multiplier form; limbs use modulus indices 0 .. limbs-1
+void launch_mask_circulant(cm_ctx *ctx, u64 *A, const u64 *T, const u64 *M, int nk, int E, int shared, int limbs, hipStream_t st);
+// the same sums through a length-E transform along the copy index (8 <= E <= 512): Mhat[E][limbs][n] from M once
+// (set-up), then A from T; tw[limbs][2][E/2][2] = omega^e, omega^-e with companions, einv[limbs] = E^-1 in multiplier form
+bool mask_ntt_supported(int E);
+void launch_mask_ntt_setup(cm_ctx *ctx, u64 *Mhat, const u64 *M, const u64 *tw, const u64 *einv, int E, int limbs, hipStream_t st);
+void launch_mask_ntt(cm_ctx *ctx, u64 *A, const u64 *T, const u64 *Mhat, const u64 *tw, const u64 *einv, int nk, int E, int shared,
+                     int limbs, hipStream_t st);
 // batch item z: table (z % tab_period)*tab_step (tab_period 0 = batch), input (z / in_group)*in_stride, output z*out_stride
 void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_step, int max_nt, u64 *out, const u64 *in,
                       size_t in_stride, size_t out_stride, const u64 *own_src, u64 own_g, hipStream_t st,

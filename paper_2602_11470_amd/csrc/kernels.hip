@@ -933,6 +933,192 @@ void launch_vmm_mac(cm_ctx *ctx, u64 *out, const u64 *babies, const u64 *pts, in
     hipLaunchKernelGGL(k_vmm_mac_lds, dim3(ctx->n / MAC_CO, limbs), dim3(TPB), 0, st, out, babies, pts, ctx->d_modc,
                        ctx->d_fpq, r_i, r_o, limbs, ctx->n, ct_stride, k0, k1, level, ctx->L);
 }
+// ---- masks before the shared rotations of query-times-K --------------------------------------------------
+// A[k] = sum_{c < nk} T[c] * M[(c + k) mod E] for k < shared: T the nk key-ciphertext sums [2][limbs][n] (stacked),
+// M the E slot rotations of the copy mask [E][limbs][n] (multiplier form), A stacked like T.  For one coefficient
+// this is a correlation of the vector over c with the vector over the copies, so a lane that owns KO consecutive
+// outputs k needs ONE new mask word per c: rows (c + k0) .. (c + k0 + KO - 1) slide by one.  A workgroup owns 64
+// coefficients of one limb and stages CIRC_CC ciphertexts at a time in LDS (32 KiB); its four waves take KO outputs
+// each.  Limbs below 2^50 multiply in FP64 (MacFp), the others in 128-bit integer sums reduced every 8 terms.
+#define CIRC_CC 32
+template <int KO>
+__global__ __launch_bounds__(TPB) void k_mask_circulant(u64 *__restrict__ A, const u64 *__restrict__ T, const u64 *__restrict__ M,
+                                                        const ModC *__restrict__ modc, const FpQ *__restrict__ fpq, int nk, int E,
+                                                        int shared, int limbs, int n) {
+    __shared__ u64 sb[CIRC_CC * 2 * MAC_CO];
+    const int l = blockIdx.y, i0 = blockIdx.x * MAC_CO;
+    const int co = threadIdx.x & (MAC_CO - 1), w = threadIdx.x >> 6;
+    const int kb = (blockIdx.z * 4 + w) * KO;
+    const bool active = kb < shared;
+    const ModC m = modc[l];
+    const FpQ fq = fpq[l];
+    const bool fp = fq.q != 0.0;
+    const MacFp F{fq.q, fq.qinv};
+    const size_t cs = (size_t)limbs * n, ctw = 2 * cs, o = (size_t)l * n + i0;
+    double s[KO][2];
+    u64 v[KO][2];
+#pragma unroll
+    for (int t = 0; t < KO; t++) s[t][0] = s[t][1] = 0.0, v[t][0] = v[t][1] = 0;
+    for (int c0 = 0; c0 < nk; c0 += CIRC_CC) {
+        const int cn = nk - c0 < CIRC_CC ? nk - c0 : CIRC_CC;
+        __syncthreads();
+        for (int e = threadIdx.x; e < cn * 2 * MAC_CO; e += TPB) {
+            const int jc = e >> 6, c = e & (MAC_CO - 1);
+            const u64 x = T[(size_t)(c0 + (jc >> 1)) * ctw + (jc & 1) * cs + o + c];
+            sb[e] = fp ? (u64)__double_as_longlong(MacFp::from_u64(x)) : x;
+        }
+        __syncthreads();
+        if (!active) continue;
+        for (int c8 = 0; c8 < cn; c8 += 8) {
+            u64 wv[KO + 7];
+#pragma unroll
+            for (int x = 0; x < KO + 7; x++)
+                wv[x] = M[((size_t)((c0 + c8 + kb + x) & (E - 1)) * limbs + l) * n + i0 + co];     // E is a power of two
+            if (fp) {
+                double wa[KO + 7], waq[KO + 7];
+#pragma unroll
+                for (int x = 0; x < KO + 7; x++) wa[x] = MacFp::from_u64(wv[x]), waq[x] = wa[x] * F.qinv;
+#pragma unroll
+                for (int cc = 0; cc < 8; cc++) {
+                    if (c8 + cc < cn) {
+                        const double y0 = __longlong_as_double((long long)sb[((c8 + cc) * 2 + 0) * MAC_CO + co]);
+                        const double y1 = __longlong_as_double((long long)sb[((c8 + cc) * 2 + 1) * MAC_CO + co]);
+#pragma unroll
+                        for (int t = 0; t < KO; t++) {
+                            s[t][0] += F.mulmod(y0, wa[cc + t], waq[cc + t]);
+                            s[t][1] += F.mulmod(y1, wa[cc + t], waq[cc + t]);
+                        }
+                    }
+                    if ((cc & 3) == 3) {
+#pragma unroll
+                        for (int t = 0; t < KO; t++) s[t][0] = F.norm(s[t][0]), s[t][1] = F.norm(s[t][1]);
+                    }
+                }
+            } else {
+                u128 a[KO][2];
+#pragma unroll
+                for (int t = 0; t < KO; t++) a[t][0] = a[t][1] = 0;
+#pragma unroll
+                for (int cc = 0; cc < 8; cc++) {
+                    if (c8 + cc < cn) {
+                        const u64 y0 = sb[((c8 + cc) * 2 + 0) * MAC_CO + co], y1 = sb[((c8 + cc) * 2 + 1) * MAC_CO + co];
+#pragma unroll
+                        for (int t = 0; t < KO; t++) a[t][0] += (u128)y0 * wv[cc + t], a[t][1] += (u128)y1 * wv[cc + t];
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < KO; t++) {
+                    v[t][0] = addmod(v[t][0], redc(a[t][0], m.q, m.qinv), m.q);
+                    v[t][1] = addmod(v[t][1], redc(a[t][1], m.q, m.qinv), m.q);
+                }
+            }
+        }
+    }
+    if (!active) return;
+#pragma unroll
+    for (int t = 0; t < KO; t++) {
+        if (kb + t < shared) {
+            u64 *dst = A + (size_t)(kb + t) * ctw + o + co;
+            dst[0] = fp ? F.canon(F.mulmod(s[t][0], fq.rinv, fq.rinvq)) : v[t][0];
+            dst[cs] = fp ? F.canon(F.mulmod(s[t][1], fq.rinv, fq.rinvq)) : v[t][1];
+        }
+    }
+}
+void launch_mask_circulant(cm_ctx *ctx, u64 *A, const u64 *T, const u64 *M, int nk, int E, int shared, int limbs, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, (double)nk * shared * 2 * limbs, st);
+    const int ko = shared >= 8 ? 8 : shared >= 4 ? 4 : 2;
+    const dim3 grid(ctx->n / MAC_CO, limbs, (shared + 4 * ko - 1) / (4 * ko)), block(TPB);
+    if (ko == 8)
+        hipLaunchKernelGGL(k_mask_circulant<8>, grid, block, 0, st, A, T, M, ctx->d_modc, ctx->d_fpq, nk, E, shared, limbs, ctx->n);
+    else if (ko == 4)
+        hipLaunchKernelGGL(k_mask_circulant<4>, grid, block, 0, st, A, T, M, ctx->d_modc, ctx->d_fpq, nk, E, shared, limbs, ctx->n);
+    else
+        hipLaunchKernelGGL(k_mask_circulant<2>, grid, block, 0, st, A, T, M, ctx->d_modc, ctx->d_fpq, nk, E, shared, limbs, ctx->n);
+}
+// The same sums through a length-E transform along the copy index: for one coefficient A[k] = sum_c t[c] m[(c + k) mod E]
+// is a cyclic correlation, so with t'[c] = t[(-c) mod E] and F the length-E number-theoretic transform (E divides
+// q - 1), A = F^-1( F(m) . F(t') ): E (log2 E + 1) products per coefficient instead of nk * shared, exact like the direct sum.
+// MODE 0 (set-up): rows M[E][limbs][n] -> Mhat = F(m) / E, kept in the order the forward pass leaves (bit-reversed);
+// MODE 1: T[nk] stacked ciphertexts -> A[shared].  A workgroup owns CO coefficients of one limb and one component and
+// keeps the E x CO words in LDS; the forward pass is decimation in frequency, the inverse one decimation in time, so
+// no reordering is needed.  tw[limbs][2][E/2][2]: omega^e and omega^-e with their companions; einv[limbs]: E^-1 in
+// multiplier form.
+template <int MODE>
+__global__ __launch_bounds__(TPB) void k_mask_ntt(u64 *__restrict__ out, const u64 *__restrict__ in, const u64 *__restrict__ Mhat,
+                                                  const u64 *__restrict__ tw, const u64 *__restrict__ einv,
+                                                  const ModC *__restrict__ modc, int nk, int E, int logE, int shared, int limbs,
+                                                  int n, int logCO) {
+    extern __shared__ u64 X[];
+    const int CO = 1 << logCO, l = blockIdx.y, comp = blockIdx.z, i0 = blockIdx.x * CO;
+    const ModC m = modc[l];
+    const u64 q = m.q;
+    const size_t cs = (size_t)limbs * n, ctw = 2 * cs, o = (size_t)l * n + i0;
+    for (int e = threadIdx.x; e < E * CO; e += TPB) {
+        const int c = e >> logCO, co = e & (CO - 1);
+        if (MODE == 1) X[(((E - c) & (E - 1)) << logCO) + co] = c < nk ? in[(size_t)c * ctw + comp * cs + o + co] : 0;
+        else X[e] = in[(size_t)c * cs + o + co];
+    }
+    __syncthreads();
+    const u64 *twf = tw + (size_t)l * 2 * E, *twi = twf + E;
+    for (int lg = logE - 1; lg >= 0; lg--) {                       // half-length 2^lg, twiddle step 2^(logE - 1 - lg)
+        const int len = 1 << lg, sh = logE - 1 - lg;
+        for (int id = threadIdx.x; id < (E / 2) * CO; id += TPB) {
+            const int bf = id >> logCO, co = id & (CO - 1), j = bf & (len - 1);
+            const int a = ((((bf >> lg) << (lg + 1)) + j) << logCO) + co, b = a + (len << logCO);
+            const u64 u = X[a], v = X[b];
+            X[a] = addmod(u, v, q);
+            const int e = j << sh;
+            X[b] = mul_shoup(submod(u, v, q), twf[2 * e], twf[2 * e + 1], q);
+        }
+        __syncthreads();
+    }
+    if (MODE == 0) {
+        const u64 s = einv[l];
+        for (int e = threadIdx.x; e < E * CO; e += TPB)
+            out[(size_t)(e >> logCO) * cs + o + (e & (CO - 1))] = redc((u128)X[e] * s, q, m.qinv);
+        return;
+    }
+    for (int e = threadIdx.x; e < E * CO; e += TPB)
+        X[e] = redc((u128)X[e] * Mhat[(size_t)(e >> logCO) * cs + o + (e & (CO - 1))], q, m.qinv);
+    __syncthreads();
+    for (int lg = 0; lg < logE; lg++) {
+        const int len = 1 << lg, sh = logE - 1 - lg;
+        for (int id = threadIdx.x; id < (E / 2) * CO; id += TPB) {
+            const int bf = id >> logCO, co = id & (CO - 1), j = bf & (len - 1);
+            const int a = ((((bf >> lg) << (lg + 1)) + j) << logCO) + co, b = a + (len << logCO);
+            const int e = j << sh;
+            const u64 u = X[a], v = mul_shoup(X[b], twi[2 * e], twi[2 * e + 1], q);
+            X[a] = addmod(u, v, q);
+            X[b] = submod(u, v, q);
+        }
+        __syncthreads();
+    }
+    for (int e = threadIdx.x; e < shared * CO; e += TPB)
+        out[(size_t)(e >> logCO) * ctw + comp * cs + o + (e & (CO - 1))] = X[e];
+}
+// CO = min(64, 4096 / E) coefficients per workgroup (32 KiB of LDS at most); 8 <= E <= 512
+static int mask_ntt_log_co(int E) {
+    int lg = 6;
+    while ((E << lg) > 4096) lg--;
+    return lg;
+}
+bool mask_ntt_supported(int E) { return E >= 8 && E <= 512 && (E & (E - 1)) == 0; }
+void launch_mask_ntt_setup(cm_ctx *ctx, u64 *Mhat, const u64 *M, const u64 *tw, const u64 *einv, int E, int limbs, hipStream_t st) {
+    int logE = 0;
+    while ((1 << logE) < E) logE++;
+    const int lg = mask_ntt_log_co(E);
+    hipLaunchKernelGGL(k_mask_ntt<0>, dim3(ctx->n >> lg, limbs, 1), dim3(TPB), ((size_t)E << lg) * 8, st, Mhat, M, nullptr, tw, einv,
+                       ctx->d_modc, E, E, logE, E, limbs, ctx->n, lg);
+}
+void launch_mask_ntt(cm_ctx *ctx, u64 *A, const u64 *T, const u64 *Mhat, const u64 *tw, const u64 *einv, int nk, int E, int shared,
+                     int limbs, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, (double)E * 2 * limbs, st);
+    int logE = 0;
+    while ((1 << logE) < E) logE++;
+    const int lg = mask_ntt_log_co(E);
+    hipLaunchKernelGGL(k_mask_ntt<1>, dim3(ctx->n >> lg, limbs, 2), dim3(TPB), ((size_t)E << lg) * 8, st, A, T, Mhat, tw, einv,
+                       ctx->d_modc, nk, E, logE, shared, limbs, ctx->n, lg);
+}
 // plaintext (j,k) between its plain form src[limbs][n] and its place in the blocked array
 __global__ void k_pt_block(u64 *blocked, u64 *plain, int n, int r_i, int r_o, int j, int k, int to_blocked) {
     const int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;

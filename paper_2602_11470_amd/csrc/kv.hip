@@ -39,6 +39,11 @@ struct cm_kv {
     // the residues in runs; tables for raising the second components of up to CM_KS_BATCH inner sums at once
     std::vector<std::vector<long long>> res_groups;
     KsManyTables giant_tabs;
+    // query-times-K with the copy mask applied before the last `shared` terms of the sum over the dims: the sums of
+    // the key ciphertexts (d_T), their masked combinations A_k (d_A) and the E slot rotations of the mask (d_M)
+    // d_Mhat: the transform of d_M along the copy index (the masked sums as a cyclic correlation), with its twiddles
+    int shared = 1;
+    u64 *d_T = nullptr, *d_A = nullptr, *d_M = nullptr, *d_Mhat = nullptr, *d_tw = nullptr, *d_einv = nullptr;
 };
 
 // ceil(L/3) runs of as equal length as possible, the longer ones first; a run lists its non-empty subset sums
@@ -163,11 +168,41 @@ extern "C" void cm_kv_destroy(cm_kv *kv) {
     if (!kv) return;
     hipFree(kv->d_k), hipFree(kv->d_v), hipFree(kv->d_mask_qk), hipFree(kv->d_mask_k), hipFree(kv->d_mask_v);
     hipFree(kv->d_mask_kg), hipFree(kv->d_mask_vg);
+    hipFree(kv->d_T), hipFree(kv->d_A), hipFree(kv->d_M), hipFree(kv->d_Mhat), hipFree(kv->d_tw), hipFree(kv->d_einv);
     hipFree(kv->d_work);
     ks_many_tables_destroy(&kv->relin_tabs);
     ks_many_tables_destroy(&kv->rot_tabs);
     ks_many_tables_destroy(&kv->giant_tabs);
     delete kv;
+}
+static u64 rot_g(const cm_kv *kv, long long step);
+// d_M[b] = the copy mask of copy b: the base mask rotated right by b copies (a Galois permutation of its rows)
+static cm_status build_mask_rows(cm_kv *kv) {
+    cm_ctx *ctx = kv->ctx;
+    const size_t row = (size_t)kv->level * ctx->n;
+    for (int b = 0; b < kv->E; b++) {
+        if (b == 0) HIPCHK(hipMemcpy(kv->d_M, kv->d_mask_qk, row * 8, hipMemcpyDeviceToDevice));
+        else launch_automorphism(ctx, kv->d_M + b * row, kv->d_mask_qk, kv->level, rot_g(kv, -(long long)b * kv->H * kv->t), 0);
+    }
+    if (kv->d_Mhat) {
+        const int E = kv->E, lv = kv->level;
+        std::vector<u64> tw((size_t)lv * 2 * E), einv(lv);
+        for (int l = 0; l < lv; l++) {
+            const u64 q = ctx->mod[l], w = h_powmod(ctx->psi[l], (u64)(2 * ctx->n / E), q), wi = h_invmod(w, q);
+            u64 a = 1, b = 1;
+            for (int e = 0; e < E / 2; e++) {
+                u64 *f = &tw[((size_t)l * 2 + 0) * E + 2 * e], *g = &tw[((size_t)l * 2 + 1) * E + 2 * e];
+                f[0] = a, f[1] = h_shoup(a, q), g[0] = b, g[1] = h_shoup(b, q);
+                a = h_mulmod(a, w, q), b = h_mulmod(b, wi, q);
+            }
+            einv[l] = h_mulmod(h_invmod((u64)E % q, q), (u64)(((u128)1 << 64) % q), q);
+        }
+        HIPCHK(hipMemcpy(kv->d_tw, tw.data(), tw.size() * 8, hipMemcpyHostToDevice));
+        HIPCHK(hipMemcpy(kv->d_einv, einv.data(), einv.size() * 8, hipMemcpyHostToDevice));
+        launch_mask_ntt_setup(ctx, kv->d_Mhat, kv->d_M, kv->d_tw, kv->d_einv, E, lv, 0);
+    }
+    HIPCHK(hipDeviceSynchronize());
+    return CM_OK;
 }
 // Parity hook: replace a base mask by given integer coefficients (kind 0: query-times-K mask at
 // level-1; 1: residue mask at level+1; 2: value mask at level+1; 3 and 4: the all-ones and value
@@ -177,7 +212,42 @@ extern "C" cm_status cm_kv_set_mask(cm_kv *kv, int32_t kind, const int64_t *coef
     if (kind > 0 && kv->level + 1 > kv->ctx->L) return CM_E_LEVEL;
     u64 *dst = kind == 0 ? kv->d_mask_qk : kind == 1 ? kv->d_mask_k : kind == 2 ? kv->d_mask_v
              : kind == 3 ? kv->d_mask_kg : kv->d_mask_vg;
-    return encode_mask(kv, kind, dst, kind == 0 ? kv->level - 1 : kv->level + 1, coeffs);
+    CMCHK(encode_mask(kv, kind, dst, kind == 0 ? kv->level - 1 : kv->level + 1, coeffs));
+    return kind == 0 && kv->d_M ? build_mask_rows(kv) : CM_OK;
+}
+// How many terms of the sum over the dims of query-times-K are taken AFTER the copy mask, by rotations shared by all
+// key ciphertexts (1 = none).  Rebuilds the runs of the per-ciphertext part and allocates the buffers of the shared part.
+extern "C" cm_status cm_kv_set_shared_dims(cm_kv *kv, int32_t shared) {
+    if (!kv || !kv->unrolled) return CM_E_INVAL;
+    if (!pow2(shared) || shared > kv->E) return CM_E_LAYOUT;
+    cm_ctx *ctx = kv->ctx;
+    std::vector<long long> ladder;
+    for (int i = 0; i < ilog2(kv->E / shared); i++) ladder.push_back((long long)(shared << i) * kv->H * kv->t);
+    auto release = [&]() {
+        hipFree(kv->d_T), hipFree(kv->d_A), hipFree(kv->d_M), hipFree(kv->d_Mhat), hipFree(kv->d_tw), hipFree(kv->d_einv);
+        kv->d_T = kv->d_A = kv->d_M = kv->d_Mhat = kv->d_tw = kv->d_einv = nullptr;
+    };
+    release();
+    kv->shared = 1;
+    if (shared > 1) {
+        const size_t n = ctx->n, ctw1 = 2 * (size_t)kv->level * n;
+        const bool ntt = mask_ntt_supported(kv->E);
+        if (hipMalloc((void **)&kv->d_T, (size_t)kv->nk_max * ctw1 * 8) != hipSuccess ||
+            hipMalloc((void **)&kv->d_A, (size_t)shared * ctw1 * 8) != hipSuccess ||
+            hipMalloc((void **)&kv->d_M, (size_t)kv->E * kv->level * n * 8) != hipSuccess ||
+            (ntt && (hipMalloc((void **)&kv->d_Mhat, (size_t)kv->E * kv->level * n * 8) != hipSuccess ||
+                     hipMalloc((void **)&kv->d_tw, (size_t)kv->level * 2 * kv->E * 8) != hipSuccess ||
+                     hipMalloc((void **)&kv->d_einv, (size_t)kv->level * 8) != hipSuccess))) {
+            release();
+            std::vector<long long> full;
+            for (int i = 0; i < ilog2(kv->E); i++) full.push_back((long long)(1 << i) * kv->H * kv->t);
+            kv->dim_groups = ladder_groups(full);
+            return CM_E_NOMEM;
+        }
+    }
+    kv->shared = shared;
+    kv->dim_groups = ladder_groups(ladder);
+    return shared > 1 ? build_mask_rows(kv) : CM_OK;
 }
 
 static std::vector<int> kv_all_steps(const cm_kv *kv) {
@@ -186,6 +256,7 @@ static std::vector<int> kv_all_steps(const cm_kv *kv) {
     if (kv->unrolled) {
         for (const auto &grp : kv->dim_groups)
             for (long long a : grp) s.push_back((int)a);                                       // sum over dims, run by run
+        for (int k = 1; k < kv->shared; k++) s.push_back(k * kv->H * kv->t);                   // ... and its shared part
     } else {
         for (int i = 0; i < ilog2(kv->E); i++) s.push_back((1 << i) * kv->H * kv->t);      // sum over dims
     }
@@ -321,6 +392,7 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     if (kv->unrolled) {
         for (const auto &grp : kv->dim_groups)
             for (long long a : grp) if (!find_key(evk, rot_g(kv, a))) return CM_E_NOKEY;
+        for (int k = 1; k < kv->shared; k++) if (!find_key(evk, rot_g(kv, (long long)k * kv->H * kv->t))) return CM_E_NOKEY;
     } else {
         for (int i = 0; i < ilog2(kv->E); i++) if (!find_key(evk, rot_g(kv, (long long)(1 << i) * kv->H * kv->t))) return CM_E_NOKEY;
     }
@@ -359,10 +431,11 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
         }
         launch_inner_product_shared_key(ctx, ip, kl.beta, lv, st);
         CMCHK(moddown_batch_into(ctx, bu, lv, m, adds, 2, 0, nullptr, outs, st));
-        CMCHK(rescale_into(ctx, PB, 2 * m, lv, RB0, st, last, red));       // stacked: [m][2][lv+1] -> [m][2][lv]
-        u64 *r0 = RB0, *r1 = RB1;
+        // with shared rotations the sums of the key ciphertexts are kept (d_T) until all of them are there
+        u64 *r0 = kv->shared > 1 ? kv->d_T + (size_t)c0 * ctw1 : RB0, *r1 = RB1;
+        CMCHK(rescale_into(ctx, PB, 2 * m, lv, r0, st, last, red));        // stacked: [m][2][lv+1] -> [m][2][lv]
         const size_t ublk1 = 2 * (size_t)kl1.ext * n, dblk1 = (size_t)kl1.beta * kl1.ext * n;
-        if (kv->unrolled) {
+        if (kv->unrolled && !kv->dim_groups.empty()) {
             // sum over the E dims in the extended basis: R = (P c0, P c1); every run adds the hoisted rotations of R by
             // its subset sums (one raise of ModDown(R1) per run, one launch per rotation amount over all m ciphertexts,
             // the key read once per launch); one ModDown of both components at the end
@@ -413,12 +486,40 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
             CMCHK(moddown_batch_into(ctx, bu, lv - 1, m, adds, 1, g, accs, outs, st));
             std::swap(r0, r1);
         }
-        {
+        if (kv->shared == 1) {
             // keep copy e = c of every key ciphertext's sums: base mask rotated right by c*H*t; one launch
             MulPtBatch mb;
             for (int r = 0; r < m; r++) mb.src[r] = nullptr, mb.g[r] = (unsigned)rot_g(kv, -(long long)((c0 + r) % kv->E) * kv->H * kv->t);
             launch_mac_pt_rot_batch(ctx, acc, r0, mb, m, kv->d_mask_qk, lv, c0 > 0, st);
         }
+    }
+    if (kv->shared > 1) {
+        // A_k = sum_c mask_{c+k} T_c; scores = ModDown( P A_0 + sum_{k >= 1} RotRaised(A_k, k H t) ): shared - 1 rotations
+        // for the whole cache, CM_KS_BATCH of them raised and summed per launch
+        // directly (nk * shared products per coefficient) or, when that is more than the transform's E (log2 E + 1) by a
+        // wide margin, as a cyclic correlation along the copy index
+        if (kv->d_Mhat && (long long)nk * kv->shared >= 16LL * kv->E)
+            launch_mask_ntt(ctx, kv->d_A, kv->d_T, kv->d_Mhat, kv->d_tw, kv->d_einv, nk, kv->E, kv->shared, lv, st);
+        else
+            launch_mask_circulant(ctx, kv->d_A, kv->d_T, kv->d_M, nk, kv->E, kv->shared, lv, st);
+        const size_t dblk1 = (size_t)kl1.beta * kl1.ext * n;
+        u64 *cur = XA, *nxt = XB;
+        launch_raise_by_P(ctx, cur, kv->d_A, lv - 1, st, 1);
+        for (int k0 = 1; k0 < kv->shared; k0 += CM_KS_BATCH) {
+            const int m = kv->shared - k0 < CM_KS_BATCH ? kv->shared - k0 : CM_KS_BATCH;
+            CMCHK(ks_raise_many(ctx, kv->rot_tabs, kv->d_A + (size_t)k0 * ctw1, ksin, digits, st, m, 0));
+            IpBatch b;
+            b.nz = 1, b.nsum = m;
+            for (int r = 0; r < m; r++) {
+                const u64 gal = rot_g(kv, (long long)(k0 + r) * kv->H * kv->t);
+                b.it[r].dig = digits + r * dblk1, b.it[r].key = find_key(evk, gal), b.it[r].g = (unsigned)gal;
+                b.it[r].c0 = kv->d_A + (size_t)(k0 + r) * ctw1, b.it[r].c0_ext = 0;
+            }
+            b.out[0] = nxt, b.extra[0] = cur;
+            launch_inner_product_batch(ctx, b, kl1.beta, lv - 1, st);
+            std::swap(cur, nxt);
+        }
+        CMCHK(moddown_into(ctx, cur, lv - 1, nullptr, 0, 0, acc, nullptr, st));
     }
     CMCHK(rescale_into(ctx, acc, 2, lv - 1, out->dev, st));
     out->level = lv - 2, out->ncomp = 2;

@@ -607,3 +607,99 @@ def test_kv_sv_with_unrolled_giant_steps_and_ladder_matches_oracle_and_float64(e
     _same(e, oa, ga)
     assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
     assert np.array_equal(gctx.ct_export(gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)), gctx.ct_export(ga))
+
+
+@pytest.mark.parametrize("ring,H,E,nk,shared", [
+    ("config1", 16, 16, 3, 16),      # every rotation shared: no per-ciphertext ladder
+    ("config1", 16, 16, 3, 4),       # two ladder steps per key ciphertext, three shared rotations
+    ("config1", 4, 64, 10, 64),      # 63 shared rotations raised in eight batches; two batches of key ciphertexts
+    ("config1", 4, 64, 10, 2),
+    ("config1", 2, 128, 40, 128),    # enough products for the transform along the copy index (nk * shared >= 16 E)
+    ("config1", 2, 128, 40, 64),     # ... with one ladder step left per key ciphertext
+    ("config1", 4, 64, 20, 64),
+    ("config1", 2, 128, 40, 16),     # more key ciphertexts than one LDS stage of the direct sums (32 + 8)
+    ("wide", 4, 16, 5, 16),          # 54-bit primes: the integer form of the direct sums
+    ("wide", 4, 16, 5, 2),
+    ("wide", 2, 32, 20, 32),         # 54-bit primes through the transform
+])
+def test_kv_qk_with_shared_dim_rotations_matches_oracle_and_float64(env, ring, H, E, nk, shared):
+    """q K^T with the copy mask applied before the last `shared` terms of the sum over the dims
+    (cm_kv_set_shared_dims): limbs against the oracle's form of it, scores against float64, and the same
+    message as the printed order."""
+    from oracle import ckks, packing, params, vmm
+    from oracle.ckks import Pt
+    from paper_2602_11470_amd import inputs
+    if ring == "wide":
+        prm = params.toy(n=4096, q0_bits=58, qi_bits=54, scale_bits=54, name="wide")
+        B = env["B"]
+        gctx = B.Context(4096, 5, 1, 1, 58, 54, 60, 2.0 ** 54)
+        octx = ckks.Context(prm)
+        e = dict(B=B, octx=octx, gctx=gctx, osk=octx.keygen_secret(1), gsk=gctx.keygen_secret(1), prm=prm)
+        assert [int(x) for x in gctx.moduli()] == [int(x) for x in octx.mod]
+    else:
+        e = env
+    try:
+        B, octx, gctx = e["B"], e["octx"], e["gctx"]
+        L = octx.prm.L
+        lay = packing.KvLayout(octx.S, H, E)
+        ntok = nk * lay.t - 2
+        q, K, V, s = inputs.attention_inputs(19, H, max(1, H // 4), E, ntok)
+        q = q * 0.3
+        lv = L - 1
+        kv = gctx.kv_create(H, E, lv, unrolled_ladders=True, shared_dims=shared)
+        steps = vmm.qk_shared_steps(lay, shared)
+        assert set(steps) <= set(kv.steps())
+        okeys = octx.keygen_rotations(e["osk"], steps, 2, with_relin=True)
+        gkeys = gctx.keygen_rotations(e["gsk"], steps, 2, with_relin=True)
+        m0 = np.zeros(octx.S)
+        m0[:H * lay.t] = 1
+        base = octx.encode_coeffs(m0, float(octx.mod[lv - 1]))
+        kv.set_mask(0, base)
+
+        def omask(c):
+            idx = octx.q_idx(lv - 1)
+            coeff = octx.automorphism_coeff(octx.from_i64(base, idx), idx, octx.galois(-(c % E) * H * lay.t))
+            return Pt(octx.ntt(coeff, idx), lv - 1, float(octx.mod[lv - 1]))
+
+        okc = []
+        for c in range(nk):
+            ok, gk = _enc_both(e, lay.pack_k(K, c), lv, 100 + c)
+            okc.append(ok)
+            kv.load(B.CM_QK, c, gk)
+        kv.set_tokens(ntok)
+        oq, gq = _enc_both(e, lay.pack_vec(q), lv, 10)
+        masks = [omask(b) for b in range(E)]
+        om = vmm.qk_scores_shared(octx, okeys, lay, oq, okc, masks, shared)
+        gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, gq)
+        _same(e, om, gm)
+        got = lay.unpack_scores(gctx.decrypt(e["gsk"], gm).real, ntok)
+        assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
+        # twice in a row on the same buffers
+        assert np.array_equal(gctx.ct_export(gctx.vmm_kv(gkeys, kv, B.CM_QK, gq)), gctx.ct_export(gm))
+        # back to the printed order on the same cache: the same scores
+        kv.set_shared_dims(1)
+        k1 = gctx.keygen_rotations(e["gsk"], kv.steps(), 2, with_relin=True)
+        ref = gctx.decrypt(e["gsk"], gctx.vmm_kv(k1, kv, B.CM_QK, gq)).real
+        assert np.abs(gctx.decrypt(e["gsk"], gm).real - ref).max() < 1e-6
+    finally:
+        if ring == "wide":
+            e["gctx"].close()
+
+
+def test_kv_shared_dims_rejects_other_caches_and_sizes(env):
+    B, gctx = env["B"], env["gctx"]
+    L = env["octx"].prm.L
+    plain = gctx.kv_create(16, 16, L - 1)
+    with pytest.raises(B.CachemirError) as ei:
+        plain.set_shared_dims(4)
+    assert ei.value.status == -1          # CM_E_INVAL: not an unrolled cache
+    kv = gctx.kv_create(16, 16, L - 1, unrolled_ladders=True)
+    for bad in (3, 32, 0):
+        with pytest.raises(B.CachemirError) as ei:
+            kv.set_shared_dims(bad)
+        assert ei.value.status == -5      # CM_E_LAYOUT
+    n0 = len(kv.steps())
+    kv.set_shared_dims(16)
+    assert {k * 16 * 8 for k in range(1, 16)} <= set(kv.steps())
+    kv.set_shared_dims(1)
+    assert len(kv.steps()) == n0

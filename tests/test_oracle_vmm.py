@@ -589,3 +589,52 @@ def test_group_scores_times_v_on_ciphertexts_in_both_forms():
         want = sum(s[:, c * lay.t + tau][:, None] * V[c * lay.t + tau] for c in range(ntok // lay.t))
         assert np.abs(lay.unpack_vec(da, tau) - want).max() < TOL
         assert np.abs(lay.unpack_vec(db, tau) - want).max() < TOL
+
+
+@pytest.mark.parametrize("shared", [1, 2, 8])
+def test_mask_before_the_shared_rotations_gives_the_same_scores_on_slots(shared):
+    """The mask moved inside the last `shared` terms of the sum over the dims: identical slot vector
+    (not only the kept copy), shared - 1 rotations for the whole cache plus log2(E / shared) per key
+    ciphertext."""
+    lay = packing.KvLayout(256, 4, 8)                   # t = 8, E = 8
+    nk = 5
+    ntok = nk * lay.t - 3
+    q, K, V, s = inputs.attention_inputs(9, 4, 2, 8, ntok)
+    kc = [lay.pack_k(K, c) for c in range(nk)]
+    ops, ops2 = vmm.SlotOps(), vmm.SlotOps()
+    ref = vmm.qk_scores(ops, lay, lay.pack_vec(q), kc, [lay.qk_mask(c) for c in range(nk)])
+    got = vmm.qk_scores_shared_ops(ops2, lay, lay.pack_vec(q), kc, [lay.qk_mask(b) for b in range(lay.E)], shared)
+    assert np.abs(got - ref).max() < 1e-12
+    assert np.abs(lay.unpack_scores(got, ntok) - np.einsum("he,nhe->hn", q, K)).max() < 1e-12
+    log2 = lambda x: x.bit_length() - 1
+    assert ops2.rotations == 3 + nk * log2(lay.E // shared) + shared - 1
+    assert ops2.pt_mults == nk * shared
+    assert len(vmm.qk_shared_steps(lay, shared)) >= 3 + shared - 1
+
+
+@pytest.mark.parametrize("shared", [2, 8])
+def test_shared_dim_rotations_on_ciphertexts_decrypt_to_q_times_K_transposed(shared):
+    prm = params.toy(n=512, n_qi=4, n_p=1, alpha=1)
+    ctx = ckks.Context(prm)
+    L = prm.L
+    sk = ctx.keygen_secret(1)
+    lay = packing.KvLayout(ctx.S, 4, 8)                 # t = 8
+    ntok = 3 * lay.t - 2
+    q, K, V, s = inputs.attention_inputs(4, 4, 2, 8, ntok)
+    steps = vmm.qk_shared_steps(lay, shared)
+    keys = ctx.keygen_rotations(sk, sorted(set(steps) | set(lay.qk_steps())), 2, with_relin=True)
+    enc = lambda v, lv, seed: ctx.level_drop(ctx.encrypt(sk, ctx.encode(v, L), seed), lv)
+    kc = [enc(lay.pack_k(K, c), L - 1, 100 + c) for c in range(3)]
+    cq = enc(lay.pack_vec(q), L - 1, 10)
+    masks = [ctx.encode(lay.qk_mask(b), L - 2) for b in range(lay.E)]
+    r0 = ctx.rot_count
+    m = vmm.qk_scores_shared(ctx, keys, lay, cq, kc, masks, shared)
+    assert ctx.rot_count - r0 == len(steps) + 2 * (len(steps) - 3 - (shared - 1))    # the per-ciphertext part three times
+    assert m.level == L - 3
+    got = lay.unpack_scores(ctx.decrypt(sk, m).real, ntok)
+    assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
+    ladder = vmm.qk_scores(vmm.CkksOps(ctx, keys), lay, cq, kc, masks[:3])
+    assert abs(m.scale / ladder.scale - 1) < 1e-12
+    assert np.abs(ctx.decrypt(sk, m) - ctx.decrypt(sk, ladder)).max() < 1e-6
+    generic = vmm.qk_scores_shared_ops(vmm.CkksOps(ctx, keys), lay, cq, kc, masks, shared)
+    assert np.abs(ctx.decrypt(sk, m) - ctx.decrypt(sk, generic)).max() < 1e-6
