@@ -206,16 +206,17 @@ def cpu_baseline(raised_sums=True):
 def attention_workload(a):
     """Config 3 (not the default line): one query against an encrypted cache of 1024 tokens, 32 heads
     x 128 dims on the config-2 ring; cache ciphertexts one level below the top.  q K^T = 3 + 128 x
-    (relinearisation + 7 rotations) key switches (--ladders), or by default the 7 rotations unrolled
-    into 13 hoisted ones that share 3 ModUps and one ModDown; scores V = 15 hoisted + 7 giant + 3 rotations and
-    8 relinearisations.  Cache contents are random slot vectors (timing does not depend on values;
+    (relinearisation + 7 rotations) key switches (--ladders); with --shared-dims 1 the 7 rotations unrolled
+    into 13 hoisted ones that share 3 ModUps and one ModDown; by default (--shared-dims 128) the copy mask
+    applied first, 128 relinearisations and 127 rotations for the whole cache; scores V = 15 hoisted + 7 giant
+    + 3 rotations and 8 relinearisations.  Cache contents are random slot vectors (timing does not depend on values;
     parity of this path is in tests/)."""
     import torch
     from paper_2602_11470_amd import binding as B
     ctx = B.llama_ring(24, 4)
     H, E, L = 32, 128, ctx.L
     lv = a.cache_level if a.cache_level > 0 else L - 1
-    kv = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=not a.ladders, shared_dims=1 if a.ladders else a.shared_dims)
+    kv = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=not a.ladders, shared_dims=1 if a.ladders else (a.shared_dims or 128))
     sk = ctx.keygen_secret(1)
     keys = ctx.keygen_rotations(sk, kv.steps(), 2, with_relin=True)
     rng = np.random.default_rng(3)
@@ -248,7 +249,7 @@ def attention_workload(a):
         res[name] = (time.perf_counter() - t0) / reps
     # per key ciphertext: one relinearisation and the sum over the 128 dims, as 7 dependent rotations or,
     # unrolled (runs of 3 + 2 + 2 ladder steps), 13 hoisted ones on 3 ModUps
-    sh = 1 if a.ladders else a.shared_dims
+    sh = 1 if a.ladders else (a.shared_dims or 128)
     per_ct = {1: 13, 2: 14, 4: 10, 8: 6, 16: 7, 32: 3, 64: 1, 128: 0}[sh]    # hoisted rotations of the runs of the ladder left per key ciphertext
     ks_qk = 3 + 128 * (8 if a.ladders else 1 + per_ct) + sh - 1
     print(json.dumps({
@@ -388,7 +389,7 @@ def prefill_workload(a):
     # delta: q K^T without replication, scores V without the sum over the residues; a group takes t of each plus
     # 2 (t - 1) inner rotations
     tk = ctx.S // (H * E)
-    kva = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=True)
+    kva = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=True, shared_dims=a.shared_dims or 16)
     akeys = ctx.keygen_rotations(sk, [s_ for s_ in kva.steps() if s_ % tk == 0], 2, with_relin=True)
     encl = lambda seed: ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), ctx.L), seed), lv)
     for c in range(128):
@@ -403,7 +404,8 @@ def prefill_workload(a):
                       "data": "synthetic", "dtype": "u64", "token_batched_4096x4096": rows,
                       "rope_group_ms": rope_ms, "inner_rotation_ms": inner_ms, "append_group_ms": append_ms,
                       "append_group_ms_per_token": append_ms / tk,
-                      "group_attention_prompt_128": {"cache_level": lv, "qk_group_ms_per_delta": qk_ms,
+                      "group_attention_prompt_128": {"cache_level": lv, "shared_dims": a.shared_dims or 16,
+                                                     "qk_group_ms_per_delta": qk_ms,
                                                      "sv_group_ms_per_delta": sv_ms,
                                                      "ms_per_group": tk * (qk_ms + sv_ms) + 2 * (tk - 1) * inner_ms}}))
 
@@ -414,8 +416,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--shared-dims", type=int, default=1,
-                    help="attention workload: terms of the sum over the dims taken after the copy mask by shared rotations")
+    ap.add_argument("--shared-dims", type=int, default=0,
+                    help="attention / prefill workloads: terms of the sum over the dims of q K^T taken after the copy mask, by "
+                         "rotations shared by all key ciphertexts (1 = the printed order; default 128 for the 128 key "
+                         "ciphertexts of the attention workload, 16 for the 16 of the prefill workload)")
     ap.add_argument("--ladders", action="store_true",
                     help="preprocess and reduce as the rotate-and-add ladders of Algorithm 1 (3 + 3 dependent rotations)")
     ap.add_argument("--nested-giants", action="store_true",

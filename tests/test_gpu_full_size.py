@@ -199,12 +199,13 @@ def test_config4_mlp_projection_shapes_decrypt_to_float64_product(ring2, d_in, d
     assert np.abs(out - x @ W).max() < TOL
 
 
-@pytest.mark.parametrize("unrolled", [False, True])
-def test_config3_attention_shapes_decrypt_to_float64_products(ring2, unrolled):
+@pytest.mark.parametrize("unrolled,shared", [(False, 1), (True, 1), (True, 128), (True, 16)])
+def test_config3_attention_shapes_decrypt_to_float64_products(ring2, unrolled, shared):
     """Llama-3-8B attention shapes on the full ring: 32 heads x 128 dims (8 KV heads repeated 4x),
     t = 8 tokens per K ciphertext, 128 V ciphertexts with 16 baby x 8 giant steps.  A short
     context (two loaded K ciphertexts plus three appended tokens) keeps the run small; every
-    ciphertext and rotation has its full size."""
+    ciphertext and rotation has its full size.  shared > 1: the copy mask before the last `shared`
+    terms of the sum over the dims (127 or 15 rotations for the whole cache)."""
     from oracle import packing
     from paper_2602_11470_amd import inputs
     B, octx, gctx, prm = ring2
@@ -215,7 +216,7 @@ def test_config3_attention_shapes_decrypt_to_float64_products(ring2, unrolled):
     ntok = n_loaded + n_app
     q, K, V, s = inputs.attention_inputs(3, H, 8, E, ntok)
     lv = L - 1
-    kv = gctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=unrolled)
+    kv = gctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=unrolled, shared_dims=shared)
     gsk = gctx.keygen_secret(1)
     gkeys = gctx.keygen_rotations(gsk, kv.steps(), 2, with_relin=True)
     enc = lambda slots, level, seed: gctx.level_drop(gctx.encrypt(gsk, gctx.encode(slots, L), seed), level)

@@ -212,8 +212,8 @@ def test_group_append_then_single_tokens_then_attention(env, r_i):
     assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
 
 
-@pytest.mark.parametrize("unrolled", [False, True])
-def test_inner_rotation_and_group_scores_match_oracle_and_all_query_key_pairs(env, unrolled):
+@pytest.mark.parametrize("unrolled,shared", [(False, 1), (True, 1), (True, 4)])
+def test_inner_rotation_and_group_scores_match_oracle_and_all_query_key_pairs(env, unrolled, shared):
     """Prompt-phase Q K^T (Sec. 5.4): a group of t queries, inner rotations by delta, then the
     un-replicated q K^T; limbs against the oracle, and every score against the float64 product of
     the query at residue (tau' - delta) mod t with key token c t + tau'."""
@@ -228,8 +228,8 @@ def test_inner_rotation_and_group_scores_match_oracle_and_all_query_key_pairs(en
     Q = rng.normal(size=(lay.t, H, E)) * 0.3
     K = rng.normal(size=(nk * lay.t, H, E))
     lv = L - 2                                           # cache level; the query group arrives one level higher
-    kv = gctx.kv_create(H, E, lv, unrolled_ladders=unrolled)
-    dim_steps = vmm.qk_unrolled_steps(lay)[3:] if unrolled else lay.qk_steps()[3:]
+    kv = gctx.kv_create(H, E, lv, unrolled_ladders=unrolled, shared_dims=shared)
+    dim_steps = vmm.qk_shared_steps(lay, shared)[3:] if unrolled else lay.qk_steps()[3:]
     deltas = (1, 5)
     steps = sorted(set(dim_steps) | {s for d in deltas for s in lay.inner_rotation_steps(d)})
     okeys = octx.keygen_rotations(e["osk"], steps, 2, with_relin=True)
@@ -262,8 +262,10 @@ def test_inner_rotation_and_group_scores_match_oracle_and_all_query_key_pairs(en
         ox = vmm.inner_rotate(vmm.CkksOps(octx, okeys, pt_scale=ql), lay, oq, delta, opts)
         gx = gctx.rope_apply(gkeys, rot, gq)
         _same(e, ox, gx)
-        masks = [omask(c) for c in range(nk)]
-        if unrolled:
+        masks = [omask(c) for c in range(E if shared > 1 else nk)]
+        if shared > 1:
+            om = vmm.qk_scores_shared(octx, okeys, lay, ox, okc, masks, shared, replicate=False)
+        elif unrolled:
             om = vmm.qk_scores_unrolled(octx, okeys, lay, ox, okc, masks, replicate=False)
         else:
             om = vmm.qk_scores(vmm.CkksOps(octx, okeys), lay, ox, okc, masks, replicate=False)
