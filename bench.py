@@ -216,7 +216,8 @@ def attention_workload(a):
     ctx = B.llama_ring(24, 4)
     H, E, L = 32, 128, ctx.L
     lv = a.cache_level if a.cache_level > 0 else L - 1
-    kv = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=not a.ladders, shared_dims=1 if a.ladders else (a.shared_dims or 128))
+    kv = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=not a.ladders, key_index=a.key_index,
+                       shared_dims=1 if a.ladders or a.key_index else (a.shared_dims or 128))
     sk = ctx.keygen_secret(1)
     keys = ctx.keygen_rotations(sk, kv.steps(), 2, with_relin=True)
     rng = np.random.default_rng(3)
@@ -224,6 +225,8 @@ def attention_workload(a):
     for c in range(128):
         kv.load(B.CM_QK, c, enc(100 + c))
         kv.load(B.CM_SV, c, enc(300 + c))
+        if a.key_index:
+            kv.load(B.CM_KV_INDEX, c, enc(500 + c))
     # appends of new tokens (inputs one level above the cache), timed on a nearly full cache
     kv.set_tokens(1024 - 8)
     new_k = ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), L), 20), lv + 1)
@@ -249,9 +252,9 @@ def attention_workload(a):
         res[name] = (time.perf_counter() - t0) / reps
     # per key ciphertext: one relinearisation and the sum over the 128 dims, as 7 dependent rotations or,
     # unrolled (runs of 3 + 2 + 2 ladder steps), 13 hoisted ones on 3 ModUps
-    sh = 1 if a.ladders else (a.shared_dims or 128)
+    sh = 1 if a.ladders or a.key_index else (a.shared_dims or 128)
     per_ct = {1: 13, 2: 14, 4: 10, 8: 6, 16: 7, 32: 3, 64: 1, 128: 0}[sh]    # hoisted rotations of the runs of the ladder left per key ciphertext
-    ks_qk = 3 + 128 * (8 if a.ladders else 1 + per_ct) + sh - 1
+    ks_qk = 3 + 15 + 8 + 7 if a.key_index else 3 + 128 * (8 if a.ladders else 1 + per_ct) + sh - 1
     print(json.dumps({
         "metric": "encrypted-cache attention products/s (config 3: q K^T and scores V, 32 heads x 128 dims, "
                   "context 1024, n=2^16, 24x50-bit + 4x60-bit primes)",
@@ -259,7 +262,8 @@ def attention_workload(a):
         "higher_is_better": True, "dtype": "u64", "data": "synthetic", "vs_baseline": None,
         "config": {"workload": "config3: q K^T (128 K ciphertexts) + scores V (128 V ciphertexts, 16 baby x 8 giant)",
                    "cache_level": lv,
-                   "dim_sum": "rotate-and-add ladder" if a.ladders else
+                   "dim_sum": "none: scores from the key index (15 hoisted rotations of the query, 8 relinearisations, 7 giant steps)"
+                              if a.key_index else "rotate-and-add ladder" if a.ladders else
                               "unrolled in the extended basis (3 ModUps, 13 rotations)" if sh == 1 else
                               "mask before the last %d terms: %d rotations per key ciphertext + %d shared" % (sh, per_ct, sh - 1)},
         "qk_ms": res["qk"] * 1e3, "sv_ms": res["sv"] * 1e3, "append_ms": append_ms,
@@ -420,6 +424,9 @@ def main():
                     help="attention / prefill workloads: terms of the sum over the dims of q K^T taken after the copy mask, by "
                          "rotations shared by all key ciphertexts (1 = the printed order; default 128 for the 128 key "
                          "ciphertexts of the attention workload, 16 for the 16 of the prefill workload)")
+    ap.add_argument("--key-index", action="store_true",
+                    help="attention workload: the cache also keeps the key index (a diagonal re-layout of the K cache maintained "
+                         "at append); q K^T runs on it like scores V")
     ap.add_argument("--ladders", action="store_true",
                     help="preprocess and reduce as the rotate-and-add ladders of Algorithm 1 (3 + 3 dependent rotations)")
     ap.add_argument("--nested-giants", action="store_true",

@@ -240,7 +240,8 @@ cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *con
  * result is sum_c s[c, h, tau'] V[c*t + tau', h, e], the contribution of the keys at residue tau' to
  * the query whose scores sit there.  An inner rotation by t - delta takes it back to the query's own
  * residue; the sum over delta is the attention output of the whole group. */
-enum { CM_QK = 0, CM_SV = 1, CM_QK_GROUP = 2, CM_SV_GROUP = 3 };
+enum { CM_QK = 0, CM_SV = 1, CM_QK_GROUP = 2, CM_SV_GROUP = 3,
+       CM_KV_INDEX = 4 /* cm_kv_load / cm_kv_export only: a ciphertext of the key index */ };
 /* Cache for `heads` heads of `dim` dims (heads*dim*t = S) holding up to max_tokens tokens
  * (<= dim*t) at ciphertext level `level` and scale `scale`.  r_i = baby steps of the
  * score-times-V product (0 = dim, no giant steps). */
@@ -254,7 +255,19 @@ cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int
  * step) and its ladder over the residues runs in the extended basis before the one ModDown and the
  * rescale.  More rotation keys (cm_kv_steps lists them), fewer ModUps and ModDowns.  Unknown bits:
  * CM_E_INVAL. */
-enum { CM_KV_UNROLLED_LADDERS = 1 };
+/* CM_KV_KEY_INDEX — next to the K cache of Sec. 5.1 the cache keeps a re-layout of it, the key index: `dim`
+ * ciphertexts X_{g r_i + j} = sum_c Rot(mask_c, -g r_i B) Rot(K_c, j B) (B = heads * t slots per copy), i.e. copy b of
+ * X_{g r_i + j} holds dim (b + j) mod dim of key group (b - g r_i) mod dim.  Sec. 5.1's scores
+ *   sum_c mask_c sum_k Rot(q . K_c, k B)  =  sum_k Rot(q, k B) . D_k,   D_k = sum_c mask_c Rot(K_c, k B)
+ * (Rot(a b) = Rot(a) Rot(b)), a diagonal product like scores-times-V (Sec. 5.2) whose baby-step / giant-step
+ * schedule runs on the index as it is: r_i - 1 hoisted rotations of the query, dim products, dim / r_i
+ * relinearisations and giant steps for the WHOLE cache, no mask afterwards: query-times-K then returns the
+ * scores ONE level below the cache (not two) and costs what scores-times-V costs.  The price is paid at
+ * append: r_i - 1 more hoisted rotations (of the new key) and `dim` more masked products per token or token
+ * group, and `dim` more ciphertexts of memory.  cm_kv_load(CM_QK) does not update the index (that would
+ * cost a level): load its ciphertexts with CM_KV_INDEX.  With the index, cm_kv_steps lists no rotation for
+ * the sum over the dims and cm_kv_set_shared_dims has no effect on query-times-K. */
+enum { CM_KV_UNROLLED_LADDERS = 1, CM_KV_KEY_INDEX = 2 };
 cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level,
                           double scale, int32_t max_tokens, uint32_t flags, cm_kv **out);
 /* Sec. 5.1 sums the product of every key ciphertext over all dim copies and then keeps copy e = c by a mask.
@@ -302,7 +315,8 @@ cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k
  * together.  Same rotation keys as cm_kv_append. */
 cm_status cm_kv_append_group(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_grp,
                              const cm_ct *v_grp, void *stream);
-/* which = CM_QK: in = query at (e, h, 0) slots, cache level; out = scores, two levels lower.
+/* which = CM_QK: in = query at (e, h, 0) slots, cache level; out = scores, two levels lower (one level lower
+ * for a cache with CM_KV_KEY_INDEX).
  * which = CM_SV: in = scores; out = attention output at (e, h, 0), one level lower.
  * CM_QK_GROUP / CM_SV_GROUP: the same levels; no keys for the residue rotations are needed. */
 cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t which,

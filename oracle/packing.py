@@ -338,6 +338,39 @@ class KvLayout:
         masked products of the V-cache update, all residues at once): block row e = (c - k) mod E."""
         return sum(self.v_append_mask(k, c * self.t + tau) for tau in range(self.t))
 
+    def pack_k_index(self, K, k):
+        """The key index (a re-layout of the K cache, derived from Sec. 5.1's identity: see
+        vmm.qk_scores_indexed): ciphertext k = g r_i + j holds at (b, h, tau) element
+        K[((b - g r_i) mod E) t + tau, h, (b + j) mod E], i.e. sum_c Rot(mask_c, -g r_i B) Rot(K_c, j B)
+        with B = H t slots per copy.  Tokens past the end are zero."""
+        g, j = k // self.r_i, k % self.r_i
+        out = np.zeros(self.S)
+        for b in range(self.E):
+            for tau in range(self.t):
+                n = ((b - g * self.r_i) % self.E) * self.t + tau
+                if n < K.shape[0]:
+                    for h in range(self.H):
+                        out[self.slot(b, h, tau)] = K[n, h, (b + j) % self.E]
+        return out
+
+    def k_index_append_mask(self, k, n):
+        """Slots of index ciphertext k that token n = c*t + tau occupies: copy (c + g r_i) mod E at residue tau."""
+        c, tau = n // self.t, n % self.t
+        m = np.zeros(self.S)
+        for h in range(self.H):
+            m[self.slot((c + (k // self.r_i) * self.r_i) % self.E, h, tau)] = 1.0
+        return m
+
+    def k_index_append_group_mask(self, k, c):
+        return sum(self.k_index_append_mask(k, c * self.t + tau) for tau in range(self.t))
+
+    def k_index_steps(self):
+        """Rotation amounts the index needs: the baby steps (of the query, and of a new key at append) and the giant step."""
+        s = [j * self.H * self.t for j in range(1, self.r_i)]
+        if self.r_o > 1:
+            s.append(self.r_i * self.H * self.t)
+        return s
+
     def qk_steps(self):
         return [-(1 << i) for i in range(_log2(self.t))] + \
                [(1 << i) * self.H * self.t for i in range(_log2(self.E))]

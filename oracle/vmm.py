@@ -343,6 +343,23 @@ def qk_scores_shared(ctx, keys, lay: KvLayout, cq, k_cts, masks, shared, replica
     return ctx.rescale(ctx.moddown_ct(acc, lv, scale))
 
 
+def qk_scores_indexed(ops, lay: KvLayout, cq, x_cts, replicate=True, sv=None):
+    """q K^T from the key index.  Sec. 5.1: scores = sum_c mask_c sum_k Rot(q . K_c, k B) (B = H t).  With
+    Rot(a b) = Rot(a) Rot(b):  = sum_k Rot(q, k B) . D_k,  D_k = sum_c mask_c Rot(K_c, k B), which depends on the
+    cache only: copy c of D_k holds dim (c + k) mod E of key group c.  That is a product of the diagonal form of
+    Sec. 5.2 (scores V) with q in the place of the scores and the D_k in the place of the V ciphertexts, so its
+    baby-step / giant-step schedule is used as it is: x_cts[g r_i + j] = Rot(D_{g r_i + j}, -g r_i B)
+    (lay.pack_k_index), scores = sum_g Rot( sum_j Rot(q, j B) (x) x_cts[g r_i + j], g r_i B ), one
+    relinearisation per giant-step group, no mask afterwards (one level less than qk_scores), no sum over the
+    residues.  `sv` = the scores-times-V routine to run (score_times_v, or the extended-basis one bound to its
+    context and keys)."""
+    for i in range(_log2(lay.t) if replicate else 0):   # replicate q over the t residues
+        cq = ops.add(cq, ops.rotate(cq, -(1 << i)))
+    if sv is not None:
+        return sv(cq, x_cts)
+    return score_times_v(ops, lay, cq, x_cts, reduce=False)
+
+
 def score_times_v(ops, lay: KvLayout, cs, v_cts, reduce=True):
     """Sec. 5.2/5.3: Att[h, e] = sum_n s[h, n] V[n, h, e]; result at (e, h, 0), the input
     layout of the next plaintext product (other residues hold partial sums).  reduce=False
@@ -422,7 +439,16 @@ def inner_rotate(ops, lay: KvLayout, c, delta, plaintexts):
     return masked_two_rotations(ops, c, plaintexts, up, down)
 
 
-def kv_append(ops, lay: KvLayout, k_cts, v_cts, n, ck_new, cv_new, k_mask, v_masks):
+def _index_append(ops, lay, x_cts, ck_new, x_masks):
+    """x_cts[g r_i + j] += mask * Rot(ck_new, j B): the baby rotations of the new key(s) are rotations of one
+    ciphertext (hoisted); x_masks[k] = lay.k_index_append_mask(k, n) or its group form."""
+    rotated = [ck_new] + ops.rotate_many(ck_new, [j * lay.H * lay.t for j in range(1, lay.r_i)])
+    for k in range(lay.E):
+        xnew = ops.rescale(ops.mul_pt(rotated[k % lay.r_i], x_masks[k]))
+        x_cts[k] = xnew if x_cts[k] is None else ops.add(x_cts[k], xnew)
+
+
+def kv_append(ops, lay: KvLayout, k_cts, v_cts, n, ck_new, cv_new, k_mask, v_masks, x_cts=None, x_masks=None):
     """Append token n = c*t + tau (Sec. 5.1 'K Cache Update', Sec. 5.2 'V Cache Update').
     ck_new / cv_new carry the new vectors at residue tau (other slots may hold partial sums);
     k_mask = lay.residue_mask(tau), v_masks[k] = lay.v_append_mask(k, n).  Masking costs the
@@ -438,9 +464,11 @@ def kv_append(ops, lay: KvLayout, k_cts, v_cts, n, ck_new, cv_new, k_mask, v_mas
     for k in range(lay.E):
         vnew = ops.rescale(ops.mul_pt(shifted[k // lay.r_i], v_masks[k]))
         v_cts[k] = vnew if v_cts[k] is None else ops.add(v_cts[k], vnew)
+    if x_cts is not None:
+        _index_append(ops, lay, x_cts, ck_new, x_masks)
 
 
-def kv_append_group(ops, lay: KvLayout, k_cts, v_cts, c, ck_grp, cv_grp, k_mask, v_masks):
+def kv_append_group(ops, lay: KvLayout, k_cts, v_cts, c, ck_grp, cv_grp, k_mask, v_masks, x_cts=None, x_masks=None):
     """Sec. 5.4, cache generation in the prompt phase: the t tokens c*t .. c*t + t-1 at once.
     ck_grp / cv_grp hold token c*t + tau at residue tau of every (e, h) block, which is already
     the layout of K ciphertext c; k_mask is all ones (the product only keeps levels and scales
@@ -451,3 +479,5 @@ def kv_append_group(ops, lay: KvLayout, k_cts, v_cts, c, ck_grp, cv_grp, k_mask,
     for k in range(lay.E):
         vnew = ops.rescale(ops.mul_pt(shifted[k // lay.r_i], v_masks[k]))
         v_cts[k] = vnew if v_cts[k] is None else ops.add(v_cts[k], vnew)
+    if x_cts is not None:
+        _index_append(ops, lay, x_cts, ck_grp, x_masks)

@@ -17,9 +17,9 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} not built: run python -m paper_2602_11470_amd.build")
 lib = C.CDLL(LIB_PATH)
 
-CM_QK, CM_SV, CM_QK_GROUP, CM_SV_GROUP = 0, 1, 2, 3
+CM_QK, CM_SV, CM_QK_GROUP, CM_SV_GROUP, CM_KV_INDEX = 0, 1, 2, 3, 4
 CM_VMM_RAISED_SUMS, CM_VMM_DIRECT_GIANTS, CM_VMM_TOKEN_BATCH, CM_VMM_UNROLLED_LADDERS = 1, 2, 4, 8
-CM_KV_UNROLLED_LADDERS = 1
+CM_KV_UNROLLED_LADDERS, CM_KV_KEY_INDEX = 1, 2
 
 
 class cm_params(C.Structure):
@@ -326,11 +326,12 @@ class Context:
         _chk(lib.cm_rope_apply(self.h, evk.h, rope.h, C.byref(x.d), C.byref(out.d), _stream()))
         return out
 
-    def kv_create(self, heads, dim, level, scale=0.0, max_tokens=None, r_i=0, unrolled_ladders=False, shared_dims=1):
-        return KvCache(self, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders, shared_dims)
+    def kv_create(self, heads, dim, level, scale=0.0, max_tokens=None, r_i=0, unrolled_ladders=False, shared_dims=1,
+                  key_index=False):
+        return KvCache(self, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders, shared_dims, key_index)
 
     def vmm_kv(self, evk, kv, which, x):
-        out = Ct(self, x.level - (1 if which in (CM_SV, CM_SV_GROUP) else 2))
+        out = Ct(self, x.level - (1 if which in (CM_SV, CM_SV_GROUP) or kv.key_index else 2))
         _chk(lib.cm_vmm_kv(self.h, evk.h, kv.h, which, C.byref(x.d), C.byref(out.d), _stream()))
         return out
 
@@ -431,12 +432,13 @@ class Rope:
 
 
 class KvCache:
-    def __init__(self, ctx, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders=False, shared_dims=1):
-        self.ctx, self.h, self.level = ctx, _vp(), level
+    def __init__(self, ctx, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders=False, shared_dims=1, key_index=False):
+        self.ctx, self.h, self.level, self.key_index = ctx, _vp(), level, key_index
         t = ctx.S // (heads * dim)
         max_tokens = dim * t if max_tokens is None else max_tokens
         _chk(lib.cm_kv_create_ex(ctx.h, heads, dim, r_i, level, scale, max_tokens,
-                                 CM_KV_UNROLLED_LADDERS if unrolled_ladders else 0, C.byref(self.h)))
+                                 (CM_KV_UNROLLED_LADDERS if unrolled_ladders else 0) | (CM_KV_KEY_INDEX if key_index else 0),
+                                 C.byref(self.h)))
         if shared_dims != 1:
             self.set_shared_dims(shared_dims)
 

@@ -42,6 +42,10 @@ struct cm_kv {
     // query-times-K with the copy mask applied before the last `shared` terms of the sum over the dims: the sums of
     // the key ciphertexts (d_T), their masked combinations A_k (d_A) and the E slot rotations of the mask (d_M)
     // d_Mhat: the transform of d_M along the copy index (the masked sums as a cyclic correlation), with its twiddles
+    // the key index: E ciphertexts like d_v, copy b of ciphertext g r_i + j = dim (b + j) of key group b - g r_i;
+    // query-times-K from it is the scores-times-V schedule with the query in the place of the scores
+    bool indexed = false;
+    u64 *d_x = nullptr;
     int shared = 1;
     u64 *d_T = nullptr, *d_A = nullptr, *d_M = nullptr, *d_Mhat = nullptr, *d_tw = nullptr, *d_einv = nullptr;
 };
@@ -97,7 +101,7 @@ extern "C" cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32
 }
 extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level, double scale,
                                      int32_t max_tokens, uint32_t flags, cm_kv **out) {
-    if (!ctx || !out || heads < 1 || dim < 1 || max_tokens < 1 || (flags & ~(uint32_t)CM_KV_UNROLLED_LADDERS)) return CM_E_INVAL;
+    if (!ctx || !out || heads < 1 || dim < 1 || max_tokens < 1 || (flags & ~(uint32_t)(CM_KV_UNROLLED_LADDERS | CM_KV_KEY_INDEX))) return CM_E_INVAL;
     if (level < 2 || level > ctx->L) return CM_E_LEVEL;
     const int S = ctx->n / 2;
     if (!pow2(heads) || !pow2(dim) || heads * dim > S) return CM_E_LAYOUT;
@@ -110,6 +114,7 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
     kv->scale = scale > 0 ? scale : ctx->prm.scale;
     kv->nk_max = (max_tokens + kv->t - 1) / kv->t;
     kv->unrolled = (flags & CM_KV_UNROLLED_LADDERS) != 0;
+    kv->indexed = (flags & CM_KV_KEY_INDEX) != 0;
     if (kv->unrolled) {
         std::vector<long long> ladder;
         for (int i = 0; i < ilog2(dim); i++) ladder.push_back((long long)(1 << i) * heads * kv->t);
@@ -135,12 +140,13 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
                           (kv->unrolled ? 2 * 2 * (size_t)kl.ext * n : 0);
         if (sv > kv->work_words) kv->work_words = sv;
         // append: mask, one product and its rescale, r_o - 1 shifted inputs, then the batch buffers
-        const size_t ap = (size_t)(level + 2) * n + (size_t)(2 + kv->r_o) * ctw_up +
+        const size_t ap = (size_t)(level + 2) * n + (size_t)(2 + (kv->indexed && kv->r_i > kv->r_o ? kv->r_i : kv->r_o)) * ctw_up +
                           B * (ctw_up + ctw + 2 * n + 2 * (size_t)(level + 1) * n);
         if (ap > kv->work_words) kv->work_words = ap;
     }
     bool ok = hipMalloc((void **)&kv->d_k, (size_t)kv->nk_max * ctw * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_v, (size_t)kv->E * ctw * 8) == hipSuccess &&
+              (!kv->indexed || hipMalloc((void **)&kv->d_x, (size_t)kv->E * ctw * 8) == hipSuccess) &&
               hipMalloc((void **)&kv->d_mask_qk, (size_t)level * n * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_mask_k, (size_t)(level + 2) * n * 8) == hipSuccess &&
               hipMalloc((void **)&kv->d_mask_v, (size_t)(level + 2) * n * 8) == hipSuccess &&
@@ -153,6 +159,7 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
     if (!ok) { cm_kv_destroy(kv); return CM_E_NOMEM; }
     hipMemset(kv->d_k, 0, (size_t)kv->nk_max * ctw * 8);      // an all-zero ciphertext encrypts 0
     hipMemset(kv->d_v, 0, (size_t)kv->E * ctw * 8);
+    if (kv->indexed) hipMemset(kv->d_x, 0, (size_t)kv->E * ctw * 8);
     cm_status s = encode_mask(kv, 0, kv->d_mask_qk, level - 1, nullptr);
     if (s == CM_OK && level + 1 <= ctx->L) {
         s = encode_mask(kv, 1, kv->d_mask_k, level + 1, nullptr);
@@ -166,7 +173,7 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
 }
 extern "C" void cm_kv_destroy(cm_kv *kv) {
     if (!kv) return;
-    hipFree(kv->d_k), hipFree(kv->d_v), hipFree(kv->d_mask_qk), hipFree(kv->d_mask_k), hipFree(kv->d_mask_v);
+    hipFree(kv->d_k), hipFree(kv->d_v), hipFree(kv->d_x), hipFree(kv->d_mask_qk), hipFree(kv->d_mask_k), hipFree(kv->d_mask_v);
     hipFree(kv->d_mask_kg), hipFree(kv->d_mask_vg);
     hipFree(kv->d_T), hipFree(kv->d_A), hipFree(kv->d_M), hipFree(kv->d_Mhat), hipFree(kv->d_tw), hipFree(kv->d_einv);
     hipFree(kv->d_work);
@@ -253,7 +260,9 @@ extern "C" cm_status cm_kv_set_shared_dims(cm_kv *kv, int32_t shared) {
 static std::vector<int> kv_all_steps(const cm_kv *kv) {
     std::vector<int> s;
     for (int i = 0; i < ilog2(kv->t); i++) s.push_back(-(1 << i));                         // replicate q
-    if (kv->unrolled) {
+    if (kv->indexed) {
+        // query-times-K runs on the index: baby and giant steps below, no sum over the dims
+    } else if (kv->unrolled) {
         for (const auto &grp : kv->dim_groups)
             for (long long a : grp) s.push_back((int)a);                                       // sum over dims, run by run
         for (int k = 1; k < kv->shared; k++) s.push_back(k * kv->H * kv->t);                   // ... and its shared part
@@ -291,17 +300,19 @@ extern "C" cm_status cm_kv_load(cm_ctx *ctx, cm_kv *kv, int32_t which, int32_t i
     if (!ctx || !kv || kv->ctx != ctx || !ct || !ct->dev || ct->ncomp != 2) return CM_E_INVAL;
     if (ct->level != kv->level) return CM_E_LEVEL;
     if (kv->scale_set && fabs(ct->scale / kv->scale - 1) > 1e-9) return CM_E_SCALE;
+    if (which != CM_QK && which != CM_SV && !(which == CM_KV_INDEX && kv->indexed)) return CM_E_INVAL;
     if (idx < 0 || idx >= (which == CM_QK ? kv->nk_max : kv->E)) return CM_E_LAYOUT;
-    u64 *dst = (which == CM_QK ? kv->d_k : kv->d_v) + (size_t)idx * kv_ctw(kv);
+    u64 *dst = (which == CM_QK ? kv->d_k : which == CM_SV ? kv->d_v : kv->d_x) + (size_t)idx * kv_ctw(kv);
     HIPCHK(hipMemcpyAsync(dst, ct->dev, kv_ctw(kv) * 8, hipMemcpyDeviceToDevice, (hipStream_t)stream));
     kv->scale = ct->scale, kv->scale_set = true;
     return CM_OK;
 }
 extern "C" cm_status cm_kv_export(cm_ctx *ctx, const cm_kv *kv, int32_t which, int32_t idx, uint64_t *out) {
     if (!ctx || !kv || !out) return CM_E_INVAL;
+    if (which != CM_QK && which != CM_SV && !(which == CM_KV_INDEX && kv->indexed)) return CM_E_INVAL;
     if (idx < 0 || idx >= (which == CM_QK ? kv->nk_max : kv->E)) return CM_E_LAYOUT;
     cm_ct ct;
-    ct.dev = (which == CM_QK ? kv->d_k : kv->d_v) + (size_t)idx * kv_ctw(kv);
+    ct.dev = (which == CM_QK ? kv->d_k : which == CM_SV ? kv->d_v : kv->d_x) + (size_t)idx * kv_ctw(kv);
     ct.level = kv->level, ct.ncomp = 2, ct.scale = kv->scale;
     return cm_ct_export(ctx, &ct, out);
 }
@@ -328,6 +339,8 @@ static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_c
     if (fabs(k_new->scale / v_new->scale - 1) > 1e-9) return CM_E_SCALE;
     for (int g = 1; g < kv->r_o; g++)
         if (!find_key(evk, rot_g(kv, -(long long)g * kv->r_i * kv->H * kv->t))) return CM_E_NOKEY;
+    for (int j = 1; j < kv->r_i && kv->indexed; j++)
+        if (!find_key(evk, rot_g(kv, (long long)j * kv->H * kv->t))) return CM_E_NOKEY;
     hipStream_t st = (hipStream_t)stream;
     const size_t n = ctx->n, ctw_up = 2 * (size_t)(lv + 1) * n, ctw = kv_ctw(kv);
     const int tok = kv->ntok, c = tok / kv->t, tau = tok % kv->t;
@@ -366,6 +379,36 @@ static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_c
         launch_mul_pt_rot_batch(ctx, prods, mb, m, group ? kv->d_mask_vg : kv->d_mask_v, lv + 1, st);
         // consecutive value ciphertexts are contiguous: the rescale adds its result onto them
         CMCHK(rescale_into(ctx, prods, 2 * m, lv, kv->d_v + (size_t)kb * ctw, st, last, red, true));
+    }
+    if (kv->indexed) {
+        // index: X_{g r_i + j} += rescale(mask * Rot(k_new, j B)), mask = copy (c + g r_i) mod E at residue tau (a group: the
+        // whole copy); the baby rotations of the new key are hoisted, the masked products go eight per launch
+        if (kv->r_i > 1) {
+            u64 *digits = arena_digits(ctx);
+            CMCHK(ks_raise(ctx, k_new->dev + (size_t)(lv + 1) * n, lv, digits, st));
+            std::vector<const u64 *> keys;
+            std::vector<u64> gs;
+            std::vector<u64 *> dst;
+            for (int j = 1; j < kv->r_i; j++) {
+                const u64 gal = rot_g(kv, (long long)j * kv->H * kv->t);
+                keys.push_back(find_key(evk, gal)), gs.push_back(gal), dst.push_back(shifted + (size_t)(j - 1) * ctw_up);
+            }
+            CMCHK(ks_apply_many(ctx, digits, lv, kv->r_i - 1, keys.data(), gs.data(), k_new->dev, dst.data(), st));
+        }
+        u64 *xp = shifted + (size_t)(kv->r_i > 1 ? kv->r_i - 1 : 0) * ctw_up, *xr = xp + (size_t)CM_KS_BATCH * ctw_up;
+        u64 *xl = xr + (size_t)CM_KS_BATCH * ctw, *xd = xl + (size_t)CM_KS_BATCH * 2 * n;
+        for (int kb = 0; kb < kv->E; kb += CM_KS_BATCH) {
+            const int m = kv->E - kb < CM_KS_BATCH ? kv->E - kb : CM_KS_BATCH;
+            MulPtBatch mb;
+            for (int r = 0; r < m; r++) {
+                const int k = kb + r, g = k / kv->r_i, j = k % kv->r_i;
+                const long long a = (long long)((c + g * kv->r_i) % kv->E) * kv->H * kv->t + tau;
+                mb.src[r] = j == 0 ? k_new->dev : shifted + (size_t)(j - 1) * ctw_up;
+                mb.g[r] = (unsigned)rot_g(kv, -a);
+            }
+            launch_mul_pt_rot_batch(ctx, xp, mb, m, group ? kv->d_mask_vg : kv->d_mask_v, lv + 1, st);
+            CMCHK(rescale_into(ctx, xp, 2 * m, lv, kv->d_x + (size_t)kb * ctw, st, xl, xd, true));
+        }
     }
     kv->ntok += group ? kv->t : 1;
     kv->scale = k_new->scale * (double)ctx->mod[lv] / (double)ctx->mod[lv];
@@ -527,9 +570,12 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     RETURN_LAUNCH_STATUS();
 }
 
+// array = the value ciphertexts, or the key index with the query in the place of the scores (replicate: the query is
+// first copied to all residues, as query-times-K does)
 static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st,
-                       bool reduce) {
+                       bool reduce, const u64 *array, bool replicate) {
     const int lv = kv->level, limbs = lv + 1;
+    for (int i = 0; i < ilog2(kv->t) && replicate; i++) if (!find_key(evk, rot_g(kv, -(1 << i)))) return CM_E_NOKEY;
     const size_t n = ctx->n, ctw = kv_ctw(kv), ln = (size_t)limbs * n;
     const u64 *relin = find_key(evk, 0);
     if (!relin) return CM_E_NOKEY;
@@ -549,6 +595,15 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
         *tmp = T + B * 3 * ln, *R = tmp + ctw, *ksin = R + ctw, *bdigits = ksin + B * ln;
     u64 *digits = arena_digits(ctx);
     HIPCHK(hipMemcpyAsync(babies, in->dev, ctw * 8, hipMemcpyDeviceToDevice, st));
+    if (replicate) {
+        u64 *cq = babies, *alt = tmp;
+        for (int i = 0; i < ilog2(kv->t); i++) {
+            const u64 g = rot_g(kv, -(1 << i));
+            CMCHK(rotate_into(ctx, find_key(evk, g), cq, lv, g, alt, st, cq));      // alt = cq + Rot(cq)
+            std::swap(cq, alt);
+        }
+        if (cq != babies) HIPCHK(hipMemcpyAsync(babies, cq, ctw * 8, hipMemcpyDeviceToDevice, st));
+    }
     if (kv->r_i > 1) {
         CMCHK(ks_raise(ctx, babies + ln, lv, digits, st));
         std::vector<const u64 *> keys;
@@ -565,7 +620,7 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     // third components raised together, one inner-product launch with the relinearisation key read once, one ModDown
     for (int g0 = 0; g0 < kv->r_o; g0 += CM_KS_BATCH) {
         const int m = kv->r_o - g0 < CM_KS_BATCH ? kv->r_o - g0 : CM_KS_BATCH;
-        launch_tensor_sum(ctx, T, babies, kv->d_v + (size_t)g0 * kv->r_i * ctw, kv->r_i, m, limbs, st);
+        launch_tensor_sum(ctx, T, babies, array + (size_t)g0 * kv->r_i * ctw, kv->r_i, m, limbs, st);
         CMCHK(ks_raise_many(ctx, kv->relin_tabs, T, ksin, bdigits, st, m, 0));
         u64 *bu = arena_batch_sums(ctx);
         IpBatch ip;
@@ -645,7 +700,10 @@ extern "C" cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, 
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
     if (!ctx || !evk || !kv || kv->ctx != ctx || !in || !in->dev || !out || !out->dev || in->ncomp != 2) return CM_E_INVAL;
     if (in->level != kv->level) return CM_E_LEVEL;
+    if ((which == CM_QK || which == CM_QK_GROUP) && kv->indexed)
+        return kv_sv(ctx, evk, kv, in, out, (hipStream_t)stream, false, kv->d_x, which == CM_QK);
     if (which == CM_QK || which == CM_QK_GROUP) return kv_qk(ctx, evk, kv, in, out, (hipStream_t)stream, which == CM_QK);
-    if (which == CM_SV || which == CM_SV_GROUP) return kv_sv(ctx, evk, kv, in, out, (hipStream_t)stream, which == CM_SV);
+    if (which == CM_SV || which == CM_SV_GROUP)
+        return kv_sv(ctx, evk, kv, in, out, (hipStream_t)stream, which == CM_SV, kv->d_v, false);
     return CM_E_INVAL;
 }

@@ -199,13 +199,15 @@ def test_config4_mlp_projection_shapes_decrypt_to_float64_product(ring2, d_in, d
     assert np.abs(out - x @ W).max() < TOL
 
 
-@pytest.mark.parametrize("unrolled,shared", [(False, 1), (True, 1), (True, 128), (True, 16)])
-def test_config3_attention_shapes_decrypt_to_float64_products(ring2, unrolled, shared):
+@pytest.mark.parametrize("unrolled,shared,index", [(False, 1, False), (True, 1, False), (True, 128, False), (True, 16, False),
+                                                   (True, 1, True)])
+def test_config3_attention_shapes_decrypt_to_float64_products(ring2, unrolled, shared, index):
     """Llama-3-8B attention shapes on the full ring: 32 heads x 128 dims (8 KV heads repeated 4x),
     t = 8 tokens per K ciphertext, 128 V ciphertexts with 16 baby x 8 giant steps.  A short
     context (two loaded K ciphertexts plus three appended tokens) keeps the run small; every
     ciphertext and rotation has its full size.  shared > 1: the copy mask before the last `shared`
-    terms of the sum over the dims (127 or 15 rotations for the whole cache)."""
+    terms of the sum over the dims (127 or 15 rotations for the whole cache); index: the cache keeps the
+    key index, loaded for the first tokens and extended by the appends, and q K^T runs on it."""
     from oracle import packing
     from paper_2602_11470_amd import inputs
     B, octx, gctx, prm = ring2
@@ -216,7 +218,7 @@ def test_config3_attention_shapes_decrypt_to_float64_products(ring2, unrolled, s
     ntok = n_loaded + n_app
     q, K, V, s = inputs.attention_inputs(3, H, 8, E, ntok)
     lv = L - 1
-    kv = gctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=unrolled, shared_dims=shared)
+    kv = gctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=unrolled, shared_dims=shared, key_index=index)
     gsk = gctx.keygen_secret(1)
     gkeys = gctx.keygen_rotations(gsk, kv.steps(), 2, with_relin=True)
     enc = lambda slots, level, seed: gctx.level_drop(gctx.encrypt(gsk, gctx.encode(slots, L), seed), level)
@@ -224,13 +226,15 @@ def test_config3_attention_shapes_decrypt_to_float64_products(ring2, unrolled, s
         kv.load(B.CM_QK, c, enc(lay.pack_k(K[:n_loaded], c), lv, 100 + c))
     for k in range(E):
         kv.load(B.CM_SV, k, enc(lay.pack_v(V[:n_loaded], k), lv, 300 + k))
+        if index:
+            kv.load(B.CM_KV_INDEX, k, enc(lay.pack_k_index(K[:n_loaded], k), lv, 800 + k))
     kv.set_tokens(n_loaded)
     for n in range(n_loaded, ntok):
         tau = n % lay.t
         kv.append(gkeys, enc(lay.pack_vec(K[n], tau), L, 600 + n), enc(lay.pack_vec(V[n], tau), L, 700 + n))
     assert kv.tokens() == ntok
     gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, enc(lay.pack_vec(q), lv, 10))
-    assert gm.level == lv - 2
+    assert gm.level == (lv - 1 if index else lv - 2)
     got = lay.unpack_scores(gctx.decrypt(gsk, gm).real, ntok)
     assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
     ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, enc(lay.pack_scores(s), lv, 50))

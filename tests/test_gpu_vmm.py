@@ -703,3 +703,108 @@ def test_kv_shared_dims_rejects_other_caches_and_sizes(env):
     assert {k * 16 * 8 for k in range(1, 16)} <= set(kv.steps())
     kv.set_shared_dims(1)
     assert len(kv.steps()) == n0
+
+
+@pytest.mark.parametrize("r_i,unrolled", [(4, False), (0, False), (4, True), (8, True)])
+def test_kv_key_index_appends_and_scores_match_oracle_and_float64(env, r_i, unrolled):
+    """CM_KV_KEY_INDEX: one token group and five single tokens are appended; the K cache, the V cache and the
+    key index limb for limb against the oracle; q K^T from the index (one level, no mask) limb for limb and
+    against float64, for one query and for a query group; scores V unchanged."""
+    from oracle import packing, vmm
+    from oracle.ckks import Pt
+    from paper_2602_11470_amd import inputs
+    e = env
+    B, octx, gctx = e["B"], e["octx"], e["gctx"]
+    H, E, L = 16, 16, octx.prm.L
+    lay = packing.KvLayout(octx.S, H, E, r_i)            # t = 8
+    ntok = lay.t + 5
+    q, K, V, s = inputs.attention_inputs(27, H, 4, E, ntok)
+    q = q * 0.3
+    lv = L - 1
+    kv = gctx.kv_create(H, E, lv, r_i=r_i, unrolled_ladders=unrolled, key_index=True)
+    sv_steps = vmm.sv_unrolled_steps(lay) if unrolled else lay.sv_steps()
+    steps = sorted(set(lay.qk_steps()[:3]) | set(sv_steps) | set(lay.append_steps()) | set(lay.k_index_steps()))
+    assert sorted(set(kv.steps())) == steps              # no rotation for the sum over the dims
+    okeys = octx.keygen_rotations(e["osk"], steps, 2, with_relin=True)
+    gkeys = gctx.keygen_rotations(e["gsk"], steps, 2, with_relin=True)
+    ops = vmm.CkksOps(octx, okeys)
+    ql = float(octx.mod[lv + 1])
+
+    def base(kind):
+        m = np.zeros(octx.S)
+        if kind == 1:
+            m[::lay.t] = 1
+        elif kind == 2:
+            m[[h * lay.t for h in range(H)]] = 1
+        elif kind == 3:
+            m[:] = 1
+        else:
+            m[:H * lay.t] = 1
+        return octx.encode_coeffs(m, ql)
+
+    bases = {k: base(k) for k in (1, 2, 3, 4)}
+    for kind, c in bases.items():
+        kv.set_mask(kind, c)
+
+    def omask(kind, shift_right):
+        idx = octx.q_idx(lv + 1)
+        coeff = octx.automorphism_coeff(octx.from_i64(bases[kind], idx), idx, octx.galois(-shift_right))
+        return Pt(octx.ntt(coeff, idx), lv + 1, ql)
+
+    okc, ovc, oxc = [], [None] * E, [None] * E
+    # group 0 at once
+    kg = sum(lay.pack_vec(K[tau], tau) for tau in range(lay.t))
+    vg = sum(lay.pack_vec(V[tau], tau) for tau in range(lay.t))
+    ok_g, gk_g = _enc_both(e, kg, L, 90)
+    ov_g, gv_g = _enc_both(e, vg, L, 91)
+    vmm.kv_append_group(ops, lay, okc, ovc, 0, ok_g, ov_g, omask(3, 0),
+                        [omask(4, lay.slot((0 - k) % E, 0, 0) + lay.v_shift(k)) for k in range(E)],
+                        oxc, [omask(4, lay.slot((0 + (k // lay.r_i) * lay.r_i) % E, 0, 0)) for k in range(E)])
+    kv.append_group(gkeys, gk_g, gv_g)
+    for n in range(lay.t, ntok):
+        c, tau = n // lay.t, n % lay.t
+        ok_new, gk_new = _enc_both(e, lay.pack_vec(K[n], tau), L, 100 + n)
+        ov_new, gv_new = _enc_both(e, lay.pack_vec(V[n], tau), L, 500 + n)
+        vmasks = [omask(2, lay.slot((c - k) % E, 0, tau) + lay.v_shift(k)) for k in range(E)]
+        xmasks = [omask(2, lay.slot((c + (k // lay.r_i) * lay.r_i) % E, 0, tau)) for k in range(E)]
+        vmm.kv_append(ops, lay, okc, ovc, n, ok_new, ov_new, omask(1, tau), vmasks, oxc, xmasks)
+        kv.append(gkeys, gk_new, gv_new)
+    assert kv.tokens() == ntok
+    for c in range(len(okc)):
+        assert np.array_equal(kv.export(B.CM_QK, c), octx.canonical(okc[c]))
+    for k in range(E):
+        assert np.array_equal(kv.export(B.CM_KV_INDEX, k), octx.canonical(oxc[k])), k
+    assert np.array_equal(kv.export(B.CM_SV, 3), octx.canonical(ovc[3]))
+    # the index decrypts to the layout
+    for k in (0, 5, E - 1):
+        assert np.abs(octx.decrypt(e["osk"], oxc[k]).real - lay.pack_k_index(K, k)).max() < TOL
+
+    sv = (lambda c, x: vmm.score_times_v_unrolled(octx, okeys, lay, c, x, reduce=False)) if unrolled else None
+    oq, gq = _enc_both(e, lay.pack_vec(q), lv, 10)
+    om = vmm.qk_scores_indexed(ops, lay, oq, oxc, sv=sv)
+    gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, gq)
+    assert gm.level == lv - 1
+    _same(e, om, gm)
+    got = lay.unpack_scores(gctx.decrypt(e["gsk"], gm).real, ntok)
+    assert np.abs(got - np.einsum("he,nhe->hn", q, K)).max() < TOL
+    # a query group: query tau against the keys of residue tau
+    Q = np.random.default_rng(5).normal(size=(lay.t, H, E)) * 0.3
+    oqg, gqg = _enc_both(e, sum(lay.pack_vec(Q[tau], tau) for tau in range(lay.t)), lv, 11)
+    og = vmm.qk_scores_indexed(ops, lay, oqg, oxc, replicate=False, sv=sv)
+    gg = gctx.vmm_kv(gkeys, kv, B.CM_QK_GROUP, gqg)
+    _same(e, og, gg)
+    gotg = lay.unpack_scores(gctx.decrypt(e["gsk"], gg).real, ntok)
+    for n in range(ntok):
+        assert np.abs(gotg[:, n] - np.einsum("he,he->h", Q[n % lay.t], K[n])).max() < TOL
+    # scores V as before
+    os_, gs = _enc_both(e, lay.pack_scores(s), lv, 50)
+    oa = vmm.score_times_v_unrolled(octx, okeys, lay, os_, ovc) if unrolled else vmm.score_times_v(ops, lay, os_, ovc)
+    ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)
+    _same(e, oa, ga)
+    # load / export of an index ciphertext; not available without the index
+    kv.load(B.CM_KV_INDEX, 2, gctx.level_drop(gk_g, lv))
+    assert np.array_equal(kv.export(B.CM_KV_INDEX, 2), gctx.ct_export(gctx.level_drop(gk_g, lv)))
+    plain = gctx.kv_create(H, E, lv, r_i=r_i)
+    with pytest.raises(B.CachemirError) as ei:
+        plain.export(B.CM_KV_INDEX, 0)
+    assert ei.value.status == -1

@@ -638,3 +638,73 @@ def test_shared_dim_rotations_on_ciphertexts_decrypt_to_q_times_K_transposed(sha
     assert np.abs(ctx.decrypt(sk, m) - ctx.decrypt(sk, ladder)).max() < 1e-6
     generic = vmm.qk_scores_shared_ops(vmm.CkksOps(ctx, keys), lay, cq, kc, masks, shared)
     assert np.abs(ctx.decrypt(sk, m) - ctx.decrypt(sk, generic)).max() < 1e-6
+
+
+@pytest.mark.parametrize("r_i", [0, 2, 4])
+def test_key_index_gives_the_scores_of_the_printed_order_on_slots(r_i):
+    """The key index (copy c of D_k = dim (c + k) of key group c) turns q K^T into a diagonal product: the
+    same slot vector as qk_scores (every slot, not only after decoding), no mask, no sum over the dims per
+    key ciphertext; and appending token by token, or a group at once, builds exactly pack_k_index."""
+    lay = packing.KvLayout(256, 4, 8, r_i)              # t = 8, E = 8
+    nk = 5
+    ntok = nk * lay.t - 3
+    q, K, V, s = inputs.attention_inputs(9, 4, 2, 8, ntok)
+    kc = [lay.pack_k(K, c) for c in range(nk)]
+    ref = vmm.qk_scores(vmm.SlotOps(), lay, lay.pack_vec(q), kc, [lay.qk_mask(c) for c in range(nk)])
+    ops = vmm.SlotOps()
+    xc = [lay.pack_k_index(K, k) for k in range(lay.E)]
+    got = vmm.qk_scores_indexed(ops, lay, lay.pack_vec(q), xc)
+    assert np.abs(got - ref).max() < 1e-12
+    assert np.abs(got - lay.pack_scores(np.einsum("he,nhe->hn", q, K))).max() < 1e-12
+    assert ops.rotations == 3 + (lay.r_i - 1) + (lay.r_o - 1) and ops.pt_mults == 0
+    # a brute-force reading of the layout: ciphertext g r_i + j, copy b = dim (b + j) of key group b - g r_i
+    for k in (0, 3, lay.E - 1):
+        g, j = k // lay.r_i, k % lay.r_i
+        for b in (0, 5):
+            for tau in (0, 6):
+                n = ((b - g * lay.r_i) % lay.E) * lay.t + tau
+                want = K[n, 2, (b + j) % lay.E] if n < ntok else 0.0
+                assert xc[k][lay.slot(b, 2, tau)] == want
+    # appends: two groups at once, then single tokens
+    ops = vmm.SlotOps()
+    k_cts, v_cts, x_cts = [], [None] * lay.E, [None] * lay.E
+    for c in range(2):
+        kg = sum(lay.pack_vec(K[c * lay.t + tau], tau) for tau in range(lay.t)) + 0.0
+        vg = sum(lay.pack_vec(V[c * lay.t + tau], tau) for tau in range(lay.t))
+        vmm.kv_append_group(ops, lay, k_cts, v_cts, c, kg, vg, np.ones(lay.S),
+                            [lay.v_append_group_mask(k, c) for k in range(lay.E)],
+                            x_cts, [lay.k_index_append_group_mask(k, c) for k in range(lay.E)])
+    for n in range(2 * lay.t, ntok):
+        junk = np.roll(lay.pack_vec(K[n] * 7, (n + 1) % lay.t), 0)      # other residues hold partial sums
+        vmm.kv_append(ops, lay, k_cts, v_cts, n, lay.pack_vec(K[n], n % lay.t) + junk, lay.pack_vec(V[n], n % lay.t),
+                      lay.residue_mask(n % lay.t), [lay.v_append_mask(k, n) for k in range(lay.E)],
+                      x_cts, [lay.k_index_append_mask(k, n) for k in range(lay.E)])
+    for k in range(lay.E):
+        assert np.abs(x_cts[k] - xc[k]).max() < 1e-12
+    for c in range(nk):
+        assert np.abs(k_cts[c] - kc[c]).max() < 1e-12
+
+
+@pytest.mark.parametrize("r_i", [0, 4])
+def test_key_index_on_ciphertexts_decrypts_to_q_times_K_transposed(r_i):
+    prm = params.toy(n=512, n_qi=4, n_p=1, alpha=1)
+    ctx = ckks.Context(prm)
+    L = prm.L
+    sk = ctx.keygen_secret(1)
+    lay = packing.KvLayout(ctx.S, 4, 8, r_i)            # t = 8
+    ntok = 3 * lay.t - 2
+    q, K, V, s = inputs.attention_inputs(4, 4, 2, 8, ntok)
+    steps = sorted(set(vmm.sv_unrolled_steps(lay)) | set(lay.sv_steps()) | set(lay.qk_steps()))
+    keys = ctx.keygen_rotations(sk, steps, 2, with_relin=True)
+    enc = lambda v, lv, seed: ctx.level_drop(ctx.encrypt(sk, ctx.encode(v, L), seed), lv)
+    xc = [enc(lay.pack_k_index(K, k), L - 1, 100 + k) for k in range(lay.E)]
+    cq = enc(lay.pack_vec(q), L - 1, 10)
+    want = np.einsum("he,nhe->hn", q, K)
+    ops = vmm.CkksOps(ctx, keys)
+    a = vmm.qk_scores_indexed(ops, lay, cq, xc)
+    assert a.level == L - 2                              # one level, not two
+    assert np.abs(lay.unpack_scores(ctx.decrypt(sk, a).real, ntok) - want).max() < TOL
+    b = vmm.qk_scores_indexed(ops, lay, cq, xc,
+                              sv=lambda c, x: vmm.score_times_v_unrolled(ctx, keys, lay, c, x, reduce=False))
+    assert b.level == L - 2 and abs(a.scale / b.scale - 1) < 1e-12
+    assert np.abs(ctx.decrypt(sk, a) - ctx.decrypt(sk, b)).max() < 1e-6
