@@ -393,13 +393,16 @@ def prefill_workload(a):
     # delta: q K^T without replication, scores V without the sum over the residues; a group takes t of each plus
     # 2 (t - 1) inner rotations
     tk = ctx.S // (H * E)
-    kva = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=True, shared_dims=a.shared_dims or 16)
+    kva = ctx.kv_create(H, E, lv, r_i=16, unrolled_ladders=True, key_index=a.key_index,
+                        shared_dims=1 if a.key_index else (a.shared_dims or 16))
     akeys = ctx.keygen_rotations(sk, [s_ for s_ in kva.steps() if s_ % tk == 0], 2, with_relin=True)
     encl = lambda seed: ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), ctx.L), seed), lv)
     for c in range(128):
         if c < 16:
             kva.load(B.CM_QK, c, encl(100 + c))
         kva.load(B.CM_SV, c, encl(300 + c))
+        if a.key_index:
+            kva.load(B.CM_KV_INDEX, c, encl(500 + c))
     kva.set_tokens(16 * tk)
     qg, sg = encl(10), encl(11)
     qk_ms = timed(lambda: ctx.vmm_kv(akeys, kva, B.CM_QK_GROUP, qg), max(2, a.steps // 4))
@@ -408,7 +411,7 @@ def prefill_workload(a):
                       "data": "synthetic", "dtype": "u64", "token_batched_4096x4096": rows,
                       "rope_group_ms": rope_ms, "inner_rotation_ms": inner_ms, "append_group_ms": append_ms,
                       "append_group_ms_per_token": append_ms / tk,
-                      "group_attention_prompt_128": {"cache_level": lv, "shared_dims": a.shared_dims or 16,
+                      "group_attention_prompt_128": {"cache_level": lv, "shared_dims": 1 if a.key_index else (a.shared_dims or 16), "key_index": bool(a.key_index),
                                                      "qk_group_ms_per_delta": qk_ms,
                                                      "sv_group_ms_per_delta": sv_ms,
                                                      "ms_per_group": tk * (qk_ms + sv_ms) + 2 * (tk - 1) * inner_ms}}))
@@ -425,7 +428,7 @@ def main():
                          "rotations shared by all key ciphertexts (1 = the printed order; default 128 for the 128 key "
                          "ciphertexts of the attention workload, 16 for the 16 of the prefill workload)")
     ap.add_argument("--key-index", action="store_true",
-                    help="attention workload: the cache also keeps the key index (a diagonal re-layout of the K cache maintained "
+                    help="attention / prefill workloads: the cache also keeps the key index (a diagonal re-layout of the K cache maintained "
                          "at append); q K^T runs on it like scores V")
     ap.add_argument("--ladders", action="store_true",
                     help="preprocess and reduce as the rotate-and-add ladders of Algorithm 1 (3 + 3 dependent rotations)")
