@@ -617,6 +617,8 @@ def test_kv_sv_with_unrolled_giant_steps_and_ladder_matches_oracle_and_float64(e
     ("config1", 2, 128, 40, 128),    # enough products for the transform along the copy index (nk * shared >= 16 E)
     ("config1", 2, 128, 40, 64),     # ... with one ladder step left per key ciphertext
     ("config1", 4, 64, 20, 64),
+    ("config1", 16, 16, 16, 16),     # the shortest transform that can pay (64 coefficients per workgroup)
+    ("config1", 2, 256, 32, 128),    # 256 copies: 16 coefficients per workgroup, half of the rows written
     ("config1", 2, 128, 40, 16),     # more key ciphertexts than one LDS stage of the direct sums (32 + 8)
     ("wide", 4, 16, 5, 16),          # 54-bit primes: the integer form of the direct sums
     ("wide", 4, 16, 5, 2),
