@@ -152,12 +152,54 @@ void launch_mac_pt_rot_batch(cm_ctx *ctx, u64 *acc, const u64 *src, const MulPtB
     hipLaunchKernelGGL(k_mac_pt_rot_batch, dim3(ctx->n / TPB, 2 * limbs), dim3(TPB), 0, st, acc, src, b, cnt, pt_mont,
                        ctx->d_modc, limbs, ctx->n, ctx->logn, accumulate);
 }
-// out[z][3][limbs][n] = sum_{j < cnt} a[j] (x) b[z*cnt + j]: a and b stacked at stride 2*limbs*n; every output written once
+// FP64 modular products for limbs whose modulus is below 2^50 (the arithmetic is explained at k_vmm_mac_lds)
+struct MacFp {
+    double q, qinv;
+    __device__ __forceinline__ double mulmod(double y, double a, double aq) const {
+        double h = y * a;
+        double l = __builtin_fma(y, a, -h);
+        double c = __builtin_rint(y * aq);
+        return __builtin_fma(-c, q, h) + l;
+    }
+    __device__ __forceinline__ double norm(double x) const { return __builtin_fma(-__builtin_rint(x * qinv), q, x); }
+    __device__ __forceinline__ static double from_u64(u64 raw) {                 // raw < 2^52
+        return __longlong_as_double((long long)(raw | 0x4330000000000000ULL)) - 4503599627370496.0;
+    }
+    __device__ __forceinline__ u64 canon(double v) const {                       // |v| < 2^52 -> [0, q)
+        double r = __builtin_fma(-__builtin_floor(v * qinv), q, v);
+        r = r < 0.0 ? r + q : r;
+        r = r >= q ? r - q : r;
+        return (u64)__double_as_longlong(r + 4503599627370496.0) & 0x000FFFFFFFFFFFFFULL;
+    }
+};
+// out[z][3][limbs][n] = sum_{j < cnt} a[j] (x) b[z*cnt + j]: a and b stacked at stride 2*limbs*n; every output written once.
+// On limbs below 2^50 the four products per term run in FP64 (no multiplier form needed), sums renormalised every two terms.
 __global__ void k_tensor_sum(u64 *__restrict__ out, const u64 *__restrict__ a, const u64 *__restrict__ b,
-                             const ModC *__restrict__ modc, int limbs, int n, int cnt) {
+                             const ModC *__restrict__ modc, const FpQ *__restrict__ fpq, int limbs, int n, int cnt) {
     int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y, z = blockIdx.z;
     const ModC m = modc[l];
     const size_t o = (size_t)l * n + i, cs = (size_t)limbs * n;
+    const FpQ fq = fpq[l];
+    if (fq.q != 0.0) {
+        const MacFp F{fq.q, fq.qinv};
+        double d0 = 0.0, d1 = 0.0, d2 = 0.0;
+        for (int j = 0; j < cnt; j++) {
+            const u64 *aj = a + (size_t)j * 2 * cs, *bj = b + ((size_t)z * cnt + j) * 2 * cs;
+            const double a0 = MacFp::from_u64(aj[o]), a1 = MacFp::from_u64(aj[o + cs]);
+            const double b0 = MacFp::from_u64(__builtin_nontemporal_load(bj + o));
+            const double b1 = MacFp::from_u64(__builtin_nontemporal_load(bj + o + cs));
+            const double b0q = b0 * F.qinv, b1q = b1 * F.qinv;
+            d0 += F.mulmod(a0, b0, b0q);
+            d1 += F.mulmod(a0, b1, b1q) + F.mulmod(a1, b0, b0q);
+            d2 += F.mulmod(a1, b1, b1q);
+            if (j & 1) d0 = F.norm(d0), d1 = F.norm(d1), d2 = F.norm(d2);
+        }
+        u64 *oz = out + (size_t)z * 3 * cs;
+        oz[o] = F.canon(d0);
+        oz[o + cs] = F.canon(d1);
+        oz[o + 2 * cs] = F.canon(d2);
+        return;
+    }
     u64 d0 = 0, d1 = 0, d2 = 0;
     for (int j = 0; j < cnt; j++) {
         const u64 *aj = a + (size_t)j * 2 * cs, *bj = b + ((size_t)z * cnt + j) * 2 * cs;
@@ -172,9 +214,54 @@ __global__ void k_tensor_sum(u64 *__restrict__ out, const u64 *__restrict__ a, c
     oz[o + cs] = d1;
     oz[o + 2 * cs] = d2;
 }
+// The same sums with the cnt <= TS_MAX_CNT ciphertexts a[j] held in registers (FP64 limbs only) while the lane runs over
+// all groups: a is read once instead of once per group, which is half of the traffic when a does not fit the caches.
+#define TS_MAX_CNT 16
+__global__ __launch_bounds__(TPB) void k_tensor_sum_stationary(u64 *__restrict__ out, const u64 *__restrict__ a,
+                                                               const u64 *__restrict__ b, const FpQ *__restrict__ fpq,
+                                                               int limbs, int n, int cnt, int groups) {
+    const int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
+    const FpQ fq = fpq[l];
+    const MacFp F{fq.q, fq.qinv};
+    const size_t o = (size_t)l * n + i, cs = (size_t)limbs * n;
+    double a0[TS_MAX_CNT], a1[TS_MAX_CNT];
+#pragma unroll
+    for (int j = 0; j < TS_MAX_CNT; j++) {
+        a0[j] = j < cnt ? MacFp::from_u64(a[(size_t)j * 2 * cs + o]) : 0.0;
+        a1[j] = j < cnt ? MacFp::from_u64(a[(size_t)j * 2 * cs + cs + o]) : 0.0;
+    }
+    for (int z = 0; z < groups; z++) {
+        double d0 = 0.0, d1 = 0.0, d2 = 0.0;
+#pragma unroll
+        for (int j = 0; j < TS_MAX_CNT; j++) {
+            if (j < cnt) {
+                const u64 *bj = b + ((size_t)z * cnt + j) * 2 * cs;
+                const double b0 = MacFp::from_u64(__builtin_nontemporal_load(bj + o));
+                const double b1 = MacFp::from_u64(__builtin_nontemporal_load(bj + o + cs));
+                const double b0q = b0 * F.qinv, b1q = b1 * F.qinv;
+                d0 += F.mulmod(a0[j], b0, b0q);
+                d1 += F.mulmod(a0[j], b1, b1q) + F.mulmod(a1[j], b0, b0q);
+                d2 += F.mulmod(a1[j], b1, b1q);
+            }
+            if (j & 1) d0 = F.norm(d0), d1 = F.norm(d1), d2 = F.norm(d2);
+        }
+        u64 *oz = out + (size_t)z * 3 * cs;
+        oz[o] = F.canon(d0);
+        oz[o + cs] = F.canon(d1);
+        oz[o + 2 * cs] = F.canon(d2);
+    }
+}
 void launch_tensor_sum(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int groups, int limbs, hipStream_t st) {
     Prof prof_(ctx, CM_K_ELEMENTWISE, 3 * limbs * groups, st);
-    hipLaunchKernelGGL(k_tensor_sum, dim3(ctx->n / TPB, limbs, groups), dim3(TPB), 0, st, out, a, b, ctx->d_modc, limbs, ctx->n, cnt);
+    bool all_fp = !getenv("CM_NTT_INT");                      // the switch that keeps every limb on the integer forms
+    for (int l = 0; l < limbs; l++) all_fp = all_fp && ctx->mod[l] < (1ULL << 50);
+    if (all_fp && cnt <= TS_MAX_CNT && groups > 1) {
+        hipLaunchKernelGGL(k_tensor_sum_stationary, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, a, b, ctx->d_fpq, limbs, ctx->n,
+                           cnt, groups);
+        return;
+    }
+    hipLaunchKernelGGL(k_tensor_sum, dim3(ctx->n / TPB, limbs, groups), dim3(TPB), 0, st, out, a, b, ctx->d_modc, ctx->d_fpq, limbs, ctx->n,
+                       cnt);
 }
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st) {
     Prof prof_(ctx, CM_K_ELEMENTWISE, 3 * limbs, st);
@@ -826,25 +913,6 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 // sums are renormalised every four terms (|sum| < 4.6 q < 2^53 stays exact).  That is 8.5
 // instructions per product against 17 for the 128-bit integer form.  The plaintexts are stored in
 // multiplier form (times 2^64), so the finished sum is multiplied by 2^-64 mod q.
-struct MacFp {
-    double q, qinv;
-    __device__ __forceinline__ double mulmod(double y, double a, double aq) const {
-        double h = y * a;
-        double l = __builtin_fma(y, a, -h);
-        double c = __builtin_rint(y * aq);
-        return __builtin_fma(-c, q, h) + l;
-    }
-    __device__ __forceinline__ double norm(double x) const { return __builtin_fma(-__builtin_rint(x * qinv), q, x); }
-    __device__ __forceinline__ static double from_u64(u64 raw) {                 // raw < 2^52
-        return __longlong_as_double((long long)(raw | 0x4330000000000000ULL)) - 4503599627370496.0;
-    }
-    __device__ __forceinline__ u64 canon(double v) const {                       // |v| < 2^52 -> [0, q)
-        double r = __builtin_fma(-__builtin_floor(v * qinv), q, v);
-        r = r < 0.0 ? r + q : r;
-        r = r >= q ? r - q : r;
-        return (u64)__double_as_longlong(r + 4503599627370496.0) & 0x000FFFFFFFFFFFFFULL;
-    }
-};
 __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, const u64 *__restrict__ babies,
                                                      const u64 *__restrict__ pts, const ModC *__restrict__ modc,
                                                      const FpQ *__restrict__ fpq, int r_i, int r_o, int limbs, int n,

@@ -810,3 +810,37 @@ def test_kv_key_index_appends_and_scores_match_oracle_and_float64(env, r_i, unro
     with pytest.raises(B.CachemirError) as ei:
         plain.export(B.CM_KV_INDEX, 0)
     assert ei.value.status == -1
+
+
+@pytest.mark.parametrize("r_i", [4, 0])
+def test_kv_sv_on_54_bit_primes_matches_oracle(env, r_i):
+    """scores V on a ring whose primes are too long for the FP64 forms: the integer form of the summed tensor products."""
+    from oracle import ckks, packing, params, vmm
+    from paper_2602_11470_amd import inputs
+    B = env["B"]
+    prm = params.toy(n=4096, q0_bits=58, qi_bits=54, scale_bits=54, name="wide")
+    gctx = B.Context(4096, 5, 1, 1, 58, 54, 60, 2.0 ** 54)
+    try:
+        octx = ckks.Context(prm)
+        e = dict(B=B, octx=octx, gctx=gctx, osk=octx.keygen_secret(1), gsk=gctx.keygen_secret(1), prm=prm)
+        H, E, L = 4, 16, prm.L
+        lay = packing.KvLayout(octx.S, H, E, r_i)        # t = 32
+        ntok = 2 * lay.t + 3
+        q, K, V, s = inputs.attention_inputs(33, H, 1, E, ntok)
+        lv = L - 1
+        kv = gctx.kv_create(H, E, lv, r_i=r_i)
+        okeys = octx.keygen_rotations(e["osk"], lay.sv_steps(), 2, with_relin=True)
+        gkeys = gctx.keygen_rotations(e["gsk"], lay.sv_steps(), 2, with_relin=True)
+        ovc = []
+        for k in range(E):
+            ov, gv = _enc_both(e, lay.pack_v(V, k), lv, 300 + k)
+            ovc.append(ov)
+            kv.load(B.CM_SV, k, gv)
+        kv.set_tokens(ntok)
+        os_, gs = _enc_both(e, lay.pack_scores(s), lv, 50)
+        oa = vmm.score_times_v(vmm.CkksOps(octx, okeys), lay, os_, ovc)
+        ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, gs)
+        _same(e, oa, ga)
+        assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
+    finally:
+        gctx.close()
