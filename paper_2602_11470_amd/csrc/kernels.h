@@ -20,7 +20,9 @@ void launch_mac_pt(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *pt_mont, int 
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st);
 // out[z][3][limbs][n] = a (x) b[z], b[z] = b + z*2*limbs*n, z < cnt
 // out[z][3][limbs][n] = sum_{j < cnt} a[j] (x) b[z*cnt + j] for z < groups (a, b stacked ciphertexts [2][limbs][n])
-void launch_tensor_sum(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int groups, int limbs, hipStream_t st);
+// b[z*group_stride + j*term_stride] is term j of group z (0, 0 = groups of cnt consecutive ciphertexts)
+void launch_tensor_sum(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int groups, int limbs, hipStream_t st,
+                       int group_stride = 0, int term_stride = 0);
 void launch_tensor_batch(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int limbs, hipStream_t st);
 void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, hipStream_t st);
 // A[k][2][limbs][n] = sum_{c < nk} T[c] * M[(c + k) mod E], k < shared (2 <= shared <= E, powers of two); T, A stacked

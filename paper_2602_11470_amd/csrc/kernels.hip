@@ -74,8 +74,28 @@ __global__ void k_mul_pt_rot_batch(u64 *__restrict__ out, MulPtBatch b, const u6
     const unsigned s = g ? perm_src(i, g, logn) : i;
     out[((size_t)z * 2 * limbs + r) * n + i] = redc((u128)b.src[z][(size_t)r * n + i] * pt_mont[(size_t)l * n + s], m.q, m.qinv);
 }
+// the same with ONE source for all cnt products: its word is read once and the lane walks over the rotations
+__global__ void k_mul_pt_rot_same(u64 *__restrict__ out, MulPtBatch b, int cnt, const u64 *__restrict__ pt_mont,
+                                  const ModC *__restrict__ modc, int limbs, int n, int logn) {
+    const unsigned i = blockIdx.x * TPB + threadIdx.x;
+    const int r = blockIdx.y, l = r % limbs;
+    const ModC m = modc[l];
+    const u64 v = b.src[0][(size_t)r * n + i];
+    for (int z = 0; z < cnt; z++) {
+        const unsigned g = b.g[z];
+        const unsigned s = g ? perm_src(i, g, logn) : i;
+        out[((size_t)z * 2 * limbs + r) * n + i] = redc((u128)v * pt_mont[(size_t)l * n + s], m.q, m.qinv);
+    }
+}
 void launch_mul_pt_rot_batch(cm_ctx *ctx, u64 *out, const MulPtBatch &b, int cnt, const u64 *pt_mont, int limbs, hipStream_t st) {
     Prof prof_(ctx, CM_K_ELEMENTWISE, cnt * 2 * limbs, st);
+    bool same = cnt > 1;
+    for (int z = 1; z < cnt; z++) same = same && b.src[z] == b.src[0];
+    if (same) {
+        hipLaunchKernelGGL(k_mul_pt_rot_same, dim3(ctx->n / TPB, 2 * limbs), dim3(TPB), 0, st, out, b, cnt, pt_mont, ctx->d_modc,
+                           limbs, ctx->n, ctx->logn);
+        return;
+    }
     hipLaunchKernelGGL(k_mul_pt_rot_batch, dim3(ctx->n / TPB, 2 * limbs, cnt), dim3(TPB), 0, st, out, b, pt_mont, ctx->d_modc,
                        limbs, ctx->n, ctx->logn);
 }
@@ -172,10 +192,12 @@ struct MacFp {
         return (u64)__double_as_longlong(r + 4503599627370496.0) & 0x000FFFFFFFFFFFFFULL;
     }
 };
-// out[z][3][limbs][n] = sum_{j < cnt} a[j] (x) b[z*cnt + j]: a and b stacked at stride 2*limbs*n; every output written once.
+// out[z][3][limbs][n] = sum_{j < cnt} a[j] (x) b[z*gs + j*ts]: a and b stacked at stride 2*limbs*n (gs, ts = the distance of
+// groups and of the terms of a group in b, in ciphertexts); every output written once.
 // On limbs below 2^50 the four products per term run in FP64 (no multiplier form needed), sums renormalised every two terms.
 __global__ void k_tensor_sum(u64 *__restrict__ out, const u64 *__restrict__ a, const u64 *__restrict__ b,
-                             const ModC *__restrict__ modc, const FpQ *__restrict__ fpq, int limbs, int n, int cnt) {
+                             const ModC *__restrict__ modc, const FpQ *__restrict__ fpq, int limbs, int n, int cnt, int gs,
+                             int ts) {
     int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y, z = blockIdx.z;
     const ModC m = modc[l];
     const size_t o = (size_t)l * n + i, cs = (size_t)limbs * n;
@@ -184,7 +206,7 @@ __global__ void k_tensor_sum(u64 *__restrict__ out, const u64 *__restrict__ a, c
         const MacFp F{fq.q, fq.qinv};
         double d0 = 0.0, d1 = 0.0, d2 = 0.0;
         for (int j = 0; j < cnt; j++) {
-            const u64 *aj = a + (size_t)j * 2 * cs, *bj = b + ((size_t)z * cnt + j) * 2 * cs;
+            const u64 *aj = a + (size_t)j * 2 * cs, *bj = b + ((size_t)z * gs + (size_t)j * ts) * 2 * cs;
             const double a0 = MacFp::from_u64(aj[o]), a1 = MacFp::from_u64(aj[o + cs]);
             const double b0 = MacFp::from_u64(__builtin_nontemporal_load(bj + o));
             const double b1 = MacFp::from_u64(__builtin_nontemporal_load(bj + o + cs));
@@ -202,7 +224,7 @@ __global__ void k_tensor_sum(u64 *__restrict__ out, const u64 *__restrict__ a, c
     }
     u64 d0 = 0, d1 = 0, d2 = 0;
     for (int j = 0; j < cnt; j++) {
-        const u64 *aj = a + (size_t)j * 2 * cs, *bj = b + ((size_t)z * cnt + j) * 2 * cs;
+        const u64 *aj = a + (size_t)j * 2 * cs, *bj = b + ((size_t)z * gs + (size_t)j * ts) * 2 * cs;
         const u64 a0 = to_mont(aj[o], m), a1 = to_mont(aj[o + cs], m);
         const u64 b0 = __builtin_nontemporal_load(bj + o), b1 = __builtin_nontemporal_load(bj + o + cs);
         d0 = addmod(d0, redc((u128)a0 * b0, m.q, m.qinv), m.q);
@@ -219,7 +241,7 @@ __global__ void k_tensor_sum(u64 *__restrict__ out, const u64 *__restrict__ a, c
 #define TS_MAX_CNT 16
 __global__ __launch_bounds__(TPB) void k_tensor_sum_stationary(u64 *__restrict__ out, const u64 *__restrict__ a,
                                                                const u64 *__restrict__ b, const FpQ *__restrict__ fpq,
-                                                               int limbs, int n, int cnt, int groups) {
+                                                               int limbs, int n, int cnt, int groups, int gs, int ts) {
     const int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
     const FpQ fq = fpq[l];
     const MacFp F{fq.q, fq.qinv};
@@ -235,7 +257,7 @@ __global__ __launch_bounds__(TPB) void k_tensor_sum_stationary(u64 *__restrict__
 #pragma unroll
         for (int j = 0; j < TS_MAX_CNT; j++) {
             if (j < cnt) {
-                const u64 *bj = b + ((size_t)z * cnt + j) * 2 * cs;
+                const u64 *bj = b + ((size_t)z * gs + (size_t)j * ts) * 2 * cs;
                 const double b0 = MacFp::from_u64(__builtin_nontemporal_load(bj + o));
                 const double b1 = MacFp::from_u64(__builtin_nontemporal_load(bj + o + cs));
                 const double b0q = b0 * F.qinv, b1q = b1 * F.qinv;
@@ -251,17 +273,19 @@ __global__ __launch_bounds__(TPB) void k_tensor_sum_stationary(u64 *__restrict__
         oz[o + 2 * cs] = F.canon(d2);
     }
 }
-void launch_tensor_sum(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int groups, int limbs, hipStream_t st) {
+void launch_tensor_sum(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cnt, int groups, int limbs, hipStream_t st,
+                       int group_stride, int term_stride) {
+    const int gs = group_stride ? group_stride : cnt, ts = term_stride ? term_stride : 1;
     Prof prof_(ctx, CM_K_ELEMENTWISE, 3 * limbs * groups, st);
     bool all_fp = !getenv("CM_NTT_INT");                      // the switch that keeps every limb on the integer forms
     for (int l = 0; l < limbs; l++) all_fp = all_fp && ctx->mod[l] < (1ULL << 50);
     if (all_fp && cnt <= TS_MAX_CNT && groups > 1) {
         hipLaunchKernelGGL(k_tensor_sum_stationary, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, a, b, ctx->d_fpq, limbs, ctx->n,
-                           cnt, groups);
+                           cnt, groups, gs, ts);
         return;
     }
     hipLaunchKernelGGL(k_tensor_sum, dim3(ctx->n / TPB, limbs, groups), dim3(TPB), 0, st, out, a, b, ctx->d_modc, ctx->d_fpq, limbs, ctx->n,
-                       cnt);
+                       cnt, gs, ts);
 }
 void launch_tensor(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int limbs, int accumulate, hipStream_t st) {
     Prof prof_(ctx, CM_K_ELEMENTWISE, 3 * limbs, st);

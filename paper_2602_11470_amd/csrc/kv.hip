@@ -43,7 +43,9 @@ struct cm_kv {
     // the key ciphertexts (d_T), their masked combinations A_k (d_A) and the E slot rotations of the mask (d_M)
     // d_Mhat: the transform of d_M along the copy index (the masked sums as a cyclic correlation), with its twiddles
     // the key index: E ciphertexts like d_v, copy b of ciphertext g r_i + j = dim (b + j) of key group b - g r_i;
-    // query-times-K from it is the scores-times-V schedule with the query in the place of the scores
+    // query-times-K from it is the scores-times-V schedule with the query in the place of the scores.  Ciphertext
+    // g r_i + j is stored at place j r_o + g: the r_o ciphertexts an append makes from ONE rotation of the new key are
+    // then neighbours (one launch reads that rotation once)
     bool indexed = false;
     u64 *d_x = nullptr;
     int shared = 1;
@@ -295,6 +297,7 @@ extern "C" cm_status cm_kv_set_tokens(cm_kv *kv, int32_t ntok) {
 }
 
 static size_t kv_ctw(const cm_kv *kv) { return 2 * (size_t)(kv->level + 1) * kv->ctx->n; }
+static int x_place(const cm_kv *kv, int k) { return (k % kv->r_i) * kv->r_o + k / kv->r_i; }
 
 extern "C" cm_status cm_kv_load(cm_ctx *ctx, cm_kv *kv, int32_t which, int32_t idx, const cm_ct *ct, void *stream) {
     if (!ctx || !kv || kv->ctx != ctx || !ct || !ct->dev || ct->ncomp != 2) return CM_E_INVAL;
@@ -302,7 +305,7 @@ extern "C" cm_status cm_kv_load(cm_ctx *ctx, cm_kv *kv, int32_t which, int32_t i
     if (kv->scale_set && fabs(ct->scale / kv->scale - 1) > 1e-9) return CM_E_SCALE;
     if (which != CM_QK && which != CM_SV && !(which == CM_KV_INDEX && kv->indexed)) return CM_E_INVAL;
     if (idx < 0 || idx >= (which == CM_QK ? kv->nk_max : kv->E)) return CM_E_LAYOUT;
-    u64 *dst = (which == CM_QK ? kv->d_k : which == CM_SV ? kv->d_v : kv->d_x) + (size_t)idx * kv_ctw(kv);
+    u64 *dst = (which == CM_QK ? kv->d_k : which == CM_SV ? kv->d_v : kv->d_x) + (size_t)(which == CM_KV_INDEX ? x_place(kv, idx) : idx) * kv_ctw(kv);
     HIPCHK(hipMemcpyAsync(dst, ct->dev, kv_ctw(kv) * 8, hipMemcpyDeviceToDevice, (hipStream_t)stream));
     kv->scale = ct->scale, kv->scale_set = true;
     return CM_OK;
@@ -312,7 +315,7 @@ extern "C" cm_status cm_kv_export(cm_ctx *ctx, const cm_kv *kv, int32_t which, i
     if (which != CM_QK && which != CM_SV && !(which == CM_KV_INDEX && kv->indexed)) return CM_E_INVAL;
     if (idx < 0 || idx >= (which == CM_QK ? kv->nk_max : kv->E)) return CM_E_LAYOUT;
     cm_ct ct;
-    ct.dev = (which == CM_QK ? kv->d_k : which == CM_SV ? kv->d_v : kv->d_x) + (size_t)idx * kv_ctw(kv);
+    ct.dev = (which == CM_QK ? kv->d_k : which == CM_SV ? kv->d_v : kv->d_x) + (size_t)(which == CM_KV_INDEX ? x_place(kv, idx) : idx) * kv_ctw(kv);
     ct.level = kv->level, ct.ncomp = 2, ct.scale = kv->scale;
     return cm_ct_export(ctx, &ct, out);
 }
@@ -401,7 +404,7 @@ static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_c
             const int m = kv->E - kb < CM_KS_BATCH ? kv->E - kb : CM_KS_BATCH;
             MulPtBatch mb;
             for (int r = 0; r < m; r++) {
-                const int k = kb + r, g = k / kv->r_i, j = k % kv->r_i;
+                const int place = kb + r, j = place / kv->r_o, g = place % kv->r_o;      // index ciphertext g r_i + j
                 const long long a = (long long)((c + g * kv->r_i) % kv->E) * kv->H * kv->t + tau;
                 mb.src[r] = j == 0 ? k_new->dev : shifted + (size_t)(j - 1) * ctw_up;
                 mb.g[r] = (unsigned)rot_g(kv, -a);
@@ -620,7 +623,8 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     // third components raised together, one inner-product launch with the relinearisation key read once, one ModDown
     for (int g0 = 0; g0 < kv->r_o; g0 += CM_KS_BATCH) {
         const int m = kv->r_o - g0 < CM_KS_BATCH ? kv->r_o - g0 : CM_KS_BATCH;
-        launch_tensor_sum(ctx, T, babies, array + (size_t)g0 * kv->r_i * ctw, kv->r_i, m, limbs, st);
+        if (array == kv->d_x) launch_tensor_sum(ctx, T, babies, array + (size_t)g0 * ctw, kv->r_i, m, limbs, st, 1, kv->r_o);
+        else launch_tensor_sum(ctx, T, babies, array + (size_t)g0 * kv->r_i * ctw, kv->r_i, m, limbs, st);
         CMCHK(ks_raise_many(ctx, kv->relin_tabs, T, ksin, bdigits, st, m, 0));
         u64 *bu = arena_batch_sums(ctx);
         IpBatch ip;
