@@ -118,7 +118,9 @@ struct FinishBatch {
     const u64 *pinv = nullptr;        // [level+1][2]: P^{-1} mod q_l and its Shoup companion
 };
 // forward transform of conv[items*ncomp*(level+1)][n] (mods 0..level repeating) with that tail; n = 65536 only
-void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const FinishBatch &fb, hipStream_t st);
+// with src: the first pass reads row d_src_rows[i] of src for limb i (words below twice that limb's modulus) instead of conv
+void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const FinishBatch &fb, hipStream_t st,
+                           const u64 *src = nullptr, const int *d_src_rows = nullptr);
 
 // ops.hip internals shared with vmm.hip
 struct KsLevel {            // cached per level: which rows of the digit array are converted / transformed

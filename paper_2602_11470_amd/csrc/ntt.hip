@@ -479,7 +479,8 @@ void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, c
         hipLaunchKernelGGL(ntt_cols_inv, grid, block, 0, st, data, d_rows, d_mod_idx, t, n, n2);
     }
 }
-void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const FinishBatch &fb, hipStream_t st) {
+void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const FinishBatch &fb, hipStream_t st, const u64 *src,
+                           const int *d_src_rows) {
     const int limbs = fb.items * fb.ncomp * (fb.level + 1), n = ctx->n;
     if (limbs <= 0) return;
     Prof prof_(ctx, CM_K_NTT_FWD, limbs, st);
@@ -488,8 +489,7 @@ void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const Fini
     t.modc = ctx->d_modc, t.fpq = ctx->d_fpq;
     t.tw = ctx->d_tw, t.twp = ctx->d_twp, t.twd = ctx->d_twd, t.twqd = ctx->d_twqd;
     t.ninv = t.ninvp = nullptr, t.ninvd = t.ninvqd = nullptr;
-    hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, conv, (const u64 *)nullptr, (const int *)nullptr,
-                       (const int *)nullptr, d_mods, t, n, n >> 8);
+    hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, conv, src, d_src_rows, (const int *)nullptr, d_mods, t, n, n >> 8);
     hipLaunchKernelGGL(ntt_rows256_fwd, grid, block, 0, st, conv, (const int *)nullptr, d_mods, t, n, fb);
 }
 void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mod_idx, int limbs,

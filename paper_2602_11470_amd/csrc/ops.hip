@@ -45,6 +45,9 @@ struct KsLevelFull : KsLevel {
     int *d_q_mods3 = nullptr;   // 0..level repeated three times
     int *d_last_mods = nullptr; // level, repeated for up to RESCALE_MAX_COMPS components
     int *d_red_mods = nullptr;  // 0..level-1, repeated likewise
+    int *d_red_src = nullptr;   // the component each of those limbs belongs to (its row in the stacked last limbs)
+    bool last_fits = false;     // the last modulus is below twice every other one (and below 2^52): its residues can enter
+                                // the other limbs' transforms as they are
     int *d_last_rows = nullptr; // rows c*(level+1)+level of stacked components
     int *d_bsp_rows = nullptr, *d_bsp_mods = nullptr;   // special rows of CM_KS_BATCH stacked [2][ext] blocks
     int *d_bsp1_rows = nullptr;                         // those of the second components only
@@ -125,15 +128,19 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
     for (int i = 0; i <= level; i++) q_rows.push_back(i);
     for (int c = 0; c < 3; c++)
         for (int i = 0; i <= level; i++) q3.push_back(i);
+    std::vector<int> red_src;
     for (int c = 0; c < RESCALE_MAX_COMPS; c++)
-        for (int i = 0; i < level; i++) red.push_back(i);
-    if (red.empty()) red.push_back(0);
+        for (int i = 0; i < level; i++) red.push_back(i), red_src.push_back(c);
+    if (red.empty()) red.push_back(0), red_src.push_back(0);
+    k.last_fits = ctx->mod[level] < (1ULL << 52);
+    for (int i = 0; i < level; i++) k.last_fits = k.last_fits && ctx->mod[level] < 2 * ctx->mod[i];
     k.d_sp_rows = up(sp_rows);
     k.d_sp_mods = up(sp_mods);
     k.d_q_rows = up(q_rows);
     k.d_q_mods3 = up(q3);
     k.d_last_mods = up(last);
     k.d_red_mods = up(red);
+    k.d_red_src = up(red_src);
     {
         std::vector<int> br, bm, bq;
         for (int r = 0; r < CM_KS_BATCH; r++)
@@ -179,7 +186,7 @@ static void drop_ks_levels(cm_ctx *ctx) {
         hipFree(k.d_modup); hipFree(k.d_moddown); hipFree(k.d_bsp_rows); hipFree(k.d_bsp1_rows); hipFree(k.d_sp1_rows); hipFree(k.d_moddown0); hipFree(k.d_bsp_mods); hipFree(k.d_bq_mods);
         hipFree(k.d_last_rows);
         hipFree(k.d_ntt_rows); hipFree(k.d_ntt_mods); hipFree(k.d_sp_rows); hipFree(k.d_sp_mods);
-        hipFree(k.d_q_rows); hipFree(k.d_q_mods3); hipFree(k.d_last_mods); hipFree(k.d_red_mods);
+        hipFree(k.d_q_rows); hipFree(k.d_q_mods3); hipFree(k.d_last_mods); hipFree(k.d_red_mods); hipFree(k.d_red_src);
         it = g_ks.erase(it);
     }
 }
@@ -809,8 +816,12 @@ cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *ou
     if (!last) last = A.misc;
     if (!red) red = A.tmp[2];
     launch_ntt_src(ctx, last, nullptr, in, k.d_last_rows, k.d_last_mods, ncomp, true, st);
-    launch_rescale_reduce(ctx, red, last, ncomp, level, st);
-    if (ctx->n == 65536 && ncomp % 2 == 0) {
+    const bool fused = ctx->n == 65536 && ncomp % 2 == 0;
+    // the residues of the last limb enter the transforms of the other limbs reduced to their moduli; where the last
+    // modulus is below twice the others the first pass of the fused transform takes them as they are (the transform is
+    // linear and its output canonical, so the result is the same) and the reduction pass is not run
+    if (!(fused && k.last_fits)) launch_rescale_reduce(ctx, red, last, ncomp, level, st);
+    if (fused) {
         // the tail (in - NTT(red)) q_level^{-1} (+ out) rides on the last pass of the transform of red: the same tail as a
         // ModDown's, with `level` output rows and level+1 input rows per component and q_level^{-1} for P^{-1}
         FinishBatch fb;
@@ -821,7 +832,8 @@ cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *ou
             fb.accum[r] = accumulate ? fb.out[r] : nullptr;
         }
         fb.pinv = get_qlinv(ctx, level);
-        launch_ntt_fwd_finish(ctx, red, k.d_red_mods, fb, st);
+        if (k.last_fits) launch_ntt_fwd_finish(ctx, red, k.d_red_mods, fb, st, last, k.d_red_src);
+        else launch_ntt_fwd_finish(ctx, red, k.d_red_mods, fb, st);
         return CM_OK;
     }
     launch_ntt(ctx, red, k.d_red_mods, ncomp * level, false, st);
