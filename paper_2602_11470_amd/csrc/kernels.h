@@ -13,6 +13,8 @@ struct MulPtBatch {
     unsigned g[CM_KS_BATCH];
 };
 void launch_mul_pt_rot_batch(cm_ctx *ctx, u64 *out, const MulPtBatch &b, int cnt, const u64 *pt_mont, int limbs, hipStream_t st);
+// the same products on the last of the `limbs` limbs only: out[z][2][n]
+void launch_mul_pt_rot_last(cm_ctx *ctx, u64 *out, const MulPtBatch &b, int cnt, const u64 *pt_mont, int limbs, hipStream_t st);
 // acc[2][limbs][n] (+)= sum_{z<cnt} src[z] * (pt rotated by b.g[z]), src[z] = src + z*2*limbs*n (b.src unused)
 void launch_mac_pt_rot_batch(cm_ctx *ctx, u64 *acc, const u64 *src, const MulPtBatch &b, int cnt, const u64 *pt_mont,
                              int limbs, int accumulate, hipStream_t st);
@@ -116,6 +118,10 @@ struct FinishBatch {
     unsigned g[CM_KS_BATCH];
     const u64 *addend[CM_KS_BATCH];   // [2][level+1][n] per item, nullable; must not alias any out
     const u64 *pinv = nullptr;        // [level+1][2]: P^{-1} mod q_l and its Shoup companion
+    // u_r is not stored but formed on the fly as u[r] * (mul_pt read through the Galois map mul_g[r]): the masked
+    // products of a cache append, whose rescale is this tail (mul_pt[ext][n], multiplier form; nullable)
+    const u64 *mul_pt = nullptr;
+    unsigned mul_g[CM_KS_BATCH] = {};
 };
 // forward transform of conv[items*ncomp*(level+1)][n] (mods 0..level repeating) with that tail; n = 65536 only
 // with src: the first pass reads row d_src_rows[i] of src for limb i (words below twice that limb's modulus) instead of conv
@@ -123,6 +129,8 @@ void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const Fini
                            const u64 *src = nullptr, const int *d_src_rows = nullptr);
 
 // ops.hip internals shared with vmm.hip
+bool rescale_masked_into(cm_ctx *ctx, const MulPtBatch &mb, int cnt, const u64 *pt, int level, u64 *out, hipStream_t st,
+                         u64 *last, u64 *red, bool accumulate);
 struct KsLevel {            // cached per level: which rows of the digit array are converted / transformed
     int level, ext, beta;
     int *d_ntt_rows = nullptr;        // rows of the [beta*ext] digit array to transform

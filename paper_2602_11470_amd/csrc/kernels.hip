@@ -74,6 +74,20 @@ __global__ void k_mul_pt_rot_batch(u64 *__restrict__ out, MulPtBatch b, const u6
     const unsigned s = g ? perm_src(i, g, logn) : i;
     out[((size_t)z * 2 * limbs + r) * n + i] = redc((u128)b.src[z][(size_t)r * n + i] * pt_mont[(size_t)l * n + s], m.q, m.qinv);
 }
+__global__ void k_mul_pt_rot_last(u64 *__restrict__ out, MulPtBatch b, const u64 *__restrict__ pt_mont,
+                                  const ModC *__restrict__ modc, int limbs, int n, int logn) {
+    const unsigned i = blockIdx.x * TPB + threadIdx.x;
+    const int c = blockIdx.y, z = blockIdx.z, l = limbs - 1;
+    const ModC m = modc[l];
+    const unsigned g = b.g[z];
+    const unsigned s = g ? perm_src(i, g, logn) : i;
+    out[((size_t)z * 2 + c) * n + i] = redc((u128)b.src[z][((size_t)c * limbs + l) * n + i] * pt_mont[(size_t)l * n + s], m.q, m.qinv);
+}
+void launch_mul_pt_rot_last(cm_ctx *ctx, u64 *out, const MulPtBatch &b, int cnt, const u64 *pt_mont, int limbs, hipStream_t st) {
+    Prof prof_(ctx, CM_K_ELEMENTWISE, cnt * 2, st);
+    hipLaunchKernelGGL(k_mul_pt_rot_last, dim3(ctx->n / TPB, 2, cnt), dim3(TPB), 0, st, out, b, pt_mont, ctx->d_modc, limbs, ctx->n,
+                       ctx->logn);
+}
 // the same with ONE source for all cnt products: its word is read once and the lane walks over the rotations
 __global__ void k_mul_pt_rot_same(u64 *__restrict__ out, MulPtBatch b, int cnt, const u64 *__restrict__ pt_mont,
                                   const ModC *__restrict__ modc, int limbs, int n, int logn) {

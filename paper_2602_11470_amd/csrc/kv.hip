@@ -379,8 +379,10 @@ static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_c
             mb.src[r] = g == 0 ? v_new->dev : shifted + (size_t)(g - 1) * ctw_up;
             mb.g[r] = (unsigned)rot_g(kv, -a);
         }
-        launch_mul_pt_rot_batch(ctx, prods, mb, m, group ? kv->d_mask_vg : kv->d_mask_v, lv + 1, st);
         // consecutive value ciphertexts are contiguous: the rescale adds its result onto them
+        const u64 *vmask = group ? kv->d_mask_vg : kv->d_mask_v;
+        if (rescale_masked_into(ctx, mb, m, vmask, lv, kv->d_v + (size_t)kb * ctw, st, last, red, true)) continue;
+        launch_mul_pt_rot_batch(ctx, prods, mb, m, vmask, lv + 1, st);
         CMCHK(rescale_into(ctx, prods, 2 * m, lv, kv->d_v + (size_t)kb * ctw, st, last, red, true));
     }
     if (kv->indexed) {
@@ -409,7 +411,9 @@ static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_c
                 mb.src[r] = j == 0 ? k_new->dev : shifted + (size_t)(j - 1) * ctw_up;
                 mb.g[r] = (unsigned)rot_g(kv, -a);
             }
-            launch_mul_pt_rot_batch(ctx, xp, mb, m, group ? kv->d_mask_vg : kv->d_mask_v, lv + 1, st);
+            const u64 *xmask = group ? kv->d_mask_vg : kv->d_mask_v;
+            if (rescale_masked_into(ctx, mb, m, xmask, lv, kv->d_x + (size_t)kb * ctw, st, xl, xd, true)) continue;
+            launch_mul_pt_rot_batch(ctx, xp, mb, m, xmask, lv + 1, st);
             CMCHK(rescale_into(ctx, xp, 2 * m, lv, kv->d_x + (size_t)kb * ctw, st, xl, xd, true));
         }
     }

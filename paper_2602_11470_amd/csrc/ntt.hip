@@ -319,6 +319,21 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
     u64 *op = fb.out[r] + row + pos0;
     const unsigned g = fb.g[r];
     const int logn = 31 - __clz(n);
+    if (fb.mul_pt) {
+        // u = u[r] * (mul_pt through the Galois map mul_g[r]), formed here instead of being read
+        const u64 qinv = t.modc[l].qinv;
+        const u64 *mp = fb.mul_pt + (size_t)l * n;
+        const unsigned mg = fb.mul_g[r];
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const unsigned pos = pos0 + 256 * k;
+            const u64 uv = redc((u128)up[256 * k] * mp[mg ? perm_src(pos, mg, logn) : pos], q, qinv);
+            u64 x = mul_shoup(submod(uv, lds[pad(threadIdx.x + 256 * k)], q), pi, pis, q);
+            if (ac) x = addmod(x, ac[256 * k], q);
+            op[256 * k] = x;
+        }
+        return;
+    }
 #pragma unroll
     for (int k = 0; k < 16; k++) {
         u64 d = submod(up[256 * k], lds[pad(threadIdx.x + 256 * k)], q);

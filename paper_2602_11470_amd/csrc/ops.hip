@@ -840,6 +840,29 @@ cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *ou
     launch_rescale_finish(ctx, out, in, red, get_qlinv(ctx, level), ncomp, level, st, accumulate);
     return CM_OK;
 }
+// out[r] (+)= rescale(src_r * (pt through the Galois map g_r)) for r < cnt, src_r = mb.src[r] ([2][level+1][n]), out
+// stacked at stride 2*level*n: the products are never stored; only their last limbs are formed (for the inverse
+// transform), the others inside the tail of the forward transform.  Only where rescale_into would take its fused path
+// and the last limb's residues fit (returns false otherwise: the caller multiplies and rescales in two steps).
+bool rescale_masked_into(cm_ctx *ctx, const MulPtBatch &mb, int cnt, const u64 *pt, int level, u64 *out, hipStream_t st,
+                         u64 *last, u64 *red, bool accumulate) {
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    if (ctx->n != 65536 || !k.last_fits || cnt < 1 || cnt > CM_KS_BATCH || !last || !red) return false;
+    if (getenv("CM_TWO_STEP_MASKS")) return false;          // parity switch: multiply, store, then rescale
+    launch_mul_pt_rot_last(ctx, last, mb, cnt, pt, level + 1, st);
+    launch_ntt(ctx, last, k.d_last_mods, 2 * cnt, true, st);
+    FinishBatch fb;
+    fb.items = cnt, fb.level = level - 1, fb.ext = level + 1, fb.addend_comps = 0, fb.ncomp = 2, fb.comp0 = 0;
+    for (int r = 0; r < CM_KS_BATCH; r++) fb.addend[r] = nullptr, fb.accum[r] = nullptr, fb.u[r] = nullptr, fb.out[r] = nullptr, fb.g[r] = 0;
+    for (int r = 0; r < cnt; r++) {
+        fb.u[r] = mb.src[r], fb.out[r] = out + (size_t)r * 2 * level * ctx->n, fb.mul_g[r] = mb.g[r];
+        fb.accum[r] = accumulate ? fb.out[r] : nullptr;
+    }
+    fb.mul_pt = pt;
+    fb.pinv = get_qlinv(ctx, level);
+    launch_ntt_fwd_finish(ctx, red, k.d_red_mods, fb, st, last, k.d_red_src);
+    return true;
+}
 extern "C" cm_status cm_rescale(cm_ctx *ctx, const cm_ct *a, cm_ct *out, void *stream) {
     if (!ctx || !ct_ok(ctx, a) || !out || !out->dev) return CM_E_INVAL;
     if (a->level < 1) return CM_E_LEVEL;

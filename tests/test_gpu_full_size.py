@@ -345,6 +345,44 @@ def test_prompt_phase_attention_of_a_query_group_on_the_full_ring(ring2):
         assert np.abs(lay.unpack_vec(res, tau) - want[tau]).max() < TOL
 
 
+def test_appends_with_the_masked_product_inside_the_rescale_equal_the_two_step_appends(ring2):
+    """At n = 2^16 an append forms its masked products inside the tail of the rescale's transform; with
+    CM_TWO_STEP_MASKS in the environment it multiplies, stores and rescales (the path the small-ring tests
+    check limb for limb against the oracle).  Same cache, same key index, bit for bit: one token group and
+    two single tokens."""
+    import os
+    from oracle import packing
+    B, octx, gctx, prm = ring2
+    H, E, lv = 32, 128, 4
+    lay = packing.KvLayout(gctx.S, H, E, 16)
+    rng = np.random.default_rng(77)
+    gsk = gctx.keygen_secret(1)
+    enc = lambda slots, level, seed: gctx.level_drop(gctx.encrypt(gsk, gctx.encode(slots, gctx.L), seed), level)
+    news = [(enc(rng.normal(size=gctx.S), lv + 1, 900 + 2 * i), enc(rng.normal(size=gctx.S), lv + 1, 901 + 2 * i)) for i in range(3)]
+    caches = []
+    keys = None
+    for two_step in (False, True):
+        kv = gctx.kv_create(H, E, lv, r_i=16, key_index=True)
+        if keys is None:
+            keys = gctx.keygen_rotations(gsk, kv.steps(), 2, with_relin=True)
+        if two_step:
+            os.environ["CM_TWO_STEP_MASKS"] = "1"
+        try:
+            kv.append_group(keys, *news[0])
+            kv.append(keys, *news[1])
+            kv.append(keys, *news[2])
+        finally:
+            os.environ.pop("CM_TWO_STEP_MASKS", None)
+        caches.append(kv)
+    a, b = caches
+    assert a.tokens() == b.tokens() == lay.t + 2
+    for k in (0, 1, 17, E - 1):
+        assert np.array_equal(a.export(B.CM_SV, k), b.export(B.CM_SV, k)), k
+        assert np.array_equal(a.export(B.CM_KV_INDEX, k), b.export(B.CM_KV_INDEX, k)), k
+    assert np.array_equal(a.export(B.CM_QK, 0), b.export(B.CM_QK, 0))
+    assert np.array_equal(a.export(B.CM_QK, 1), b.export(B.CM_QK, 1))
+
+
 def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
     """Two decode steps of one Llama-3-8B-shaped layer's linear path on the 36 + 6 prime ring: k / v /
     q projections (8 KV heads replicated to 32 by repeating weight columns, columns ordered as the
