@@ -242,11 +242,13 @@ def test_config3_attention_shapes_decrypt_to_float64_products(ring2, unrolled, s
     assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
 
 
-def test_prompt_phase_on_the_full_ring_builds_a_cache_the_decode_products_can_use(ring2):
+@pytest.mark.parametrize("index", [False, True])
+def test_prompt_phase_on_the_full_ring_builds_a_cache_the_decode_products_can_use(ring2, index):
     """Sec. 5.4 at Llama-3-8B shapes: two ciphertexts of t = 8 tokens each go through the token-batched
     4096 x 4096 k and v projections (4096 diagonals, 128 baby x 32 giant steps, columns ordered (e, h)),
     the rotary embedding of a token group and the group append; then the decode-phase q K^T and
-    scores V run against that cache.  Everything is compared with the float64 computation."""
+    scores V run against that cache.  Everything is compared with the float64 computation.  index: the cache
+    also keeps the key index, which the group appends extend and q K^T then runs on."""
     from oracle import packing
     B, octx, gctx, prm = ring2
     H, E, d = 32, 128, 4096
@@ -262,7 +264,7 @@ def test_prompt_phase_on_the_full_ring_builds_a_cache_the_decode_products_can_us
     pk = gctx.vmm_plan(d, d, W=Wk, level=lvx, direct_giants=True, token_batch=True)
     pv = gctx.vmm_plan(d, d, W=Wv, level=lvx, direct_giants=True, token_batch=True)
     assert (pk.r_i, pk.r_o, pk.n_rotations) == (128, 32, 158)
-    kv = gctx.kv_create(H, E, lv, r_i=16)
+    kv = gctx.kv_create(H, E, lv, r_i=16, key_index=index)
     ropes = [gctx.rope(H, E, lvx - 1, c * t, tau=-1) for c in range(groups)]
     steps = sorted(set(pk.steps()) | set(kv.steps()) | set(ropes[0].steps()))
     gkeys = gctx.keygen_rotations(gsk, steps, 2, with_relin=True)
