@@ -27,7 +27,14 @@ from .native import lib, p as _p, pi as _pi
 from .params import Params
 
 # stream identifiers of the counter-based generator: purpose in the top byte
-ST_SECRET, ST_EVK_A, ST_EVK_E, ST_ENC_A, ST_ENC_E = 1, 2, 3, 4, 5
+ST_SECRET, ST_EVK_A, ST_EVK_E, ST_ENC_A, ST_ENC_E, ST_NOISE = 1, 2, 3, 4, 5, 6
+# Which seed keys which stream.  The seed given to keygen_rotations / encrypt is PUBLIC: the uniform
+# halves (a_j of a key, c1 of a ciphertext) are its streams, and the generator's finaliser is a
+# bijection, so anything derived from it alone can be recomputed by whoever holds the key or the
+# ciphertext.  The error polynomials are therefore drawn from the streams of (seed XOR noise), where
+# noise = key(secret key's seed, ST_NOISE) is a 64-bit value only the holder of the secret key has.
+# The generator is a reproducibility device (both implementations must draw identical values), not
+# a cryptographic one.
 RELIN_ID = 0  # evaluation-key identifier of s^2 -> s (Galois elements are odd, never 0)
 
 
@@ -246,7 +253,8 @@ class Context:
     def keygen_secret(self, seed):
         s = self.sample_secret(seed)
         all_idx = list(range(len(self.mod)))
-        return {"coeffs": s, "ntt": self.ntt(self.from_i64(s, all_idx), all_idx)}
+        return {"coeffs": s, "ntt": self.ntt(self.from_i64(s, all_idx), all_idx),
+                "noise": lib.orc_rng_key(seed, stream_id(ST_NOISE))}
 
     def _uniform(self, idx, seed, purpose, ident=0, digit=0):
         out = np.empty((len(idx), self.n), dtype=np.uint64)
@@ -269,7 +277,8 @@ class Context:
         psi^(2k+1) is draw brev(k) of its stream (the draws fill the bit-reversed order in which an
         in-place transform leaves its output).  The transform is a bijection, so this is the same
         distribution as drawing coefficients, and an implementation may then regenerate a_j from the
-        seed wherever it is used instead of storing it."""
+        seed wherever it is used instead of storing it.  The errors e_j come from the streams of
+        seed XOR sk["noise"], which the public seed does not determine."""
         prm, all_idx = self.prm, list(range(len(self.mod)))
         P = 1
         for m in prm.p:
@@ -278,7 +287,7 @@ class Context:
         bs, as_ = [], []
         for j, D in enumerate(digits):
             a = self._uniform(all_idx, seed, ST_EVK_A, ident, j)[:, self.brev]
-            e = self.ntt(self.from_i64(self._gauss(seed, ST_EVK_E, ident, j), all_idx), all_idx)
+            e = self.ntt(self.from_i64(self._gauss(seed ^ sk["noise"], ST_EVK_E, ident, j), all_idx), all_idx)
             b = self.sub(e, self.mul(a, sk["ntt"], all_idx), all_idx)
             fac = [P % int(self.mod[i]) if i in D else 0 for i in all_idx]
             b = self.add(b, self.mul_scalar(s_from_ntt, fac, all_idx), all_idx)
@@ -301,10 +310,11 @@ class Context:
 
     # ---- encrypt / decrypt -----------------------------------------------------------
     def encrypt(self, sk, pt: Pt, seed) -> Ct:
-        """Symmetric encryption (c0, c1) = (-a s + e + m, a)."""
+        """Symmetric encryption (c0, c1) = (-a s + e + m, a); a from the streams of the (public)
+        seed, e from those of seed XOR sk["noise"]."""
         idx = self.q_idx(pt.level)
         a = self.ntt(self._uniform(idx, seed, ST_ENC_A), idx)
-        e = self.ntt(self.from_i64(self._gauss(seed, ST_ENC_E), idx), idx)
+        e = self.ntt(self.from_i64(self._gauss(seed ^ sk["noise"], ST_ENC_E), idx), idx)
         c0 = self.add(self.sub(e, self.mul(a, sk["ntt"][idx], idx), idx), pt.m, idx)
         return Ct([c0, a], pt.level, pt.scale)
 

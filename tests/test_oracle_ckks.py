@@ -82,6 +82,7 @@ def test_decrypt_of_encrypt_and_noise_size(mid):
     noise = np.array(ctx.decrypt_coeffs(sk, ct), dtype=np.float64) - ctx.encode_coeffs(z, pt.scale)
     assert abs(noise.std() - ctx.prm.sigma) < 0.2        # c0 + c1 s - m = e exactly
     assert np.abs(noise).max() <= 19
+    assert np.array_equal(noise.astype(np.int64), ctx._gauss(11 ^ sk["noise"], ckks.ST_ENC_E))
     # c1 is the uniform sample itself, in the coefficient domain
     can = ctx.canonical(ct)
     assert np.array_equal(can[1], ctx._uniform(ctx.q_idx(ctx.prm.L), 11, ckks.ST_ENC_A))
@@ -161,7 +162,7 @@ def test_evaluation_key_structure(small):
     assert evk.b.shape == (len(digits), len(all_idx), ctx.n)
     for j, D in enumerate(digits):
         lhs = ctx.intt(ctx.add(evk.b[j], ctx.mul(evk.a[j], sk["ntt"], all_idx), all_idx), all_idx)
-        e = ctx._gauss(9, ckks.ST_EVK_E, g, j)
+        e = ctx._gauss(9 ^ sk["noise"], ckks.ST_EVK_E, g, j)      # the errors: streams of seed XOR the secret key's value
         for i in all_idx:
             q = int(ctx.mod[i])
             want = [(int(e[c]) + (P * int(s_from[i, c]) if i in D else 0)) % q
@@ -246,3 +247,51 @@ def test_single_digit_with_one_special_prime_does_not_decrypt():
     z = np.random.default_rng(0).uniform(-1, 1, ctx.S)
     ct = ctx.encrypt(sk, ctx.encode(z, prm.L), 3)
     assert np.abs(ctx.decrypt(sk, ctx.rotate(ct, 1, keys)) - np.roll(z, -1)).max() > 1e6
+
+
+def _unmix(z):
+    """Inverse of the generator's finaliser (the SplitMix64 output function is a bijection on 64-bit words)."""
+    M = (1 << 64) - 1
+
+    def unshift(v, s):
+        out = v
+        for _ in range(64 // s + 1):
+            out = v ^ (out >> s)
+        return out
+    z = unshift(z, 31)
+    z = z * pow(0x94D049BB133111EB, -1, 1 << 64) & M
+    z = unshift(z, 27)
+    z = z * pow(0xBF58476D1CE4E5B9, -1, 1 << 64) & M
+    return unshift(z, 30)
+
+
+def test_the_public_seed_does_not_give_the_error_streams(small):
+    """What an evaluation key or a ciphertext publishes (the uniform half, hence its stream key, hence --
+    the finaliser being invertible -- the seed of the call) must not determine the error polynomials: they
+    are the streams of seed XOR a value derived from the SECRET key's seed."""
+    from oracle.native import lib
+    ctx, sk = small
+    seed, g = 0x1234, ctx.galois(3)
+    # the attack the plain scheme allowed: stream key of a_0 -> mix(seed) -> seed
+    stream = ckks.stream_id(ckks.ST_EVK_A, g, 0, 0)
+    key = lib.orc_rng_key(seed, stream)
+    assert _unmix(_unmix(key) ^ stream) == seed
+    evk = ctx.keygen_rotations(sk, [3], seed)[g]
+    all_idx = list(range(len(ctx.mod)))
+    s_from = ctx.automorphism_coeff(ctx.from_i64(sk["coeffs"], all_idx), all_idx, g)
+    P = math.prod(ctx.prm.p)
+    D = ctx.prm.digits(ctx.prm.L)[0]
+    lhs = ctx.intt(ctx.add(evk.b[0], ctx.mul(evk.a[0], sk["ntt"], all_idx), all_idx), all_idx)
+    q0 = int(ctx.mod[0])
+    e_true = [(int(lhs[0, c]) - P * int(s_from[0, c])) % q0 for c in range(ctx.n)]
+    e_true = [v - q0 if v > q0 // 2 else v for v in e_true]
+    assert 0 in D
+    assert e_true == ctx._gauss(seed ^ sk["noise"], ckks.ST_EVK_E, g, 0).tolist()
+    assert e_true != ctx._gauss(seed, ckks.ST_EVK_E, g, 0).tolist()          # the recovered seed alone is not enough
+    # the value mixed in belongs to the secret key: another secret, other errors under the same public seed
+    sk2 = ctx.keygen_secret(4)
+    assert sk2["noise"] != sk["noise"] and sk["noise"] == lib.orc_rng_key(3, ckks.stream_id(ckks.ST_NOISE))
+    ct1, ct2 = ctx.encrypt(sk, ctx.encode(np.zeros(ctx.S), 2), 77), ctx.encrypt(sk2, ctx.encode(np.zeros(ctx.S), 2), 77)
+    assert np.array_equal(ct1.c[1], ct2.c[1])                                 # same public half
+    n1 = np.array(ctx.decrypt_coeffs(sk, ct1)), np.array(ctx.decrypt_coeffs(sk2, ct2))
+    assert not np.array_equal(n1[0], n1[1])

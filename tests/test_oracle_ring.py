@@ -41,6 +41,20 @@ def test_prime_chain_rule():
         assert all((q - 1) % (2 * n) == 0 and q < (1 << bits) for q in got)
 
 
+def test_prime_chain_anchor_values():
+    """Values of the chains of the benchmark configurations, computed once by an independent scan (plain
+    trial of 2^bits + 1 - k 2n with a general-purpose primality test) and written here as constants."""
+    c1 = params.config1()
+    assert c1.q == [1125899906826241, 1099511480321, 1099511390209, 1099511259137, 1099511111681]
+    assert c1.p == [1152921504606830593]
+    c5 = params.config5()
+    assert c5.q[:3] == [1125899903827969, 1125899902124033, 1125899887312897]
+    assert c5.q[23] == 1125899843665921 and c5.q[35] == 1125899822694401
+    assert c5.p[:2] == [1152921504606584833, 1152921504598720513]
+    c2 = params.config2()
+    assert c2.q == c5.q[:24] and c2.p == c5.p[:4]
+
+
 def test_config_shapes():
     c1 = params.config1()
     assert [q.bit_length() for q in c1.q] == [50, 40, 40, 40, 40] and len(c1.p) == 1
