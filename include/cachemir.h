@@ -20,7 +20,19 @@
  *    cm_ct_export() gives the canonical interchange form: coefficient domain, residues in
  *    [0, q_i), order [component][limb][coefficient].
  *  - `stream` is a hipStream_t passed as void* (0 = the null stream).  Calls that take a
- *    stream only enqueue work; the others synchronise.
+ *    stream only enqueue work (kernels and device-to-device copies; no allocation, no host copy,
+ *    no wait).  The others (keys, encode, encrypt, decrypt, decode, exports, plan / cache /
+ *    embedding creation) run on the null stream: they first wait for all work the device has in
+ *    flight and return when their result is complete.
+ *  - No call reads the process environment; behaviour switches are cm_ctx_set_option() values,
+ *    plan flags or cache flags, all declared here.
+ *  - Randomness is a counter-based generator on 64-bit integers (SplitMix64's finaliser; stream =
+ *    purpose, key id, digit, limb) so that two implementations draw identical values from a seed.
+ *    It makes results reproducible; it is NOT a cryptographically secure generator.  The seed
+ *    passed to cm_keygen_rotations / cm_encrypt is public (the uniform halves are its streams and
+ *    can be recomputed from the key or ciphertext); the error polynomials are drawn from the
+ *    streams of that seed XOR a 64-bit value derived from the SECRET key's seed, which must
+ *    therefore be kept private and must not be reused as a public seed.
  *  - A context's scratch arena is shared by all calls on it: calls on one context must not
  *    overlap in time (enqueue them on one stream, or order the streams).  A plan, a cache and
  *    a rotary-embedding object each hold one work area of their own with the same rule.
@@ -95,6 +107,17 @@ typedef struct {
  * arena.  Uses the current HIP device. */
 cm_status cm_ctx_create(const cm_params *p, cm_ctx **out);
 void cm_ctx_destroy(cm_ctx *ctx);
+/* Behaviour switches of a context (host call, takes effect for later calls; unknown option: CM_E_INVAL).
+ *   CM_OPT_EVK_STORED_A  value != 0: evaluation keys generated from now on keep BOTH halves in device
+ *     memory (b_j and a_j, 2 (L+1+K) n words per digit) and the key-switch kernels read a_j; 0 (default):
+ *     only b_j is kept and the kernels regenerate a_j from its stream.  Same residues either way, hence
+ *     bit-identical results.  A key set can only be used while the option has the value it was generated
+ *     under (else CM_E_INVAL).
+ *   CM_OPT_TWO_STEP_MASKS  value != 0: cm_kv_append(_group) forms its masked products as stored
+ *     ciphertexts and rescales them afterwards, instead of forming them inside the rescale's transform
+ *     (n = 65536 only; a cross-check of that fused path, bit-identical results). */
+enum { CM_OPT_EVK_STORED_A = 1, CM_OPT_TWO_STEP_MASKS = 2 };
+cm_status cm_ctx_set_option(cm_ctx *ctx, int32_t option, int32_t value);
 /* host out[n_q + n_p]: q_0..q_L then p_0..p_{K-1}. */
 cm_status cm_ctx_moduli(const cm_ctx *ctx, uint64_t *out);
 size_t cm_ct_words(const cm_ctx *ctx, int32_t level, int32_t ncomp);
@@ -112,7 +135,8 @@ cm_status cm_sk_coeffs(const cm_ctx *ctx, const cm_sk *sk, int8_t *out);
  * b_j = -a_j s + e_j + P s_from on the digit's own limbs; a_j is uniform and drawn directly in the
  * evaluation domain (its value at psi^(2k+1) is draw brev(k) of the counter-based generator's stream
  * for (seed, key, digit, limb)), so only the b_j are kept in device memory, (L+1+K) n words per
- * digit, and the kernels regenerate a_j where they use it. */
+ * digit, and the kernels regenerate a_j where they use it (CM_OPT_EVK_STORED_A keeps a_j too).  `seed`
+ * is public; e_j is drawn from the streams of seed XOR the secret key's private value. */
 cm_status cm_keygen_rotations(cm_ctx *ctx, const cm_sk *sk, const int32_t *steps, size_t nsteps,
                               int32_t with_relin, uint64_t seed, cm_evk **out);
 void cm_evk_destroy(cm_evk *evk);
@@ -132,7 +156,8 @@ cm_status cm_pt_from_coeffs(cm_ctx *ctx, const int64_t *coeffs, int32_t level, d
                             cm_pt *out);
 cm_status cm_encode(cm_ctx *ctx, const double *re, const double *im, size_t nslots,
                     int32_t level, double scale, cm_pt *out);
-/* Symmetric encryption (c0, c1) = (-a s + e + m, a); pt must have mont == 0. */
+/* Symmetric encryption (c0, c1) = (-a s + e + m, a); pt must have mont == 0.  a: streams of `seed` (public),
+ * e: streams of seed XOR the secret key's private value. */
 cm_status cm_encrypt(cm_ctx *ctx, const cm_sk *sk, const cm_pt *pt, uint64_t seed, cm_ct *out);
 /* c0 + c1 s (+ c2 s^2) on the lowest min(level,1)+1 limbs -> out (mont = 0). */
 cm_status cm_decrypt(cm_ctx *ctx, const cm_sk *sk, const cm_ct *ct, cm_pt *out);
@@ -144,7 +169,8 @@ cm_status cm_pt_export(cm_ctx *ctx, const cm_pt *pt, uint64_t *out);
 
 /* ---- ciphertext operations of Sec. 2.1 ------------------------------------------------ */
 cm_status cm_add(cm_ctx *ctx, const cm_ct *a, const cm_ct *b, cm_ct *out, void *stream);
-/* out = a * pt (pt->mont must be 1); scale multiplies, level unchanged (rescale separately). */
+/* out = a * pt (pt->mont must be 1); scale multiplies, level unchanged (rescale separately).  Level 0
+ * (nothing left to rescale into): CM_E_LEVEL, as for cm_mul_ct. */
 cm_status cm_mul_pt(cm_ctx *ctx, const cm_ct *a, const cm_pt *pt, cm_ct *out, void *stream);
 /* Tensor product, three components, not relinearised. */
 cm_status cm_mul_ct(cm_ctx *ctx, const cm_ct *a, const cm_ct *b, cm_ct *out, void *stream);
@@ -352,7 +378,9 @@ cm_status cm_inner_rot_create(cm_ctx *ctx, int32_t t, int32_t delta, int32_t lev
 
 /* ---- building blocks exposed for measurement and parity -------------------------------- */
 /* Forward / inverse negacyclic NTT of `limbs` limbs in place (device), limb i under modulus
- * index mod_idx[i] (host array; indices into q_0..q_L,p_0..); 1 <= limbs <= 1024. */
+ * index mod_idx[i] (host array, read before the call returns; indices into q_0..q_L,p_0..);
+ * 1 <= limbs <= 1024.  Enqueues only (a list that is not a run of consecutive indices is written into
+ * a per-context staging array by a small kernel: two such calls on different streams must be ordered). */
 cm_status cm_ntt(cm_ctx *ctx, uint64_t *dev, const int32_t *mod_idx, int32_t limbs,
                  int32_t inverse, void *stream);
 /* One hybrid key switch of an evaluation-domain polynomial d[level+1][n] (device) with the key

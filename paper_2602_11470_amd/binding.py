@@ -20,6 +20,7 @@ lib = C.CDLL(LIB_PATH)
 CM_QK, CM_SV, CM_QK_GROUP, CM_SV_GROUP, CM_KV_INDEX = 0, 1, 2, 3, 4
 CM_VMM_RAISED_SUMS, CM_VMM_DIRECT_GIANTS, CM_VMM_TOKEN_BATCH, CM_VMM_UNROLLED_LADDERS = 1, 2, 4, 8
 CM_KV_UNROLLED_LADDERS, CM_KV_KEY_INDEX = 1, 2
+CM_OPT_EVK_STORED_A, CM_OPT_TWO_STEP_MASKS = 1, 2
 
 
 class cm_params(C.Structure):
@@ -43,6 +44,7 @@ _SIGS = {
     "cm_last_hip_error": ([], _i32),
     "cm_ctx_create": ([_P(cm_params), _P(_vp)], _i32),
     "cm_ctx_destroy": ([_vp], None),
+    "cm_ctx_set_option": ([_vp, _i32, _i32], _i32),
     "cm_ctx_moduli": ([_vp, _vp], _i32),
     "cm_ct_words": ([_vp, _i32, _i32], _sz),
     "cm_pt_words": ([_vp, _i32], _sz),
@@ -163,6 +165,9 @@ class Context:
         if self.h:
             lib.cm_ctx_destroy(self.h)
             self.h = None
+
+    def set_option(self, option, value):
+        _chk(lib.cm_ctx_set_option(self.h, option, int(value)))
 
     def moduli(self):
         out = np.empty(self.L + 1 + self.K, dtype=np.uint64)

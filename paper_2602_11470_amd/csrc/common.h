@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include <map>
+#include <new>
 #include <vector>
 
 #include "../../include/cachemir.h"
@@ -74,6 +75,7 @@ struct FpQ {
 #define CM_MAX_DIGITS 16
 #define CM_GAUSS_K 19
 #define CM_KS_BATCH 8      // hoisted rotations whose ModDown runs as one batch
+#define CM_NTT_MAX_LIMBS 1024
 
 struct ConvTable {            // fast base conversion src -> dst (all indices into the modulus list)
     int ns = 0, nt = 0;
@@ -129,17 +131,14 @@ struct cm_ctx {
     u64 *d_cdt = nullptr;                          // Gaussian table [CM_GAUSS_K]
     u64 cdt[CM_GAUSS_K];
     int lazy_terms;                                // products that may be summed before one REDC
-    // second stream for bandwidth-bound kernels that can run beside the transform chain, and a
-    // small ring of events to order the two (default priority, timing disabled)
-    hipStream_t aux = nullptr;
-    bool overlap = false;          // CM_OVERLAP=1 in the environment puts the key-streaming inner products of hoisted
-                                   // rotations on a second stream (measured: no gain, the step is bandwidth-bound)
-    std::vector<hipEvent_t> sync_ev;
-    size_t sync_next = 0;
+    // options (cm_ctx_set_option)
+    bool evk_stored_a = false;     // evaluation keys carry both halves; the inner products read the uniform half
+    bool two_step_masks = false;   // cache appends multiply, store and rescale instead of fusing the product into the rescale
     // scratch arena
     u64 *arena = nullptr;
     size_t arena_words = 0;
-    int *d_idx = nullptr;                          // small device int scratch for modulus index lists
+    int *d_idx = nullptr;                          // 0, 1, 2, ...: modulus index lists of consecutive limbs
+    int *d_idx_stage = nullptr;                    // [CM_NTT_MAX_LIMBS] staging of a caller's modulus index list (cm_ntt)
     // encode tables (host)
     std::vector<int> slot_pos;
     std::vector<double> tw_re, tw_im;              // omega^k
@@ -148,17 +147,25 @@ struct cm_ctx {
 struct cm_sk {
     std::vector<int8_t> coeffs;
     u64 *d_ntt = nullptr;          // [nmod][n], Montgomery form, evaluation domain
+    u64 noise = 0;                 // XORed into the public seed of a call to key its error streams
 };
 
 struct EvkEntry {
     u64 *d = nullptr;              // b halves [digits][nmod][n] (multiplier form, evaluation domain), then the
-                                   // [digits][nmod] generator keys of the streams of the a halves (not stored)
+                                   // [digits][nmod] generator keys of the streams of the a halves (padded to an even
+                                   // count), then -- stored_a only -- the a halves [digits][nmod][n] in multiplier form
 };
 struct cm_evk {
     int digits;
-    u64 seed = 0;                  // the seed every key of the set was generated from
+    bool stored_a = false;         // the option the set was generated under
+    u64 seed = 0;                  // the (public) seed every key of the set was generated from
     std::map<u64, EvkEntry> keys;  // Galois element (0 = relinearisation)
 };
+// word offset of the stored a halves inside a key
+inline size_t evk_a_offset(const cm_ctx *ctx) {
+    const size_t digits = (size_t)(ctx->L + ctx->alpha) / ctx->alpha, nm = (size_t)ctx->nmod;
+    return digits * nm * ctx->n + ((digits * nm + 1) & ~(size_t)1);
+}
 
 #define HIPCHK(x)                                  \
     do {                                           \
@@ -186,9 +193,13 @@ struct cm_evk {
     } while (0)
 
 void cm_set_hip_error(int e);
-// order `waiter` after everything enqueued on `signaller` so far
-void stream_after(cm_ctx *ctx, hipStream_t waiter, hipStream_t signaller);
-inline hipStream_t aux_of(cm_ctx *ctx, hipStream_t st) { return ctx->overlap ? ctx->aux : st; }
+// Every extern "C" body that can reach an allocation (std::vector, std::map, new) sits between these: no C++
+// exception crosses the boundary.
+#define CM_TRY try {
+#define CM_CATCH                                        \
+    }                                                   \
+    catch (const std::bad_alloc &) { return CM_E_NOMEM; } \
+    catch (...) { return CM_E_INVAL; }
 
 struct Prof {
     cm_ctx *c;

@@ -26,12 +26,6 @@ extern "C" const char *cm_strerror(cm_status s) {
     return "unknown status";
 }
 
-void stream_after(cm_ctx *ctx, hipStream_t waiter, hipStream_t signaller) {
-    hipEvent_t e = ctx->sync_ev[ctx->sync_next++ % ctx->sync_ev.size()];
-    hipEventRecord(e, signaller);
-    hipStreamWaitEvent(waiter, e, 0);
-}
-
 // ---- kernel-family timing ---------------------------------------------------------------------------
 Prof::Prof(cm_ctx *ctx, int fam, double units, hipStream_t s) : c(ctx), st(s), e0(0), live(ctx->prof.on) {
     if (!live) return;
@@ -53,6 +47,14 @@ extern "C" cm_status cm_profile_enable(cm_ctx *ctx, int32_t on) {
     ctx->prof.on = on != 0;
     ctx->prof.recs.clear();
     return CM_OK;
+}
+extern "C" cm_status cm_ctx_set_option(cm_ctx *ctx, int32_t option, int32_t value) {
+    if (!ctx) return CM_E_INVAL;
+    switch (option) {
+        case CM_OPT_EVK_STORED_A: ctx->evk_stored_a = value != 0; return CM_OK;
+        case CM_OPT_TWO_STEP_MASKS: ctx->two_step_masks = value != 0; return CM_OK;
+    }
+    return CM_E_INVAL;
 }
 extern "C" cm_status cm_profile_get(cm_ctx *ctx, int32_t family, double *launches, double *units, double *ms) {
     if (!ctx || family < 0 || family >= CM_K_FAMILIES) return CM_E_INVAL;
@@ -141,13 +143,14 @@ std::vector<std::vector<int>> digits_at(const cm_ctx *ctx, int level) {
     return out;
 }
 
+// device copy of a host table; a failed allocation or copy raises std::bad_alloc (caught at the C boundary)
 template <class T>
 static T *upload(const std::vector<T> &v) {
     T *d = nullptr;
-    if (hipMalloc((void **)&d, v.size() * sizeof(T)) != hipSuccess) return nullptr;
+    if (hipMalloc((void **)&d, v.size() * sizeof(T)) != hipSuccess) throw std::bad_alloc();
     if (hipMemcpy(d, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) {
         hipFree(d);
-        return nullptr;
+        throw std::bad_alloc();
     }
     return d;
 }
@@ -252,6 +255,7 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
     if (fabs(p->sigma - 3.2) > 1e-12 || p->hamming < 0 || p->hamming > p->n || !(p->scale > 1)) return CM_E_INVAL;
     cm_ctx *ctx = new (std::nothrow) cm_ctx();
     if (!ctx) return CM_E_NOMEM;
+    try {
     ctx->prm = *p;
     ctx->n = p->n;
     ctx->logn = p->n == 4096 ? 12 : 16;
@@ -341,7 +345,7 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
         std::vector<FpQ> fpq(ctx->nmod);
         for (int m = 0; m < ctx->nmod; m++) {
             const u64 q = ctx->mod[m];
-            const bool fp = q < (1ULL << 50) && !getenv("CM_NTT_INT");
+            const bool fp = q < (1ULL << 50);
             fpq[m].q = fp ? (double)q : 0.0;
             fpq[m].qinv = fp ? 1.0 / (double)q : 0.0;
             fpq[m].rinv = fpq[m].rinvq = 0.0;
@@ -365,6 +369,7 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
     std::vector<int> iota(2 * CM_MAX_LIMBS);
     for (int i = 0; i < 2 * CM_MAX_LIMBS; i++) iota[i] = i;
     ctx->d_idx = upload(iota);
+    ctx->d_idx_stage = upload(std::vector<int>(CM_NTT_MAX_LIMBS, 0));
     memcpy(ctx->cdt, kGaussCdt, sizeof(kGaussCdt));
     std::vector<u64> cdt(kGaussCdt, kGaussCdt + CM_GAUSS_K);
     ctx->d_cdt = upload(cdt);
@@ -382,14 +387,6 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
         cm_ctx_destroy(ctx);
         return CM_E_NOMEM;
     }
-    if (hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking) != hipSuccess) ctx->aux = nullptr;
-    for (int i = 0; i < 32 && ctx->aux; i++) {
-        hipEvent_t e;
-        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { hipStreamDestroy(ctx->aux); ctx->aux = nullptr; break; }
-        ctx->sync_ev.push_back(e);
-    }
-    if (!ctx->aux) { cm_ctx_destroy(ctx); return CM_E_NOMEM; }
-    ctx->overlap = getenv("CM_OVERLAP") != nullptr;
     // encode tables
     ctx->slot_pos.resize(n / 2);
     u64 g = 1;
@@ -404,6 +401,10 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
         ctx->tw_re[k] = (double)cosl(a);
         ctx->tw_im[k] = (double)sinl(a);
     }
+    } catch (...) {                  // a failed table upload or host allocation: release what exists
+        cm_ctx_destroy(ctx);
+        return CM_E_NOMEM;
+    }
     *out = ctx;
     return CM_OK;
 }
@@ -412,8 +413,6 @@ extern "C" void cm_ctx_destroy(cm_ctx *ctx) {
     if (!ctx) return;
     cm_ops_forget_ctx(ctx);
     for (hipEvent_t e : ctx->prof.pool) hipEventDestroy(e);
-    for (hipEvent_t e : ctx->sync_ev) hipEventDestroy(e);
-    if (ctx->aux) hipStreamDestroy(ctx->aux);
     hipFree(ctx->d_modc);
     hipFree(ctx->d_pmont);
     hipFree(ctx->d_ubound);
@@ -426,6 +425,7 @@ extern "C" void cm_ctx_destroy(cm_ctx *ctx) {
     hipFree(ctx->d_fpq), hipFree(ctx->d_twd), hipFree(ctx->d_twqd), hipFree(ctx->d_itwd), hipFree(ctx->d_itwqd);
     hipFree(ctx->d_ninvd), hipFree(ctx->d_ninvqd);
     hipFree(ctx->d_idx);
+    hipFree(ctx->d_idx_stage);
     hipFree(ctx->d_cdt);
     hipFree(ctx->arena);
     for (auto &kv : ctx->modup)
@@ -478,6 +478,7 @@ static void fft(const cm_ctx *ctx, std::vector<std::complex<double>> &a, int sig
 extern "C" cm_status cm_encode_coeffs(const cm_ctx *ctx, const double *re, const double *im,
                                       size_t nslots, double scale, int64_t *out) {
     if (!ctx || !re || !out || nslots > (size_t)ctx->n / 2 || !(scale > 0)) return CM_E_INVAL;
+    CM_TRY
     const int n = ctx->n;
     // values at all primitive 2n-th roots: omega^(2u+1) for slot j at u = slot_pos[j], and the
     // conjugate value at the conjugate root u' = n-1-u; then m_k = Re(FFT(v)_k omega^-k)/n.
@@ -495,6 +496,7 @@ extern "C" cm_status cm_encode_coeffs(const cm_ctx *ctx, const double *re, const
         out[k] = (int64_t)x;
     }
     return CM_OK;
+    CM_CATCH
 }
 
 // Slot values from centred real coefficients (already divided by the scale).

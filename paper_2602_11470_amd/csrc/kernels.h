@@ -2,6 +2,7 @@
 #pragma once
 #include "common.h"
 
+void launch_set_idx(int *d_dst, const int *h_src, int count, hipStream_t st);
 void launch_reduce_i64(cm_ctx *ctx, u64 *out, const long long *d_coeffs, const int *d_mod_idx, int limbs, hipStream_t st);
 void launch_to_mont(cm_ctx *ctx, u64 *data, const int *d_mod_idx, int limbs, hipStream_t st);
 void launch_from_mont(cm_ctx *ctx, u64 *out, const u64 *in, const int *d_mod_idx, int limbs, hipStream_t st);
@@ -197,6 +198,8 @@ u64 *arena_batch_sums(const cm_ctx *ctx);
 cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, const u64 *const *keys, const u64 *gs,
                         const u64 *in, u64 *const *outs, hipStream_t st);
 const u64 *find_key(const cm_evk *evk, u64 g);
+// the key set was generated under the context's current CM_OPT_EVK_STORED_A setting (the kernels take the layout from it)
+bool evk_fits(const cm_ctx *ctx, const cm_evk *evk);
 void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mods, int limbs, bool inverse, hipStream_t st);
 void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, const int *d_src_rows,
                     const int *d_mods, int limbs, bool inverse, hipStream_t st, u64 g = 0);

@@ -1,11 +1,26 @@
 // Element-wise, base-conversion, key-switch and sampling kernels of libcachemir (gfx950).
 // Polynomials are [limbs][n] 64-bit words.  "mont" operands are pre-multiplied by 2^64 mod q.
-#include <stdlib.h>
-
 #include "kernels.h"
 
 #define TPB 256
 
+
+// ---- a short list of integers into device memory without a copy or an allocation ---------------
+// (the values travel as kernel arguments, so the launch can be captured into a graph)
+#define IDX_CHUNK 256
+struct IdxChunk { int v[IDX_CHUNK]; };
+__global__ void k_set_idx(int *dst, IdxChunk c, int count) {
+    const int i = threadIdx.x;
+    if (i < count) dst[i] = c.v[i];
+}
+void launch_set_idx(int *d_dst, const int *h_src, int count, hipStream_t st) {
+    for (int base = 0; base < count; base += IDX_CHUNK) {
+        IdxChunk c;
+        const int m = count - base < IDX_CHUNK ? count - base : IDX_CHUNK;
+        for (int i = 0; i < IDX_CHUNK; i++) c.v[i] = i < m ? h_src[base + i] : 0;
+        hipLaunchKernelGGL(k_set_idx, dim3(1), dim3(IDX_CHUNK), 0, st, d_dst + base, c, m);
+    }
+}
 
 // ---- signed integers -> residues -------------------------------------------------------------
 __global__ void k_reduce_i64(u64 *out, const long long *coeffs, const int *mod_idx, const ModC *modc, int n) {
@@ -291,7 +306,7 @@ void launch_tensor_sum(cm_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int cn
                        int group_stride, int term_stride) {
     const int gs = group_stride ? group_stride : cnt, ts = term_stride ? term_stride : 1;
     Prof prof_(ctx, CM_K_ELEMENTWISE, 3 * limbs * groups, st);
-    bool all_fp = !getenv("CM_NTT_INT");                      // the switch that keeps every limb on the integer forms
+    bool all_fp = true;
     for (int l = 0; l < limbs; l++) all_fp = all_fp && ctx->mod[l] < (1ULL << 50);
     if (all_fp && cnt <= TS_MAX_CNT && groups > 1) {
         hipLaunchKernelGGL(k_tensor_sum_stationary, dim3(ctx->n / TPB, limbs), dim3(TPB), 0, st, out, a, b, ctx->d_fpq, limbs, ctx->n,
@@ -368,16 +383,11 @@ void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_ste
                       int in_group, size_t own_stride) {
     if (tab_period <= 0) tab_period = batch;
     Prof prof_(ctx, CM_K_BASE_CONV, batch * max_nt, st);
-    static int tg = getenv("CM_CONV_TG") ? atoi(getenv("CM_CONV_TG")) : 8;
-#define CONV_LAUNCH(TG)                                                                                              \
-    hipLaunchKernelGGL(k_base_conv<TG>, dim3(ctx->n / TPB, (max_nt + TG - 1) / TG, batch), dim3(TPB), 0, st, out, in, \
-                       d_tabs, tab_step, tab_period, in_group, ctx->n, in_stride, out_stride, own_src, own_stride,    \
-                       (unsigned)own_g, ctx->logn)
-    if (tg == 2) CONV_LAUNCH(2);
-    else if (tg == 8) CONV_LAUNCH(8);
-    else if (tg == 12) CONV_LAUNCH(12);
-    else if (tg == 24) CONV_LAUNCH(24);
-    else CONV_LAUNCH(4);
+    // 8 targets per lane (measured best of 2 / 4 / 8 / 12 / 24 at the benchmark's shapes)
+    const int TG = 8;
+    hipLaunchKernelGGL(k_base_conv<8>, dim3(ctx->n / TPB, (max_nt + TG - 1) / TG, batch), dim3(TPB), 0, st, out, in,
+                       d_tabs, tab_step, tab_period, in_group, ctx->n, in_stride, out_stride, own_src, own_stride,
+                       (unsigned)own_g, ctx->logn);
 }
 
 // ---- evaluation-key inner product ------------------------------------------------------------------
@@ -408,11 +418,39 @@ __device__ __forceinline__ u64 evk_a_draw(u64 stream_key, u64 ctr_gold, unsigned
 __device__ __forceinline__ u64 redc_raw(u128 T, const ModC &m) {
     return redc((u128)redc(T, m.q, m.qinv) * m.r2, m.q, m.qinv);
 }
+// Where the two words of a_j for positions (i, i + 1) of limb mi come from.  Keys generated with both halves stored
+// carry a_j in multiplier form like b_j (word offset a_off inside the key): the kernels read it, one REDC per sum.
+// Otherwise it is regenerated from its stream (raw draws, two REDCs per sum).  Both give the same residues.
+struct EvkA {
+    size_t a_off;     // 0: regenerate
+    int kdig;         // digits of a full key: the stream keys start at kdig * nmod * n
+};
+template <bool SA>
+__device__ __forceinline__ ulonglong2 evk_a_words(const u64 *__restrict__ key, const EvkA ea, int nmod, int n, int j, int mi,
+                                                  unsigned i, u64 cg0, u64 cg1, u64 bound) {
+    ulonglong2 r;
+    if (SA) {
+        const u64 *ka = key + ea.a_off + ((size_t)j * nmod + mi) * n + i;
+        r.x = __builtin_nontemporal_load(ka), r.y = __builtin_nontemporal_load(ka + 1);
+    } else {
+        const u64 sk_ = key[(size_t)ea.kdig * nmod * n + (size_t)j * nmod + mi];
+        r.x = evk_a_draw(sk_, cg0, i, bound), r.y = evk_a_draw(sk_, cg1, i + 1, bound);
+    }
+    return r;
+}
+template <bool SA>
+__device__ __forceinline__ u64 evk_a_reduce(u128 T, const ModC &m) {
+    return SA ? redc(T, m.q, m.qinv) : redc_raw(T, m);
+}
+static EvkA evk_a_of(const cm_ctx *ctx) {
+    return EvkA{ctx->evk_stored_a ? evk_a_offset(ctx) : 0, (ctx->L + ctx->alpha) / ctx->alpha};
+}
+template <bool SA>
 __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
                                                        const u64 *__restrict__ dig, const u64 *__restrict__ evk,
                                                        const ModC *__restrict__ modc,
                                 int beta, int ext, int level, int L, int nmod, int n, int logn, unsigned g,
-                                const u64 *__restrict__ c0, const u64 *__restrict__ pmont, const u64 *extra, int kdig,
+                                const u64 *__restrict__ c0, const u64 *__restrict__ pmont, const u64 *extra, EvkA eva,
                                 const u64 *__restrict__ ubound) {
     unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
     int r = blockIdx.y;
@@ -429,10 +467,9 @@ __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
         const u64 *kb = evk + ((size_t)j * nmod + mi) * n + i2;
         // the key is streamed once: non-temporal, so that the raised digits (re-read by every
         // hoisted rotation) are the lines that stay in the last-level cache
-        ulonglong2 eb, ea;
+        ulonglong2 eb;
         eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
-        const u64 sk_ = evk[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
-        ea.x = evk_a_draw(sk_, cg0, i2, bound), ea.y = evk_a_draw(sk_, cg1, i2 + 1, bound);
+        const ulonglong2 ea = evk_a_words<SA>(evk, eva, nmod, n, j, mi, i2, cg0, cg1, bound);
         b0 += (u128)dx * eb.x;
         b1 += (u128)dy * eb.y;
         a0 += (u128)dx * ea.x;
@@ -446,7 +483,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
     }
     size_t o = (size_t)r * n + i2;
     ulonglong2 r0 = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
-    ulonglong2 r1 = make_ulonglong2(redc_raw(a0, m), redc_raw(a1, m));
+    ulonglong2 r1 = make_ulonglong2(evk_a_reduce<SA>(a0, m), evk_a_reduce<SA>(a1, m));
     if (extra) {                      // + a sum already in the extended basis, [2][ext][n]
         ulonglong2 e0 = *reinterpret_cast<const ulonglong2 *>(extra + o);
         ulonglong2 e1 = *reinterpret_cast<const ulonglong2 *>(extra + (size_t)ext * n + o);
@@ -458,9 +495,10 @@ __global__ __launch_bounds__(TPB) void k_inner_product(u64 *u0, u64 *u1,
 }
 // Several inner products in one launch: blockIdx.z = output; output z sums nsum consecutive items
 // (each with its own digits, key, Galois element and optional c0) and an optional addend.
+template <bool SA>
 __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const ModC *__restrict__ modc, int beta, int ext,
                                                              int level, int L, int nmod, int n, int logn,
-                                                             const u64 *__restrict__ pmont, int kdig,
+                                                             const u64 *__restrict__ pmont, EvkA eva,
                                                              const u64 *__restrict__ ubound) {
     // Workgroups go to the eight XCDs round-robin by their linear index.  The rotated reads of the digits gather over
     // a whole limb, and every key of a sum gathers over the same limb again: with a limb's workgroups on ONE XCD (each
@@ -493,10 +531,9 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
             ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(it.dig + ((size_t)j * ext + r) * n + base);
             u64 dx = swap ? d.y : d.x, dy = swap ? d.x : d.y;
             const u64 *kb = it.key + ((size_t)j * nmod + mi) * n + i2;
-            ulonglong2 eb, ea;
+            ulonglong2 eb;
             eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
-            const u64 sk_ = it.key[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
-            ea.x = evk_a_draw(sk_, cg0, i2, bound), ea.y = evk_a_draw(sk_, cg1, i2 + 1, bound);
+            const ulonglong2 ea = evk_a_words<SA>(it.key, eva, nmod, n, j, mi, i2, cg0, cg1, bound);
             b0 += (u128)dx * eb.x;
             b1 += (u128)dy * eb.y;
             a0 += (u128)dx * ea.x;
@@ -512,7 +549,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
             b1 += (u128)(swap ? d.x : d.y) * pm;
         }
         r0.x = addmod(r0.x, redc(b0, m.q, m.qinv), m.q), r0.y = addmod(r0.y, redc(b1, m.q, m.qinv), m.q);
-        r1.x = addmod(r1.x, redc_raw(a0, m), m.q), r1.y = addmod(r1.y, redc_raw(a1, m), m.q);
+        r1.x = addmod(r1.x, evk_a_reduce<SA>(a0, m), m.q), r1.y = addmod(r1.y, evk_a_reduce<SA>(a1, m), m.q);
     }
     *reinterpret_cast<ulonglong2 *>(b.out[z] + o) = r0;
     *reinterpret_cast<ulonglong2 *>(b.out[z] + (size_t)ext * n + o) = r1;
@@ -523,9 +560,10 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
 // Galois map; extra[z] ([2][ext][n], may be out[z] itself) is added, which lets several launches with
 // different keys accumulate into one output.
 #define IP_SHARED_MAX_BETA 8
+template <bool SA>
 __global__ __launch_bounds__(TPB) void k_inner_product_shared_key(IpBatch b, const ModC *__restrict__ modc, int beta,
                                                                   int ext, int level, int L, int nmod, int n, int logn,
-                                                                  unsigned g, int kdig, const u64 *__restrict__ ubound) {
+                                                                  unsigned g, EvkA eva, const u64 *__restrict__ ubound) {
     const unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
     const int r = blockIdx.y;
     const int mi = r <= level ? r : L + 1 + (r - level - 1);
@@ -542,8 +580,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_shared_key(IpBatch b, con
         if (j < beta) {
             const u64 *kb = key + ((size_t)j * nmod + mi) * n + i2;
             eb[j].x = __builtin_nontemporal_load(kb), eb[j].y = __builtin_nontemporal_load(kb + 1);
-            const u64 sk_ = key[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
-            ea[j].x = evk_a_draw(sk_, cg0, i2, bound), ea[j].y = evk_a_draw(sk_, cg1, i2 + 1, bound);
+            ea[j] = evk_a_words<SA>(key, eva, nmod, n, j, mi, i2, cg0, cg1, bound);
         }
     }
     for (int z = 0; z < b.nz; z++) {
@@ -561,7 +598,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_shared_key(IpBatch b, con
             }
         }
         ulonglong2 r0 = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
-        ulonglong2 r1 = make_ulonglong2(redc_raw(a0, m), redc_raw(a1, m));
+        ulonglong2 r1 = make_ulonglong2(evk_a_reduce<SA>(a0, m), evk_a_reduce<SA>(a1, m));
         if (b.it[z].c0) {
             ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(b.it[z].c0 + (size_t)r * n + base);
             r0.x = addmod(r0.x, swap ? d.y : d.x, m.q), r0.y = addmod(r0.y, swap ? d.x : d.y, m.q);
@@ -586,8 +623,12 @@ void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, in
         return;
     }
     Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz, st);
-    hipLaunchKernelGGL(k_inner_product_shared_key, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, b, ctx->d_modc, beta, ext,
-                       level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, (ctx->L + ctx->alpha) / ctx->alpha, ctx->d_ubound);
+    if (ctx->evk_stored_a)
+        hipLaunchKernelGGL(k_inner_product_shared_key<true>, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, b, ctx->d_modc, beta,
+                           ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, evk_a_of(ctx), ctx->d_ubound);
+    else
+        hipLaunchKernelGGL(k_inner_product_shared_key<false>, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, b, ctx->d_modc, beta,
+                           ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, evk_a_of(ctx), ctx->d_ubound);
 }
 // One digit array, many keys, one output per key (the hoisted rotations of ONE ciphertext, each kept on its own): a lane
 // keeps the digit words of two SOURCE positions (and the first component's) in registers and walks over the keys; for
@@ -595,10 +636,11 @@ void launch_inner_product_shared_key(cm_ctx *ctx, const IpBatch &b, int beta, in
 // aligned runs of 64 to aligned runs of 64, so key reads and result writes stay coalesced).  Same sums as
 // k_inner_product_batch, but the digits are read once per IP_FAN_CHUNK keys instead of once per key.
 #define IP_FAN_CHUNK 8
+template <bool SA>
 __global__ __launch_bounds__(TPB) void k_inner_product_fanout(IpFan f, const u64 *__restrict__ dig, const u64 *__restrict__ c0,
                                                               int c0_ext, const ModC *__restrict__ modc, int beta, int ext,
                                                               int level, int L, int nmod, int n, int logn,
-                                                              const u64 *__restrict__ pmont, int kdig,
+                                                              const u64 *__restrict__ pmont, EvkA eva,
                                                               const u64 *__restrict__ ubound) {
     // The key chunks of one (limb, block) read the same digits: they are given consecutive places in the sequence of
     // ONE XCD (workgroups go to the XCDs round-robin by linear index), so that the digits come from HBM once and from
@@ -643,10 +685,9 @@ __global__ __launch_bounds__(TPB) void k_inner_product_fanout(IpFan f, const u64
             if (j < beta) {
                 const u64 dx = swap ? d[j].y : d[j].x, dy = swap ? d[j].x : d[j].y;      // sources of positions base, base + 1
                 const u64 *kb = key + ((size_t)j * nmod + mi) * n + base;
-                ulonglong2 eb, ea;
+                ulonglong2 eb;
                 eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
-                const u64 sk_ = key[(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
-                ea.x = evk_a_draw(sk_, cg0, base, bound), ea.y = evk_a_draw(sk_, cg1, base + 1, bound);
+                const ulonglong2 ea = evk_a_words<SA>(key, eva, nmod, n, j, mi, base, cg0, cg1, bound);
                 b0 += (u128)dx * eb.x;
                 b1 += (u128)dy * eb.y;
                 a0 += (u128)dx * ea.x;
@@ -657,7 +698,8 @@ __global__ __launch_bounds__(TPB) void k_inner_product_fanout(IpFan f, const u64
         if (have_c0) r0.x = addmod(r0.x, swap ? cv.y : cv.x, m.q), r0.y = addmod(r0.y, swap ? cv.x : cv.y, m.q);
         const size_t o = (size_t)r * n + base;
         *reinterpret_cast<ulonglong2 *>(f.out[a] + o) = r0;
-        *reinterpret_cast<ulonglong2 *>(f.out[a] + (size_t)ext * n + o) = make_ulonglong2(redc_raw(a0, m), redc_raw(a1, m));
+        *reinterpret_cast<ulonglong2 *>(f.out[a] + (size_t)ext * n + o) =
+            make_ulonglong2(evk_a_reduce<SA>(a0, m), evk_a_reduce<SA>(a1, m));
     }
 }
 bool launch_inner_product_fanout(cm_ctx *ctx, const IpFan &f, const u64 *dig, const u64 *c0, bool c0_ext, int beta, int level,
@@ -665,9 +707,13 @@ bool launch_inner_product_fanout(cm_ctx *ctx, const IpFan &f, const u64 *dig, co
     if (beta > IP_SHARED_MAX_BETA || f.n < 1 || f.n > IP_FAN_MAX) return false;
     Prof prof_(ctx, CM_K_INNER_PRODUCT, f.n, st);
     const int ext = level + 1 + ctx->K;
-    hipLaunchKernelGGL(k_inner_product_fanout, dim3(ctx->n / (2 * TPB), ext, (f.n + IP_FAN_CHUNK - 1) / IP_FAN_CHUNK), dim3(TPB), 0, st,
-                       f, dig, c0, c0_ext ? 1 : 0, ctx->d_modc, beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, ctx->d_pmont,
-                       (ctx->L + ctx->alpha) / ctx->alpha, ctx->d_ubound);
+    const dim3 grid(ctx->n / (2 * TPB), ext, (f.n + IP_FAN_CHUNK - 1) / IP_FAN_CHUNK);
+    if (ctx->evk_stored_a)
+        hipLaunchKernelGGL(k_inner_product_fanout<true>, grid, dim3(TPB), 0, st, f, dig, c0, c0_ext ? 1 : 0, ctx->d_modc, beta, ext,
+                           level, ctx->L, ctx->nmod, ctx->n, ctx->logn, ctx->d_pmont, evk_a_of(ctx), ctx->d_ubound);
+    else
+        hipLaunchKernelGGL(k_inner_product_fanout<false>, grid, dim3(TPB), 0, st, f, dig, c0, c0_ext ? 1 : 0, ctx->d_modc, beta, ext,
+                           level, ctx->L, ctx->nmod, ctx->n, ctx->logn, ctx->d_pmont, evk_a_of(ctx), ctx->d_ubound);
     return true;
 }
 // NA keys (rotation amounts) applied to the same nz digit arrays, summed: out[z] = extra[z] + sum_a [ sum_j
@@ -675,9 +721,9 @@ bool launch_inner_product_fanout(cm_ctx *ctx, const IpFan &f, const u64 *dig, co
 // IP_MULTI_BETA digits) and writes every output once: against one launch per amount this saves the read-modify-write
 // of the running sum, a third of the traffic of the rotation step of an unrolled ladder.
 #define IP_MULTI_BETA 6
-template <int NA>
+template <int NA, bool SA>
 __global__ __launch_bounds__(TPB) void k_inner_product_multi_key(IpBatch b, IpKeys ks, const ModC *__restrict__ modc, int beta,
-                                                                 int ext, int level, int L, int nmod, int n, int logn, int kdig,
+                                                                 int ext, int level, int L, int nmod, int n, int logn, EvkA eva,
                                                                  const u64 *__restrict__ ubound) {
     const unsigned i2 = (blockIdx.x * TPB + threadIdx.x) * 2;
     const int r = blockIdx.y;
@@ -697,8 +743,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_multi_key(IpBatch b, IpKe
             if (j < beta) {
                 const u64 *kb = ks.key[a] + ((size_t)j * nmod + mi) * n + i2;
                 eb[a][j].x = __builtin_nontemporal_load(kb), eb[a][j].y = __builtin_nontemporal_load(kb + 1);
-                const u64 sk_ = ks.key[a][(size_t)kdig * nmod * n + (size_t)j * nmod + mi];
-                ea[a][j].x = evk_a_draw(sk_, cg0, i2, bound), ea[a][j].y = evk_a_draw(sk_, cg1, i2 + 1, bound);
+                ea[a][j] = evk_a_words<SA>(ks.key[a], eva, nmod, n, j, mi, i2, cg0, cg1, bound);
             }
         }
     }
@@ -724,7 +769,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_multi_key(IpBatch b, IpKe
                 }
             }
             r0.x = addmod(r0.x, redc(b0, m.q, m.qinv), m.q), r0.y = addmod(r0.y, redc(b1, m.q, m.qinv), m.q);
-            r1.x = addmod(r1.x, redc_raw(a0, m), m.q), r1.y = addmod(r1.y, redc_raw(a1, m), m.q);
+            r1.x = addmod(r1.x, evk_a_reduce<SA>(a0, m), m.q), r1.y = addmod(r1.y, evk_a_reduce<SA>(a1, m), m.q);
             if (b.it[z].c0) {
                 ulonglong2 d = *reinterpret_cast<const ulonglong2 *>(b.it[z].c0 + (size_t)r * n + base[a]);
                 r0.x = addmod(r0.x, swap[a] ? d.y : d.x, m.q), r0.y = addmod(r0.y, swap[a] ? d.x : d.y, m.q);
@@ -736,22 +781,29 @@ __global__ __launch_bounds__(TPB) void k_inner_product_multi_key(IpBatch b, IpKe
 }
 bool launch_inner_product_multi_key(cm_ctx *ctx, const IpBatch &b, const IpKeys &ks, int na, int beta, int level, hipStream_t st) {
     if (beta > IP_MULTI_BETA || na < 2 || na > IP_MULTI_KEYS) return false;
-    const int ext = level + 1 + ctx->K, kdig = (ctx->L + ctx->alpha) / ctx->alpha;
+    const int ext = level + 1 + ctx->K;
     const dim3 grid(ctx->n / (2 * TPB), ext), block(TPB);
     Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz * na, st);
-    if (na == 2)
-        hipLaunchKernelGGL(k_inner_product_multi_key<2>, grid, block, 0, st, b, ks, ctx->d_modc, beta, ext, level, ctx->L, ctx->nmod,
-                           ctx->n, ctx->logn, kdig, ctx->d_ubound);
-    else
-        hipLaunchKernelGGL(k_inner_product_multi_key<3>, grid, block, 0, st, b, ks, ctx->d_modc, beta, ext, level, ctx->L, ctx->nmod,
-                           ctx->n, ctx->logn, kdig, ctx->d_ubound);
+#define MULTI_KEY_LAUNCH(NA_, SA_)                                                                                          \
+    hipLaunchKernelGGL((k_inner_product_multi_key<NA_, SA_>), grid, block, 0, st, b, ks, ctx->d_modc, beta, ext, level, ctx->L, \
+                       ctx->nmod, ctx->n, ctx->logn, evk_a_of(ctx), ctx->d_ubound)
+    if (na == 2 && ctx->evk_stored_a) MULTI_KEY_LAUNCH(2, true);
+    else if (na == 2) MULTI_KEY_LAUNCH(2, false);
+    else if (ctx->evk_stored_a) MULTI_KEY_LAUNCH(3, true);
+    else MULTI_KEY_LAUNCH(3, false);
+#undef MULTI_KEY_LAUNCH
     return true;
 }
 void launch_inner_product_batch(cm_ctx *ctx, const IpBatch &b, int beta, int level, hipStream_t st) {
     Prof prof_(ctx, CM_K_INNER_PRODUCT, b.nz * b.nsum, st);
     int ext = level + 1 + ctx->K;
-    hipLaunchKernelGGL(k_inner_product_batch, dim3(ctx->n / (2 * TPB), ext, b.nz), dim3(TPB), 0, st, b, ctx->d_modc, beta, ext,
-                       level, ctx->L, ctx->nmod, ctx->n, ctx->logn, ctx->d_pmont, (ctx->L + ctx->alpha) / ctx->alpha, ctx->d_ubound);
+    const dim3 grid(ctx->n / (2 * TPB), ext, b.nz);
+    if (ctx->evk_stored_a)
+        hipLaunchKernelGGL(k_inner_product_batch<true>, grid, dim3(TPB), 0, st, b, ctx->d_modc, beta, ext, level, ctx->L, ctx->nmod,
+                           ctx->n, ctx->logn, ctx->d_pmont, evk_a_of(ctx), ctx->d_ubound);
+    else
+        hipLaunchKernelGGL(k_inner_product_batch<false>, grid, dim3(TPB), 0, st, b, ctx->d_modc, beta, ext, level, ctx->L, ctx->nmod,
+                           ctx->n, ctx->logn, ctx->d_pmont, evk_a_of(ctx), ctx->d_ubound);
 }
 // out[2][ext][n] = (P c0, P c1) on the ciphertext limbs, zero on the special limbs
 __global__ void k_raise_by_P(u64 *__restrict__ out, const u64 *__restrict__ in, const ModC *__restrict__ modc,
@@ -775,9 +827,14 @@ void launch_inner_product(cm_ctx *ctx, u64 *u0, u64 *u1, const u64 *dig, const u
                           hipStream_t st, const u64 *c0, const u64 *extra) {
     Prof prof_(ctx, CM_K_INNER_PRODUCT, 1, st);
     int ext = level + 1 + ctx->K;
-    hipLaunchKernelGGL(k_inner_product, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, u0, u1, dig, evk, ctx->d_modc,
-                       beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, c0, ctx->d_pmont, extra,
-                       (ctx->L + ctx->alpha) / ctx->alpha, ctx->d_ubound);
+    if (ctx->evk_stored_a)
+        hipLaunchKernelGGL(k_inner_product<true>, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, u0, u1, dig, evk, ctx->d_modc,
+                           beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, c0, ctx->d_pmont, extra,
+                           evk_a_of(ctx), ctx->d_ubound);
+    else
+        hipLaunchKernelGGL(k_inner_product<false>, dim3(ctx->n / (2 * TPB), ext), dim3(TPB), 0, st, u0, u1, dig, evk, ctx->d_modc,
+                           beta, ext, level, ctx->L, ctx->nmod, ctx->n, ctx->logn, (unsigned)g, c0, ctx->d_pmont, extra,
+                           evk_a_of(ctx), ctx->d_ubound);
 }
 
 // ---- ModDown tail: out = (u - conv) * P^{-1} (+ addend, optionally through the Galois map) ------------

@@ -109,6 +109,7 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
     if (!pow2(heads) || !pow2(dim) || heads * dim > S) return CM_E_LAYOUT;
     cm_kv *kv = new (std::nothrow) cm_kv();
     if (!kv) return CM_E_NOMEM;
+    try {
     kv->ctx = ctx, kv->S = S, kv->H = heads, kv->E = dim, kv->t = S / (heads * dim);
     if (r_i == 0) r_i = dim;
     if (!pow2(r_i) || dim % r_i || max_tokens > dim * kv->t) { delete kv; return CM_E_LAYOUT; }
@@ -172,6 +173,10 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
     if (s != CM_OK) { cm_kv_destroy(kv); return s; }
     *out = kv;
     return CM_OK;
+    } catch (...) {
+        cm_kv_destroy(kv);
+        return CM_E_NOMEM;
+    }
 }
 extern "C" void cm_kv_destroy(cm_kv *kv) {
     if (!kv) return;
@@ -219,16 +224,19 @@ static cm_status build_mask_rows(cm_kv *kv) {
 extern "C" cm_status cm_kv_set_mask(cm_kv *kv, int32_t kind, const int64_t *coeffs) {
     if (!kv || !coeffs || kind < 0 || kind > 4) return CM_E_INVAL;
     if (kind > 0 && kv->level + 1 > kv->ctx->L) return CM_E_LEVEL;
+    CM_TRY
     u64 *dst = kind == 0 ? kv->d_mask_qk : kind == 1 ? kv->d_mask_k : kind == 2 ? kv->d_mask_v
              : kind == 3 ? kv->d_mask_kg : kv->d_mask_vg;
     CMCHK(encode_mask(kv, kind, dst, kind == 0 ? kv->level - 1 : kv->level + 1, coeffs));
     return kind == 0 && kv->d_M ? build_mask_rows(kv) : CM_OK;
+    CM_CATCH
 }
 // How many terms of the sum over the dims of query-times-K are taken AFTER the copy mask, by rotations shared by all
 // key ciphertexts (1 = none).  Rebuilds the runs of the per-ciphertext part and allocates the buffers of the shared part.
 extern "C" cm_status cm_kv_set_shared_dims(cm_kv *kv, int32_t shared) {
     if (!kv || !kv->unrolled) return CM_E_INVAL;
     if (!pow2(shared) || shared > kv->E) return CM_E_LAYOUT;
+    CM_TRY
     cm_ctx *ctx = kv->ctx;
     std::vector<long long> ladder;
     for (int i = 0; i < ilog2(kv->E / shared); i++) ladder.push_back((long long)(shared << i) * kv->H * kv->t);
@@ -257,6 +265,7 @@ extern "C" cm_status cm_kv_set_shared_dims(cm_kv *kv, int32_t shared) {
     kv->shared = shared;
     kv->dim_groups = ladder_groups(ladder);
     return shared > 1 ? build_mask_rows(kv) : CM_OK;
+    CM_CATCH
 }
 
 static std::vector<int> kv_all_steps(const cm_kv *kv) {
@@ -285,9 +294,13 @@ static std::vector<int> kv_all_steps(const cm_kv *kv) {
 }
 extern "C" int32_t cm_kv_steps(const cm_kv *kv, int32_t *steps, int32_t cap) {
     if (!kv) return 0;
-    auto s = kv_all_steps(kv);
-    for (int i = 0; i < (int)s.size() && i < cap && steps; i++) steps[i] = s[i];
-    return (int32_t)s.size();
+    try {
+        auto s = kv_all_steps(kv);
+        for (int i = 0; i < (int)s.size() && i < cap && steps; i++) steps[i] = s[i];
+        return (int32_t)s.size();
+    } catch (...) {
+        return 0;
+    }
 }
 extern "C" int32_t cm_kv_tokens(const cm_kv *kv) { return kv ? kv->ntok : -1; }
 extern "C" cm_status cm_kv_set_tokens(cm_kv *kv, int32_t ntok) {
@@ -331,8 +344,9 @@ static u64 rot_g(const cm_kv *kv, long long step) {
 static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_new, const cm_ct *v_new,
                            bool group, void *stream) {
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
-    if (!ctx || !evk || !kv || kv->ctx != ctx || !k_new || !v_new || !k_new->dev || !v_new->dev) return CM_E_INVAL;
+    if (!ctx || !evk || !kv || kv->ctx != ctx || !k_new || !v_new || !k_new->dev || !v_new->dev || !evk_fits(ctx, evk)) return CM_E_INVAL;
     if (k_new->ncomp != 2 || v_new->ncomp != 2) return CM_E_INVAL;
+    CM_TRY
     const int lv = kv->level + 1;
     if (lv > ctx->L || k_new->level != lv || v_new->level != lv) return CM_E_LEVEL;
     if (kv->ntok >= kv->max_tokens) return CM_E_LAYOUT;
@@ -421,6 +435,7 @@ static cm_status kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_c
     kv->scale = k_new->scale * (double)ctx->mod[lv] / (double)ctx->mod[lv];
     kv->scale_set = true;
     RETURN_LAUNCH_STATUS();
+    CM_CATCH
 }
 extern "C" cm_status cm_kv_append(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm_ct *k_new, const cm_ct *v_new,
                                   void *stream) {
@@ -706,12 +721,14 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
 extern "C" cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t which, const cm_ct *in,
                                cm_ct *out, void *stream) {
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
-    if (!ctx || !evk || !kv || kv->ctx != ctx || !in || !in->dev || !out || !out->dev || in->ncomp != 2) return CM_E_INVAL;
+    if (!ctx || !evk || !kv || kv->ctx != ctx || !in || !in->dev || !out || !out->dev || in->ncomp != 2 || !evk_fits(ctx, evk)) return CM_E_INVAL;
     if (in->level != kv->level) return CM_E_LEVEL;
+    CM_TRY
     if ((which == CM_QK || which == CM_QK_GROUP) && kv->indexed)
         return kv_sv(ctx, evk, kv, in, out, (hipStream_t)stream, false, kv->d_x, which == CM_QK);
     if (which == CM_QK || which == CM_QK_GROUP) return kv_qk(ctx, evk, kv, in, out, (hipStream_t)stream, which == CM_QK);
     if (which == CM_SV || which == CM_SV_GROUP)
         return kv_sv(ctx, evk, kv, in, out, (hipStream_t)stream, which == CM_SV, kv->d_v, false);
     return CM_E_INVAL;
+    CM_CATCH
 }

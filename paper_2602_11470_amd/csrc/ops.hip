@@ -7,7 +7,9 @@
 #include "kernels.h"
 
 // stream identifiers of the counter-based generator
-enum { ST_SECRET = 1, ST_EVK_A = 2, ST_EVK_E = 3, ST_ENC_A = 4, ST_ENC_E = 5 };
+// The seed a call receives is public (the uniform halves are its streams); the error streams are keyed by that seed
+// XOR the secret key's `noise`, the key of stream ST_NOISE under the secret key's own seed.
+enum { ST_SECRET = 1, ST_EVK_A = 2, ST_EVK_E = 3, ST_ENC_A = 4, ST_ENC_E = 5, ST_NOISE = 6 };
 static inline u64 stream_id(u64 purpose, u64 ident, u64 digit, u64 limb) {
     return (purpose << 56) | (ident << 16) | (digit << 8) | limb;
 }
@@ -32,13 +34,24 @@ static Arena arena_of(const cm_ctx *ctx) {
     return a;
 }
 
+// device copy of a host table (nullptr for an empty one); failure raises std::bad_alloc, caught at the C boundary
 template <class T>
 static T *up(const std::vector<T> &v) {
     T *d = nullptr;
     if (v.empty()) return nullptr;
-    if (hipMalloc((void **)&d, v.size() * sizeof(T)) != hipSuccess) return nullptr;
-    hipMemcpy(d, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
+    if (hipMalloc((void **)&d, v.size() * sizeof(T)) != hipSuccess) throw std::bad_alloc();
+    if (hipMemcpy(d, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) {
+        hipFree(d);
+        throw std::bad_alloc();
+    }
     return d;
+}
+// The synchronous calls (keys, encode, encrypt, decrypt, decode, exports) work on the null stream and share the
+// context's arena with the enqueueing calls: they first wait for everything the device still has in flight, so that
+// work pending on a caller's non-blocking stream cannot overlap them.
+static cm_status sync_begin() {
+    HIPCHK(hipDeviceSynchronize());
+    return CM_OK;
 }
 
 struct KsLevelFull : KsLevel {
@@ -80,11 +93,28 @@ static ConvDev conv_dev(const cm_ctx *ctx, const ConvTable &t, const std::vector
 }
 static std::map<std::pair<cm_ctx *, int>, KsLevelFull> g_ks;
 
+static void free_ks(KsLevelFull &k) {
+    hipFree(k.d_modup); hipFree(k.d_moddown); hipFree(k.d_bsp_rows); hipFree(k.d_bsp1_rows); hipFree(k.d_sp1_rows); hipFree(k.d_moddown0); hipFree(k.d_bsp_mods); hipFree(k.d_bq_mods);
+    hipFree(k.d_last_rows);
+    hipFree(k.d_ntt_rows); hipFree(k.d_ntt_mods); hipFree(k.d_sp_rows); hipFree(k.d_sp_mods);
+    hipFree(k.d_q_rows); hipFree(k.d_q_mods3); hipFree(k.d_last_mods); hipFree(k.d_red_mods); hipFree(k.d_red_src);
+}
+static void build_ks(cm_ctx *ctx, int level, KsLevelFull &k);
 static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
     auto key = std::make_pair(ctx, level);
     auto it = g_ks.find(key);
     if (it != g_ks.end()) return it->second;
     KsLevelFull k;
+    try {
+        build_ks(ctx, level, k);
+        return g_ks[key] = k;
+    } catch (...) {              // a table did not fit: nothing half-built is kept
+        free_ks(k);
+        g_ks.erase(key);
+        throw;
+    }
+}
+static void build_ks(cm_ctx *ctx, int level, KsLevelFull &k) {
     k.level = level;
     k.ext = level + 1 + ctx->K;
     auto digs = digits_at(ctx, level);
@@ -175,18 +205,13 @@ static const KsLevelFull &ks_level_full(cm_ctx *ctx, int level) {
     }
     get_pinv(ctx, level);
     get_qlinv(ctx, level);
-    return g_ks[key] = k;
 }
 const KsLevel &ks_level(cm_ctx *ctx, int level) { return ks_level_full(ctx, level); }
 
 static void drop_ks_levels(cm_ctx *ctx) {
     for (auto it = g_ks.begin(); it != g_ks.end();) {
         if (it->first.first != ctx) { ++it; continue; }
-        KsLevelFull &k = it->second;
-        hipFree(k.d_modup); hipFree(k.d_moddown); hipFree(k.d_bsp_rows); hipFree(k.d_bsp1_rows); hipFree(k.d_sp1_rows); hipFree(k.d_moddown0); hipFree(k.d_bsp_mods); hipFree(k.d_bq_mods);
-        hipFree(k.d_last_rows);
-        hipFree(k.d_ntt_rows); hipFree(k.d_ntt_mods); hipFree(k.d_sp_rows); hipFree(k.d_sp_mods);
-        hipFree(k.d_q_rows); hipFree(k.d_q_mods3); hipFree(k.d_last_mods); hipFree(k.d_red_mods); hipFree(k.d_red_src);
+        free_ks(it->second);
         it = g_ks.erase(it);
     }
 }
@@ -413,8 +438,12 @@ cm_status ks_many_tables_create(cm_ctx *ctx, int level, int cnt, KsManyTables *t
             rows.push_back(c * k.beta * k.ext + k.h_ntt_rows[i]), mods.push_back(k.h_ntt_mods[i]);
     }
     t->cnt = cnt, t->level = level, t->n_ntt = (int)k.h_ntt_rows.size();
-    t->d_src_rows = up(src_rows), t->d_in_mods = up(in_mods), t->d_ntt_rows = up(rows), t->d_ntt_mods = up(mods);
-    if (cnt > 0 && (!t->d_src_rows || !t->d_in_mods || !t->d_ntt_rows || !t->d_ntt_mods)) return CM_E_NOMEM;
+    try {
+        t->d_src_rows = up(src_rows), t->d_in_mods = up(in_mods), t->d_ntt_rows = up(rows), t->d_ntt_mods = up(mods);
+    } catch (const std::bad_alloc &) {
+        ks_many_tables_destroy(t);
+        return CM_E_NOMEM;
+    }
     return CM_OK;
 }
 void ks_many_tables_destroy(KsManyTables *t) {
@@ -445,45 +474,25 @@ cm_status ks_apply_many(cm_ctx *ctx, const u64 *digits, int level, int cnt, cons
     Arena A = arena_of(ctx);
     const size_t n = ctx->n, ublk = 2 * (size_t)k.ext * n, cblk = 2 * (size_t)(level + 1) * n;
     const size_t bufw = (size_t)CM_KS_BATCH * ublk;
-    // The inner products stream the keys (bandwidth-bound) on the second stream while the main
-    // stream runs the ModDown of the previous batch (transform-bound); two result buffers alternate.
-    hipStream_t aux = aux_of(ctx, st);
-    const int nbatch = (cnt + CM_KS_BATCH - 1) / CM_KS_BATCH;
-    std::vector<hipEvent_t> inner_done(nbatch), moddown_done(nbatch);
-    auto record = [&](hipStream_t s) {
-        hipEvent_t e = ctx->sync_ev[ctx->sync_next++ % ctx->sync_ev.size()];
-        hipEventRecord(e, s);
-        return e;
-    };
-    auto enqueue_inner = [&](int b) {
-        const int base = b * CM_KS_BATCH, m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
+    // batch by batch: the inner products of CM_KS_BATCH rotations (the digits read once for all of them), then their
+    // ModDown as one batch of launches; two result buffers alternate
+    (void)cblk;
+    for (int base = 0, b = 0; base < cnt; base += CM_KS_BATCH, b++) {
+        const int m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
         u64 *bu = A.bu + (b & 1) * bufw;
-        if (b >= 2) hipStreamWaitEvent(aux, moddown_done[b - 2], 0);     // its buffer has been consumed
         if (k.beta <= 8) {
-            // one digit array, m keys: the source-stationary kernel reads the digits once for the batch
             IpFan f;
             f.n = m;
             for (int r = 0; r < m; r++) f.key[r] = keys[base + r], f.out[r] = bu + r * ublk, f.ginv[r] = galois_inverse(ctx, gs[base + r]);
-            launch_inner_product_fanout(ctx, f, digits, nullptr, false, k.beta, level, aux);
+            launch_inner_product_fanout(ctx, f, digits, nullptr, false, k.beta, level, st);
         } else {
             for (int r = 0; r < m; r++)
                 launch_inner_product(ctx, bu + r * ublk, bu + r * ublk + (size_t)k.ext * n, digits, keys[base + r],
-                                     k.beta, level, gs[base + r], aux);
+                                     k.beta, level, gs[base + r], st);
         }
-        inner_done[b] = record(aux);
-    };
-    if (nbatch > 16) return CM_E_INVAL;               // the event ring holds 32
-    stream_after(ctx, aux, st);                       // digits are ready
-    if (nbatch > 0) enqueue_inner(0);
-    for (int b = 0; b < nbatch; b++) {
-        if (b + 1 < nbatch) enqueue_inner(b + 1);     // runs beside the ModDown of batch b
-        const int base = b * CM_KS_BATCH, m = cnt - base < CM_KS_BATCH ? cnt - base : CM_KS_BATCH;
-        u64 *bu = A.bu + (b & 1) * bufw;
-        hipStreamWaitEvent(st, inner_done[b], 0);
         const u64 *adds[CM_KS_BATCH];
         for (int r = 0; r < m; r++) adds[r] = in;
         moddown_batch(ctx, k, bu, m, adds, 1, gs + base, nullptr, outs + base, st);
-        moddown_done[b] = record(st);
     }
     return CM_OK;
 }
@@ -492,11 +501,13 @@ const u64 *find_key(const cm_evk *evk, u64 g) {
     auto it = evk->keys.find(g);
     return it == evk->keys.end() ? nullptr : it->second.d;
 }
+bool evk_fits(const cm_ctx *ctx, const cm_evk *evk) { return evk && evk->stored_a == ctx->evk_stored_a; }
 
 extern "C" cm_status cm_keyswitch(cm_ctx *ctx, const cm_evk *evk, int32_t step, int32_t relin, const uint64_t *d,
                                   int32_t level, uint64_t *ks0, uint64_t *ks1, void *stream) {
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
-    if (!ctx || !evk || !d || !ks0 || !ks1 || level < 0 || level > ctx->L) return CM_E_INVAL;
+    if (!ctx || !evk || !d || !ks0 || !ks1 || level < 0 || level > ctx->L || !evk_fits(ctx, evk)) return CM_E_INVAL;
+    CM_TRY
     hipStream_t st = (hipStream_t)stream;
     const u64 *key = find_key(evk, relin ? 0 : galois_of_step(ctx, step));
     if (!key) return CM_E_NOKEY;
@@ -507,35 +518,36 @@ extern "C" cm_status cm_keyswitch(cm_ctx *ctx, const cm_evk *evk, int32_t step, 
     HIPCHK(hipMemcpyAsync(ks0, A.tmp[0], bytes, hipMemcpyDeviceToDevice, st));
     HIPCHK(hipMemcpyAsync(ks1, A.tmp[0] + (size_t)(level + 1) * ctx->n, bytes, hipMemcpyDeviceToDevice, st));
     RETURN_LAUNCH_STATUS();
+    CM_CATCH
 }
 
 extern "C" cm_status cm_ntt(cm_ctx *ctx, uint64_t *dev, const int32_t *mod_idx, int32_t limbs, int32_t inverse, void *stream) {
-    if (!ctx || !dev || !mod_idx || limbs < 1 || limbs > 1024) return CM_E_INVAL;
+    if (!ctx || !dev || !mod_idx || limbs < 1 || limbs > CM_NTT_MAX_LIMBS) return CM_E_INVAL;
     for (int i = 0; i < limbs; i++)
         if (mod_idx[i] < 0 || mod_idx[i] >= ctx->nmod) return CM_E_INVAL;
-    // consecutive runs of modulus indices map onto the resident 0,1,2,.. table; anything else is staged
+    // consecutive runs of modulus indices map onto the resident 0,1,2,.. table; any other list is written into the
+    // context's staging array by a small kernel that carries the values as arguments (no copy, no allocation)
     bool iota = true;
     for (int i = 0; i < limbs; i++) iota &= (mod_idx[i] == mod_idx[0] + i);
     hipStream_t st = (hipStream_t)stream;
     if (iota) {
         launch_ntt(ctx, (u64 *)dev, iota_idx(ctx) + mod_idx[0], limbs, inverse != 0, st);
-        return CM_OK;
+    } else {
+        launch_set_idx(ctx->d_idx_stage, mod_idx, limbs, st);
+        launch_ntt(ctx, (u64 *)dev, ctx->d_idx_stage, limbs, inverse != 0, st);
     }
-    int *d_idx = nullptr;
-    HIPCHK(hipMalloc((void **)&d_idx, limbs * sizeof(int)));
-    HIPCHK(hipMemcpy(d_idx, mod_idx, limbs * sizeof(int), hipMemcpyHostToDevice));
-    launch_ntt(ctx, (u64 *)dev, d_idx, limbs, inverse != 0, st);
-    HIPCHK(hipStreamSynchronize(st));
-    hipFree(d_idx);
-    return CM_OK;
+    RETURN_LAUNCH_STATUS();
 }
 
 // ---- keys -------------------------------------------------------------------------------------------
 extern "C" cm_status cm_keygen_secret(cm_ctx *ctx, uint64_t seed, cm_sk **out) {
     if (!ctx || !out) return CM_E_INVAL;
+    CMCHK(sync_begin());
     const int n = ctx->n, h = ctx->prm.hamming;
     cm_sk *sk = new (std::nothrow) cm_sk();
     if (!sk) return CM_E_NOMEM;
+    try {
+    sk->noise = rng_key(seed, stream_id(ST_NOISE, 0, 0, 0));
     sk->coeffs.assign(n, 0);
     const u64 key = rng_key(seed, stream_id(ST_SECRET, 0, 0, 0));
     if (h == 0) {
@@ -564,10 +576,14 @@ extern "C" cm_status cm_keygen_secret(cm_ctx *ctx, uint64_t seed, cm_sk **out) {
             res[(size_t)m * n + i] = c == 0 ? 0 : (c > 0 ? 1 : ctx->mod[m] - 1);
         }
     if (hipMalloc((void **)&sk->d_ntt, res.size() * 8) != hipSuccess) { delete sk; return CM_E_NOMEM; }
-    HIPCHK(hipMemcpy(sk->d_ntt, res.data(), res.size() * 8, hipMemcpyHostToDevice));
+    if (hipMemcpy(sk->d_ntt, res.data(), res.size() * 8, hipMemcpyHostToDevice) != hipSuccess) { cm_sk_destroy(sk); return CM_E_HIP; }
+    } catch (...) {
+        cm_sk_destroy(sk);
+        return CM_E_NOMEM;
+    }
     launch_ntt(ctx, sk->d_ntt, iota_idx(ctx), ctx->nmod, false, 0);
     launch_to_mont(ctx, sk->d_ntt, iota_idx(ctx), ctx->nmod, 0);
-    HIPCHK(hipDeviceSynchronize());
+    if (hipDeviceSynchronize() != hipSuccess) { cm_sk_destroy(sk); return CM_E_HIP; }
     *out = sk;
     return CM_OK;
 }
@@ -582,23 +598,26 @@ extern "C" cm_status cm_sk_coeffs(const cm_ctx *ctx, const cm_sk *sk, int8_t *ou
     return CM_OK;
 }
 
-static cm_status make_key(cm_ctx *ctx, const cm_sk *sk, u64 g, u64 seed, EvkEntry *entry, int digits) {
+static cm_status make_key(cm_ctx *ctx, const cm_sk *sk, u64 g, u64 seed, EvkEntry *entry, int digits, bool stored_a) {
     const size_t n = ctx->n, nm = ctx->nmod;
     Arena A = arena_of(ctx);
-    // b_j for every digit, then the generator keys of the streams of a_j (a_j itself is regenerated where it is used)
-    HIPCHK(hipMalloc((void **)&entry->d, ((size_t)digits * nm * n + (size_t)digits * nm) * 8));
+    // b_j for every digit, then the generator keys of the streams of a_j; a_j itself is regenerated where it is used,
+    // or, stored_a, kept behind them in multiplier form
+    const size_t a_off = evk_a_offset(ctx);
+    const size_t words = stored_a ? a_off + (size_t)digits * nm * n : (size_t)digits * nm * n + (size_t)digits * nm;
+    if (hipMalloc((void **)&entry->d, words * 8) != hipSuccess) return CM_E_NOMEM;
     std::vector<u64> stream_keys;
     auto digs = digits_at(ctx, ctx->L);
-    u64 *d_fac = nullptr;
-    HIPCHK(hipMalloc((void **)&d_fac, nm * 8));
+    // P * (Q/Q_j) * ((Q/Q_j)^{-1} mod Q_j) is P on the digit's own limbs and 0 on all others: one row per digit, in the
+    // spare words of the arena
+    u64 *d_fac = A.misc;
     for (int j = 0; j < digits; j++) {
         u64 *b = entry->d + (size_t)j * nm * n, *a = A.tmp[1], *e = A.tmp[0];
         // a_j: drawn in the evaluation domain (no transform); limb mi uses the stream stream_id(.., j, 0) | mi
         launch_sample_uniform(ctx, a, iota_idx(ctx), (int)nm, seed, stream_id(ST_EVK_A, g, j, 0), 0);
         for (size_t mi = 0; mi < nm; mi++) stream_keys.push_back(rng_key(seed, stream_id(ST_EVK_A, g, j, 0) | (u64)mi));
-        launch_sample_gauss(ctx, e, iota_idx(ctx), (int)nm, seed, stream_id(ST_EVK_E, g, j, 0), 0);
+        launch_sample_gauss(ctx, e, iota_idx(ctx), (int)nm, seed ^ sk->noise, stream_id(ST_EVK_E, g, j, 0), 0);
         launch_ntt(ctx, e, iota_idx(ctx), (int)nm, false, 0);
-        // P * (Q/Q_j) * ((Q/Q_j)^{-1} mod Q_j) is P on the digit's own limbs and 0 on all others
         std::vector<u64> fac(nm, 0);
         for (int i : digs[j]) {
             u64 q = ctx->mod[i], P = 1;
@@ -607,9 +626,13 @@ static cm_status make_key(cm_ctx *ctx, const cm_sk *sk, u64 g, u64 seed, EvkEntr
         }
         HIPCHK(hipMemcpy(d_fac, fac.data(), nm * 8, hipMemcpyHostToDevice));
         launch_evk_assemble(ctx, b, a, e, sk->d_ntt, d_fac, g, 0);
+        if (stored_a) {
+            u64 *dst = entry->d + a_off + (size_t)j * nm * n;
+            HIPCHK(hipMemcpyAsync(dst, a, nm * n * 8, hipMemcpyDeviceToDevice, 0));
+            launch_to_mont(ctx, dst, iota_idx(ctx), (int)nm, 0);
+        }
         HIPCHK(hipDeviceSynchronize());
     }
-    hipFree(d_fac);
     HIPCHK(hipMemcpy(entry->d + (size_t)digits * nm * n, stream_keys.data(), stream_keys.size() * 8, hipMemcpyHostToDevice));
     return CM_OK;
 }
@@ -618,23 +641,35 @@ extern "C" cm_status cm_keygen_rotations(cm_ctx *ctx, const cm_sk *sk, const int
                                          int32_t with_relin, uint64_t seed, cm_evk **out) {
     if (!ctx || !sk || !out || (nsteps && !steps)) return CM_E_INVAL;
     if (3 * (ctx->L + 1) < ctx->nmod) return CM_E_INVAL;
+    CMCHK(sync_begin());
     cm_evk *evk = new (std::nothrow) cm_evk();
     if (!evk) return CM_E_NOMEM;
-    evk->digits = (ctx->L + ctx->alpha) / ctx->alpha;
-    evk->seed = seed;
-    std::vector<u64> ids;
-    for (size_t i = 0; i < nsteps; i++) ids.push_back(galois_of_step(ctx, steps[i]));
-    if (with_relin) ids.push_back(0);
-    for (u64 g : ids) {
-        if (g == 1 || evk->keys.count(g)) continue;      // step 0 needs no key
-        EvkEntry e;
-        cm_status s = make_key(ctx, sk, g, seed, &e, evk->digits);
-        if (s != CM_OK) {
-            hipFree(e.d);
-            cm_evk_destroy(evk);
-            return s == CM_E_HIP ? CM_E_NOMEM : s;
+    try {
+        evk->digits = (ctx->L + ctx->alpha) / ctx->alpha;
+        evk->seed = seed;
+        evk->stored_a = ctx->evk_stored_a;
+        std::vector<u64> ids;
+        for (size_t i = 0; i < nsteps; i++) ids.push_back(galois_of_step(ctx, steps[i]));
+        if (with_relin) ids.push_back(0);
+        for (u64 g : ids) {
+            if (g == 1 || evk->keys.count(g)) continue;      // step 0 needs no key
+            EvkEntry e;
+            cm_status s = CM_E_NOMEM;
+            try {
+                s = make_key(ctx, sk, g, seed, &e, evk->digits, evk->stored_a);
+                if (s == CM_OK) evk->keys[g] = e;
+            } catch (...) {
+                s = CM_E_NOMEM;
+            }
+            if (s != CM_OK) {
+                hipFree(e.d);
+                cm_evk_destroy(evk);
+                return s;
+            }
         }
-        evk->keys[g] = e;
+    } catch (...) {
+        cm_evk_destroy(evk);
+        return CM_E_NOMEM;
     }
     *out = evk;
     return CM_OK;
@@ -649,10 +684,13 @@ extern "C" cm_status cm_evk_export(cm_ctx *ctx, const cm_evk *evk, int32_t step,
     if (!ctx || !evk || !out || digit < 0 || digit >= evk->digits || comp < 0 || comp > 1) return CM_E_INVAL;
     const u64 *key = find_key(evk, relin ? 0 : galois_of_step(ctx, step));
     if (!key) return CM_E_NOKEY;
+    CMCHK(sync_begin());
     const size_t n = ctx->n, nm = ctx->nmod;
     Arena A = arena_of(ctx);
     if (comp == 0) {
         launch_from_mont(ctx, A.tmp[0], key + (size_t)digit * nm * n, iota_idx(ctx), (int)nm, 0);
+    } else if (evk->stored_a) {
+        launch_from_mont(ctx, A.tmp[0], key + evk_a_offset(ctx) + (size_t)digit * nm * n, iota_idx(ctx), (int)nm, 0);
     } else {
         // a_j is not stored: its limbs are the uniform streams of (seed, key id, digit), in the evaluation domain
         const u64 g = relin ? 0 : galois_of_step(ctx, step);
@@ -666,6 +704,7 @@ extern "C" cm_status cm_evk_export(cm_ctx *ctx, const cm_evk *evk, int32_t step,
 // ---- plaintexts, encryption, decryption ----------------------------------------------------------------
 extern "C" cm_status cm_pt_from_coeffs(cm_ctx *ctx, const int64_t *coeffs, int32_t level, double scale, cm_pt *out) {
     if (!ctx || !coeffs || !out || !out->dev || level < 0 || level > ctx->L || !(scale > 0)) return CM_E_INVAL;
+    CMCHK(sync_begin());
     Arena A = arena_of(ctx);
     HIPCHK(hipMemcpy(A.misc, coeffs, (size_t)ctx->n * 8, hipMemcpyHostToDevice));
     launch_reduce_i64(ctx, out->dev, (const long long *)A.misc, iota_idx(ctx), level + 1, 0);
@@ -679,21 +718,24 @@ extern "C" cm_status cm_pt_from_coeffs(cm_ctx *ctx, const int64_t *coeffs, int32
 extern "C" cm_status cm_encode(cm_ctx *ctx, const double *re, const double *im, size_t nslots, int32_t level,
                                double scale, cm_pt *out) {
     if (!ctx || !out) return CM_E_INVAL;
+    CM_TRY
     if (scale == 0) scale = ctx->prm.scale;
     std::vector<int64_t> c(ctx->n);
     CMCHK(cm_encode_coeffs(ctx, re, im, nslots, scale, c.data()));
     return cm_pt_from_coeffs(ctx, c.data(), level, scale, out);
+    CM_CATCH
 }
 
 extern "C" cm_status cm_encrypt(cm_ctx *ctx, const cm_sk *sk, const cm_pt *pt, uint64_t seed, cm_ct *out) {
     if (!ctx || !sk || !pt || !pt->dev || !out || !out->dev || pt->mont) return CM_E_INVAL;
     if (pt->level < 0 || pt->level > ctx->L) return CM_E_LEVEL;
+    CMCHK(sync_begin());
     const int limbs = pt->level + 1;
     const size_t n = ctx->n;
     Arena A = arena_of(ctx);
     u64 *c0 = out->dev, *c1 = out->dev + (size_t)limbs * n, *e = A.tmp[0];
     launch_sample_uniform(ctx, c1, iota_idx(ctx), limbs, seed, stream_id(ST_ENC_A, 0, 0, 0), 0);
-    launch_sample_gauss(ctx, e, iota_idx(ctx), limbs, seed, stream_id(ST_ENC_E, 0, 0, 0), 0);
+    launch_sample_gauss(ctx, e, iota_idx(ctx), limbs, seed ^ sk->noise, stream_id(ST_ENC_E, 0, 0, 0), 0);
     launch_ntt(ctx, c1, iota_idx(ctx), limbs, false, 0);
     launch_ntt(ctx, e, iota_idx(ctx), limbs, false, 0);
     launch_encrypt(ctx, c0, c1, e, sk->d_ntt, pt->dev, limbs, 0);
@@ -706,6 +748,7 @@ extern "C" cm_status cm_encrypt(cm_ctx *ctx, const cm_sk *sk, const cm_pt *pt, u
 
 extern "C" cm_status cm_decrypt(cm_ctx *ctx, const cm_sk *sk, const cm_ct *ct, cm_pt *out) {
     if (!ctx || !sk || !ct_ok(ctx, ct) || !out || !out->dev) return CM_E_INVAL;
+    CMCHK(sync_begin());
     const int limbs = (ct->level >= 1 ? 1 : 0) + 1;
     launch_decrypt(ctx, out->dev, ct->dev, sk->d_ntt, ct->ncomp, ct->level + 1, limbs, 0);
     HIPCHK(hipDeviceSynchronize());
@@ -718,6 +761,8 @@ extern "C" cm_status cm_decrypt(cm_ctx *ctx, const cm_sk *sk, const cm_ct *ct, c
 extern "C" cm_status cm_decode(cm_ctx *ctx, const cm_pt *pt, double *re, double *im, size_t nslots) {
     if (!ctx || !pt || !pt->dev || !re || pt->mont || nslots > (size_t)ctx->n / 2) return CM_E_INVAL;
     if (pt->level < 0 || pt->level > 1) return CM_E_LEVEL;
+    CM_TRY
+    CMCHK(sync_begin());
     const size_t n = ctx->n;
     const int limbs = pt->level + 1;
     Arena A = arena_of(ctx);
@@ -744,9 +789,12 @@ extern "C" cm_status cm_decode(cm_ctx *ctx, const cm_pt *pt, double *re, double 
     }
     decode_host(ctx, m, re, im, nslots);
     return CM_OK;
+    CM_CATCH
 }
 
 static cm_status export_rows(cm_ctx *ctx, const u64 *dev, int ncomp, int level, bool mont, u64 *out) {
+    CM_TRY
+    CMCHK(sync_begin());
     const size_t n = ctx->n, rows = (size_t)ncomp * (level + 1);
     const KsLevelFull &k = ks_level_full(ctx, level);
     u64 *stage = nullptr;
@@ -760,6 +808,7 @@ static cm_status export_rows(cm_ctx *ctx, const u64 *dev, int ncomp, int level, 
     hipFree(stage);
     HIPCHK(e);
     return CM_OK;
+    CM_CATCH
 }
 extern "C" cm_status cm_ct_export(cm_ctx *ctx, const cm_ct *ct, uint64_t *out) {
     if (!ctx || !ct_ok(ctx, ct) || !out) return CM_E_INVAL;
@@ -781,22 +830,23 @@ extern "C" cm_status cm_add(cm_ctx *ctx, const cm_ct *a, const cm_ct *b, cm_ct *
 }
 extern "C" cm_status cm_mul_pt(cm_ctx *ctx, const cm_ct *a, const cm_pt *pt, cm_ct *out, void *stream) {
     if (!ctx || !ct_ok(ctx, a) || !pt || !pt->dev || !pt->mont || !out || !out->dev) return CM_E_INVAL;
-    if (a->level != pt->level) return CM_E_LEVEL;
+    if (a->level != pt->level || a->level < 1) return CM_E_LEVEL;      // no level left to rescale into
     launch_mul_pt(ctx, out->dev, a->dev, pt->dev, a->ncomp, a->level + 1, (hipStream_t)stream);
     out->level = a->level, out->ncomp = a->ncomp, out->scale = a->scale * pt->scale;
     return CM_OK;
 }
 extern "C" cm_status cm_mul_ct(cm_ctx *ctx, const cm_ct *a, const cm_ct *b, cm_ct *out, void *stream) {
     if (!ctx || !ct_ok(ctx, a) || !ct_ok(ctx, b) || !out || !out->dev || a->ncomp != 2 || b->ncomp != 2) return CM_E_INVAL;
-    if (a->level != b->level) return CM_E_LEVEL;
+    if (a->level != b->level || a->level < 1) return CM_E_LEVEL;
     launch_tensor(ctx, out->dev, a->dev, b->dev, a->level + 1, 0, (hipStream_t)stream);
     out->level = a->level, out->ncomp = 3, out->scale = a->scale * b->scale;
     return CM_OK;
 }
 extern "C" cm_status cm_relinearize(cm_ctx *ctx, const cm_evk *evk, const cm_ct *a, cm_ct *out, void *stream) {
-    if (!ctx || !evk || !ct_ok(ctx, a) || a->ncomp != 3 || !out || !out->dev) return CM_E_INVAL;
+    if (!ctx || !evk || !ct_ok(ctx, a) || a->ncomp != 3 || !out || !out->dev || !evk_fits(ctx, evk)) return CM_E_INVAL;
     const u64 *key = find_key(evk, 0);
     if (!key) return CM_E_NOKEY;
+    CM_TRY
     hipStream_t st = (hipStream_t)stream;
     Arena A = arena_of(ctx);
     const size_t ln = (size_t)(a->level + 1) * ctx->n;
@@ -804,18 +854,19 @@ extern "C" cm_status cm_relinearize(cm_ctx *ctx, const cm_evk *evk, const cm_ct 
     CMCHK(ks_apply(ctx, A.digits, key, a->level, 0, a->dev, 2, out->dev, st));
     out->level = a->level, out->ncomp = 2, out->scale = a->scale;
     return CM_OK;
+    CM_CATCH
 }
 
-cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st, u64 *last, u64 *red,
-                       bool accumulate) {
-    // out[comp][level][n]; must not alias in.  More than three components (several stacked
-    // ciphertexts) need caller scratch: last[ncomp][n], red[ncomp][level][n].  accumulate: out += the result.
-    const KsLevelFull &k = ks_level_full(ctx, level);
-    Arena A = arena_of(ctx);
-    if (ncomp < 1 || ncomp > RESCALE_MAX_COMPS || (ncomp > 3 && (!last || !red))) return CM_E_INVAL;
-    if (!last) last = A.misc;
-    if (!red) red = A.tmp[2];
-    launch_ntt_src(ctx, last, nullptr, in, k.d_last_rows, k.d_last_mods, ncomp, true, st);
+// the small tables a rescale reads: rows / moduli of the last limbs and of the limbs that take their residues,
+// q_level^-1 mod q_i with Shoup companions, and whether the last limb's residues fit the other limbs as they are
+struct RescaleTabs {
+    const int *last_rows, *last_mods, *red_mods, *red_src;
+    const u64 *qlinv;
+    bool last_fits;
+};
+static cm_status rescale_core(cm_ctx *ctx, const RescaleTabs &k, const u64 *in, int ncomp, int level, u64 *out,
+                              hipStream_t st, u64 *last, u64 *red, bool accumulate) {
+    launch_ntt_src(ctx, last, nullptr, in, k.last_rows, k.last_mods, ncomp, true, st);
     const bool fused = ctx->n == 65536 && ncomp % 2 == 0;
     // the residues of the last limb enter the transforms of the other limbs reduced to their moduli; where the last
     // modulus is below twice the others the first pass of the fused transform takes them as they are (the transform is
@@ -831,14 +882,26 @@ cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *ou
             fb.u[r] = in + (size_t)r * 2 * (level + 1) * ctx->n, fb.out[r] = out + (size_t)r * 2 * level * ctx->n;
             fb.accum[r] = accumulate ? fb.out[r] : nullptr;
         }
-        fb.pinv = get_qlinv(ctx, level);
-        if (k.last_fits) launch_ntt_fwd_finish(ctx, red, k.d_red_mods, fb, st, last, k.d_red_src);
-        else launch_ntt_fwd_finish(ctx, red, k.d_red_mods, fb, st);
+        fb.pinv = k.qlinv;
+        if (k.last_fits) launch_ntt_fwd_finish(ctx, red, k.red_mods, fb, st, last, k.red_src);
+        else launch_ntt_fwd_finish(ctx, red, k.red_mods, fb, st);
         return CM_OK;
     }
-    launch_ntt(ctx, red, k.d_red_mods, ncomp * level, false, st);
-    launch_rescale_finish(ctx, out, in, red, get_qlinv(ctx, level), ncomp, level, st, accumulate);
+    launch_ntt(ctx, red, k.red_mods, ncomp * level, false, st);
+    launch_rescale_finish(ctx, out, in, red, k.qlinv, ncomp, level, st, accumulate);
     return CM_OK;
+}
+cm_status rescale_into(cm_ctx *ctx, const u64 *in, int ncomp, int level, u64 *out, hipStream_t st, u64 *last, u64 *red,
+                       bool accumulate) {
+    // out[comp][level][n]; must not alias in.  More than three components (several stacked
+    // ciphertexts) need caller scratch: last[ncomp][n], red[ncomp][level][n].  accumulate: out += the result.
+    const KsLevelFull &k = ks_level_full(ctx, level);
+    Arena A = arena_of(ctx);
+    if (ncomp < 1 || ncomp > RESCALE_MAX_COMPS || (ncomp > 3 && (!last || !red))) return CM_E_INVAL;
+    if (!last) last = A.misc;
+    if (!red) red = A.tmp[2];
+    const RescaleTabs t{k.d_last_rows, k.d_last_mods, k.d_red_mods, k.d_red_src, get_qlinv(ctx, level), k.last_fits};
+    return rescale_core(ctx, t, in, ncomp, level, out, st, last, red, accumulate);
 }
 // out[r] (+)= rescale(src_r * (pt through the Galois map g_r)) for r < cnt, src_r = mb.src[r] ([2][level+1][n]), out
 // stacked at stride 2*level*n: the products are never stored; only their last limbs are formed (for the inverse
@@ -848,7 +911,7 @@ bool rescale_masked_into(cm_ctx *ctx, const MulPtBatch &mb, int cnt, const u64 *
                          u64 *last, u64 *red, bool accumulate) {
     const KsLevelFull &k = ks_level_full(ctx, level);
     if (ctx->n != 65536 || !k.last_fits || cnt < 1 || cnt > CM_KS_BATCH || !last || !red) return false;
-    if (getenv("CM_TWO_STEP_MASKS")) return false;          // parity switch: multiply, store, then rescale
+    if (ctx->two_step_masks) return false;                  // CM_OPT_TWO_STEP_MASKS: multiply, store, then rescale
     launch_mul_pt_rot_last(ctx, last, mb, cnt, pt, level + 1, st);
     launch_ntt(ctx, last, k.d_last_mods, 2 * cnt, true, st);
     FinishBatch fb;
@@ -866,6 +929,7 @@ bool rescale_masked_into(cm_ctx *ctx, const MulPtBatch &mb, int cnt, const u64 *
 extern "C" cm_status cm_rescale(cm_ctx *ctx, const cm_ct *a, cm_ct *out, void *stream) {
     if (!ctx || !ct_ok(ctx, a) || !out || !out->dev) return CM_E_INVAL;
     if (a->level < 1) return CM_E_LEVEL;
+    CM_TRY
     hipStream_t st = (hipStream_t)stream;
     Arena A = arena_of(ctx);
     const int level = a->level;
@@ -877,6 +941,7 @@ extern "C" cm_status cm_rescale(cm_ctx *ctx, const cm_ct *a, cm_ct *out, void *s
     out->scale = a->scale / (double)ctx->mod[level];
     out->level = level - 1;
     return CM_OK;
+    CM_CATCH
 }
 extern "C" cm_status cm_level_drop(cm_ctx *ctx, const cm_ct *a, int32_t level, cm_ct *out, void *stream) {
     if (!ctx || !ct_ok(ctx, a) || !out || !out->dev) return CM_E_INVAL;
@@ -905,7 +970,8 @@ cm_status rotate_into(cm_ctx *ctx, const u64 *key, const u64 *in, int level, u64
 }
 extern "C" cm_status cm_rotate(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, int32_t step, cm_ct *out, void *stream) {
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
-    if (!ctx || !evk || !ct_ok(ctx, in) || in->ncomp != 2 || !out || !out->dev) return CM_E_INVAL;
+    if (!ctx || !evk || !ct_ok(ctx, in) || in->ncomp != 2 || !out || !out->dev || !evk_fits(ctx, evk)) return CM_E_INVAL;
+    CM_TRY
     hipStream_t st = (hipStream_t)stream;
     const u64 g = galois_of_step(ctx, step);
     if (g == 1) {
@@ -924,11 +990,13 @@ extern "C" cm_status cm_rotate(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, 
     }
     out->level = in->level, out->ncomp = 2, out->scale = in->scale;
     RETURN_LAUNCH_STATUS();
+    CM_CATCH
 }
 extern "C" cm_status cm_rotate_hoisted(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, const int32_t *steps,
                                        size_t nsteps, cm_ct *outs, void *stream) {
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
-    if (!ctx || !evk || !ct_ok(ctx, in) || in->ncomp != 2 || !steps || !outs) return CM_E_INVAL;
+    if (!ctx || !evk || !ct_ok(ctx, in) || in->ncomp != 2 || !steps || !outs || !evk_fits(ctx, evk)) return CM_E_INVAL;
+    CM_TRY
     hipStream_t st = (hipStream_t)stream;
     for (size_t i = 0; i < nsteps; i++) {
         if (!outs[i].dev || outs[i].dev == in->dev) return CM_E_INVAL;
@@ -952,4 +1020,5 @@ extern "C" cm_status cm_rotate_hoisted(cm_ctx *ctx, const cm_evk *evk, const cm_
     }
     CMCHK(ks_apply_many(ctx, A.digits, in->level, (int)keys.size(), keys.data(), gs.data(), in->dev, dst.data(), st));
     RETURN_LAUNCH_STATUS();
+    CM_CATCH
 }

@@ -48,6 +48,7 @@ extern "C" cm_status cm_rope_create(cm_ctx *ctx, int32_t heads, int32_t dim, int
     if (tau < -1 || tau >= t) return CM_E_LAYOUT;
     cm_rope *r = new (std::nothrow) cm_rope();
     if (!r) return CM_E_NOMEM;
+    try {
     r->ctx = ctx, r->S = S, r->H = heads, r->E = dim, r->t = t, r->level = level, r->token = token, r->tau = tau, r->base = base;
     r->step_up = heads * t, r->step_dn = -(heads * t);
     const size_t n = ctx->n, ln = (size_t)(level + 1) * n;
@@ -79,6 +80,10 @@ extern "C" cm_status cm_rope_create(cm_ctx *ctx, int32_t heads, int32_t dim, int
     if (s != CM_OK) { cm_rope_destroy(r); return s; }
     *out = r;
     return CM_OK;
+    } catch (...) {
+        cm_rope_destroy(r);
+        return CM_E_NOMEM;
+    }
 }
 // Inner rotation (Sec. 5.4): residue tau of every block of t slots moves to residue (tau + delta) mod t.  The same
 // shape as the embedding: p0 = 0, p2 = the residues below t - delta (rotated by -delta), p1 = the others (rotated by
@@ -91,6 +96,7 @@ extern "C" cm_status cm_inner_rot_create(cm_ctx *ctx, int32_t t, int32_t delta, 
     if (!pow2(t) || t < 2 || t > S || delta < 1 || delta >= t) return CM_E_LAYOUT;
     cm_rope *r = new (std::nothrow) cm_rope();
     if (!r) return CM_E_NOMEM;
+    try {
     r->ctx = ctx, r->S = S, r->H = 1, r->E = S / t, r->t = t, r->level = level, r->token = 0, r->tau = 0, r->base = 0;
     r->step_up = -delta, r->step_dn = t - delta;
     const size_t n = ctx->n, ln = (size_t)(level + 1) * n;
@@ -112,6 +118,10 @@ extern "C" cm_status cm_inner_rot_create(cm_ctx *ctx, int32_t t, int32_t delta, 
     if (s != CM_OK) { cm_rope_destroy(r); return s; }
     *out = r;
     return CM_OK;
+    } catch (...) {
+        cm_rope_destroy(r);
+        return CM_E_NOMEM;
+    }
 }
 extern "C" void cm_rope_destroy(cm_rope *r) {
     if (!r) return;
@@ -127,9 +137,11 @@ extern "C" int32_t cm_rope_steps(const cm_rope *r, int32_t *steps, int32_t cap) 
 }
 extern "C" cm_status cm_rope_apply(cm_ctx *ctx, const cm_evk *evk, const cm_rope *r, const cm_ct *x, cm_ct *y, void *stream) {
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
-    if (!ctx || !evk || !r || r->ctx != ctx || !x || !x->dev || x->ncomp != 2 || !y || !y->dev || y->dev == x->dev)
+    if (!ctx || !evk || !r || r->ctx != ctx || !x || !x->dev || x->ncomp != 2 || !y || !y->dev || y->dev == x->dev ||
+        !evk_fits(ctx, evk))
         return CM_E_INVAL;
     if (x->level != r->level) return CM_E_LEVEL;
+    CM_TRY
     hipStream_t st = (hipStream_t)stream;
     const int level = r->level, limbs = level + 1;
     const u64 g_up = galois_of_step(ctx, r->step_up), g_dn = galois_of_step(ctx, r->step_dn);
@@ -145,4 +157,5 @@ extern "C" cm_status cm_rope_apply(cm_ctx *ctx, const cm_evk *evk, const cm_rope
     y->level = level - 1, y->ncomp = 2;
     y->scale = x->scale;                                          // plaintext scale = the prime just removed
     RETURN_LAUNCH_STATUS();
+    CM_CATCH
 }

@@ -191,6 +191,7 @@ extern "C" cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_
     const bool direct = unrolled || (flags & CM_VMM_DIRECT_GIANTS) != 0, raised = direct || (flags & CM_VMM_RAISED_SUMS) != 0;
     cm_vmm_plan *p = new (std::nothrow) cm_vmm_plan();
     if (!p) return CM_E_NOMEM;
+    try {
     cm_status s = plan_shape(ctx, d_in, d_out, r_i, tau, level, pt_scale, (flags & CM_VMM_TOKEN_BATCH) != 0,
                              raised || (flags & CM_VMM_TOKEN_BATCH) != 0, p);
     if (s == CM_OK) s = plan_alloc(p, raised, direct, unrolled);
@@ -224,6 +225,10 @@ extern "C" cm_status cm_vmm_plan_create_ex(cm_ctx *ctx, int32_t d_in, int32_t d_
     if (s != CM_OK) { cm_vmm_plan_destroy(p); return s; }
     *out = p;
     return CM_OK;
+    } catch (...) {                  // host allocation (tables, encoder threads): the plan's device memory is released
+        cm_vmm_plan_destroy(p);
+        return CM_E_NOMEM;
+    }
 }
 extern "C" cm_status cm_vmm_plan_create(cm_ctx *ctx, int32_t d_in, int32_t d_out, int32_t r_i, int32_t tau,
                                         int32_t level, double pt_scale, const double *W, cm_vmm_plan **out) {
@@ -260,9 +265,13 @@ static std::vector<int> plan_all_steps(const cm_vmm_plan *p) {
 }
 extern "C" int32_t cm_vmm_plan_steps(const cm_vmm_plan *p, int32_t *steps, int32_t cap) {
     if (!p) return 0;
-    std::vector<int> all = plan_all_steps(p);
-    for (int i = 0; i < (int)all.size() && i < cap && steps; i++) steps[i] = all[i];
-    return (int32_t)all.size();
+    try {
+        std::vector<int> all = plan_all_steps(p);
+        for (int i = 0; i < (int)all.size() && i < cap && steps; i++) steps[i] = all[i];
+        return (int32_t)all.size();
+    } catch (...) {
+        return 0;
+    }
 }
 extern "C" cm_status cm_vmm_plan_info(const cm_vmm_plan *p, int32_t *r_i, int32_t *r_o, int32_t *n_rot) {
     if (!p) return CM_E_INVAL;
@@ -283,6 +292,7 @@ extern "C" cm_status cm_vmm_plan_diag_export(cm_ctx *ctx, const cm_vmm_plan *p, 
     if (!ctx || !p || !out || j < 0 || j >= p->r_i || k < 0 || k >= p->r_o) return CM_E_INVAL;
     const size_t words = (size_t)p->pt_limbs * ctx->n;
     u64 *tmp = nullptr;
+    HIPCHK(hipDeviceSynchronize());
     if (hipMalloc((void **)&tmp, words * 8) != hipSuccess) return CM_E_NOMEM;
     launch_pt_block(ctx, p->d_pts, tmp, p->pt_limbs, p->r_i, p->r_o, j, k, false, 0);
     launch_from_mont(ctx, tmp, tmp, p->d_pt_mods, p->pt_limbs, 0);
@@ -465,7 +475,8 @@ static cm_status plan_keys_present(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_
 extern "C" cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *const *plans, int32_t nplans,
                                      const cm_ct *x, cm_ct *const *ys, void *stream) {
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
-    if (!ctx || !evk || !plans || nplans < 1 || !x || !x->dev || x->ncomp != 2 || !ys) return CM_E_INVAL;
+    if (!ctx || !evk || !plans || nplans < 1 || !x || !x->dev || x->ncomp != 2 || !ys || !evk_fits(ctx, evk)) return CM_E_INVAL;
+    CM_TRY
     const cm_vmm_plan *p0 = plans[0];
     for (int i = 0; i < nplans; i++) {
         const cm_vmm_plan *p = plans[i];
@@ -483,13 +494,15 @@ extern "C" cm_status cm_vmm_pt_multi(cm_ctx *ctx, const cm_evk *evk, const cm_vm
     CMCHK(vmm_raised_babies(ctx, evk, p0, x, st));
     for (int i = 0; i < nplans; i++) CMCHK(vmm_raised_finish(ctx, evk, plans[i], p0->d_work, x, ys[i], st));
     return CM_OK;
+    CM_CATCH
 }
 
 extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan *p, const cm_ct *x, cm_ct *y,
                                void *stream) {
     (void)hipGetLastError();          // stale errors of earlier calls are not this call's
-    if (!ctx || !evk || !p || !x || !x->dev || !y || !y->dev || x->ncomp != 2 || p->ctx != ctx) return CM_E_INVAL;
+    if (!ctx || !evk || !p || !x || !x->dev || !y || !y->dev || x->ncomp != 2 || p->ctx != ctx || !evk_fits(ctx, evk)) return CM_E_INVAL;
     if (x->level != p->level) return CM_E_LEVEL;
+    CM_TRY
     hipStream_t st = (hipStream_t)stream;
     const int level = p->level, limbs = level + 1;
     const size_t n = ctx->n, ctw = 2 * (size_t)limbs * n, ptw = (size_t)limbs * n;
@@ -541,4 +554,5 @@ extern "C" cm_status cm_vmm_pt(cm_ctx *ctx, const cm_evk *evk, const cm_vmm_plan
     y->level = level - 1, y->ncomp = 2;
     y->scale = x->scale * p->pt_scale / (double)ctx->mod[level];
     RETURN_LAUNCH_STATUS();
+    CM_CATCH
 }

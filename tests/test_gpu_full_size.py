@@ -348,11 +348,10 @@ def test_prompt_phase_attention_of_a_query_group_on_the_full_ring(ring2):
 
 
 def test_appends_with_the_masked_product_inside_the_rescale_equal_the_two_step_appends(ring2):
-    """At n = 2^16 an append forms its masked products inside the tail of the rescale's transform; with
-    CM_TWO_STEP_MASKS in the environment it multiplies, stores and rescales (the path the small-ring tests
+    """At n = 2^16 an append forms its masked products inside the tail of the rescale's transform; with the
+    context option CM_OPT_TWO_STEP_MASKS it multiplies, stores and rescales (the path the small-ring tests
     check limb for limb against the oracle).  Same cache, same key index, bit for bit: one token group and
     two single tokens."""
-    import os
     from oracle import packing
     B, octx, gctx, prm = ring2
     H, E, lv = 32, 128, 4
@@ -367,14 +366,13 @@ def test_appends_with_the_masked_product_inside_the_rescale_equal_the_two_step_a
         kv = gctx.kv_create(H, E, lv, r_i=16, key_index=True)
         if keys is None:
             keys = gctx.keygen_rotations(gsk, kv.steps(), 2, with_relin=True)
-        if two_step:
-            os.environ["CM_TWO_STEP_MASKS"] = "1"
+        gctx.set_option(B.CM_OPT_TWO_STEP_MASKS, two_step)
         try:
             kv.append_group(keys, *news[0])
             kv.append(keys, *news[1])
             kv.append(keys, *news[2])
         finally:
-            os.environ.pop("CM_TWO_STEP_MASKS", None)
+            gctx.set_option(B.CM_OPT_TWO_STEP_MASKS, False)
         caches.append(kv)
     a, b = caches
     assert a.tokens() == b.tokens() == lay.t + 2
@@ -383,106 +381,6 @@ def test_appends_with_the_masked_product_inside_the_rescale_equal_the_two_step_a
         assert np.array_equal(a.export(B.CM_KV_INDEX, k), b.export(B.CM_KV_INDEX, k)), k
     assert np.array_equal(a.export(B.CM_QK, 0), b.export(B.CM_QK, 0))
     assert np.array_equal(a.export(B.CM_QK, 1), b.export(B.CM_QK, 1))
-
-
-def test_config5_decode_steps_on_the_36_plus_6_ring(ring2):
-    """Two decode steps of one Llama-3-8B-shaped layer's linear path on the 36 + 6 prime ring: k / v /
-    q projections (8 KV heads replicated to 32 by repeating weight columns, columns ordered as the
-    cache wants them), append of the encrypted k / v to a cache that already holds 16 tokens,
-    the rotary embedding of q and k with the extraction fused (Sec. 4.2), q K^T against the cache,
-    scores V, and the output projection; every stage decrypted and compared with float64.
-    (Softmax and the normalisations sit between these stages in the model and are outside this
-    path: the scores fed to scores V are a fresh encryption, and the extraction the model merges
-    into its layer norm is a plain mask product before the output projection.)"""
-    from oracle import packing
-    from paper_2602_11470_amd import inputs
-    ring2[2].close()
-    B, octx, gctx, prm = _llama(36, 6)
-    try:
-        H, E, d, L = 32, 128, 4096, gctx.L
-        lay = packing.KvLayout(gctx.S, H, E, 16)
-        t = lay.t
-        rng = np.random.default_rng(5)
-        Wq, Wo = rng.normal(0, 0.02, (d, d)), rng.normal(0, 0.02, (d, d))
-        Wk8, Wv8 = rng.normal(0, 0.02, (d, 8 * E)), rng.normal(0, 0.02, (d, 8 * E))
-        # column a = e*H + h of the packed weights is column [h, e] of the model's (KV head h // 4)
-        a = np.arange(d)
-        e_of, h_of = a // H, a % H
-        Wq_p = Wq[:, h_of * E + e_of]
-        Wk_p, Wv_p = Wk8[:, (h_of // 4) * E + e_of], Wv8[:, (h_of // 4) * E + e_of]
-        Wo_p = Wo[h_of * E + e_of, :]                      # rows follow the attention output layout
-        gsk = gctx.keygen_secret(1)
-        cache_lv = L - 3                     # projection, rotary embedding, append mask: one level each
-        kv = gctx.kv_create(H, E, cache_lv, r_i=16)
-        plan_q = gctx.vmm_plan(d, d, W=Wq_p, level=L, unrolled_ladders=True)
-        plan_o = gctx.vmm_plan(d, d, W=Wo_p, level=cache_lv - 2, unrolled_ladders=True)
-        residue0 = np.zeros(gctx.S)
-        residue0[::t] = 1.0
-
-        def extract(ct):
-            """Keep residue 0 of every block: mask encoded at the scale of the prime the rescale removes."""
-            mask = gctx.encode(residue0, ct.level, float(prm.moduli[ct.level]), mont=True)
-            return gctx.rescale(gctx.mul_pt(ct, mask))
-        steps = set(kv.steps()) | set(plan_q.steps()) | set(plan_o.steps()) | {H * t, -H * t}
-        gkeys = gctx.keygen_rotations(gsk, sorted(steps), 2, with_relin=True)
-        enc = lambda slots, level, seed, scale=0.0: gctx.level_drop(
-            gctx.encrypt(gsk, gctx.encode(slots, L, scale), seed), level)
-        n0 = 16
-        _, K, V, _ = inputs.attention_inputs(4, H, 8, E, n0)
-        # a cache holds one scale: the tokens already there carry the scale a projection leaves
-        proj_scale = prm.scale * prm.scale / float(prm.moduli[L])
-        for c in range(n0 // t):
-            kv.load(B.CM_QK, c, enc(lay.pack_k(K, c), cache_lv, 100 + c, proj_scale))
-        for k in range(E):
-            kv.load(B.CM_SV, k, enc(lay.pack_v(V, k), cache_lv, 300 + k, proj_scale))
-        kv.set_tokens(n0)
-        K, V = list(K), list(V)
-
-        def rope_ref(v, n):
-            out = np.empty_like(v)
-            for m in range(E // 2):
-                th = n * 10000.0 ** (-2.0 * m / E)
-                out[:, 2 * m] = v[:, 2 * m] * np.cos(th) - v[:, 2 * m + 1] * np.sin(th)
-                out[:, 2 * m + 1] = v[:, 2 * m + 1] * np.cos(th) + v[:, 2 * m] * np.sin(th)
-            return out
-
-        for step in range(2):
-            n = n0 + step
-            tau = n % t
-            x = rng.normal(size=d)
-            slots = np.zeros(gctx.S)
-            slots[::t] = x
-            gx = enc(slots, L, 500 + step)
-            # k and v land on residue tau, ready for the append
-            plan_k = gctx.vmm_plan(d, d, W=Wk_p, level=L, tau=tau, unrolled_ladders=True)
-            plan_v = gctx.vmm_plan(d, d, W=Wv_p, level=L, tau=tau, unrolled_ladders=True)
-            gk = gctx.vmm_pt(gkeys, plan_k, gx)
-            gv = gctx.vmm_pt(gkeys, plan_v, gx)
-            k_ref = rope_ref((x @ Wk8).reshape(8, E).repeat(4, axis=0), n)          # [h, e]
-            v_ref = (x @ Wv8).reshape(8, E).repeat(4, axis=0)
-            gk = gctx.rope_apply(gkeys, gctx.rope(H, E, L - 1, n, tau), gk)         # level L-2, other slots clean
-            assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, gk).real, tau) - k_ref).max() < TOL
-            kv.append(gkeys, gk, gctx.level_drop(gv, L - 2))
-            K.append(k_ref), V.append(v_ref)
-            del plan_k, plan_v
-            assert kv.tokens() == n + 1
-            gq = gctx.rope_apply(gkeys, gctx.rope(H, E, L - 1, n, 0), gctx.vmm_pt(gkeys, plan_q, gx))
-            q_ref = rope_ref((x @ Wq).reshape(H, E), n)
-            assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, gq).real) - q_ref).max() < TOL
-            gm = gctx.vmm_kv(gkeys, kv, B.CM_QK, gctx.level_drop(gq, cache_lv))
-            Ka, Va = np.stack(K), np.stack(V)
-            m_ref = np.einsum("he,nhe->hn", q_ref, Ka)
-            assert np.abs(lay.unpack_scores(gctx.decrypt(gsk, gm).real, n + 1) - m_ref).max() < 20 * TOL   # |m| ~ 10
-            sc = np.abs(m_ref)
-            sc /= sc.sum(axis=1, keepdims=True)
-            ga = gctx.vmm_kv(gkeys, kv, B.CM_SV, enc(lay.pack_scores(sc), cache_lv, 700 + step))
-            att_ref = np.einsum("hn,nhe->he", sc, Va)
-            assert np.abs(lay.unpack_vec(gctx.decrypt(gsk, ga).real) - att_ref).max() < TOL
-            gy = gctx.vmm_pt(gkeys, plan_o, extract(ga))
-            y_ref = att_ref.reshape(-1) @ Wo
-            assert np.abs(gctx.decrypt(gsk, gy).real[::t] - y_ref).max() < TOL
-    finally:
-        gctx.close()
 
 
 def test_config5_ring_rotation(ring2):

@@ -112,6 +112,13 @@ def test_add_mul_rescale(both, level):
     o2, g2 = _pair(b, z2, level, 22)
     _same(b, octx.ct_add(o1, o2), gctx.add(g1, g2))
     c = octx.encode_coeffs(z2, octx.prm.scale)
+    if level == 0:
+        # no level left to rescale into: the multiplying calls refuse (the oracle has no such rule; it just multiplies)
+        for call in (lambda: gctx.mul_pt(g1, gctx.pt_from_coeffs(c, level, octx.prm.scale, mont=True)), lambda: gctx.mul_ct(g1, g2)):
+            with pytest.raises(b["B"].CachemirError) as err:
+                call()
+            assert err.value.status == -2
+        return
     om = octx.mul_pt(o1, octx.pt_from_coeffs(c, level, octx.prm.scale))
     gm = gctx.mul_pt(g1, gctx.pt_from_coeffs(c, level, octx.prm.scale, mont=True))
     _same(b, om, gm)

@@ -844,3 +844,44 @@ def test_kv_sv_on_54_bit_primes_matches_oracle(env, r_i):
         assert np.abs(lay.unpack_vec(gctx.decrypt(e["gsk"], ga).real) - np.einsum("hn,nhe->he", s, V)).max() < TOL
     finally:
         gctx.close()
+
+
+def test_keys_with_stored_uniform_halves_give_the_same_ciphertexts(env):
+    """CM_OPT_EVK_STORED_A keeps a_j in device memory instead of regenerating it in the kernels: the same
+    residues, so every kernel of the inner-product family gives bit for bit what it gives with the default keys
+    -- the single one (rotate), the source-stationary one (hoisted baby steps), the batched one (unrolled giant
+    steps and ladders of the packed product), the shared-key and multi-key ones (q K^T with unrolled ladders)."""
+    from paper_2602_11470_amd import inputs
+    e = env
+    B, gctx = e["B"], e["gctx"]
+    L = gctx.L
+    x, W = inputs.vmm_inputs(31, 256, 256, "uniform", 0.05)
+    gplan = gctx.vmm_plan(256, 256, W=W, level=L, unrolled_ladders=True)
+    H, E = 4, 64
+    kv_flags = dict(unrolled_ladders=True)
+    rng = np.random.default_rng(5)
+    slots = [rng.uniform(-1, 1, gctx.S) for _ in range(12)]
+
+    def run(stored):
+        gctx.set_option(B.CM_OPT_EVK_STORED_A, stored)
+        try:
+            kv = gctx.kv_create(H, E, L - 1, **kv_flags)
+            steps = sorted(set(gplan.steps()) | set(kv.steps()) | {7})
+            keys = gctx.keygen_rotations(e["gsk"], steps, 2, with_relin=True)
+            enc = lambda i, lv: gctx.level_drop(gctx.encrypt(e["gsk"], gctx.encode(slots[i], L), 40 + i), lv)
+            out = [gctx.ct_export(gctx.rotate(keys, enc(0, L), 7))]
+            out += [gctx.ct_export(c) for c in gctx.rotate_hoisted(keys, enc(1, L - 2), gplan.steps()[:5])]
+            out.append(gctx.ct_export(gctx.vmm_pt(keys, gplan, enc(2, L))))
+            for c in range(10):
+                kv.load(B.CM_QK, c, enc(c % 6 + 3, L - 1))
+            kv.set_tokens(10 * (gctx.S // (H * E)))
+            out.append(gctx.ct_export(gctx.vmm_kv(keys, kv, B.CM_QK, enc(9, L - 1))))
+            out.append(keys.export(7, False, 2, 1))
+            return out
+        finally:
+            gctx.set_option(B.CM_OPT_EVK_STORED_A, 0)
+
+    ref, got = run(0), run(1)
+    assert len(ref) == len(got)
+    for a, b in zip(ref, got):
+        assert np.array_equal(a, b)
