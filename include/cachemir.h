@@ -60,7 +60,8 @@ enum {
     CM_E_NOKEY = -4,   /* rotation step or relinearisation key not generated */
     CM_E_LAYOUT = -5,  /* plan / cache / ciphertext shapes do not fit together */
     CM_E_NOMEM = -6,   /* device or host allocation failed */
-    CM_E_HIP = -7      /* a HIP call failed; see cm_last_hip_error() */
+    CM_E_HIP = -7,     /* a HIP call failed; see cm_last_hip_error() */
+    CM_E_TOOBIG = -8   /* the operand exceeds the fixed work area of an entry point that allocates nothing */
 };
 const char *cm_strerror(cm_status s);
 int32_t cm_last_hip_error(void);
@@ -177,6 +178,15 @@ cm_status cm_mul_ct(cm_ctx *ctx, const cm_ct *a, const cm_ct *b, cm_ct *out, voi
 cm_status cm_relinearize(cm_ctx *ctx, const cm_evk *evk, const cm_ct *a, cm_ct *out, void *stream);
 /* Division by the last prime (floor variant): level drops by one. */
 cm_status cm_rescale(cm_ctx *ctx, const cm_ct *a, cm_ct *out, void *stream);
+/* cm_rescale for callers that cannot allocate device memory at all (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation): the same result, bit for bit, but nothing is taken from
+ * the context's arena or from per-level tables (which an ordinary call builds, and allocates, the first time a
+ * level is used).  Its work area is a fixed 32 MiB device array inside the library (one per GPU, held until
+ * the process ends), so ncomp * (level + 1) * n may be at most 4 Mi words (n = 65536: two components up to
+ * level 31, three up to level 20): beyond that CM_E_TOOBIG and nothing is enqueued.  out must not alias a.
+ * The call only enqueues kernels on `stream`; it calls no allocator.  All calls on one GPU share the work area:
+ * calls that may overlap in time (different streams without ordering, different contexts) race. */
+cm_status cm_rescale_static(cm_ctx *ctx, const cm_ct *a, cm_ct *out, void *stream);
 cm_status cm_level_drop(cm_ctx *ctx, const cm_ct *a, int32_t level, cm_ct *out, void *stream);
 /* Rot(in, step)[i] = in[i + step]: Galois map, then key switch of the second component. */
 cm_status cm_rotate(cm_ctx *ctx, const cm_evk *evk, const cm_ct *in, int32_t step, cm_ct *out,

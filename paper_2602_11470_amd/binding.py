@@ -68,6 +68,7 @@ _SIGS = {
     "cm_mul_ct": ([_vp, _P(cm_ct), _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_relinearize": ([_vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_rescale": ([_vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
+    "cm_rescale_static": ([_vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_level_drop": ([_vp, _P(cm_ct), _i32, _P(cm_ct), _vp], _i32),
     "cm_rotate": ([_vp, _vp, _P(cm_ct), _i32, _P(cm_ct), _vp], _i32),
     "cm_rotate_hoisted": ([_vp, _vp, _P(cm_ct), _vp, _sz, _P(cm_ct), _vp], _i32),
@@ -260,6 +261,11 @@ class Context:
     def rescale(self, a):
         out = Ct(self, a.level - 1, a.ncomp)
         _chk(lib.cm_rescale(self.h, C.byref(a.d), C.byref(out.d), _stream()))
+        return out
+
+    def rescale_static(self, a, out=None):
+        out = out or Ct(self, a.level - 1, a.ncomp)
+        _chk(lib.cm_rescale_static(self.h, C.byref(a.d), C.byref(out.d), _stream()))
         return out
 
     def level_drop(self, a, level):

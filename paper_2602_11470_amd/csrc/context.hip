@@ -9,6 +9,7 @@
 #include "common.h"
 
 void cm_ops_forget_ctx(cm_ctx *ctx);
+void cm_ops_device_init();
 static thread_local int g_hip_error = 0;
 void cm_set_hip_error(int e) { g_hip_error = e; }
 extern "C" int32_t cm_last_hip_error(void) { return g_hip_error; }
@@ -22,6 +23,7 @@ extern "C" const char *cm_strerror(cm_status s) {
         case CM_E_LAYOUT: return "plan, cache and ciphertext shapes do not fit together";
         case CM_E_NOMEM: return "out of memory";
         case CM_E_HIP: return "HIP runtime error (see cm_last_hip_error)";
+        case CM_E_TOOBIG: return "operand larger than the fixed work area of this entry point";
     }
     return "unknown status";
 }
@@ -405,6 +407,7 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
         cm_ctx_destroy(ctx);
         return CM_E_NOMEM;
     }
+    cm_ops_device_init();            // per-device addresses of file-scope device arrays, looked up with this device current
     *out = ctx;
     return CM_OK;
 }

@@ -74,6 +74,7 @@ struct KsLevelFull : KsLevel {
 };
 
 #define RESCALE_MAX_COMPS (2 * CM_KS_BATCH)
+#define IDX_CHUNK_U64 128
 static ConvDev conv_dev(const cm_ctx *ctx, const ConvTable &t, const std::vector<int> &in_rows,
                         const std::vector<int> &out_rows) {
     ConvDev d;
@@ -942,6 +943,84 @@ extern "C" cm_status cm_rescale(cm_ctx *ctx, const cm_ct *a, cm_ct *out, void *s
     out->level = level - 1;
     return CM_OK;
     CM_CATCH
+}
+// ---- the rescale for callers that cannot allocate -------------------------------------------------------------
+// Everything cm_rescale takes from the context's arena and from per-level tables (built, hence allocated, on the first
+// call at a level) lives here in one file-scope device array instead: a head of SCRATCH_HEAD words for the small
+// tables of the call (written by kernels that carry the values as arguments), then the coefficient form of the last
+// limbs and their residues under the other moduli.  Each GPU holds its own copy of the array at its own address; the
+// address is looked up once per device and kept.  Calls on one GPU share the array: two that overlap in time race.
+#define SCRATCH_HEAD 4096
+#define SCRATCH_WORDS ((size_t)(4u << 20) + SCRATCH_HEAD)        // 32 MiB of limbs + the head
+static __device__ __align__(256) u64 scratch[SCRATCH_WORDS];
+#define SCRATCH_MAX_DEVICES 64
+static u64 *g_scratch_ptr[SCRATCH_MAX_DEVICES];
+// the device address of `scratch` on the current device (nullptr: the lookup failed; the error is recorded)
+static u64 *scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= SCRATCH_MAX_DEVICES) return nullptr;
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) {
+            cm_set_hip_error((int)e);
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = (u64 *)p;
+    }
+    return g_scratch_ptr[dev];
+}
+// called by cm_ctx_create with the context's device current
+void cm_ops_device_init() { (void)scratch_of_current_device(); }
+
+struct U64Chunk { u64 v[IDX_CHUNK_U64]; };
+__global__ void k_set_u64(u64 *dst, U64Chunk c, int count) {
+    const int i = threadIdx.x;
+    if (i < count) dst[i] = c.v[i];
+}
+extern "C" cm_status cm_rescale_static(cm_ctx *ctx, const cm_ct *a, cm_ct *out, void *stream) {
+    (void)hipGetLastError();          // stale errors of earlier calls are not this call's
+    if (!ctx || !ct_ok(ctx, a) || !out || !out->dev || out->dev == a->dev) return CM_E_INVAL;
+    if (a->level < 1) return CM_E_LEVEL;
+    const int level = a->level, ncomp = a->ncomp;
+    const size_t n = ctx->n;
+    // head: four integer tables of at most ncomp * level entries each, then level pairs of 64-bit constants
+    const size_t tab = (size_t)ncomp * level, head_words = (2 * (size_t)ncomp + 2 * tab + 1) / 2 + 2 * (size_t)level;
+    if (head_words > SCRATCH_HEAD || SCRATCH_HEAD + (size_t)ncomp * n + tab * n > SCRATCH_WORDS) return CM_E_TOOBIG;
+    u64 *S = scratch_of_current_device();
+    if (!S) return CM_E_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    int h_int[2 * 3 + 2 * 3 * CM_MAX_LIMBS];
+    int *h_last_rows = h_int, *h_last_mods = h_int + ncomp, *h_red_mods = h_int + 2 * ncomp, *h_red_src = h_red_mods + tab;
+    bool last_fits = ctx->mod[level] < (1ULL << 52);
+    for (int i = 0; i < level; i++) last_fits = last_fits && ctx->mod[level] < 2 * ctx->mod[i];
+    for (int c = 0; c < ncomp; c++) {
+        h_last_rows[c] = c * (level + 1) + level, h_last_mods[c] = level;
+        for (int i = 0; i < level; i++) h_red_mods[c * level + i] = i, h_red_src[c * level + i] = c;
+    }
+    int *d_int = (int *)S;
+    launch_set_idx(d_int, h_int, (int)(2 * ncomp + 2 * tab), st);
+    u64 *d_qlinv = S + (2 * (size_t)ncomp + 2 * tab + 1) / 2;
+    for (int base = 0; base < 2 * level; base += IDX_CHUNK_U64) {
+        U64Chunk c;
+        const int m = 2 * level - base < IDX_CHUNK_U64 ? 2 * level - base : IDX_CHUNK_U64;
+        for (int i = 0; i < IDX_CHUNK_U64; i++) {
+            c.v[i] = 0;
+            if (i < m) {
+                const int l = (base + i) / 2;
+                const u64 q = ctx->mod[l], inv = h_invmod(ctx->mod[level] % q, q);
+                c.v[i] = ((base + i) & 1) ? h_shoup(inv, q) : inv;
+            }
+        }
+        hipLaunchKernelGGL(k_set_u64, dim3(1), dim3(IDX_CHUNK_U64), 0, st, d_qlinv + base, c, m);
+    }
+    u64 *last = S + SCRATCH_HEAD, *red = last + (size_t)ncomp * n;
+    const RescaleTabs t{d_int, d_int + ncomp, d_int + 2 * ncomp, d_int + 2 * ncomp + tab, d_qlinv, last_fits};
+    CMCHK(rescale_core(ctx, t, a->dev, ncomp, level, out->dev, st, last, red, false));
+    out->ncomp = ncomp;
+    out->scale = a->scale / (double)ctx->mod[level];
+    out->level = level - 1;
+    RETURN_LAUNCH_STATUS();
 }
 extern "C" cm_status cm_level_drop(cm_ctx *ctx, const cm_ct *a, int32_t level, cm_ct *out, void *stream) {
     if (!ctx || !ct_ok(ctx, a) || !out || !out->dev) return CM_E_INVAL;
