@@ -197,13 +197,19 @@ class KvLayout:
     (e, h, tau); K ciphertext c holds token c*t + tau at residue tau; the score ciphertext
     holds token c*t + tau of head h at (c, h, tau), so it has room for E*t = S/H tokens;
     V ciphertext k holds V[((e + k) mod E)*t + r, h, e] at (e, h, r), stored rotated right by
-    the giant step of its BSGS group."""
+    the giant step of its BSGS group.
+    A head count that is not a power of two (GPT2-base: 12 heads of 64 dims, Table 3) is padded to the
+    next one, as the paper pads that model's width 768 to 1024 (Table 4): H becomes the padded count (the
+    stride of the layout), `heads` keeps the real one; the padding heads hold zeros, vectors and scores
+    are exchanged for the real heads only."""
     S: int
     H: int
     E: int
     r_i: int = 0    # baby steps of the score-times-V product; 0 -> E (no giant steps)
 
     def __post_init__(self):
+        self.heads = self.H
+        self.H = 1 << (self.H - 1).bit_length()
         self.t = self.S // (self.H * self.E)
         assert self.t * self.H * self.E == self.S
         self.r_i = self.r_i or self.E
@@ -217,14 +223,14 @@ class KvLayout:
     def pack_vec(self, v, tau=0):
         """v[h, e] at (e, h, tau), zero elsewhere."""
         out = np.zeros(self.S)
-        for h in range(self.H):
+        for h in range(self.heads):
             for e in range(self.E):
                 out[self.slot(e, h, tau)] = v[h, e]
         return out
 
     def unpack_vec(self, slots, tau=0):
         return np.array([[slots[self.slot(e, h, tau)] for e in range(self.E)]
-                         for h in range(self.H)])
+                         for h in range(self.heads)])
 
     # ---- rotary position embedding with the extraction fused (Sec. 4.2, App. D) --------------
     # The embedding turns the pair of dims (2m, 2m+1) of every head by the angle
@@ -288,14 +294,14 @@ class KvLayout:
     def pack_scores(self, s):
         """s[h, token] -> score layout."""
         out = np.zeros(self.S)
-        for h in range(self.H):
+        for h in range(self.heads):
             for n in range(s.shape[1]):
                 out[self.slot(n // self.t, h, n % self.t)] = s[h, n]
         return out
 
     def unpack_scores(self, slots, ntok):
         return np.array([[slots[self.slot(n // self.t, h, n % self.t)] for n in range(ntok)]
-                         for h in range(self.H)])
+                         for h in range(self.heads)])
 
     def v_shift(self, k):
         """Right rotation applied to stored V ciphertext k."""
@@ -304,7 +310,7 @@ class KvLayout:
     def pack_v(self, V, k):
         out = np.zeros(self.S)
         for e in range(self.E):
-            for h in range(self.H):
+            for h in range(self.heads):
                 for r in range(self.t):
                     n = ((e + k) % self.E) * self.t + r
                     if n < V.shape[0]:
@@ -349,7 +355,7 @@ class KvLayout:
             for tau in range(self.t):
                 n = ((b - g * self.r_i) % self.E) * self.t + tau
                 if n < K.shape[0]:
-                    for h in range(self.H):
+                    for h in range(self.heads):
                         out[self.slot(b, h, tau)] = K[n, h, (b + j) % self.E]
         return out
 
@@ -383,3 +389,80 @@ class KvLayout:
 
     def append_steps(self):
         return [-(g * self.r_i * self.H * self.t) for g in range(1, self.r_o)]
+
+
+# ---- grouped-query attention against a cache that stores every KV head once -------------------------------
+@dataclass
+class GqaLayout:
+    """The paper packs the cache with one K / V head per query head (Sec. 5.3; its Llama-3-8B has H = 32 of
+    both).  A model with grouped-query attention has Hkv < H KV heads, each shared by G = H / Hkv query heads;
+    repeating every KV head G times fits the paper's layout but stores and appends everything G times.  This
+    layout stores each KV head ONCE: the cache is the paper's layout for Hkv heads (`kv`, t_kv = S / (Hkv E)
+    tokens per K ciphertext, G times as many as before), the query and the attention output keep the paper's
+    layout for H heads (`q`, t = S / (H E)) with head h = hk G + g, and the two meet because
+
+        q.slot(e, hk G + g, tau) == kv.slot(e, hk, g t + tau):
+
+    inside a block of t_kv slots of KV head hk, the G query heads of the group occupy G runs of t residues.
+    A query head must meet every token residue j = g' t + tau of its KV head, not only those of its own run,
+    so the products run G times, the query moved by the inner rotation (Sec. 5.4) of delta t residues,
+    delta = 0 .. G-1: in pass delta the run g' holds query head (g' - delta) mod G.  The scores of a head are
+    spread over the G results (token c t_kv + j of head (hk, g) in pass delta = (j // t - g) mod G at slot
+    (c, hk, j)); scores V undoes the rotation per pass and sums.  Same number of ciphertext products as the
+    replicated layout, 1/G of the cache memory and of the append work, 2 (G - 1) inner rotations per token."""
+    S: int
+    H: int
+    Hkv: int
+    E: int
+    r_i: int = 0
+
+    def __post_init__(self):
+        assert self.H % self.Hkv == 0
+        self.G = self.H // self.Hkv
+        self.kv = KvLayout(self.S, self.Hkv, self.E, self.r_i)
+        self.q = KvLayout(self.S, self.H, self.E)
+        self.t = self.q.t
+        assert self.kv.t == self.G * self.t
+        self.capacity = self.kv.capacity
+
+    def pass_of(self, g, j):
+        """The pass in which query head g of a group meets token residue j."""
+        return (j // self.t - g) % self.G
+
+    def inner_delta(self, delta):
+        """Residues by which the replicated query is moved for pass delta (0 for pass 0)."""
+        return delta * self.t
+
+    def pack_scores(self, s):
+        """s[h, token] -> the G slot vectors that scores V reads (the layout q K^T writes)."""
+        out = [np.zeros(self.S) for _ in range(self.G)]
+        tk = self.kv.t
+        for h in range(self.H):
+            hk, g = divmod(h, self.G)
+            for n in range(s.shape[1]):
+                c, j = divmod(n, tk)
+                out[self.pass_of(g, j)][self.kv.slot(c, hk, j)] = s[h, n]
+        return out
+
+    def unpack_scores(self, vecs, ntok):
+        tk = self.kv.t
+        m = np.zeros((self.H, ntok))
+        for h in range(self.H):
+            hk, g = divmod(h, self.G)
+            for n in range(ntok):
+                c, j = divmod(n, tk)
+                m[h, n] = vecs[self.pass_of(g, j)][self.kv.slot(c, hk, j)]
+        return m
+
+    def qk_steps(self):
+        """Replication of the query over its t residues, the inner rotations of the passes, the sum over the dims."""
+        s = [-(1 << i) for i in range(_log2(self.t))]
+        for delta in range(1, self.G):
+            s += self.kv.inner_rotation_steps(self.inner_delta(delta))
+        return s + [(1 << i) * self.Hkv * self.kv.t for i in range(_log2(self.E))]
+
+    def sv_steps(self):
+        s = [a for a in self.kv.sv_steps() if a % self.kv.t == 0]         # nothing sums over the residues of the cache layout
+        for back in range(1, self.G):
+            s += self.kv.inner_rotation_steps(self.inner_delta(back))
+        return s + [1 << l for l in range(_log2(self.t))]

@@ -7,7 +7,7 @@ cryptography) and on oracle ciphertexts (`CkksOps`).
 """
 import numpy as np
 
-from .packing import KvLayout, VmmPlan, _log2
+from .packing import GqaLayout, KvLayout, VmmPlan, _log2
 
 
 class SlotOps:
@@ -40,6 +40,9 @@ class SlotOps:
         return a
 
     def rescale(self, a):
+        return a
+
+    def drop(self, a):
         return a
 
 
@@ -75,6 +78,10 @@ class CkksOps:
 
     def rescale(self, a):
         return self.ctx.rescale(a)
+
+    def drop(self, a):
+        """One level down without touching the message (Sec. 2.1, level drop)."""
+        return self.ctx.level_drop(a, a.level - 1)
 
 
 def _sum(ops, terms):
@@ -481,3 +488,38 @@ def kv_append_group(ops, lay: KvLayout, k_cts, v_cts, c, ck_grp, cv_grp, k_mask,
         v_cts[k] = vnew if v_cts[k] is None else ops.add(v_cts[k], vnew)
     if x_cts is not None:
         _index_append(ops, lay, x_cts, ck_grp, x_masks)
+
+
+def gqa_qk_scores(ops, glay: GqaLayout, cq, k_cts, masks, rot_plaintexts, qk=None):
+    """q K^T of one token against a cache that stores every KV head once (packing.GqaLayout).  cq: the query
+    at (e, h, 0) of the H-head layout, one level above the cache.  It is replicated over its t residues
+    (Sec. 5.1 step 1), then for every pass delta moved by the inner rotation of delta t residues (Sec. 5.4;
+    pass 0 only drops the level) and multiplied into the cache WITHOUT further replication (qk_scores with
+    replicate=False).  rot_plaintexts[delta] = glay.kv.inner_rotation_plaintexts(delta t) (slot vectors or
+    encoded plaintexts), masks[c] as for qk_scores on glay.kv.  Returns the G score ciphertexts, two levels
+    below the cache.  `qk` = the q K^T routine to run per pass (default: the printed order)."""
+    for i in range(_log2(glay.t)):
+        cq = ops.add(cq, ops.rotate(cq, -(1 << i)))
+    outs = []
+    for delta in range(glay.G):
+        x = ops.drop(cq) if delta == 0 else inner_rotate(ops, glay.kv, cq, glay.inner_delta(delta), rot_plaintexts[delta])
+        outs.append(qk(x) if qk is not None else qk_scores(ops, glay.kv, x, k_cts, masks, replicate=False))
+    return outs
+
+
+def gqa_score_times_v(ops, glay: GqaLayout, cs_list, v_cts, rot_plaintexts, sv=None):
+    """scores V for the same layout.  cs_list[delta]: the scores of pass delta (the layout gqa_qk_scores
+    writes, GqaLayout.pack_scores), at the cache level.  Every pass meets V without the sum over the residues
+    (score_times_v with reduce=False), is moved back by the inner rotation of (G - delta) t residues (pass 0
+    only drops the level), the passes are added, and the t residues of a query head's run are summed by
+    log2(t) rotate-and-add steps.  Result: Att[h, e] at (e, h, 0) of the H-head layout, two levels below the
+    cache.  rot_plaintexts[b] = glay.kv.inner_rotation_plaintexts(b t)."""
+    acc = None
+    for delta in range(glay.G):
+        part = sv(cs_list[delta]) if sv is not None else score_times_v(ops, glay.kv, cs_list[delta], v_cts, reduce=False)
+        back = (glay.G - delta) % glay.G
+        part = ops.drop(part) if back == 0 else inner_rotate(ops, glay.kv, part, glay.inner_delta(back), rot_plaintexts[back])
+        acc = part if acc is None else ops.add(acc, part)
+    for l in range(_log2(glay.t)):
+        acc = ops.add(acc, ops.rotate(acc, 1 << l))
+    return acc

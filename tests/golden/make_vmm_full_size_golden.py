@@ -13,7 +13,11 @@ every limb.  Run from the repository root:
     python tests/golden/make_vmm_full_size_golden.py raised     (baby-step sums kept in the extended basis)
     python tests/golden/make_vmm_full_size_golden.py direct     (that, with the giant steps unrolled)
     python tests/golden/make_vmm_full_size_golden.py unrolled   (that, with the two ladders unrolled too, 64 x 8 steps: 84 rotations)
-(about ten minutes each on 8 cores, ~20 GiB of memory).
+    python tests/golden/make_vmm_full_size_golden.py mlp_up     (vmm_full_size_mlp_up.txt: 4096 -> 16384, the MLP up / gate shape with
+                                                                 14336 padded to 16384 (App. C, non-square), unrolled form, 128 x 16
+                                                                 steps, 2048 products, at the paper's operating level 4)
+    python tests/golden/make_vmm_full_size_golden.py mlp_down   (vmm_full_size_mlp_down.txt: 16384 -> 4096, the same for the down projection)
+(a few minutes each on 8 cores, ~20 GiB of memory).
 """
 import hashlib
 import os
@@ -39,26 +43,40 @@ def integer_inputs(n, plan):
     return xc, diag
 
 
+MLP_WIDE, MLP_LEVEL = 16384, 4
+
+
 def plan_for(S, form):
     """32 baby x 16 giant steps (the 52 rotations of Table 2); the unrolled form, which is the one bench.py
-    times, with the split it runs there: 64 x 8."""
+    times, with the split it runs there: 64 x 8.  The MLP shapes (2048 diagonals) with the split the library
+    takes for them in the unrolled form: 128 x 16."""
+    if form == "mlp_up":
+        return packing.make_plan(S, D, MLP_WIDE, r_i=128)
+    if form == "mlp_down":
+        return packing.make_plan(S, MLP_WIDE, D, r_i=128)
     return packing.make_plan(S, D, D, r_i=64 if form == "unrolled" else None)
 
 
+def level_for(prm, form):
+    return MLP_LEVEL if form.startswith("mlp") else prm.L
+
+
 def main(form="plain"):
-    raised, direct, unrolled = form in ("raised", "direct", "unrolled"), form == "direct", form == "unrolled"
+    mlp = form.startswith("mlp")
+    raised, direct, unrolled = form in ("raised", "direct", "unrolled") or mlp, form == "direct", form == "unrolled" or mlp
     t0 = time.time()
     prm = params.config2()
     ctx = ckks.Context(prm)
+    level = level_for(prm, form)
     plan = plan_for(ctx.S, form)
     xc, diag = integer_inputs(ctx.n, plan)
     sk = ctx.keygen_secret(SEED_SK)
     steps = vmm.unrolled_steps(plan) if unrolled else vmm.direct_giant_steps(plan) if direct else plan.all_steps()
     keys = ctx.keygen_rotations(sk, steps, SEED_EVK)
     print("keys", len(keys), time.time() - t0, flush=True)
-    ct = ctx.encrypt(sk, ctx.pt_from_coeffs(xc, prm.L, prm.scale), SEED_ENC)
+    ct = ctx.level_drop(ctx.encrypt(sk, ctx.pt_from_coeffs(xc, prm.L, prm.scale), SEED_ENC), level)
     make_pt = ctx.pt_from_coeffs_ext if raised else ctx.pt_from_coeffs
-    pts = [[make_pt(diag[j * plan.r_o + k], prm.L, prm.scale) for k in range(plan.r_o)] for j in range(plan.r_i)]
+    pts = [[make_pt(diag[j * plan.r_o + k], level, prm.scale) for k in range(plan.r_o)] for j in range(plan.r_i)]
     print("plaintexts", time.time() - t0, flush=True)
     if unrolled:
         y = vmm.vmm_pt_unrolled(ctx, keys, plan, ct, pts)
@@ -72,10 +90,13 @@ def main(form="plain"):
     print("vmm", time.time() - t0, ctx.rot_count, ctx.ptmul_count, flush=True)
     out = os.path.join(ROOT, "tests", "golden", {"plain": "vmm_full_size.txt", "raised": "vmm_full_size_raised.txt",
                                                   "direct": "vmm_full_size_direct.txt",
-                                                  "unrolled": "vmm_full_size_unrolled.txt"}[form])
+                                                  "unrolled": "vmm_full_size_unrolled.txt",
+                                                  "mlp_up": "vmm_full_size_mlp_up.txt",
+                                                  "mlp_down": "vmm_full_size_mlp_down.txt"}[form])
     with open(out, "w") as f:
-        f.write("# Oracle output of the full-size packed product (Algorithm 1 of App. C at the Table 2 shape\n"
-                "# (S, d) = (32768, 4096)) on integer plaintexts; written by make_vmm_full_size_golden.py"
+        f.write("# Oracle output of the full-size packed product (Algorithm 1 of App. C at the "
+                + (f"MLP shape {plan.d_in} -> {plan.d_out},\n# level {level}" if mlp else "Table 2 shape\n# (S, d) = (32768, 4096)")
+                + ") on integer plaintexts; written by make_vmm_full_size_golden.py"
                 + (f" {form}\n# (sums of the baby steps kept in the extended basis"
                    + (", giant steps unrolled" if direct or unrolled else "")
                    + (", rotate-and-add ladders unrolled" if unrolled else "") + ").\n" if raised else ".\n"))

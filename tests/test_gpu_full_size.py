@@ -69,33 +69,39 @@ def test_config2_chain_keys_and_single_operations(ring2):
     assert np.abs(gctx.decrypt(gsk, gm).real - z * z).max() < 1e-6
 
 
-@pytest.mark.parametrize("form", ["plain", "raised", "direct", "unrolled"])
+@pytest.mark.parametrize("form", ["plain", "raised", "direct", "unrolled", "mlp_up", "mlp_down"])
 def test_config2_full_packed_product_against_stored_oracle_result(ring2, golden, form):
     """52 rotations (84 in the unrolled form with its 64 x 8 split), 512 plaintext multiply-accumulates at (S, d) =
     (32768, 4096); the expected ciphertext was written by tests/golden/make_vmm_full_size_golden.py
     from the oracle, for the algorithm as printed, for the form that keeps the baby-step sums in the
     extended basis, for that with the giant steps unrolled, and for that with the two ladders
-    unrolled as well (the configuration bench.py times)."""
+    unrolled as well (the configuration bench.py times).  mlp_up / mlp_down: the MLP shapes of benchmark
+    configuration 4 (4096 -> 16384 and back, 14336 padded; 2048 products, 128 x 16 steps, 150 rotations) at the
+    paper's operating level 4, unrolled form."""
     import importlib.util
     import os
     B, octx, gctx, prm = ring2
-    raised, direct, unrolled = form != "plain", form == "direct", form == "unrolled"
+    mlp = form.startswith("mlp")
+    raised, direct, unrolled = form != "plain", form == "direct", form == "unrolled" or mlp
     g = golden({"plain": "vmm_full_size.txt", "raised": "vmm_full_size_raised.txt", "direct": "vmm_full_size_direct.txt",
-                "unrolled": "vmm_full_size_unrolled.txt"}[form])
+                "unrolled": "vmm_full_size_unrolled.txt", "mlp_up": "vmm_full_size_mlp_up.txt",
+                "mlp_down": "vmm_full_size_mlp_down.txt"}[form])
     spec = importlib.util.spec_from_file_location(
         "mk", os.path.join(os.path.dirname(__file__), "golden", "make_vmm_full_size_golden.py"))
     mk = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mk)
     plan = mk.plan_for(octx.S, form)
+    level = mk.level_for(prm, form)
     xc, diag = mk.integer_inputs(octx.n, plan)
-    gplan = gctx.vmm_plan(mk.D, mk.D, level=prm.L, r_i=plan.r_i, coeffs=np.stack(diag), pt_scale=prm.scale,
+    gplan = gctx.vmm_plan(plan.d_in, plan.d_out, level=level, r_i=plan.r_i, coeffs=np.stack(diag), pt_scale=prm.scale,
                           raised_sums=raised, direct_giants=direct, unrolled_ladders=unrolled)
-    assert gplan.n_rotations == int(g["rotations"]) == (84 if unrolled else 52)
-    assert (gplan.r_i, gplan.r_o) == ((64, 8) if unrolled else (32, 16))
-    assert gplan.r_i * gplan.r_o == int(g["pt_mults"]) == 512
+    del diag
+    assert gplan.n_rotations == int(g["rotations"]) == (150 if mlp else 84 if unrolled else 52)
+    assert (gplan.r_i, gplan.r_o) == ((128, 16) if mlp else (64, 8) if unrolled else (32, 16))
+    assert gplan.r_i * gplan.r_o == int(g["pt_mults"]) == (2048 if mlp else 512)
     gsk = gctx.keygen_secret(mk.SEED_SK)
     gkeys = gctx.keygen_rotations(gsk, gplan.steps(), mk.SEED_EVK)
-    gx = gctx.encrypt(gsk, gctx.pt_from_coeffs(xc, prm.L, prm.scale), mk.SEED_ENC)
+    gx = gctx.level_drop(gctx.encrypt(gsk, gctx.pt_from_coeffs(xc, prm.L, prm.scale), mk.SEED_ENC), level)
     gy = gctx.vmm_pt(gkeys, gplan, gx)
     can = gctx.ct_export(gy)
     assert list(can.shape) == [int(v) for v in g["shape"].split()] and gy.level == int(g["level"])

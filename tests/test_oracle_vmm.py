@@ -708,3 +708,114 @@ def test_key_index_on_ciphertexts_decrypts_to_q_times_K_transposed(r_i):
                               sv=lambda c, x: vmm.score_times_v_unrolled(ctx, keys, lay, c, x, reduce=False))
     assert b.level == L - 2 and abs(a.scale / b.scale - 1) < 1e-12
     assert np.abs(ctx.decrypt(sk, a) - ctx.decrypt(sk, b)).max() < 1e-6
+
+
+# ---- grouped-query attention against a cache that stores every KV head once ---------------------------------
+def _gqa_inputs(seed, H, Hkv, E, ntok):
+    rng = np.random.default_rng(seed)
+    q = rng.normal(size=(H, E))
+    K, V = rng.normal(size=(ntok, Hkv, E)), rng.normal(size=(ntok, Hkv, E))
+    s = rng.uniform(0, 1, size=(H, ntok))
+    return q, K, V, s / s.sum(axis=1, keepdims=True)
+
+
+@pytest.mark.parametrize("S,H,Hkv,E,r_i,ntok", [(2048, 8, 2, 16, 4, 150), (2048, 4, 2, 32, 0, 37), (512, 8, 1, 8, 2, 64)])
+def test_gqa_layout_on_slots_is_grouped_attention_and_matches_the_replicated_layout(S, H, Hkv, E, r_i, ntok):
+    """Slot level (no cryptography): the query layout and the cache layout meet slot for slot; q K^T and scores V
+    through the G passes equal the einsum with each KV head shared by G query heads, and equal, number for
+    number, what the paper's layout gives with every KV head repeated G times; the cache is 1/G as many
+    ciphertexts, the ciphertext products as many as before."""
+    glay = packing.GqaLayout(S, H, Hkv, E, r_i)
+    G, t, kvl = glay.G, glay.t, glay.kv
+    for e, hk, g, tau in ((0, 0, 0, 0), (E - 1, Hkv - 1, G - 1, t - 1), (3, Hkv - 1, 1, t // 2)):
+        assert glay.q.slot(e, hk * G + g, tau) == kvl.slot(e, hk, g * t + tau)
+    q, K, V, s = _gqa_inputs(S + H, H, Hkv, E, ntok)
+    Krep, Vrep = np.repeat(K, G, axis=1), np.repeat(V, G, axis=1)
+    nk = -(-ntok // kvl.t)
+    k_cts = [kvl.pack_k(K, c) for c in range(nk)]
+    v_cts = [kvl.pack_v(V, k) for k in range(E)]
+    rots = {d: kvl.inner_rotation_plaintexts(glay.inner_delta(d)) for d in range(1, G)}
+    ops = vmm.SlotOps()
+    outs = vmm.gqa_qk_scores(ops, glay, glay.q.pack_vec(q), k_cts, [kvl.qk_mask(c) for c in range(nk)], rots)
+    assert len(outs) == G and ops.ct_mults == G * nk
+    m = glay.unpack_scores(outs, ntok)
+    want = np.einsum("he,nhe->hn", q, Krep)
+    assert np.abs(m - want).max() < 1e-10
+    # every slot of every pass is either a score or zero: nothing is computed twice
+    assert sum(int(np.count_nonzero(np.abs(o) > 1e-300)) for o in outs) <= H * nk * kvl.t
+    # the paper's layout with repeated heads: the same numbers from G times as many key ciphertexts
+    rep = packing.KvLayout(S, H, E, r_i)
+    nk_rep = -(-ntok // rep.t)
+    ops_r = vmm.SlotOps()
+    m_rep = vmm.qk_scores(ops_r, rep, rep.pack_vec(q), [rep.pack_k(Krep, c) for c in range(nk_rep)],
+                          [rep.qk_mask(c) for c in range(nk_rep)])
+    assert np.abs(rep.unpack_scores(m_rep, ntok) - m).max() < 1e-10
+    assert G * (nk - 1) < nk_rep <= G * nk and ops_r.ct_mults == nk_rep
+    # scores V
+    ops = vmm.SlotOps()
+    att = vmm.gqa_score_times_v(ops, glay, glay.pack_scores(s), v_cts, rots)
+    assert ops.ct_mults == G * E
+    want_att = np.einsum("hn,nhe->he", s, Vrep)
+    assert np.abs(glay.q.unpack_vec(att) - want_att).max() < 1e-10
+    att_rep = vmm.score_times_v(vmm.SlotOps(), rep, rep.pack_scores(s), [rep.pack_v(Vrep, k) for k in range(E)])
+    assert np.abs(rep.unpack_vec(att_rep) - glay.q.unpack_vec(att)).max() < 1e-10
+    # pack_scores / unpack_scores are inverse to each other and cover every (head, token) once
+    assert np.array_equal(glay.unpack_scores(glay.pack_scores(s), ntok), s)
+    assert sum(int(np.count_nonzero(v)) for v in glay.pack_scores(s)) == H * ntok
+
+
+def test_gqa_attention_on_ciphertexts_decrypts_to_grouped_attention():
+    """The same two products on oracle ciphertexts (config-1 ring: 8 query heads on 2 KV heads, 16 dims):
+    decrypted scores and outputs within 1e-4 of float64, levels as documented."""
+    prm = params.config1()
+    ctx = ckks.Context(prm)
+    H, Hkv, E, ntok = 8, 2, 16, 70
+    glay = packing.GqaLayout(ctx.S, H, Hkv, E, 4)
+    kvl, G, L = glay.kv, glay.G, prm.L
+    q, K, V, s = _gqa_inputs(5, H, Hkv, E, ntok)
+    sk = ctx.keygen_secret(1)
+    keys = ctx.keygen_rotations(sk, glay.qk_steps() + glay.sv_steps(), 2, with_relin=True)
+    lv = L - 1
+    enc = lambda v, level, seed: ctx.level_drop(ctx.encrypt(sk, ctx.encode(v, L), seed), level)
+    nk = -(-ntok // kvl.t)
+    k_cts = [enc(kvl.pack_k(K, c), lv, 100 + c) for c in range(nk)]
+    v_cts = [enc(kvl.pack_v(V, k), lv, 300 + k) for k in range(E)]
+    ops = vmm.CkksOps(ctx, keys)
+
+    def rot_pts(level):
+        ql = float(ctx.mod[level])
+        return {d: [ctx.encode(p, level, ql) for p in kvl.inner_rotation_plaintexts(glay.inner_delta(d))] for d in range(1, G)}
+    masks = [ctx.encode(kvl.qk_mask(c), lv - 1, float(ctx.mod[lv - 1])) for c in range(nk)]
+    outs = vmm.gqa_qk_scores(ops, glay, enc(glay.q.pack_vec(q), lv + 1, 10), k_cts, masks, rot_pts(lv + 1))
+    assert all(o.level == lv - 2 for o in outs)
+    m = glay.unpack_scores([ctx.decrypt(sk, o).real for o in outs], ntok)
+    assert np.abs(m - np.einsum("he,nhe->hn", q, np.repeat(K, G, axis=1))).max() < 1e-4
+    cs = [enc(v, lv, 50 + d) for d, v in enumerate(glay.pack_scores(s))]
+    att = vmm.gqa_score_times_v(ops, glay, cs, v_cts, rot_pts(lv - 1))
+    assert att.level == lv - 2
+    got = glay.q.unpack_vec(ctx.decrypt(sk, att).real)
+    assert np.abs(got - np.einsum("hn,nhe->he", s, np.repeat(V, G, axis=1))).max() < 1e-4
+
+
+def test_twelve_heads_are_padded_to_sixteen_and_attention_is_unchanged():
+    """GPT2-base (Table 3: 12 heads of 64 dims, width 768): the layout pads the head count to the next power of
+    two the way Table 4 pads the width to 1024 (= 16 x 64).  On slots q K^T and scores V are the einsum over the
+    12 real heads; the padding heads' slots stay zero."""
+    S, H, E, ntok = 32768, 12, 64, 75
+    lay = packing.KvLayout(S, H, E, 8)
+    assert (lay.heads, lay.H, lay.H * lay.E, lay.t, lay.capacity) == (12, 16, 1024, 32, 2048)
+    rng = np.random.default_rng(12)
+    q = rng.normal(size=(H, E))
+    K, V = rng.normal(size=(ntok, H, E)), rng.normal(size=(ntok, H, E))
+    s = rng.uniform(0, 1, size=(H, ntok))
+    nk = -(-ntok // lay.t)
+    ops = vmm.SlotOps()
+    m = vmm.qk_scores(ops, lay, lay.pack_vec(q), [lay.pack_k(K, c) for c in range(nk)], [lay.qk_mask(c) for c in range(nk)])
+    assert np.abs(lay.unpack_scores(m, ntok) - np.einsum("he,nhe->hn", q, K)).max() < 1e-10
+    pad = [lay.slot(c, h, tau) for c in range(E) for h in range(12, 16) for tau in range(lay.t)]
+    assert not np.any(m[pad])
+    att = vmm.score_times_v(ops, lay, lay.pack_scores(s), [lay.pack_v(V, k) for k in range(E)])
+    assert np.abs(lay.unpack_vec(att) - np.einsum("hn,nhe->he", s, V)).max() < 1e-10
+    assert not np.any(att[[lay.slot(e, h, 0) for e in range(E) for h in range(12, 16)]])
+    # the packed product that feeds it: the padded width 1024 takes the 20 rotations of Table 4
+    assert packing.make_plan(S, 1024, 1024).n_rotations == 20
