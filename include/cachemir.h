@@ -280,7 +280,9 @@ enum { CM_QK = 0, CM_SV = 1, CM_QK_GROUP = 2, CM_SV_GROUP = 3,
        CM_KV_INDEX = 4 /* cm_kv_load / cm_kv_export only: a ciphertext of the key index */ };
 /* Cache for `heads` heads of `dim` dims (heads*dim*t = S) holding up to max_tokens tokens
  * (<= dim*t) at ciphertext level `level` and scale `scale`.  r_i = baby steps of the
- * score-times-V product (0 = dim, no giant steps). */
+ * score-times-V product (0 = dim, no giant steps).  A head count that is not a power of two (GPT2-base:
+ * 12) is padded to the next one, Hp: the layout is slot (e, h, tau) = (e*Hp + h)*t + tau with t = S/(Hp*dim),
+ * the padding heads hold zeros (the same holds for cm_rope_create). */
 cm_status cm_kv_create(cm_ctx *ctx, int32_t heads, int32_t dim, int32_t r_i, int32_t level,
                        double scale, int32_t max_tokens, cm_kv **out);
 /* flags: CM_KV_UNROLLED_LADDERS — in query-times-K the sum over the dims of every head (Sec. 5.1 step 2,
@@ -357,6 +359,33 @@ cm_status cm_kv_append_group(cm_ctx *ctx, const cm_evk *evk, cm_kv *kv, const cm
  * CM_QK_GROUP / CM_SV_GROUP: the same levels; no keys for the residue rotations are needed. */
 cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t which,
                     const cm_ct *in, cm_ct *out, void *stream);
+
+/* ---- grouped-query attention on a cache that stores every KV head once -------------------------------
+ * The paper packs one K / V head per query head (Sec. 5.3).  For a model whose `heads` KV heads are each shared by
+ * `group` query heads, create the cache with cm_kv_create(heads = KV heads): it then holds t_kv = S/(heads*dim)
+ * tokens per K ciphertext and dim*t_kv tokens in all (4096 for 8 x 128 on 2^15 slots), 1/group of the memory and of
+ * the append work of a cache with every KV head repeated.  The query and the attention output use the layout of
+ * H = group*heads heads (t = t_kv/group), head h = hk*group + g, whose slot (e, h, tau) IS slot (e, hk, g*t + tau)
+ * of the cache layout.  A query head meets all t_kv token residues of its KV head in `group` passes: in pass delta
+ * the replicated query is moved by the inner rotation (Sec. 5.4) of delta*t residues and multiplied into the cache
+ * as a query group (CM_QK_GROUP).  scores[delta] (an array of `group` ciphertexts, two levels below the cache)
+ * holds at slot (c, hk, j) the score of head (hk, (j/t - delta) mod group) against token c*t_kv + j.
+ * cm_gqa_sv takes `group` score ciphertexts in that layout at the cache level, runs scores-times-V per pass
+ * without the sum over the residues (CM_SV_GROUP), moves each result back by (group - delta)*t residues, adds them
+ * and sums the t residues of a run: Att[h, e] at (e, h, 0), two levels below the cache.
+ * cm_gqa_create: kv must outlive the object; group a power of two dividing t_kv (else CM_E_LAYOUT); coeffs
+ * (nullable, host [2][group-1][3][n]): integer coefficients of the plaintexts of the inner rotations by delta*t,
+ * delta = 1..group-1, first those applied to the query (level+1), then those applied to the results (level-1), each
+ * as cm_inner_rot_create takes them.  cm_gqa_steps lists the rotations needed beyond those of cm_kv_steps that are
+ * multiples of t_kv (no other step of the cache is used).  q: (e, h, 0) layout, one level above the cache. */
+typedef struct cm_gqa cm_gqa;
+cm_status cm_gqa_create(cm_ctx *ctx, const cm_kv *kv, int32_t group, const int64_t *coeffs, cm_gqa **out);
+void cm_gqa_destroy(cm_gqa *gqa);
+int32_t cm_gqa_steps(const cm_gqa *gqa, int32_t *steps, int32_t cap);
+cm_status cm_gqa_qk(cm_ctx *ctx, const cm_evk *evk, const cm_gqa *gqa, const cm_kv *kv, const cm_ct *q, cm_ct *scores,
+                    void *stream);
+cm_status cm_gqa_sv(cm_ctx *ctx, const cm_evk *evk, const cm_gqa *gqa, const cm_kv *kv, const cm_ct *scores, cm_ct *out,
+                    void *stream);
 
 /* ---- rotary embedding with the extraction fused (Sec. 4.2, App. D) ------------------------ */
 /* The element-wise layer after the q / k projections: for token `token`, every pair of dims

@@ -99,6 +99,11 @@ _SIGS = {
     "cm_kv_create_ex": ([_vp, _i32, _i32, _i32, _i32, _f64, _i32, C.c_uint32, _P(_vp)], _i32),
     "cm_kv_append_group": ([_vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_vmm_kv": ([_vp, _vp, _vp, _i32, _P(cm_ct), _P(cm_ct), _vp], _i32),
+    "cm_gqa_create": ([_vp, _vp, _i32, _vp, _P(_vp)], _i32),
+    "cm_gqa_destroy": ([_vp], None),
+    "cm_gqa_steps": ([_vp, _vp, _i32], _i32),
+    "cm_gqa_qk": ([_vp, _vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
+    "cm_gqa_sv": ([_vp, _vp, _vp, _vp, _P(cm_ct), _P(cm_ct), _vp], _i32),
     "cm_profile_enable": ([_vp, _i32], _i32),
     "cm_profile_get": ([_vp, _i32, _P(_f64), _P(_f64), _P(_f64)], _i32),
     "cm_ntt": ([_vp, _vp, _vp, _i32, _i32, _vp], _i32),
@@ -341,6 +346,24 @@ class Context:
                   key_index=False):
         return KvCache(self, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders, shared_dims, key_index)
 
+    def gqa(self, kv, group, coeffs=None):
+        return Gqa(self, kv, group, coeffs)
+
+    def gqa_qk(self, evk, gqa, q):
+        """group score ciphertexts (pass delta at index delta), two levels below the cache."""
+        outs = [Ct(self, q.level - 3) for _ in range(gqa.group)]
+        arr = (cm_ct * gqa.group)(*[o.d for o in outs])
+        _chk(lib.cm_gqa_qk(self.h, evk.h, gqa.h, gqa.kv.h, C.byref(q.d), arr, _stream()))
+        for o, d in zip(outs, arr):
+            o.d = cm_ct(d.dev, d.level, d.ncomp, d.scale)
+        return outs
+
+    def gqa_sv(self, evk, gqa, scores):
+        out = Ct(self, scores[0].level - 2)
+        arr = (cm_ct * gqa.group)(*[s.d for s in scores])
+        _chk(lib.cm_gqa_sv(self.h, evk.h, gqa.h, gqa.kv.h, arr, C.byref(out.d), _stream()))
+        return out
+
     def vmm_kv(self, evk, kv, which, x):
         out = Ct(self, x.level - (1 if which in (CM_SV, CM_SV_GROUP) or kv.key_index else 2))
         _chk(lib.cm_vmm_kv(self.h, evk.h, kv.h, which, C.byref(x.d), C.byref(out.d), _stream()))
@@ -442,10 +465,30 @@ class Rope:
             self.h = None
 
 
+class Gqa:
+    """Grouped-query attention on a cache of the KV heads (cm_gqa_*)."""
+
+    def __init__(self, ctx, kv, group, coeffs=None):
+        self.ctx, self.kv, self.group, self.h = ctx, kv, group, _vp()
+        c = _np(coeffs, np.int64) if coeffs is not None else None
+        _chk(lib.cm_gqa_create(ctx.h, kv.h, group, c.ctypes.data if c is not None else None, C.byref(self.h)))
+
+    def steps(self):
+        n = lib.cm_gqa_steps(self.h, None, 0)
+        out = np.empty(n, dtype=np.int32)
+        lib.cm_gqa_steps(self.h, out.ctypes.data, n)
+        return out.tolist()
+
+    def __del__(self):
+        if getattr(self, "h", None) and lib is not None:
+            lib.cm_gqa_destroy(self.h)
+            self.h = None
+
+
 class KvCache:
     def __init__(self, ctx, heads, dim, r_i, level, scale, max_tokens, unrolled_ladders=False, shared_dims=1, key_index=False):
         self.ctx, self.h, self.level, self.key_index = ctx, _vp(), level, key_index
-        t = ctx.S // (heads * dim)
+        t = ctx.S // ((1 << (heads - 1).bit_length()) * dim)
         max_tokens = dim * t if max_tokens is None else max_tokens
         _chk(lib.cm_kv_create_ex(ctx.h, heads, dim, r_i, level, scale, max_tokens,
                                  (CM_KV_UNROLLED_LADDERS if unrolled_ladders else 0) | (CM_KV_KEY_INDEX if key_index else 0),

@@ -106,7 +106,8 @@ extern "C" cm_status cm_kv_create_ex(cm_ctx *ctx, int32_t heads, int32_t dim, in
     if (!ctx || !out || heads < 1 || dim < 1 || max_tokens < 1 || (flags & ~(uint32_t)(CM_KV_UNROLLED_LADDERS | CM_KV_KEY_INDEX))) return CM_E_INVAL;
     if (level < 2 || level > ctx->L) return CM_E_LEVEL;
     const int S = ctx->n / 2;
-    if (!pow2(heads) || !pow2(dim) || heads * dim > S) return CM_E_LAYOUT;
+    heads = 1 << ilog2(heads);            // a head count that is not a power of two is padded to the next one
+    if (!pow2(dim) || heads * dim > S) return CM_E_LAYOUT;
     cm_kv *kv = new (std::nothrow) cm_kv();
     if (!kv) return CM_E_NOMEM;
     try {
@@ -446,13 +447,10 @@ extern "C" cm_status cm_kv_append_group(cm_ctx *ctx, const cm_evk *evk, cm_kv *k
     return kv_append(ctx, evk, kv, k_grp, v_grp, true, stream);
 }
 
-static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st,
-                       bool replicate) {
-    const int lv = kv->level, limbs = lv + 1;
-    if (lv < 2) return CM_E_LEVEL;
-    const size_t n = ctx->n, ctw = kv_ctw(kv), ln = (size_t)limbs * n;
-    const u64 *relin = find_key(evk, 0);
-    if (!relin) return CM_E_NOKEY;
+// every key query-times-K needs is there (checked before anything is enqueued)
+static cm_status kv_qk_keys(const cm_evk *evk, const cm_kv *kv, bool replicate) {
+    if (kv->level < 2) return CM_E_LEVEL;
+    if (!find_key(evk, 0)) return CM_E_NOKEY;
     for (int i = 0; i < ilog2(kv->t) && replicate; i++) if (!find_key(evk, rot_g(kv, -(1 << i)))) return CM_E_NOKEY;
     if (kv->unrolled) {
         for (const auto &grp : kv->dim_groups)
@@ -461,8 +459,15 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
     } else {
         for (int i = 0; i < ilog2(kv->E); i++) if (!find_key(evk, rot_g(kv, (long long)(1 << i) * kv->H * kv->t))) return CM_E_NOKEY;
     }
+    return (kv->ntok + kv->t - 1) / kv->t < 1 ? CM_E_LAYOUT : CM_OK;
+}
+static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st,
+                       bool replicate) {
+    const int lv = kv->level, limbs = lv + 1;
+    CMCHK(kv_qk_keys(evk, kv, replicate));
+    const size_t n = ctx->n, ctw = kv_ctw(kv), ln = (size_t)limbs * n;
+    const u64 *relin = find_key(evk, 0);
     const int nk = (kv->ntok + kv->t - 1) / kv->t;
-    if (nk < 1) return CM_E_LAYOUT;
     // The key ciphertexts are independent until the final sum, so CM_KS_BATCH of them go through every
     // step together: their raises, their ModDowns and their rescales are single batches of launches.
     const KsLevel &kl = ks_level(ctx, lv), &kl1 = ks_level(ctx, lv - 1);
@@ -594,13 +599,9 @@ static cm_status kv_qk(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
 
 // array = the value ciphertexts, or the key index with the query in the place of the scores (replicate: the query is
 // first copied to all residues, as query-times-K does)
-static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st,
-                       bool reduce, const u64 *array, bool replicate) {
-    const int lv = kv->level, limbs = lv + 1;
+static cm_status kv_sv_keys(const cm_evk *evk, const cm_kv *kv, bool reduce, bool replicate) {
     for (int i = 0; i < ilog2(kv->t) && replicate; i++) if (!find_key(evk, rot_g(kv, -(1 << i)))) return CM_E_NOKEY;
-    const size_t n = ctx->n, ctw = kv_ctw(kv), ln = (size_t)limbs * n;
-    const u64 *relin = find_key(evk, 0);
-    if (!relin) return CM_E_NOKEY;
+    if (!find_key(evk, 0)) return CM_E_NOKEY;
     const long long Ht = (long long)kv->H * kv->t;
     for (int j = 1; j < kv->r_i; j++) if (!find_key(evk, rot_g(kv, j * Ht))) return CM_E_NOKEY;
     if (kv->unrolled) {
@@ -611,6 +612,15 @@ static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm
         if (kv->r_o > 1 && !find_key(evk, rot_g(kv, kv->r_i * Ht))) return CM_E_NOKEY;
         for (int l = 0; l < ilog2(kv->t) && reduce; l++) if (!find_key(evk, rot_g(kv, 1 << l))) return CM_E_NOKEY;
     }
+    return CM_OK;
+}
+static cm_status kv_sv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, const cm_ct *in, cm_ct *out, hipStream_t st,
+                       bool reduce, const u64 *array, bool replicate) {
+    const int lv = kv->level, limbs = lv + 1;
+    CMCHK(kv_sv_keys(evk, kv, reduce, replicate));
+    const size_t n = ctx->n, ctw = kv_ctw(kv), ln = (size_t)limbs * n;
+    const u64 *relin = find_key(evk, 0);
+    const long long Ht = (long long)kv->H * kv->t;
     const KsLevel &kl = ks_level(ctx, lv);
     const size_t B = CM_KS_BATCH, dblk = (size_t)kl.beta * kl.ext * n, ublk = 2 * (size_t)kl.ext * n;
     u64 *babies = kv->d_work, *inner = babies + (size_t)kv->r_i * ctw, *T = inner + (size_t)kv->r_o * ctw,
@@ -730,5 +740,147 @@ extern "C" cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, 
     if (which == CM_SV || which == CM_SV_GROUP)
         return kv_sv(ctx, evk, kv, in, out, (hipStream_t)stream, which == CM_SV, kv->d_v, false);
     return CM_E_INVAL;
+    CM_CATCH
+}
+
+// ---- grouped-query attention against a cache that stores every KV head once ----------------------------------------
+// The cache is the layout of Sec. 5.3 for the Hkv KV heads (t_kv tokens per K ciphertext); the query and the attention
+// output use the layout for H = G Hkv heads (t = t_kv / G) with head h = hk G + g, whose slot (e, h, tau) is slot
+// (e, hk, g t + tau) of the cache layout.  A query head meets all t_kv token residues of its KV head in G passes: in
+// pass delta the replicated query is moved by the inner rotation (Sec. 5.4) of delta t residues and multiplied into the
+// cache without further replication (CM_QK_GROUP); scores V runs per pass without the sum over the residues
+// (CM_SV_GROUP), is moved back by (G - delta) t residues, the passes are added and the t residues of a run summed.
+struct cm_gqa {
+    cm_ctx *ctx = nullptr;
+    int G = 1, t = 1, t_kv = 1, level = 0;       // level of the cache
+    std::vector<cm_rope *> fwd, back;            // inner rotations by delta t at level+1 / level-1, delta = 1 .. G-1
+    u64 *d_work = nullptr;                       // six ciphertexts of level+2 limbs
+};
+extern "C" void cm_gqa_destroy(cm_gqa *g) {
+    if (!g) return;
+    for (cm_rope *r : g->fwd) cm_rope_destroy(r);
+    for (cm_rope *r : g->back) cm_rope_destroy(r);
+    hipFree(g->d_work);
+    delete g;
+}
+extern "C" cm_status cm_gqa_create(cm_ctx *ctx, const cm_kv *kv, int32_t group, const int64_t *coeffs, cm_gqa **out) {
+    if (!ctx || !kv || kv->ctx != ctx || !out || group < 1) return CM_E_INVAL;
+    if (!pow2(group) || kv->t % group) return CM_E_LAYOUT;
+    if (kv->level + 1 > ctx->L || kv->level < 2) return CM_E_LEVEL;
+    cm_gqa *g = new (std::nothrow) cm_gqa();
+    if (!g) return CM_E_NOMEM;
+    try {
+        g->ctx = ctx, g->G = group, g->t_kv = kv->t, g->t = kv->t / group, g->level = kv->level;
+        const size_t n = ctx->n;
+        if (hipMalloc((void **)&g->d_work, 6 * 2 * (size_t)(kv->level + 2) * n * 8) != hipSuccess) {
+            cm_gqa_destroy(g);
+            return CM_E_NOMEM;
+        }
+        for (int dir = 0; dir < 2; dir++)
+            for (int delta = 1; delta < group; delta++) {
+                cm_rope *r = nullptr;
+                const int64_t *cf = coeffs ? coeffs + ((size_t)dir * (group - 1) + (delta - 1)) * 3 * n : nullptr;
+                cm_status s = cm_inner_rot_create(ctx, kv->t, delta * g->t, dir == 0 ? kv->level + 1 : kv->level - 1, cf, &r);
+                if (s != CM_OK) {
+                    cm_gqa_destroy(g);
+                    return s;
+                }
+                (dir == 0 ? g->fwd : g->back).push_back(r);
+            }
+    } catch (...) {
+        cm_gqa_destroy(g);
+        return CM_E_NOMEM;
+    }
+    *out = g;
+    return CM_OK;
+}
+static std::vector<int> gqa_all_steps(const cm_gqa *g) {
+    std::vector<int> s;
+    for (int i = 0; i < ilog2(g->t); i++) s.push_back(-(1 << i));            // replicate the query over its run
+    for (int delta = 1; delta < g->G; delta++) s.push_back(-delta * g->t), s.push_back(g->t_kv - delta * g->t);   // inner rotations
+    for (int l = 0; l < ilog2(g->t); l++) s.push_back(1 << l);               // sum over the residues of a run
+    return s;
+}
+extern "C" int32_t cm_gqa_steps(const cm_gqa *g, int32_t *steps, int32_t cap) {
+    if (!g) return 0;
+    try {
+        auto s = gqa_all_steps(g);
+        for (int i = 0; i < (int)s.size() && i < cap && steps; i++) steps[i] = s[i];
+        return (int32_t)s.size();
+    } catch (...) {
+        return 0;
+    }
+}
+static cm_status gqa_keys(cm_ctx *ctx, const cm_evk *evk, const cm_gqa *g) {
+    for (int a : gqa_all_steps(g))
+        if (!find_key(evk, galois_of_step(ctx, a))) return CM_E_NOKEY;
+    return CM_OK;
+}
+extern "C" cm_status cm_gqa_qk(cm_ctx *ctx, const cm_evk *evk, const cm_gqa *g, const cm_kv *kv, const cm_ct *q, cm_ct *scores,
+                               void *stream) {
+    (void)hipGetLastError();
+    if (!ctx || !evk || !g || !kv || g->ctx != ctx || kv->ctx != ctx || !q || !q->dev || q->ncomp != 2 || !scores || !evk_fits(ctx, evk))
+        return CM_E_INVAL;
+    if (kv->t != g->t_kv || kv->level != g->level) return CM_E_LAYOUT;
+    if (q->level != kv->level + 1) return CM_E_LEVEL;
+    for (int d = 0; d < g->G; d++) if (!scores[d].dev) return CM_E_INVAL;
+    CM_TRY
+    CMCHK(gqa_keys(ctx, evk, g));
+    CMCHK(kv_qk_keys(evk, kv, false));
+    hipStream_t st = (hipStream_t)stream;
+    const int lq = q->level;
+    const size_t n = ctx->n, ctq = 2 * (size_t)(lq + 1) * n, slot = 2 * (size_t)(kv->level + 2) * n;
+    u64 *cq = g->d_work, *alt = cq + slot, *xd = alt + slot;
+    HIPCHK(hipMemcpyAsync(cq, q->dev, ctq * 8, hipMemcpyDeviceToDevice, st));
+    for (int i = 0; i < ilog2(g->t); i++) {
+        const u64 gal = galois_of_step(ctx, -(1 << i));
+        CMCHK(rotate_into(ctx, find_key(evk, gal), cq, lq, gal, alt, st, cq));      // alt = cq + Rot(cq)
+        std::swap(cq, alt);
+    }
+    cm_ct rep{cq, lq, 2, q->scale}, x{xd, kv->level, 2, q->scale};
+    for (int delta = 0; delta < g->G; delta++) {
+        if (delta == 0) CMCHK(cm_level_drop(ctx, &rep, kv->level, &x, stream));
+        else CMCHK(cm_rope_apply(ctx, evk, g->fwd[delta - 1], &rep, &x, stream));
+        CMCHK(kv_qk(ctx, evk, kv, &x, &scores[delta], st, false));
+    }
+    RETURN_LAUNCH_STATUS();
+    CM_CATCH
+}
+extern "C" cm_status cm_gqa_sv(cm_ctx *ctx, const cm_evk *evk, const cm_gqa *g, const cm_kv *kv, const cm_ct *scores, cm_ct *out,
+                               void *stream) {
+    (void)hipGetLastError();
+    if (!ctx || !evk || !g || !kv || g->ctx != ctx || kv->ctx != ctx || !scores || !out || !out->dev || !evk_fits(ctx, evk))
+        return CM_E_INVAL;
+    if (kv->t != g->t_kv || kv->level != g->level) return CM_E_LAYOUT;
+    for (int d = 0; d < g->G; d++) {
+        if (!scores[d].dev || scores[d].ncomp != 2) return CM_E_INVAL;
+        if (scores[d].level != kv->level) return CM_E_LEVEL;
+        if (fabs(scores[d].scale / scores[0].scale - 1) > 1e-9) return CM_E_SCALE;
+    }
+    CM_TRY
+    CMCHK(gqa_keys(ctx, evk, g));
+    CMCHK(kv_sv_keys(evk, kv, false, false));
+    hipStream_t st = (hipStream_t)stream;
+    const int lv = kv->level, lo = lv - 2;
+    const size_t n = ctx->n, slot = 2 * (size_t)(lv + 2) * n;
+    u64 *pd = g->d_work, *md = pd + slot, *acc = md + slot, *alt = acc + slot;
+    cm_ct part{pd, lv - 1, 2, 0.0}, moved{md, lo, 2, 0.0};
+    for (int delta = 0; delta < g->G; delta++) {
+        CMCHK(kv_sv(ctx, evk, kv, &scores[delta], &part, st, false, kv->d_v, false));
+        const int back = (g->G - delta) % g->G;
+        cm_ct dst{delta == 0 ? acc : md, lo, 2, 0.0};
+        if (back == 0) CMCHK(cm_level_drop(ctx, &part, lo, &dst, stream));
+        else CMCHK(cm_rope_apply(ctx, evk, g->back[back - 1], &part, &dst, stream));
+        if (delta) launch_add(ctx, acc, acc, md, 2, lo + 1, st);
+        moved.scale = dst.scale;
+    }
+    for (int l = 0; l < ilog2(g->t); l++) {
+        const u64 gal = galois_of_step(ctx, 1 << l);
+        CMCHK(rotate_into(ctx, find_key(evk, gal), acc, lo, gal, alt, st, acc));
+        std::swap(acc, alt);
+    }
+    HIPCHK(hipMemcpyAsync(out->dev, acc, 2 * (size_t)(lo + 1) * n * 8, hipMemcpyDeviceToDevice, st));
+    out->level = lo, out->ncomp = 2, out->scale = moved.scale;
+    RETURN_LAUNCH_STATUS();
     CM_CATCH
 }

@@ -43,7 +43,8 @@ extern "C" cm_status cm_rope_create(cm_ctx *ctx, int32_t heads, int32_t dim, int
     if (!ctx || !out || heads < 1 || dim < 2 || token < 0 || !(base > 1.0)) return CM_E_INVAL;
     if (level < 1 || level > ctx->L) return CM_E_LEVEL;
     const int S = ctx->n / 2;
-    if (!pow2(heads) || !pow2(dim) || heads * dim > S) return CM_E_LAYOUT;
+    while (!pow2(heads)) heads++;          // a head count that is not a power of two is padded to the next one
+    if (!pow2(dim) || heads * dim > S) return CM_E_LAYOUT;
     const int t = S / (heads * dim);
     if (tau < -1 || tau >= t) return CM_E_LAYOUT;
     cm_rope *r = new (std::nothrow) cm_rope();
