@@ -15,13 +15,17 @@ rotation by P on its own (Algorithm 1 as printed, 32 x 16, 52 rotations).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--ladders | --nested-giants | --plain-sums]
 
-    python bench.py --workload attention        (config 3, a JSON line of its own)
+    python bench.py --workload attention        (config 3, a JSON line of its own; --gqa: every KV head stored once)
     python bench.py --workload prefill          (prompt phase: token-batched product, group append, group attention)
+    python bench.py --workload layer            (config 5: one decoder layer's linear path per token on the 36 + 6 ring,
+                                                 context 4096 with every KV head stored once, four decode steps)
 
 Prints one JSON line.  `roofline` describes the kernel family with the most time in the step:
 achieved = algorithmic bytes per unit / measured time per unit (HIP events around every launch of
-the family on its stream), peak = 8 TB/s HBM, traffic = measured HBM bytes from the committed
-counter summary under profiles/.
+the family on its stream), peak = 8 TB/s HBM, traffic = HBM bytes from the committed counter summary under
+profiles/ (read from that file, not measured in this run: `traffic_source` names it).
+`cpu_baseline` (default --cpu-baseline full): ONE full product of the same workload run by the oracle on the host
+cores and timed (Algorithm 1 as printed, 52 rotations, 512 products), plus one key switch on a single thread.
 """
 import argparse
 import json
@@ -156,11 +160,15 @@ def calibration_kernel(g):
     g["torch"].cuda.synchronize()
 
 
-def cpu_baseline(raised_sums=True):
-    """The oracle as it stands on the host cores, on a bounded sample of the same workload: the
-    ring of the benchmark, 3 full rotations, one hoisting + 3 hoisted rotations, 8 plaintext
-    multiply-accumulates, one ModDown (raised sums only) and one rescale, each timed and scaled by
-    the step's operation counts (21 / 1 / 31 / 512 / 1 / 1)."""
+def _oracle_cores():
+    return int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+
+
+def cpu_baseline_sample(raised_sums=True):
+    """The oracle's primitives on a bounded sample of the workload (the ring of the benchmark, 3 full rotations,
+    one hoisting + 3 hoisted rotations, 8 plaintext multiply-accumulates, one ModDown and one rescale), each timed
+    and scaled by the operation counts of Algorithm 1 (21 / 1 / 31 / 512 / 1 / 1): an extrapolation, kept as a
+    cross-check of the measured run."""
     from oracle import ckks, params
     prm = params.config2()
     ctx = ckks.Context(prm)
@@ -194,13 +202,70 @@ def cpu_baseline(raised_sums=True):
         t_md = 0.0
     t_resc, _ = timed(lambda: ctx.rescale(x), 1)
     t_vmm = 21 * t_rot + t_hoist + 31 * t_hrot + 512 * t_mac + t_md + t_resc
-    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": 1.0 / t_vmm, "unit": "VMM/s", "cores": cores, "kind": "oracle",
+    return {"value": 1.0 / t_vmm, "unit": "VMM/s", "cores": _oracle_cores(), "kind": "oracle", "measured": False,
             "sample": "n=2^16, 24+4 primes: 3 rotations, 1 hoisting, 3 hoisted rotations, 8 pt-ct MACs, "
                       + ("1 ModDown, " if raised_sums else "") +
                       "1 rescale timed; scaled by the step's counts 21/1/31/512/" + ("1/" if raised_sums else "") +
                       "1 of Algorithm 1 with its ladders (extrapolated)",
             "key_switch_s": t_rot, "seconds_per_vmm": t_vmm}
+
+
+_SINGLE_THREAD_KS = r"""
+import sys, time
+import numpy as np
+sys.path.insert(0, sys.argv[1])
+from oracle import ckks, params
+prm = params.config2()
+ctx = ckks.Context(prm)
+sk = ctx.keygen_secret(1)
+keys = ctx.keygen_rotations(sk, [7], 2)
+ct = ctx.encrypt(sk, ctx.encode(np.random.default_rng(0).normal(size=ctx.S), prm.L), 3)
+t0 = time.perf_counter()
+ctx.rotate(ct, 7, keys)
+print(time.perf_counter() - t0)
+"""
+
+
+def cpu_baseline_full():
+    """The oracle as it stands, timed on ONE full product of the benchmark's workload (config 2, top level): Algorithm 1
+    as printed (preprocess ladder, 31 hoisted baby steps, 512 plaintext products, 15 nested giant steps, reduce ladder,
+    rescale: 52 rotations), with the inputs bench.py gives the GPU.  Key generation and encoding are set-up and timed
+    apart.  One un-hoisted rotation is also timed on all cores and, in a process of its own with OMP_NUM_THREADS=1, on a
+    single thread."""
+    import subprocess
+    from oracle import ckks, packing, params, vmm
+    from paper_2602_11470_amd import inputs
+    t_setup = time.perf_counter()
+    prm = params.config2()
+    ctx = ckks.Context(prm)
+    plan = packing.make_plan(ctx.S, D, D)
+    x, W = inputs.vmm_inputs(1, D, D)
+    sk = ctx.keygen_secret(1)
+    keys = ctx.keygen_rotations(sk, plan.all_steps(), 2)
+    diags = [[ctx.encode(v, prm.L) for v in row] for row in plan.diagonals(W)]
+    ct = ctx.encrypt(sk, ctx.encode(plan.pack_input(x), prm.L), 3)
+    t_setup = time.perf_counter() - t_setup
+    ctx.rot_count = ctx.ptmul_count = 0
+    t0 = time.perf_counter()
+    y = vmm.vmm_pt(vmm.CkksOps(ctx, keys), plan, ct, diags)
+    t_vmm = time.perf_counter() - t0
+    err = float(np.abs(plan.unpack_output(ctx.decrypt(sk, y).real) - x @ W).max())
+    rotations, products = ctx.rot_count, ctx.ptmul_count
+    t0 = time.perf_counter()
+    ctx.rotate(ct, plan.pre_steps[0], keys)
+    t_rot = time.perf_counter() - t0
+    env = dict(os.environ, OMP_NUM_THREADS="1")
+    t_rot1 = None
+    try:
+        r = subprocess.run([sys.executable, "-c", _SINGLE_THREAD_KS, ROOT], env=env, capture_output=True, text=True, timeout=300)
+        t_rot1 = float(r.stdout.strip().splitlines()[-1])
+    except Exception:                                          # reported as missing, never guessed
+        pass
+    return {"value": 1.0 / t_vmm, "unit": "VMM/s", "cores": _oracle_cores(), "kind": "oracle", "measured": True,
+            "sample": "one full 4096x4096 product at config 2 (n=2^16, 24+4 primes, top level), Algorithm 1 as printed: "
+                      f"{rotations} rotations, {products} plaintext products, one rescale; oracle.vmm.vmm_pt timed as it stands",
+            "seconds_per_vmm": t_vmm, "setup_seconds": t_setup, "max_abs_err_vs_float64": err,
+            "key_switch_s": t_rot, "key_switch_s_single_thread": t_rot1}
 
 
 def attention_workload(a):
@@ -213,6 +278,8 @@ def attention_workload(a):
     parity of this path is in tests/)."""
     import torch
     from paper_2602_11470_amd import binding as B
+    if a.gqa:
+        return attention_workload_gqa(a)
     ctx = B.llama_ring(24, 4)
     H, E, L = 32, 128, ctx.L
     lv = a.cache_level if a.cache_level > 0 else L - 1
@@ -268,6 +335,171 @@ def attention_workload(a):
                               "mask before the last %d terms: %d rotations per key ciphertext + %d shared" % (sh, per_ct, sh - 1)},
         "qk_ms": res["qk"] * 1e3, "sv_ms": res["sv"] * 1e3, "append_ms": append_ms,
         "qk_key_switches": ks_qk, "qk_key_switches_per_s": ks_qk / res["qk"]}))
+
+
+def attention_workload_gqa(a):
+    """Config 3 with every KV head stored once: 8 KV heads x 128 dims, t_kv = 32 tokens per K ciphertext, so the context
+    of 1024 tokens is 32 K ciphertexts + 128 V ciphertexts (a quarter of the replicated layout's 128 + 128 at four times
+    the capacity); q K^T and scores V run in four passes (inner rotation of the query / of the result, un-replicated
+    products).  Same number of ciphertext products as the replicated layout."""
+    import torch
+    from paper_2602_11470_amd import binding as B
+    ctx = B.llama_ring(24, 4)
+    Hkv, G, E, L = 8, 4, 128, ctx.L
+    lv = a.cache_level if a.cache_level > 0 else L - 2
+    kv = ctx.kv_create(Hkv, E, lv, r_i=16, unrolled_ladders=True, key_index=a.key_index,
+                       shared_dims=1 if a.key_index else (a.shared_dims or 32))
+    gqa = ctx.gqa(kv, G)
+    tk = ctx.S // (Hkv * E)
+    sk = ctx.keygen_secret(1)
+    keys = ctx.keygen_rotations(sk, sorted({s_ for s_ in kv.steps() if s_ % tk == 0} | set(gqa.steps())), 2, with_relin=True)
+    rng = np.random.default_rng(3)
+    enc = lambda seed, level: ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), L), seed), level)
+    nk = 1024 // tk
+    for c in range(nk):
+        kv.load(B.CM_QK, c, enc(100 + c, lv))
+    for c in range(E):
+        kv.load(B.CM_SV, c, enc(300 + c, lv))
+        if a.key_index:
+            kv.load(B.CM_KV_INDEX, c, enc(500 + c, lv))
+    kv.set_tokens(1024 - 8)
+    new_k, new_v = enc(20, lv + 1), enc(21, lv + 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(8):
+        kv.append(keys, new_k, new_v)
+    torch.cuda.synchronize()
+    append_ms = (time.perf_counter() - t0) / 8 * 1e3
+    q = enc(10, lv + 1)
+    scores = [enc(11 + d, lv) for d in range(G)]
+    res = {}
+    for name, fn in (("qk", lambda: ctx.gqa_qk(keys, gqa, q)), ("sv", lambda: ctx.gqa_sv(keys, gqa, scores))):
+        for _ in range(max(1, a.warmup // 2)):
+            fn()
+        torch.cuda.synchronize()
+        reps = max(1, a.steps // 5)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        res[name] = (time.perf_counter() - t0) / reps
+    free, total = torch.cuda.mem_get_info()
+    print(json.dumps({
+        "metric": "encrypted-cache attention products/s (config 3: q K^T and scores V, 32 query heads on 8 KV heads x 128 dims, "
+                  "context 1024, n=2^16, 24x50-bit + 4x60-bit primes; every KV head stored once)",
+        "value": 1.0 / (res["qk"] + res["sv"]), "unit": "attention steps/s", "n_gpus": 1,
+        "higher_is_better": True, "dtype": "u64", "data": "synthetic", "vs_baseline": None,
+        "config": {"workload": "config3, GQA-native: q K^T (32 K ciphertexts x 4 passes) + scores V (128 V ciphertexts x 4 passes)",
+                   "cache_level": lv, "shared_dims": 1 if a.key_index else (a.shared_dims or 32), "key_index": bool(a.key_index),
+                   "cache_ciphertexts": nk + E * (2 if a.key_index else 1)},
+        "qk_ms": res["qk"] * 1e3, "sv_ms": res["sv"] * 1e3, "append_ms": append_ms,
+        "device_bytes_in_use": total - free}))
+
+
+def layer_workload(a):
+    """Config 5: the linear path of one Llama-3-8B-shaped decoder layer per token on the ring of 36 + 6 primes, context
+    4096 in ONE cache that stores the 8 KV heads once (128 K + 128 V ciphertexts), four decode steps: q projection
+    (4096 x 4096), k / v projections (4096 x 1024, one shared-baby-step call, outputs on the residue of the token), rotary
+    embedding of q and k, append, q K^T and scores V in four passes each, extraction, output projection, gate / up (one
+    call) and down.  Where the model has a non-linear layer (softmax, normalisation, SiLU) the next stage starts from a
+    resident ciphertext at the level the stage runs at.  Everything is resident in HBM before the timed region."""
+    import torch
+    from paper_2602_11470_amd import binding as B
+    t_setup = time.perf_counter()
+    ctx = B.llama_ring(36, 6)
+    H, Hkv, G, E, d, dm, L = 32, 8, 4, 128, 4096, 16384, ctx.L
+    t, tk = ctx.S // d, ctx.S // (Hkv * E)
+    cache_lv = L - 3                       # projection, rotary embedding, append mask: one level each
+    o_lv = cache_lv - 3                    # scores V (one level), the move back to the query heads' runs, the extraction
+    mlp_lv, down_lv = 12, 10               # the MLP further down the chain (the paper runs it at its lowest levels, Table 5)
+    rng = np.random.default_rng(5)
+    Wsq = lambda: rng.normal(0, 0.02, (d, d))
+    sk = ctx.keygen_secret(1)
+    index = not a.no_key_index
+    kv = ctx.kv_create(Hkv, E, cache_lv, r_i=16, unrolled_ladders=True, key_index=index,
+                       shared_dims=1 if index else (a.shared_dims or 128))
+    gqa = ctx.gqa(kv, G)
+    plan_q = ctx.vmm_plan(d, d, W=Wsq(), level=L, unrolled_ladders=True)
+    plan_o = ctx.vmm_plan(d, d, W=Wsq(), level=o_lv, unrolled_ladders=True)
+    plan_g = ctx.vmm_plan(d, dm, W=rng.normal(0, 0.02, (d, dm)), level=mlp_lv, unrolled_ladders=True)
+    plan_u = ctx.vmm_plan(d, dm, W=rng.normal(0, 0.02, (d, dm)), level=mlp_lv, unrolled_ladders=True)
+    plan_d = ctx.vmm_plan(dm, d, W=rng.normal(0, 0.02, (dm, d)), level=down_lv, unrolled_ladders=True)
+    n0 = 4096 - 4
+    taus = [(n0 + i) % tk for i in range(4)]
+    Wk, Wv = rng.normal(0, 0.02, (d, Hkv * E)), rng.normal(0, 0.02, (d, Hkv * E))
+    plans_kv = [(ctx.vmm_plan(d, Hkv * E, W=Wk, level=L, tau=tau, unrolled_ladders=True),
+                 ctx.vmm_plan(d, Hkv * E, W=Wv, level=L, tau=tau, unrolled_ladders=True)) for tau in taus]
+    ropes_q = [ctx.rope(H, E, L - 1, n0 + i, 0) for i in range(4)]
+    ropes_k = [ctx.rope(Hkv, E, L - 1, n0 + i, taus[i]) for i in range(4)]
+    steps = {s_ for s_ in kv.steps() if s_ % tk == 0} | set(gqa.steps()) | {H * t, -H * t, Hkv * tk, -Hkv * tk}
+    for p in [plan_q, plan_o, plan_g, plan_u, plan_d] + [p for pair in plans_kv for p in pair]:
+        steps |= set(p.steps())
+    keys = ctx.keygen_rotations(sk, sorted(steps), 2, with_relin=True)
+    enc = lambda level, seed, scale=0.0: ctx.level_drop(ctx.encrypt(sk, ctx.encode(rng.normal(size=ctx.S), L, scale), seed), level)
+    mods = ctx.moduli()
+    proj_scale = ctx.scale * ctx.scale / float(mods[L])          # a cache holds one scale: the one a projection leaves
+    for c in range(128):
+        kv.load(B.CM_QK, c, enc(cache_lv, 100 + c, proj_scale))
+        kv.load(B.CM_SV, c, enc(cache_lv, 300 + c, proj_scale))
+        if index:
+            kv.load(B.CM_KV_INDEX, c, enc(cache_lv, 500 + c, proj_scale))
+    residue0 = np.zeros(ctx.S)
+    residue0[::t] = 1.0
+    mask = ctx.encode(residue0, cache_lv - 2, float(mods[cache_lv - 2]), mont=True)
+    x = enc(L, 500)
+    scores = [enc(cache_lv, 700 + d_) for d_ in range(G)]
+    h_in, act = enc(mlp_lv, 800), enc(down_lv, 900)
+    torch.cuda.synchronize()
+    free, total = torch.cuda.mem_get_info()
+    t_setup = time.perf_counter() - t_setup
+
+    def run():
+        kv.set_tokens(n0)
+        marks = []
+        for i in range(4):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            gq = ctx.vmm_pt(keys, plan_q, x)
+            gk, gv = ctx.vmm_pt_multi(keys, list(plans_kv[i]), x)
+            gq = ctx.rope_apply(keys, ropes_q[i], gq)
+            gk = ctx.rope_apply(keys, ropes_k[i], gk)
+            kv.append(keys, gk, ctx.level_drop(gv, L - 2))
+            e1 = torch.cuda.Event(enable_timing=True)
+            e1.record()
+            ctx.gqa_qk(keys, gqa, gq)
+            e2 = torch.cuda.Event(enable_timing=True)
+            e2.record()
+            ga = ctx.gqa_sv(keys, gqa, scores)
+            e3 = torch.cuda.Event(enable_timing=True)
+            e3.record()
+            ctx.vmm_pt(keys, plan_o, ctx.rescale(ctx.mul_pt(ga, mask)))
+            ctx.vmm_pt_multi(keys, [plan_g, plan_u], h_in)
+            ctx.vmm_pt(keys, plan_d, act)
+            e4 = torch.cuda.Event(enable_timing=True)
+            e4.record()
+            marks.append((e0, e1, e2, e3, e4))
+        torch.cuda.synchronize()
+        return marks
+
+    run()                                   # warm-up: per-level tables, allocator
+    t0 = time.perf_counter()
+    marks = run()
+    sec = (time.perf_counter() - t0) / 4
+    parts = np.array([[m[j].elapsed_time(m[j + 1]) for j in range(4)] for m in marks]).mean(axis=0)
+    print(json.dumps({
+        "metric": "decoder-layer linear path per token (config 5: n=2^16, 36x50-bit + 6x60-bit primes, dnum 6; context 4096, "
+                  "8 KV heads stored once; four decode steps)",
+        "value": 1.0 / sec, "unit": "decode steps/s", "ms_per_step": sec * 1e3, "n_gpus": 1, "steps": 4,
+        "higher_is_better": True, "dtype": "u64", "data": "synthetic", "vs_baseline": None,
+        "config": {"workload": "config5: q, k, v, o, gate, up, down projections + rotary embedding + append + q K^T + scores V "
+                               "per token, context 4096",
+                   "levels": {"input": L, "cache": cache_lv, "output_projection": o_lv, "gate_up": mlp_lv, "down": down_lv},
+                   "rotation_keys": len(steps), "cache_ciphertexts": 384 if index else 256,
+                   "q_k_transposed": "from the key index (the scores V schedule per pass)" if index else
+                                     "copy mask in front of the sum over the dims, %d shared rotations per pass" % ((a.shared_dims or 128) - 1)},
+        "ms": {"projections_rope_append": float(parts[0]), "qk": float(parts[1]), "sv": float(parts[2]),
+               "o_gate_up_down": float(parts[3])},
+        "device_bytes_resident": int(total - free), "setup_seconds": t_setup}))
 
 
 def sweep_workload(a):
@@ -422,7 +654,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="same as --cpu-baseline none")
+    ap.add_argument("--cpu-baseline", choices=["full", "sample", "none"], default="full",
+                    help="full (default): one full product of the workload timed on the oracle (about two minutes of host "
+                         "time) and the extrapolation from a sample beside it; sample: the extrapolation only; none")
+    ap.add_argument("--no-key-index", action="store_true",
+                    help="layer workload: q K^T from the K cache itself instead of the key index")
+    ap.add_argument("--gqa", action="store_true",
+                    help="attention workload: the cache stores the 8 KV heads once (32 K ciphertexts of 32 tokens), q K^T and "
+                         "scores V run in four passes (cm_gqa_*)")
     ap.add_argument("--shared-dims", type=int, default=0,
                     help="attention / prefill workloads: terms of the sum over the dims of q K^T taken after the copy mask, by "
                          "rotations shared by all key ciphertexts (1 = the printed order; default 128 for the 128 key "
@@ -437,7 +677,7 @@ def main():
     ap.add_argument("--plain-sums", action="store_true",
                     help="divide every hoisted rotation by P on its own (31 more ModDowns per step)")
     ap.add_argument("--cache-level", type=int, default=0, help="attention workload: level of the cache (default L-1)")
-    ap.add_argument("--workload", choices=["projection", "attention", "sweep", "prefill"], default="projection",
+    ap.add_argument("--workload", choices=["projection", "attention", "sweep", "prefill", "layer"], default="projection",
                     help="projection = config 2 (the benchmark line); attention = config 3; sweep = other widths "
                          "and levels; the last two print a line of their own")
     a = ap.parse_args()
@@ -453,6 +693,9 @@ def main():
         return
     if a.workload == "sweep":
         sweep_workload(a)
+        return
+    if a.workload == "layer":
+        layer_workload(a)
         return
     nested = a.plain_sums or a.nested_giants
     g = gpu_setup(raised_sums=not a.plain_sums, direct_giants=not nested, unrolled_ladders=not (nested or a.ladders))
@@ -551,13 +794,22 @@ def main():
         "kernel_ms_per_step": {k: round(v["ms"], 4) for k, v in fam.items()},
         "dominant_kernel_family": dom,
         "roofline": roofline,
+        "traffic_source": "profiles/pmc_hbm_traffic_bench_config2.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary committed "
+                          "with the code; read from the file, not measured in this run)",
         "roofline_inner_product": roofs["inner_product"],
         "roofline_vmm_mac": roofs["vmm_mac"],
         "roofline_key_switch_inner_product": roofs["inner_product_single"],
         "roofline_ntt_fwd": roofs["ntt_fwd"],
     }
-    if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(raised_sums=not a.plain_sums)
+    mode = "none" if a.no_cpu_baseline else a.cpu_baseline
+    if mode != "none":
+        g.clear()                                        # the GPU's memory and the host's cores go back before the oracle runs
+        sample = cpu_baseline_sample(raised_sums=not a.plain_sums)
+        if mode == "full":
+            out["cpu_baseline"] = cpu_baseline_full()
+            out["cpu_baseline"]["extrapolated_seconds_per_vmm"] = sample["seconds_per_vmm"]
+        else:
+            out["cpu_baseline"] = sample
     print(json.dumps(out))
 
 

@@ -368,7 +368,8 @@ cm_status cm_vmm_kv(cm_ctx *ctx, const cm_evk *evk, const cm_kv *kv, int32_t whi
  * H = group*heads heads (t = t_kv/group), head h = hk*group + g, whose slot (e, h, tau) IS slot (e, hk, g*t + tau)
  * of the cache layout.  A query head meets all t_kv token residues of its KV head in `group` passes: in pass delta
  * the replicated query is moved by the inner rotation (Sec. 5.4) of delta*t residues and multiplied into the cache
- * as a query group (CM_QK_GROUP).  scores[delta] (an array of `group` ciphertexts, two levels below the cache)
+ * as a query group (CM_QK_GROUP).  scores[delta] (an array of `group` ciphertexts, two levels below the cache; one
+ * level below it for a cache with CM_KV_KEY_INDEX, whose passes run on the index at the cost of scores-times-V)
  * holds at slot (c, hk, j) the score of head (hk, (j/t - delta) mod group) against token c*t_kv + j.
  * cm_gqa_sv takes `group` score ciphertexts in that layout at the cache level, runs scores-times-V per pass
  * without the sum over the residues (CM_SV_GROUP), moves each result back by (group - delta)*t residues, adds them

@@ -351,7 +351,7 @@ class Context:
 
     def gqa_qk(self, evk, gqa, q):
         """group score ciphertexts (pass delta at index delta), two levels below the cache."""
-        outs = [Ct(self, q.level - 3) for _ in range(gqa.group)]
+        outs = [Ct(self, q.level - (2 if gqa.kv.key_index else 3)) for _ in range(gqa.group)]
         arr = (cm_ct * gqa.group)(*[o.d for o in outs])
         _chk(lib.cm_gqa_qk(self.h, evk.h, gqa.h, gqa.kv.h, C.byref(q.d), arr, _stream()))
         for o, d in zip(outs, arr):

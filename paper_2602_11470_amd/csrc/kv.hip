@@ -826,7 +826,10 @@ extern "C" cm_status cm_gqa_qk(cm_ctx *ctx, const cm_evk *evk, const cm_gqa *g, 
     for (int d = 0; d < g->G; d++) if (!scores[d].dev) return CM_E_INVAL;
     CM_TRY
     CMCHK(gqa_keys(ctx, evk, g));
-    CMCHK(kv_qk_keys(evk, kv, false));
+    // a cache with the key index: every pass is the scores-times-V schedule on the index (scores one level below the
+    // cache); otherwise the un-replicated query-times-K of the cache's form (two levels below)
+    if (kv->indexed) CMCHK(kv_sv_keys(evk, kv, false, false));
+    else CMCHK(kv_qk_keys(evk, kv, false));
     hipStream_t st = (hipStream_t)stream;
     const int lq = q->level;
     const size_t n = ctx->n, ctq = 2 * (size_t)(lq + 1) * n, slot = 2 * (size_t)(kv->level + 2) * n;
@@ -841,7 +844,8 @@ extern "C" cm_status cm_gqa_qk(cm_ctx *ctx, const cm_evk *evk, const cm_gqa *g, 
     for (int delta = 0; delta < g->G; delta++) {
         if (delta == 0) CMCHK(cm_level_drop(ctx, &rep, kv->level, &x, stream));
         else CMCHK(cm_rope_apply(ctx, evk, g->fwd[delta - 1], &rep, &x, stream));
-        CMCHK(kv_qk(ctx, evk, kv, &x, &scores[delta], st, false));
+        if (kv->indexed) CMCHK(kv_sv(ctx, evk, kv, &x, &scores[delta], st, false, kv->d_x, false));
+        else CMCHK(kv_qk(ctx, evk, kv, &x, &scores[delta], st, false));
     }
     RETURN_LAUNCH_STATUS();
     CM_CATCH

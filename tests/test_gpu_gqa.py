@@ -36,8 +36,8 @@ def _same(e, o, g):
     assert np.array_equal(e["gctx"].ct_export(g), e["octx"].canonical(o))
 
 
-@pytest.mark.parametrize("unrolled,r_i", [(False, 4), (True, 0)])
-def test_gqa_products_match_oracle_and_float64(env, unrolled, r_i):
+@pytest.mark.parametrize("unrolled,r_i,index", [(False, 4, False), (True, 0, False), (False, 4, True), (True, 4, True)])
+def test_gqa_products_match_oracle_and_float64(env, unrolled, r_i, index):
     """8 query heads on 2 KV heads of 16 dims (G = 4, t_kv = 64, t = 16) on the 2048-slot ring: the four score
     ciphertexts of q K^T and the output of scores V limb for limb against the oracle's composition of the same
     steps, and against the einsum with shared KV heads."""
@@ -54,7 +54,7 @@ def test_gqa_products_match_oracle_and_float64(env, unrolled, r_i):
     s = rng.uniform(0, 1, size=(H, ntok))
     s /= s.sum(axis=1, keepdims=True)
     lv = L - 1
-    kv = gctx.kv_create(Hkv, E, lv, r_i=r_i, unrolled_ladders=unrolled)
+    kv = gctx.kv_create(Hkv, E, lv, r_i=r_i, unrolled_ladders=unrolled, key_index=index)
     rot_coeffs = {}
     for d_, level in ((0, lv + 1), (1, lv - 1)):
         ql = float(octx.mod[level])
@@ -62,7 +62,7 @@ def test_gqa_products_match_oracle_and_float64(env, unrolled, r_i):
             rot_coeffs[d_, delta] = [octx.encode_coeffs(p, ql) for p in kvl.inner_rotation_plaintexts(glay.inner_delta(delta))]
     gqa = gctx.gqa(kv, G, coeffs=np.stack([np.stack(rot_coeffs[d_, delta]) for d_ in (0, 1) for delta in range(1, G)]))
     steps = sorted({a for a in kv.steps() if a % kvl.t == 0} | set(gqa.steps()))
-    assert set(glay.qk_steps()) | set(glay.sv_steps()) <= set(steps) or unrolled
+    assert set(glay.qk_steps()) | set(glay.sv_steps()) <= set(steps) or unrolled or index
     okeys = octx.keygen_rotations(e["osk"], steps, 2, with_relin=True)
     gkeys = gctx.keygen_rotations(e["gsk"], steps, 2, with_relin=True)
     m0 = np.zeros(octx.S)
@@ -84,15 +84,24 @@ def test_gqa_products_match_oracle_and_float64(env, unrolled, r_i):
         ok, gk = _enc_both(e, kvl.pack_k(K, c), lv, 100 + c)
         okc.append(ok)
         kv.load(B.CM_QK, c, gk)
+    oxc = []
     for k in range(E):
         ov, gv = _enc_both(e, kvl.pack_v(V, k), lv, 300 + k)
         ovc.append(ov)
         kv.load(B.CM_SV, k, gv)
+        if index:
+            ox, gx = _enc_both(e, kvl.pack_k_index(K, k), lv, 700 + k)
+            oxc.append(ox)
+            kv.load(B.CM_KV_INDEX, k, gx)
     kv.set_tokens(ntok)
     ops = vmm.CkksOps(octx, okeys)
     oq, gq = _enc_both(e, glay.q.pack_vec(q), lv + 1, 10)
     masks = [omask(c) for c in range(nk)]
     qk = (lambda x: vmm.qk_scores_unrolled(octx, okeys, kvl, x, okc, masks, replicate=False)) if unrolled else None
+    if index and unrolled:
+        qk = lambda x: vmm.score_times_v_unrolled(octx, okeys, kvl, x, oxc, reduce=False)
+    elif index:
+        qk = lambda x: vmm.qk_scores_indexed(ops, kvl, x, oxc, replicate=False)
     oms = vmm.gqa_qk_scores(ops, glay, oq, okc, masks, opts(0, lv + 1), qk=qk)
     gms = gctx.gqa_qk(gkeys, gqa, gq)
     assert len(gms) == G
