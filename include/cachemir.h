@@ -70,7 +70,8 @@ int32_t cm_last_hip_error(void);
  *   candidates 2^bits + 1 - k*2n (k = 1,2,..), primes kept in order:
  * q_0 from q0_bits, q_1..q_{n_q-1} from qi_bits (one scan: if q0_bits == qi_bits the chain is
  * the first n_q primes of that scan), special primes p_0..p_{n_p-1} from p_bits.
- * alpha = primes per key-switch digit.  hamming = 0: i.i.d. uniform ternary secret, else the
+ * alpha = primes per key-switch digit (alpha <= 8 and n_p <= 8, n_q + n_p <= 64, at most 16 digits;
+ * anything else is CM_E_INVAL).  hamming = 0: i.i.d. uniform ternary secret, else the
  * exact number of non-zero secret coefficients.  sigma must be 3.2 (error table is fixed). */
 typedef struct {
     int32_t n;          /* ring degree: 4096 or 65536 */

@@ -251,6 +251,7 @@ extern "C" cm_status cm_ctx_create(const cm_params *p, cm_ctx **out) {
     if (p->n != 4096 && p->n != 65536) return CM_E_INVAL;
     if (p->n_q < 1 || p->n_p < 1 || p->alpha < 1 || p->n_q + p->n_p > CM_MAX_LIMBS) return CM_E_INVAL;
     if ((p->n_q + p->alpha - 1) / p->alpha > CM_MAX_DIGITS) return CM_E_INVAL;
+    if (p->alpha > CONV_MAX_SRC || p->n_p > CONV_MAX_SRC) return CM_E_INVAL;   // sources of one base conversion
     if (p->q0_bits > 61 || p->qi_bits > 61 || p->p_bits > 61 || p->q0_bits < 20 || p->qi_bits < 20 ||
         p->p_bits < 20)
         return CM_E_INVAL;

@@ -341,7 +341,10 @@ void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, 
 // z % beta and its polynomials over z / beta).  blockIdx.y = group of CONV_TG targets; the cheap y_m are recomputed per group so
 // that a conversion fills the machine.  If own_src is given, group 0 also copies the source rows
 // of own_src (the evaluation-domain input) to the same rows of the output.
-template <int CONV_TG>
+// NS = compile-time bound on the source count: the table rows past ns are all zero (a zero inverse, a zero modulus, zero
+// weights, input row 0), so the arithmetic runs unconditionally over NS rows and every load of a lane is in flight at once
+// instead of one load-wait-use chain per source.
+template <int CONV_TG, int NS>
 __global__ __launch_bounds__(TPB) void k_base_conv(u64 *__restrict__ out, const u64 *__restrict__ in,
                                                    const ConvDev *__restrict__ tabs, int tab_step, int tab_period,
                                                    int in_group, int n, size_t in_stride, size_t out_stride,
@@ -354,26 +357,28 @@ __global__ __launch_bounds__(TPB) void k_base_conv(u64 *__restrict__ out, const 
     if (r0 >= nt) return;
     in += (blockIdx.z / in_group) * in_stride;
     out += blockIdx.z * out_stride;
-    if (own_src) own_src += (blockIdx.z / in_group) * own_stride;
-    u64 y[CONV_MAX_SRC];
+    u64 x[NS], y[NS];
 #pragma unroll
-    for (int m = 0; m < CONV_MAX_SRC; m++) {
-        y[m] = 0;
-        if (m < ns) {
-            y[m] = mul_shoup(in[(size_t)t.in_rows[m] * n + i], t.inv_hat[m], t.inv_hat_sh[m], t.src_q[m]);
-            if (own_src && r0 == 0)
-                out[(size_t)t.in_rows[m] * n + i] =
-                    own_src[(size_t)t.in_rows[m] * n + (own_g ? perm_src((unsigned)i, own_g, logn) : (unsigned)i)];
-        }
+    for (int m = 0; m < NS; m++) x[m] = in[(size_t)t.in_rows[m] * n + i];
+    if (own_src && r0 == 0) {
+        own_src += (blockIdx.z / in_group) * own_stride;
+        const unsigned s = own_g ? perm_src((unsigned)i, own_g, logn) : (unsigned)i;
+        u64 o[NS];
+#pragma unroll
+        for (int m = 0; m < NS; m++) o[m] = own_src[(size_t)t.in_rows[m] * n + s];
+#pragma unroll
+        for (int m = 0; m < NS; m++)
+            if (m < ns) out[(size_t)t.in_rows[m] * n + i] = o[m];
     }
+#pragma unroll
+    for (int m = 0; m < NS; m++) y[m] = mul_shoup(x[m], t.inv_hat[m], t.inv_hat_sh[m], t.src_q[m]);
 #pragma unroll
     for (int rr = 0; rr < CONV_TG; rr++) {
         const int r = r0 + rr;
         if (r < nt) {
             u128 acc = 0;
 #pragma unroll
-            for (int m = 0; m < CONV_MAX_SRC; m++)
-                if (m < ns) acc += (u128)y[m] * t.hat_mont[m * nt + r];
+            for (int m = 0; m < NS; m++) acc += (u128)y[m] * t.hat_mont[m * nt + r];
             out[(size_t)t.out_rows[r] * n + i] = redc(acc, t.dst_q[r], t.dst_qinv[r]);
         }
     }
@@ -383,11 +388,19 @@ void launch_base_conv(cm_ctx *ctx, const ConvDev *d_tabs, int batch, int tab_ste
                       int in_group, size_t own_stride) {
     if (tab_period <= 0) tab_period = batch;
     Prof prof_(ctx, CM_K_BASE_CONV, batch * max_nt, st);
-    // 8 targets per lane (measured best of 2 / 4 / 8 / 12 / 24 at the benchmark's shapes)
-    const int TG = 8;
-    hipLaunchKernelGGL(k_base_conv<8>, dim3(ctx->n / TPB, (max_nt + TG - 1) / TG, batch), dim3(TPB), 0, st, out, in,
-                       d_tabs, tab_step, tab_period, in_group, ctx->n, in_stride, out_stride, own_src, own_stride,
-                       (unsigned)own_g, ctx->logn);
+    // 8 targets per lane (measured best of 2 / 4 / 8 / 12 / 24 at the benchmark's shapes); the source bound is the larger
+    // of the digit size and the special prime count, rounded up to an instantiated one
+    const int TG = 8, ns = ctx->alpha > ctx->K ? ctx->alpha : ctx->K;
+    const dim3 grid(ctx->n / TPB, (max_nt + TG - 1) / TG, batch);
+#define CONV_LAUNCH(NS_)                                                                                                 \
+    hipLaunchKernelGGL((k_base_conv<8, NS_>), grid, dim3(TPB), 0, st, out, in, d_tabs, tab_step, tab_period, in_group, ctx->n, \
+                       in_stride, out_stride, own_src, own_stride, (unsigned)own_g, ctx->logn)
+    if (ns <= 1) CONV_LAUNCH(1);
+    else if (ns <= 2) CONV_LAUNCH(2);
+    else if (ns <= 4) CONV_LAUNCH(4);
+    else if (ns <= 6) CONV_LAUNCH(6);
+    else CONV_LAUNCH(8);
+#undef CONV_LAUNCH
 }
 
 // ---- evaluation-key inner product ------------------------------------------------------------------
@@ -515,7 +528,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
     const int mi = r <= level ? r : L + 1 + (r - level - 1);
     const ModC m = modc[mi];
     const size_t o = (size_t)r * n + i2;
-    const u64 bound = ubound[mi], cg0 = ((u64)i2 + 1) * GOLD, cg1 = cg0 + GOLD;
+    const u64 bound = ubound[mi];
     ulonglong2 r0 = make_ulonglong2(0, 0), r1 = make_ulonglong2(0, 0);
     if (b.extra[z]) {
         r0 = *reinterpret_cast<const ulonglong2 *>(b.extra[z] + o);
@@ -1001,6 +1014,7 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 // baby ciphertexts per pass (32 KiB of LDS).
 #define MAC_CO 64
 #define MAC_JC 32
+typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 // Limbs whose modulus is below 2^50 run the products in FP64 (the arithmetic of the transforms'
 // butterflies): residues as exact integers in doubles, a modular product
 //     h = y a;  l = fma(y, a, -h);  c = rint(y (a / q));  r = fma(-c, q, h) + l        (|r| < q)
@@ -1008,6 +1022,13 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 // sums are renormalised every four terms (|sum| < 4.6 q < 2^53 stays exact).  That is 8.5
 // instructions per product against 17 for the 128-bit integer form.  The plaintexts are stored in
 // multiplier form (times 2^64), so the finished sum is multiplied by 2^-64 mod q.
+// With an even number of baby steps the words of plaintexts (2j', k) and (2j'+1, k) are interleaved
+// (word c of the pair at 2c, 2c+1 of a 128-word row), so that a lane reads both with one 16-byte load and a
+// wavefront instruction covers 1 KiB of the stream.
+__host__ __device__ __forceinline__ size_t mac_pt_index(int n, int r_i, int r_o, int l, int ch, int k, int j, int c) {
+    const size_t row = (((size_t)l * (n / MAC_CO) + ch) * r_o + k) * r_i;
+    return (r_i & 1) ? (row + j) * MAC_CO + c : (row + (j & ~1)) * MAC_CO + 2 * c + (j & 1);
+}
 __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, const u64 *__restrict__ babies,
                                                      const u64 *__restrict__ pts, const ModC *__restrict__ modc,
                                                      const FpQ *__restrict__ fpq, int r_i, int r_o, int limbs, int n,
@@ -1019,9 +1040,10 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
     const ModC m = modc[mi];
     const FpQ fq = fpq[mi];
     const bool fp = fq.q != 0.0;
+    const bool pair = !(r_i & 1);
     const MacFp F{fq.q, fq.qinv};
     const size_t o = (size_t)l * n + i0, cs = (size_t)limbs * n;
-    const u64 *pblk = pts + ((size_t)l * (n / MAC_CO) + blockIdx.x) * r_o * r_i * MAC_CO + co;
+    const u64 *pblk = pts + ((size_t)l * (n / MAC_CO) + blockIdx.x) * r_o * r_i * MAC_CO;
     for (int j0 = 0; j0 < r_i; j0 += MAC_JC) {
         const int jn = r_i - j0 < MAC_JC ? r_i - j0 : MAC_JC;
         __syncthreads();
@@ -1035,17 +1057,28 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
         // REDC): after every group for the 60-bit special primes.
         for (int k = k0 + kq; k < k1; k += 4) {
             const u64 *pk = pblk + ((size_t)k * r_i + j0) * MAC_CO;
-            u64 p[8], pn[8];
+            // words of plaintexts j0 + j8 .. j0 + j8 + 7 for this lane's coefficient (zero past the end)
+            auto load8 = [&](int j8, u64 (&w)[8]) {
+                if (pair) {
 #pragma unroll
-            for (int jj = 0; jj < 8; jj++) p[jj] = jj < jn ? __builtin_nontemporal_load(pk + (size_t)jj * MAC_CO) : 0;
+                    for (int jj = 0; jj < 8; jj += 2) {
+                        u64x2 v = {0, 0};
+                        if (j8 + jj < jn) v = __builtin_nontemporal_load(reinterpret_cast<const u64x2 *>(pk + (size_t)(j8 + jj) * MAC_CO) + co);
+                        w[jj] = v.x, w[jj + 1] = v.y;
+                    }
+                } else {
+#pragma unroll
+                    for (int jj = 0; jj < 8; jj++) w[jj] = j8 + jj < jn ? __builtin_nontemporal_load(pk + (size_t)(j8 + jj) * MAC_CO + co) : 0;
+                }
+            };
+            u64 p[8], pn[8];
+            load8(0, p);
             u64 v0, v1;
             if (fp) {
                 double s0 = 0.0, s1 = 0.0;
                 for (int j8 = 0; j8 < jn; j8 += 8) {
                     // the next group is in flight while this one is multiplied
-#pragma unroll
-                    for (int jj = 0; jj < 8; jj++)
-                        pn[jj] = j8 + 8 + jj < jn ? __builtin_nontemporal_load(pk + (size_t)(j8 + 8 + jj) * MAC_CO) : 0;
+                    load8(j8 + 8, pn);
 #pragma unroll
                     for (int jj = 0; jj < 8; jj++) {
                         if (j8 + jj < jn) {
@@ -1063,9 +1096,7 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
             } else {
                 v0 = v1 = 0;
                 for (int j8 = 0; j8 < jn; j8 += 8) {
-#pragma unroll
-                    for (int jj = 0; jj < 8; jj++)
-                        pn[jj] = j8 + 8 + jj < jn ? __builtin_nontemporal_load(pk + (size_t)(j8 + 8 + jj) * MAC_CO) : 0;
+                    load8(j8 + 8, pn);
                     u128 s0 = 0, s1 = 0;
 #pragma unroll
                     for (int jj = 0; jj < 8; jj++) {
@@ -1285,7 +1316,7 @@ void launch_mask_ntt(cm_ctx *ctx, u64 *A, const u64 *T, const u64 *Mhat, const u
 // plaintext (j,k) between its plain form src[limbs][n] and its place in the blocked array
 __global__ void k_pt_block(u64 *blocked, u64 *plain, int n, int r_i, int r_o, int j, int k, int to_blocked) {
     const int i = blockIdx.x * TPB + threadIdx.x, l = blockIdx.y;
-    const size_t b = ((((size_t)l * (n / MAC_CO) + i / MAC_CO) * r_o + k) * r_i + j) * MAC_CO + i % MAC_CO;
+    const size_t b = mac_pt_index(n, r_i, r_o, l, i / MAC_CO, k, j, i % MAC_CO);
     const size_t p = (size_t)l * n + i;
     if (to_blocked) blocked[b] = plain[p];
     else plain[p] = blocked[b];

@@ -119,12 +119,33 @@ struct FpArith {
 
 // Twiddle providers for four stages starting at stage s0 with base0 = 2^s0 + (block index):
 // stage s0 + a, group g uses table entry (base0 << a) + g.
+// Integer limbs read the entry and its companion where the butterfly uses them.  FP64 limbs read all fifteen
+// entries up front (one exposure to memory latency instead of one per stage, and the loads overlap the data loads
+// or the LDS exchange in front of them); the second factor w/q is taken as w * (1/q), one multiplication instead
+// of a second table: the quotient estimate may then be off by one more unit, the product stays exact
+// (|r| <= 1.3 q for |y| <= 2.1 q).
 template <class A>
-struct TableTw {
-    const A &ar;
+struct TableTw;
+template <>
+struct TableTw<IntArith> {
+    const IntArith &ar;
     u64 base0;
-    __device__ __forceinline__ void get(int a, int g, typename A::W &w0, typename A::W &w1) const {
-        ar.load_tw((base0 << a) + g, w0, w1);
+    __device__ __forceinline__ TableTw(const IntArith &a_, u64 b0) : ar(a_), base0(b0) {}
+    __device__ __forceinline__ void get(int a, int g, u64 &w0, u64 &w1) const { ar.load_tw((base0 << a) + g, w0, w1); }
+};
+template <>
+struct TableTw<FpArith> {
+    const FpArith &ar;
+    double w[15];
+    __device__ __forceinline__ TableTw(const FpArith &a_, u64 b0) : ar(a_) {
+#pragma unroll
+        for (int a = 0; a < 4; a++)
+#pragma unroll
+            for (int g = 0; g < (1 << a); g++) w[(1 << a) - 1 + g] = ar.w[(b0 << a) + g];
+    }
+    __device__ __forceinline__ void get(int a, int g, double &w0, double &w1) const {
+        w0 = w[(1 << a) - 1 + g];
+        w1 = w0 * ar.qinv;
     }
 };
 // The same entries computed from ONE table word (FP64 limbs): with T_a = tw[base0 << a],
@@ -183,26 +204,18 @@ __device__ __forceinline__ void radix16_inv_tw(typename A::T (&v)[16], const A &
         }
     }
 }
-template <class A>
-__device__ __forceinline__ void radix16_fwd(typename A::T (&v)[16], const A &ar, u64 base0) {
-    radix16_fwd_tw(v, ar, TableTw<A>{ar, base0});
-}
-template <class A>
-__device__ __forceinline__ void radix16_inv(typename A::T (&v)[16], const A &ar, u64 base0) {
-    radix16_inv_tw(v, ar, TableTw<A>{ar, base0});
-}
 // last four stages of the row pass: generated twiddles for FP64 limbs, table for the others
 __device__ __forceinline__ void radix16_fwd_last(double (&v)[16], const FpArith &ar, u64 base0) {
     radix16_fwd_tw(v, ar, GenTw(ar, base0));
 }
 __device__ __forceinline__ void radix16_fwd_last(u64 (&v)[16], const IntArith &ar, u64 base0) {
-    radix16_fwd_tw(v, ar, TableTw<IntArith>{ar, base0});
+    radix16_fwd_tw(v, ar, TableTw<IntArith>(ar, base0));
 }
 __device__ __forceinline__ void radix16_inv_last(double (&v)[16], const FpArith &ar, u64 base0) {
     radix16_inv_tw(v, ar, GenTw(ar, base0));
 }
 __device__ __forceinline__ void radix16_inv_last(u64 (&v)[16], const IntArith &ar, u64 base0) {
-    radix16_inv_tw(v, ar, TableTw<IntArith>{ar, base0});
+    radix16_inv_tw(v, ar, TableTw<IntArith>(ar, base0));
 }
 
 // LDS index with one pad word per 16 so that lanes reading words 16 apart hit distinct banks
@@ -216,15 +229,22 @@ __device__ __forceinline__ void cols_fwd_body(u64 *lds, u64 *p, const u64 *ps, c
     ar.init(t, mi, n);
     const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
     typename A::T v[16];
+    u64 raw[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = ar.from_rest(ps[(unsigned)((sub + 16 * k) * n2 + c)]);
-    radix16_fwd(v, ar, 1);
+    for (int k = 0; k < 16; k++) raw[k] = ps[(unsigned)((sub + 16 * k) * n2 + c)];
+    {
+        const TableTw<A> tw(ar, 1);                 // in flight together with the data
+#pragma unroll
+        for (int k = 0; k < 16; k++) v[k] = ar.from_rest(raw[k]);
+        radix16_fwd_tw(v, ar, tw);
+    }
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[pad((sub + 16 * k) * 16 + c)] = ar.to_mid(v[k]);
+    const TableTw<A> tw2(ar, 16 + sub);             // in flight across the exchange
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad((16 * sub + k) * 16 + c)]);
-    radix16_fwd(v, ar, 16 + sub);
+    radix16_fwd_tw(v, ar, tw2);
 #pragma unroll
     for (int k = 0; k < 16; k++) p[(unsigned)((16 * sub + k) * n2 + c)] = ar.to_mid(v[k]);
 }
@@ -234,15 +254,22 @@ __device__ __forceinline__ void cols_inv_body(u64 *lds, u64 *p, const NttTables 
     ar.init(t, mi, n);
     const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
     typename A::T v[16];
+    u64 raw[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(p[(unsigned)((16 * sub + k) * n2 + c)]);
-    radix16_inv(v, ar, 16 + sub);
+    for (int k = 0; k < 16; k++) raw[k] = p[(unsigned)((16 * sub + k) * n2 + c)];
+    {
+        const TableTw<A> tw(ar, 16 + sub);          // in flight together with the data
+#pragma unroll
+        for (int k = 0; k < 16; k++) v[k] = ar.from_mid(raw[k]);
+        radix16_inv_tw(v, ar, tw);
+    }
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[pad((16 * sub + k) * 16 + c)] = ar.to_mid(v[k]);
+    const TableTw<A> tw2(ar, 1);
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad((sub + 16 * k) * 16 + c)]);
-    radix16_inv(v, ar, 1);
+    radix16_inv_tw(v, ar, tw2);
 #pragma unroll
     for (int k = 0; k < 16; k++) p[(unsigned)((sub + 16 * k) * n2 + c)] = ar.to_rest_inv(v[k]);
 }
@@ -279,7 +306,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_cols_inv(u64 *__restrict__ da
 }
 
 // ---- row passes on contiguous blocks of 256 words (n = 65536): a workgroup owns 16 blocks ---------------
-template <class A>
+template <class A, bool TAIL>
 __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTables &t, int mi, int n, int chunk,
                                                  int limb, const FinishBatch &fb) {
     A ar;
@@ -287,9 +314,15 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
     const int sub = threadIdx.x & 15, blk = threadIdx.x >> 4;
     const u64 B = (u64)chunk * 16 + blk;
     typename A::T v[16];
+    u64 raw[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) v[k] = ar.from_mid(p[blk * 256 + sub + 16 * k]);
-    radix16_fwd(v, ar, 256 + B);
+    for (int k = 0; k < 16; k++) raw[k] = p[blk * 256 + sub + 16 * k];
+    {
+        const TableTw<A> tw(ar, 256 + B);           // in flight together with the data
+#pragma unroll
+        for (int k = 0; k < 16; k++) v[k] = ar.from_mid(raw[k]);
+        radix16_fwd_tw(v, ar, tw);
+    }
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[pad(blk * 256 + sub + 16 * k)] = ar.to_mid(v[k]);
     __syncthreads();
@@ -302,7 +335,7 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[pad(blk * 256 + 16 * sub + k)] = ar.to_rest_fwd(v[k]);
     __syncthreads();
-    if (fb.items == 0) {
+    if (!TAIL) {
 #pragma unroll
         for (int k = 0; k < 16; k++) p[threadIdx.x + 256 * k] = lds[pad(threadIdx.x + 256 * k)];
         return;
@@ -319,27 +352,55 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
     u64 *op = fb.out[r] + row + pos0;
     const unsigned g = fb.g[r];
     const int logn = 31 - __clz(n);
+    // All operands of the tail are loaded first, then combined: sixteen independent loads per stream are in flight at
+    // once instead of one load-wait-use chain per word.
+    u64 uu[16], aa[16], cc[16];
     if (fb.mul_pt) {
         // u = u[r] * (mul_pt through the Galois map mul_g[r]), formed here instead of being read
         const u64 qinv = t.modc[l].qinv;
         const u64 *mp = fb.mul_pt + (size_t)l * n;
         const unsigned mg = fb.mul_g[r];
 #pragma unroll
+        for (int k = 0; k < 16; k++) uu[k] = up[256 * k];
+        if (mg) {
+#pragma unroll
+            for (int k = 0; k < 16; k++) aa[k] = mp[perm_src(pos0 + 256 * k, mg, logn)];
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; k++) aa[k] = mp[pos0 + 256 * k];
+        }
+        if (ac) {
+#pragma unroll
+            for (int k = 0; k < 16; k++) cc[k] = ac[256 * k];
+        }
+#pragma unroll
         for (int k = 0; k < 16; k++) {
-            const unsigned pos = pos0 + 256 * k;
-            const u64 uv = redc((u128)up[256 * k] * mp[mg ? perm_src(pos, mg, logn) : pos], q, qinv);
+            const u64 uv = redc((u128)uu[k] * aa[k], q, qinv);
             u64 x = mul_shoup(submod(uv, lds[pad(threadIdx.x + 256 * k)], q), pi, pis, q);
-            if (ac) x = addmod(x, ac[256 * k], q);
+            if (ac) x = addmod(x, cc[k], q);
             op[256 * k] = x;
         }
         return;
     }
 #pragma unroll
+    for (int k = 0; k < 16; k++) uu[k] = up[256 * k];
+    if (ad && g) {
+#pragma unroll
+        for (int k = 0; k < 16; k++) aa[k] = ad[perm_src(pos0 + 256 * k, g, logn)];
+    } else if (ad) {
+#pragma unroll
+        for (int k = 0; k < 16; k++) aa[k] = ad[pos0 + 256 * k];
+    }
+    if (ac) {
+#pragma unroll
+        for (int k = 0; k < 16; k++) cc[k] = ac[256 * k];
+    }
+#pragma unroll
     for (int k = 0; k < 16; k++) {
-        u64 d = submod(up[256 * k], lds[pad(threadIdx.x + 256 * k)], q);
+        u64 d = submod(uu[k], lds[pad(threadIdx.x + 256 * k)], q);
         u64 x = mul_shoup(d, pi, pis, q);
-        if (ad) x = addmod(x, ad[g ? perm_src(pos0 + 256 * k, g, logn) : pos0 + 256 * k], q);
-        if (ac) x = addmod(x, ac[256 * k], q);
+        if (ad) x = addmod(x, aa[k], q);
+        if (ac) x = addmod(x, cc[k], q);
         op[256 * k] = x;
     }
 }
@@ -356,9 +417,16 @@ __device__ __forceinline__ void rows256_inv_body(u64 *lds, u64 *p, const u64 *ps
     {
         const int logn = 31 - __clz(n);
         const unsigned pos0 = (unsigned)chunk * 4096 + threadIdx.x;
+        u64 w[16];                        // sixteen independent loads in flight, then the writes to LDS
+        if (g) {
 #pragma unroll
-        for (int k = 0; k < 16; k++)
-            lds[pad(threadIdx.x + 256 * k)] = g ? psrow[perm_src(pos0 + 256 * k, g, logn)] : ps[threadIdx.x + 256 * k];
+            for (int k = 0; k < 16; k++) w[k] = psrow[perm_src(pos0 + 256 * k, g, logn)];
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; k++) w[k] = ps[threadIdx.x + 256 * k];
+        }
+#pragma unroll
+        for (int k = 0; k < 16; k++) lds[pad(threadIdx.x + 256 * k)] = w[k];
         __syncthreads();
 #pragma unroll
         for (int k = 0; k < 16; k++) v[k] = ar.from_rest(lds[pad(blk * 256 + 16 * sub + k)]);
@@ -367,13 +435,16 @@ __device__ __forceinline__ void rows256_inv_body(u64 *lds, u64 *p, const u64 *ps
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[pad(blk * 256 + 16 * sub + k)] = ar.to_mid(v[k]);
     __syncthreads();
+    const TableTw<A> tw2(ar, 256 + B);
 #pragma unroll
     for (int k = 0; k < 16; k++) v[k] = ar.from_mid(lds[pad(blk * 256 + sub + 16 * k)]);
-    radix16_inv(v, ar, 256 + B);
+    radix16_inv_tw(v, ar, tw2);
 #pragma unroll
     for (int k = 0; k < 16; k++) p[blk * 256 + sub + 16 * k] = ar.to_mid(v[k]);
 }
-// grid.x = limbs * n/4096
+// grid.x = limbs * n/4096; TAIL: the fused ModDown / rescale tail (a kernel of its own, so that the registers its
+// operands take do not lower the occupancy of the plain transform)
+template <bool TAIL>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_fwd(u64 *__restrict__ data, const int *__restrict__ rows,
                                                               const int *__restrict__ mod_idx, NttTables t, int n,
                                                               FinishBatch fb) {
@@ -383,9 +454,9 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_fwd(u64 *__restrict__
     const int mi = mod_idx[limb];
     u64 *p = data + (size_t)(rows ? rows[limb] : limb) * n + (size_t)chunk * 4096;
     if (t.fpq[mi].q != 0.0)
-        rows256_fwd_body<FpArith>(lds, p, t, mi, n, chunk, limb, fb);
+        rows256_fwd_body<FpArith, TAIL>(lds, p, t, mi, n, chunk, limb, fb);
     else
-        rows256_fwd_body<IntArith>(lds, p, t, mi, n, chunk, limb, fb);
+        rows256_fwd_body<IntArith, TAIL>(lds, p, t, mi, n, chunk, limb, fb);
 }
 __global__ __launch_bounds__(NTT_THREADS) void ntt_rows256_inv(u64 *__restrict__ data, const u64 *__restrict__ src,
                                                               const int *__restrict__ src_rows,
@@ -413,7 +484,7 @@ __device__ __forceinline__ void rows16_fwd_body(u64 *p, const NttTables &t, int 
     typename A::T v[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) v[k] = ar.from_mid(p[k]);
-    radix16_fwd(v, ar, 256 + B);
+    radix16_fwd_tw(v, ar, TableTw<A>(ar, 256 + B));
 #pragma unroll
     for (int k = 0; k < 16; k++) p[k] = ar.to_rest_fwd(v[k]);
 }
@@ -427,7 +498,7 @@ __device__ __forceinline__ void rows16_inv_body(u64 *p, const u64 *ps, const u64
 #pragma unroll
     for (int k = 0; k < 16; k++)
         v[k] = ar.from_rest(g ? psrow[perm_src((unsigned)(B * 16 + k), g, logn)] : ps[k]);
-    radix16_inv(v, ar, 256 + B);
+    radix16_inv_tw(v, ar, TableTw<A>(ar, 256 + B));
 #pragma unroll
     for (int k = 0; k < 16; k++) p[k] = ar.to_mid(v[k]);
 }
@@ -479,7 +550,7 @@ void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, c
         t.ninv = t.ninvp = nullptr, t.ninvd = t.ninvqd = nullptr;
         hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, data, src, d_src_rows, d_rows, d_mod_idx, t, n, n2);
         if (n2 == 256)
-            hipLaunchKernelGGL(ntt_rows256_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, t, n, FinishBatch());
+            hipLaunchKernelGGL(ntt_rows256_fwd<false>, grid, block, 0, st, data, d_rows, d_mod_idx, t, n, FinishBatch());
         else
             hipLaunchKernelGGL(ntt_rows16_fwd, grid, block, 0, st, data, d_rows, d_mod_idx, t, n);
     } else {
@@ -505,7 +576,7 @@ void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const Fini
     t.tw = ctx->d_tw, t.twp = ctx->d_twp, t.twd = ctx->d_twd, t.twqd = ctx->d_twqd;
     t.ninv = t.ninvp = nullptr, t.ninvd = t.ninvqd = nullptr;
     hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, conv, src, d_src_rows, (const int *)nullptr, d_mods, t, n, n >> 8);
-    hipLaunchKernelGGL(ntt_rows256_fwd, grid, block, 0, st, conv, (const int *)nullptr, d_mods, t, n, fb);
+    hipLaunchKernelGGL(ntt_rows256_fwd<true>, grid, block, 0, st, conv, (const int *)nullptr, d_mods, t, n, fb);
 }
 void launch_ntt_rows(cm_ctx *ctx, u64 *data, const int *d_rows, const int *d_mod_idx, int limbs,
                      bool inverse, hipStream_t st) {
