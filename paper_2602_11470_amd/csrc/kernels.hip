@@ -528,7 +528,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_batch(IpBatch b, const Mo
     const int mi = r <= level ? r : L + 1 + (r - level - 1);
     const ModC m = modc[mi];
     const size_t o = (size_t)r * n + i2;
-    const u64 bound = ubound[mi];
+    const u64 bound = ubound[mi], cg0 = ((u64)i2 + 1) * GOLD, cg1 = cg0 + GOLD;
     ulonglong2 r0 = make_ulonglong2(0, 0), r1 = make_ulonglong2(0, 0);
     if (b.extra[z]) {
         r0 = *reinterpret_cast<const ulonglong2 *>(b.extra[z] + o);
@@ -1014,6 +1014,7 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 // baby ciphertexts per pass (32 KiB of LDS).
 #define MAC_CO 64
 #define MAC_JC 32
+#define MAC_G 8       // plaintext words a lane keeps in flight per group (the next group is loaded while one is multiplied; 16 and 32 measured slower)
 typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 // Limbs whose modulus is below 2^50 run the products in FP64 (the arithmetic of the transforms'
 // butterflies): residues as exact integers in doubles, a modular product
@@ -1034,7 +1035,7 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
                                                      const FpQ *__restrict__ fpq, int r_i, int r_o, int limbs, int n,
                                                      size_t ct_stride, int k0, int k1, int level, int L) {
     __shared__ u64 sb[MAC_JC * 2 * MAC_CO];
-    const int l = blockIdx.y, i0 = blockIdx.x * MAC_CO;
+    const int l = blockIdx.y, ch = blockIdx.x, i0 = ch * MAC_CO;
     const int co = threadIdx.x & (MAC_CO - 1), kq = threadIdx.x >> 6;
     const int mi = l <= level ? l : L + 1 + (l - level - 1);
     const ModC m = modc[mi];
@@ -1043,44 +1044,54 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
     const bool pair = !(r_i & 1);
     const MacFp F{fq.q, fq.qinv};
     const size_t o = (size_t)l * n + i0, cs = (size_t)limbs * n;
-    const u64 *pblk = pts + ((size_t)l * (n / MAC_CO) + blockIdx.x) * r_o * r_i * MAC_CO;
+    const u64 *pblk = pts + ((size_t)l * (n / MAC_CO) + ch) * r_o * r_i * MAC_CO;
     for (int j0 = 0; j0 < r_i; j0 += MAC_JC) {
         const int jn = r_i - j0 < MAC_JC ? r_i - j0 : MAC_JC;
         __syncthreads();
-        for (int e = threadIdx.x; e < jn * 2 * MAC_CO; e += TPB) {
-            int jc = e >> 6, c = e & (MAC_CO - 1);
-            u64 v = babies[(size_t)(j0 + (jc >> 1)) * ct_stride + (jc & 1) * cs + o + c];
-            sb[e] = fp ? (u64)__double_as_longlong(MacFp::from_u64(v)) : v;
+        {
+            // a lane stages word `co` of rows kq, kq + 4, ...: all its loads are issued before the first is used
+            constexpr int ROWS = MAC_JC * 2 * MAC_CO / TPB;
+            u64 w[ROWS];
+#pragma unroll
+            for (int it = 0; it < ROWS; it++) {
+                const int jc = kq + 4 * it;
+                w[it] = jc < 2 * jn ? babies[(size_t)(j0 + (jc >> 1)) * ct_stride + (jc & 1) * cs + o + co] : 0;
+            }
+#pragma unroll
+            for (int it = 0; it < ROWS; it++) {
+                const int jc = kq + 4 * it;
+                if (jc < 2 * jn) sb[jc * MAC_CO + co] = fp ? (u64)__double_as_longlong(MacFp::from_u64(w[it])) : w[it];
+            }
         }
         __syncthreads();
         // A sum of products is reduced when one more group of 8 could pass q * 2^64 (the bound of
         // REDC): after every group for the 60-bit special primes.
         for (int k = k0 + kq; k < k1; k += 4) {
             const u64 *pk = pblk + ((size_t)k * r_i + j0) * MAC_CO;
-            // words of plaintexts j0 + j8 .. j0 + j8 + 7 for this lane's coefficient (zero past the end)
-            auto load8 = [&](int j8, u64 (&w)[8]) {
+            // words of plaintexts j0 + j8 .. j0 + j8 + MAC_G - 1 for this lane's coefficient (zero past the end)
+            auto load_group = [&](int j8, u64 (&w)[MAC_G]) {
                 if (pair) {
 #pragma unroll
-                    for (int jj = 0; jj < 8; jj += 2) {
+                    for (int jj = 0; jj < MAC_G; jj += 2) {
                         u64x2 v = {0, 0};
                         if (j8 + jj < jn) v = __builtin_nontemporal_load(reinterpret_cast<const u64x2 *>(pk + (size_t)(j8 + jj) * MAC_CO) + co);
                         w[jj] = v.x, w[jj + 1] = v.y;
                     }
                 } else {
 #pragma unroll
-                    for (int jj = 0; jj < 8; jj++) w[jj] = j8 + jj < jn ? __builtin_nontemporal_load(pk + (size_t)(j8 + jj) * MAC_CO + co) : 0;
+                    for (int jj = 0; jj < MAC_G; jj++) w[jj] = j8 + jj < jn ? __builtin_nontemporal_load(pk + (size_t)(j8 + jj) * MAC_CO + co) : 0;
                 }
             };
-            u64 p[8], pn[8];
-            load8(0, p);
+            u64 p[MAC_G], pn[MAC_G];
+            load_group(0, p);
             u64 v0, v1;
             if (fp) {
                 double s0 = 0.0, s1 = 0.0;
-                for (int j8 = 0; j8 < jn; j8 += 8) {
+                for (int j8 = 0; j8 < jn; j8 += MAC_G) {
                     // the next group is in flight while this one is multiplied
-                    load8(j8 + 8, pn);
+                    load_group(j8 + MAC_G, pn);
 #pragma unroll
-                    for (int jj = 0; jj < 8; jj++) {
+                    for (int jj = 0; jj < MAC_G; jj++) {
                         if (j8 + jj < jn) {
                             const double a = MacFp::from_u64(p[jj]), aq = a * F.qinv;
                             s0 += F.mulmod(__longlong_as_double((long long)sb[((j8 + jj) * 2 + 0) * MAC_CO + co]), a, aq);
@@ -1089,26 +1100,29 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
                         if ((jj & 3) == 3) s0 = F.norm(s0), s1 = F.norm(s1);
                     }
 #pragma unroll
-                    for (int jj = 0; jj < 8; jj++) p[jj] = pn[jj];
+                    for (int jj = 0; jj < MAC_G; jj++) p[jj] = pn[jj];
                 }
                 v0 = F.canon(F.mulmod(s0, fq.rinv, fq.rinvq));
                 v1 = F.canon(F.mulmod(s1, fq.rinv, fq.rinvq));
             } else {
                 v0 = v1 = 0;
-                for (int j8 = 0; j8 < jn; j8 += 8) {
-                    load8(j8 + 8, pn);
-                    u128 s0 = 0, s1 = 0;
+                for (int j8 = 0; j8 < jn; j8 += MAC_G) {
+                    load_group(j8 + MAC_G, pn);
 #pragma unroll
-                    for (int jj = 0; jj < 8; jj++) {
-                        if (j8 + jj < jn) {
-                            s0 += (u128)sb[((j8 + jj) * 2 + 0) * MAC_CO + co] * p[jj];
-                            s1 += (u128)sb[((j8 + jj) * 2 + 1) * MAC_CO + co] * p[jj];
+                    for (int h = 0; h < MAC_G; h += 8) {
+                        u128 s0 = 0, s1 = 0;
+#pragma unroll
+                        for (int jj = h; jj < h + 8; jj++) {
+                            if (j8 + jj < jn) {
+                                s0 += (u128)sb[((j8 + jj) * 2 + 0) * MAC_CO + co] * p[jj];
+                                s1 += (u128)sb[((j8 + jj) * 2 + 1) * MAC_CO + co] * p[jj];
+                            }
                         }
+                        v0 = addmod(v0, redc(s0, m.q, m.qinv), m.q);
+                        v1 = addmod(v1, redc(s1, m.q, m.qinv), m.q);
                     }
-                    v0 = addmod(v0, redc(s0, m.q, m.qinv), m.q);
-                    v1 = addmod(v1, redc(s1, m.q, m.qinv), m.q);
 #pragma unroll
-                    for (int jj = 0; jj < 8; jj++) p[jj] = pn[jj];
+                    for (int jj = 0; jj < MAC_G; jj++) p[jj] = pn[jj];
                 }
             }
             u64 *dst = out + (size_t)k * ct_stride + o + co;
@@ -1156,10 +1170,19 @@ __global__ __launch_bounds__(TPB) void k_mask_circulant(u64 *__restrict__ A, con
     for (int c0 = 0; c0 < nk; c0 += CIRC_CC) {
         const int cn = nk - c0 < CIRC_CC ? nk - c0 : CIRC_CC;
         __syncthreads();
-        for (int e = threadIdx.x; e < cn * 2 * MAC_CO; e += TPB) {
-            const int jc = e >> 6, c = e & (MAC_CO - 1);
-            const u64 x = T[(size_t)(c0 + (jc >> 1)) * ctw + (jc & 1) * cs + o + c];
-            sb[e] = fp ? (u64)__double_as_longlong(MacFp::from_u64(x)) : x;
+        {
+            constexpr int ROWS = CIRC_CC * 2 * MAC_CO / TPB;      // all loads of a lane in flight before the first is used
+            u64 x[ROWS];
+#pragma unroll
+            for (int it = 0; it < ROWS; it++) {
+                const int jc = w + 4 * it;
+                x[it] = jc < 2 * cn ? T[(size_t)(c0 + (jc >> 1)) * ctw + (jc & 1) * cs + o + co] : 0;
+            }
+#pragma unroll
+            for (int it = 0; it < ROWS; it++) {
+                const int jc = w + 4 * it;
+                if (jc < 2 * cn) sb[jc * MAC_CO + co] = fp ? (u64)__double_as_longlong(MacFp::from_u64(x[it])) : x[it];
+            }
         }
         __syncthreads();
         if (!active) continue;
