@@ -455,6 +455,21 @@ template <bool SA>
 __device__ __forceinline__ u64 evk_a_reduce(u128 T, const ModC &m) {
     return SA ? redc(T, m.q, m.qinv) : redc_raw(T, m);
 }
+// Sum of products d * w with d below 2^50 held as two 25-bit halves (d = d0 + 2^25 d1) and w any 64-bit word: four
+// 32 x 32 -> 64-bit multiply-adds into four accumulators that cannot overflow for up to 16 terms (each term is below
+// 2^57), so a product costs four instructions and no carry chain; the accumulators are combined once per sum.  The
+// generic form (64 x 64 -> 128 with carries, about ten instructions) stays for the 60-bit moduli.
+struct Acc50 {
+    u64 t00 = 0, t01 = 0, t10 = 0, t11 = 0;
+    __device__ __forceinline__ void mac(unsigned d0, unsigned d1, u64 w) {
+        const unsigned w0 = (unsigned)w, w1 = (unsigned)(w >> 32);
+        t00 += (u64)d0 * w0, t01 += (u64)d0 * w1, t10 += (u64)d1 * w0, t11 += (u64)d1 * w1;
+    }
+    __device__ __forceinline__ u128 total() const {
+        return (u128)t00 + ((u128)t01 << 32) + ((u128)t10 << 25) + ((u128)t11 << 57);
+    }
+};
+#define LOW25 0x1FFFFFFu
 static EvkA evk_a_of(const cm_ctx *ctx) {
     return EvkA{ctx->evk_stored_a ? evk_a_offset(ctx) : 0, (ctx->L + ctx->alpha) / ctx->alpha};
 }
@@ -670,6 +685,7 @@ __global__ __launch_bounds__(TPB) void k_inner_product_fanout(IpFan f, const u64
     const int mi = r <= level ? r : L + 1 + (r - level - 1);
     const ModC m = modc[mi];
     const u64 bound = ubound[mi];
+    const bool small = m.q < (1ULL << 50);
     ulonglong2 d[IP_SHARED_MAX_BETA];
 #pragma unroll
     for (int j = 0; j < IP_SHARED_MAX_BETA; j++)
@@ -686,25 +702,79 @@ __global__ __launch_bounds__(TPB) void k_inner_product_fanout(IpFan f, const u64
         }
     }
     const int a_end = min(f.n, (int)(bz + 1) * IP_FAN_CHUNK);
+    // The generator stream keys of this chunk's (key, digit) pairs: lane 8 a' + j of every wave fetches one, and the loop
+    // below broadcasts it with a lane read, so that no draw waits for a load of its own.
+    u64 my_sk = 0;
+    if (!SA) {
+        const int la = (threadIdx.x & 63) >> 3, lj = threadIdx.x & 7;
+        static_assert(IP_FAN_CHUNK * IP_SHARED_MAX_BETA == 64, "one lane per (key, digit) of a chunk");
+        if ((int)bz * IP_FAN_CHUNK + la < a_end && lj < beta)
+            my_sk = f.key[bz * IP_FAN_CHUNK + la][(size_t)eva.kdig * nmod * n + (size_t)lj * nmod + mi];
+    }
     for (int a = bz * IP_FAN_CHUNK; a < a_end; a++) {
         const unsigned dst = perm_src(s2, f.ginv[a], logn);       // where this rotation puts source s2; s2 + 1 goes to dst ^ 1
         const unsigned base = dst & ~1u;
         const bool swap = dst & 1u;
         const u64 *key = f.key[a];
         const u64 cg0 = ((u64)base + 1) * GOLD, cg1 = cg0 + GOLD;
-        u128 a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+        // every key word of this rotation is requested before the first is used
+        ulonglong2 eb[IP_SHARED_MAX_BETA], ea[IP_SHARED_MAX_BETA];
 #pragma unroll
-        for (int j = 0; j < IP_SHARED_MAX_BETA; j++) {
+        for (int j = 0; j < IP_SHARED_MAX_BETA; j++)
             if (j < beta) {
-                const u64 dx = swap ? d[j].y : d[j].x, dy = swap ? d[j].x : d[j].y;      // sources of positions base, base + 1
                 const u64 *kb = key + ((size_t)j * nmod + mi) * n + base;
-                ulonglong2 eb;
-                eb.x = __builtin_nontemporal_load(kb), eb.y = __builtin_nontemporal_load(kb + 1);
-                const ulonglong2 ea = evk_a_words<SA>(key, eva, nmod, n, j, mi, base, cg0, cg1, bound);
-                b0 += (u128)dx * eb.x;
-                b1 += (u128)dy * eb.y;
-                a0 += (u128)dx * ea.x;
-                a1 += (u128)dy * ea.y;
+                eb[j].x = __builtin_nontemporal_load(kb), eb[j].y = __builtin_nontemporal_load(kb + 1);
+                if (SA) {
+                    const u64 *ka = kb + eva.a_off;
+                    ea[j].x = __builtin_nontemporal_load(ka), ea[j].y = __builtin_nontemporal_load(ka + 1);
+                }
+            }
+        if (!SA) {
+            // attempt 0 of every draw in straight-line code; the rejected ones (a 2^-14 chance under a 50-bit modulus,
+            // up to 1/16 under a 60-bit one) are redone in one branch behind them
+            const int l0 = (a - (int)bz * IP_FAN_CHUNK) * 8;
+            bool rej = false;
+#pragma unroll
+            for (int j = 0; j < IP_SHARED_MAX_BETA; j++)
+                if (j < beta) {
+                    const u64 sk_ = ((u64)__builtin_amdgcn_readlane((int)(my_sk >> 32), l0 + j) << 32) |
+                                    (unsigned)__builtin_amdgcn_readlane((int)my_sk, l0 + j);
+                    ea[j].x = mix64(sk_ + cg0), ea[j].y = mix64(sk_ + cg1);
+                    rej |= (ea[j].x >= bound) | (ea[j].y >= bound);
+                }
+            if (rej) {
+#pragma unroll
+                for (int j = 0; j < IP_SHARED_MAX_BETA; j++)
+                    if (j < beta) {
+                        const u64 sk_ = ((u64)__builtin_amdgcn_readlane((int)(my_sk >> 32), l0 + j) << 32) |
+                                        (unsigned)__builtin_amdgcn_readlane((int)my_sk, l0 + j);
+                        ea[j].x = evk_a_draw(sk_, cg0, base, bound), ea[j].y = evk_a_draw(sk_, cg1, base + 1, bound);
+                    }
+            }
+        }
+        u128 a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+        if (small) {
+            Acc50 A0, A1, B0, B1;
+#pragma unroll
+            for (int j = 0; j < IP_SHARED_MAX_BETA; j++) {
+                if (j < beta) {
+                    const u64 dx = swap ? d[j].y : d[j].x, dy = swap ? d[j].x : d[j].y;      // sources of positions base, base + 1
+                    const unsigned x0 = (unsigned)dx & LOW25, x1 = (unsigned)(dx >> 25), y0 = (unsigned)dy & LOW25, y1 = (unsigned)(dy >> 25);
+                    B0.mac(x0, x1, eb[j].x), B1.mac(y0, y1, eb[j].y);
+                    A0.mac(x0, x1, ea[j].x), A1.mac(y0, y1, ea[j].y);
+                }
+            }
+            a0 = A0.total(), a1 = A1.total(), b0 = B0.total(), b1 = B1.total();
+        } else {
+#pragma unroll
+            for (int j = 0; j < IP_SHARED_MAX_BETA; j++) {
+                if (j < beta) {
+                    const u64 dx = swap ? d[j].y : d[j].x, dy = swap ? d[j].x : d[j].y;
+                    b0 += (u128)dx * eb[j].x;
+                    b1 += (u128)dy * eb[j].y;
+                    a0 += (u128)dx * ea[j].x;
+                    a1 += (u128)dy * ea[j].y;
+                }
             }
         }
         ulonglong2 r0 = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
