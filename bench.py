@@ -776,6 +776,22 @@ def main():
                     "traffic": tr.get("k_vmm_mac_lds"), "kernel": "k_vmm_mac_lds (one launch per step)",
                     "algorithmic_bytes_per_launch": mac_bytes, "us_per_launch": mac_s * 1e6},
     }
+    # What plain streaming kernels of the same read/write mix reach on this device (cm_hbm_probe), and each family's rate
+    # as a fraction of it.  The transform pair moves every limb twice in each direction (column pass, row pass), so its
+    # traffic is twice its algorithmic bytes.
+    B = g["B"]
+    probe = {"read": B.hbm_probe(B.CM_PROBE_READ), "read1_write1": B.hbm_probe(B.CM_PROBE_COPY),
+             "read3_write1": B.hbm_probe(B.CM_PROBE_READ3_WRITE1), "unit": "GB/s",
+             "what": "best of 5 passes of a plain streaming kernel over 4 GiB (16-byte non-temporal accesses): reads only; one "
+                     "read and one write stream; three read streams and one write stream"}
+    roofs["ntt_fwd"]["frac_of_probe"] = 2 * ntt_gbs / probe["read1_write1"]
+    roofs["ntt_fwd"]["probe"] = "read1_write1, against the pair's traffic of 2 MiB per limb"
+    roofs["inner_product"]["frac_of_probe"] = ip_gbs / probe["read3_write1"]
+    roofs["inner_product"]["probe"] = "read3_write1"
+    roofs["inner_product_single"]["frac_of_probe"] = roofs["inner_product_single"]["achieved"] / probe["read"]
+    roofs["inner_product_single"]["probe"] = "read (15 words read per word written)"
+    roofs["vmm_mac"]["frac_of_probe"] = mac_gbs / probe["read"]
+    roofs["vmm_mac"]["probe"] = "read"
     roofline = roofs.get(dom, roofs["inner_product"])
     ks_bytes = limb_bytes * (kh * beta * ext + limbs + 2 * limbs)        # stored key halves once + input + output
     out = {
@@ -802,6 +818,7 @@ def main():
         "kernel_ms_per_step": {k: round(v["ms"], 4) for k, v in fam.items()},
         "dominant_kernel_family": dom,
         "roofline": roofline,
+        "hbm_probe": probe,
         "traffic_source": "profiles/pmc_hbm_traffic_bench_config2.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary committed "
                           "with the code; read from the file, not measured in this run)",
         "roofline_inner_product": roofs["inner_product"],

@@ -442,6 +442,18 @@ enum {
 cm_status cm_profile_enable(cm_ctx *ctx, int32_t on);
 cm_status cm_profile_get(cm_ctx *ctx, int32_t family, double *launches, double *units, double *ms);
 
+/* Streaming-bandwidth probe (a measurement aid, not part of the method; for callers that report a kernel's rate
+ * against what the device's memory system gives a plain kernel of the same read/write mix): runs a plain streaming
+ * kernel `reps` times over about `bytes` bytes of its own device buffers (64 MiB .. 16 GiB, allocated and freed
+ * inside; null stream, synchronous) and returns the best rate in GB/s (10^9 bytes) of bytes read plus bytes written.
+ *   CM_PROBE_READ          one contiguous run per workgroup, 16-byte non-temporal loads (the plaintext stream of the
+ *                          packed product, the key stream of an inner product)
+ *   CM_PROBE_COPY          one read stream, one write stream (the two passes of a transform)
+ *   CM_PROBE_READ3_WRITE1  three read streams, one write stream (an inner product that writes its rotated outputs)
+ * Errors: CM_E_INVAL (arguments), CM_E_NOMEM, CM_E_HIP. */
+enum { CM_PROBE_READ = 0, CM_PROBE_COPY = 1, CM_PROBE_READ3_WRITE1 = 2 };
+cm_status cm_hbm_probe(int32_t kind, uint64_t bytes, int32_t reps, double *gb_per_s);
+
 #ifdef __cplusplus
 }
 #endif

@@ -108,6 +108,7 @@ _SIGS = {
     "cm_profile_get": ([_vp, _i32, _P(_f64), _P(_f64), _P(_f64)], _i32),
     "cm_ntt": ([_vp, _vp, _vp, _i32, _i32, _vp], _i32),
     "cm_keyswitch": ([_vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp], _i32),
+    "cm_hbm_probe": ([_i32, _u64, _i32, _P(_f64)], _i32),
 }
 for _name, (_args, _res) in _SIGS.items():
     _f = getattr(lib, _name)
@@ -539,6 +540,16 @@ def config1():
     """Benchmark configuration 1: n = 4096, a 50-bit base prime, four 40-bit primes, one 60-bit
     special prime, one prime per key-switch digit, scale 2^40, uniform ternary secret."""
     return Context(4096, 5, 1, 1, 50, 40, 60, 2.0 ** 40, hamming=0)
+
+
+CM_PROBE_READ, CM_PROBE_COPY, CM_PROBE_READ3_WRITE1 = 0, 1, 2
+
+
+def hbm_probe(kind, nbytes=4 << 30, reps=5):
+    """GB/s a plain streaming kernel of the given read/write mix reaches on the current device."""
+    r = _f64()
+    _chk(lib.cm_hbm_probe(kind, nbytes, reps, C.byref(r)))
+    return r.value
 
 
 def llama_ring(n_q=24, n_p=4, n=65536):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libcachemir.so")
 BUILD = os.path.join(HERE, "_build")
-SOURCES = ["context.hip", "ntt.hip", "kernels.hip", "ops.hip", "vmm.hip", "kv.hip", "rope.hip"]
+SOURCES = ["context.hip", "ntt.hip", "kernels.hip", "ops.hip", "vmm.hip", "kv.hip", "rope.hip", "probe.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wno-unused-result",
          # the FP64 butterflies rely on exact products: no fused contraction the source does not spell
          "-ffp-contract=off",
