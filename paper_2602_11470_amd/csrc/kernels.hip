@@ -332,6 +332,21 @@ void launch_automorphism(cm_ctx *ctx, u64 *out, const u64 *in, int rows, u64 g, 
     hipLaunchKernelGGL(k_automorphism, dim3(ctx->n / TPB, rows), dim3(TPB), 0, st, out, in, ctx->n, ctx->logn, (unsigned)g);
 }
 
+// Sum of products d * w with d below 2^50 held as two 25-bit halves (d = d0 + 2^25 d1) and w any 64-bit word: four
+// 32 x 32 -> 64-bit multiply-adds into four accumulators that cannot overflow for up to 16 terms (each term is below
+// 2^57), so a product costs four instructions and no carry chain; the accumulators are combined once per sum.  The
+// generic form (64 x 64 -> 128 with carries, about ten instructions) stays for the 60-bit moduli.
+struct Acc50 {
+    u64 t00 = 0, t01 = 0, t10 = 0, t11 = 0;
+    __device__ __forceinline__ void mac(unsigned d0, unsigned d1, u64 w) {
+        const unsigned w0 = (unsigned)w, w1 = (unsigned)(w >> 32);
+        t00 += (u64)d0 * w0, t01 += (u64)d0 * w1, t10 += (u64)d1 * w0, t11 += (u64)d1 * w1;
+    }
+    __device__ __forceinline__ u128 total() const {
+        return (u128)t00 + ((u128)t01 << 32) + ((u128)t10 << 25) + ((u128)t11 << 57);
+    }
+};
+#define LOW25 0x1FFFFFFu
 // ---- fast base conversion ----------------------------------------------------------------------
 // in rows in_rows[m] (coefficient domain, residues under src moduli) -> out rows out_rows[r]:
 //   y_m = a_m * inv_hat_m mod q_m;  out_r = sum_m y_m * hat_{m,r} mod q_r   (no correction term)
@@ -372,6 +387,26 @@ __global__ __launch_bounds__(TPB) void k_base_conv(u64 *__restrict__ out, const 
     }
 #pragma unroll
     for (int m = 0; m < NS; m++) y[m] = mul_shoup(x[m], t.inv_hat[m], t.inv_hat_sh[m], t.src_q[m]);
+    // source moduli below 2^50 (the digits of a ModUp): carry-free split products, four multiply-adds per term
+    u64 qmax = 0;
+#pragma unroll
+    for (int m = 0; m < NS; m++) qmax = t.src_q[m] > qmax ? t.src_q[m] : qmax;
+    if (qmax < (1ULL << 50)) {
+        unsigned y0[NS], y1[NS];
+#pragma unroll
+        for (int m = 0; m < NS; m++) y0[m] = (unsigned)y[m] & LOW25, y1[m] = (unsigned)(y[m] >> 25);
+#pragma unroll
+        for (int rr = 0; rr < CONV_TG; rr++) {
+            const int r = r0 + rr;
+            if (r < nt) {
+                Acc50 acc;
+#pragma unroll
+                for (int m = 0; m < NS; m++) acc.mac(y0[m], y1[m], t.hat_mont[m * nt + r]);
+                out[(size_t)t.out_rows[r] * n + i] = redc(acc.total(), t.dst_q[r], t.dst_qinv[r]);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int rr = 0; rr < CONV_TG; rr++) {
         const int r = r0 + rr;
@@ -455,21 +490,6 @@ template <bool SA>
 __device__ __forceinline__ u64 evk_a_reduce(u128 T, const ModC &m) {
     return SA ? redc(T, m.q, m.qinv) : redc_raw(T, m);
 }
-// Sum of products d * w with d below 2^50 held as two 25-bit halves (d = d0 + 2^25 d1) and w any 64-bit word: four
-// 32 x 32 -> 64-bit multiply-adds into four accumulators that cannot overflow for up to 16 terms (each term is below
-// 2^57), so a product costs four instructions and no carry chain; the accumulators are combined once per sum.  The
-// generic form (64 x 64 -> 128 with carries, about ten instructions) stays for the 60-bit moduli.
-struct Acc50 {
-    u64 t00 = 0, t01 = 0, t10 = 0, t11 = 0;
-    __device__ __forceinline__ void mac(unsigned d0, unsigned d1, u64 w) {
-        const unsigned w0 = (unsigned)w, w1 = (unsigned)(w >> 32);
-        t00 += (u64)d0 * w0, t01 += (u64)d0 * w1, t10 += (u64)d1 * w0, t11 += (u64)d1 * w1;
-    }
-    __device__ __forceinline__ u128 total() const {
-        return (u128)t00 + ((u128)t01 << 32) + ((u128)t10 << 25) + ((u128)t11 << 57);
-    }
-};
-#define LOW25 0x1FFFFFFu
 static EvkA evk_a_of(const cm_ctx *ctx) {
     return EvkA{ctx->evk_stored_a ? evk_a_offset(ctx) : 0, (ctx->L + ctx->alpha) / ctx->alpha};
 }
