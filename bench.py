@@ -820,7 +820,7 @@ def main():
         "roofline": roofline,
         "hbm_probe": probe,
         "traffic_source": "profiles/pmc_hbm_traffic_bench_config2.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary committed "
-                          "with the code; read from the file, not measured in this run)",
+                          "with the code, which names the commit it measured; read from the file, not measured in this run)",
         "roofline_inner_product": roofs["inner_product"],
         "roofline_vmm_mac": roofs["vmm_mac"],
         "roofline_key_switch_inner_product": roofs["inner_product_single"],
