@@ -24,6 +24,10 @@ Prints one JSON line.  `roofline` describes the kernel family with the most time
 achieved = algorithmic bytes per unit / measured time per unit (HIP events around every launch of
 the family on its stream), peak = 8 TB/s HBM, traffic = HBM bytes from the committed counter summary under
 profiles/ (read from that file, not measured in this run: `traffic_source` names it).
+`hbm_probe` = what plain streaming kernels reach on this device (cm_hbm_probe), `frac_of_probe` in every roofline object
+the family's rate against the probe of its read/write mix.  `attention_config3` carries the times of configuration 3
+(q K^T, scores V and one append against a 1024-token cache; `--workload attention` with and without `--key-index`)
+measured in the same run after the timed region (--no-attention leaves them out).
 `cpu_baseline` (default --cpu-baseline full): ONE full product of the same workload run by the oracle on the host
 cores and timed (Algorithm 1 as printed, 52 rotations, 512 products), plus one key switch on a single thread.
 """
@@ -271,7 +275,13 @@ def cpu_baseline_full():
 
 
 def attention_workload(a):
-    """Config 3 (not the default line): one query against an encrypted cache of 1024 tokens, 32 heads
+    if a.gqa:
+        return attention_workload_gqa(a)
+    print(json.dumps(attention_result(a)))
+
+
+def attention_result(a):
+    """Config 3 (a line of its own with --workload attention; its times also ride in the default line): one query against an encrypted cache of 1024 tokens, 32 heads
     x 128 dims on the config-2 ring; cache ciphertexts one level below the top.  q K^T = 3 + 128 x
     (relinearisation + 7 rotations) key switches (--ladders); with --shared-dims 1 the 7 rotations unrolled
     into 13 hoisted ones that share 3 ModUps and one ModDown; by default (--shared-dims 128) the copy mask
@@ -280,8 +290,6 @@ def attention_workload(a):
     parity of this path is in tests/)."""
     import torch
     from paper_2602_11470_amd import binding as B
-    if a.gqa:
-        return attention_workload_gqa(a)
     ctx = B.llama_ring(24, 4)
     H, E, L = 32, 128, ctx.L
     lv = a.cache_level if a.cache_level > 0 else L - 1
@@ -324,7 +332,7 @@ def attention_workload(a):
     sh = 1 if a.ladders or a.key_index else (a.shared_dims or 128)
     per_ct = {1: 13, 2: 14, 4: 10, 8: 6, 16: 7, 32: 3, 64: 1, 128: 0}[sh]    # hoisted rotations of the runs of the ladder left per key ciphertext
     ks_qk = 3 + 15 + 8 + 7 if a.key_index else 3 + 128 * (8 if a.ladders else 1 + per_ct) + sh - 1
-    print(json.dumps({
+    out = {
         "metric": "encrypted-cache attention products/s (config 3: q K^T and scores V, 32 heads x 128 dims, "
                   "context 1024, n=2^16, 24x50-bit + 4x60-bit primes)",
         "value": 1.0 / (res["qk"] + res["sv"]), "unit": "attention steps/s", "n_gpus": 1,
@@ -336,7 +344,10 @@ def attention_workload(a):
                               "unrolled in the extended basis (3 ModUps, 13 rotations)" if sh == 1 else
                               "mask before the last %d terms: %d rotations per key ciphertext + %d shared" % (sh, per_ct, sh - 1)},
         "qk_ms": res["qk"] * 1e3, "sv_ms": res["sv"] * 1e3, "append_ms": append_ms,
-        "qk_key_switches": ks_qk, "qk_key_switches_per_s": ks_qk / res["qk"]}))
+        "qk_key_switches": ks_qk, "qk_key_switches_per_s": ks_qk / res["qk"]}
+    del kv, keys, q, sc, new_k, new_v
+    ctx.close()
+    return out
 
 
 def attention_workload_gqa(a):
@@ -660,6 +671,7 @@ def main():
     ap.add_argument("--cpu-baseline", choices=["full", "sample", "none"], default="full",
                     help="full (default): one full product of the workload timed on the oracle (about two minutes of host "
                          "time) and the extrapolation from a sample beside it; sample: the extrapolation only; none")
+    ap.add_argument("--no-attention", action="store_true", help="leave the configuration-3 attention times out of the default line")
     ap.add_argument("--stored-a", action="store_true",
                     help="evaluation keys with both halves in device memory (CM_OPT_EVK_STORED_A): the inner products read the "
                          "uniform half instead of regenerating it")
@@ -826,6 +838,18 @@ def main():
         "roofline_key_switch_inner_product": roofs["inner_product_single"],
         "roofline_ntt_fwd": roofs["ntt_fwd"],
     }
+    g.clear()                                            # keys, plaintexts and context of the product go back
+    if not a.no_attention:
+        # configuration 3 beside the headline: one query against the 1024-token cache of 32 heads x 128 dims at level 22,
+        # in the workload's default form and with the key index (what `--workload attention [--key-index]` prints)
+        import copy
+        att = {}
+        for name, ki in (("copy_mask_first", False), ("key_index", True)):
+            b = copy.copy(a)
+            b.gqa, b.key_index, b.ladders, b.shared_dims, b.cache_level = False, ki, False, 0, 0
+            r = attention_result(b)
+            att[name] = {k: round(r[k], 3) for k in ("qk_ms", "sv_ms", "append_ms")}
+        out["attention_config3"] = att
     mode = "none" if a.no_cpu_baseline else a.cpu_baseline
     if mode != "none":
         g.clear()                                        # the GPU's memory and the host's cores go back before the oracle runs
