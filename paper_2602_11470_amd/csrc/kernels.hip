@@ -1104,6 +1104,7 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 // baby ciphertexts per pass (32 KiB of LDS).
 #define MAC_CO 64
 #define MAC_JC 32
+#define MAC_KW 4      // giant steps per wave whose sums stay in registers over the passes
 #define MAC_G 8       // plaintext words a lane keeps in flight per group (the next group is loaded while one is multiplied; 16 and 32 measured slower)
 typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 // Limbs whose modulus is below 2^50 run the products in FP64 (the arithmetic of the transforms'
@@ -1135,6 +1136,12 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
     const MacFp F{fq.q, fq.qinv};
     const size_t o = (size_t)l * n + i0, cs = (size_t)limbs * n;
     const u64 *pblk = pts + ((size_t)l * (n / MAC_CO) + ch) * r_o * r_i * MAC_CO;
+    // up to MAC_KW giant steps per wave keep their running sums in registers across the passes over the baby steps
+    // (otherwise every pass after the first re-reads and re-writes the output)
+    u64 acc0[MAC_KW], acc1[MAC_KW];
+#pragma unroll
+    for (int x = 0; x < MAC_KW; x++) acc0[x] = acc1[x] = 0;
+    const bool keep = k1 - k0 <= 4 * MAC_KW;
     for (int j0 = 0; j0 < r_i; j0 += MAC_JC) {
         const int jn = r_i - j0 < MAC_JC ? r_i - j0 : MAC_JC;
         __syncthreads();
@@ -1216,12 +1223,25 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
                 }
             }
             u64 *dst = out + (size_t)k * ct_stride + o + co;
-            if (j0) {
-                v0 = addmod(v0, dst[0], m.q);
-                v1 = addmod(v1, dst[cs], m.q);
+            if (keep) {
+                // the sums of this wave's giant steps stay in registers over the passes and are written once
+                const int ki = (k - k0 - kq) >> 2;
+                const bool last = j0 + MAC_JC >= r_i;
+#pragma unroll
+                for (int x = 0; x < MAC_KW; x++)
+                    if (x == ki) {
+                        if (j0) v0 = addmod(v0, acc0[x], m.q), v1 = addmod(v1, acc1[x], m.q);
+                        acc0[x] = v0, acc1[x] = v1;
+                    }
+                if (last) dst[0] = v0, dst[cs] = v1;
+            } else {
+                if (j0) {
+                    v0 = addmod(v0, dst[0], m.q);
+                    v1 = addmod(v1, dst[cs], m.q);
+                }
+                dst[0] = v0;
+                dst[cs] = v1;
             }
-            dst[0] = v0;
-            dst[cs] = v1;
         }
     }
 }
