@@ -283,18 +283,29 @@ __global__ __launch_bounds__(TPB) void k_tensor_sum_stationary(u64 *__restrict__
     }
     for (int z = 0; z < groups; z++) {
         double d0 = 0.0, d1 = 0.0, d2 = 0.0;
+        // Eight terms at a time: their sixteen words are requested before the first is used.  Terms at or past cnt read
+        // term 0's words again (a valid address) and multiply them by a zero, so no load sits behind a branch.
 #pragma unroll
-        for (int j = 0; j < TS_MAX_CNT; j++) {
-            if (j < cnt) {
-                const u64 *bj = b + ((size_t)z * gs + (size_t)j * ts) * 2 * cs;
-                const double b0 = MacFp::from_u64(__builtin_nontemporal_load(bj + o));
-                const double b1 = MacFp::from_u64(__builtin_nontemporal_load(bj + o + cs));
-                const double b0q = b0 * F.qinv, b1q = b1 * F.qinv;
-                d0 += F.mulmod(a0[j], b0, b0q);
-                d1 += F.mulmod(a0[j], b1, b1q) + F.mulmod(a1[j], b0, b0q);
-                d2 += F.mulmod(a1[j], b1, b1q);
+        for (int jc = 0; jc < TS_MAX_CNT; jc += 8) {
+            if (jc < cnt) {
+                u64 r0[8], r1[8];
+#pragma unroll
+                for (int jj = 0; jj < 8; jj++) {
+                    const int j = jc + jj < cnt ? jc + jj : 0;
+                    const u64 *bj = b + ((size_t)z * gs + (size_t)j * ts) * 2 * cs;
+                    r0[jj] = __builtin_nontemporal_load(bj + o), r1[jj] = __builtin_nontemporal_load(bj + o + cs);
+                }
+#pragma unroll
+                for (int jj = 0; jj < 8; jj++) {
+                    const int j = jc + jj;
+                    const double b0 = MacFp::from_u64(r0[jj]), b1 = MacFp::from_u64(r1[jj]);
+                    const double b0q = b0 * F.qinv, b1q = b1 * F.qinv;
+                    d0 += F.mulmod(a0[j], b0, b0q);
+                    d1 += F.mulmod(a0[j], b1, b1q) + F.mulmod(a1[j], b0, b0q);
+                    d2 += F.mulmod(a1[j], b1, b1q);
+                    if (jj & 1) d0 = F.norm(d0), d1 = F.norm(d1), d2 = F.norm(d2);
+                }
             }
-            if (j & 1) d0 = F.norm(d0), d1 = F.norm(d1), d2 = F.norm(d2);
         }
         u64 *oz = out + (size_t)z * 3 * cs;
         oz[o] = F.canon(d0);
