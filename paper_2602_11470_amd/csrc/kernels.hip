@@ -1137,7 +1137,9 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
                                                      const FpQ *__restrict__ fpq, int r_i, int r_o, int limbs, int n,
                                                      size_t ct_stride, int k0, int k1, int level, int L) {
     __shared__ u64 sb[MAC_JC * 2 * MAC_CO];
-    const int l = blockIdx.y, ch = blockIdx.x, i0 = ch * MAC_CO;
+    // the limbs of the special primes (integer products, the slowest workgroups) are dispatched first, not last
+    const int nsp = limbs - (level + 1), y = blockIdx.y;
+    const int l = y < nsp ? level + 1 + y : y - nsp, ch = blockIdx.x, i0 = ch * MAC_CO;
     const int co = threadIdx.x & (MAC_CO - 1), kq = threadIdx.x >> 6;
     const int mi = l <= level ? l : L + 1 + (l - level - 1);
     const ModC m = modc[mi];

@@ -141,7 +141,12 @@ static void build_ks(cm_ctx *ctx, int level, KsLevelFull &k) {
         // instead of being refetched by every XCD for every digit.
         std::vector<int> order(ntt_rows.size());
         for (size_t i = 0; i < order.size(); i++) order[i] = (int)i;
-        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return ntt_mods[a] < ntt_mods[b]; });
+        // The limbs under the 60-bit primes go first: their integer butterflies take about twice the instructions of the
+        // FP64 ones, and a launch that ends on them has a long tail of its slowest workgroups.
+        auto slow = [&](int i) { return ctx->mod[ntt_mods[i]] >= (1ULL << 50) ? 0 : 1; };
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+            return slow(a) != slow(b) ? slow(a) < slow(b) : ntt_mods[a] < ntt_mods[b];
+        });
         std::vector<int> r2, m2;
         for (int i : order) r2.push_back(ntt_rows[i]), m2.push_back(ntt_mods[i]);
         ntt_rows.swap(r2), ntt_mods.swap(m2);
