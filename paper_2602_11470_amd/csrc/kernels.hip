@@ -3,6 +3,7 @@
 #include "kernels.h"
 
 #define TPB 256
+typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 
 
 // ---- a short list of integers into device memory without a copy or an allocation ---------------
@@ -811,9 +812,10 @@ __global__ __launch_bounds__(TPB) void k_inner_product_fanout(IpFan f, const u64
         ulonglong2 r0 = make_ulonglong2(redc(b0, m.q, m.qinv), redc(b1, m.q, m.qinv));
         if (have_c0) r0.x = addmod(r0.x, swap ? cv.y : cv.x, m.q), r0.y = addmod(r0.y, swap ? cv.x : cv.y, m.q);
         const size_t o = (size_t)r * n + base;
-        *reinterpret_cast<ulonglong2 *>(f.out[a] + o) = r0;
-        *reinterpret_cast<ulonglong2 *>(f.out[a] + (size_t)ext * n + o) =
-            make_ulonglong2(evk_a_reduce<SA>(a0, m), evk_a_reduce<SA>(a1, m));
+        // the rotated ciphertexts are read back much later (by the multiply-accumulate kernel): streamed past the caches
+        const u64x2 w0 = {r0.x, r0.y}, w1 = {evk_a_reduce<SA>(a0, m), evk_a_reduce<SA>(a1, m)};
+        __builtin_nontemporal_store(w0, reinterpret_cast<u64x2 *>(f.out[a] + o));
+        __builtin_nontemporal_store(w1, reinterpret_cast<u64x2 *>(f.out[a] + (size_t)ext * n + o));
     }
 }
 bool launch_inner_product_fanout(cm_ctx *ctx, const IpFan &f, const u64 *dig, const u64 *c0, bool c0_ext, int beta, int level,
@@ -1117,7 +1119,6 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 #define MAC_JC 32
 #define MAC_KW 4      // giant steps per wave whose sums stay in registers over the passes
 #define MAC_G 8       // plaintext words a lane keeps in flight per group (the next group is loaded while one is multiplied; 16 and 32 measured slower)
-typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 // Limbs whose modulus is below 2^50 run the products in FP64 (the arithmetic of the transforms'
 // butterflies): residues as exact integers in doubles, a modular product
 //     h = y a;  l = fma(y, a, -h);  c = rint(y (a / q));  r = fma(-c, q, h) + l        (|r| < q)
