@@ -359,6 +359,8 @@ struct Acc50 {
     }
 };
 #define LOW25 0x1FFFFFFu
+// converted limbs are written with non-temporal stores (next read by the transform kernel, after the whole launch)
+#define CONV_ST(ptr, val) __builtin_nontemporal_store((u64)(val), (ptr))
 // ---- fast base conversion ----------------------------------------------------------------------
 // in rows in_rows[m] (coefficient domain, residues under src moduli) -> out rows out_rows[r]:
 //   y_m = a_m * inv_hat_m mod q_m;  out_r = sum_m y_m * hat_{m,r} mod q_r   (no correction term)
@@ -414,7 +416,7 @@ __global__ __launch_bounds__(TPB) void k_base_conv(u64 *__restrict__ out, const 
                 Acc50 acc;
 #pragma unroll
                 for (int m = 0; m < NS; m++) acc.mac(y0[m], y1[m], t.hat_mont[m * nt + r]);
-                out[(size_t)t.out_rows[r] * n + i] = redc(acc.total(), t.dst_q[r], t.dst_qinv[r]);
+                CONV_ST(out + (size_t)t.out_rows[r] * n + i, redc(acc.total(), t.dst_q[r], t.dst_qinv[r]));
             }
         }
         return;
@@ -426,7 +428,7 @@ __global__ __launch_bounds__(TPB) void k_base_conv(u64 *__restrict__ out, const 
             u128 acc = 0;
 #pragma unroll
             for (int m = 0; m < NS; m++) acc += (u128)y[m] * t.hat_mont[m * nt + r];
-            out[(size_t)t.out_rows[r] * n + i] = redc(acc, t.dst_q[r], t.dst_qinv[r]);
+            CONV_ST(out + (size_t)t.out_rows[r] * n + i, redc(acc, t.dst_q[r], t.dst_qinv[r]));
         }
     }
 }
