@@ -1118,6 +1118,8 @@ void launch_decrypt(cm_ctx *ctx, u64 *out, const u64 *ct, const u64 *s_mont, int
 // j for its k, so each output is written once and each plaintext word is read once.  Up to 32
 // baby ciphertexts per pass (32 KiB of LDS).
 #define MAC_CO 64
+// the baby ciphertexts are read once per launch, like the plaintexts: non-temporal loads (2 % off the kernel)
+#define MAC_LD(ptr) __builtin_nontemporal_load(ptr)
 #define MAC_JC 32
 #define MAC_KW 4      // giant steps per wave whose sums stay in registers over the passes
 #define MAC_G 8       // plaintext words a lane keeps in flight per group (the next group is loaded while one is multiplied; 16 and 32 measured slower)
@@ -1168,7 +1170,7 @@ __global__ __launch_bounds__(TPB) void k_vmm_mac_lds(u64 *__restrict__ out, cons
 #pragma unroll
             for (int it = 0; it < ROWS; it++) {
                 const int jc = kq + 4 * it;
-                w[it] = jc < 2 * jn ? babies[(size_t)(j0 + (jc >> 1)) * ct_stride + (jc & 1) * cs + o + co] : 0;
+                w[it] = jc < 2 * jn ? MAC_LD(babies + (size_t)(j0 + (jc >> 1)) * ct_stride + (jc & 1) * cs + o + co) : 0;
             }
 #pragma unroll
             for (int it = 0; it < ROWS; it++) {
