@@ -33,6 +33,9 @@ struct NttTables {
     const u64 *ninv, *ninvp;      // [nmod] n^{-1} (inverse only)
     const double *ninvd, *ninvqd;
     const FpQ *fpq;               // [nmod] q and 1/q as doubles; q = 0 where the limb must use IntArith
+    // Large launches (256 limbs and more) read with non-temporal loads: their input was written long before and is read
+    // once.  Small launches find theirs in the caches and read plainly (a single key switch is 3 % slower otherwise).
+    int stream_loads;
 };
 
 // ---- integer arithmetic --------------------------------------------------------------------------
@@ -233,8 +236,13 @@ __device__ __forceinline__ void cols_fwd_body(u64 *lds, u64 *p, const u64 *ps, c
     const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
     typename A::T v[16];
     u64 raw[16];
+    if (t.stream_loads) {
 #pragma unroll
-    for (int k = 0; k < 16; k++) raw[k] = ps[(unsigned)((sub + 16 * k) * n2 + c)];
+        for (int k = 0; k < 16; k++) raw[k] = __builtin_nontemporal_load(ps + (unsigned)((sub + 16 * k) * n2 + c));
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; k++) raw[k] = ps[(unsigned)((sub + 16 * k) * n2 + c)];
+    }
     {
         const TableTw<A> tw(ar, 1);                 // in flight together with the data
 #pragma unroll
@@ -258,8 +266,13 @@ __device__ __forceinline__ void cols_inv_body(u64 *lds, u64 *p, const NttTables 
     const int c = threadIdx.x & 15, sub = threadIdx.x >> 4;
     typename A::T v[16];
     u64 raw[16];
+    if (t.stream_loads) {
 #pragma unroll
-    for (int k = 0; k < 16; k++) raw[k] = p[(unsigned)((16 * sub + k) * n2 + c)];
+        for (int k = 0; k < 16; k++) raw[k] = __builtin_nontemporal_load(p + (unsigned)((16 * sub + k) * n2 + c));
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; k++) raw[k] = p[(unsigned)((16 * sub + k) * n2 + c)];
+    }
     {
         const TableTw<A> tw(ar, 16 + sub);          // in flight together with the data
 #pragma unroll
@@ -378,8 +391,13 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
     const u64 B = (u64)chunk * 16 + blk;
     typename A::T v[16];
     u64 raw[16];
+    if (t.stream_loads) {
 #pragma unroll
-    for (int k = 0; k < 16; k++) raw[k] = p[blk * 256 + sub + 16 * k];
+        for (int k = 0; k < 16; k++) raw[k] = __builtin_nontemporal_load(p + blk * 256 + sub + 16 * k);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; k++) raw[k] = p[blk * 256 + sub + 16 * k];
+    }
     {
         const TableTw<A> tw(ar, 256 + B);           // in flight together with the data
 #pragma unroll
@@ -479,6 +497,9 @@ __device__ __forceinline__ void rows256_inv_body(u64 *lds, u64 *p, const u64 *ps
         if (g) {
 #pragma unroll
             for (int k = 0; k < 16; k++) w[k] = psrow[perm_src(pos0 + 256 * k, g, logn)];
+        } else if (t.stream_loads) {
+#pragma unroll
+            for (int k = 0; k < 16; k++) w[k] = __builtin_nontemporal_load(ps + threadIdx.x + 256 * k);
         } else {
 #pragma unroll
             for (int k = 0; k < 16; k++) w[k] = ps[threadIdx.x + 256 * k];
@@ -599,6 +620,7 @@ void launch_ntt_src(cm_ctx *ctx, u64 *data, const int *d_rows, const u64 *src, c
     dim3 grid((unsigned)limbs * (n >> 12)), block(NTT_THREADS);
     NttTables t;
     t.modc = ctx->d_modc, t.fpq = ctx->d_fpq;
+    t.stream_loads = limbs >= 256;
     if (!inverse) {
         t.tw = ctx->d_tw, t.twp = ctx->d_twp, t.twd = ctx->d_twd, t.twqd = ctx->d_twqd;
         t.ninv = t.ninvp = nullptr, t.ninvd = t.ninvqd = nullptr;
@@ -627,6 +649,7 @@ void launch_ntt_fwd_finish(cm_ctx *ctx, u64 *conv, const int *d_mods, const Fini
     dim3 grid((unsigned)limbs * (n >> 12)), block(NTT_THREADS);
     NttTables t;
     t.modc = ctx->d_modc, t.fpq = ctx->d_fpq;
+    t.stream_loads = limbs >= 256;
     t.tw = ctx->d_tw, t.twp = ctx->d_twp, t.twd = ctx->d_twd, t.twqd = ctx->d_twqd;
     t.ninv = t.ninvp = nullptr, t.ninvd = t.ninvqd = nullptr;
     hipLaunchKernelGGL(ntt_cols_fwd, grid, block, 0, st, conv, src, d_src_rows, (const int *)nullptr, d_mods, t, n, n >> 8);
