@@ -225,6 +225,10 @@ __device__ __forceinline__ void radix16_inv_last(u64 (&v)[16], const IntArith &a
 // The passes write with non-temporal stores: a limb is read again only by a later kernel, after hundreds of MiB of other
 // limbs have gone by (measured: 1 % off the transforms of a step against plain stores).
 #define NTT_ST(ptr, val) __builtin_nontemporal_store((u64)(val), (ptr))
+// the masked products of a cache append read the cached ciphertext they add to and write it back past the caches (the
+// cache is gigabytes; 3 % off an append)
+#define TAIL_LD(ptr) __builtin_nontemporal_load(ptr)
+#define TAIL_ST(ptr, val) __builtin_nontemporal_store((u64)(val), (ptr))
 __device__ __forceinline__ int pad(int e) { return e + (e >> 4); }
 #define LDS_WORDS (4096 + 256)
 
@@ -447,14 +451,14 @@ __device__ __forceinline__ void rows256_fwd_body(u64 *lds, u64 *p, const NttTabl
         }
         if (ac) {
 #pragma unroll
-            for (int k = 0; k < 16; k++) cc[k] = ac[256 * k];
+            for (int k = 0; k < 16; k++) cc[k] = TAIL_LD(ac + 256 * k);
         }
 #pragma unroll
         for (int k = 0; k < 16; k++) {
             const u64 uv = redc((u128)uu[k] * aa[k], q, qinv);
             u64 x = mul_shoup(submod(uv, lds[pad(threadIdx.x + 256 * k)], q), pi, pis, q);
             if (ac) x = addmod(x, cc[k], q);
-            op[256 * k] = x;
+            TAIL_ST(op + 256 * k, x);
         }
         return;
     }
